@@ -1,0 +1,268 @@
+"""ctypes binding and step composition for the CPU oracle (sdt_oracle.c).
+
+TEST INFRASTRUCTURE, NOT PRODUCT.  Only tests, the smoke check and the
+benchmark's cpu_baseline leg import this module; the HIP package never does,
+and this module never imports the HIP package or the input generator.
+
+The step follows the per-worker loop the paper sketches in Sec. II-A and
+Sec. III-D/E (sample a mini-batch sub-graph, fetch its features, aggregate
+neighbourhoods in a GraphSAGE model, compute gradients, update the local
+weights); the conventions the paper leaves open (fan-out order, frontier
+order, bias/ReLU, plain SGD, bf16 storage points) are the ones stated in the
+function docstrings below.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import List, Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sdt_oracle.c")
+_LIB_PATH = os.path.join(_HERE, "libsdt_oracle.so")
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    if force or not os.path.exists(_LIB_PATH):
+        subprocess.run(["gcc", "-O2", "-shared", "-fPIC", "-std=c11", _SRC, "-o", _LIB_PATH, "-lm"], check=True)
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        build(force=True)
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64, u32, u64, f64 = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64,
+                                   ctypes.c_uint32, ctypes.c_uint64, ctypes.c_double)
+    L.orc_philox4x32_10.restype = None
+    L.orc_philox4x32_10.argtypes = [vp, vp, vp]
+    L.orc_sample_positions.restype = i32
+    L.orc_sample_positions.argtypes = [i64, i32, u64, u32, u32, u32, vp]
+    L.orc_sample_rows.restype = i64
+    L.orc_sample_rows.argtypes = [vp, vp, vp, i32, i32, u64, u32, u32, vp, vp]
+    L.orc_build_frontier.restype = i32
+    L.orc_build_frontier.argtypes = [i64, vp, i32, vp, i64, vp, vp]
+    L.orc_transpose_block.restype = None
+    L.orc_transpose_block.argtypes = [i32, i32, vp, vp, vp, vp]
+    L.orc_gather_rows.restype = None
+    L.orc_gather_rows.argtypes = [vp, i64, i64, vp, i64, vp, i64]
+    L.orc_aggregate_fwd.restype = None
+    L.orc_aggregate_fwd.argtypes = [i64, vp, vp, vp, i64, vp]
+    L.orc_linear_fwd.restype = None
+    L.orc_linear_fwd.argtypes = [i64, i64, i64, vp, i64, vp, vp, vp, i32, vp]
+    L.orc_softmax_xent.restype = f64
+    L.orc_softmax_xent.argtypes = [i64, i64, vp, vp, vp]
+    L.orc_linear_bwd.restype = None
+    L.orc_linear_bwd.argtypes = [i64, i64, i64, vp, vp, i32, vp, i64, vp, vp, vp, vp, vp, vp]
+    L.orc_aggregate_bwd.restype = None
+    L.orc_aggregate_bwd.argtypes = [i64, i64, vp, vp, vp, vp, i64, vp]
+    L.orc_sgd.restype = None
+    L.orc_sgd.argtypes = [i64, vp, vp, f64]
+    L.orc_round_bf16.restype = None
+    L.orc_round_bf16.argtypes = [i64, vp]
+    _lib = L
+    return L
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+# ------------------------------------------------------------------ primitives
+def philox4x32_10(ctr, key) -> np.ndarray:
+    c, k = _c(ctr, np.uint32), _c(key, np.uint32)
+    out = np.empty(4, dtype=np.uint32)
+    _load().orc_philox4x32_10(_p(c), _p(k), _p(out))
+    return out
+
+
+def sample_positions(d: int, k: int, seed: int, step: int, layer: int, node: int) -> np.ndarray:
+    pos = np.empty(max(k, 1), dtype=np.int64)
+    m = _load().orc_sample_positions(d, k, seed, step, layer, node, _p(pos))
+    return pos[:m].copy()
+
+
+@dataclass
+class Block:
+    """One sampled bipartite layer.  src_nodes[:n_dst] are the destinations."""
+    n_dst: int
+    n_src: int
+    indptr: np.ndarray     # int32 [n_dst+1]
+    cols: np.ndarray       # int32 [nnz], local ids into src_nodes
+    src_nodes: np.ndarray  # int32 [n_src], global ids
+    e_glob: np.ndarray     # int32 [nnz], global ids of the sampled neighbours
+    t_indptr: np.ndarray   # int32 [n_src+1]
+    t_rows: np.ndarray     # int32 [nnz]
+
+    @property
+    def nnz(self) -> int:
+        return int(self.indptr[-1])
+
+
+def sample_block(indptr, indices, dst_nodes, fanout: int, seed: int, step: int, layer: int) -> Block:
+    indptr, indices, dst = _c(indptr, np.int64), _c(indices, np.int32), _c(dst_nodes, np.int32)
+    n_dst, n_nodes = len(dst), len(indptr) - 1
+    b_indptr = np.zeros(n_dst + 1, dtype=np.int32)
+    e_glob = np.empty(max(n_dst * max(fanout, 0), 1), dtype=np.int32)
+    nnz = _load().orc_sample_rows(_p(indptr), _p(indices), _p(dst), n_dst, fanout, seed, step, layer,
+                                  _p(b_indptr), _p(e_glob))
+    e_glob = e_glob[:nnz].copy()
+    src = np.empty(n_dst + nnz, dtype=np.int32)
+    cols = np.empty(max(nnz, 1), dtype=np.int32)
+    n_src = _load().orc_build_frontier(n_nodes, _p(dst), n_dst, _p(e_glob), nnz, _p(src), _p(cols))
+    src, cols = src[:n_src].copy(), cols[:nnz].copy()
+    t_indptr = np.zeros(n_src + 1, dtype=np.int32)
+    t_rows = np.empty(max(nnz, 1), dtype=np.int32)
+    _load().orc_transpose_block(n_dst, n_src, _p(b_indptr), _p(cols), _p(t_indptr), _p(t_rows))
+    return Block(n_dst, n_src, b_indptr, cols, src, e_glob, t_indptr, t_rows[:nnz].copy())
+
+
+def sample_blocks(indptr, indices, seeds, fanouts: List[int], seed: int, step: int) -> List[Block]:
+    """blocks[l] feeds GNN layer l (l = 0 is the input-most layer and uses
+    fanouts[0]).  Sampling starts at the seeds with the last fan-out and walks
+    outwards; each block's source frontier is the next block's destinations."""
+    L = len(fanouts)
+    blocks: List[Optional[Block]] = [None] * L
+    dst = _c(seeds, np.int32)
+    for l in range(L - 1, -1, -1):
+        blocks[l] = sample_block(indptr, indices, dst, fanouts[l], seed, step, l)
+        dst = blocks[l].src_nodes
+    return blocks
+
+
+def gather_rows(X: np.ndarray, idx) -> np.ndarray:
+    X = np.ascontiguousarray(X)
+    idx = _c(idx, np.int32)
+    out = np.empty((len(idx),) + X.shape[1:], dtype=X.dtype)
+    rb = X.strides[0]
+    _load().orc_gather_rows(_p(X), rb, rb, _p(idx), len(idx), _p(out), rb)
+    return out
+
+
+def aggregate_fwd(b_indptr, b_cols, H: np.ndarray, n_dst: Optional[int] = None) -> np.ndarray:
+    ip, cols, H = _c(b_indptr, np.int64), _c(b_cols, np.int32), _c(H, np.float64)
+    n_dst = len(ip) - 1 if n_dst is None else n_dst
+    A = np.empty((n_dst, H.shape[1]), dtype=np.float64)
+    _load().orc_aggregate_fwd(n_dst, _p(ip), _p(cols), _p(H), H.shape[1], _p(A))
+    return A
+
+
+def linear_fwd(Hself, A, W, b, relu: bool) -> np.ndarray:
+    """Hself may have more rows than A; its first len(A) rows are used."""
+    Hself, A, W, b = _c(Hself, np.float64), _c(A, np.float64), _c(W, np.float64), _c(b, np.float64)
+    n, fin = A.shape
+    fout = W.shape[1]
+    assert W.shape[0] == 2 * fin and Hself.shape[1] == fin and Hself.shape[0] >= n
+    Y = np.empty((n, fout), dtype=np.float64)
+    _load().orc_linear_fwd(n, fin, fout, _p(Hself), fin, _p(A), _p(W), _p(b), int(relu), _p(Y))
+    return Y
+
+
+def softmax_xent(Z, y):
+    Z, y = _c(Z, np.float64), _c(y, np.int32)
+    dZ = np.empty_like(Z)
+    loss = _load().orc_softmax_xent(Z.shape[0], Z.shape[1], _p(Z), _p(y), _p(dZ))
+    return float(loss), dZ
+
+
+def linear_bwd(dY, Y, relu: bool, Hself, A, W, need_input_grad: bool = True):
+    dY, Y, Hself, A, W = (_c(x, np.float64) for x in (dY, Y, Hself, A, W))
+    n, fin = A.shape
+    fout = W.shape[1]
+    dW = np.empty((2 * fin, fout), dtype=np.float64)
+    db = np.empty(fout, dtype=np.float64)
+    dSelf = np.empty((n, fin), dtype=np.float64) if need_input_grad else None
+    dAgg = np.empty((n, fin), dtype=np.float64) if need_input_grad else None
+    _load().orc_linear_bwd(n, fin, fout, _p(dY), _p(Y), int(relu), _p(Hself), fin, _p(A), _p(W),
+                           _p(dW), _p(db), _p(dSelf), _p(dAgg))
+    return dW, db, dSelf, dAgg
+
+
+def aggregate_bwd(b_indptr, b_cols, n_src: int, dAgg, dSelf) -> np.ndarray:
+    ip, cols, dAgg = _c(b_indptr, np.int64), _c(b_cols, np.int32), _c(dAgg, np.float64)
+    dSelf = None if dSelf is None else _c(dSelf, np.float64)
+    n_dst, F = dAgg.shape
+    dH = np.empty((n_src, F), dtype=np.float64)
+    _load().orc_aggregate_bwd(n_dst, n_src, _p(ip), _p(cols), _p(dAgg), _p(dSelf), F, _p(dH))
+    return dH
+
+
+def sgd(w, g, lr: float) -> np.ndarray:
+    w = np.array(w, dtype=np.float64, copy=True, order="C")
+    g = _c(g, np.float64)
+    _load().orc_sgd(w.size, _p(w), _p(g), lr)
+    return w
+
+
+def round_bf16(x) -> np.ndarray:
+    x = np.array(x, dtype=np.float64, copy=True, order="C")
+    _load().orc_round_bf16(x.size, _p(x))
+    return x
+
+
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Exact widening of bf16 bit patterns (uint16) to float64."""
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+# ------------------------------------------------------------------ the step
+def forward(blocks: List[Block], H0, W, b, bf16: bool = False):
+    """Layer l: A = mean of sampled neighbours, Z = H[:n_dst] W_self + A W_neigh + b,
+    ReLU on all but the last layer.  With bf16=True the tensors the bf16
+    configuration stores in bf16 (A, hidden activations) are rounded when
+    produced and the weights are rounded where they enter a product; logits
+    stay unrounded."""
+    rnd = round_bf16 if bf16 else (lambda t: t)
+    L = len(blocks)
+    H = [np.asarray(H0, dtype=np.float64)]
+    A = []
+    for l, blk in enumerate(blocks):
+        a = rnd(aggregate_fwd(blk.indptr, blk.cols, H[l]))
+        z = linear_fwd(H[l], a, rnd(W[l]), b[l], relu=(l < L - 1))
+        A.append(a)
+        H.append(rnd(z) if l < L - 1 else z)
+    return H, A
+
+
+def train_step(indptr, indices, X, y, seeds, fanouts, W, b, seed: int, step: int, lr: float,
+               bf16: bool = False, blocks: Optional[List[Block]] = None):
+    """One mini-batch step.  X is fp32 (or uint16 bf16 bit patterns when
+    bf16=True); W[l] is [2*in_l, out_l], b[l] is [out_l].  Returns a dict with
+    every intermediate the HIP path can expose."""
+    rnd = round_bf16 if bf16 else (lambda t: t)
+    L = len(fanouts)
+    if blocks is None:
+        blocks = sample_blocks(indptr, indices, seeds, fanouts, seed, step)
+    Xrows = gather_rows(X, blocks[0].src_nodes)
+    H0 = bf16_bits_to_f64(Xrows) if bf16 else Xrows.astype(np.float64)
+    W = [np.asarray(w, dtype=np.float64) for w in W]
+    b = [np.asarray(v, dtype=np.float64) for v in b]
+    H, A = forward(blocks, H0, W, b, bf16)
+    loss, dZ = softmax_xent(H[L], np.asarray(y)[np.asarray(seeds)])
+    dH = rnd(dZ)
+    dW, db = [None] * L, [None] * L
+    dSelf, dAgg, dHs = [None] * L, [None] * L, [None] * L
+    for l in range(L - 1, -1, -1):
+        blk = blocks[l]
+        dW[l], db[l], ds, da = linear_bwd(dH, H[l + 1], l < L - 1, H[l][:blk.n_dst], A[l], rnd(W[l]),
+                                          need_input_grad=(l > 0))
+        if l > 0:
+            dSelf[l], dAgg[l] = rnd(ds), rnd(da)
+            dH = rnd(aggregate_bwd(blk.indptr, blk.cols, blk.n_src, dAgg[l], dSelf[l]))
+            dHs[l] = dH
+    W_new = [sgd(W[l], dW[l], lr) for l in range(L)]
+    b_new = [sgd(b[l], db[l], lr) for l in range(L)]
+    return dict(blocks=blocks, H=H, A=A, logits=H[L], loss=loss, dZ=dZ, dW=dW, db=db,
+                dSelf=dSelf, dAgg=dAgg, dH=dHs, W_new=W_new, b_new=b_new)

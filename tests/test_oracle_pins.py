@@ -1,0 +1,404 @@
+"""Pins for the CPU oracle: every function is checked against something other
+than itself -- published known-answer vectors, invariants, brute force,
+hand-built graphs, library routines, closed forms and finite differences."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import sdt_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------- Philox
+def test_philox_known_answers():
+    n = 0
+    for line in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        v = [int(x, 16) for x in line.split()]
+        assert list(orc.philox4x32_10(v[:4], v[4:6])) == v[6:]
+        n += 1
+    assert n == 3
+
+
+# ----------------------------------------------------------------- sampling
+def test_sample_positions_invariants():
+    for d, k in [(0, 5), (1, 5), (5, 5), (4, 10), (6, 5), (30, 10), (1000, 25), (100000, 64), (7, 0)]:
+        for node in range(20):
+            pos = orc.sample_positions(d, k, 1234, 3, 1, node)
+            assert len(pos) == min(d, max(k, 0))
+            assert np.all(np.diff(pos) > 0)                      # distinct and ascending
+            if len(pos):
+                assert pos[0] >= 0 and pos[-1] < d
+            if d <= k:
+                assert list(pos) == list(range(d))               # clamp: the whole row
+
+
+def test_sample_positions_keyed_by_every_argument():
+    base = dict(seed=7, step=11, layer=1, node=99)
+    ref = orc.sample_positions(5000, 10, **base)
+    assert np.array_equal(ref, orc.sample_positions(5000, 10, **base))
+    for name, val in [("seed", 8), ("seed", 7 + (1 << 32)), ("step", 12), ("layer", 0), ("node", 98)]:
+        other = dict(base)
+        other[name] = val
+        assert not np.array_equal(ref, orc.sample_positions(5000, 10, **other)), name
+
+
+def test_sample_subsets_uniform_chi_square():
+    # d=4, k=2: the 6 subsets must be equally likely (chi-square, 5 dof;
+    # 20.5 is the 0.1 % point, a wrong index or range gives thousands).
+    counts = {}
+    n = 60000
+    for key in range(n):
+        s = tuple(orc.sample_positions(4, 2, key, 0, 0, 5))
+        counts[s] = counts.get(s, 0) + 1
+    assert len(counts) == 6
+    chi2 = sum((c - n / 6) ** 2 / (n / 6) for c in counts.values())
+    assert chi2 < 20.5, (chi2, counts)
+
+
+@pytest.mark.parametrize("d,k", [(30, 10), (1000, 25)])
+def test_sample_inclusion_frequency(d, k):
+    trials = 6000 if d == 30 else 4000
+    hits = np.zeros(d)
+    for key in range(trials):
+        hits[orc.sample_positions(d, k, 99, key, 0, key % 17)] += 1
+    p = k / d
+    sigma = math.sqrt(trials * p * (1 - p))
+    assert np.all(np.abs(hits - trials * p) < 5.5 * sigma)
+    assert hits.sum() == trials * k
+
+
+def test_sample_matches_explicit_fisher_yates():
+    # Same rule on a fully materialised array: swap-based Fisher-Yates driven
+    # by the same published generator, written independently with numpy ints.
+    d, k, seed, step, layer, node = 37, 9, (5 << 32) | 77, 4, 1, 123
+    a = list(range(d))
+    out = []
+    for i in range(k):
+        w = orc.philox4x32_10([i >> 2, node, layer, step], [seed & 0xFFFFFFFF, seed >> 32])[i & 3]
+        j = i + ((int(w) * (d - i)) >> 32)
+        out.append(a[j])
+        a[j] = a[i]
+    assert sorted(out) == list(orc.sample_positions(d, k, seed, step, layer, node))
+
+
+def _random_csr(rng, n, avg_deg, allow_dups=False):
+    rows = []
+    for v in range(n):
+        d = int(rng.integers(0, 2 * avg_deg + 1))
+        if allow_dups:
+            r = np.sort(rng.integers(0, n, size=d))
+        else:
+            r = np.sort(rng.choice(n, size=min(d, n), replace=False))
+        rows.append(r.astype(np.int32))
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    indptr[1:] = np.cumsum([len(r) for r in rows])
+    return indptr, (np.concatenate(rows) if n else np.zeros(0, np.int32)).astype(np.int32)
+
+
+def _check_block(indptr, indices, dst, fanout, blk):
+    n_dst = len(dst)
+    assert blk.n_dst == n_dst
+    assert np.array_equal(blk.src_nodes[:n_dst], dst)                       # dst prefix
+    assert len(np.unique(blk.src_nodes)) == blk.n_src                        # unique
+    tail = blk.src_nodes[n_dst:]
+    assert np.all(np.diff(tail) > 0)                                         # ascending tail
+    assert np.all((blk.cols >= 0) & (blk.cols < blk.n_src))
+    if len(tail):
+        assert set(range(n_dst, blk.n_src)) <= set(blk.cols.tolist())        # every new node is used
+    for i, v in enumerate(dst):
+        row = indices[indptr[v]:indptr[v + 1]]
+        got = blk.src_nodes[blk.cols[blk.indptr[i]:blk.indptr[i + 1]]]
+        assert len(got) == min(len(row), fanout)
+        if len(row) <= fanout:
+            assert np.array_equal(got, row)
+        else:
+            # true neighbours, drawn without replacement (compare as multisets of positions)
+            rl = row.tolist()
+            for g in got:
+                assert g in rl
+                rl.remove(g)
+    # transposed block holds the same edges, rows ascending per segment
+    edges = sorted((int(c), i) for i in range(n_dst) for c in blk.cols[blk.indptr[i]:blk.indptr[i + 1]])
+    tedges = [(j, int(r)) for j in range(blk.n_src) for r in blk.t_rows[blk.t_indptr[j]:blk.t_indptr[j + 1]]]
+    assert edges == tedges
+    assert blk.t_indptr[-1] == blk.nnz
+
+
+@pytest.mark.parametrize("dups", [False, True])
+def test_block_invariants(dups):
+    rng = np.random.default_rng(5)
+    indptr, indices = _random_csr(rng, 300, 8, allow_dups=dups)
+    dst = rng.choice(300, size=40, replace=False).astype(np.int32)
+    for fanout in (0, 1, 4, 100):
+        blk = orc.sample_block(indptr, indices, dst, fanout, 3, 1, 0)
+        _check_block(indptr, indices, dst, fanout, blk)
+
+
+def test_blocks_chain_and_fanout_order():
+    rng = np.random.default_rng(6)
+    indptr, indices = _random_csr(rng, 500, 12)
+    seeds = rng.choice(500, size=16, replace=False).astype(np.int32)
+    blocks = orc.sample_blocks(indptr, indices, seeds, [7, 3], 9, 2)
+    # the seeds are sampled with the LAST fan-out, the outer frontier with the first
+    assert np.array_equal(blocks[1].src_nodes[:16], seeds)
+    assert np.array_equal(blocks[0].src_nodes[:blocks[0].n_dst], blocks[1].src_nodes)
+    assert np.max(np.diff(blocks[1].indptr)) <= 3 and np.max(np.diff(blocks[0].indptr)) <= 7
+    assert np.max(np.diff(blocks[0].indptr)) > 3
+    _check_block(indptr, indices, blocks[1].src_nodes, 7, blocks[0])
+    # empty seed set
+    empty = orc.sample_blocks(indptr, indices, np.zeros(0, np.int32), [7, 3], 9, 2)
+    assert empty[0].n_src == 0 and empty[0].nnz == 0
+
+
+# ----------------------------------------------------------------- gather
+def test_gather_is_bit_copy():
+    rng = np.random.default_rng(0)
+    X = rng.standard_normal((50, 7)).astype(np.float32)
+    X[3, 2] = np.nan
+    X[4, 1] = -0.0
+    idx = rng.integers(0, 50, size=200).astype(np.int32)
+    assert np.array_equal(orc.gather_rows(X, idx).view(np.uint32), X[idx].view(np.uint32))
+    Xb = rng.integers(0, 65536, size=(50, 5)).astype(np.uint16)
+    assert np.array_equal(orc.gather_rows(Xb, idx), Xb[idx])
+
+
+# ----------------------------------------------------------------- mean aggregation
+def _block_from_rows(rows):
+    indptr = np.zeros(len(rows) + 1, dtype=np.int32)
+    indptr[1:] = np.cumsum([len(r) for r in rows])
+    cols = np.array([c for r in rows for c in r], dtype=np.int32)
+    return indptr, cols
+
+
+def test_aggregate_hand_graphs():
+    # star: node 0 is the centre, 1..4 the leaves
+    X = np.array([[10., 1.], [2., 4.], [4., 8.], [6., 0.], [8., -4.]])
+    ip, cols = _block_from_rows([[1, 2, 3, 4], [0], [0], [0], [0]])
+    A = orc.aggregate_fwd(ip, cols, X)
+    assert np.array_equal(A[0], [5., 2.])
+    for leaf in range(1, 5):
+        assert np.array_equal(A[leaf], X[0])
+    # path 0-1-2-3
+    ip, cols = _block_from_rows([[1], [0, 2], [1, 3], [2]])
+    A = orc.aggregate_fwd(ip, cols, X[:4])
+    assert np.array_equal(A, [[2., 4.], [7., 4.5], [4., 2.], [4., 8.]])
+    # isolated row -> zeros; self-loop -> own row takes part; duplicate edge counts twice
+    ip, cols = _block_from_rows([[], [1, 2], [0, 0, 1]])
+    A = orc.aggregate_fwd(ip, cols, X[:3])
+    assert np.array_equal(A[0], [0., 0.])
+    assert np.array_equal(A[1], [3., 6.])
+    assert np.allclose(A[2], [(10 + 10 + 2) / 3, (1 + 1 + 4) / 3], rtol=0, atol=1e-15)
+
+
+def test_aggregate_equals_dense_normalised_adjacency():
+    rng = np.random.default_rng(2)
+    indptr, indices = _random_csr(rng, 60, 5, allow_dups=True)
+    X = rng.standard_normal((60, 9))
+    adj = np.zeros((60, 60))
+    for v in range(60):
+        for u in indices[indptr[v]:indptr[v + 1]]:
+            adj[v, u] += 1.0
+    deg = adj.sum(1, keepdims=True)
+    dense = np.divide(adj @ X, deg, out=np.zeros_like(X), where=deg > 0)
+    A = orc.aggregate_fwd(indptr, indices, X)
+    assert np.allclose(A, dense, rtol=1e-13, atol=1e-13)
+    # full fan-out sampling reproduces the same thing through a block
+    dst = np.arange(60, dtype=np.int32)
+    blk = orc.sample_block(indptr, indices, dst, 1000, 0, 0, 0)
+    A2 = orc.aggregate_fwd(blk.indptr, blk.cols, X[blk.src_nodes])
+    assert np.allclose(A2, dense, rtol=1e-13, atol=1e-13)
+    # constant features stay constant on rows that have neighbours
+    Ac = orc.aggregate_fwd(indptr, indices, np.full((60, 3), 2.5))
+    assert np.array_equal(Ac[deg[:, 0] > 0], np.full((int((deg > 0).sum()), 3), 2.5))
+
+
+# ----------------------------------------------------------------- projection
+def test_linear_matches_matmul_and_special_cases():
+    rng = np.random.default_rng(3)
+    n, fin, fout = 13, 5, 4
+    H, A = rng.standard_normal((n + 3, fin)), rng.standard_normal((n, fin))
+    W, b = rng.standard_normal((2 * fin, fout)), rng.standard_normal(fout)
+    ref = np.concatenate([H[:n], A], axis=1) @ W + b
+    assert np.allclose(orc.linear_fwd(H, A, W, b, relu=False), ref, rtol=1e-13, atol=1e-13)
+    assert np.allclose(orc.linear_fwd(H, A, W, b, relu=True), np.maximum(ref, 0), rtol=1e-13, atol=1e-13)
+    assert np.array_equal(orc.linear_fwd(H, A, np.zeros_like(W), b, relu=False), np.tile(b, (n, 1)))
+    Wid = np.concatenate([np.eye(fin), np.zeros((fin, fin))])
+    assert np.array_equal(orc.linear_fwd(H, A, Wid, np.zeros(fin), relu=False), H[:n])
+    Wid2 = np.concatenate([np.zeros((fin, fin)), np.eye(fin)])
+    assert np.array_equal(orc.linear_fwd(H, A, Wid2, np.zeros(fin), relu=False), A)
+
+
+# ----------------------------------------------------------------- loss
+@pytest.mark.parametrize("C", [8, 47, 41, 172])
+def test_loss_at_zero_logits_is_log_classes(C):
+    B = 6
+    y = np.arange(B, dtype=np.int32) % C
+    loss, dZ = orc.softmax_xent(np.zeros((B, C)), y)
+    assert abs(loss - math.log(C)) < 1e-14
+    expect = np.full((B, C), 1.0 / C)
+    expect[np.arange(B), y] -= 1.0
+    assert np.allclose(dZ, expect / B, rtol=0, atol=1e-16)
+
+
+def test_loss_matches_library_and_is_shift_invariant():
+    rng = np.random.default_rng(4)
+    Z = rng.standard_normal((9, 11)) * 5
+    y = rng.integers(0, 11, size=9).astype(np.int32)
+    loss, dZ = orc.softmax_xent(Z, y)
+    zt = torch.tensor(Z, requires_grad=True)
+    lt = torch.nn.functional.cross_entropy(zt, torch.tensor(y, dtype=torch.long))
+    lt.backward()
+    assert abs(loss - lt.item()) < 1e-13
+    assert np.allclose(dZ, zt.grad.numpy(), rtol=1e-12, atol=1e-15)
+    assert np.allclose(dZ.sum(1), 0, atol=1e-16)
+    loss2, _ = orc.softmax_xent(Z + 1000.0, y)                      # max-subtraction
+    assert abs(loss - loss2) < 1e-9
+
+
+# ----------------------------------------------------------------- backward
+def _tiny_problem(L, seed=0, n=24, F=3, Hd=4, C=3):
+    rng = np.random.default_rng(seed)
+    indptr, indices = _random_csr(rng, n, 3, allow_dups=True)
+    X = rng.standard_normal((n, F)).astype(np.float32)
+    y = rng.integers(0, C, size=n).astype(np.int32)
+    dims = [F] + [Hd] * (L - 1) + [C]
+    W = [rng.standard_normal((2 * dims[l], dims[l + 1])) * 0.7 for l in range(L)]
+    b = [rng.standard_normal(dims[l + 1]) * 0.3 for l in range(L)]
+    seeds = rng.choice(n, size=6, replace=False).astype(np.int32)
+    fanouts = [3, 2, 2][:L]
+    return indptr, indices, X, y, seeds, fanouts, W, b
+
+
+def _loss_only(blocks, H0, W, b, y_seeds):
+    H, _ = orc.forward(blocks, H0, W, b)
+    return orc.softmax_xent(H[-1], y_seeds)[0], H
+
+
+@pytest.mark.parametrize("L", [2, 3])
+def test_gradients_by_central_differences(L):
+    indptr, indices, X, y, seeds, fanouts, W, b = _tiny_problem(L, seed=L)
+    out = orc.train_step(indptr, indices, X, y, seeds, fanouts, W, b, seed=1, step=0, lr=0.0)
+    blocks, H0 = out["blocks"], out["H"][0]
+    # keep the check meaningful: no pre-activation may sit at the ReLU kink
+    for l in range(1, L):
+        nz = out["H"][l][np.abs(out["H"][l]) > 0]
+        assert np.min(np.abs(nz)) > 1e-4
+    h = 1e-6
+    ys = y[seeds]
+    for l in range(L):
+        for P, G in ((W, out["dW"]), (b, out["db"])):
+            flat = P[l].reshape(-1)
+            g = G[l].reshape(-1)
+            for idx in range(flat.size):
+                keep = flat[idx]
+                flat[idx] = keep + h
+                lp, _ = _loss_only(blocks, H0, W, b, ys)
+                flat[idx] = keep - h
+                lm, _ = _loss_only(blocks, H0, W, b, ys)
+                flat[idx] = keep
+                fd = (lp - lm) / (2 * h)
+                assert abs(fd - g[idx]) <= 1e-6 * max(1.0, abs(g[idx])) + 1e-9, (l, idx, fd, g[idx])
+
+
+@pytest.mark.parametrize("L", [2, 3])
+def test_gradients_match_autograd(L):
+    # An independent derivation: the same model written with torch CPU ops in
+    # fp64 (index_add for the mean) and differentiated by autograd.
+    indptr, indices, X, y, seeds, fanouts, W, b = _tiny_problem(L, seed=10 + L, n=40)
+    out = orc.train_step(indptr, indices, X, y, seeds, fanouts, W, b, seed=5, step=3, lr=0.0)
+    blocks = out["blocks"]
+    Wt = [torch.tensor(w, requires_grad=True) for w in W]
+    bt = [torch.tensor(v, requires_grad=True) for v in b]
+    h = torch.tensor(X[blocks[0].src_nodes].astype(np.float64))
+    inter = []
+    for l, blk in enumerate(blocks):
+        rows = torch.repeat_interleave(torch.arange(blk.n_dst), torch.tensor(np.diff(blk.indptr)).long())
+        agg = torch.zeros(blk.n_dst, h.shape[1], dtype=torch.float64)
+        agg = agg.index_add(0, rows, h[torch.tensor(blk.cols).long()])
+        m = torch.tensor(np.diff(blk.indptr).astype(np.float64)).clamp(min=1).unsqueeze(1)
+        z = torch.cat([h[:blk.n_dst], agg / m], dim=1) @ Wt[l] + bt[l]
+        h = torch.relu(z) if l < L - 1 else z
+        h.retain_grad()
+        inter.append(h)
+    loss = torch.nn.functional.cross_entropy(h, torch.tensor(y[seeds]).long())
+    loss.backward()
+    assert abs(loss.item() - out["loss"]) < 1e-12
+    for l in range(L):
+        assert np.allclose(out["dW"][l], Wt[l].grad.numpy(), rtol=1e-10, atol=1e-13)
+        assert np.allclose(out["db"][l], bt[l].grad.numpy(), rtol=1e-10, atol=1e-13)
+    for l in range(1, L):
+        # dH[l] is the gradient w.r.t. the activations entering layer l
+        assert np.allclose(out["dH"][l], inter[l - 1].grad.numpy(), rtol=1e-10, atol=1e-13)
+
+
+def test_aggregate_bwd_is_the_transpose_of_fwd():
+    rng = np.random.default_rng(8)
+    indptr, indices = _random_csr(rng, 80, 6, allow_dups=True)
+    dst = rng.choice(80, size=20, replace=False).astype(np.int32)
+    blk = orc.sample_block(indptr, indices, dst, 4, 2, 0, 1)
+    H = rng.standard_normal((blk.n_src, 5))
+    G = rng.standard_normal((blk.n_dst, 5))
+    S = rng.standard_normal((blk.n_dst, 5))
+    A = orc.aggregate_fwd(blk.indptr, blk.cols, H)
+    dH = orc.aggregate_bwd(blk.indptr, blk.cols, blk.n_src, G, None)
+    assert abs((A * G).sum() - (H * dH).sum()) < 1e-11                      # <A(H),G> = <H,A^T(G)>
+    dH2 = orc.aggregate_bwd(blk.indptr, blk.cols, blk.n_src, G, S)
+    assert np.allclose(dH2[:blk.n_dst] - dH[:blk.n_dst], S, atol=1e-14)
+    has = np.diff(blk.indptr) > 0
+    assert np.allclose(dH2.sum(0), S.sum(0) + G[has].sum(0), atol=1e-12)   # conservation
+    # the same result through the transposed block (what a gather-style kernel reads)
+    m = np.diff(blk.indptr).astype(np.float64)
+    viaT = np.zeros_like(dH)
+    for j in range(blk.n_src):
+        for r in blk.t_rows[blk.t_indptr[j]:blk.t_indptr[j + 1]]:
+            viaT[j] += G[r] / m[r]
+    assert np.allclose(viaT, dH, atol=1e-14)
+
+
+# ----------------------------------------------------------------- update
+def test_sgd_step():
+    indptr, indices, X, y, seeds, fanouts, W, b = _tiny_problem(2, seed=21)
+    out0 = orc.train_step(indptr, indices, X, y, seeds, fanouts, W, b, seed=1, step=0, lr=0.0)
+    for l in range(2):
+        assert np.array_equal(out0["W_new"][l], W[l]) and np.array_equal(out0["b_new"][l], b[l])
+    out1 = orc.train_step(indptr, indices, X, y, seeds, fanouts, W, b, seed=1, step=0, lr=0.05)
+    assert np.allclose(out1["W_new"][0], W[0] - 0.05 * out0["dW"][0], rtol=0, atol=1e-15)
+    out2 = orc.train_step(indptr, indices, X, y, seeds, fanouts, out1["W_new"], out1["b_new"], seed=1, step=0, lr=0.0)
+    assert out2["loss"] < out0["loss"]
+
+
+# ----------------------------------------------------------------- bf16 storage
+def test_round_bf16_matches_library_rounding():
+    rng = np.random.default_rng(11)
+    x32 = np.concatenate([
+        rng.standard_normal(5000).astype(np.float32) * np.float32(10.0) ** rng.integers(-30, 30, 5000).astype(np.float32),
+        np.array([0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3.3895314e38, 1e-40, -3e-39, 65280.0], dtype=np.float32)])
+    got = orc.round_bf16(x32.astype(np.float64))
+    ref = torch.tensor(x32).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(got, ref)
+    # ties go to even: 1 + 2^-8 is halfway between 1 and 1 + 2^-7
+    assert orc.round_bf16(np.array([1.0 + 2.0 ** -8]))[0] == 1.0
+    assert orc.round_bf16(np.array([1.0 + 3 * 2.0 ** -8]))[0] == 1.0 + 2.0 ** -6
+    bits = np.array([0x3F80, 0xC000, 0x0001, 0x7F7F], dtype=np.uint16)
+    assert np.array_equal(orc.bf16_bits_to_f64(bits), [1.0, -2.0, 2.0 ** -133, 3.3895313892515355e38])
+
+
+def test_bf16_step_rounds_only_where_stored():
+    indptr, indices, X, y, seeds, fanouts, W, b = _tiny_problem(3, seed=33, n=40, F=4, Hd=6, C=5)
+    Xb = (torch.tensor(X).to(torch.bfloat16).view(torch.int16).numpy()).view(np.uint16)
+    out = orc.train_step(indptr, indices, Xb, y, seeds, fanouts, W, b, seed=2, step=1, lr=0.1, bf16=True)
+    is_bf16 = lambda t: np.array_equal(orc.round_bf16(t), t)
+    assert all(is_bf16(a) for a in out["A"]) and all(is_bf16(h) for h in out["H"][:-1])
+    assert not is_bf16(out["logits"])
+    assert all(is_bf16(out["dSelf"][l]) and is_bf16(out["dAgg"][l]) and is_bf16(out["dH"][l]) for l in (1, 2))
+    ref = orc.train_step(indptr, indices, orc.bf16_bits_to_f64(Xb).astype(np.float32), y, seeds, fanouts, W, b,
+                         seed=2, step=1, lr=0.1)
+    assert abs(out["loss"] - ref["loss"]) < 2e-2 * max(1.0, abs(ref["loss"]))
+    for l in range(3):
+        assert np.max(np.abs(out["dW"][l] - ref["dW"][l])) <= 3e-2 * np.max(np.abs(ref["dW"][l]))

@@ -1,0 +1,222 @@
+/*
+ * sdt.h -- C ABI of the MI355X (gfx950) per-worker GraphSAGE-mean training step.
+ *
+ * The operations are the ones a worker of the paper's training loop runs on
+ * its own partition for every mini-batch (Sec. II-A "Distributed GNN
+ * Training": graph sampling, neighbourhood aggregation, per-mini-batch
+ * gradients; Sec. III-B: a partition keeps the full neighbour list of the
+ * nodes it owns; Sec. III-E: sampler + graph store with feature data +
+ * GraphSAGE model).  The paper fixes none of the details; the conventions are
+ * stated per call below.
+ *
+ * General rules
+ *  - Every function returns an sdt_status.  No exceptions, no aborts, nothing
+ *    is printed.  sdt_last_error() gives a thread-local message for the last
+ *    failing call on the calling thread.
+ *  - Every pointer is a DEVICE pointer owned by the caller unless its comment
+ *    says "host".  The library allocates and frees no device memory and keeps
+ *    no state between calls; scratch space is passed in as `ws`/`ws_bytes`
+ *    (size from the matching *_workspace_bytes query, pure host arithmetic
+ *    on the upper bounds; contents need no initialisation and are garbage
+ *    afterwards).  Workspace and all row pointers must be 16-byte aligned.
+ *  - `stream` is a hipStream_t (NULL = default stream).  All work is enqueued
+ *    asynchronously; no call synchronises with the host.  Outputs are valid
+ *    once the stream has been synchronised.  Two calls that share a workspace
+ *    must be ordered by the caller.
+ *  - Sizes that depend on the data (frontier sizes, edge counts) stay on the
+ *    device.  A row count is passed as a host upper bound `*_cap` (sizes the
+ *    launch) plus an optional device scalar `*_d` holding the true count
+ *    (NULL: the true count is the bound).
+ *  - Leading dimensions (`ld*`) are in elements and may exceed the row width.
+ *  - Node ids and block-local ids are int32; graph row offsets are int64.
+ */
+#ifndef SDT_H
+#define SDT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum sdt_status {
+    SDT_OK = 0,
+    SDT_ERR_INVALID_ARG = -1, /* null pointer, negative size, unknown dtype, fan-out out of range, overflow */
+    SDT_ERR_WORKSPACE = -2,   /* ws too small or misaligned */
+    SDT_ERR_HIP = -3          /* a HIP runtime call or launch failed */
+} sdt_status;
+
+typedef enum sdt_dtype {
+    SDT_F32 = 0, /* IEEE binary32 */
+    SDT_BF16 = 1 /* bfloat16 storage, fp32 accumulation */
+} sdt_dtype;
+
+#define SDT_MAX_LAYERS 8
+#define SDT_MAX_FANOUT 64 /* one wavefront lane per sampled neighbour */
+
+/* A partition's graph in CSR form.  Row v lists the neighbours of node v in
+ * indices[indptr[v] .. indptr[v+1]).  Rows may contain self-loops and repeated
+ * entries; a row must be shorter than 2^31. */
+typedef struct sdt_csr {
+    int64_t n_nodes;
+    const int64_t *indptr;  /* [n_nodes + 1] */
+    const int32_t *indices; /* [indptr[n_nodes]] */
+} sdt_csr;
+
+/* One sampled bipartite layer ("block").  Destination row i aggregates the
+ * source rows cols[indptr[i] .. indptr[i+1]).  src_nodes lists the global id
+ * of each source row; its first n_dst entries are the destination nodes in
+ * their given order, the rest are the newly reached nodes in ascending id.
+ * The transposed block (optional: pass both pointers or neither) lists for
+ * source j the destination rows that use it, ascending.
+ * counts = {n_dst, n_src, nnz, 0} on the device. */
+typedef struct sdt_block {
+    int32_t cap_dst;    /* host: upper bound on n_dst */
+    int32_t cap_src;    /* host: capacity of src_nodes, >= min(cap_dst*(1+fanout), n_nodes) */
+    int32_t cap_nnz;    /* host: capacity of cols / t_rows, >= cap_dst*fanout */
+    int32_t reserved;
+    int32_t *counts;    /* [4] */
+    int32_t *indptr;    /* [cap_dst + 1] */
+    int32_t *cols;      /* [cap_nnz] */
+    int32_t *src_nodes; /* [cap_src] */
+    int32_t *t_indptr;  /* [cap_src + 1] or NULL */
+    int32_t *t_rows;    /* [cap_nnz] or NULL */
+} sdt_block;
+
+/* Model of L GraphSAGE-mean layers.  Layer l maps dims[l] -> dims[l+1]:
+ * Z = H[:n_dst] W[l][0:in] + mean_neigh(H) W[l][in:2in] + b[l], ReLU on all
+ * but the last layer.  W[l] is fp32 [2*dims[l], dims[l+1]] row-major (rows
+ * 0..in-1 act on the node's own features), b[l] fp32 [dims[l+1]].
+ * dW/db (same shapes, nullable per layer) receive the gradients. */
+typedef struct sdt_model {
+    int32_t n_layers;
+    int32_t dims[SDT_MAX_LAYERS + 1];
+    float *W[SDT_MAX_LAYERS];
+    float *b[SDT_MAX_LAYERS];
+    float *dW[SDT_MAX_LAYERS];
+    float *db[SDT_MAX_LAYERS];
+} sdt_model;
+
+/* Byte offsets, inside the sdt_train_step workspace, of everything the step
+ * produces (so a caller can inspect it), plus the capacities they were sized
+ * for.  Index l is the GNN layer (0 = input-most).  H[0] is the gathered
+ * input [cap_src[0], dims[0]]; H[l+1] the output of layer l (H[L] = logits,
+ * always fp32); A[l] the mean-aggregated neighbours; dZ the loss gradient
+ * w.r.t. the logits (fp32); dH[l] (l >= 1) the gradient w.r.t. H[l] with the
+ * ReLU mask of layer l-1 already applied; dSelf/dAgg[l] (l >= 1) the input
+ * gradients of layer l's projection; dW/db the weight gradients (fp32).
+ * t_indptr/t_rows exist for l >= 1 only (layer 0 needs no input gradient). */
+typedef struct sdt_step_layout {
+    uint64_t total_bytes;
+    int32_t n_layers;
+    int32_t cap_dst[SDT_MAX_LAYERS];
+    int32_t cap_src[SDT_MAX_LAYERS];
+    int32_t cap_nnz[SDT_MAX_LAYERS];
+    uint64_t counts[SDT_MAX_LAYERS];
+    uint64_t indptr[SDT_MAX_LAYERS];
+    uint64_t cols[SDT_MAX_LAYERS];
+    uint64_t src_nodes[SDT_MAX_LAYERS];
+    uint64_t t_indptr[SDT_MAX_LAYERS];
+    uint64_t t_rows[SDT_MAX_LAYERS];
+    uint64_t H[SDT_MAX_LAYERS + 1];
+    uint64_t A[SDT_MAX_LAYERS];
+    uint64_t dZ;
+    uint64_t dH[SDT_MAX_LAYERS];
+    uint64_t dSelf[SDT_MAX_LAYERS];
+    uint64_t dAgg[SDT_MAX_LAYERS];
+    uint64_t dW[SDT_MAX_LAYERS];
+    uint64_t db[SDT_MAX_LAYERS];
+    uint64_t row_loss; /* fp32 [B]: per-seed loss before the mean */
+    uint64_t scratch;  /* internal */
+} sdt_step_layout;
+
+/* Library version as "major.minor.patch" (host string, static storage). */
+const char *sdt_version(void);
+/* Message of the last failing call on this thread (host string; "" if none). */
+const char *sdt_last_error(void);
+
+/* ---- sampling (Sec. II-A: mini-batch graph sampling; Sec. III-B: the full
+ * neighbour list of every owned node is present in the partition) ----------
+ * For each destination node v (distinct ids in [0, n_nodes)) with degree d:
+ * take all d neighbours if d <= fanout, else `fanout` distinct CSR positions
+ * chosen uniformly by a partial Fisher-Yates shuffle of the positions, step i
+ * swapping position i with position i + floor(r_i (d - i) / 2^32), r_i the
+ * Philox4x32-10 word (key = seed halves, counter = (i/4, v, layer, step),
+ * word i%4).  Neighbours are emitted in ascending CSR position.  Then builds
+ * the source frontier, local column ids, and (if requested) the transposed
+ * block; writes out->counts.  0 <= fanout <= SDT_MAX_FANOUT.
+ * Errors: INVALID_ARG for bad arguments or capacities below the bounds in
+ * sdt_block; WORKSPACE if ws is too small. */
+size_t sdt_sample_workspace_bytes(int64_t n_nodes, int32_t cap_dst, int32_t fanout);
+int32_t sdt_sample_csr(const sdt_csr *graph /*host struct*/, const int32_t *dst_nodes, int32_t n_dst_cap,
+                       const int32_t *n_dst_d, int32_t fanout, uint64_t seed, uint32_t step, uint32_t layer,
+                       const sdt_block *out /*host struct*/, void *ws, size_t ws_bytes, void *stream);
+
+/* ---- feature fetch (Sec. III-E: graph store holding the partition's node
+ * features) --- out[j, 0:F] = X[idx[j], 0:F] for j < n, a bit copy.
+ * idx values must lie inside X. */
+int32_t sdt_gather_features(const void *X, int64_t ldx, int32_t F, int32_t dtype, const int32_t *idx,
+                            int32_t n_cap, const int32_t *n_d, void *out, int64_t ldo, void *stream);
+
+/* ---- neighbourhood aggregation (Sec. II-A: "neighborhood aggregation as a
+ * key operation"), mean variant: A[i,:] = (1/m_i) sum_{e in row i} H[cols[e],:],
+ * m_i = row length, zeros when m_i = 0; fp32 accumulation in edge order.
+ * Uses blk->counts[0] rows. */
+int32_t sdt_sage_aggregate_fwd(const sdt_block *blk /*host struct*/, const void *H, int64_t ldh, int32_t F,
+                               int32_t dtype, void *A, int64_t lda, void *stream);
+/* Same over a whole graph with the identity frontier (layer-wise inference):
+ * row v aggregates H[indices[e],:] over its CSR row. */
+int32_t sdt_sage_aggregate_csr_fwd(const sdt_csr *graph /*host struct*/, const void *H, int64_t ldh, int32_t F,
+                                   int32_t dtype, void *A, int64_t lda, void *stream);
+/* Backward: dH[j,:] = [j < n_dst] dSelf[j,:] + sum over edges (i -> j) of
+ * dAgg[i,:]/m_i, for j < n_src, gathered through the transposed block (no
+ * atomics; deterministic).  dSelf may be NULL.  If relu_of != NULL the result
+ * is zeroed wherever relu_of[j,f] <= 0 (the ReLU mask of the layer that
+ * produced H; relu_of has the same dtype and leading dimension as dH).
+ * dH is overwritten. */
+int32_t sdt_sage_aggregate_bwd(const sdt_block *blk /*host struct*/, const void *dAgg, int64_t ldg,
+                               const void *dSelf, int64_t lds, const void *relu_of, int32_t F, int32_t dtype,
+                               void *dH, int64_t ldd, void *stream);
+
+/* ---- GraphSAGE projection (Sec. III-E / IV-A: GraphSAGE is the model trained)
+ * Y = act(Hself W[0:in,:] + A W[in:2in,:] + b), act = ReLU if relu else id.
+ * Hself, A are `dtype`; W, b fp32 (rounded to bf16 as MFMA operands when
+ * dtype is BF16); Y is `y_dtype`; accumulation fp32 on the matrix cores. */
+int32_t sdt_sage_linear_fwd(const void *Hself, int64_t ldh, const void *A, int64_t lda, int32_t n_cap,
+                            const int32_t *n_d, int32_t in, int32_t out, const float *W, const float *b,
+                            int32_t relu, int32_t dtype, void *Y, int64_t ldy, int32_t y_dtype, void *stream);
+/* Backward.  dZ = dY masked by Y > 0 when relu (Y in `dtype`, may be NULL
+ * otherwise); dW = [Hself|A]^T dZ (fp32 [2in,out]); db = column sums of dZ;
+ * dSelf = dZ W[0:in]^T and dAgg = dZ W[in:2in]^T in `dtype` with leading
+ * dimension ldi (pass both or neither).  dY is `dy_dtype`.  The reduction over
+ * rows is split and summed in a fixed order (deterministic). */
+size_t sdt_linear_bwd_workspace_bytes(int32_t n_cap, int32_t in, int32_t out);
+int32_t sdt_sage_linear_bwd(const void *dY, int64_t lddy, int32_t dy_dtype, const void *Y, int64_t ldy,
+                            int32_t relu, const void *Hself, int64_t ldh, const void *A, int64_t lda,
+                            int32_t n_cap, const int32_t *n_d, int32_t in, int32_t out, const float *W,
+                            int32_t dtype, float *dW, float *db, void *dSelf, void *dAgg, int64_t ldi,
+                            void *ws, size_t ws_bytes, void *stream);
+
+/* ---- the whole mini-batch step (Sec. II-A and III-D: local training on the
+ * worker's partition between two model synchronisations) -------------------
+ * blocks are sampled from the seeds outwards: layer L-1 uses fanouts[L-1] on
+ * the seeds, layer l's sources are layer l-1's destinations; then gather,
+ * forward, mean softmax cross-entropy over the B seeds against
+ * labels[seeds[i]], backward, and W -= lr dW, b -= lr db (plain SGD on the
+ * fp32 weights; lr = 0 leaves them bit-identical).  loss_d receives the loss.
+ * X is [n_nodes, F = dims[0]] in `dtype` with leading dimension ldx.
+ * sdt_train_step_layout fills `layout` (host) with the workspace size and
+ * the offsets of every intermediate. */
+int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const int32_t *fanouts /*host*/,
+                              const sdt_model *model /*host struct; only n_layers, dims read*/, int32_t dtype,
+                              sdt_step_layout *layout /*host*/);
+int32_t sdt_train_step(const sdt_csr *graph /*host struct*/, const void *X, int64_t ldx, int32_t dtype,
+                       const int32_t *labels, const int32_t *seeds, int32_t batch,
+                       const int32_t *fanouts /*host*/, const sdt_model *model /*host struct*/, uint64_t seed,
+                       uint32_t step, float lr, float *loss_d, void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SDT_H */

@@ -236,12 +236,36 @@ def forward(blocks: List[Block], H0, W, b, bf16: bool = False):
     return H, A
 
 
+def backward(blocks: List[Block], H, A, W, dZ, bf16: bool = False, relu_masks=None):
+    """Gradients of every layer from the loss gradient dZ w.r.t. the logits.
+    The ReLU derivative of hidden layer l is [H[l+1] > 0]; `relu_masks[l]`
+    (boolean, same shape) replaces that decision when given -- the parity
+    tests use it for pre-activations that sit within rounding of zero, where
+    either decision is valid."""
+    rnd = round_bf16 if bf16 else (lambda t: t)
+    L = len(blocks)
+    dH = rnd(dZ)
+    dW, db = [None] * L, [None] * L
+    dSelf, dAgg, dHs = [None] * L, [None] * L, [None] * L
+    for l in range(L - 1, -1, -1):
+        blk = blocks[l]
+        Y = H[l + 1]
+        if relu_masks is not None and l < L - 1 and relu_masks[l] is not None:
+            Y = np.asarray(relu_masks[l], dtype=np.float64)
+        dW[l], db[l], ds, da = linear_bwd(dH, Y, l < L - 1, H[l][:blk.n_dst], A[l], rnd(W[l]),
+                                          need_input_grad=(l > 0))
+        if l > 0:
+            dSelf[l], dAgg[l] = rnd(ds), rnd(da)
+            dH = rnd(aggregate_bwd(blk.indptr, blk.cols, blk.n_src, dAgg[l], dSelf[l]))
+            dHs[l] = dH
+    return dict(dW=dW, db=db, dSelf=dSelf, dAgg=dAgg, dH=dHs)
+
+
 def train_step(indptr, indices, X, y, seeds, fanouts, W, b, seed: int, step: int, lr: float,
-               bf16: bool = False, blocks: Optional[List[Block]] = None):
+               bf16: bool = False, blocks: Optional[List[Block]] = None, relu_masks=None):
     """One mini-batch step.  X is fp32 (or uint16 bf16 bit patterns when
     bf16=True); W[l] is [2*in_l, out_l], b[l] is [out_l].  Returns a dict with
     every intermediate the HIP path can expose."""
-    rnd = round_bf16 if bf16 else (lambda t: t)
     L = len(fanouts)
     if blocks is None:
         blocks = sample_blocks(indptr, indices, seeds, fanouts, seed, step)
@@ -251,18 +275,7 @@ def train_step(indptr, indices, X, y, seeds, fanouts, W, b, seed: int, step: int
     b = [np.asarray(v, dtype=np.float64) for v in b]
     H, A = forward(blocks, H0, W, b, bf16)
     loss, dZ = softmax_xent(H[L], np.asarray(y)[np.asarray(seeds)])
-    dH = rnd(dZ)
-    dW, db = [None] * L, [None] * L
-    dSelf, dAgg, dHs = [None] * L, [None] * L, [None] * L
-    for l in range(L - 1, -1, -1):
-        blk = blocks[l]
-        dW[l], db[l], ds, da = linear_bwd(dH, H[l + 1], l < L - 1, H[l][:blk.n_dst], A[l], rnd(W[l]),
-                                          need_input_grad=(l > 0))
-        if l > 0:
-            dSelf[l], dAgg[l] = rnd(ds), rnd(da)
-            dH = rnd(aggregate_bwd(blk.indptr, blk.cols, blk.n_src, dAgg[l], dSelf[l]))
-            dHs[l] = dH
-    W_new = [sgd(W[l], dW[l], lr) for l in range(L)]
-    b_new = [sgd(b[l], db[l], lr) for l in range(L)]
-    return dict(blocks=blocks, H=H, A=A, logits=H[L], loss=loss, dZ=dZ, dW=dW, db=db,
-                dSelf=dSelf, dAgg=dAgg, dH=dHs, W_new=W_new, b_new=b_new)
+    g = backward(blocks, H, A, W, dZ, bf16, relu_masks)
+    W_new = [sgd(W[l], g["dW"][l], lr) for l in range(L)]
+    b_new = [sgd(b[l], g["db"][l], lr) for l in range(L)]
+    return dict(blocks=blocks, H=H, A=A, logits=H[L], loss=loss, dZ=dZ, W=W, W_new=W_new, b_new=b_new, **g)

@@ -1,0 +1,276 @@
+"""Thin ctypes binding over libsdt.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (see include/sdt.h),
+takes torch tensors that already live on the GPU, passes their device pointers
+and the current torch stream, and raises SdtError when the library reports a
+failure.  Nothing is computed here; there is no fallback: if libsdt.so is
+missing the import of the library fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsdt.so")
+
+SDT_OK, SDT_ERR_INVALID_ARG, SDT_ERR_WORKSPACE, SDT_ERR_HIP = 0, -1, -2, -3
+SDT_F32, SDT_BF16 = 0, 1
+SDT_MAX_LAYERS = 8
+SDT_MAX_FANOUT = 64
+
+_vp, _i32, _i64, _u32, _u64, _sz = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32,
+                                    ctypes.c_uint64, ctypes.c_size_t)
+
+
+class SdtError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"sdt error {code}: {msg}")
+        self.code = code
+
+
+class sdt_csr(ctypes.Structure):
+    _fields_ = [("n_nodes", _i64), ("indptr", _vp), ("indices", _vp)]
+
+
+class sdt_block(ctypes.Structure):
+    _fields_ = [("cap_dst", _i32), ("cap_src", _i32), ("cap_nnz", _i32), ("reserved", _i32),
+                ("counts", _vp), ("indptr", _vp), ("cols", _vp), ("src_nodes", _vp),
+                ("t_indptr", _vp), ("t_rows", _vp)]
+
+
+class sdt_model(ctypes.Structure):
+    _fields_ = [("n_layers", _i32), ("dims", _i32 * (SDT_MAX_LAYERS + 1)),
+                ("W", _vp * SDT_MAX_LAYERS), ("b", _vp * SDT_MAX_LAYERS),
+                ("dW", _vp * SDT_MAX_LAYERS), ("db", _vp * SDT_MAX_LAYERS)]
+
+
+class sdt_step_layout(ctypes.Structure):
+    _L = SDT_MAX_LAYERS
+    _fields_ = [("total_bytes", _u64), ("n_layers", _i32),
+                ("cap_dst", _i32 * _L), ("cap_src", _i32 * _L), ("cap_nnz", _i32 * _L),
+                ("counts", _u64 * _L), ("indptr", _u64 * _L), ("cols", _u64 * _L), ("src_nodes", _u64 * _L),
+                ("t_indptr", _u64 * _L), ("t_rows", _u64 * _L),
+                ("H", _u64 * (_L + 1)), ("A", _u64 * _L), ("dZ", _u64),
+                ("dH", _u64 * _L), ("dSelf", _u64 * _L), ("dAgg", _u64 * _L),
+                ("dW", _u64 * _L), ("db", _u64 * _L), ("row_loss", _u64), ("scratch", _u64)]
+
+
+EXPORTS = {
+    "sdt_version": (ctypes.c_char_p, []),
+    "sdt_last_error": (ctypes.c_char_p, []),
+    "sdt_sample_workspace_bytes": (_sz, [_i64, _i32, _i32]),
+    "sdt_sample_csr": (_i32, [_vp, _vp, _i32, _vp, _i32, _u64, _u32, _u32, _vp, _vp, _sz, _vp]),
+    "sdt_gather_features": (_i32, [_vp, _i64, _i32, _i32, _vp, _i32, _vp, _vp, _i64, _vp]),
+    "sdt_sage_aggregate_fwd": (_i32, [_vp, _vp, _i64, _i32, _i32, _vp, _i64, _vp]),
+    "sdt_sage_aggregate_csr_fwd": (_i32, [_vp, _vp, _i64, _i32, _i32, _vp, _i64, _vp]),
+    "sdt_sage_aggregate_bwd": (_i32, [_vp, _vp, _i64, _vp, _i64, _vp, _i32, _i32, _vp, _i64, _vp]),
+    "sdt_sage_linear_fwd": (_i32, [_vp, _i64, _vp, _i64, _i32, _vp, _i32, _i32, _vp, _vp, _i32, _i32, _vp, _i64,
+                                   _i32, _vp]),
+    "sdt_linear_bwd_workspace_bytes": (_sz, [_i32, _i32, _i32]),
+    "sdt_sage_linear_bwd": (_i32, [_vp, _i64, _i32, _vp, _i64, _i32, _vp, _i64, _vp, _i64, _i32, _vp, _i32, _i32,
+                                   _vp, _i32, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
+    "sdt_train_step_layout": (_i32, [_i64, _i32, _vp, _vp, _i32, _vp]),
+    "sdt_train_step": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp, _i32, _vp, _vp, _u64, _u32, ctypes.c_float, _vp, _vp,
+                              _sz, _vp]),
+}
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libsdt.so (built by paper_2404_02300_amd.build); no fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                              "(there is no CPU or PyTorch fallback for the HIP path)")
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != SDT_OK:
+        raise SdtError(rc, lib().sdt_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda, "device tensor expected"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return SDT_F32
+    if t.dtype == torch.bfloat16:
+        return SDT_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def sdt_version() -> str:
+    return lib().sdt_version().decode()
+
+
+def sdt_last_error() -> str:
+    return lib().sdt_last_error().decode()
+
+
+# ----------------------------------------------------------------- graph / block holders
+class Csr:
+    """Device CSR (int64 indptr, int32 indices) plus its C struct."""
+
+    def __init__(self, indptr: torch.Tensor, indices: torch.Tensor):
+        assert indptr.dtype == torch.int64 and indices.dtype == torch.int32 and indptr.is_cuda and indices.is_cuda
+        self.indptr, self.indices = indptr.contiguous(), indices.contiguous()
+        self.n_nodes = indptr.numel() - 1
+        self.c = sdt_csr(self.n_nodes, self.indptr.data_ptr(), self.indices.data_ptr())
+
+
+class Block:
+    """Caller-owned device arrays of one sampled layer plus the C struct."""
+
+    def __init__(self, cap_dst: int, fanout: int, n_nodes: int, device, transposed: bool = True):
+        cap_nnz = cap_dst * fanout
+        cap_src = max(cap_dst, min(cap_dst + cap_nnz, n_nodes))
+        i32 = dict(dtype=torch.int32, device=device)
+        self.cap_dst, self.cap_src, self.cap_nnz = cap_dst, cap_src, cap_nnz
+        self.counts = torch.zeros(4, **i32)
+        self.indptr = torch.zeros(cap_dst + 1, **i32)
+        self.cols = torch.zeros(max(cap_nnz, 1), **i32)
+        self.src_nodes = torch.zeros(max(cap_src, 1), **i32)
+        self.t_indptr = torch.zeros(cap_src + 1, **i32) if transposed else None
+        self.t_rows = torch.zeros(max(cap_nnz, 1), **i32) if transposed else None
+        self.c = sdt_block(cap_dst, cap_src, cap_nnz, 0, self.counts.data_ptr(), self.indptr.data_ptr(),
+                           self.cols.data_ptr(), self.src_nodes.data_ptr(),
+                           self.t_indptr.data_ptr() if transposed else None,
+                           self.t_rows.data_ptr() if transposed else None)
+
+    @classmethod
+    def from_arrays(cls, indptr, cols, n_src: int, src_nodes=None, t_indptr=None, t_rows=None):
+        """Wrap existing device arrays (e.g. an oracle-built block uploaded for a unit test)."""
+        self = cls.__new__(cls)
+        dev = indptr.device
+        n_dst, nnz = indptr.numel() - 1, cols.numel()
+        self.cap_dst, self.cap_src, self.cap_nnz = n_dst, n_src, nnz
+        self.counts = torch.tensor([n_dst, n_src, nnz, 0], dtype=torch.int32, device=dev)
+        self.indptr, self.cols = indptr, cols
+        self.src_nodes, self.t_indptr, self.t_rows = src_nodes, t_indptr, t_rows
+        self.c = sdt_block(n_dst, n_src, nnz, 0, self.counts.data_ptr(), indptr.data_ptr(),
+                           cols.data_ptr() if nnz else None,
+                           src_nodes.data_ptr() if src_nodes is not None else None,
+                           t_indptr.data_ptr() if t_indptr is not None else None,
+                           t_rows.data_ptr() if t_rows is not None and nnz else None)
+        return self
+
+
+# ----------------------------------------------------------------- entry points
+def sdt_sample_workspace_bytes(n_nodes: int, cap_dst: int, fanout: int) -> int:
+    return lib().sdt_sample_workspace_bytes(n_nodes, cap_dst, fanout)
+
+
+def sdt_sample_csr(graph: Csr, dst_nodes: torch.Tensor, fanout: int, seed: int, step: int, layer: int, out: Block,
+                   ws: torch.Tensor, n_dst_d: Optional[torch.Tensor] = None, n_dst_cap: Optional[int] = None):
+    cap = dst_nodes.numel() if n_dst_cap is None else n_dst_cap
+    _check(lib().sdt_sample_csr(ctypes.byref(graph.c), _ptr(dst_nodes) if dst_nodes.numel() else None, cap,
+                                _ptr(n_dst_d), fanout, seed, step, layer, ctypes.byref(out.c), _ptr(ws),
+                                ws.numel() * ws.element_size(), _stream()))
+
+
+def sdt_gather_features(X: torch.Tensor, idx: torch.Tensor, out: torch.Tensor, n_d: Optional[torch.Tensor] = None):
+    _check(lib().sdt_gather_features(_ptr(X), X.stride(0), X.shape[1], dtype_code(X), _ptr(idx), idx.numel(),
+                                     _ptr(n_d), _ptr(out), out.stride(0), _stream()))
+
+
+def sdt_sage_aggregate_fwd(blk: Block, H: torch.Tensor, A: torch.Tensor):
+    _check(lib().sdt_sage_aggregate_fwd(ctypes.byref(blk.c), _ptr(H), H.stride(0), H.shape[1], dtype_code(H),
+                                        _ptr(A), A.stride(0), _stream()))
+
+
+def sdt_sage_aggregate_csr_fwd(graph: Csr, H: torch.Tensor, A: torch.Tensor):
+    _check(lib().sdt_sage_aggregate_csr_fwd(ctypes.byref(graph.c), _ptr(H), H.stride(0), H.shape[1], dtype_code(H),
+                                            _ptr(A), A.stride(0), _stream()))
+
+
+def sdt_sage_aggregate_bwd(blk: Block, dAgg: torch.Tensor, dSelf: Optional[torch.Tensor], dH: torch.Tensor,
+                           relu_of: Optional[torch.Tensor] = None):
+    _check(lib().sdt_sage_aggregate_bwd(ctypes.byref(blk.c), _ptr(dAgg), dAgg.stride(0), _ptr(dSelf),
+                                        dSelf.stride(0) if dSelf is not None else 0, _ptr(relu_of), dAgg.shape[1],
+                                        dtype_code(dAgg), _ptr(dH), dH.stride(0), _stream()))
+
+
+def sdt_sage_linear_fwd(Hself: torch.Tensor, A: torch.Tensor, W: torch.Tensor, b: torch.Tensor, relu: bool,
+                        Y: torch.Tensor, n_d: Optional[torch.Tensor] = None):
+    n, fin = A.shape
+    _check(lib().sdt_sage_linear_fwd(_ptr(Hself), Hself.stride(0), _ptr(A), A.stride(0), n, _ptr(n_d), fin,
+                                     W.shape[1], _ptr(W), _ptr(b), int(relu), dtype_code(A), _ptr(Y), Y.stride(0),
+                                     dtype_code(Y), _stream()))
+
+
+def sdt_linear_bwd_workspace_bytes(n_cap: int, fin: int, fout: int) -> int:
+    return lib().sdt_linear_bwd_workspace_bytes(n_cap, fin, fout)
+
+
+def sdt_sage_linear_bwd(dY: torch.Tensor, Y: Optional[torch.Tensor], relu: bool, Hself: torch.Tensor,
+                        A: torch.Tensor, W: torch.Tensor, dW: torch.Tensor, db: torch.Tensor,
+                        dSelf: Optional[torch.Tensor], dAgg: Optional[torch.Tensor], ws: torch.Tensor,
+                        n_d: Optional[torch.Tensor] = None):
+    n, fin = A.shape
+    _check(lib().sdt_sage_linear_bwd(_ptr(dY), dY.stride(0), dtype_code(dY), _ptr(Y),
+                                     Y.stride(0) if Y is not None else 0, int(relu), _ptr(Hself), Hself.stride(0),
+                                     _ptr(A), A.stride(0), n, _ptr(n_d), fin, W.shape[1], _ptr(W), dtype_code(A),
+                                     _ptr(dW), _ptr(db), _ptr(dSelf), _ptr(dAgg),
+                                     dSelf.stride(0) if dSelf is not None else 0, _ptr(ws),
+                                     ws.numel() * ws.element_size(), _stream()))
+
+
+def make_model(dims: Sequence[int], W: List[torch.Tensor], b: List[torch.Tensor],
+               dW: Optional[List[torch.Tensor]] = None, db: Optional[List[torch.Tensor]] = None) -> sdt_model:
+    m = sdt_model()
+    m.n_layers = len(dims) - 1
+    for i, d in enumerate(dims):
+        m.dims[i] = d
+    for l in range(m.n_layers):
+        assert W[l].dtype == torch.float32 and W[l].is_contiguous() and tuple(W[l].shape) == (2 * dims[l], dims[l + 1])
+        m.W[l], m.b[l] = W[l].data_ptr(), b[l].data_ptr()
+        m.dW[l] = dW[l].data_ptr() if dW is not None else None
+        m.db[l] = db[l].data_ptr() if db is not None else None
+    return m
+
+
+def sdt_train_step_layout(n_nodes: int, batch: int, fanouts: Sequence[int], model: sdt_model,
+                          dtype: int) -> sdt_step_layout:
+    lay = sdt_step_layout()
+    f = (_i32 * len(fanouts))(*fanouts)
+    _check(lib().sdt_train_step_layout(n_nodes, batch, f, ctypes.byref(model), dtype, ctypes.byref(lay)))
+    return lay
+
+
+def sdt_train_step(graph: Csr, X: torch.Tensor, labels: torch.Tensor, seeds: torch.Tensor, fanouts: Sequence[int],
+                   model: sdt_model, seed: int, step: int, lr: float, loss: torch.Tensor, ws: torch.Tensor):
+    f = (_i32 * len(fanouts))(*fanouts)
+    _check(lib().sdt_train_step(ctypes.byref(graph.c), _ptr(X), X.stride(0), dtype_code(X), _ptr(labels),
+                                _ptr(seeds), seeds.numel(), f, ctypes.byref(model), seed, step, lr, _ptr(loss),
+                                _ptr(ws), ws.numel() * ws.element_size(), _stream()))
+
+
+# ----------------------------------------------------------------- workspace views (for inspection)
+def ws_view(ws: torch.Tensor, offset: int, shape, dtype: torch.dtype) -> torch.Tensor:
+    """A tensor view of `shape`/`dtype` at byte `offset` of the uint8 workspace."""
+    n = 1
+    for s in shape:
+        n *= s
+    nbytes = n * torch.empty((), dtype=dtype).element_size()
+    return ws[offset:offset + nbytes].view(dtype).view(*shape)

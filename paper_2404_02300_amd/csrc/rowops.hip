@@ -1,0 +1,337 @@
+// Row-wise, bandwidth-bound stages on gfx950: feature gather, mean aggregation
+// (sampled block or whole CSR) and its backward through the transposed block.
+//
+// A row of F elements is handled by a group of G lanes (G = 8..64, the smallest
+// power of two that covers the row with one vector per lane, wider rows loop
+// in chunks).  Every lane moves the widest vector the row alignment allows
+// (16 B when rows are 16-byte aligned).  The edge loop issues a batch of
+// independent row loads before consuming them, so each wave keeps several KB
+// in flight; sums are taken in edge order in fp32, which makes the result
+// independent of the launch shape.
+#include "common.h"
+
+namespace sdt {
+namespace {
+
+constexpr int TB = 256;
+constexpr int UNROLL = 8;  // row loads in flight per lane
+
+template <int BYTES> struct Raw;
+template <> struct Raw<16> { using type = uint4; };
+template <> struct Raw<8> { using type = uint2; };
+template <> struct Raw<4> { using type = uint32_t; };
+template <> struct Raw<2> { using type = uint16_t; };
+
+template <typename T, int VE>
+struct Vec {
+    using raw_t = typename Raw<VE * sizeof(T)>::type;
+    union {
+        raw_t raw;
+        T e[VE];
+    };
+    __device__ __forceinline__ Vec() {}
+};
+
+template <typename T, int VE>
+__device__ __forceinline__ void load_f32(const T* p, float out[VE]) {
+    Vec<T, VE> v;
+    v.raw = *reinterpret_cast<const typename Vec<T, VE>::raw_t*>(p);
+#pragma unroll
+    for (int q = 0; q < VE; ++q) out[q] = to_f32<T>(v.e[q]);
+}
+
+template <typename T, int VE>
+__device__ __forceinline__ void store_f32(T* p, const float in[VE]) {
+    Vec<T, VE> v;
+#pragma unroll
+    for (int q = 0; q < VE; ++q) v.e[q] = from_f32<T>(in[q]);
+    *reinterpret_cast<typename Vec<T, VE>::raw_t*>(p) = v.raw;
+}
+
+// ---- gather: out[j,:] = X[idx[j],:] -------------------------------------------
+template <int VB, int G>
+__global__ __launch_bounds__(TB) void k_gather(const char* __restrict__ X, int64_t ldx_b, int row_b,
+                                               const int32_t* __restrict__ idx, int n_cap, const int32_t* n_d,
+                                               char* __restrict__ out, int64_t ldo_b) {
+    using raw_t = typename Raw<VB>::type;
+    const int n = dev_count(n_cap, n_d);
+    const int gl = threadIdx.x % G;
+    const int64_t ngrp = (int64_t)gridDim.x * (TB / G);
+    for (int64_t j = (int64_t)blockIdx.x * (TB / G) + threadIdx.x / G; j < n; j += ngrp) {
+        const char* src = X + (int64_t)idx[j] * ldx_b;
+        char* dst = out + j * ldo_b;
+        for (int b = gl * VB; b < row_b; b += G * VB)
+            *reinterpret_cast<raw_t*>(dst + b) = *reinterpret_cast<const raw_t*>(src + b);
+    }
+}
+
+// ---- mean aggregation forward ---------------------------------------------------
+template <typename T, int VE, int G, typename IP>
+__global__ __launch_bounds__(TB) void k_aggregate_fwd(const IP* __restrict__ indptr, const int32_t* __restrict__ cols,
+                                                      int64_t n_cap, const int32_t* n_d, const T* __restrict__ H,
+                                                      int64_t ldh, int F, T* __restrict__ A, int64_t lda) {
+    int64_t n = n_cap;
+    if (n_d) n = *n_d < n_cap ? *n_d : n_cap;
+    const int gl = threadIdx.x % G;
+    const int64_t ngrp = (int64_t)gridDim.x * (TB / G);
+    for (int64_t i = (int64_t)blockIdx.x * (TB / G) + threadIdx.x / G; i < n; i += ngrp) {
+        const IP e0 = indptr[i], e1 = indptr[i + 1];
+        const float m = (float)(e1 - e0);
+        for (int f0 = gl * VE; f0 < F; f0 += G * VE) {
+            float acc[VE];
+#pragma unroll
+            for (int q = 0; q < VE; ++q) acc[q] = 0.f;
+            for (IP e = e0; e < e1; e += UNROLL) {
+                int c[UNROLL];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) c[u] = (e + u < e1) ? cols[e + u] : -1;
+                float v[UNROLL][VE];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    if (c[u] >= 0) {
+                        load_f32<T, VE>(H + (int64_t)c[u] * ldh + f0, v[u]);
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < VE; ++q) v[u][q] = 0.f;
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+                    for (int q = 0; q < VE; ++q) acc[q] += v[u][q];
+            }
+            if (e1 > e0) {
+#pragma unroll
+                for (int q = 0; q < VE; ++q) acc[q] = acc[q] / m;
+            }
+            store_f32<T, VE>(A + i * lda + f0, acc);
+        }
+    }
+}
+
+// ---- mean aggregation backward (gather through the transposed block) ------------
+template <typename T, int VE, int G>
+__global__ __launch_bounds__(TB) void k_aggregate_bwd(const int32_t* __restrict__ t_indptr,
+                                                      const int32_t* __restrict__ t_rows,
+                                                      const int32_t* __restrict__ b_indptr, const int32_t* counts,
+                                                      const T* __restrict__ dAgg, int64_t ldg,
+                                                      const T* __restrict__ dSelf, int64_t lds,
+                                                      const T* __restrict__ relu_of, int F, T* __restrict__ dH,
+                                                      int64_t ldd) {
+    const int n_dst = counts[0], n_src = counts[1];
+    const int gl = threadIdx.x % G;
+    const int ngrp = gridDim.x * (TB / G);
+    for (int j = blockIdx.x * (TB / G) + threadIdx.x / G; j < n_src; j += ngrp) {
+        const int e0 = t_indptr[j], e1 = t_indptr[j + 1];
+        for (int f0 = gl * VE; f0 < F; f0 += G * VE) {
+            float acc[VE];
+            if (dSelf && j < n_dst) {
+                load_f32<T, VE>(dSelf + (int64_t)j * lds + f0, acc);
+            } else {
+#pragma unroll
+                for (int q = 0; q < VE; ++q) acc[q] = 0.f;
+            }
+            for (int e = e0; e < e1; e += UNROLL) {
+                int r[UNROLL];
+                float w[UNROLL];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) r[u] = (e + u < e1) ? t_rows[e + u] : -1;
+                float v[UNROLL][VE];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    if (r[u] >= 0) {
+                        w[u] = (float)(b_indptr[r[u] + 1] - b_indptr[r[u]]);
+                        load_f32<T, VE>(dAgg + (int64_t)r[u] * ldg + f0, v[u]);
+                    } else {
+                        w[u] = 1.f;
+#pragma unroll
+                        for (int q = 0; q < VE; ++q) v[u][q] = 0.f;
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+                    for (int q = 0; q < VE; ++q) acc[q] += v[u][q] / w[u];
+            }
+            if (relu_of) {
+                float y[VE];
+                load_f32<T, VE>(relu_of + (int64_t)j * ldd + f0, y);
+#pragma unroll
+                for (int q = 0; q < VE; ++q)
+                    if (!(y[q] > 0.f)) acc[q] = 0.f;
+            }
+            store_f32<T, VE>(dH + (int64_t)j * ldd + f0, acc);
+        }
+    }
+}
+
+// Largest power-of-two vector (bytes, <= 16) that divides every row start and the row width.
+int vec_bytes(size_t elem, int F, std::initializer_list<int64_t> lds, std::initializer_list<const void*> ptrs) {
+    int vb = 16;
+    auto fit = [&](uint64_t x) {
+        while (vb > (int)elem && (x % vb) != 0) vb >>= 1;
+    };
+    fit((uint64_t)F * elem);
+    for (int64_t ld : lds) fit((uint64_t)ld * elem);
+    for (const void* p : ptrs) fit(reinterpret_cast<uintptr_t>(p));
+    return vb;
+}
+
+int group_lanes(int vecs_per_row) {
+    int g = 8;
+    while (g < 64 && g < vecs_per_row) g <<= 1;
+    return g;
+}
+
+inline int grid_rows(int64_t rows, int G) {
+    int64_t b = (rows + (TB / G) - 1) / (TB / G);
+    if (b < 1) b = 1;
+    const int64_t cap = 256 * 64;  // enough blocks to fill every CU many times over
+    return (int)(b > cap ? cap : b);
+}
+
+// Dispatch over (dtype, vector width, group width) without writing the table out by hand.
+template <typename F32Fn, typename BF16Fn>
+bool dispatch(int32_t dtype, int ve, int G, F32Fn&& f32, BF16Fn&& bf) {
+#define SDT_G(T, VE, fn)                                  \
+    switch (G) {                                          \
+        case 8: fn(T{}, std::integral_constant<int, VE>{}, std::integral_constant<int, 8>{}); return true;   \
+        case 16: fn(T{}, std::integral_constant<int, VE>{}, std::integral_constant<int, 16>{}); return true; \
+        case 32: fn(T{}, std::integral_constant<int, VE>{}, std::integral_constant<int, 32>{}); return true; \
+        case 64: fn(T{}, std::integral_constant<int, VE>{}, std::integral_constant<int, 64>{}); return true; \
+    }
+    if (dtype == SDT_F32) {
+        switch (ve) {
+            case 4: SDT_G(float, 4, f32) break;
+            case 2: SDT_G(float, 2, f32) break;
+            case 1: SDT_G(float, 1, f32) break;
+        }
+    } else {
+        switch (ve) {
+            case 8: SDT_G(bf16_t, 8, bf) break;
+            case 4: SDT_G(bf16_t, 4, bf) break;
+            case 2: SDT_G(bf16_t, 2, bf) break;
+            case 1: SDT_G(bf16_t, 1, bf) break;
+        }
+    }
+#undef SDT_G
+    return false;
+}
+
+template <typename IP>
+int32_t launch_aggregate_fwd(const IP* indptr, const int32_t* cols, int64_t n_cap, const int32_t* n_d, const void* H,
+                             int64_t ldh, int32_t F, int32_t dtype, void* A, int64_t lda, hipStream_t st) {
+    if (n_cap == 0 || F == 0) return SDT_OK;
+    const size_t es = dtype_size(dtype);
+    const int ve = vec_bytes(es, F, {ldh, lda}, {H, A}) / (int)es;
+    const int G = group_lanes((F + ve - 1) / ve);
+    auto go = [&](auto t, auto vec, auto grp) {
+        using T = decltype(t);
+        constexpr int VE = decltype(vec)::value, GG = decltype(grp)::value;
+        hipLaunchKernelGGL((k_aggregate_fwd<T, VE, GG, IP>), dim3(grid_rows(n_cap, GG)), dim3(TB), 0, st, indptr, cols,
+                           n_cap, n_d, static_cast<const T*>(H), ldh, F, static_cast<T*>(A), lda);
+    };
+    if (!dispatch(dtype, ve, G, go, go)) {
+        set_error("aggregate_fwd: no kernel for dtype %d vec %d group %d", dtype, ve, G);
+        return SDT_ERR_INVALID_ARG;
+    }
+    SDT_CHECK_LAUNCH("aggregate_fwd");
+    return SDT_OK;
+}
+
+}  // namespace
+}  // namespace sdt
+
+using namespace sdt;
+
+extern "C" int32_t sdt_gather_features(const void* X, int64_t ldx, int32_t F, int32_t dtype, const int32_t* idx,
+                                       int32_t n_cap, const int32_t* n_d, void* out, int64_t ldo, void* stream) {
+    SDT_REQUIRE(dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_gather_features: unknown dtype %d", dtype);
+    SDT_REQUIRE(F >= 0 && n_cap >= 0 && ldx >= F && ldo >= F, SDT_ERR_INVALID_ARG,
+                "sdt_gather_features: bad sizes F=%d n=%d ldx=%lld ldo=%lld", F, n_cap, (long long)ldx, (long long)ldo);
+    if (n_cap == 0 || F == 0) return SDT_OK;
+    SDT_REQUIRE(X && idx && out, SDT_ERR_INVALID_ARG, "sdt_gather_features: null pointer");
+    const size_t es = dtype_size(dtype);
+    const int vb = vec_bytes(es, F, {ldx, ldo}, {X, out});
+    const int row_b = (int)(F * es);
+    const int G = group_lanes((row_b + vb - 1) / vb);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const char* Xc = static_cast<const char*>(X);
+    char* oc = static_cast<char*>(out);
+    const int64_t ldx_b = ldx * (int64_t)es, ldo_b = ldo * (int64_t)es;
+#define SDT_GATHER(VB, GG)                                                                                         \
+    hipLaunchKernelGGL((k_gather<VB, GG>), dim3(grid_rows(n_cap, GG)), dim3(TB), 0, st, Xc, ldx_b, row_b, idx, n_cap, \
+                       n_d, oc, ldo_b)
+#define SDT_GATHER_G(VB)                    \
+    switch (G) {                            \
+        case 8: SDT_GATHER(VB, 8); break;   \
+        case 16: SDT_GATHER(VB, 16); break; \
+        case 32: SDT_GATHER(VB, 32); break; \
+        default: SDT_GATHER(VB, 64); break; \
+    }
+    switch (vb) {
+        case 16: SDT_GATHER_G(16) break;
+        case 8: SDT_GATHER_G(8) break;
+        case 4: SDT_GATHER_G(4) break;
+        default: SDT_GATHER_G(2) break;
+    }
+#undef SDT_GATHER_G
+#undef SDT_GATHER
+    SDT_CHECK_LAUNCH("gather");
+    return SDT_OK;
+}
+
+extern "C" int32_t sdt_sage_aggregate_fwd(const sdt_block* blk, const void* H, int64_t ldh, int32_t F, int32_t dtype,
+                                          void* A, int64_t lda, void* stream) {
+    SDT_REQUIRE(blk, SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_fwd: null block");
+    SDT_REQUIRE(dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_fwd: unknown dtype %d", dtype);
+    SDT_REQUIRE(F >= 0 && blk->cap_dst >= 0 && ldh >= F && lda >= F, SDT_ERR_INVALID_ARG,
+                "sdt_sage_aggregate_fwd: bad sizes");
+    if (blk->cap_dst == 0 || F == 0) return SDT_OK;
+    SDT_REQUIRE(blk->counts && blk->indptr && H && A && (blk->cols || blk->cap_nnz == 0), SDT_ERR_INVALID_ARG,
+                "sdt_sage_aggregate_fwd: null pointer");
+    return launch_aggregate_fwd<int32_t>(blk->indptr, blk->cols, blk->cap_dst, blk->counts, H, ldh, F, dtype, A, lda,
+                                         static_cast<hipStream_t>(stream));
+}
+
+extern "C" int32_t sdt_sage_aggregate_csr_fwd(const sdt_csr* g, const void* H, int64_t ldh, int32_t F, int32_t dtype,
+                                              void* A, int64_t lda, void* stream) {
+    SDT_REQUIRE(g, SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_csr_fwd: null graph");
+    SDT_REQUIRE(dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_csr_fwd: unknown dtype %d", dtype);
+    SDT_REQUIRE(F >= 0 && g->n_nodes >= 0 && g->n_nodes <= 0x7FFFFFFF && ldh >= F && lda >= F, SDT_ERR_INVALID_ARG,
+                "sdt_sage_aggregate_csr_fwd: bad sizes");
+    if (g->n_nodes == 0 || F == 0) return SDT_OK;
+    SDT_REQUIRE(g->indptr && g->indices && H && A, SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_csr_fwd: null pointer");
+    return launch_aggregate_fwd<int64_t>(g->indptr, g->indices, g->n_nodes, nullptr, H, ldh, F, dtype, A, lda,
+                                         static_cast<hipStream_t>(stream));
+}
+
+extern "C" int32_t sdt_sage_aggregate_bwd(const sdt_block* blk, const void* dAgg, int64_t ldg, const void* dSelf,
+                                          int64_t lds, const void* relu_of, int32_t F, int32_t dtype, void* dH,
+                                          int64_t ldd, void* stream) {
+    SDT_REQUIRE(blk, SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_bwd: null block");
+    SDT_REQUIRE(dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_bwd: unknown dtype %d", dtype);
+    SDT_REQUIRE(F >= 0 && blk->cap_src >= 0 && ldg >= F && ldd >= F && (!dSelf || lds >= F), SDT_ERR_INVALID_ARG,
+                "sdt_sage_aggregate_bwd: bad sizes");
+    if (blk->cap_src == 0 || F == 0) return SDT_OK;
+    SDT_REQUIRE(blk->counts && blk->indptr && blk->t_indptr && blk->t_rows && dAgg && dH, SDT_ERR_INVALID_ARG,
+                "sdt_sage_aggregate_bwd: null pointer (the block needs its transposed arrays)");
+    const size_t es = dtype_size(dtype);
+    const int ve = vec_bytes(es, F, {ldg, ldd, dSelf ? lds : ldd}, {dAgg, dH, dSelf, relu_of}) / (int)es;
+    const int G = group_lanes((F + ve - 1) / ve);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    auto go = [&](auto t, auto vec, auto grp) {
+        using T = decltype(t);
+        constexpr int VE = decltype(vec)::value, GG = decltype(grp)::value;
+        hipLaunchKernelGGL((k_aggregate_bwd<T, VE, GG>), dim3(grid_rows(blk->cap_src, GG)), dim3(TB), 0, st,
+                           blk->t_indptr, blk->t_rows, blk->indptr, blk->counts, static_cast<const T*>(dAgg), ldg,
+                           static_cast<const T*>(dSelf), lds, static_cast<const T*>(relu_of), F, static_cast<T*>(dH),
+                           ldd);
+    };
+    if (!dispatch(dtype, ve, G, go, go)) {
+        set_error("sdt_sage_aggregate_bwd: no kernel for dtype %d vec %d group %d", dtype, ve, G);
+        return SDT_ERR_INVALID_ARG;
+    }
+    SDT_CHECK_LAUNCH("aggregate_bwd");
+    return SDT_OK;
+}

@@ -1,0 +1,553 @@
+// Fan-out neighbour sampling over a CSR partition and construction of the
+// sampled block (frontier, local column ids, transposed block) on gfx950.
+//
+// One wavefront samples one destination row: lane i owns Fisher-Yates step i
+// (its Philox word, its swap target); the k dependent swaps are resolved with
+// k rounds of cross-lane broadcasts instead of a per-row array.  Frontier
+// de-duplication is direct addressing: a bitmap over the partition's nodes is
+// marked with idempotent atomic ORs, scanned with popcount prefix sums (which
+// yields the new nodes in ascending id order for free) and a dense
+// node -> local-id map is extended.  Nothing depends on the order in which
+// waves run, so every index output is reproducible bit for bit.
+#include "common.h"
+
+namespace sdt {
+
+namespace {
+
+constexpr int TB = 256;           // threads per block
+constexpr int ITEMS = 8;          // scan items per thread
+constexpr int TILE = TB * ITEMS;  // scan items per block
+constexpr int SHORT_SEG = 32;     // transposed segments up to this length are sorted by one thread
+constexpr int LDS_SEG = 8192;     // ... up to this length by one block in LDS
+
+// ---- Philox4x32-10 (Salmon et al., SC'11) -------------------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                              uint32_t k1, uint32_t out[4]) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
+        uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
+        c0 = h1 ^ c1 ^ k0;
+        c1 = l1;
+        c2 = h0 ^ c3 ^ k1;
+        c3 = l0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+__global__ __launch_bounds__(TB) void k_fill_i32(int32_t* p, int64_t n, int32_t v) {
+    int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * TB;
+    for (; i < n; i += stride) p[i] = v;
+}
+
+__global__ __launch_bounds__(TB) void k_scatter_ids(int32_t* map, const int32_t* dst, int n_cap, const int32_t* n_d) {
+    int n = dev_count(n_cap, n_d);
+    for (int i = blockIdx.x * TB + threadIdx.x; i < n; i += gridDim.x * TB) map[dst[i]] = i;
+}
+
+// One wave per destination row.
+__global__ __launch_bounds__(TB) void k_sample_rows(const int64_t* __restrict__ indptr,
+                                                    const int32_t* __restrict__ indices,
+                                                    const int32_t* __restrict__ dst_nodes, int n_cap,
+                                                    const int32_t* n_d, int fanout, uint32_t k0, uint32_t k1,
+                                                    uint32_t step, uint32_t layer, const int32_t* __restrict__ map,
+                                                    uint32_t* bitmap, int32_t* __restrict__ e_pad,
+                                                    int32_t* __restrict__ m_out) {
+    const int n = dev_count(n_cap, n_d);
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wave = (blockIdx.x * TB + threadIdx.x) / WAVE;
+    const int nwaves = gridDim.x * TB / WAVE;
+    for (int i = wave; i < n; i += nwaves) {
+        const int v = dst_nodes[i];
+        const int64_t start = indptr[v];
+        const uint32_t d = (uint32_t)(indptr[v + 1] - start);
+        const int m = d < (uint32_t)fanout ? (int)d : fanout;
+        uint32_t pos = lane;
+        int rank = lane;
+        if (d > (uint32_t)fanout) {
+            uint32_t w[4];
+            philox4x32_10((uint32_t)lane >> 2, (uint32_t)v, layer, step, k0, k1, w);
+            const uint32_t r = w[lane & 3];
+            // step `lane` of the shuffle swaps position lane with position j
+            const uint32_t j = (uint32_t)lane + __umulhi(r, d - (uint32_t)lane);
+            uint32_t cur = j;      // content of position j just before step `lane`
+            uint32_t self = lane;  // content of position lane just before step `lane`
+            for (int t = 0; t < fanout; ++t) {
+                const uint32_t st = __builtin_amdgcn_readlane(self, t);
+                const uint32_t jt = __builtin_amdgcn_readlane(j, t);
+                if (lane > t) {
+                    if (jt == j) cur = st;
+                    if (jt == (uint32_t)lane) self = st;
+                }
+            }
+            pos = cur;
+            rank = 0;
+            for (int t = 0; t < fanout; ++t) {
+                const uint32_t pt = __builtin_amdgcn_readlane(pos, t);
+                rank += (pt < pos) ? 1 : 0;
+            }
+        }
+        if (lane < m) {
+            const int g = indices[start + pos];
+            e_pad[(int64_t)i * fanout + rank] = g;
+            if (map[g] < 0) {
+                const uint32_t bit = 1u << (g & 31);
+                if (!(bitmap[g >> 5] & bit)) atomicOr(&bitmap[g >> 5], bit);
+            }
+        }
+        if (lane == 0) m_out[i] = m;
+    }
+}
+
+// ---- block-level exclusive scan of ITEMS values per thread --------------------
+__device__ __forceinline__ int wave_incl_scan(int x) {
+    const int lane = threadIdx.x & (WAVE - 1);
+#pragma unroll
+    for (int o = 1; o < WAVE; o <<= 1) {
+        int y = __shfl_up(x, o);
+        if (lane >= o) x += y;
+    }
+    return x;
+}
+
+// Returns the exclusive prefix of `sum` over the block's threads; *total = block sum.
+__device__ __forceinline__ int block_excl_scan(int sum, int* total) {
+    __shared__ int wsum[TB / WAVE];
+    const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
+    const int incl = wave_incl_scan(sum);
+    __syncthreads();
+    if (lane == WAVE - 1) wsum[w] = incl;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int q = 0; q < TB / WAVE; ++q) {
+        if (q < w) base += wsum[q];
+        tot += wsum[q];
+    }
+    *total = tot;
+    return base + incl - sum;
+}
+
+// Pass 1 of the fused scans: blocks [0, pm) sum tiles of m[], blocks [pm, pm+pb)
+// sum popcounts of bitmap tiles.
+__global__ __launch_bounds__(TB) void k_front_partials(const int32_t* __restrict__ m, int n_cap, const int32_t* n_d,
+                                                       const uint32_t* __restrict__ bitmap, int nwords, int pm,
+                                                       int32_t* part) {
+    int sum = 0;
+    if ((int)blockIdx.x < pm) {
+        const int n = dev_count(n_cap, n_d);
+        const int base = blockIdx.x * TILE + threadIdx.x * ITEMS;
+#pragma unroll
+        for (int q = 0; q < ITEMS; ++q)
+            if (base + q < n) sum += m[base + q];
+    } else {
+        const int base = (blockIdx.x - pm) * TILE + threadIdx.x * ITEMS;
+#pragma unroll
+        for (int q = 0; q < ITEMS; ++q)
+            if (base + q < nwords) sum += __popc(bitmap[base + q]);
+    }
+    int total;
+    block_excl_scan(sum, &total);
+    if (threadIdx.x == 0) part[blockIdx.x] = total;
+}
+
+// Sequential-by-chunks exclusive scan of `cnt` values by one block; returns the total.
+__device__ int spine_scan(int32_t* p, int cnt) {
+    __shared__ int carry_s;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (int c0 = 0; c0 < cnt; c0 += TB) {
+        const int idx = c0 + threadIdx.x;
+        const int x = idx < cnt ? p[idx] : 0;
+        int total;
+        const int ex = block_excl_scan(x, &total);
+        const int carry = carry_s;
+        if (idx < cnt) p[idx] = carry + ex;
+        __syncthreads();
+        if (threadIdx.x == 0) carry_s = carry + total;
+        __syncthreads();
+    }
+    return carry_s;
+}
+
+__global__ __launch_bounds__(TB) void k_front_spine(int32_t* part, int pm, int pb, int n_cap, const int32_t* n_d,
+                                                    int32_t* counts, int32_t* b_indptr) {
+    const int n = dev_count(n_cap, n_d);
+    const int nnz = spine_scan(part, pm);
+    __syncthreads();
+    const int n_new = spine_scan(part + pm, pb);
+    if (threadIdx.x == 0) {
+        counts[0] = n;
+        counts[1] = n + n_new;
+        counts[2] = nnz;
+        counts[3] = 0;
+        b_indptr[n] = nnz;
+    }
+}
+
+// Pass 3: write b_indptr; emit the new frontier nodes (ascending id), extend the
+// node -> local-id map, clear the bitmap; zero the histogram of the transposed block.
+__global__ __launch_bounds__(TB) void k_front_apply(const int32_t* __restrict__ m, int n_cap, const int32_t* n_d,
+                                                    uint32_t* bitmap, int nwords, int pm,
+                                                    const int32_t* __restrict__ part, const int32_t* counts,
+                                                    int32_t* __restrict__ b_indptr, int32_t* __restrict__ src_nodes,
+                                                    const int32_t* __restrict__ dst_nodes, int32_t* map,
+                                                    int32_t* hist) {
+    const int n = dev_count(n_cap, n_d);
+    if ((int)blockIdx.x < pm) {
+        const int base = blockIdx.x * TILE + threadIdx.x * ITEMS;
+        int v[ITEMS], sum = 0;
+#pragma unroll
+        for (int q = 0; q < ITEMS; ++q) {
+            v[q] = (base + q < n) ? m[base + q] : 0;
+            sum += v[q];
+        }
+        int total;
+        int run = block_excl_scan(sum, &total) + part[blockIdx.x];
+#pragma unroll
+        for (int q = 0; q < ITEMS; ++q) {
+            if (base + q < n) {
+                b_indptr[base + q] = run;
+                src_nodes[base + q] = dst_nodes[base + q];  // destination prefix of the frontier
+            }
+            run += v[q];
+        }
+    } else {
+        const int base = (blockIdx.x - pm) * TILE + threadIdx.x * ITEMS;
+        uint32_t wd[ITEMS];
+        int sum = 0;
+#pragma unroll
+        for (int q = 0; q < ITEMS; ++q) {
+            wd[q] = (base + q < nwords) ? bitmap[base + q] : 0u;
+            sum += __popc(wd[q]);
+        }
+        int total;
+        int run = n + part[blockIdx.x] + block_excl_scan(sum, &total);
+#pragma unroll
+        for (int q = 0; q < ITEMS; ++q) {
+            uint32_t x = wd[q];
+            if (x) bitmap[base + q] = 0u;
+            while (x) {
+                const int b = __ffs(x) - 1;
+                x &= x - 1;
+                const int g = (base + q) * 32 + b;
+                src_nodes[run] = g;
+                map[g] = run;
+                ++run;
+            }
+        }
+    }
+    if (hist) {
+        const int n_src = counts[1];
+        for (int j = blockIdx.x * TB + threadIdx.x; j <= n_src; j += gridDim.x * TB) hist[j] = 0;
+    }
+}
+
+// cols[e] = local id of the sampled neighbour; optionally count the uses of each source.
+__global__ __launch_bounds__(TB) void k_relabel(const int32_t* __restrict__ e_pad, const int32_t* __restrict__ m,
+                                                const int32_t* __restrict__ b_indptr, int n_cap, const int32_t* n_d,
+                                                int fanout, const int32_t* __restrict__ map,
+                                                int32_t* __restrict__ cols, int32_t* hist) {
+    const int n = dev_count(n_cap, n_d);
+    const int64_t total = (int64_t)n * fanout;
+    for (int64_t idx = (int64_t)blockIdx.x * TB + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * TB) {
+        const int i = (int)(idx / fanout), t = (int)(idx - (int64_t)i * fanout);
+        if (t < m[i]) {
+            const int c = map[e_pad[idx]];
+            cols[b_indptr[i] + t] = c;
+            if (hist) atomicAdd(&hist[c], 1);
+        }
+    }
+}
+
+// ---- generic three-pass exclusive scan: out[0..n] from in[0..n), n = *n_d + n_add
+__global__ __launch_bounds__(TB) void k_scan_partials(const int32_t* __restrict__ in, const int32_t* n_d, int n_add,
+                                                      int32_t* part) {
+    const int n = *n_d + n_add;
+    const int base = blockIdx.x * TILE + threadIdx.x * ITEMS;
+    int sum = 0;
+#pragma unroll
+    for (int q = 0; q < ITEMS; ++q)
+        if (base + q < n) sum += in[base + q];
+    int total;
+    block_excl_scan(sum, &total);
+    if (threadIdx.x == 0) part[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(TB) void k_scan_spine(int32_t* part, int nparts, int32_t* long_count) {
+    spine_scan(part, nparts);
+    if (threadIdx.x == 0 && long_count) *long_count = 0;
+}
+
+// in-place capable: reads its tile fully before writing
+__global__ __launch_bounds__(TB) void k_scan_apply(const int32_t* in, const int32_t* n_d, int n_add,
+                                                   const int32_t* __restrict__ part, int32_t* out, int32_t* zero_me) {
+    const int n = *n_d + n_add;
+    const int base = blockIdx.x * TILE + threadIdx.x * ITEMS;
+    int v[ITEMS], sum = 0;
+#pragma unroll
+    for (int q = 0; q < ITEMS; ++q) {
+        v[q] = (base + q < n) ? in[base + q] : 0;
+        sum += v[q];
+    }
+    int total;
+    int run = block_excl_scan(sum, &total) + part[blockIdx.x];
+#pragma unroll
+    for (int q = 0; q < ITEMS; ++q) {
+        if (base + q < n) {
+            out[base + q] = run;
+            if (zero_me) zero_me[base + q] = 0;
+        }
+        run += v[q];
+    }
+}
+
+// t_rows filled in arbitrary order inside each segment (sorted afterwards).
+__global__ __launch_bounds__(TB) void k_transpose_fill(const int32_t* __restrict__ b_indptr,
+                                                       const int32_t* __restrict__ cols, int n_cap,
+                                                       const int32_t* n_d, int fanout,
+                                                       const int32_t* __restrict__ t_indptr, int32_t* cursor,
+                                                       int32_t* __restrict__ t_rows) {
+    const int n = dev_count(n_cap, n_d);
+    const int64_t total = (int64_t)n * fanout;
+    for (int64_t idx = (int64_t)blockIdx.x * TB + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * TB) {
+        const int i = (int)(idx / fanout), t = (int)(idx - (int64_t)i * fanout);
+        const int b0 = b_indptr[i];
+        if (t < b_indptr[i + 1] - b0) {
+            const int c = cols[b0 + t];
+            const int slot = atomicAdd(&cursor[c], 1);
+            t_rows[t_indptr[c] + slot] = i;
+        }
+    }
+}
+
+// Each segment ascending: short ones by one thread, the rest queued for k_sort_long.
+__global__ __launch_bounds__(TB) void k_sort_short(const int32_t* __restrict__ t_indptr, const int32_t* counts,
+                                                   int32_t* t_rows, int32_t* long_count, int32_t* long_list) {
+    const int n_src = counts[1];
+    for (int j = blockIdx.x * TB + threadIdx.x; j < n_src; j += gridDim.x * TB) {
+        const int b = t_indptr[j], len = t_indptr[j + 1] - b;
+        if (len <= 1) continue;
+        if (len > SHORT_SEG) {
+            long_list[atomicAdd(long_count, 1)] = j;
+            continue;
+        }
+        int32_t* s = t_rows + b;
+        for (int a = 1; a < len; ++a) {
+            const int x = s[a];
+            int q = a - 1;
+            while (q >= 0 && s[q] > x) {
+                s[q + 1] = s[q];
+                --q;
+            }
+            s[q + 1] = x;
+        }
+    }
+}
+
+__global__ __launch_bounds__(TB) void k_sort_long(const int32_t* __restrict__ t_indptr, int32_t* t_rows,
+                                                  const int32_t* long_count, const int32_t* long_list,
+                                                  int32_t* tmp) {
+    __shared__ int32_t buf[LDS_SEG];
+    const int cnt = *long_count;
+    for (int li = blockIdx.x; li < cnt; li += gridDim.x) {
+        const int j = long_list[li];
+        const int b = t_indptr[j], len = t_indptr[j + 1] - b;
+        if (len <= LDS_SEG) {
+            int p2 = 1;
+            while (p2 < len) p2 <<= 1;
+            for (int a = threadIdx.x; a < p2; a += TB) buf[a] = a < len ? t_rows[b + a] : 0x7FFFFFFF;
+            __syncthreads();
+            for (int k = 2; k <= p2; k <<= 1)
+                for (int s = k >> 1; s > 0; s >>= 1) {
+                    for (int a = threadIdx.x; a < p2; a += TB) {
+                        const int o = a ^ s;
+                        if (o > a) {
+                            const int x = buf[a], y = buf[o];
+                            const bool up = (a & k) == 0;
+                            if ((x > y) == up) { buf[a] = y; buf[o] = x; }
+                        }
+                    }
+                    __syncthreads();
+                }
+            for (int a = threadIdx.x; a < len; a += TB) t_rows[b + a] = buf[a];
+            __syncthreads();
+        } else {
+            // longer than the LDS buffer: place each element at its rank (quadratic, rare)
+            for (int a = threadIdx.x; a < len; a += TB) tmp[b + a] = t_rows[b + a];
+            __syncthreads();
+            for (int a0 = 0; a0 < len; a0 += TB) {
+                const int a = a0 + threadIdx.x;
+                const int x = a < len ? tmp[b + a] : 0;
+                int rank = 0;
+                for (int c0 = 0; c0 < len; c0 += LDS_SEG) {
+                    const int cl = min(LDS_SEG, len - c0);
+                    __syncthreads();
+                    for (int c = threadIdx.x; c < cl; c += TB) buf[c] = tmp[b + c0 + c];
+                    __syncthreads();
+                    if (a < len)
+                        for (int c = 0; c < cl; ++c) {
+                            const int y = buf[c];
+                            rank += (y < x || (y == x && c0 + c < a)) ? 1 : 0;
+                        }
+                }
+                if (a < len) t_rows[b + rank] = x;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+inline int grid_for(int64_t items, int per_block, int max_blocks) {
+    int64_t g = (items + per_block - 1) / per_block;
+    if (g < 1) g = 1;
+    if (g > max_blocks) g = max_blocks;
+    return (int)g;
+}
+
+}  // namespace
+
+size_t sample_ws_carve(Arena& a, int64_t n_nodes, int32_t cap_dst, int32_t fanout, SampleWs* out) {
+    const int64_t nwords = (n_nodes + 31) / 32;
+    const int64_t cap_nnz = (int64_t)cap_dst * fanout;
+    int64_t cap_src = (int64_t)cap_dst + cap_nnz;
+    if (cap_src > n_nodes) cap_src = n_nodes;
+    if (cap_src < cap_dst) cap_src = cap_dst;
+    const int64_t pm = (cap_dst + TILE - 1) / TILE, pb = (nwords + TILE - 1) / TILE;
+    const int64_t pt = (cap_src + 1 + TILE - 1) / TILE;
+    SampleWs w;
+    w.map = a.take<int32_t>(n_nodes);
+    w.bitmap = a.take<uint32_t>(nwords);
+    w.e_pad = a.take<int32_t>(cap_nnz > 0 ? cap_nnz : 1);
+    w.m = a.take<int32_t>(cap_dst > 0 ? cap_dst : 1);
+    w.part = a.take<int32_t>((pm + pb > pt ? pm + pb : pt) + 1);
+    w.cursor = a.take<int32_t>(cap_src + 1);
+    w.longlist = a.take<int32_t>(cap_src + 2);
+    if (out) *out = w;
+    return a.off;
+}
+
+int32_t sample_init_map(const SampleWs& ws, int64_t n_nodes, const int32_t* dst_nodes, int32_t n_dst_cap,
+                        const int32_t* n_dst_d, hipStream_t st) {
+    hipLaunchKernelGGL(k_fill_i32, dim3(grid_for(n_nodes, TB * 4, 4096)), dim3(TB), 0, st, ws.map, n_nodes, -1);
+    SDT_CHECK_LAUNCH("fill map");
+    hipLaunchKernelGGL(k_fill_i32, dim3(grid_for((n_nodes + 31) / 32, TB * 4, 2048)), dim3(TB), 0, st,
+                       reinterpret_cast<int32_t*>(ws.bitmap), (n_nodes + 31) / 32, 0);
+    SDT_CHECK_LAUNCH("fill bitmap");
+    hipLaunchKernelGGL(k_scatter_ids, dim3(grid_for(n_dst_cap, TB, 1024)), dim3(TB), 0, st, ws.map, dst_nodes,
+                       n_dst_cap, n_dst_d);
+    SDT_CHECK_LAUNCH("scatter ids");
+    return SDT_OK;
+}
+
+int32_t sample_layer(const sdt_csr& g, const int32_t* dst_nodes, int32_t n_dst_cap, const int32_t* n_dst_d,
+                     int32_t fanout, uint64_t seed, uint32_t step, uint32_t layer, const sdt_block& out,
+                     const SampleWs& ws, bool map_ready, hipStream_t st) {
+    if (!map_ready) {
+        int32_t rc = sample_init_map(ws, g.n_nodes, dst_nodes, n_dst_cap, n_dst_d, st);
+        if (rc != SDT_OK) return rc;
+    }
+    const int nwords = (int)((g.n_nodes + 31) / 32);
+    const int pm = ceil_div(n_dst_cap > 0 ? n_dst_cap : 1, TILE), pb = ceil_div(nwords, TILE);
+    const bool want_t = out.t_indptr != nullptr;
+    int32_t* hist = want_t ? out.t_indptr : nullptr;  // counted in place, then scanned in place
+
+    if (n_dst_cap > 0 && fanout > 0) {
+        hipLaunchKernelGGL(k_sample_rows, dim3(grid_for(n_dst_cap, TB / WAVE, 8192)), dim3(TB), 0, st, g.indptr,
+                           g.indices, dst_nodes, n_dst_cap, n_dst_d, fanout, (uint32_t)seed,
+                           (uint32_t)(seed >> 32), step, layer, ws.map, ws.bitmap, ws.e_pad, ws.m);
+        SDT_CHECK_LAUNCH("sample rows");
+    } else if (n_dst_cap > 0) {
+        hipLaunchKernelGGL(k_fill_i32, dim3(grid_for(n_dst_cap, TB, 1024)), dim3(TB), 0, st, ws.m,
+                           (int64_t)n_dst_cap, 0);
+        SDT_CHECK_LAUNCH("zero m");
+    }
+    hipLaunchKernelGGL(k_front_partials, dim3(pm + pb), dim3(TB), 0, st, ws.m, n_dst_cap, n_dst_d, ws.bitmap, nwords,
+                       pm, ws.part);
+    SDT_CHECK_LAUNCH("frontier partials");
+    hipLaunchKernelGGL(k_front_spine, dim3(1), dim3(TB), 0, st, ws.part, pm, pb, n_dst_cap, n_dst_d, out.counts,
+                       out.indptr);
+    SDT_CHECK_LAUNCH("frontier spine");
+    hipLaunchKernelGGL(k_front_apply, dim3(pm + pb), dim3(TB), 0, st, ws.m, n_dst_cap, n_dst_d, ws.bitmap, nwords, pm,
+                       ws.part, out.counts, out.indptr, out.src_nodes, dst_nodes, ws.map, hist);
+    SDT_CHECK_LAUNCH("frontier apply");
+    if (n_dst_cap > 0 && fanout > 0) {
+        hipLaunchKernelGGL(k_relabel, dim3(grid_for((int64_t)n_dst_cap * fanout, TB, 8192)), dim3(TB), 0, st,
+                           ws.e_pad, ws.m, out.indptr, n_dst_cap, n_dst_d, fanout, ws.map, out.cols, hist);
+        SDT_CHECK_LAUNCH("relabel");
+    }
+    if (want_t) {
+        const int pt = ceil_div((int64_t)out.cap_src + 1, TILE);
+        hipLaunchKernelGGL(k_scan_partials, dim3(pt), dim3(TB), 0, st, hist, out.counts + 1, 1, ws.part);
+        SDT_CHECK_LAUNCH("transpose partials");
+        hipLaunchKernelGGL(k_scan_spine, dim3(1), dim3(TB), 0, st, ws.part, pt, ws.longlist);
+        SDT_CHECK_LAUNCH("transpose spine");
+        hipLaunchKernelGGL(k_scan_apply, dim3(pt), dim3(TB), 0, st, hist, out.counts + 1, 1, ws.part, out.t_indptr,
+                           ws.cursor);
+        SDT_CHECK_LAUNCH("transpose apply");
+        if (n_dst_cap > 0 && fanout > 0) {
+            hipLaunchKernelGGL(k_transpose_fill, dim3(grid_for((int64_t)n_dst_cap * fanout, TB, 8192)), dim3(TB), 0,
+                               st, out.indptr, out.cols, n_dst_cap, n_dst_d, fanout, out.t_indptr, ws.cursor,
+                               out.t_rows);
+            SDT_CHECK_LAUNCH("transpose fill");
+            hipLaunchKernelGGL(k_sort_short, dim3(grid_for(out.cap_src, TB, 4096)), dim3(TB), 0, st, out.t_indptr,
+                               out.counts, out.t_rows, ws.longlist, ws.longlist + 1);
+            SDT_CHECK_LAUNCH("sort short");
+            hipLaunchKernelGGL(k_sort_long, dim3(64), dim3(TB), 0, st, out.t_indptr, out.t_rows, ws.longlist,
+                               ws.longlist + 1, ws.e_pad);
+            SDT_CHECK_LAUNCH("sort long");
+        }
+    }
+    return SDT_OK;
+}
+
+}  // namespace sdt
+
+extern "C" size_t sdt_sample_workspace_bytes(int64_t n_nodes, int32_t cap_dst, int32_t fanout) {
+    if (n_nodes < 0 || cap_dst < 0 || fanout < 0) return 0;
+    sdt::Arena a(nullptr);
+    return sdt::sample_ws_carve(a, n_nodes, cap_dst, fanout, nullptr);
+}
+
+extern "C" int32_t sdt_sample_csr(const sdt_csr* graph, const int32_t* dst_nodes, int32_t n_dst_cap,
+                                  const int32_t* n_dst_d, int32_t fanout, uint64_t seed, uint32_t step,
+                                  uint32_t layer, const sdt_block* out, void* ws, size_t ws_bytes, void* stream) {
+    using namespace sdt;
+    SDT_REQUIRE(graph && out, SDT_ERR_INVALID_ARG, "sdt_sample_csr: null graph or block");
+    SDT_REQUIRE(graph->n_nodes >= 0 && graph->n_nodes <= 0x7FFFFFFF, SDT_ERR_INVALID_ARG,
+                "sdt_sample_csr: n_nodes %lld out of range", (long long)graph->n_nodes);
+    SDT_REQUIRE(graph->indptr && (graph->indices || graph->n_nodes == 0), SDT_ERR_INVALID_ARG,
+                "sdt_sample_csr: null CSR arrays");
+    SDT_REQUIRE(n_dst_cap >= 0 && (dst_nodes || n_dst_cap == 0), SDT_ERR_INVALID_ARG,
+                "sdt_sample_csr: bad destination list");
+    SDT_REQUIRE(fanout >= 0 && fanout <= SDT_MAX_FANOUT, SDT_ERR_INVALID_ARG,
+                "sdt_sample_csr: fanout %d outside [0, %d]", fanout, SDT_MAX_FANOUT);
+    SDT_REQUIRE(layer < 65536u, SDT_ERR_INVALID_ARG, "sdt_sample_csr: layer %u too large", layer);
+    const int64_t need_nnz = (int64_t)n_dst_cap * fanout;
+    SDT_REQUIRE(need_nnz <= 0x7FFFFFFF, SDT_ERR_INVALID_ARG, "sdt_sample_csr: n_dst_cap*fanout overflows int32");
+    int64_t need_src = (int64_t)n_dst_cap + need_nnz;
+    if (need_src > graph->n_nodes) need_src = graph->n_nodes;
+    if (need_src < n_dst_cap) need_src = n_dst_cap;
+    SDT_REQUIRE(out->cap_dst >= n_dst_cap && out->cap_nnz >= need_nnz && out->cap_src >= need_src,
+                SDT_ERR_INVALID_ARG, "sdt_sample_csr: block capacities (%d,%d,%d) below the bounds (%d,%lld,%lld)",
+                out->cap_dst, out->cap_src, out->cap_nnz, n_dst_cap, (long long)need_src, (long long)need_nnz);
+    SDT_REQUIRE(out->counts && out->indptr && out->src_nodes && (out->cols || need_nnz == 0), SDT_ERR_INVALID_ARG,
+                "sdt_sample_csr: null block arrays");
+    SDT_REQUIRE((out->t_indptr == nullptr) == (out->t_rows == nullptr), SDT_ERR_INVALID_ARG,
+                "sdt_sample_csr: pass both transposed arrays or neither");
+    const size_t need = sdt_sample_workspace_bytes(graph->n_nodes, n_dst_cap, fanout);
+    SDT_REQUIRE(ws && ws_bytes >= need && aligned16(ws), SDT_ERR_WORKSPACE,
+                "sdt_sample_csr: workspace of %zu bytes needed, %zu given", need, ws_bytes);
+    Arena a(ws);
+    SampleWs sw;
+    sample_ws_carve(a, graph->n_nodes, n_dst_cap, fanout, &sw);
+    // The transposed scan sizes its grid from the capacity the workspace was carved for.
+    sdt_block blk = *out;
+    blk.cap_src = (int32_t)need_src;
+    return sample_layer(*graph, dst_nodes, n_dst_cap, n_dst_d, fanout, seed, step, layer, blk, sw, false,
+                        static_cast<hipStream_t>(stream));
+}

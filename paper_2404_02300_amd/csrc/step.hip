@@ -1,0 +1,196 @@
+// sdt_train_step: one mini-batch of GraphSAGE-mean training on the worker's
+// partition, enqueued on one stream with no host synchronisation.  All
+// data-dependent sizes (frontier sizes, edge counts) stay in device memory;
+// every kernel is launched for the upper bound and reads the true count.
+#include "common.h"
+
+namespace sdt {
+namespace {
+
+struct Caps {
+    int32_t dst[SDT_MAX_LAYERS], src[SDT_MAX_LAYERS], nnz[SDT_MAX_LAYERS];
+};
+
+bool compute_caps(int64_t n_nodes, int32_t batch, const int32_t* fanouts, int L, Caps* c) {
+    int64_t dst = batch;
+    for (int l = L - 1; l >= 0; --l) {
+        const int64_t nnz = dst * fanouts[l];
+        int64_t src = dst + nnz;
+        if (src > n_nodes) src = n_nodes;
+        if (src < dst) src = dst;
+        if (nnz > 0x7FFFFFFF || src > 0x7FFFFFFF) return false;
+        c->dst[l] = (int32_t)dst;
+        c->nnz[l] = (int32_t)nnz;
+        c->src[l] = (int32_t)src;
+        dst = src;
+    }
+    return true;
+}
+
+int32_t check_model(const sdt_model* m, const int32_t* fanouts, const char* who) {
+    SDT_REQUIRE(m && fanouts, SDT_ERR_INVALID_ARG, "%s: null model or fanouts", who);
+    SDT_REQUIRE(m->n_layers >= 1 && m->n_layers <= SDT_MAX_LAYERS, SDT_ERR_INVALID_ARG, "%s: n_layers %d outside [1,%d]",
+                who, m->n_layers, SDT_MAX_LAYERS);
+    for (int l = 0; l <= m->n_layers; ++l)
+        SDT_REQUIRE(m->dims[l] > 0, SDT_ERR_INVALID_ARG, "%s: dims[%d] = %d", who, l, m->dims[l]);
+    for (int l = 0; l < m->n_layers; ++l)
+        SDT_REQUIRE(fanouts[l] >= 0 && fanouts[l] <= SDT_MAX_FANOUT, SDT_ERR_INVALID_ARG,
+                    "%s: fanouts[%d] = %d outside [0,%d]", who, l, fanouts[l], SDT_MAX_FANOUT);
+    return SDT_OK;
+}
+
+}  // namespace
+}  // namespace sdt
+
+using namespace sdt;
+
+extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const int32_t* fanouts, const sdt_model* model,
+                                         int32_t dtype, sdt_step_layout* lay) {
+    SDT_REQUIRE(lay, SDT_ERR_INVALID_ARG, "sdt_train_step_layout: null layout");
+    int32_t rc = check_model(model, fanouts, "sdt_train_step_layout");
+    if (rc != SDT_OK) return rc;
+    SDT_REQUIRE(dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_train_step_layout: unknown dtype %d", dtype);
+    SDT_REQUIRE(n_nodes >= 0 && n_nodes <= 0x7FFFFFFF && batch >= 0 && batch <= n_nodes, SDT_ERR_INVALID_ARG,
+                "sdt_train_step_layout: n_nodes=%lld batch=%d", (long long)n_nodes, batch);
+    const int L = model->n_layers;
+    Caps c;
+    SDT_REQUIRE(compute_caps(n_nodes, batch, fanouts, L, &c), SDT_ERR_INVALID_ARG,
+                "sdt_train_step_layout: frontier bounds overflow int32");
+    const size_t es = dtype_size(dtype);
+    const int32_t* d = model->dims;
+    *lay = sdt_step_layout{};
+    lay->n_layers = L;
+    Arena a(nullptr);
+    size_t scratch = 0;
+    for (int l = 0; l < L; ++l) {
+        lay->cap_dst[l] = c.dst[l];
+        lay->cap_src[l] = c.src[l];
+        lay->cap_nnz[l] = c.nnz[l];
+        lay->counts[l] = a.take_off(4 * sizeof(int32_t));
+        lay->indptr[l] = a.take_off(((size_t)c.dst[l] + 1) * 4);
+        lay->cols[l] = a.take_off((size_t)(c.nnz[l] > 0 ? c.nnz[l] : 1) * 4);
+        lay->src_nodes[l] = a.take_off((size_t)(c.src[l] > 0 ? c.src[l] : 1) * 4);
+        if (l >= 1) {
+            lay->t_indptr[l] = a.take_off(((size_t)c.src[l] + 1) * 4);
+            lay->t_rows[l] = a.take_off((size_t)(c.nnz[l] > 0 ? c.nnz[l] : 1) * 4);
+            lay->dH[l] = a.take_off((size_t)c.src[l] * d[l] * es);
+            lay->dSelf[l] = a.take_off((size_t)c.dst[l] * d[l] * es);
+            lay->dAgg[l] = a.take_off((size_t)c.dst[l] * d[l] * es);
+        }
+        lay->A[l] = a.take_off((size_t)c.dst[l] * d[l] * es);
+        lay->H[l + 1] = a.take_off((size_t)c.dst[l] * d[l + 1] * (l == L - 1 ? 4 : es));
+        lay->dW[l] = a.take_off((size_t)2 * d[l] * d[l + 1] * 4);
+        lay->db[l] = a.take_off((size_t)d[l + 1] * 4);
+        Arena s(nullptr);
+        size_t sb = sample_ws_carve(s, n_nodes, c.dst[l], fanouts[l], nullptr);
+        size_t lb = sdt_linear_bwd_workspace_bytes(c.dst[l], d[l], d[l + 1]);
+        if (sb > scratch) scratch = sb;
+        if (lb > scratch) scratch = lb;
+    }
+    lay->H[0] = a.take_off((size_t)c.src[0] * d[0] * es);
+    lay->dZ = a.take_off((size_t)batch * d[L] * 4);
+    lay->row_loss = a.take_off((size_t)(batch > 0 ? batch : 1) * 4);
+    lay->scratch = a.take_off(scratch);
+    lay->total_bytes = a.off;
+    return SDT_OK;
+}
+
+extern "C" int32_t sdt_train_step(const sdt_csr* graph, const void* X, int64_t ldx, int32_t dtype, const int32_t* labels,
+                                  const int32_t* seeds, int32_t batch, const int32_t* fanouts, const sdt_model* model,
+                                  uint64_t seed, uint32_t step, float lr, float* loss_d, void* ws, size_t ws_bytes,
+                                  void* stream) {
+    SDT_REQUIRE(graph && graph->indptr, SDT_ERR_INVALID_ARG, "sdt_train_step: null graph");
+    sdt_step_layout lay;
+    int32_t rc = sdt_train_step_layout(graph->n_nodes, batch, fanouts, model, dtype, &lay);
+    if (rc != SDT_OK) return rc;
+    const int L = model->n_layers;
+    const int32_t* d = model->dims;
+    SDT_REQUIRE(batch > 0, SDT_ERR_INVALID_ARG, "sdt_train_step: empty batch");
+    SDT_REQUIRE(X && labels && seeds && loss_d && ldx >= d[0], SDT_ERR_INVALID_ARG,
+                "sdt_train_step: null input or ldx < dims[0]");
+    SDT_REQUIRE(graph->indices || graph->n_nodes == 0, SDT_ERR_INVALID_ARG, "sdt_train_step: null indices");
+    for (int l = 0; l < L; ++l)
+        SDT_REQUIRE(model->W[l] && model->b[l], SDT_ERR_INVALID_ARG, "sdt_train_step: null weights of layer %d", l);
+    SDT_REQUIRE(ws && ws_bytes >= lay.total_bytes && aligned16(ws), SDT_ERR_WORKSPACE,
+                "sdt_train_step: workspace of %llu bytes needed, %zu given", (unsigned long long)lay.total_bytes,
+                ws_bytes);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(ws);
+    auto at = [&](uint64_t off) { return static_cast<void*>(base + off); };
+
+    sdt_block blk[SDT_MAX_LAYERS];
+    for (int l = 0; l < L; ++l) {
+        blk[l].cap_dst = lay.cap_dst[l];
+        blk[l].cap_src = lay.cap_src[l];
+        blk[l].cap_nnz = lay.cap_nnz[l];
+        blk[l].reserved = 0;
+        blk[l].counts = static_cast<int32_t*>(at(lay.counts[l]));
+        blk[l].indptr = static_cast<int32_t*>(at(lay.indptr[l]));
+        blk[l].cols = static_cast<int32_t*>(at(lay.cols[l]));
+        blk[l].src_nodes = static_cast<int32_t*>(at(lay.src_nodes[l]));
+        blk[l].t_indptr = l >= 1 ? static_cast<int32_t*>(at(lay.t_indptr[l])) : nullptr;
+        blk[l].t_rows = l >= 1 ? static_cast<int32_t*>(at(lay.t_rows[l])) : nullptr;
+    }
+
+    // ---- sample from the seeds outwards; the node -> local-id map carries over
+    const int32_t* dst = seeds;
+    const int32_t* n_d = nullptr;
+    for (int l = L - 1; l >= 0; --l) {
+        Arena a(at(lay.scratch));
+        SampleWs sw;
+        sample_ws_carve(a, graph->n_nodes, lay.cap_dst[l], fanouts[l], &sw);
+        rc = sample_layer(*graph, dst, lay.cap_dst[l], n_d, fanouts[l], seed, step, (uint32_t)l, blk[l], sw, l != L - 1,
+                          st);
+        if (rc != SDT_OK) return rc;
+        dst = blk[l].src_nodes;
+        n_d = blk[l].counts + 1;
+    }
+
+    // ---- gather the input features of the outermost frontier
+    rc = sdt_gather_features(X, ldx, d[0], dtype, blk[0].src_nodes, lay.cap_src[0], blk[0].counts + 1, at(lay.H[0]),
+                             d[0], st);
+    if (rc != SDT_OK) return rc;
+
+    // ---- forward
+    for (int l = 0; l < L; ++l) {
+        rc = sdt_sage_aggregate_fwd(&blk[l], at(lay.H[l]), d[l], d[l], dtype, at(lay.A[l]), d[l], st);
+        if (rc != SDT_OK) return rc;
+        const bool last = l == L - 1;
+        rc = sdt_sage_linear_fwd(at(lay.H[l]), d[l], at(lay.A[l]), d[l], lay.cap_dst[l], blk[l].counts, d[l], d[l + 1],
+                                 model->W[l], model->b[l], last ? 0 : 1, dtype, at(lay.H[l + 1]), d[l + 1],
+                                 last ? SDT_F32 : dtype, st);
+        if (rc != SDT_OK) return rc;
+    }
+
+    // ---- loss and its gradient
+    rc = softmax_xent(static_cast<const float*>(at(lay.H[L])), d[L], batch, d[L], labels, seeds,
+                      static_cast<float*>(at(lay.dZ)), static_cast<float*>(at(lay.row_loss)), loss_d, st);
+    if (rc != SDT_OK) return rc;
+
+    // ---- backward
+    float* dW[SDT_MAX_LAYERS];
+    float* db[SDT_MAX_LAYERS];
+    const void* dY = at(lay.dZ);
+    int32_t dy_dtype = SDT_F32;
+    for (int l = L - 1; l >= 0; --l) {
+        dW[l] = model->dW[l] ? model->dW[l] : static_cast<float*>(at(lay.dW[l]));
+        db[l] = model->db[l] ? model->db[l] : static_cast<float*>(at(lay.db[l]));
+        const bool inner = l > 0;
+        rc = sdt_sage_linear_bwd(dY, d[l + 1], dy_dtype, nullptr, 0, 0, at(lay.H[l]), d[l], at(lay.A[l]), d[l],
+                                 lay.cap_dst[l], blk[l].counts, d[l], d[l + 1], model->W[l], dtype, dW[l], db[l],
+                                 inner ? at(lay.dSelf[l]) : nullptr, inner ? at(lay.dAgg[l]) : nullptr, d[l],
+                                 at(lay.scratch), ws_bytes - lay.scratch, st);
+        if (rc != SDT_OK) return rc;
+        if (inner) {
+            // gradient w.r.t. H[l], masked by the ReLU that produced H[l]
+            rc = sdt_sage_aggregate_bwd(&blk[l], at(lay.dAgg[l]), d[l], at(lay.dSelf[l]), d[l], at(lay.H[l]), d[l], dtype,
+                                        at(lay.dH[l]), d[l], st);
+            if (rc != SDT_OK) return rc;
+            dY = at(lay.dH[l]);
+            dy_dtype = dtype;
+        }
+    }
+
+    // ---- plain SGD on the fp32 weights
+    return sgd_update(*model, dW, db, lr, st);
+}

@@ -1,0 +1,86 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol the header declares, and its pure-host queries and argument
+validation behave."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2404_02300_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    hdr = open(os.path.join(ROOT, "include", "sdt.h")).read()
+    return sorted(set(re.findall(r"\b(sdt_[a-z_0-9]+)\s*\(", hdr)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    names = _declared()
+    assert len(names) >= 13
+    for n in names:
+        assert hasattr(L, n), n
+        assert n in B.EXPORTS, f"binding lacks {n}"
+    assert re.fullmatch(r"\d+\.\d+\.\d+", B.sdt_version())
+
+
+def test_binding_mirrors_header_names():
+    for n in _declared():
+        assert hasattr(B, n), n
+
+
+def test_workspace_queries_are_host_arithmetic():
+    a = B.sdt_sample_workspace_bytes(1 << 21, 1024, 10)
+    b = B.sdt_sample_workspace_bytes(1 << 21, 11264, 15)
+    assert 0 < a < b
+    assert a >= (1 << 21) * 4 + (1 << 21) // 8            # id map + bitmap
+    assert B.sdt_sample_workspace_bytes(-1, 4, 4) == 0
+    assert B.sdt_linear_bwd_workspace_bytes(11264, 100, 256) >= 2 * 100 * 256 * 4
+
+
+def _model(dims):
+    m = B.sdt_model()
+    m.n_layers = len(dims) - 1
+    for i, d in enumerate(dims):
+        m.dims[i] = d
+    return m
+
+
+def test_step_layout_bounds_match_the_frontier_recurrence():
+    lay = B.sdt_train_step_layout(1 << 21, 1024, [15, 10], _model([100, 256, 47]), B.SDT_F32)
+    assert list(lay.cap_dst[:2]) == [11264, 1024]
+    assert list(lay.cap_nnz[:2]) == [168960, 10240]
+    assert list(lay.cap_src[:2]) == [180224, 11264]
+    lay4 = B.sdt_train_step_layout(1 << 24, 1024, [15, 10, 5], _model([128, 256, 256, 172]), B.SDT_BF16)
+    assert list(lay4.cap_dst[:3]) == [67584, 6144, 1024] and lay4.cap_src[0] == 1081344
+    # the frontier can never exceed the partition
+    small = B.sdt_train_step_layout(1 << 14, 256, [10, 5], _model([64, 64, 8]), B.SDT_F32)
+    assert small.cap_src[0] == 1 << 14 and small.cap_dst[0] == 1536
+    offs = [small.counts[0], small.indptr[0], small.cols[0], small.src_nodes[0], small.H[0], small.H[1], small.H[2],
+            small.A[0], small.A[1], small.dZ, small.scratch]
+    assert len(set(offs)) == len(offs) and max(offs) < small.total_bytes
+    assert all(o % 256 == 0 for o in offs)
+
+
+def test_invalid_arguments_are_reported_not_crashed():
+    f = (ctypes.c_int32 * 2)(10, 5)
+    lay = B.sdt_step_layout()
+    L = B.lib()
+    m = _model([64, 64, 8])
+    assert L.sdt_train_step_layout(1 << 14, 256, f, ctypes.byref(m), 7, ctypes.byref(lay)) == B.SDT_ERR_INVALID_ARG
+    assert "dtype" in B.sdt_last_error()
+    bad = (ctypes.c_int32 * 2)(10, 65)
+    assert L.sdt_train_step_layout(1 << 14, 256, bad, ctypes.byref(m), 0, ctypes.byref(lay)) == B.SDT_ERR_INVALID_ARG
+    assert L.sdt_train_step_layout(100, 256, f, ctypes.byref(m), 0, ctypes.byref(lay)) == B.SDT_ERR_INVALID_ARG
+    m.n_layers = 9
+    assert L.sdt_train_step_layout(1 << 14, 256, f, ctypes.byref(m), 0, ctypes.byref(lay)) == B.SDT_ERR_INVALID_ARG
+    with pytest.raises(B.SdtError):
+        B.sdt_train_step_layout(1 << 14, 256, [10, 5], m, 0)
+    # null graph / null block are rejected before any launch
+    assert L.sdt_sample_csr(None, None, 0, None, 4, 0, 0, 0, None, None, 0, None) == B.SDT_ERR_INVALID_ARG
+    assert L.sdt_sage_aggregate_fwd(None, None, 0, 4, 0, None, 0, None) == B.SDT_ERR_INVALID_ARG
+    assert L.sdt_gather_features(None, 4, 8, 0, None, 3, None, None, 8, None) == B.SDT_ERR_INVALID_ARG
+    assert L.sdt_sage_linear_fwd(None, 4, None, 4, 3, None, 4, 4, None, None, 0, 0, None, 4, 0, None) == B.SDT_ERR_INVALID_ARG

@@ -1,0 +1,326 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Index outputs must be bit-exact, floats within 1e-5
+(fp32) / 2e-2 (bf16) max-norm relative error."""
+import numpy as np
+import pytest
+import torch
+
+import sdt_gen as gen
+from oracle import sdt_oracle as orc
+from paper_2404_02300_amd import binding as B
+from parity_util import (TOL, StepRunner, assert_close, bf16_from_bits, check_step_against_oracle, dev, f64,
+                         upload_block)
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _random_csr(rng, n, avg_deg, dups=False, hub=None):
+    rows = []
+    for v in range(n):
+        d = int(rng.integers(0, 2 * avg_deg + 1))
+        if hub is not None and v in hub:
+            d = hub[v]
+        r = np.sort(rng.integers(0, n, size=d)) if dups else np.sort(rng.choice(n, size=min(d, n), replace=False))
+        rows.append(r.astype(np.int32))
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    indptr[1:] = np.cumsum([len(r) for r in rows])
+    return indptr, np.concatenate(rows).astype(np.int32)
+
+
+def _gpu_sample(indptr, indices, dst, fanout, seed, step, layer, n_dst_d=None, cap=None):
+    g = B.Csr(dev(indptr), dev(indices))
+    cap = len(dst) if cap is None else cap
+    blk = B.Block(cap, fanout, g.n_nodes, "cuda")
+    ws = torch.empty(max(B.sdt_sample_workspace_bytes(g.n_nodes, cap, fanout), 16), dtype=torch.uint8, device="cuda")
+    d = dev(np.asarray(dst, dtype=np.int32)) if cap else torch.zeros(1, dtype=torch.int32, device="cuda")
+    B.sdt_sample_csr(g, d, fanout, seed, step, layer, blk, ws, n_dst_d=n_dst_d, n_dst_cap=cap)
+    torch.cuda.synchronize()
+    return blk
+
+
+def _assert_block_equal(blk: B.Block, ref):
+    n_dst, n_src, nnz, _ = blk.counts.cpu().numpy()
+    assert (n_dst, n_src, nnz) == (ref.n_dst, ref.n_src, ref.nnz)
+    assert np.array_equal(blk.indptr[:n_dst + 1].cpu().numpy(), ref.indptr)
+    assert np.array_equal(blk.src_nodes[:n_src].cpu().numpy(), ref.src_nodes)
+    assert np.array_equal(blk.cols[:nnz].cpu().numpy(), ref.cols)
+    assert np.array_equal(blk.t_indptr[:n_src + 1].cpu().numpy(), ref.t_indptr)
+    assert np.array_equal(blk.t_rows[:nnz].cpu().numpy(), ref.t_rows)
+
+
+# ----------------------------------------------------------------- sampling
+@pytest.mark.parametrize("fanout", [0, 1, 5, 10, 25, 64])
+@pytest.mark.parametrize("dups", [False, True])
+def test_sample_block_bit_exact(fanout, dups):
+    _say(f"sample fanout={fanout} dups={dups}")
+    rng = np.random.default_rng(100 + fanout)
+    indptr, indices = _random_csr(rng, 3000, 20, dups=dups, hub={7: 2500, 11: 64, 12: 65, 13: 63})
+    dst = np.concatenate([[7, 11, 12, 13], rng.choice(np.arange(20, 3000), size=700, replace=False)]).astype(np.int32)
+    for seed, step, layer in [(1, 0, 0), ((9 << 32) | 5, 77, 2)]:
+        ref = orc.sample_block(indptr, indices, dst, fanout, seed, step, layer)
+        _assert_block_equal(_gpu_sample(indptr, indices, dst, fanout, seed, step, layer), ref)
+
+
+def test_sample_device_count_and_empty():
+    _say("sample with device-side row count / empty input")
+    rng = np.random.default_rng(3)
+    indptr, indices = _random_csr(rng, 500, 10)
+    dst = rng.choice(500, size=200, replace=False).astype(np.int32)
+    n_d = torch.tensor([150], dtype=torch.int32, device="cuda")
+    blk = _gpu_sample(indptr, indices, dst, 6, 4, 1, 0, n_dst_d=n_d)
+    _assert_block_equal(blk, orc.sample_block(indptr, indices, dst[:150], 6, 4, 1, 0))
+    zero = torch.tensor([0], dtype=torch.int32, device="cuda")
+    blk = _gpu_sample(indptr, indices, dst, 6, 4, 1, 0, n_dst_d=zero)
+    assert blk.counts.cpu().tolist()[:3] == [0, 0, 0]
+    blk = _gpu_sample(indptr, indices, np.zeros(0, np.int32), 6, 4, 1, 0)
+    assert blk.counts.cpu().tolist()[:3] == [0, 0, 0]
+
+
+def test_sample_star_graph_long_transposed_segment():
+    # every leaf samples the centre: one transposed segment as long as the batch
+    _say("sample star graph (long transposed segment)")
+    n = 20000
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    indptr[1] = n - 1
+    indptr[2:] = n - 1 + np.arange(1, n)
+    indices = np.concatenate([np.arange(1, n), np.zeros(n - 1)]).astype(np.int32)
+    dst = np.random.default_rng(0).permutation(np.arange(1, n))[:12000].astype(np.int32)
+    ref = orc.sample_block(indptr, indices, dst, 3, 5, 0, 1)
+    assert ref.t_indptr[ref.n_dst + 1] - ref.t_indptr[ref.n_dst] == 12000
+    _assert_block_equal(_gpu_sample(indptr, indices, dst, 3, 5, 0, 1), ref)
+    dst2 = np.concatenate([[0], dst[:50]]).astype(np.int32)       # the centre itself: degree >> fanout
+    _assert_block_equal(_gpu_sample(indptr, indices, dst2, 25, 6, 1, 0), orc.sample_block(indptr, indices, dst2, 25, 6, 1, 0))
+
+
+def test_sample_rejects_bad_arguments():
+    rng = np.random.default_rng(3)
+    indptr, indices = _random_csr(rng, 100, 4)
+    g = B.Csr(dev(indptr), dev(indices))
+    blk = B.Block(10, 4, 100, "cuda")
+    ws = torch.empty(B.sdt_sample_workspace_bytes(100, 10, 4), dtype=torch.uint8, device="cuda")
+    d = torch.arange(10, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.SdtError) as e:
+        B.sdt_sample_csr(g, d, 65, 0, 0, 0, blk, ws)
+    assert e.value.code == B.SDT_ERR_INVALID_ARG
+    with pytest.raises(B.SdtError) as e:
+        B.sdt_sample_csr(g, d, 4, 0, 0, 0, blk, ws[:64])
+    assert e.value.code == B.SDT_ERR_WORKSPACE
+    with pytest.raises(B.SdtError) as e:
+        B.sdt_sample_csr(g, d, 8, 0, 0, 0, blk, ws)               # block too small for fanout 8
+    assert e.value.code == B.SDT_ERR_INVALID_ARG
+
+
+# ----------------------------------------------------------------- gather
+@pytest.mark.parametrize("F,bf16", [(100, False), (602, False), (7, False), (64, False), (128, True), (5, True), (602, True)])
+def test_gather_bit_copy(F, bf16):
+    _say(f"gather F={F} bf16={bf16}")
+    rng = np.random.default_rng(F)
+    n, m = 5000, 12345
+    idx = rng.integers(0, n, size=m).astype(np.int32)
+    if bf16:
+        bits = rng.integers(0, 65536, size=(n, F)).astype(np.uint16)
+        X = bf16_from_bits(bits).cuda()
+        out = torch.zeros(m, F, dtype=torch.bfloat16, device="cuda")
+        B.sdt_gather_features(X, dev(idx), out)
+        assert np.array_equal(out.view(torch.int16).cpu().numpy().view(np.uint16), orc.gather_rows(bits, idx))
+    else:
+        Xh = rng.standard_normal((n, F)).astype(np.float32)
+        out = torch.zeros(m, F, dtype=torch.float32, device="cuda")
+        B.sdt_gather_features(dev(Xh), dev(idx), out)
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), orc.gather_rows(Xh, idx).view(np.uint32))
+    # device-side count: rows past it stay untouched
+    out.zero_()
+    n_d = torch.tensor([100], dtype=torch.int32, device="cuda")
+    B.sdt_gather_features(X if bf16 else dev(Xh), dev(idx), out, n_d=n_d)
+    assert not out[100:].any() and out[:100].any()
+
+
+# ----------------------------------------------------------------- aggregation
+def _blocks_for_agg(seed, n=4000, n_dst=900, fanout=10):
+    rng = np.random.default_rng(seed)
+    indptr, indices = _random_csr(rng, n, 12, dups=True, hub={3: 900})
+    dst = np.concatenate([[3], rng.choice(np.arange(4, n), size=n_dst - 1, replace=False)]).astype(np.int32)
+    return rng, orc.sample_block(indptr, indices, dst, fanout, seed, 0, 1)
+
+
+@pytest.mark.parametrize("F,bf16", [(100, False), (602, False), (64, False), (33, False), (128, True), (256, True), (6, True)])
+def test_aggregate_fwd_bwd(F, bf16):
+    _say(f"aggregate F={F} bf16={bf16}")
+    rng, blk = _blocks_for_agg(F)
+    dt = torch.bfloat16 if bf16 else torch.float32
+    tol = TOL[dt]
+    gb = upload_block(blk)
+    H = torch.from_numpy(rng.standard_normal((blk.n_src, F)).astype(np.float32)).to(dt).cuda()
+    A = torch.empty(blk.n_dst, F, dtype=dt, device="cuda")
+    B.sdt_sage_aggregate_fwd(gb, H, A)
+    refA = orc.aggregate_fwd(blk.indptr, blk.cols, f64(H))
+    assert_close(f64(A), orc.round_bf16(refA) if bf16 else refA, tol, "A")
+    empty = np.diff(blk.indptr) == 0
+    assert empty.any() and not A[torch.from_numpy(empty).cuda()].any()             # rows without neighbours are zero
+    dAgg = torch.from_numpy(rng.standard_normal((blk.n_dst, F)).astype(np.float32)).to(dt).cuda()
+    dSelf = torch.from_numpy(rng.standard_normal((blk.n_dst, F)).astype(np.float32)).to(dt).cuda()
+    dH = torch.empty(blk.n_src, F, dtype=dt, device="cuda")
+    B.sdt_sage_aggregate_bwd(gb, dAgg, dSelf, dH)
+    ref = orc.aggregate_bwd(blk.indptr, blk.cols, blk.n_src, f64(dAgg), f64(dSelf))
+    assert_close(f64(dH), ref, tol, "dH")
+    B.sdt_sage_aggregate_bwd(gb, dAgg, None, dH)
+    assert_close(f64(dH), orc.aggregate_bwd(blk.indptr, blk.cols, blk.n_src, f64(dAgg), None), tol, "dH without self")
+    Y = torch.from_numpy(rng.standard_normal((blk.n_src, F)).astype(np.float32)).to(dt).cuda()
+    B.sdt_sage_aggregate_bwd(gb, dAgg, dSelf, dH, relu_of=Y)
+    assert_close(f64(dH), ref * (f64(Y) > 0), tol, "dH with ReLU mask")
+
+
+def test_aggregate_whole_csr():
+    _say("aggregate over a whole CSR (identity frontier)")
+    wl = gen.WORKLOADS["tiny"]
+    indptr, indices = gen.make_graph(wl)
+    X = gen.normal_features(wl.n_nodes, 256, seed=4)
+    A = torch.empty(wl.n_nodes, 256, dtype=torch.float32, device="cuda")
+    B.sdt_sage_aggregate_csr_fwd(B.Csr(dev(indptr), dev(indices)), dev(X), A)
+    assert_close(f64(A), orc.aggregate_fwd(indptr, indices, X.astype(np.float64)), 1e-5, "A")
+
+
+# ----------------------------------------------------------------- projection
+@pytest.mark.parametrize("n,fin,fout,bf16", [(1000, 100, 256, False), (333, 70, 41, False), (65, 602, 256, False),
+                                             (1, 8, 8, False), (2000, 64, 8, False), (700, 128, 256, True),
+                                             (129, 256, 172, True), (50, 6, 10, True)])
+def test_linear_fwd_bwd(n, fin, fout, bf16):
+    _say(f"linear n={n} in={fin} out={fout} bf16={bf16}")
+    rng = np.random.default_rng(n + fin)
+    dt = torch.bfloat16 if bf16 else torch.float32
+    tol = TOL[dt]
+    rnd = orc.round_bf16 if bf16 else (lambda t: t)
+    Hs = torch.from_numpy(rng.standard_normal((n + 5, fin)).astype(np.float32)).to(dt).cuda()
+    A = torch.from_numpy(rng.standard_normal((n, fin)).astype(np.float32)).to(dt).cuda()
+    W = (rng.standard_normal((2 * fin, fout)) / np.sqrt(2 * fin)).astype(np.float32)
+    b = rng.standard_normal(fout).astype(np.float32)
+    Wd, bd = dev(W), dev(b)
+    for relu in (True, False):
+        ydt = dt if relu else torch.float32                       # hidden layers store `dt`, logits fp32
+        Y = torch.empty(n, fout, dtype=ydt, device="cuda")
+        B.sdt_sage_linear_fwd(Hs, A, Wd, bd, relu, Y)
+        ref = orc.linear_fwd(f64(Hs), f64(A), rnd(W.astype(np.float64)), b, relu)
+        assert_close(f64(Y), ref, tol, f"Y relu={relu}")
+    # backward of a hidden layer (ReLU mask from Y) and of the last layer (fp32 dY, no mask)
+    ws = torch.empty(B.sdt_linear_bwd_workspace_bytes(n, fin, fout), dtype=torch.uint8, device="cuda")
+    Yh = torch.empty(n, fout, dtype=dt, device="cuda")
+    B.sdt_sage_linear_fwd(Hs, A, Wd, bd, True, Yh)
+    for relu in (True, False):
+        dY = torch.from_numpy(rng.standard_normal((n, fout)).astype(np.float32)).to(dt if relu else torch.float32).cuda()
+        dW = torch.empty(2 * fin, fout, dtype=torch.float32, device="cuda")
+        db = torch.empty(fout, dtype=torch.float32, device="cuda")
+        dS = torch.empty(n, fin, dtype=dt, device="cuda")
+        dA = torch.empty(n, fin, dtype=dt, device="cuda")
+        B.sdt_sage_linear_bwd(dY, Yh if relu else None, relu, Hs, A, Wd, dW, db, dS, dA, ws)
+        rdW, rdb, rdS, rdA = orc.linear_bwd(rnd(f64(dY)), f64(Yh), relu, f64(Hs)[:n], f64(A), rnd(W.astype(np.float64)))
+        assert_close(f64(dW), rdW, tol, "dW")
+        assert_close(f64(db), rdb, tol, "db")
+        assert_close(f64(dS), rdS, tol, "dSelf")
+        assert_close(f64(dA), rdA, tol, "dAgg")
+        dW2 = torch.empty_like(dW)
+        B.sdt_sage_linear_bwd(dY, Yh if relu else None, relu, Hs, A, Wd, dW2, db, None, None, ws)
+        assert torch.equal(dW, dW2)                               # deterministic, with or without input grads
+
+
+def test_linear_device_row_count():
+    _say("linear with device-side row count")
+    rng = np.random.default_rng(0)
+    n, fin, fout = 500, 32, 48
+    Hs, A = dev(rng.standard_normal((n, fin)).astype(np.float32)), dev(rng.standard_normal((n, fin)).astype(np.float32))
+    W, b = dev(rng.standard_normal((2 * fin, fout)).astype(np.float32)), dev(np.zeros(fout, np.float32))
+    Y = torch.zeros(n, fout, device="cuda")
+    n_d = torch.tensor([130], dtype=torch.int32, device="cuda")
+    B.sdt_sage_linear_fwd(Hs, A, W, b, False, Y, n_d=n_d)
+    ref = orc.linear_fwd(f64(Hs)[:130], f64(A)[:130], f64(W), f64(b), False)
+    assert_close(f64(Y[:130]), ref, 1e-5, "Y")
+    assert not Y[130:].any()
+
+
+# ----------------------------------------------------------------- whole step
+def _reconcile_relu(run, ref, tol_zero=1e-5):
+    """Where a hidden pre-activation is within rounding of zero the two sides may
+    take different ReLU decisions; both are valid.  Returns the masks the GPU
+    used when they differ from the oracle's, after checking that every
+    difference is such a borderline element."""
+    masks, changed = [], False
+    for l in range(run.L - 1):
+        h_ref = ref["H"][l + 1]
+        h_gpu = run.H(l + 1, h_ref.shape[0])
+        diff = (h_gpu > 0) != (h_ref > 0)
+        if diff.any():
+            scale = np.max(np.abs(h_ref))
+            assert np.max(np.maximum(np.abs(h_gpu[diff]), np.abs(h_ref[diff]))) <= tol_zero * scale
+            changed = True
+        masks.append(h_gpu > 0)
+    return masks if changed else None
+
+
+def _run_and_check(inst, wl, steps, lr=0.01, check_float_steps=(0,)):
+    run = StepRunner(inst.indptr, inst.indices, inst.X, inst.y, inst.W, inst.b, wl.fanouts, wl.batch, bf16=wl.bf16)
+    tol = TOL[run.dt]
+    for step in range(steps):
+        seeds = inst.batch(step)
+        W_before = [f64(w) for w in run.W]
+        b_before = [f64(v) for v in run.b]
+        loss = run.step(seeds, wl.seed, step, lr)
+        floats = step in check_float_steps
+        if floats:
+            # teacher-forced: the oracle starts from the weights the GPU had
+            ref = orc.train_step(inst.indptr, inst.indices, inst.X, inst.y, seeds, wl.fanouts, W_before, b_before,
+                                 wl.seed, step, lr, bf16=wl.bf16)
+            masks = _reconcile_relu(run, ref)
+            if masks is not None:
+                ref.update(orc.backward(ref["blocks"], ref["H"], ref["A"], ref["W"], ref["dZ"], wl.bf16, masks))
+                ref["W_new"] = [orc.sgd(ref["W"][l], ref["dW"][l], lr) for l in range(run.L)]
+            assert abs(loss - ref["loss"]) <= tol * max(1.0, abs(ref["loss"])), (loss, ref["loss"])
+            check_step_against_oracle(run, ref, tol)
+            for l in range(run.L):
+                assert_close(f64(run.W[l]), ref["W_new"][l], tol, f"updated W[{l}]")
+        else:
+            blocks = orc.sample_blocks(inst.indptr, inst.indices, seeds, wl.fanouts, wl.seed, step)
+            check_step_against_oracle(run, dict(blocks=blocks), tol, floats=False)
+        _say(f"  step {step}: loss {loss:.6f} ok")
+    return run
+
+
+def test_train_step_tiny_config():
+    _say("train step: tiny config")
+    wl = gen.WORKLOADS["tiny"]
+    inst = gen.make_instance(wl)
+    _run_and_check(inst, wl, steps=3, check_float_steps=(0, 1, 2))
+
+
+def test_train_step_lr_zero_keeps_weights_and_is_repeatable():
+    _say("train step: lr = 0, run-to-run determinism")
+    wl = gen.WORKLOADS["tiny"]
+    inst = gen.make_instance(wl)
+    run = StepRunner(inst.indptr, inst.indices, inst.X, inst.y, inst.W, inst.b, wl.fanouts, wl.batch)
+    seeds = inst.batch(0)
+    l0 = run.step(seeds, 0, 0, 0.0)
+    snap = run.ws.clone()
+    for l in range(2):
+        assert np.array_equal(run.W[l].cpu().numpy(), inst.W[l])
+    l1 = run.step(seeds, 0, 0, 0.0)
+    assert l0 == l1
+    lay = run.lay
+    for off, nbytes in [(lay.dW[0], 2 * 64 * 64 * 4), (lay.dW[1], 2 * 64 * 8 * 4), (lay.H[2], 256 * 8 * 4)]:
+        assert torch.equal(snap[off:off + nbytes], run.ws[off:off + nbytes])
+    assert 0.5 * np.log(8) < l0 < 2 * np.log(8)                    # random init: the order of ln C
+
+
+def test_train_step_three_layers_bf16_small():
+    _say("train step: 3 layers, bf16 storage, small graph")
+    wl = gen.Workload("small_bf16", "rmat", 13, 12, 40, 10, 48, 3, [6, 4, 3], 128, 7, 2, bf16=True)
+    inst = gen.make_instance(wl)
+    _run_and_check(inst, wl, steps=2, check_float_steps=(0, 1))
+
+
+def test_train_step_ragged_dims_fp32():
+    _say("train step: odd feature widths (scalar load paths)")
+    wl = gen.Workload("odd", "rmat", 12, 10, 37, 5, 19, 2, [4, 3], 100, 9, 1)
+    inst = gen.make_instance(wl)
+    _run_and_check(inst, wl, steps=1)

@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole mini-batch step (sdt_train_step) on one MI355X.
+
+A "step" is one pass of the hot path -- sample, gather, forward, loss, backward,
+SGD -- over one seeded synthetic mini-batch of the products-shaped workload
+(R-MAT 2^21 nodes, degree ~25, F=100, 47 classes, 2-layer GraphSAGE-mean with
+hidden 256, fan-out [15,10], 1024 seeds drawn from the owned quarter).  Graph,
+features, labels, weights and all seed batches are resident in HBM before the
+timed region starts.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="products", choices=["tiny", "products", "dense", "sparse_bf16"])
+    ap.add_argument("--lr", type=float, default=0.01)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-steps", type=int, default=2, help="oracle steps timed for cpu_baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU (the per-worker step has no collectives); --gpus must be 1")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import sdt_gen as gen
+    import paper_2404_02300_amd as sdt
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = gen.WORKLOADS[args.workload]
+    K, Wm = args.steps, args.warmup
+
+    t0 = time.time()
+    inst = gen.make_instance(wl)
+    nnz_graph = int(inst.indptr[-1])
+    log(f"[bench] generated {wl.name}: N={wl.n_nodes} nnz={nnz_graph} avg_deg={nnz_graph / wl.n_nodes:.2f} "
+        f"in {time.time() - t0:.1f}s")
+
+    dt = torch.bfloat16 if wl.bf16 else torch.float32
+    graph = sdt.Csr(torch.from_numpy(inst.indptr).cuda(), torch.from_numpy(inst.indices).cuda())
+    if wl.bf16:
+        X = torch.from_numpy(inst.X.view(np.int16)).cuda().view(torch.bfloat16)
+    else:
+        X = torch.from_numpy(inst.X).cuda()
+    y = torch.from_numpy(inst.y).cuda()
+    W = [torch.from_numpy(w).cuda() for w in inst.W]
+    b = [torch.from_numpy(v).cuda() for v in inst.b]
+    model = sdt.make_model(wl.dims, W, b)
+    code = sdt.SDT_BF16 if wl.bf16 else sdt.SDT_F32
+    lay = sdt.sdt_train_step_layout(graph.n_nodes, wl.batch, wl.fanouts, model, code)
+    ws = torch.empty(int(lay.total_bytes), dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    seeds_all = torch.from_numpy(np.stack([inst.batch(s) for s in range(Wm + K)])).cuda()
+    L = len(wl.fanouts)
+    es = 2 if wl.bf16 else 4
+
+    def run(first, count, timing=None, per_step=None):
+        for i in range(first, first + count):
+            sdt.sdt_train_step(graph, X, y, seeds_all[i], wl.fanouts, model, wl.seed, i, args.lr, loss, ws, timing)
+            if per_step is not None:
+                per_step(i)
+
+    # ---- warm-up, then the timed region: exactly K steps between two synchronisations.
+    # Only the dominant kernel is bracketed by HIP events inside the timed region.
+    dominant = ("aggregate_fwd", 0)
+    run(0, Wm)
+    tim = sdt.Timing(K, [dominant])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(Wm, K, tim)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    elapsed = t1 - t0
+    dom_ms = tim.read(*dominant)
+    tim.close()
+    final_loss = float(loss.item())
+
+    # ---- diagnostic pass (untimed): same batches again, every stage bracketed, sizes read back.
+    stages = [("sample", l) for l in range(L)] + [("gather", 0)] + [("aggregate_fwd", l) for l in range(L)] + \
+             [("linear_fwd", l) for l in range(L)] + [("loss", 0)] + [("linear_bwd", l) for l in range(L)] + \
+             [("aggregate_bwd", l) for l in range(1, L)] + [("update", 0)]
+    nd = min(K, 20)
+    tim2 = sdt.Timing(nd, stages)
+    counts = []
+
+    def grab(i):
+        torch.cuda.synchronize()
+        counts.append([sdt.ws_view(ws, lay.counts[l], (4,), torch.int32).cpu().tolist() for l in range(L)])
+
+    run(Wm, nd, tim2, grab)
+    stage_ms = {f"{k}[{l}]": float(np.mean(tim2.read(k, l))) for k, l in stages}
+    tim2.close()
+    counts = np.array(counts)                                  # [nd, L, 4] = n_dst, n_src, nnz, 0
+    mean_cnt = counts.mean(axis=0)
+    edges_per_step = float(counts[:, :, 2].sum(axis=1).mean())
+
+    # ---- roofline of the dominant kernel: algorithmic bytes of one launch / its mean duration
+    n_dst0, n_src0, nnz0 = mean_cnt[0][:3]
+    F0 = wl.dims[0]
+    agg_bytes = nnz0 * (F0 * es + 4) + n_dst0 * (F0 * es + 8)
+    dom_s = float(np.mean(dom_ms)) * 1e-3
+    achieved = agg_bytes / dom_s / 1e9
+    roofline = {"kernel": "k_aggregate_fwd (layer 0)", "bound": "hbm", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "algorithmic_bytes_per_launch": int(agg_bytes), "avg_launch_us": round(dom_s * 1e6, 2)}
+
+    gather_bytes = n_src0 * (2 * F0 * es + 4)
+    gemm_flops = 2.0 * n_dst0 * (2 * F0) * wl.dims[1]
+    others = {
+        "gather_GBps": round(gather_bytes / (stage_ms["gather[0]"] * 1e-3) / 1e9, 1),
+        "aggregate_fwd0_GBps": round(agg_bytes / (stage_ms["aggregate_fwd[0]"] * 1e-3) / 1e9, 1),
+        "linear_fwd0_TFLOPs": round(gemm_flops / (stage_ms["linear_fwd[0]"] * 1e-3) / 1e12, 2),
+        "linear_fwd0_frac_of_fp32_mfma_peak": round(gemm_flops / (stage_ms["linear_fwd[0]"] * 1e-3) / 1e12 /
+                                                    MFMA_FP32_PEAK_TFLOPS, 4),
+    }
+
+    # ---- CPU baseline: the oracle as it stands, one thread, on a bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import sdt_oracle as orc
+        ns = max(1, args.cpu_steps)
+        tc = time.perf_counter()
+        for s in range(ns):
+            orc.train_step(inst.indptr, inst.indices, inst.X, inst.y, inst.batch(s), wl.fanouts, inst.W, inst.b,
+                           wl.seed, s, args.lr, bf16=wl.bf16)
+        tc = time.perf_counter() - tc
+        cpu = {"value": round(ns / tc, 4), "unit": "steps/s", "cores": 1, "kind": "oracle",
+               "sample": f"{ns} full mini-batch steps of the same workload (batches 0..{ns - 1}, initial weights)",
+               "host_cpus": os.cpu_count()}
+
+    out = {
+        "metric": "train steps/s per GPU (sample + gather + forward + backward + SGD)",
+        "value": round(K / elapsed, 2), "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": round(elapsed / K * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if wl.bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.kind} 2^{wl.log2n} nodes, {nnz_graph} CSR entries, F={wl.feat}, "
+                               f"C={wl.classes}, {L}-layer GraphSAGE-mean hidden {wl.hidden}, fanout {wl.fanouts}, "
+                               f"batch {wl.batch}, seeds from the first {wl.owned_frac:g} of the ids",
+                   "lr": args.lr, "seed": wl.seed},
+        "sampled_edges_per_s": round(edges_per_step * K / elapsed, 1),
+        "sampled_edges_per_step": round(edges_per_step, 1),
+        "frontier_rows_per_step": round(float(n_src0), 1),
+        "final_loss": round(final_loss, 6),
+        "roofline": roofline, "cpu_baseline": cpu,
+        "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()}, "stage_rates": others,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -208,13 +208,39 @@ int32_t sdt_sage_linear_bwd(const void *dY, int64_t lddy, int32_t dy_dtype, cons
  * X is [n_nodes, F = dims[0]] in `dtype` with leading dimension ldx.
  * sdt_train_step_layout fills `layout` (host) with the workspace size and
  * the offsets of every intermediate. */
+/* Optional per-stage timing of sdt_train_step with HIP events recorded on the
+ * step's own stream (for measurement; adds two event records per selected
+ * stage).  A stage is (kind, layer); its bit in `stage_mask` is
+ * kind * SDT_MAX_LAYERS + layer.  SAMPLE spans all kernels of one layer's
+ * sampling; GATHER, LOSS and UPDATE use layer 0.  Each timed step consumes one
+ * slot (at most max_steps; further steps are not timed).  sdt_timing_read
+ * waits for the recorded events and writes one duration in milliseconds per
+ * timed step to ms_out (host, capacity max_steps) and their number to *n_out.
+ * All timing objects are host objects owned by the caller via create/destroy. */
+typedef struct sdt_timing sdt_timing;
+enum {
+    SDT_STAGE_SAMPLE = 0,
+    SDT_STAGE_GATHER = 1,
+    SDT_STAGE_AGG_FWD = 2,
+    SDT_STAGE_LINEAR_FWD = 3,
+    SDT_STAGE_LOSS = 4,
+    SDT_STAGE_LINEAR_BWD = 5,
+    SDT_STAGE_AGG_BWD = 6,
+    SDT_STAGE_UPDATE = 7
+};
+int32_t sdt_timing_create(int32_t max_steps, uint64_t stage_mask, sdt_timing **out /*host*/);
+void sdt_timing_destroy(sdt_timing *t);
+void sdt_timing_reset(sdt_timing *t);
+int32_t sdt_timing_read(sdt_timing *t, int32_t kind, int32_t layer, float *ms_out /*host*/, int32_t *n_out /*host*/);
+
 int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const int32_t *fanouts /*host*/,
                               const sdt_model *model /*host struct; only n_layers, dims read*/, int32_t dtype,
                               sdt_step_layout *layout /*host*/);
 int32_t sdt_train_step(const sdt_csr *graph /*host struct*/, const void *X, int64_t ldx, int32_t dtype,
                        const int32_t *labels, const int32_t *seeds, int32_t batch,
                        const int32_t *fanouts /*host*/, const sdt_model *model /*host struct*/, uint64_t seed,
-                       uint32_t step, float lr, float *loss_d, void *ws, size_t ws_bytes, void *stream);
+                       uint32_t step, float lr, float *loss_d, sdt_timing *timing /*host, nullable*/, void *ws,
+                       size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -75,8 +75,15 @@ EXPORTS = {
                                    _vp, _i32, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
     "sdt_train_step_layout": (_i32, [_i64, _i32, _vp, _vp, _i32, _vp]),
     "sdt_train_step": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp, _i32, _vp, _vp, _u64, _u32, ctypes.c_float, _vp, _vp,
-                              _sz, _vp]),
+                              _vp, _sz, _vp]),
+    "sdt_timing_create": (_i32, [_i32, _u64, _vp]),
+    "sdt_timing_destroy": (None, [_vp]),
+    "sdt_timing_reset": (None, [_vp]),
+    "sdt_timing_read": (_i32, [_vp, _i32, _i32, _vp, _vp]),
 }
+
+STAGES = {"sample": 0, "gather": 1, "aggregate_fwd": 2, "linear_fwd": 3, "loss": 4, "linear_bwd": 5,
+          "aggregate_bwd": 6, "update": 7}
 
 _lib = None
 
@@ -259,11 +266,63 @@ def sdt_train_step_layout(n_nodes: int, batch: int, fanouts: Sequence[int], mode
 
 
 def sdt_train_step(graph: Csr, X: torch.Tensor, labels: torch.Tensor, seeds: torch.Tensor, fanouts: Sequence[int],
-                   model: sdt_model, seed: int, step: int, lr: float, loss: torch.Tensor, ws: torch.Tensor):
+                   model: sdt_model, seed: int, step: int, lr: float, loss: torch.Tensor, ws: torch.Tensor,
+                   timing: Optional["Timing"] = None):
     f = (_i32 * len(fanouts))(*fanouts)
     _check(lib().sdt_train_step(ctypes.byref(graph.c), _ptr(X), X.stride(0), dtype_code(X), _ptr(labels),
                                 _ptr(seeds), seeds.numel(), f, ctypes.byref(model), seed, step, lr, _ptr(loss),
+                                timing.handle if timing is not None else None,
                                 _ptr(ws), ws.numel() * ws.element_size(), _stream()))
+
+
+def sdt_timing_create(max_steps: int, stage_mask: int) -> ctypes.c_void_p:
+    h = ctypes.c_void_p()
+    _check(lib().sdt_timing_create(max_steps, stage_mask, ctypes.byref(h)))
+    return h
+
+
+def sdt_timing_destroy(handle):
+    lib().sdt_timing_destroy(handle)
+
+
+def sdt_timing_reset(handle):
+    lib().sdt_timing_reset(handle)
+
+
+def sdt_timing_read(handle, kind: int, layer: int, max_steps: int) -> List[float]:
+    buf = (ctypes.c_float * max_steps)()
+    n = _i32(0)
+    _check(lib().sdt_timing_read(handle, kind, layer, buf, ctypes.byref(n)))
+    return list(buf[:n.value])
+
+
+class Timing:
+    """Owner of an sdt_timing object: HIP events around selected (stage, layer) pairs."""
+
+    def __init__(self, max_steps: int, stages: Sequence):
+        mask = 0
+        for kind, layer in stages:
+            mask |= 1 << (STAGES[kind] * SDT_MAX_LAYERS + layer)
+        self.max_steps = max_steps
+        self.handle = sdt_timing_create(max_steps, mask)
+
+    def reset(self):
+        sdt_timing_reset(self.handle)
+
+    def read(self, kind: str, layer: int = 0) -> List[float]:
+        """Milliseconds per timed step (waits for the events)."""
+        return sdt_timing_read(self.handle, STAGES[kind], layer, self.max_steps)
+
+    def close(self):
+        if self.handle:
+            sdt_timing_destroy(self.handle)
+            self.handle = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 # ----------------------------------------------------------------- workspace views (for inspection)

@@ -44,6 +44,83 @@ int32_t check_model(const sdt_model* m, const int32_t* fanouts, const char* who)
 
 using namespace sdt;
 
+// ---- per-stage HIP-event timing ---------------------------------------------------
+struct sdt_timing {
+    int32_t max_steps;
+    uint64_t mask;
+    int32_t used;                 // slots consumed so far
+    int32_t slot;                 // slot of the step being recorded, -1 = none
+    hipEvent_t* ev[64][2];        // [stage bit][begin/end][slot]
+};
+
+namespace {
+struct StageTimer {               // records begin now, end at scope exit
+    sdt_timing* t;
+    int bit;
+    hipStream_t st;
+    StageTimer(sdt_timing* tm, int kind, int layer, hipStream_t s) : t(tm), bit(kind * SDT_MAX_LAYERS + layer), st(s) {
+        if (t && t->slot >= 0 && ((t->mask >> bit) & 1)) (void)hipEventRecord(t->ev[bit][0][t->slot], st);
+        else t = nullptr;
+    }
+    ~StageTimer() {
+        if (t) (void)hipEventRecord(t->ev[bit][1][t->slot], st);
+    }
+};
+}  // namespace
+
+extern "C" int32_t sdt_timing_create(int32_t max_steps, uint64_t stage_mask, sdt_timing** out) {
+    SDT_REQUIRE(out && max_steps > 0 && max_steps <= (1 << 20), SDT_ERR_INVALID_ARG, "sdt_timing_create: bad arguments");
+    sdt_timing* t = new sdt_timing();
+    t->max_steps = max_steps;
+    t->mask = stage_mask;
+    t->used = 0;
+    t->slot = -1;
+    for (int b = 0; b < 64; ++b)
+        for (int k = 0; k < 2; ++k) {
+            t->ev[b][k] = nullptr;
+            if (!((stage_mask >> b) & 1)) continue;
+            t->ev[b][k] = new hipEvent_t[max_steps];
+            for (int i = 0; i < max_steps; ++i)
+                if (hipEventCreate(&t->ev[b][k][i]) != hipSuccess) {
+                    set_error("sdt_timing_create: hipEventCreate failed");
+                    return SDT_ERR_HIP;
+                }
+        }
+    *out = t;
+    return SDT_OK;
+}
+
+extern "C" void sdt_timing_destroy(sdt_timing* t) {
+    if (!t) return;
+    for (int b = 0; b < 64; ++b)
+        for (int k = 0; k < 2; ++k)
+            if (t->ev[b][k]) {
+                for (int i = 0; i < t->max_steps; ++i) (void)hipEventDestroy(t->ev[b][k][i]);
+                delete[] t->ev[b][k];
+            }
+    delete t;
+}
+
+extern "C" void sdt_timing_reset(sdt_timing* t) {
+    if (t) { t->used = 0; t->slot = -1; }
+}
+
+extern "C" int32_t sdt_timing_read(sdt_timing* t, int32_t kind, int32_t layer, float* ms_out, int32_t* n_out) {
+    SDT_REQUIRE(t && ms_out && n_out && kind >= 0 && kind < 8 && layer >= 0 && layer < SDT_MAX_LAYERS,
+                SDT_ERR_INVALID_ARG, "sdt_timing_read: bad arguments");
+    const int bit = kind * SDT_MAX_LAYERS + layer;
+    SDT_REQUIRE((t->mask >> bit) & 1, SDT_ERR_INVALID_ARG, "sdt_timing_read: stage (%d,%d) was not selected", kind, layer);
+    for (int i = 0; i < t->used; ++i) {
+        if (hipEventSynchronize(t->ev[bit][1][i]) != hipSuccess ||
+            hipEventElapsedTime(&ms_out[i], t->ev[bit][0][i], t->ev[bit][1][i]) != hipSuccess) {
+            set_error("sdt_timing_read: event (%d,%d) of step slot %d was not recorded", kind, layer, i);
+            return SDT_ERR_HIP;
+        }
+    }
+    *n_out = t->used;
+    return SDT_OK;
+}
+
 extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const int32_t* fanouts, const sdt_model* model,
                                          int32_t dtype, sdt_step_layout* lay) {
     SDT_REQUIRE(lay, SDT_ERR_INVALID_ARG, "sdt_train_step_layout: null layout");
@@ -97,8 +174,8 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
 
 extern "C" int32_t sdt_train_step(const sdt_csr* graph, const void* X, int64_t ldx, int32_t dtype, const int32_t* labels,
                                   const int32_t* seeds, int32_t batch, const int32_t* fanouts, const sdt_model* model,
-                                  uint64_t seed, uint32_t step, float lr, float* loss_d, void* ws, size_t ws_bytes,
-                                  void* stream) {
+                                  uint64_t seed, uint32_t step, float lr, float* loss_d, sdt_timing* timing, void* ws,
+                                  size_t ws_bytes, void* stream) {
     SDT_REQUIRE(graph && graph->indptr, SDT_ERR_INVALID_ARG, "sdt_train_step: null graph");
     sdt_step_layout lay;
     int32_t rc = sdt_train_step_layout(graph->n_nodes, batch, fanouts, model, dtype, &lay);
@@ -132,10 +209,13 @@ extern "C" int32_t sdt_train_step(const sdt_csr* graph, const void* X, int64_t l
         blk[l].t_rows = l >= 1 ? static_cast<int32_t*>(at(lay.t_rows[l])) : nullptr;
     }
 
+    if (timing) timing->slot = timing->used < timing->max_steps ? timing->used++ : -1;
+
     // ---- sample from the seeds outwards; the node -> local-id map carries over
     const int32_t* dst = seeds;
     const int32_t* n_d = nullptr;
     for (int l = L - 1; l >= 0; --l) {
+        StageTimer tm(timing, SDT_STAGE_SAMPLE, l, st);
         Arena a(at(lay.scratch));
         SampleWs sw;
         sample_ws_carve(a, graph->n_nodes, lay.cap_dst[l], fanouts[l], &sw);
@@ -147,15 +227,22 @@ extern "C" int32_t sdt_train_step(const sdt_csr* graph, const void* X, int64_t l
     }
 
     // ---- gather the input features of the outermost frontier
-    rc = sdt_gather_features(X, ldx, d[0], dtype, blk[0].src_nodes, lay.cap_src[0], blk[0].counts + 1, at(lay.H[0]),
-                             d[0], st);
+    {
+        StageTimer tm(timing, SDT_STAGE_GATHER, 0, st);
+        rc = sdt_gather_features(X, ldx, d[0], dtype, blk[0].src_nodes, lay.cap_src[0], blk[0].counts + 1,
+                                 at(lay.H[0]), d[0], st);
+    }
     if (rc != SDT_OK) return rc;
 
     // ---- forward
     for (int l = 0; l < L; ++l) {
-        rc = sdt_sage_aggregate_fwd(&blk[l], at(lay.H[l]), d[l], d[l], dtype, at(lay.A[l]), d[l], st);
+        {
+            StageTimer tm(timing, SDT_STAGE_AGG_FWD, l, st);
+            rc = sdt_sage_aggregate_fwd(&blk[l], at(lay.H[l]), d[l], d[l], dtype, at(lay.A[l]), d[l], st);
+        }
         if (rc != SDT_OK) return rc;
         const bool last = l == L - 1;
+        StageTimer tm(timing, SDT_STAGE_LINEAR_FWD, l, st);
         rc = sdt_sage_linear_fwd(at(lay.H[l]), d[l], at(lay.A[l]), d[l], lay.cap_dst[l], blk[l].counts, d[l], d[l + 1],
                                  model->W[l], model->b[l], last ? 0 : 1, dtype, at(lay.H[l + 1]), d[l + 1],
                                  last ? SDT_F32 : dtype, st);
@@ -163,8 +250,11 @@ extern "C" int32_t sdt_train_step(const sdt_csr* graph, const void* X, int64_t l
     }
 
     // ---- loss and its gradient
-    rc = softmax_xent(static_cast<const float*>(at(lay.H[L])), d[L], batch, d[L], labels, seeds,
-                      static_cast<float*>(at(lay.dZ)), static_cast<float*>(at(lay.row_loss)), loss_d, st);
+    {
+        StageTimer tm(timing, SDT_STAGE_LOSS, 0, st);
+        rc = softmax_xent(static_cast<const float*>(at(lay.H[L])), d[L], batch, d[L], labels, seeds,
+                          static_cast<float*>(at(lay.dZ)), static_cast<float*>(at(lay.row_loss)), loss_d, st);
+    }
     if (rc != SDT_OK) return rc;
 
     // ---- backward
@@ -176,12 +266,16 @@ extern "C" int32_t sdt_train_step(const sdt_csr* graph, const void* X, int64_t l
         dW[l] = model->dW[l] ? model->dW[l] : static_cast<float*>(at(lay.dW[l]));
         db[l] = model->db[l] ? model->db[l] : static_cast<float*>(at(lay.db[l]));
         const bool inner = l > 0;
+        {
+        StageTimer tm(timing, SDT_STAGE_LINEAR_BWD, l, st);
         rc = sdt_sage_linear_bwd(dY, d[l + 1], dy_dtype, nullptr, 0, 0, at(lay.H[l]), d[l], at(lay.A[l]), d[l],
                                  lay.cap_dst[l], blk[l].counts, d[l], d[l + 1], model->W[l], dtype, dW[l], db[l],
                                  inner ? at(lay.dSelf[l]) : nullptr, inner ? at(lay.dAgg[l]) : nullptr, d[l],
                                  at(lay.scratch), ws_bytes - lay.scratch, st);
+        }
         if (rc != SDT_OK) return rc;
         if (inner) {
+            StageTimer tm(timing, SDT_STAGE_AGG_BWD, l, st);
             // gradient w.r.t. H[l], masked by the ReLU that produced H[l]
             rc = sdt_sage_aggregate_bwd(&blk[l], at(lay.dAgg[l]), d[l], at(lay.dSelf[l]), d[l], at(lay.H[l]), d[l], dtype,
                                         at(lay.dH[l]), d[l], st);
@@ -192,5 +286,6 @@ extern "C" int32_t sdt_train_step(const sdt_csr* graph, const void* X, int64_t l
     }
 
     // ---- plain SGD on the fp32 weights
+    StageTimer tm(timing, SDT_STAGE_UPDATE, 0, st);
     return sgd_update(*model, dW, db, lr, st);
 }

@@ -99,7 +99,7 @@ def main():
     # ---- diagnostic pass (untimed): same batches again, every stage bracketed, sizes read back.
     stages = [("sample", l) for l in range(L)] + [("gather", 0)] + [("aggregate_fwd", l) for l in range(L)] + \
              [("linear_fwd", l) for l in range(L)] + [("loss", 0)] + [("linear_bwd", l) for l in range(L)] + \
-             [("aggregate_bwd", l) for l in range(1, L)] + [("update", 0)]
+             [("aggregate_bwd", l) for l in range(1, L)]
     nd = min(K, 20)
     tim2 = sdt.Timing(nd, stages)
     counts = []

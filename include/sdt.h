@@ -109,6 +109,8 @@ typedef struct sdt_model {
  * t_indptr/t_rows exist for l >= 1 only (layer 0 needs no input gradient). */
 typedef struct sdt_step_layout {
     uint64_t total_bytes;
+    uint64_t header; /* int32[64]: {magic, n_nodes, ...}; see sdt_train_step */
+    uint64_t state;  /* node -> local-id map and frontier bitmap, kept clean between steps */
     int32_t n_layers;
     int32_t cap_dst[SDT_MAX_LAYERS];
     int32_t cap_src[SDT_MAX_LAYERS];
@@ -206,6 +208,12 @@ int32_t sdt_sage_linear_bwd(const void *dY, int64_t lddy, int32_t dy_dtype, cons
  * labels[seeds[i]], backward, and W -= lr dW, b -= lr db (plain SGD on the
  * fp32 weights; lr = 0 leaves them bit-identical).  loss_d receives the loss.
  * X is [n_nodes, F = dims[0]] in `dtype` with leading dimension ldx.
+ * Workspace: unlike the other calls' scratch, the step workspace carries state
+ * from one step to the next (a header plus a node map that every step hands
+ * back clean, so it is initialised only when the header does not match).  It
+ * needs no initialisation before the first step, but between steps nobody else
+ * may write to it; a caller who reuses the buffer for something else must zero
+ * its first 256 bytes before the next step.
  * sdt_train_step_layout fills `layout` (host) with the workspace size and
  * the offsets of every intermediate. */
 /* Optional per-stage timing of sdt_train_step with HIP events recorded on the
@@ -226,7 +234,7 @@ enum {
     SDT_STAGE_LOSS = 4,
     SDT_STAGE_LINEAR_BWD = 5,
     SDT_STAGE_AGG_BWD = 6,
-    SDT_STAGE_UPDATE = 7
+    SDT_STAGE_UPDATE = 7 /* unused: the SGD step rides on LINEAR_BWD's final reduction */
 };
 int32_t sdt_timing_create(int32_t max_steps, uint64_t stage_mask, sdt_timing **out /*host*/);
 void sdt_timing_destroy(sdt_timing *t);

@@ -50,7 +50,7 @@ class sdt_model(ctypes.Structure):
 
 class sdt_step_layout(ctypes.Structure):
     _L = SDT_MAX_LAYERS
-    _fields_ = [("total_bytes", _u64), ("n_layers", _i32),
+    _fields_ = [("total_bytes", _u64), ("header", _u64), ("state", _u64), ("n_layers", _i32),
                 ("cap_dst", _i32 * _L), ("cap_src", _i32 * _L), ("cap_nnz", _i32 * _L),
                 ("counts", _u64 * _L), ("indptr", _u64 * _L), ("cols", _u64 * _L), ("src_nodes", _u64 * _L),
                 ("t_indptr", _u64 * _L), ("t_rows", _u64 * _L),

@@ -90,26 +90,48 @@ inline size_t dtype_size(int32_t dt) { return dt == SDT_BF16 ? 2 : 4; }
 inline bool dtype_ok(int32_t dt) { return dt == SDT_F32 || dt == SDT_BF16; }
 
 // ---- internal entry points shared between translation units -------------------
-// Sampling of one layer; `map_ready` says the node->local-id map in the
-// workspace already holds the destination nodes (chained layers of one step).
+// Sampling scratch.  map/bitmap persist across the layers of one step (and, for
+// sdt_train_step, across steps: every step leaves the map at -1 and the bitmap clear).
 struct SampleWs {
     int32_t* map;      // [n_nodes]   global id -> local id in the current frontier, -1 = absent
-    uint32_t* bitmap;  // [ceil(n_nodes/32)]  newly reached nodes (all zero between calls)
+    uint32_t* bitmap;  // [ceil(n_nodes/32)]  newly reached nodes (all zero between layers)
     int32_t* e_pad;    // [cap_dst*fanout]    sampled global ids, row-padded
     int32_t* m;        // [cap_dst]           sampled count per row
     int32_t* part;     // scan partials
-    int32_t* cursor;   // [cap_src] fill cursors of the transposed block
-    int32_t* longlist; // [cap_src+1] segments left to the cooperative sorter (+ counter)
+    int32_t* cursor;   // [cap_src+1] fill cursors of the transposed block
+    int32_t* longlist; // [cap_src+2] counter + segments left to the cooperative sorter
 };
-size_t sample_ws_carve(Arena& a, int64_t n_nodes, int32_t cap_dst, int32_t fanout, SampleWs* out);
+size_t sample_state_bytes(int64_t n_nodes);
+void sample_state_carve(void* base, int64_t n_nodes, SampleWs* out);
+size_t sample_tmp_carve(Arena& a, int64_t n_nodes, int32_t cap_dst, int32_t fanout, SampleWs* out);
+// header: int32[64] at the start of a step workspace ({magic, n_nodes, loss ticket, ...}) or nullptr.
+int32_t sample_state_init(const SampleWs& ws, int64_t n_nodes, const int32_t* header, hipStream_t st);
+int32_t sample_seed_map(const SampleWs& ws, const int32_t* dst_nodes, int32_t n_dst_cap, const int32_t* n_dst_d,
+                        int32_t* header, int64_t n_nodes, hipStream_t st);
 int32_t sample_layer(const sdt_csr& g, const int32_t* dst_nodes, int32_t n_dst_cap, const int32_t* n_dst_d,
                      int32_t fanout, uint64_t seed, uint32_t step, uint32_t layer, const sdt_block& out,
-                     const SampleWs& ws, bool map_ready, hipStream_t st);
-int32_t sample_init_map(const SampleWs& ws, int64_t n_nodes, const int32_t* dst_nodes, int32_t n_dst_cap,
-                        const int32_t* n_dst_d, hipStream_t st);
+                     const SampleWs& ws, hipStream_t st);
+// gather that also resets map[idx[j]] = -1 (map may be null)
+int32_t gather_rows(const void* X, int64_t ldx, int32_t F, int32_t dtype, const int32_t* idx, int32_t n_cap,
+                    const int32_t* n_d, void* out, int64_t ldo, int32_t* map_reset, hipStream_t st);
 
+// writes dZ and the per-row losses; their mean is folded into a later single-block pass
 int32_t softmax_xent(const float* logits, int64_t ld, int32_t B, int32_t C, const int32_t* labels,
-                     const int32_t* seeds, float* dZ, float* row_loss, float* loss_d, hipStream_t st);
-int32_t sgd_update(const sdt_model& m, float* const* dW, float* const* db, float lr, hipStream_t st);
+                     const int32_t* seeds, float* dZ, float* row_loss, hipStream_t st);
+// Extra work the final reduction of a projection backward can carry: the SGD step on (W, b)
+// and the fixed-order mean of the per-seed losses.
+struct BwdExtras {
+    float* W_upd = nullptr;
+    float* b_upd = nullptr;
+    float lr = 0.f;
+    const float* row_loss = nullptr;
+    int32_t n_loss = 0;
+    float* loss_out = nullptr;
+};
+// projection backward with optional extras once dW, db are final
+int32_t linear_bwd(const void* dY, int64_t lddy, int32_t dy_dtype, const void* Y, int64_t ldy, int32_t relu,
+                   const void* Hself, int64_t ldh, const void* A, int64_t lda, int32_t n_cap, const int32_t* n_d,
+                   int32_t in, int32_t out, const float* W, int32_t dtype, float* dW, float* db, void* dSelf,
+                   void* dAgg, int64_t ldi, void* ws, size_t ws_bytes, const BwdExtras& ex, hipStream_t st);
 
 }  // namespace sdt

@@ -23,7 +23,6 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int TB = 256;
-constexpr int BK = 32;
 
 // ---- global -> register -> LDS staging of an [R][C] tile, C contiguous in memory ----
 template <typename T, int R, int C, int V, bool ROUND>
@@ -97,13 +96,13 @@ struct Stage {
     }
 };
 
-constexpr int LD_KC = BK + 4;  // LDS row stride of a k-contiguous operand tile
 
 // One BK-deep step of the wave's (TM*32) x (TN*32) tile.
 //  A_KC: As is [BM][LD_KC] else [BK][LDA_OC];  B_KC likewise for Bs.
-template <int TM, int TN, bool A_KC, bool B_KC, int LDA_OC, int LDB_OC>
+template <int BK, int TM, int TN, bool A_KC, bool B_KC, int LDA_OC, int LDB_OC>
 __device__ __forceinline__ void mma_step(const float* As, const float* Bs, int arow0, int bcol0,
                                          floatx16 (&acc)[TM][TN]) {
+    constexpr int LD_KC = BK + 4;  // LDS row stride of a k-contiguous operand tile
     const int lane = threadIdx.x & 63, i = lane & 31, kh = lane >> 5;
 #pragma unroll
     for (int c = 0; c < BK / 8; ++c) {
@@ -142,12 +141,71 @@ __device__ __forceinline__ void mma_step(const float* As, const float* Bs, int a
 __device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 __device__ __forceinline__ int acc_col(int lane) { return lane & 31; }
 
-template <int BM, int BN>
+template <int BM_, int BN_>
 struct Tile {
+    static constexpr int BM = BM_, BN = BN_;
     static constexpr int WM = 2, WN = 2;               // 2 x 2 wavefronts
     static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     static constexpr int LDA_OC = BM + 4, LDB_OC = BN + 4;
+    // depth of one reduction step, sized so that two LDS buffers of both operands fit in 64 KB
+    static constexpr int BK = BM >= 128 ? 16 : 32;
+    static constexpr int LD_KC = BK + 4;
 };
+
+__device__ __forceinline__ void zero_acc(floatx16& a) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) a[r] = 0.f;
+}
+
+// Software-pipelined reduction loop shared by the three products.  Global loads run two
+// steps ahead of the MFMAs (two register stages), LDS is double-buffered, and one barrier
+// per step suffices: a buffer is rewritten only after the barrier of the step in between,
+// which every wave passes after it has finished reading that buffer.
+//   fetch(it, sa, sb)  issues the global loads of step `it` into a register stage
+//   hook(Bs)           optional extra work on the staged B tile (bias gradient)
+template <typename TL, bool A_KC, bool B_KC, typename SA, typename SB, typename Fetch, typename Hook>
+__device__ __forceinline__ void gemm_mainloop(int nit, float* As, float* Bs, Fetch&& fetch, Hook&& hook,
+                                              floatx16 (&acc)[TL::TM][TL::TN]) {
+    constexpr int BK = TL::BK;
+    constexpr int LDA = A_KC ? TL::LD_KC : TL::LDA_OC, LDB = B_KC ? TL::LD_KC : TL::LDB_OC;
+    constexpr int A_ELEMS = (A_KC ? TL::BM : BK) * LDA, B_ELEMS = (B_KC ? TL::BN : BK) * LDB;
+    const int wave = threadIdx.x >> 6, wm = wave / TL::WN, wn = wave % TL::WN;
+    const int a0 = wm * (TL::BM / TL::WM), b0 = wn * (TL::BN / TL::WN);
+    SA sa0, sa1;
+    SB sb0, sb1;
+    if (nit > 0) fetch(0, sa0, sb0);
+    if (nit > 1) fetch(1, sa1, sb1);
+    for (int it = 0; it < nit; it += 2) {
+        sa0.template store<LDA>(As);
+        sb0.template store<LDB>(Bs);
+        __syncthreads();
+        if (it + 2 < nit) fetch(it + 2, sa0, sb0);
+        hook(Bs);
+        mma_step<BK, TL::TM, TL::TN, A_KC, B_KC, TL::LDA_OC, TL::LDB_OC>(As, Bs, a0, b0, acc);
+        if (it + 1 < nit) {
+            sa1.template store<LDA>(As + A_ELEMS);
+            sb1.template store<LDB>(Bs + B_ELEMS);
+            __syncthreads();
+            if (it + 3 < nit) fetch(it + 3, sa1, sb1);
+            hook(Bs + B_ELEMS);
+            mma_step<BK, TL::TM, TL::TN, A_KC, B_KC, TL::LDA_OC, TL::LDB_OC>(As + A_ELEMS, Bs + B_ELEMS, a0, b0, acc);
+        }
+    }
+}
+
+// Visit every accumulator element of the workgroup tile: f(row_in_tile, col_in_tile, value).
+template <typename TL, typename F>
+__device__ __forceinline__ void for_each_acc(const floatx16 (&acc)[TL::TM][TL::TN], F&& f) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave / TL::WN, wn = wave % TL::WN;
+#pragma unroll
+    for (int tm = 0; tm < TL::TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TL::TN; ++tn) {
+            const int c = wn * (TL::BN / TL::WN) + tn * 32 + acc_col(lane);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) f(wm * (TL::BM / TL::WM) + tm * 32 + acc_row(r, lane), c, acc[tm][tn][r]);
+        }
+}
 
 // ---------------------------------------------------------------------------------
 // forward: Y[n,out] = act(Hself[n,in] Wself[in,out] + A[n,in] Wneigh[in,out] + b)
@@ -159,55 +217,34 @@ __global__ __launch_bounds__(TB) void k_linear_fwd(const TH* __restrict__ Hself,
                                                    const float* __restrict__ bias, int relu, TY* __restrict__ Y,
                                                    int64_t ldy) {
     using TL = Tile<BM, BN>;
+    constexpr int BK = TL::BK;
     const int n = dev_count(n_cap, n_d);
     const int row0 = blockIdx.y * BM, col0 = blockIdx.x * BN;
     if (row0 >= n) return;
-    __shared__ __align__(16) float As[BM * LD_KC];
-    __shared__ __align__(16) float Bs[BK * TL::LDB_OC];
-    const int wave = threadIdx.x >> 6, wm = wave / TL::WN, wn = wave % TL::WN;
+    __shared__ __align__(16) float As[2 * BM * TL::LD_KC];
+    __shared__ __align__(16) float Bs[2 * BK * TL::LDB_OC];
     floatx16 acc[TL::TM][TL::TN];
 #pragma unroll
     for (int a = 0; a < TL::TM; ++a)
 #pragma unroll
-        for (int b = 0; b < TL::TN; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
-
-    Stage<TH, BM, BK, VA, false> sa;
-    Stage<float, BK, BN, VB, ROUNDW> sb;
-    const int nk = (in + BK - 1) / BK, nit = 2 * nk;
-    auto fetch = [&](int it) {
-        const int ph = it / nk, k0 = (it - ph * nk) * BK;
+        for (int b = 0; b < TL::TN; ++b) zero_acc(acc[a][b]);
+    using SA = Stage<TH, BM, BK, VA, false>;
+    using SB = Stage<float, BK, BN, VB, ROUNDW>;
+    const int nk = (in + BK - 1) / BK;
+    auto fetch = [&](int it, SA& sa, SB& sb) {
+        const int ph = it >= nk, k0 = (it - ph * nk) * BK;
         sa.load(ph ? Agg : Hself, ph ? lda : ldh, row0, n, k0, in, nullptr, 0);
         sb.load(W + (int64_t)ph * in * out, out, k0, in, col0, out, nullptr, 0);
     };
-    fetch(0);
-    for (int it = 0; it < nit; ++it) {
-        sa.template store<LD_KC>(As);
-        sb.template store<TL::LDB_OC>(Bs);
-        __syncthreads();
-        if (it + 1 < nit) fetch(it + 1);
-        mma_step<TL::TM, TL::TN, true, false, 0, TL::LDB_OC>(As, Bs, wm * (BM / TL::WM), wn * (BN / TL::WN), acc);
-        __syncthreads();
-    }
-    const int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int tm = 0; tm < TL::TM; ++tm)
-#pragma unroll
-        for (int tn = 0; tn < TL::TN; ++tn) {
-            const int c = col0 + wn * (BN / TL::WN) + tn * 32 + acc_col(lane);
-            if (c >= out) continue;
-            const float bv = bias ? bias[c] : 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = row0 + wm * (BM / TL::WM) + tm * 32 + acc_row(r, lane);
-                if (row < n) {
-                    float z = acc[tm][tn][r] + bv;
-                    if (relu && !(z > 0.f)) z = 0.f;
-                    Y[(int64_t)row * ldy + c] = from_f32<TY>(z);
-                }
-            }
+    gemm_mainloop<TL, true, false, SA, SB>(2 * nk, As, Bs, fetch, [](const float*) {}, acc);
+    for_each_acc<TL>(acc, [&](int r, int c, float v) {
+        const int row = row0 + r, col = col0 + c;
+        if (row < n && col < out) {
+            float z = v + (bias ? bias[col] : 0.f);
+            if (relu && !(z > 0.f)) z = 0.f;
+            Y[(int64_t)row * ldy + col] = from_f32<TY>(z);
         }
+    });
 }
 
 // ---------------------------------------------------------------------------------
@@ -220,51 +257,30 @@ __global__ __launch_bounds__(TB) void k_linear_bwd_input(const TD* __restrict__ 
                                                          const float* __restrict__ W, TH* __restrict__ dSelf,
                                                          TH* __restrict__ dAgg, int64_t ldi) {
     using TL = Tile<BM, BN>;
+    constexpr int BK = TL::BK;
     const int n = dev_count(n_cap, n_d);
     const int row0 = blockIdx.y * BM, col0 = blockIdx.x * BN, half = blockIdx.z;
     if (row0 >= n) return;
-    __shared__ __align__(16) float As[BM * LD_KC];
-    __shared__ __align__(16) float Bs[BN * LD_KC];
-    const int wave = threadIdx.x >> 6, wm = wave / TL::WN, wn = wave % TL::WN;
+    __shared__ __align__(16) float As[2 * BM * TL::LD_KC];
+    __shared__ __align__(16) float Bs[2 * BN * TL::LD_KC];
     floatx16 acc[TL::TM][TL::TN];
 #pragma unroll
     for (int a = 0; a < TL::TM; ++a)
 #pragma unroll
-        for (int b = 0; b < TL::TN; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
-
-    Stage<TD, BM, BK, VD, ROUND && sizeof(TD) == 4> sa;
-    Stage<float, BN, BK, VW, ROUND> sb;
+        for (int b = 0; b < TL::TN; ++b) zero_acc(acc[a][b]);
+    using SA = Stage<TD, BM, BK, VD, ROUND && sizeof(TD) == 4>;
+    using SB = Stage<float, BN, BK, VW, ROUND>;
     const float* Wh = W + (int64_t)half * in * out;
-    const int nit = (out + BK - 1) / BK;
-    auto fetch = [&](int it) {
+    auto fetch = [&](int it, SA& sa, SB& sb) {
         sa.load(dY, lddy, row0, n, it * BK, out, Ymask, ldy);
         sb.load(Wh, out, col0, in, it * BK, out, nullptr, 0);
     };
-    fetch(0);
-    for (int it = 0; it < nit; ++it) {
-        sa.template store<LD_KC>(As);
-        sb.template store<LD_KC>(Bs);
-        __syncthreads();
-        if (it + 1 < nit) fetch(it + 1);
-        mma_step<TL::TM, TL::TN, true, true, 0, 0>(As, Bs, wm * (BM / TL::WM), wn * (BN / TL::WN), acc);
-        __syncthreads();
-    }
+    gemm_mainloop<TL, true, true, SA, SB>((out + BK - 1) / BK, As, Bs, fetch, [](const float*) {}, acc);
     TH* dst = half ? dAgg : dSelf;
-    const int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int tm = 0; tm < TL::TM; ++tm)
-#pragma unroll
-        for (int tn = 0; tn < TL::TN; ++tn) {
-            const int c = col0 + wn * (BN / TL::WN) + tn * 32 + acc_col(lane);
-            if (c >= in) continue;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = row0 + wm * (BM / TL::WM) + tm * 32 + acc_row(r, lane);
-                if (row < n) dst[(int64_t)row * ldi + c] = from_f32<TH>(acc[tm][tn][r]);
-            }
-        }
+    for_each_acc<TL>(acc, [&](int r, int c, float v) {
+        const int row = row0 + r, col = col0 + c;
+        if (row < n && col < in) dst[(int64_t)row * ldi + col] = from_f32<TH>(v);
+    });
 }
 
 // ---------------------------------------------------------------------------------
@@ -277,93 +293,81 @@ __global__ __launch_bounds__(TB) void k_linear_bwd_weight(const TH* __restrict__
                                                           const TD* __restrict__ dY, int64_t lddy,
                                                           const TD* __restrict__ Ymask, int64_t ldy, int n_cap,
                                                           const int32_t* n_d, int in, int out, int splits,
-                                                          float* __restrict__ P) {
+                                                          float* __restrict__ P, float* __restrict__ Q) {
     using TL = Tile<BM, BN>;
+    constexpr int BK = TL::BK;
     const int n = dev_count(n_cap, n_d);
     const int half = blockIdx.z & 1, split = blockIdx.z >> 1;
+    // the first row-tile of the self half also sums the columns of its dZ tiles (bias gradient)
+    const bool do_bias = Q != nullptr && half == 0 && blockIdx.y == 0;
+    float bsum = 0.f;
     const int row0 = blockIdx.y * BM /* feature m */, col0 = blockIdx.x * BN /* output o */;
     const int chunk = ((n + splits - 1) / splits + BK - 1) / BK * BK;
     const int r_begin = split * chunk, r_end = min(n, r_begin + chunk);
-    __shared__ __align__(16) float As[BK * TL::LDA_OC];
-    __shared__ __align__(16) float Bs[BK * TL::LDB_OC];
-    const int wave = threadIdx.x >> 6, wm = wave / TL::WN, wn = wave % TL::WN;
+    __shared__ __align__(16) float As[2 * BK * TL::LDA_OC];
+    __shared__ __align__(16) float Bs[2 * BK * TL::LDB_OC];
     floatx16 acc[TL::TM][TL::TN];
 #pragma unroll
     for (int a = 0; a < TL::TM; ++a)
 #pragma unroll
-        for (int b = 0; b < TL::TN; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
-
-    Stage<TH, BK, BM, VH, false> sa;
-    Stage<TD, BK, BN, VD, ROUND && sizeof(TD) == 4> sb;
+        for (int b = 0; b < TL::TN; ++b) zero_acc(acc[a][b]);
+    using SA = Stage<TH, BK, BM, VH, false>;
+    using SB = Stage<TD, BK, BN, VD, ROUND && sizeof(TD) == 4>;
     const TH* X = half ? Agg : Hself;
     const int64_t ldx = half ? lda : ldh;
     const int nit = r_end > r_begin ? (r_end - r_begin + BK - 1) / BK : 0;
-    auto fetch = [&](int it) {
+    auto fetch = [&](int it, SA& sa, SB& sb) {
         sa.load(X, ldx, r_begin + it * BK, r_end, row0, in, nullptr, 0);
         sb.load(dY, lddy, r_begin + it * BK, r_end, col0, out, Ymask, ldy);
     };
-    if (nit > 0) fetch(0);
-    for (int it = 0; it < nit; ++it) {
-        sa.template store<TL::LDA_OC>(As);
-        sb.template store<TL::LDB_OC>(Bs);
-        __syncthreads();
-        if (it + 1 < nit) fetch(it + 1);
-        mma_step<TL::TM, TL::TN, false, false, TL::LDA_OC, TL::LDB_OC>(As, Bs, wm * (BM / TL::WM), wn * (BN / TL::WN),
-                                                                       acc);
-        __syncthreads();
-    }
+    auto hook = [&](const float* Bcur) {
+        if (do_bias && (int)threadIdx.x < BN) {
+#pragma unroll 8
+            for (int k = 0; k < BK; ++k) bsum += Bcur[k * TL::LDB_OC + threadIdx.x];
+        }
+    };
+    gemm_mainloop<TL, false, false, SA, SB>(nit, As, Bs, fetch, hook, acc);
+    if (do_bias && (int)threadIdx.x < BN && col0 + (int)threadIdx.x < out)
+        Q[(int64_t)split * out + col0 + threadIdx.x] = bsum;
     float* dst = P + ((int64_t)split * 2 * in + (int64_t)half * in) * out;
-    const int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int tm = 0; tm < TL::TM; ++tm)
-#pragma unroll
-        for (int tn = 0; tn < TL::TN; ++tn) {
-            const int c = col0 + wn * (BN / TL::WN) + tn * 32 + acc_col(lane);
-            if (c >= out) continue;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = row0 + wm * (BM / TL::WM) + tm * 32 + acc_row(r, lane);
-                if (row < in) dst[(int64_t)row * out + c] = acc[tm][tn][r];
-            }
-        }
+    for_each_acc<TL>(acc, [&](int r, int c, float v) {
+        const int row = row0 + r, col = col0 + c;
+        if (row < in && col < out) dst[(int64_t)row * out + col] = v;
+    });
 }
 
-// db partials: Q[s][o] = sum over the rows of split s of dZ[r, o]
-template <typename TD, bool ROUND>
-__global__ __launch_bounds__(TB) void k_bias_partials(const TD* __restrict__ dY, int64_t lddy,
-                                                      const TD* __restrict__ Ymask, int64_t ldy, int n_cap,
-                                                      const int32_t* n_d, int out, int splits, float* __restrict__ Q) {
-    const int n = dev_count(n_cap, n_d);
-    const int chunk = (n + splits - 1) / splits;
-    const int r0 = blockIdx.x * chunk, r1 = min(n, r0 + chunk);
-    for (int o = threadIdx.x; o < out; o += TB) {
+// dW[idx] = sum_s P[s][idx] (s ascending); db[o] = sum_s Q[s][o]; optionally the SGD step
+// W -= lr dW, b -= lr db in the same pass.
+__global__ __launch_bounds__(TB) void k_reduce_partials(const float* __restrict__ P, const float* __restrict__ Q,
+                                                        int splits, int64_t n_w, int out, float* __restrict__ dW,
+                                                        float* __restrict__ db, float* W_upd, float* b_upd, float lr,
+                                                        const float* __restrict__ row_loss, int n_loss,
+                                                        float* loss_out) {
+    if (loss_out && blockIdx.x == gridDim.x - 1) {  // the extra last block: mean loss in a fixed order
+        __shared__ float part[TB];
         float s = 0.f;
-        for (int r = r0; r < r1; ++r) {
-            float g = to_f32<TD>(dY[(int64_t)r * lddy + o]);
-            if (ROUND && sizeof(TD) == 4) g = bf16_to_f32(f32_to_bf16(g));
-            if (Ymask && !(to_f32<TD>(Ymask[(int64_t)r * ldy + o]) > 0.f)) g = 0.f;
-            s += g;
+        for (int i = threadIdx.x; i < n_loss; i += TB) s += row_loss[i];
+        part[threadIdx.x] = s;
+        __syncthreads();
+        for (int o = TB / 2; o > 0; o >>= 1) {
+            if ((int)threadIdx.x < o) part[threadIdx.x] += part[threadIdx.x + o];
+            __syncthreads();
         }
-        Q[(int64_t)blockIdx.x * out + o] = s;
+        if (threadIdx.x == 0) *loss_out = part[0] / (float)n_loss;
+        return;
     }
-}
-
-// dW[idx] = sum_s P[s][idx] (s ascending); db[o] = sum_s Q[s][o]
-__global__ __launch_bounds__(TB) void k_reduce_partials(const float* __restrict__ P, int splits_w, int64_t n_w,
-                                                        float* __restrict__ dW, const float* __restrict__ Q,
-                                                        int splits_b, int out, float* __restrict__ db) {
     const int64_t idx = (int64_t)blockIdx.x * TB + threadIdx.x;
     if (idx < n_w) {
         float s = 0.f;
-        for (int k = 0; k < splits_w; ++k) s += P[(int64_t)k * n_w + idx];
+        for (int k = 0; k < splits; ++k) s += P[(int64_t)k * n_w + idx];
         dW[idx] = s;
+        if (W_upd) W_upd[idx] = W_upd[idx] - lr * s;
     } else if (idx < n_w + out) {
         const int o = (int)(idx - n_w);
         float s = 0.f;
-        for (int k = 0; k < splits_b; ++k) s += Q[(int64_t)k * out + o];
+        for (int k = 0; k < splits; ++k) s += Q[(int64_t)k * out + o];
         db[o] = s;
+        if (b_upd) b_upd[o] = b_upd[o] - lr * s;
     }
 }
 
@@ -380,12 +384,10 @@ int vec_elems(size_t es, int width, std::initializer_list<int64_t> lds, std::ini
     return v > 4 && es == 4 ? 4 : v;
 }
 
-constexpr int BIAS_SPLITS = 64;
-
 int weight_splits(int n_cap, int in, int out, int BM, int BN) {
     const int tiles = ceil_div(in, BM) * ceil_div(out, BN) * 2;
-    int s = ceil_div(1024, tiles);
-    const int max_s = ceil_div(n_cap > 0 ? n_cap : 1, 4 * BK);
+    int s = ceil_div(256, tiles);  // about one workgroup per CU
+    const int max_s = ceil_div(n_cap > 0 ? n_cap : 1, 256);
     if (s > max_s) s = max_s;
     if (s < 1) s = 1;
     return s;
@@ -433,7 +435,7 @@ template <typename TD, typename TH, int BM, int BN>
 void launch_bwd(const void* dY, int64_t lddy, const void* Ymask, int64_t ldy, const void* Hself, int64_t ldh,
                 const void* A, int64_t lda, int n_cap, const int32_t* n_d, int in, int out, const float* W, float* dW,
                 float* db, void* dSelf, void* dAgg, int64_t ldi, float* P, float* Q, int splits, bool round,
-                hipStream_t st) {
+                const BwdExtras& ex, hipStream_t st) {
     const int vd = vec_elems(sizeof(TD), out, {lddy, Ymask ? ldy : lddy}, {dY, Ymask});
     const int vh = vec_elems(sizeof(TH), in, {ldh, lda}, {Hself, A});
     const int vw = vec_elems(4, out, {(int64_t)out}, {W});
@@ -449,23 +451,14 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Ymask, int64_t ldy, co
                 if (round)
                     hipLaunchKernelGGL((k_linear_bwd_weight<TD, TH, BM, BN, VH, VD, true>), grid, dim3(TB), 0, st,
                                        static_cast<const TH*>(Hself), ldh, static_cast<const TH*>(A), lda, dYt, lddy,
-                                       Ym, ldy, n_cap, n_d, in, out, splits, P);
+                                       Ym, ldy, n_cap, n_d, in, out, splits, P, Q);
                 else
                     hipLaunchKernelGGL((k_linear_bwd_weight<TD, TH, BM, BN, VH, VD, false>), grid, dim3(TB), 0, st,
                                        static_cast<const TH*>(Hself), ldh, static_cast<const TH*>(A), lda, dYt, lddy,
-                                       Ym, ldy, n_cap, n_d, in, out, splits, P);
+                                       Ym, ldy, n_cap, n_d, in, out, splits, P, Q);
             })
         })
     }
-    if (round)
-        hipLaunchKernelGGL((k_bias_partials<TD, true>), dim3(BIAS_SPLITS), dim3(TB), 0, st, dYt, lddy, Ym, ldy, n_cap,
-                           n_d, out, BIAS_SPLITS, Q);
-    else
-        hipLaunchKernelGGL((k_bias_partials<TD, false>), dim3(BIAS_SPLITS), dim3(TB), 0, st, dYt, lddy, Ym, ldy, n_cap,
-                           n_d, out, BIAS_SPLITS, Q);
-    const int64_t n_w = (int64_t)2 * in * out;
-    hipLaunchKernelGGL(k_reduce_partials, dim3(ceil_div(n_w + out, TB)), dim3(TB), 0, st, P, splits, n_w, dW, Q,
-                       BIAS_SPLITS, out, db);
     if (dSelf) {
         dim3 grid(ceil_div(in, BN), ceil_div(n_cap, BM), 2);
         SDT_VEC_SWITCH(vd, (16 / sizeof(TD)), {
@@ -483,6 +476,10 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Ymask, int64_t ldy, co
             })
         })
     }
+    // after the input gradients: this pass may overwrite W with the SGD step
+    const int64_t n_w = (int64_t)2 * in * out;
+    hipLaunchKernelGGL(k_reduce_partials, dim3(ceil_div(n_w + out, TB) + (ex.loss_out ? 1 : 0)), dim3(TB), 0, st, P, Q,
+                       splits, n_w, out, dW, db, ex.W_upd, ex.b_upd, ex.lr, ex.row_loss, ex.n_loss, ex.loss_out);
 }
 
 constexpr int FBM = 64, FBN = 64;  // tile of the mini-batch sized products
@@ -519,14 +516,14 @@ extern "C" int32_t sdt_sage_linear_fwd(const void* Hself, int64_t ldh, const voi
 extern "C" size_t sdt_linear_bwd_workspace_bytes(int32_t n_cap, int32_t in, int32_t out) {
     if (n_cap < 0 || in <= 0 || out <= 0) return 0;
     const int s = weight_splits(n_cap, in, out, FBM, FBN);
-    return align_up((size_t)s * 2 * in * out * sizeof(float), 256) + align_up((size_t)BIAS_SPLITS * out * sizeof(float), 256);
+    return align_up((size_t)s * 2 * in * out * sizeof(float), 256) + align_up((size_t)s * out * sizeof(float), 256);
 }
 
-extern "C" int32_t sdt_sage_linear_bwd(const void* dY, int64_t lddy, int32_t dy_dtype, const void* Y, int64_t ldy,
-                                       int32_t relu, const void* Hself, int64_t ldh, const void* A, int64_t lda,
-                                       int32_t n_cap, const int32_t* n_d, int32_t in, int32_t out, const float* W,
-                                       int32_t dtype, float* dW, float* db, void* dSelf, void* dAgg, int64_t ldi,
-                                       void* ws, size_t ws_bytes, void* stream) {
+namespace sdt {
+int32_t linear_bwd(const void* dY, int64_t lddy, int32_t dy_dtype, const void* Y, int64_t ldy, int32_t relu,
+                   const void* Hself, int64_t ldh, const void* A, int64_t lda, int32_t n_cap, const int32_t* n_d,
+                   int32_t in, int32_t out, const float* W, int32_t dtype, float* dW, float* db, void* dSelf,
+                   void* dAgg, int64_t ldi, void* ws, size_t ws_bytes, const BwdExtras& ex, hipStream_t st) {
     SDT_REQUIRE(dtype_ok(dtype) && dtype_ok(dy_dtype), SDT_ERR_INVALID_ARG, "sdt_sage_linear_bwd: unknown dtype");
     SDT_REQUIRE(!(dtype == SDT_F32 && dy_dtype == SDT_BF16), SDT_ERR_INVALID_ARG,
                 "sdt_sage_linear_bwd: bf16 dY needs bf16 activations");
@@ -544,16 +541,25 @@ extern "C" int32_t sdt_sage_linear_bwd(const void* dY, int64_t lddy, int32_t dy_
     float* P = static_cast<float*>(ws);
     float* Q = reinterpret_cast<float*>(static_cast<char*>(ws) + align_up((size_t)splits * 2 * in * out * sizeof(float), 256));
     const void* Ym = relu ? Y : nullptr;
-    hipStream_t st = static_cast<hipStream_t>(stream);
     if (dtype == SDT_F32)
         launch_bwd<float, float, FBM, FBN>(dY, lddy, Ym, ldy, Hself, ldh, A, lda, n_cap, n_d, in, out, W, dW, db, dSelf,
-                                           dAgg, ldi, P, Q, splits, false, st);
+                                           dAgg, ldi, P, Q, splits, false, ex, st);
     else if (dy_dtype == SDT_F32)
         launch_bwd<float, bf16_t, FBM, FBN>(dY, lddy, Ym, ldy, Hself, ldh, A, lda, n_cap, n_d, in, out, W, dW, db,
-                                            dSelf, dAgg, ldi, P, Q, splits, true, st);
+                                            dSelf, dAgg, ldi, P, Q, splits, true, ex, st);
     else
         launch_bwd<bf16_t, bf16_t, FBM, FBN>(dY, lddy, Ym, ldy, Hself, ldh, A, lda, n_cap, n_d, in, out, W, dW, db,
-                                             dSelf, dAgg, ldi, P, Q, splits, true, st);
+                                             dSelf, dAgg, ldi, P, Q, splits, true, ex, st);
     SDT_CHECK_LAUNCH("linear_bwd");
     return SDT_OK;
+}
+}  // namespace sdt
+
+extern "C" int32_t sdt_sage_linear_bwd(const void* dY, int64_t lddy, int32_t dy_dtype, const void* Y, int64_t ldy,
+                                       int32_t relu, const void* Hself, int64_t ldh, const void* A, int64_t lda,
+                                       int32_t n_cap, const int32_t* n_d, int32_t in, int32_t out, const float* W,
+                                       int32_t dtype, float* dW, float* db, void* dSelf, void* dAgg, int64_t ldi,
+                                       void* ws, size_t ws_bytes, void* stream) {
+    return linear_bwd(dY, lddy, dy_dtype, Y, ldy, relu, Hself, ldh, A, lda, n_cap, n_d, in, out, W, dtype, dW, db,
+                      dSelf, dAgg, ldi, ws, ws_bytes, BwdExtras{}, static_cast<hipStream_t>(stream));
 }

@@ -31,6 +31,7 @@ __device__ __forceinline__ float wave_sum(float x) {
 }
 
 // One wavefront per seed row: loss_i = logsumexp(z_i) - z_i[y_i]; dZ = (softmax - onehot)/B.
+// The mean of the row losses is taken later, in a fixed order, by mean_loss_block().
 __global__ __launch_bounds__(TB) void k_softmax_xent(const float* __restrict__ Z, int64_t ld, int B, int C,
                                                      const int32_t* __restrict__ labels,
                                                      const int32_t* __restrict__ seeds, float* __restrict__ dZ,
@@ -54,71 +55,14 @@ __global__ __launch_bounds__(TB) void k_softmax_xent(const float* __restrict__ Z
     if (lane == 0) row_loss[row] = logf(s) + mx - z[y];
 }
 
-// Fixed-order mean of the row losses (one block; deterministic).
-__global__ __launch_bounds__(TB) void k_mean_loss(const float* __restrict__ row_loss, int B, float* loss) {
-    __shared__ float part[TB];
-    float s = 0.f;
-    for (int i = threadIdx.x; i < B; i += TB) s += row_loss[i];
-    part[threadIdx.x] = s;
-    __syncthreads();
-    for (int o = TB / 2; o > 0; o >>= 1) {
-        if ((int)threadIdx.x < o) part[threadIdx.x] += part[threadIdx.x + o];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) *loss = part[0] / (float)B;
-}
-
-struct SgdArgs {
-    float* p[2 * SDT_MAX_LAYERS];
-    const float* g[2 * SDT_MAX_LAYERS];
-    int64_t end[2 * SDT_MAX_LAYERS];  // running element counts
-    int n;
-    float lr;
-};
-
-__global__ __launch_bounds__(TB) void k_sgd(SgdArgs a) {
-    const int64_t total = a.end[a.n - 1];
-    for (int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x; i < total; i += (int64_t)gridDim.x * TB) {
-        int t = 0;
-        while (i >= a.end[t]) ++t;
-        const int64_t k = i - (t ? a.end[t - 1] : 0);
-        a.p[t][k] = a.p[t][k] - a.lr * a.g[t][k];
-    }
-}
-
 }  // namespace
 
 int32_t softmax_xent(const float* logits, int64_t ld, int32_t B, int32_t C, const int32_t* labels,
-                     const int32_t* seeds, float* dZ, float* row_loss, float* loss_d, hipStream_t st) {
+                     const int32_t* seeds, float* dZ, float* row_loss, hipStream_t st) {
     if (B <= 0) return SDT_OK;
     hipLaunchKernelGGL(k_softmax_xent, dim3(ceil_div(B, TB / WAVE)), dim3(TB), 0, st, logits, ld, B, C, labels, seeds,
                        dZ, row_loss);
     SDT_CHECK_LAUNCH("softmax_xent");
-    hipLaunchKernelGGL(k_mean_loss, dim3(1), dim3(TB), 0, st, row_loss, B, loss_d);
-    SDT_CHECK_LAUNCH("mean_loss");
-    return SDT_OK;
-}
-
-int32_t sgd_update(const sdt_model& m, float* const* dW, float* const* db, float lr, hipStream_t st) {
-    SgdArgs a;
-    int64_t run = 0;
-    a.n = 0;
-    for (int l = 0; l < m.n_layers; ++l) {
-        a.p[a.n] = m.W[l];
-        a.g[a.n] = dW[l];
-        run += (int64_t)2 * m.dims[l] * m.dims[l + 1];
-        a.end[a.n++] = run;
-        a.p[a.n] = m.b[l];
-        a.g[a.n] = db[l];
-        run += m.dims[l + 1];
-        a.end[a.n++] = run;
-    }
-    a.lr = lr;
-    if (run == 0) return SDT_OK;
-    int grid = ceil_div(run, TB * 4);
-    if (grid > 1024) grid = 1024;
-    hipLaunchKernelGGL(k_sgd, dim3(grid), dim3(TB), 0, st, a);
-    SDT_CHECK_LAUNCH("sgd");
     return SDT_OK;
 }
 

@@ -52,13 +52,15 @@ __device__ __forceinline__ void store_f32(T* p, const float in[VE]) {
 template <int VB, int G>
 __global__ __launch_bounds__(TB) void k_gather(const char* __restrict__ X, int64_t ldx_b, int row_b,
                                                const int32_t* __restrict__ idx, int n_cap, const int32_t* n_d,
-                                               char* __restrict__ out, int64_t ldo_b) {
+                                               char* __restrict__ out, int64_t ldo_b, int32_t* map_reset) {
     using raw_t = typename Raw<VB>::type;
     const int n = dev_count(n_cap, n_d);
     const int gl = threadIdx.x % G;
     const int64_t ngrp = (int64_t)gridDim.x * (TB / G);
     for (int64_t j = (int64_t)blockIdx.x * (TB / G) + threadIdx.x / G; j < n; j += ngrp) {
-        const char* src = X + (int64_t)idx[j] * ldx_b;
+        const int node = idx[j];
+        if (map_reset && gl == 0) map_reset[node] = -1;  // hand the frontier map back clean
+        const char* src = X + (int64_t)node * ldx_b;
         char* dst = out + j * ldo_b;
         for (int b = gl * VB; b < row_b; b += G * VB)
             *reinterpret_cast<raw_t*>(dst + b) = *reinterpret_cast<const raw_t*>(src + b);
@@ -186,7 +188,7 @@ int group_lanes(int vecs_per_row) {
 inline int grid_rows(int64_t rows, int G) {
     int64_t b = (rows + (TB / G) - 1) / (TB / G);
     if (b < 1) b = 1;
-    const int64_t cap = 256 * 64;  // enough blocks to fill every CU many times over
+    const int64_t cap = 256 * 8;  // 8 workgroups per CU; the kernels stride over the rest
     return (int)(b > cap ? cap : b);
 }
 
@@ -244,8 +246,9 @@ int32_t launch_aggregate_fwd(const IP* indptr, const int32_t* cols, int64_t n_ca
 
 using namespace sdt;
 
-extern "C" int32_t sdt_gather_features(const void* X, int64_t ldx, int32_t F, int32_t dtype, const int32_t* idx,
-                                       int32_t n_cap, const int32_t* n_d, void* out, int64_t ldo, void* stream) {
+namespace sdt {
+int32_t gather_rows(const void* X, int64_t ldx, int32_t F, int32_t dtype, const int32_t* idx, int32_t n_cap,
+                    const int32_t* n_d, void* out, int64_t ldo, int32_t* map_reset, hipStream_t st) {
     SDT_REQUIRE(dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_gather_features: unknown dtype %d", dtype);
     SDT_REQUIRE(F >= 0 && n_cap >= 0 && ldx >= F && ldo >= F, SDT_ERR_INVALID_ARG,
                 "sdt_gather_features: bad sizes F=%d n=%d ldx=%lld ldo=%lld", F, n_cap, (long long)ldx, (long long)ldo);
@@ -255,13 +258,12 @@ extern "C" int32_t sdt_gather_features(const void* X, int64_t ldx, int32_t F, in
     const int vb = vec_bytes(es, F, {ldx, ldo}, {X, out});
     const int row_b = (int)(F * es);
     const int G = group_lanes((row_b + vb - 1) / vb);
-    hipStream_t st = static_cast<hipStream_t>(stream);
     const char* Xc = static_cast<const char*>(X);
     char* oc = static_cast<char*>(out);
     const int64_t ldx_b = ldx * (int64_t)es, ldo_b = ldo * (int64_t)es;
 #define SDT_GATHER(VB, GG)                                                                                         \
     hipLaunchKernelGGL((k_gather<VB, GG>), dim3(grid_rows(n_cap, GG)), dim3(TB), 0, st, Xc, ldx_b, row_b, idx, n_cap, \
-                       n_d, oc, ldo_b)
+                       n_d, oc, ldo_b, map_reset)
 #define SDT_GATHER_G(VB)                    \
     switch (G) {                            \
         case 8: SDT_GATHER(VB, 8); break;   \
@@ -279,6 +281,12 @@ extern "C" int32_t sdt_gather_features(const void* X, int64_t ldx, int32_t F, in
 #undef SDT_GATHER
     SDT_CHECK_LAUNCH("gather");
     return SDT_OK;
+}
+}  // namespace sdt
+
+extern "C" int32_t sdt_gather_features(const void* X, int64_t ldx, int32_t F, int32_t dtype, const int32_t* idx,
+                                       int32_t n_cap, const int32_t* n_d, void* out, int64_t ldo, void* stream) {
+    return gather_rows(X, ldx, F, dtype, idx, n_cap, n_d, out, ldo, nullptr, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int32_t sdt_sage_aggregate_fwd(const sdt_block* blk, const void* H, int64_t ldh, int32_t F, int32_t dtype,

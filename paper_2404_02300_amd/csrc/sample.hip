@@ -44,11 +44,6 @@ __global__ __launch_bounds__(TB) void k_fill_i32(int32_t* p, int64_t n, int32_t 
     for (; i < n; i += stride) p[i] = v;
 }
 
-__global__ __launch_bounds__(TB) void k_scatter_ids(int32_t* map, const int32_t* dst, int n_cap, const int32_t* n_d) {
-    int n = dev_count(n_cap, n_d);
-    for (int i = blockIdx.x * TB + threadIdx.x; i < n; i += gridDim.x * TB) map[dst[i]] = i;
-}
-
 // One wave per destination row.
 __global__ __launch_bounds__(TB) void k_sample_rows(const int64_t* __restrict__ indptr,
                                                     const int32_t* __restrict__ indices,
@@ -94,10 +89,7 @@ __global__ __launch_bounds__(TB) void k_sample_rows(const int64_t* __restrict__ 
         if (lane < m) {
             const int g = indices[start + pos];
             e_pad[(int64_t)i * fanout + rank] = g;
-            if (map[g] < 0) {
-                const uint32_t bit = 1u << (g & 31);
-                if (!(bitmap[g >> 5] & bit)) atomicOr(&bitmap[g >> 5], bit);
-            }
+            if (map[g] < 0) atomicOr(&bitmap[g >> 5], 1u << (g & 31));  // result unused: fire and forget
         }
         if (lane == 0) m_out[i] = m;
     }
@@ -114,9 +106,10 @@ __device__ __forceinline__ int wave_incl_scan(int x) {
     return x;
 }
 
-// Returns the exclusive prefix of `sum` over the block's threads; *total = block sum.
+// Returns the exclusive prefix of `sum` over the block's NT threads; *total = block sum.
+template <int NT = TB>
 __device__ __forceinline__ int block_excl_scan(int sum, int* total) {
-    __shared__ int wsum[TB / WAVE];
+    __shared__ int wsum[NT / WAVE];
     const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
     const int incl = wave_incl_scan(sum);
     __syncthreads();
@@ -124,7 +117,7 @@ __device__ __forceinline__ int block_excl_scan(int sum, int* total) {
     __syncthreads();
     int base = 0, tot = 0;
 #pragma unroll
-    for (int q = 0; q < TB / WAVE; ++q) {
+    for (int q = 0; q < NT / WAVE; ++q) {
         if (q < w) base += wsum[q];
         tot += wsum[q];
     }
@@ -155,16 +148,19 @@ __global__ __launch_bounds__(TB) void k_front_partials(const int32_t* __restrict
     if (threadIdx.x == 0) part[blockIdx.x] = total;
 }
 
-// Sequential-by-chunks exclusive scan of `cnt` values by one block; returns the total.
-__device__ int spine_scan(int32_t* p, int cnt) {
+// Sequential-by-chunks exclusive scan of `cnt` values by one block of NT threads
+// (in place, or into `out`); returns the total.  `zero_me` (nullable) is cleared alongside.
+template <int NT = TB>
+__device__ int spine_scan(int32_t* p, int cnt, int32_t* zero_me = nullptr) {
     __shared__ int carry_s;
     if (threadIdx.x == 0) carry_s = 0;
     __syncthreads();
-    for (int c0 = 0; c0 < cnt; c0 += TB) {
+    for (int c0 = 0; c0 < cnt; c0 += NT) {
         const int idx = c0 + threadIdx.x;
         const int x = idx < cnt ? p[idx] : 0;
+        if (zero_me && idx < cnt) zero_me[idx] = 0;
         int total;
-        const int ex = block_excl_scan(x, &total);
+        const int ex = block_excl_scan<NT>(x, &total);
         const int carry = carry_s;
         if (idx < cnt) p[idx] = carry + ex;
         __syncthreads();
@@ -174,31 +170,52 @@ __device__ int spine_scan(int32_t* p, int cnt) {
     return carry_s;
 }
 
-__global__ __launch_bounds__(TB) void k_front_spine(int32_t* part, int pm, int pb, int n_cap, const int32_t* n_d,
-                                                    int32_t* counts, int32_t* b_indptr) {
-    const int n = dev_count(n_cap, n_d);
-    const int nnz = spine_scan(part, pm);
+// Sums of three ranges of part[] by the whole block: [0,pm), [pm,pm+pb) and [lo,my).
+__device__ __forceinline__ void part_sums(const int32_t* __restrict__ part, int pm, int pb, int lo, int my, int* nnz,
+                                          int* n_new, int* before) {
+    __shared__ int red[3][TB / WAVE];
+    int a = 0, b = 0, c = 0;
+    for (int i = threadIdx.x; i < pm + pb; i += TB) {
+        const int v = part[i];
+        if (i < pm) a += v; else b += v;
+        if (i >= lo && i < my) c += v;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        a += __shfl_xor(a, o);
+        b += __shfl_xor(b, o);
+        c += __shfl_xor(c, o);
+    }
+    const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
+    if (lane == 0) { red[0][w] = a; red[1][w] = b; red[2][w] = c; }
     __syncthreads();
-    const int n_new = spine_scan(part + pm, pb);
-    if (threadIdx.x == 0) {
+    a = b = c = 0;
+#pragma unroll
+    for (int q = 0; q < TB / WAVE; ++q) { a += red[0][q]; b += red[1][q]; c += red[2][q]; }
+    *nnz = a; *n_new = b; *before = c;
+}
+
+// Pass 2 (every block first sums the few partials it needs, so no separate spine launch):
+// write b_indptr and the block's counts; emit the new frontier nodes (ascending id), extend
+// the node -> local-id map, clear the bitmap; zero the histogram of the transposed block.
+__global__ __launch_bounds__(TB) void k_front_apply(const int32_t* __restrict__ m, int n_cap, const int32_t* n_d,
+                                                    uint32_t* bitmap, int nwords, int pm, int pb,
+                                                    const int32_t* __restrict__ part, int32_t* counts,
+                                                    int32_t* __restrict__ b_indptr, int32_t* __restrict__ src_nodes,
+                                                    const int32_t* __restrict__ dst_nodes, int32_t* map,
+                                                    int32_t* hist) {
+    const int n = dev_count(n_cap, n_d);
+    const bool is_m = (int)blockIdx.x < pm;
+    int nnz, n_new, before;
+    part_sums(part, pm, pb, is_m ? 0 : pm, blockIdx.x, &nnz, &n_new, &before);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
         counts[0] = n;
         counts[1] = n + n_new;
         counts[2] = nnz;
         counts[3] = 0;
         b_indptr[n] = nnz;
     }
-}
-
-// Pass 3: write b_indptr; emit the new frontier nodes (ascending id), extend the
-// node -> local-id map, clear the bitmap; zero the histogram of the transposed block.
-__global__ __launch_bounds__(TB) void k_front_apply(const int32_t* __restrict__ m, int n_cap, const int32_t* n_d,
-                                                    uint32_t* bitmap, int nwords, int pm,
-                                                    const int32_t* __restrict__ part, const int32_t* counts,
-                                                    int32_t* __restrict__ b_indptr, int32_t* __restrict__ src_nodes,
-                                                    const int32_t* __restrict__ dst_nodes, int32_t* map,
-                                                    int32_t* hist) {
-    const int n = dev_count(n_cap, n_d);
-    if ((int)blockIdx.x < pm) {
+    if (is_m) {
         const int base = blockIdx.x * TILE + threadIdx.x * ITEMS;
         int v[ITEMS], sum = 0;
 #pragma unroll
@@ -207,7 +224,7 @@ __global__ __launch_bounds__(TB) void k_front_apply(const int32_t* __restrict__ 
             sum += v[q];
         }
         int total;
-        int run = block_excl_scan(sum, &total) + part[blockIdx.x];
+        int run = block_excl_scan(sum, &total) + before;
 #pragma unroll
         for (int q = 0; q < ITEMS; ++q) {
             if (base + q < n) {
@@ -226,7 +243,7 @@ __global__ __launch_bounds__(TB) void k_front_apply(const int32_t* __restrict__ 
             sum += __popc(wd[q]);
         }
         int total;
-        int run = n + part[blockIdx.x] + block_excl_scan(sum, &total);
+        int run = n + before + block_excl_scan(sum, &total);
 #pragma unroll
         for (int q = 0; q < ITEMS; ++q) {
             uint32_t x = wd[q];
@@ -242,7 +259,7 @@ __global__ __launch_bounds__(TB) void k_front_apply(const int32_t* __restrict__ 
         }
     }
     if (hist) {
-        const int n_src = counts[1];
+        const int n_src = n + n_new;
         for (int j = blockIdx.x * TB + threadIdx.x; j <= n_src; j += gridDim.x * TB) hist[j] = 0;
     }
 }
@@ -264,7 +281,7 @@ __global__ __launch_bounds__(TB) void k_relabel(const int32_t* __restrict__ e_pa
     }
 }
 
-// ---- generic three-pass exclusive scan: out[0..n] from in[0..n), n = *n_d + n_add
+// ---- two-pass exclusive scan: out[0..n] from in[0..n), n = *n_d + n_add ---------
 __global__ __launch_bounds__(TB) void k_scan_partials(const int32_t* __restrict__ in, const int32_t* n_d, int n_add,
                                                       int32_t* part) {
     const int n = *n_d + n_add;
@@ -278,15 +295,14 @@ __global__ __launch_bounds__(TB) void k_scan_partials(const int32_t* __restrict_
     if (threadIdx.x == 0) part[blockIdx.x] = total;
 }
 
-__global__ __launch_bounds__(TB) void k_scan_spine(int32_t* part, int nparts, int32_t* long_count) {
-    spine_scan(part, nparts);
-    if (threadIdx.x == 0 && long_count) *long_count = 0;
-}
-
-// in-place capable: reads its tile fully before writing
+// in-place capable (reads its tile fully before writing); each block sums the partials before it
 __global__ __launch_bounds__(TB) void k_scan_apply(const int32_t* in, const int32_t* n_d, int n_add,
-                                                   const int32_t* __restrict__ part, int32_t* out, int32_t* zero_me) {
+                                                   const int32_t* __restrict__ part, int32_t* out, int32_t* zero_me,
+                                                   int32_t* long_count) {
     const int n = *n_d + n_add;
+    int t0, t1, before;
+    part_sums(part, gridDim.x, 0, 0, blockIdx.x, &t0, &t1, &before);
+    if (blockIdx.x == 0 && threadIdx.x == 0 && long_count) *long_count = 0;
     const int base = blockIdx.x * TILE + threadIdx.x * ITEMS;
     int v[ITEMS], sum = 0;
 #pragma unroll
@@ -295,7 +311,7 @@ __global__ __launch_bounds__(TB) void k_scan_apply(const int32_t* in, const int3
         sum += v[q];
     }
     int total;
-    int run = block_excl_scan(sum, &total) + part[blockIdx.x];
+    int run = block_excl_scan(sum, &total) + before;
 #pragma unroll
     for (int q = 0; q < ITEMS; ++q) {
         if (base + q < n) {
@@ -325,6 +341,65 @@ __global__ __launch_bounds__(TB) void k_transpose_fill(const int32_t* __restrict
     }
 }
 
+__device__ __forceinline__ void insertion_sort(int32_t* s, int len) {
+    for (int a = 1; a < len; ++a) {
+        const int x = s[a];
+        int q = a - 1;
+        while (q >= 0 && s[q] > x) {
+            s[q + 1] = s[q];
+            --q;
+        }
+        s[q + 1] = x;
+    }
+}
+
+// The whole block sorts t_rows[b, b+len) ascending; buf is >= LDS_SEG ints of LDS, tmp global scratch.
+template <int NT>
+__device__ void block_sort_segment(int32_t* t_rows, int b, int len, int32_t* buf, int32_t* tmp) {
+    if (len <= LDS_SEG) {
+        int p2 = 1;
+        while (p2 < len) p2 <<= 1;
+        for (int a = threadIdx.x; a < p2; a += NT) buf[a] = a < len ? t_rows[b + a] : 0x7FFFFFFF;
+        __syncthreads();
+        for (int k = 2; k <= p2; k <<= 1)
+            for (int s = k >> 1; s > 0; s >>= 1) {
+                for (int a = threadIdx.x; a < p2; a += NT) {
+                    const int o = a ^ s;
+                    if (o > a) {
+                        const int x = buf[a], y = buf[o];
+                        const bool up = (a & k) == 0;
+                        if ((x > y) == up) { buf[a] = y; buf[o] = x; }
+                    }
+                }
+                __syncthreads();
+            }
+        for (int a = threadIdx.x; a < len; a += NT) t_rows[b + a] = buf[a];
+        __syncthreads();
+    } else {
+        // longer than the LDS buffer: place each element at its rank (quadratic, rare)
+        for (int a = threadIdx.x; a < len; a += NT) tmp[b + a] = t_rows[b + a];
+        __syncthreads();
+        for (int a0 = 0; a0 < len; a0 += NT) {
+            const int a = a0 + threadIdx.x;
+            const int x = a < len ? tmp[b + a] : 0;
+            int rank = 0;
+            for (int c0 = 0; c0 < len; c0 += LDS_SEG) {
+                const int cl = min(LDS_SEG, len - c0);
+                __syncthreads();
+                for (int c = threadIdx.x; c < cl; c += NT) buf[c] = tmp[b + c0 + c];
+                __syncthreads();
+                if (a < len)
+                    for (int c = 0; c < cl; ++c) {
+                        const int y = buf[c];
+                        rank += (y < x || (y == x && c0 + c < a)) ? 1 : 0;
+                    }
+            }
+            if (a < len) t_rows[b + rank] = x;
+        }
+        __syncthreads();
+    }
+}
+
 // Each segment ascending: short ones by one thread, the rest queued for k_sort_long.
 __global__ __launch_bounds__(TB) void k_sort_short(const int32_t* __restrict__ t_indptr, const int32_t* counts,
                                                    int32_t* t_rows, int32_t* long_count, int32_t* long_list) {
@@ -336,16 +411,7 @@ __global__ __launch_bounds__(TB) void k_sort_short(const int32_t* __restrict__ t
             long_list[atomicAdd(long_count, 1)] = j;
             continue;
         }
-        int32_t* s = t_rows + b;
-        for (int a = 1; a < len; ++a) {
-            const int x = s[a];
-            int q = a - 1;
-            while (q >= 0 && s[q] > x) {
-                s[q + 1] = s[q];
-                --q;
-            }
-            s[q + 1] = x;
-        }
+        insertion_sort(t_rows + b, len);
     }
 }
 
@@ -356,49 +422,78 @@ __global__ __launch_bounds__(TB) void k_sort_long(const int32_t* __restrict__ t_
     const int cnt = *long_count;
     for (int li = blockIdx.x; li < cnt; li += gridDim.x) {
         const int j = long_list[li];
-        const int b = t_indptr[j], len = t_indptr[j + 1] - b;
-        if (len <= LDS_SEG) {
-            int p2 = 1;
-            while (p2 < len) p2 <<= 1;
-            for (int a = threadIdx.x; a < p2; a += TB) buf[a] = a < len ? t_rows[b + a] : 0x7FFFFFFF;
-            __syncthreads();
-            for (int k = 2; k <= p2; k <<= 1)
-                for (int s = k >> 1; s > 0; s >>= 1) {
-                    for (int a = threadIdx.x; a < p2; a += TB) {
-                        const int o = a ^ s;
-                        if (o > a) {
-                            const int x = buf[a], y = buf[o];
-                            const bool up = (a & k) == 0;
-                            if ((x > y) == up) { buf[a] = y; buf[o] = x; }
-                        }
-                    }
-                    __syncthreads();
-                }
-            for (int a = threadIdx.x; a < len; a += TB) t_rows[b + a] = buf[a];
-            __syncthreads();
-        } else {
-            // longer than the LDS buffer: place each element at its rank (quadratic, rare)
-            for (int a = threadIdx.x; a < len; a += TB) tmp[b + a] = t_rows[b + a];
-            __syncthreads();
-            for (int a0 = 0; a0 < len; a0 += TB) {
-                const int a = a0 + threadIdx.x;
-                const int x = a < len ? tmp[b + a] : 0;
-                int rank = 0;
-                for (int c0 = 0; c0 < len; c0 += LDS_SEG) {
-                    const int cl = min(LDS_SEG, len - c0);
-                    __syncthreads();
-                    for (int c = threadIdx.x; c < cl; c += TB) buf[c] = tmp[b + c0 + c];
-                    __syncthreads();
-                    if (a < len)
-                        for (int c = 0; c < cl; ++c) {
-                            const int y = buf[c];
-                            rank += (y < x || (y == x && c0 + c < a)) ? 1 : 0;
-                        }
-                }
-                if (a < len) t_rows[b + rank] = x;
-            }
-            __syncthreads();
+        const int b = t_indptr[j];
+        block_sort_segment<TB>(t_rows, b, t_indptr[j + 1] - b, buf, tmp);
+    }
+}
+
+// Transposed block of a small layer in ONE launch of one 1024-thread workgroup:
+// scan the per-source counts (left in t_indptr by k_relabel), fill, sort the segments.
+// Fill cursors live in LDS when the frontier fits (returning LDS atomics are ~10x faster
+// than device-scope ones and a thread issues up to `fanout` of them back to back).
+constexpr int TS = 1024;
+constexpr int TS_LDS = 12288;  // ints of LDS: fill cursors first, sort buffer afterwards
+__global__ __launch_bounds__(TS) void k_transpose_small(const int32_t* __restrict__ b_indptr,
+                                                        const int32_t* __restrict__ cols, const int32_t* counts,
+                                                        int fanout, int32_t* t_indptr, int32_t* cursor_g,
+                                                        int32_t* t_rows, int32_t* long_list, int32_t* tmp) {
+    __shared__ int32_t buf[TS_LDS];
+    __shared__ int n_long;
+    const int n_dst = counts[0], n_src = counts[1];
+    const bool lds_cur = n_src <= TS_LDS;
+    if (threadIdx.x == 0) n_long = 0;
+    spine_scan<TS>(t_indptr, n_src + 1, lds_cur ? nullptr : cursor_g);  // counts -> offsets in place
+    if (lds_cur)
+        for (int j = threadIdx.x; j < n_src; j += TS) buf[j] = 0;
+    __syncthreads();
+    const int total = n_dst * fanout;
+    for (int idx = threadIdx.x; idx < total; idx += TS) {
+        const int i = idx / fanout, t = idx - i * fanout;
+        const int b0 = b_indptr[i];
+        if (t < b_indptr[i + 1] - b0) {
+            const int c = cols[b0 + t];
+            const int slot = lds_cur ? atomicAdd(&buf[c], 1) : atomicAdd(&cursor_g[c], 1);
+            t_rows[t_indptr[c] + slot] = i;
         }
+    }
+    __syncthreads();
+    for (int j = threadIdx.x; j < n_src; j += TS) {
+        const int b = t_indptr[j], len = t_indptr[j + 1] - b;
+        if (len <= 1) continue;
+        if (len > SHORT_SEG) long_list[atomicAdd(&n_long, 1)] = j;
+        else insertion_sort(t_rows + b, len);
+    }
+    __syncthreads();
+    const int cnt = n_long;
+    for (int li = 0; li < cnt; ++li) {
+        const int j = long_list[li];
+        const int b = t_indptr[j];
+        block_sort_segment<TS>(t_rows, b, t_indptr[j + 1] - b, buf, tmp);
+    }
+}
+
+// ---- state that persists across the layers (and steps) of a training run ---------
+constexpr int32_t STATE_MAGIC = 0x53445431;  // "SDT1"
+
+// Fill the node map with -1 and clear the bitmap unless the header says a previous step
+// left them in that state already (every step restores them before it ends).
+__global__ __launch_bounds__(TB) void k_state_check_init(const int32_t* header, int32_t* map, int64_t n,
+                                                         uint32_t* bitmap, int64_t nwords) {
+    if (header && header[0] == STATE_MAGIC && header[1] == (int32_t)n) return;
+    const int64_t stride = (int64_t)gridDim.x * TB;
+    for (int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x; i < n; i += stride) map[i] = -1;
+    for (int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x; i < nwords; i += stride) bitmap[i] = 0u;
+}
+
+// map[dst[i]] = i; also stamps the header (after k_state_check_init has read it).
+__global__ __launch_bounds__(TB) void k_seed_map(int32_t* map, const int32_t* __restrict__ dst, int n_cap,
+                                                 const int32_t* n_d, int32_t* header, int32_t n_nodes) {
+    const int n = dev_count(n_cap, n_d);
+    for (int i = blockIdx.x * TB + threadIdx.x; i < n; i += gridDim.x * TB) map[dst[i]] = i;
+    if (header && blockIdx.x == 0 && threadIdx.x == 0) {
+        if (header[0] != STATE_MAGIC || header[1] != n_nodes) header[2] = 0;  // loss ticket
+        header[0] = STATE_MAGIC;
+        header[1] = n_nodes;
     }
 }
 
@@ -409,9 +504,21 @@ inline int grid_for(int64_t items, int per_block, int max_blocks) {
     return (int)g;
 }
 
+constexpr int SMALL_T_NNZ = 1 << 16;  // layers up to this many sampled edges use k_transpose_small
+
 }  // namespace
 
-size_t sample_ws_carve(Arena& a, int64_t n_nodes, int32_t cap_dst, int32_t fanout, SampleWs* out) {
+size_t sample_state_bytes(int64_t n_nodes) {
+    return align_up((size_t)n_nodes * 4, 256) + align_up((size_t)((n_nodes + 31) / 32) * 4, 256);
+}
+
+void sample_state_carve(void* base, int64_t n_nodes, SampleWs* out) {
+    Arena a(base);
+    out->map = a.take<int32_t>(n_nodes);
+    out->bitmap = a.take<uint32_t>((n_nodes + 31) / 32);
+}
+
+size_t sample_tmp_carve(Arena& a, int64_t n_nodes, int32_t cap_dst, int32_t fanout, SampleWs* out) {
     const int64_t nwords = (n_nodes + 31) / 32;
     const int64_t cap_nnz = (int64_t)cap_dst * fanout;
     int64_t cap_src = (int64_t)cap_dst + cap_nnz;
@@ -419,9 +526,7 @@ size_t sample_ws_carve(Arena& a, int64_t n_nodes, int32_t cap_dst, int32_t fanou
     if (cap_src < cap_dst) cap_src = cap_dst;
     const int64_t pm = (cap_dst + TILE - 1) / TILE, pb = (nwords + TILE - 1) / TILE;
     const int64_t pt = (cap_src + 1 + TILE - 1) / TILE;
-    SampleWs w;
-    w.map = a.take<int32_t>(n_nodes);
-    w.bitmap = a.take<uint32_t>(nwords);
+    SampleWs w = out ? *out : SampleWs{};
     w.e_pad = a.take<int32_t>(cap_nnz > 0 ? cap_nnz : 1);
     w.m = a.take<int32_t>(cap_dst > 0 ? cap_dst : 1);
     w.part = a.take<int32_t>((pm + pb > pt ? pm + pb : pt) + 1);
@@ -431,32 +536,33 @@ size_t sample_ws_carve(Arena& a, int64_t n_nodes, int32_t cap_dst, int32_t fanou
     return a.off;
 }
 
-int32_t sample_init_map(const SampleWs& ws, int64_t n_nodes, const int32_t* dst_nodes, int32_t n_dst_cap,
-                        const int32_t* n_dst_d, hipStream_t st) {
-    hipLaunchKernelGGL(k_fill_i32, dim3(grid_for(n_nodes, TB * 4, 4096)), dim3(TB), 0, st, ws.map, n_nodes, -1);
-    SDT_CHECK_LAUNCH("fill map");
-    hipLaunchKernelGGL(k_fill_i32, dim3(grid_for((n_nodes + 31) / 32, TB * 4, 2048)), dim3(TB), 0, st,
-                       reinterpret_cast<int32_t*>(ws.bitmap), (n_nodes + 31) / 32, 0);
-    SDT_CHECK_LAUNCH("fill bitmap");
-    hipLaunchKernelGGL(k_scatter_ids, dim3(grid_for(n_dst_cap, TB, 1024)), dim3(TB), 0, st, ws.map, dst_nodes,
-                       n_dst_cap, n_dst_d);
-    SDT_CHECK_LAUNCH("scatter ids");
+int32_t sample_state_init(const SampleWs& ws, int64_t n_nodes, const int32_t* header, hipStream_t st) {
+    hipLaunchKernelGGL(k_state_check_init, dim3(grid_for(n_nodes, TB * 4, 2048)), dim3(TB), 0, st, header, ws.map,
+                       n_nodes, ws.bitmap, (n_nodes + 31) / 32);
+    SDT_CHECK_LAUNCH("state init");
     return SDT_OK;
 }
 
+int32_t sample_seed_map(const SampleWs& ws, const int32_t* dst_nodes, int32_t n_dst_cap, const int32_t* n_dst_d,
+                        int32_t* header, int64_t n_nodes, hipStream_t st) {
+    hipLaunchKernelGGL(k_seed_map, dim3(grid_for(n_dst_cap, TB, 256)), dim3(TB), 0, st, ws.map, dst_nodes, n_dst_cap,
+                       n_dst_d, header, (int32_t)n_nodes);
+    SDT_CHECK_LAUNCH("seed map");
+    return SDT_OK;
+}
+
+// Expects ws.map to hold the destination nodes (and only frontier nodes) and ws.bitmap to be clear;
+// leaves the map extended by the new frontier nodes and the bitmap clear again.
 int32_t sample_layer(const sdt_csr& g, const int32_t* dst_nodes, int32_t n_dst_cap, const int32_t* n_dst_d,
                      int32_t fanout, uint64_t seed, uint32_t step, uint32_t layer, const sdt_block& out,
-                     const SampleWs& ws, bool map_ready, hipStream_t st) {
-    if (!map_ready) {
-        int32_t rc = sample_init_map(ws, g.n_nodes, dst_nodes, n_dst_cap, n_dst_d, st);
-        if (rc != SDT_OK) return rc;
-    }
+                     const SampleWs& ws, hipStream_t st) {
     const int nwords = (int)((g.n_nodes + 31) / 32);
     const int pm = ceil_div(n_dst_cap > 0 ? n_dst_cap : 1, TILE), pb = ceil_div(nwords, TILE);
     const bool want_t = out.t_indptr != nullptr;
     int32_t* hist = want_t ? out.t_indptr : nullptr;  // counted in place, then scanned in place
+    const bool any = n_dst_cap > 0 && fanout > 0;
 
-    if (n_dst_cap > 0 && fanout > 0) {
+    if (any) {
         hipLaunchKernelGGL(k_sample_rows, dim3(grid_for(n_dst_cap, TB / WAVE, 8192)), dim3(TB), 0, st, g.indptr,
                            g.indices, dst_nodes, n_dst_cap, n_dst_d, fanout, (uint32_t)seed,
                            (uint32_t)(seed >> 32), step, layer, ws.map, ws.bitmap, ws.e_pad, ws.m);
@@ -469,39 +575,36 @@ int32_t sample_layer(const sdt_csr& g, const int32_t* dst_nodes, int32_t n_dst_c
     hipLaunchKernelGGL(k_front_partials, dim3(pm + pb), dim3(TB), 0, st, ws.m, n_dst_cap, n_dst_d, ws.bitmap, nwords,
                        pm, ws.part);
     SDT_CHECK_LAUNCH("frontier partials");
-    hipLaunchKernelGGL(k_front_spine, dim3(1), dim3(TB), 0, st, ws.part, pm, pb, n_dst_cap, n_dst_d, out.counts,
-                       out.indptr);
-    SDT_CHECK_LAUNCH("frontier spine");
     hipLaunchKernelGGL(k_front_apply, dim3(pm + pb), dim3(TB), 0, st, ws.m, n_dst_cap, n_dst_d, ws.bitmap, nwords, pm,
-                       ws.part, out.counts, out.indptr, out.src_nodes, dst_nodes, ws.map, hist);
+                       pb, ws.part, out.counts, out.indptr, out.src_nodes, dst_nodes, ws.map, hist);
     SDT_CHECK_LAUNCH("frontier apply");
-    if (n_dst_cap > 0 && fanout > 0) {
-        hipLaunchKernelGGL(k_relabel, dim3(grid_for((int64_t)n_dst_cap * fanout, TB, 8192)), dim3(TB), 0, st,
+    if (any) {
+        hipLaunchKernelGGL(k_relabel, dim3(grid_for((int64_t)n_dst_cap * fanout, TB, 2048)), dim3(TB), 0, st,
                            ws.e_pad, ws.m, out.indptr, n_dst_cap, n_dst_d, fanout, ws.map, out.cols, hist);
         SDT_CHECK_LAUNCH("relabel");
     }
-    if (want_t) {
-        const int pt = ceil_div((int64_t)out.cap_src + 1, TILE);
-        hipLaunchKernelGGL(k_scan_partials, dim3(pt), dim3(TB), 0, st, hist, out.counts + 1, 1, ws.part);
-        SDT_CHECK_LAUNCH("transpose partials");
-        hipLaunchKernelGGL(k_scan_spine, dim3(1), dim3(TB), 0, st, ws.part, pt, ws.longlist);
-        SDT_CHECK_LAUNCH("transpose spine");
-        hipLaunchKernelGGL(k_scan_apply, dim3(pt), dim3(TB), 0, st, hist, out.counts + 1, 1, ws.part, out.t_indptr,
-                           ws.cursor);
-        SDT_CHECK_LAUNCH("transpose apply");
-        if (n_dst_cap > 0 && fanout > 0) {
-            hipLaunchKernelGGL(k_transpose_fill, dim3(grid_for((int64_t)n_dst_cap * fanout, TB, 8192)), dim3(TB), 0,
-                               st, out.indptr, out.cols, n_dst_cap, n_dst_d, fanout, out.t_indptr, ws.cursor,
-                               out.t_rows);
-            SDT_CHECK_LAUNCH("transpose fill");
-            hipLaunchKernelGGL(k_sort_short, dim3(grid_for(out.cap_src, TB, 4096)), dim3(TB), 0, st, out.t_indptr,
-                               out.counts, out.t_rows, ws.longlist, ws.longlist + 1);
-            SDT_CHECK_LAUNCH("sort short");
-            hipLaunchKernelGGL(k_sort_long, dim3(64), dim3(TB), 0, st, out.t_indptr, out.t_rows, ws.longlist,
-                               ws.longlist + 1, ws.e_pad);
-            SDT_CHECK_LAUNCH("sort long");
-        }
+    if (!want_t) return SDT_OK;
+    if ((int64_t)n_dst_cap * fanout <= SMALL_T_NNZ) {
+        hipLaunchKernelGGL(k_transpose_small, dim3(1), dim3(TS), 0, st, out.indptr, out.cols, out.counts, fanout,
+                           out.t_indptr, ws.cursor, out.t_rows, ws.longlist, ws.e_pad);
+        SDT_CHECK_LAUNCH("transpose small");
+        return SDT_OK;
     }
+    const int pt = ceil_div((int64_t)out.cap_src + 1, TILE);
+    hipLaunchKernelGGL(k_scan_partials, dim3(pt), dim3(TB), 0, st, hist, out.counts + 1, 1, ws.part);
+    SDT_CHECK_LAUNCH("transpose partials");
+    hipLaunchKernelGGL(k_scan_apply, dim3(pt), dim3(TB), 0, st, hist, out.counts + 1, 1, ws.part, out.t_indptr,
+                       ws.cursor, ws.longlist);
+    SDT_CHECK_LAUNCH("transpose apply");
+    hipLaunchKernelGGL(k_transpose_fill, dim3(grid_for((int64_t)n_dst_cap * fanout, TB, 2048)), dim3(TB), 0, st,
+                       out.indptr, out.cols, n_dst_cap, n_dst_d, fanout, out.t_indptr, ws.cursor, out.t_rows);
+    SDT_CHECK_LAUNCH("transpose fill");
+    hipLaunchKernelGGL(k_sort_short, dim3(grid_for(out.cap_src, TB, 2048)), dim3(TB), 0, st, out.t_indptr, out.counts,
+                       out.t_rows, ws.longlist, ws.longlist + 1);
+    SDT_CHECK_LAUNCH("sort short");
+    hipLaunchKernelGGL(k_sort_long, dim3(64), dim3(TB), 0, st, out.t_indptr, out.t_rows, ws.longlist, ws.longlist + 1,
+                       ws.e_pad);
+    SDT_CHECK_LAUNCH("sort long");
     return SDT_OK;
 }
 
@@ -510,7 +613,7 @@ int32_t sample_layer(const sdt_csr& g, const int32_t* dst_nodes, int32_t n_dst_c
 extern "C" size_t sdt_sample_workspace_bytes(int64_t n_nodes, int32_t cap_dst, int32_t fanout) {
     if (n_nodes < 0 || cap_dst < 0 || fanout < 0) return 0;
     sdt::Arena a(nullptr);
-    return sdt::sample_ws_carve(a, n_nodes, cap_dst, fanout, nullptr);
+    return sdt::sample_state_bytes(n_nodes) + sdt::sample_tmp_carve(a, n_nodes, cap_dst, fanout, nullptr);
 }
 
 extern "C" int32_t sdt_sample_csr(const sdt_csr* graph, const int32_t* dst_nodes, int32_t n_dst_cap,
@@ -542,12 +645,17 @@ extern "C" int32_t sdt_sample_csr(const sdt_csr* graph, const int32_t* dst_nodes
     const size_t need = sdt_sample_workspace_bytes(graph->n_nodes, n_dst_cap, fanout);
     SDT_REQUIRE(ws && ws_bytes >= need && aligned16(ws), SDT_ERR_WORKSPACE,
                 "sdt_sample_csr: workspace of %zu bytes needed, %zu given", need, ws_bytes);
-    Arena a(ws);
-    SampleWs sw;
-    sample_ws_carve(a, graph->n_nodes, n_dst_cap, fanout, &sw);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    SampleWs sw{};
+    sample_state_carve(ws, graph->n_nodes, &sw);
+    Arena a(static_cast<char*>(ws) + sample_state_bytes(graph->n_nodes));
+    sample_tmp_carve(a, graph->n_nodes, n_dst_cap, fanout, &sw);
+    int32_t rc = sample_state_init(sw, graph->n_nodes, nullptr, st);  // unconditional: ws contents are arbitrary
+    if (rc != SDT_OK) return rc;
+    rc = sample_seed_map(sw, dst_nodes, n_dst_cap, n_dst_d, nullptr, graph->n_nodes, st);
+    if (rc != SDT_OK) return rc;
     // The transposed scan sizes its grid from the capacity the workspace was carved for.
     sdt_block blk = *out;
     blk.cap_src = (int32_t)need_src;
-    return sample_layer(*graph, dst_nodes, n_dst_cap, n_dst_d, fanout, seed, step, layer, blk, sw, false,
-                        static_cast<hipStream_t>(stream));
+    return sample_layer(*graph, dst_nodes, n_dst_cap, n_dst_d, fanout, seed, step, layer, blk, sw, st);
 }

@@ -139,6 +139,8 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
     lay->n_layers = L;
     Arena a(nullptr);
     size_t scratch = 0;
+    lay->header = a.take_off(64 * sizeof(int32_t));
+    lay->state = a.take_off(sample_state_bytes(n_nodes));
     for (int l = 0; l < L; ++l) {
         lay->cap_dst[l] = c.dst[l];
         lay->cap_src[l] = c.src[l];
@@ -159,7 +161,7 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
         lay->dW[l] = a.take_off((size_t)2 * d[l] * d[l + 1] * 4);
         lay->db[l] = a.take_off((size_t)d[l + 1] * 4);
         Arena s(nullptr);
-        size_t sb = sample_ws_carve(s, n_nodes, c.dst[l], fanouts[l], nullptr);
+        size_t sb = sample_tmp_carve(s, n_nodes, c.dst[l], fanouts[l], nullptr);
         size_t lb = sdt_linear_bwd_workspace_bytes(c.dst[l], d[l], d[l + 1]);
         if (sb > scratch) scratch = sb;
         if (lb > scratch) scratch = lb;
@@ -211,26 +213,36 @@ extern "C" int32_t sdt_train_step(const sdt_csr* graph, const void* X, int64_t l
 
     if (timing) timing->slot = timing->used < timing->max_steps ? timing->used++ : -1;
 
-    // ---- sample from the seeds outwards; the node -> local-id map carries over
-    const int32_t* dst = seeds;
-    const int32_t* n_d = nullptr;
-    for (int l = L - 1; l >= 0; --l) {
-        StageTimer tm(timing, SDT_STAGE_SAMPLE, l, st);
-        Arena a(at(lay.scratch));
-        SampleWs sw;
-        sample_ws_carve(a, graph->n_nodes, lay.cap_dst[l], fanouts[l], &sw);
-        rc = sample_layer(*graph, dst, lay.cap_dst[l], n_d, fanouts[l], seed, step, (uint32_t)l, blk[l], sw, l != L - 1,
-                          st);
-        if (rc != SDT_OK) return rc;
-        dst = blk[l].src_nodes;
-        n_d = blk[l].counts + 1;
+    // ---- sample from the seeds outwards; the node -> local-id map carries over from layer
+    // to layer, and from step to step it is handed back clean (see the gather below)
+    int32_t* header = static_cast<int32_t*>(at(lay.header));
+    SampleWs sw{};
+    sample_state_carve(at(lay.state), graph->n_nodes, &sw);
+    {
+        const int32_t* dst = seeds;
+        const int32_t* n_d = nullptr;
+        for (int l = L - 1; l >= 0; --l) {
+            StageTimer tl(timing, SDT_STAGE_SAMPLE, l, st);
+            if (l == L - 1) {
+                rc = sample_state_init(sw, graph->n_nodes, header, st);
+                if (rc != SDT_OK) return rc;
+                rc = sample_seed_map(sw, seeds, batch, nullptr, header, graph->n_nodes, st);
+                if (rc != SDT_OK) return rc;
+            }
+            Arena a(at(lay.scratch));
+            sample_tmp_carve(a, graph->n_nodes, lay.cap_dst[l], fanouts[l], &sw);
+            rc = sample_layer(*graph, dst, lay.cap_dst[l], n_d, fanouts[l], seed, step, (uint32_t)l, blk[l], sw, st);
+            if (rc != SDT_OK) return rc;
+            dst = blk[l].src_nodes;
+            n_d = blk[l].counts + 1;
+        }
     }
 
     // ---- gather the input features of the outermost frontier
     {
         StageTimer tm(timing, SDT_STAGE_GATHER, 0, st);
-        rc = sdt_gather_features(X, ldx, d[0], dtype, blk[0].src_nodes, lay.cap_src[0], blk[0].counts + 1,
-                                 at(lay.H[0]), d[0], st);
+        rc = gather_rows(X, ldx, d[0], dtype, blk[0].src_nodes, lay.cap_src[0], blk[0].counts + 1, at(lay.H[0]), d[0],
+                         sw.map, st);
     }
     if (rc != SDT_OK) return rc;
 
@@ -253,7 +265,7 @@ extern "C" int32_t sdt_train_step(const sdt_csr* graph, const void* X, int64_t l
     {
         StageTimer tm(timing, SDT_STAGE_LOSS, 0, st);
         rc = softmax_xent(static_cast<const float*>(at(lay.H[L])), d[L], batch, d[L], labels, seeds,
-                          static_cast<float*>(at(lay.dZ)), static_cast<float*>(at(lay.row_loss)), loss_d, st);
+                          static_cast<float*>(at(lay.dZ)), static_cast<float*>(at(lay.row_loss)), st);
     }
     if (rc != SDT_OK) return rc;
 
@@ -268,10 +280,21 @@ extern "C" int32_t sdt_train_step(const sdt_csr* graph, const void* X, int64_t l
         const bool inner = l > 0;
         {
         StageTimer tm(timing, SDT_STAGE_LINEAR_BWD, l, st);
-        rc = sdt_sage_linear_bwd(dY, d[l + 1], dy_dtype, nullptr, 0, 0, at(lay.H[l]), d[l], at(lay.A[l]), d[l],
-                                 lay.cap_dst[l], blk[l].counts, d[l], d[l + 1], model->W[l], dtype, dW[l], db[l],
-                                 inner ? at(lay.dSelf[l]) : nullptr, inner ? at(lay.dAgg[l]) : nullptr, d[l],
-                                 at(lay.scratch), ws_bytes - lay.scratch, st);
+        // the SGD step of this layer (and, for the last layer, the mean of the per-seed
+        // losses) ride on the final reduction of its weight gradient
+        BwdExtras ex;
+        ex.W_upd = model->W[l];
+        ex.b_upd = model->b[l];
+        ex.lr = lr;
+        if (l == L - 1) {
+            ex.row_loss = static_cast<const float*>(at(lay.row_loss));
+            ex.n_loss = batch;
+            ex.loss_out = loss_d;
+        }
+        rc = linear_bwd(dY, d[l + 1], dy_dtype, nullptr, 0, 0, at(lay.H[l]), d[l], at(lay.A[l]), d[l], lay.cap_dst[l],
+                        blk[l].counts, d[l], d[l + 1], model->W[l], dtype, dW[l], db[l],
+                        inner ? at(lay.dSelf[l]) : nullptr, inner ? at(lay.dAgg[l]) : nullptr, d[l], at(lay.scratch),
+                        ws_bytes - lay.scratch, ex, st);
         }
         if (rc != SDT_OK) return rc;
         if (inner) {
@@ -285,7 +308,5 @@ extern "C" int32_t sdt_train_step(const sdt_csr* graph, const void* X, int64_t l
         }
     }
 
-    // ---- plain SGD on the fp32 weights
-    StageTimer tm(timing, SDT_STAGE_UPDATE, 0, st);
-    return sgd_update(*model, dW, db, lr, st);
+    return SDT_OK;
 }

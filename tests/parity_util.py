@@ -146,5 +146,8 @@ def check_step_against_oracle(run: StepRunner, ref: dict, tol: float, floats: bo
         if l >= 1:
             assert_close(run.grad("dSelf", l, blocks[l].n_dst), ref["dSelf"][l], tol, f"dSelf[{l}]")
             assert_close(run.grad("dAgg", l, blocks[l].n_dst), ref["dAgg"][l], tol, f"dAgg[{l}]")
-            masked = ref["dH"][l] * (ref["H"][l] > 0)
+            # the ReLU decisions the oracle's backward used (reconciled ones if present)
+            masks = ref.get("relu_masks")
+            keep = masks[l - 1] if masks is not None and masks[l - 1] is not None else ref["H"][l] > 0
+            masked = ref["dH"][l] * keep
             assert_close(run.grad("dH", l, blocks[l].n_src), masked, tol, f"dH[{l}] (ReLU-masked)")

@@ -241,11 +241,12 @@ def test_linear_device_row_count():
 
 
 # ----------------------------------------------------------------- whole step
-def _reconcile_relu(run, ref, tol_zero=1e-5):
+def _reconcile_relu(run, ref, tol_zero):
     """Where a hidden pre-activation is within rounding of zero the two sides may
     take different ReLU decisions; both are valid.  Returns the masks the GPU
     used when they differ from the oracle's, after checking that every
-    difference is such a borderline element."""
+    difference is such a borderline element (within the float tolerance of the
+    storage dtype, relative to the largest activation)."""
     masks, changed = [], False
     for l in range(run.L - 1):
         h_ref = ref["H"][l + 1]
@@ -272,9 +273,10 @@ def _run_and_check(inst, wl, steps, lr=0.01, check_float_steps=(0,)):
             # teacher-forced: the oracle starts from the weights the GPU had
             ref = orc.train_step(inst.indptr, inst.indices, inst.X, inst.y, seeds, wl.fanouts, W_before, b_before,
                                  wl.seed, step, lr, bf16=wl.bf16)
-            masks = _reconcile_relu(run, ref)
+            masks = _reconcile_relu(run, ref, tol)
             if masks is not None:
                 ref.update(orc.backward(ref["blocks"], ref["H"], ref["A"], ref["W"], ref["dZ"], wl.bf16, masks))
+                ref["relu_masks"] = masks
                 ref["W_new"] = [orc.sgd(ref["W"][l], ref["dW"][l], lr) for l in range(run.L)]
             assert abs(loss - ref["loss"]) <= tol * max(1.0, abs(ref["loss"])), (loss, ref["loss"])
             check_step_against_oracle(run, ref, tol)
@@ -310,6 +312,11 @@ def test_train_step_lr_zero_keeps_weights_and_is_repeatable():
     for off, nbytes in [(lay.dW[0], 2 * 64 * 64 * 4), (lay.dW[1], 2 * 64 * 8 * 4), (lay.H[2], 256 * 8 * 4)]:
         assert torch.equal(snap[off:off + nbytes], run.ws[off:off + nbytes])
     assert 0.5 * np.log(8) < l0 < 2 * np.log(8)                    # random init: the order of ln C
+    # every step hands the node map and the frontier bitmap back clean
+    n = wl.n_nodes
+    node_map = B.ws_view(run.ws, lay.state, (n,), torch.int32)
+    bitmap = B.ws_view(run.ws, lay.state + (n * 4 + 255) // 256 * 256, (n // 32,), torch.int32)
+    assert bool((node_map == -1).all()) and not bool(bitmap.any())
 
 
 def test_train_step_three_layers_bf16_small():

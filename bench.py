@@ -32,9 +32,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="products", choices=["tiny", "products", "dense", "sparse_bf16"])
+    ap.add_argument("--workload", default="products",
+                    choices=["tiny", "products", "dense", "sparse_bf16", "fullgraph"])
     ap.add_argument("--lr", type=float, default=0.01)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--serial", action="store_true", help="no auxiliary stream: every step strictly in sequence")
     ap.add_argument("--cpu-steps", type=int, default=2, help="oracle steps timed for cpu_baseline")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -50,6 +52,8 @@ def main():
     torch.cuda.set_device(0)
     wl = gen.WORKLOADS[args.workload]
     K, Wm = args.steps, args.warmup
+    if args.workload == "fullgraph":
+        return bench_fullgraph(args, wl)
 
     t0 = time.time()
     inst = gen.make_instance(wl)
@@ -69,11 +73,20 @@ def main():
     model = sdt.make_model(wl.dims, W, b)
     code = sdt.SDT_BF16 if wl.bf16 else sdt.SDT_F32
     lay = sdt.sdt_train_step_layout(graph.n_nodes, wl.batch, wl.fanouts, model, code)
-    ws = torch.empty(int(lay.total_bytes), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(sdt.sdt_train_loop_workspace_bytes(graph.n_nodes, wl.batch, wl.fanouts, model, code),
+                     dtype=torch.uint8, device="cuda")
     loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    losses = torch.zeros(Wm + K, dtype=torch.float32, device="cuda")
     seeds_all = torch.from_numpy(np.stack([inst.batch(s) for s in range(Wm + K)])).cuda()
+    aux = None if args.serial else torch.cuda.Stream()
     L = len(wl.fanouts)
     es = 2 if wl.bf16 else 4
+
+    def run_loop(first, count, timing=None):
+        # one native call enqueues `count` whole steps; the sampling phase of a step runs on the
+        # auxiliary stream, ahead of the forward/backward phase of the previous one
+        sdt.sdt_train_loop(graph, X, y, seeds_all[first:first + count], wl.fanouts, model, wl.seed, first, args.lr,
+                           losses[first:first + count], ws, aux, timing)
 
     def run(first, count, timing=None, per_step=None):
         for i in range(first, first + count):
@@ -84,17 +97,17 @@ def main():
     # ---- warm-up, then the timed region: exactly K steps between two synchronisations.
     # Only the dominant kernel is bracketed by HIP events inside the timed region.
     dominant = ("aggregate_fwd", 0)
-    run(0, Wm)
+    run_loop(0, Wm)
     tim = sdt.Timing(K, [dominant])
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run(Wm, K, tim)
+    run_loop(Wm, K, tim)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     elapsed = t1 - t0
     dom_ms = tim.read(*dominant)
     tim.close()
-    final_loss = float(loss.item())
+    final_loss = float(losses[-1].item())
 
     # ---- diagnostic pass (untimed): same batches again, every stage bracketed, sizes read back.
     stages = [("sample", l) for l in range(L)] + [("gather", 0)] + [("aggregate_fwd", l) for l in range(L)] + \
@@ -161,9 +174,84 @@ def main():
         "sampled_edges_per_s": round(edges_per_step * K / elapsed, 1),
         "sampled_edges_per_step": round(edges_per_step, 1),
         "frontier_rows_per_step": round(float(n_src0), 1),
-        "final_loss": round(final_loss, 6),
+        "final_loss": round(final_loss, 6), "overlap": "serial" if args.serial else "sampling of step i+1 on an auxiliary stream",
         "roofline": roofline, "cpu_baseline": cpu,
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()}, "stage_rates": others,
+    }
+    print(json.dumps(out), flush=True)
+
+
+def bench_fullgraph(args, wl):
+    """One full-neighbour GraphSAGE-mean layer over every node of the graph (layer-wise
+    inference): segmented-mean SpMM over the whole CSR, then the [x | mean] projection."""
+    import numpy as np
+    import torch
+    import sdt_gen as gen
+    import paper_2404_02300_amd as sdt
+
+    K, Wm = min(args.steps, 20), min(args.warmup, 3)
+    t0 = time.time()
+    indptr, indices = gen.make_graph(wl)
+    Xh = gen.normal_features(wl.n_nodes, wl.feat, wl.seed)
+    Wh, bh = gen.glorot_sage_weights(wl.dims, wl.seed)
+    N, F, O, nnz = wl.n_nodes, wl.dims[0], wl.dims[1], int(indptr[-1])
+    log(f"[bench] generated {wl.name}: N={N} nnz={nnz} in {time.time() - t0:.1f}s")
+    g = sdt.Csr(torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda())
+    X = torch.from_numpy(Xh).cuda()
+    W, b = torch.from_numpy(Wh[0]).cuda(), torch.from_numpy(bh[0]).cuda()
+    A = torch.empty(N, F, dtype=torch.float32, device="cuda")
+    Y = torch.empty(N, O, dtype=torch.float32, device="cuda")
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+    for _ in range(Wm):
+        sdt.sdt_sage_aggregate_csr_fwd(g, X, A)
+        sdt.sdt_sage_linear_fwd(X, A, W, b, True, Y)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):          # events sit on torch's current stream, the one the kernels are launched on
+        ev[i][0].record()
+        sdt.sdt_sage_aggregate_csr_fwd(g, X, A)
+        ev[i][1].record()
+        sdt.sdt_sage_linear_fwd(X, A, W, b, True, Y)
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    agg_s = float(np.mean([e[0].elapsed_time(e[1]) for e in ev])) * 1e-3
+    gemm_s = float(np.mean([e[1].elapsed_time(e[2]) for e in ev])) * 1e-3
+    agg_bytes = nnz * (F * 4 + 4) + N * (F * 4 + 8)          # every neighbour row read once per edge
+    compulsory = 2 * N * F * 4 + nnz * 4 + N * 8            # each row read once, A written once
+    flops = 2.0 * N * (2 * F) * O
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import sdt_oracle as orc
+        rows = np.random.default_rng(wl.seed).choice(N, size=1 << 13, replace=False)
+        deg = np.diff(indptr)
+        sub_ip = np.zeros(len(rows) + 1, dtype=np.int64)
+        sub_ip[1:] = np.cumsum(deg[rows])
+        sub_cols = np.concatenate([indices[indptr[r]:indptr[r + 1]] for r in rows]).astype(np.int32)
+        X64 = Xh.astype(np.float64)
+        tc = time.perf_counter()
+        refA = orc.aggregate_fwd(sub_ip, sub_cols, X64)
+        orc.linear_fwd(X64[rows], refA, Wh[0], bh[0], relu=True)
+        tc = time.perf_counter() - tc
+        cpu = {"value": round(len(rows) / tc, 1), "unit": "nodes/s", "cores": 1, "kind": "oracle",
+               "sample": f"{len(rows)} seeded random rows of the same layer (SpMM + projection), rows are independent",
+               "host_cpus": os.cpu_count()}
+    out = {
+        "metric": "full-neighbour GraphSAGE-mean layer, nodes/s (SpMM over the whole CSR + projection)",
+        "value": round(N * K / elapsed, 1), "unit": "nodes/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": round(elapsed / K * 1e3, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: rmat 2^{wl.log2n} nodes, {nnz} CSR entries, F={F} -> {O}, one layer, "
+                               f"no sampling", "seed": wl.seed},
+        "roofline": {"kernel": "k_aggregate_fwd<float,4,64,long> (whole CSR)", "bound": "hbm",
+                     "achieved": round(agg_bytes / agg_s / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(agg_bytes / agg_s / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": int(agg_bytes), "compulsory_bytes_per_launch": int(compulsory),
+                     "compulsory_GBps": round(compulsory / agg_s / 1e9, 1), "avg_launch_us": round(agg_s * 1e6, 1)},
+        "gemm": {"kernel": "k_linear_fwd<float,float,128,128>", "bound": "mfma", "TFLOPs": round(flops / gemm_s / 1e12, 2),
+                 "peak": MFMA_FP32_PEAK_TFLOPS, "frac": round(flops / gemm_s / 1e12 / MFMA_FP32_PEAK_TFLOPS, 4),
+                 "flops_per_launch": flops, "avg_launch_us": round(gemm_s * 1e6, 1)},
+        "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
 

@@ -250,6 +250,29 @@ int32_t sdt_train_step(const sdt_csr *graph /*host struct*/, const void *X, int6
                        uint32_t step, float lr, float *loss_d, sdt_timing *timing /*host, nullable*/, void *ws,
                        size_t ws_bytes, void *stream);
 
+/* ---- a run of consecutive steps with sampling overlapped --------------------
+ * Same result, bit for bit, as n_steps calls of sdt_train_step with step =
+ * first_step + i, seeds + i*batch and loss_d = losses_d + i -- but the phase of
+ * a step that needs no weights (sampling, frontier, gather) is enqueued on
+ * `aux_stream` and runs up to two steps ahead of the forward/backward phase on
+ * `stream`, double-buffered through two step workspaces (Sec. II-A: the
+ * mini-batch sub-graphs are independent of the model; Sec. III-D: a worker
+ * trains many mini-batches between two synchronisations).  Ordering between
+ * the two streams uses HIP events created and released inside the call.  When
+ * the call returns everything is enqueued; synchronising `stream` is enough.
+ * seeds is device int32[n_steps, batch]; losses_d device fp32[n_steps].  The
+ * workspace (sdt_train_loop_workspace_bytes: two step workspaces, each with
+ * sdt_train_step's layout, the second starting at half the size) carries
+ * state like sdt_train_step's.  aux_stream == stream gives the serial order.
+ * Both streams must have the default priority. */
+size_t sdt_train_loop_workspace_bytes(int64_t n_nodes, int32_t batch, const int32_t *fanouts /*host*/,
+                                      const sdt_model *model /*host struct*/, int32_t dtype);
+int32_t sdt_train_loop(const sdt_csr *graph /*host struct*/, const void *X, int64_t ldx, int32_t dtype,
+                       const int32_t *labels, const int32_t *seeds, int32_t batch, int32_t n_steps,
+                       const int32_t *fanouts /*host*/, const sdt_model *model /*host struct*/, uint64_t seed,
+                       uint32_t first_step, float lr, float *losses_d, sdt_timing *timing /*host, nullable*/,
+                       void *ws, size_t ws_bytes, void *stream, void *aux_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -76,6 +76,9 @@ EXPORTS = {
     "sdt_train_step_layout": (_i32, [_i64, _i32, _vp, _vp, _i32, _vp]),
     "sdt_train_step": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp, _i32, _vp, _vp, _u64, _u32, ctypes.c_float, _vp, _vp,
                               _vp, _sz, _vp]),
+    "sdt_train_loop_workspace_bytes": (_sz, [_i64, _i32, _vp, _vp, _i32]),
+    "sdt_train_loop": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp, _i32, _i32, _vp, _vp, _u64, _u32, ctypes.c_float, _vp,
+                              _vp, _vp, _sz, _vp, _vp]),
     "sdt_timing_create": (_i32, [_i32, _u64, _vp]),
     "sdt_timing_destroy": (None, [_vp]),
     "sdt_timing_reset": (None, [_vp]),
@@ -273,6 +276,26 @@ def sdt_train_step(graph: Csr, X: torch.Tensor, labels: torch.Tensor, seeds: tor
                                 _ptr(seeds), seeds.numel(), f, ctypes.byref(model), seed, step, lr, _ptr(loss),
                                 timing.handle if timing is not None else None,
                                 _ptr(ws), ws.numel() * ws.element_size(), _stream()))
+
+
+def sdt_train_loop_workspace_bytes(n_nodes: int, batch: int, fanouts: Sequence[int], model: sdt_model,
+                                   dtype: int) -> int:
+    f = (_i32 * len(fanouts))(*fanouts)
+    return lib().sdt_train_loop_workspace_bytes(n_nodes, batch, f, ctypes.byref(model), dtype)
+
+
+def sdt_train_loop(graph: Csr, X: torch.Tensor, labels: torch.Tensor, seeds: torch.Tensor, fanouts: Sequence[int],
+                   model: sdt_model, seed: int, first_step: int, lr: float, losses: torch.Tensor, ws: torch.Tensor,
+                   aux_stream: Optional[torch.cuda.Stream] = None, timing: Optional["Timing"] = None):
+    """seeds: int32 [n_steps, batch] on the device; losses: fp32 [n_steps]."""
+    assert seeds.dim() == 2 and seeds.is_contiguous() and losses.numel() >= seeds.shape[0]
+    f = (_i32 * len(fanouts))(*fanouts)
+    main = _stream()
+    aux = ctypes.c_void_p(aux_stream.cuda_stream) if aux_stream is not None else main
+    _check(lib().sdt_train_loop(ctypes.byref(graph.c), _ptr(X), X.stride(0), dtype_code(X), _ptr(labels),
+                                _ptr(seeds), seeds.shape[1], seeds.shape[0], f, ctypes.byref(model), seed,
+                                first_step, lr, _ptr(losses), timing.handle if timing is not None else None,
+                                _ptr(ws), ws.numel() * ws.element_size(), main, aux))
 
 
 def sdt_timing_create(max_steps: int, stage_mask: int) -> ctypes.c_void_p:

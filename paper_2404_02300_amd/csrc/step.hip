@@ -174,139 +174,253 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
     return SDT_OK;
 }
 
+namespace {
+
+// Everything one step needs, resolved once per call.
+struct StepCtx {
+    const sdt_csr* graph;
+    const void* X;
+    int64_t ldx;
+    int32_t dtype;
+    const int32_t* labels;
+    int32_t batch;
+    const int32_t* fanouts;
+    const sdt_model* model;
+    uint64_t seed;
+    float lr;
+    sdt_timing* timing;
+    sdt_step_layout lay;
+};
+
+struct StepBuffers {
+    char* base;
+    size_t bytes;
+    sdt_block blk[SDT_MAX_LAYERS];
+    void* at(uint64_t off) const { return base + off; }
+};
+
+int32_t check_step_args(const char* who, const sdt_csr* graph, const void* X, int64_t ldx, const int32_t* labels,
+                        const int32_t* seeds, int32_t batch, const sdt_model* model, const float* loss_d) {
+    SDT_REQUIRE(batch > 0, SDT_ERR_INVALID_ARG, "%s: empty batch", who);
+    SDT_REQUIRE(X && labels && seeds && loss_d && ldx >= model->dims[0], SDT_ERR_INVALID_ARG,
+                "%s: null input or ldx < dims[0]", who);
+    SDT_REQUIRE(graph->indices || graph->n_nodes == 0, SDT_ERR_INVALID_ARG, "%s: null indices", who);
+    for (int l = 0; l < model->n_layers; ++l)
+        SDT_REQUIRE(model->W[l] && model->b[l], SDT_ERR_INVALID_ARG, "%s: null weights of layer %d", who, l);
+    return SDT_OK;
+}
+
+void bind_buffers(const sdt_step_layout& lay, void* ws, size_t bytes, StepBuffers* b) {
+    b->base = static_cast<char*>(ws);
+    b->bytes = bytes;
+    for (int l = 0; l < lay.n_layers; ++l) {
+        sdt_block& k = b->blk[l];
+        k.cap_dst = lay.cap_dst[l];
+        k.cap_src = lay.cap_src[l];
+        k.cap_nnz = lay.cap_nnz[l];
+        k.reserved = 0;
+        k.counts = static_cast<int32_t*>(b->at(lay.counts[l]));
+        k.indptr = static_cast<int32_t*>(b->at(lay.indptr[l]));
+        k.cols = static_cast<int32_t*>(b->at(lay.cols[l]));
+        k.src_nodes = static_cast<int32_t*>(b->at(lay.src_nodes[l]));
+        k.t_indptr = l >= 1 ? static_cast<int32_t*>(b->at(lay.t_indptr[l])) : nullptr;
+        k.t_rows = l >= 1 ? static_cast<int32_t*>(b->at(lay.t_rows[l])) : nullptr;
+    }
+}
+
+// Phase 1 (needs no weights): sample from the seeds outwards, then gather the input features
+// of the outermost frontier.  The node -> local-id map carries over from layer to layer; the
+// gather hands it back clean for the next step that uses this workspace.
+int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds, uint32_t step, hipStream_t st) {
+    const sdt_step_layout& lay = c.lay;
+    const int L = c.model->n_layers;
+    const int32_t* d = c.model->dims;
+    const int64_t N = c.graph->n_nodes;
+    int32_t* header = static_cast<int32_t*>(b.at(lay.header));
+    SampleWs sw{};
+    sample_state_carve(b.at(lay.state), N, &sw);
+    int32_t rc;
+    const int32_t* dst = seeds;
+    const int32_t* n_d = nullptr;
+    for (int l = L - 1; l >= 0; --l) {
+        StageTimer tl(c.timing, SDT_STAGE_SAMPLE, l, st);
+        if (l == L - 1) {
+            rc = sample_state_init(sw, N, header, st);
+            if (rc != SDT_OK) return rc;
+            rc = sample_seed_map(sw, seeds, c.batch, nullptr, header, N, st);
+            if (rc != SDT_OK) return rc;
+        }
+        Arena a(b.at(lay.scratch));
+        sample_tmp_carve(a, N, lay.cap_dst[l], c.fanouts[l], &sw);
+        rc = sample_layer(*c.graph, dst, lay.cap_dst[l], n_d, c.fanouts[l], c.seed, step, (uint32_t)l, b.blk[l], sw, st);
+        if (rc != SDT_OK) return rc;
+        dst = b.blk[l].src_nodes;
+        n_d = b.blk[l].counts + 1;
+    }
+    StageTimer tm(c.timing, SDT_STAGE_GATHER, 0, st);
+    return gather_rows(c.X, c.ldx, d[0], c.dtype, b.blk[0].src_nodes, lay.cap_src[0], b.blk[0].counts + 1,
+                       b.at(lay.H[0]), d[0], sw.map, st);
+}
+
+// Phase 2: forward, loss, backward, SGD on the blocks and features phase 1 left in `b`.
+int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seeds, float* loss_d, hipStream_t st) {
+    const sdt_step_layout& lay = c.lay;
+    const sdt_model* model = c.model;
+    const int L = model->n_layers;
+    const int32_t* d = model->dims;
+    const int32_t dtype = c.dtype;
+    sdt_timing* timing = c.timing;
+    int32_t rc;
+    for (int l = 0; l < L; ++l) {
+        {
+            StageTimer tm(timing, SDT_STAGE_AGG_FWD, l, st);
+            rc = sdt_sage_aggregate_fwd(&b.blk[l], b.at(lay.H[l]), d[l], d[l], dtype, b.at(lay.A[l]), d[l], st);
+        }
+        if (rc != SDT_OK) return rc;
+        const bool last = l == L - 1;
+        StageTimer tm(timing, SDT_STAGE_LINEAR_FWD, l, st);
+        rc = sdt_sage_linear_fwd(b.at(lay.H[l]), d[l], b.at(lay.A[l]), d[l], lay.cap_dst[l], b.blk[l].counts, d[l],
+                                 d[l + 1], model->W[l], model->b[l], last ? 0 : 1, dtype, b.at(lay.H[l + 1]), d[l + 1],
+                                 last ? SDT_F32 : dtype, st);
+        if (rc != SDT_OK) return rc;
+    }
+    {
+        StageTimer tm(timing, SDT_STAGE_LOSS, 0, st);
+        rc = softmax_xent(static_cast<const float*>(b.at(lay.H[L])), d[L], c.batch, d[L], c.labels, seeds,
+                          static_cast<float*>(b.at(lay.dZ)), static_cast<float*>(b.at(lay.row_loss)), st);
+    }
+    if (rc != SDT_OK) return rc;
+    const void* dY = b.at(lay.dZ);
+    int32_t dy_dtype = SDT_F32;
+    for (int l = L - 1; l >= 0; --l) {
+        float* dW = model->dW[l] ? model->dW[l] : static_cast<float*>(b.at(lay.dW[l]));
+        float* db = model->db[l] ? model->db[l] : static_cast<float*>(b.at(lay.db[l]));
+        const bool inner = l > 0;
+        {
+            StageTimer tm(timing, SDT_STAGE_LINEAR_BWD, l, st);
+            // the SGD step of this layer (and, for the last layer, the mean of the per-seed
+            // losses) ride on the final reduction of its weight gradient
+            BwdExtras ex;
+            ex.W_upd = model->W[l];
+            ex.b_upd = model->b[l];
+            ex.lr = c.lr;
+            if (l == L - 1) {
+                ex.row_loss = static_cast<const float*>(b.at(lay.row_loss));
+                ex.n_loss = c.batch;
+                ex.loss_out = loss_d;
+            }
+            rc = linear_bwd(dY, d[l + 1], dy_dtype, nullptr, 0, 0, b.at(lay.H[l]), d[l], b.at(lay.A[l]), d[l],
+                            lay.cap_dst[l], b.blk[l].counts, d[l], d[l + 1], model->W[l], dtype, dW, db,
+                            inner ? b.at(lay.dSelf[l]) : nullptr, inner ? b.at(lay.dAgg[l]) : nullptr, d[l],
+                            b.at(lay.scratch), b.bytes - lay.scratch, ex, st);
+        }
+        if (rc != SDT_OK) return rc;
+        if (inner) {
+            // gradient w.r.t. H[l], masked by the ReLU that produced H[l]
+            StageTimer tm(timing, SDT_STAGE_AGG_BWD, l, st);
+            rc = sdt_sage_aggregate_bwd(&b.blk[l], b.at(lay.dAgg[l]), d[l], b.at(lay.dSelf[l]), d[l], b.at(lay.H[l]), d[l],
+                                        dtype, b.at(lay.dH[l]), d[l], st);
+            if (rc != SDT_OK) return rc;
+            dY = b.at(lay.dH[l]);
+            dy_dtype = dtype;
+        }
+    }
+    return SDT_OK;
+}
+
+}  // namespace
+
 extern "C" int32_t sdt_train_step(const sdt_csr* graph, const void* X, int64_t ldx, int32_t dtype, const int32_t* labels,
                                   const int32_t* seeds, int32_t batch, const int32_t* fanouts, const sdt_model* model,
                                   uint64_t seed, uint32_t step, float lr, float* loss_d, sdt_timing* timing, void* ws,
                                   size_t ws_bytes, void* stream) {
     SDT_REQUIRE(graph && graph->indptr, SDT_ERR_INVALID_ARG, "sdt_train_step: null graph");
-    sdt_step_layout lay;
-    int32_t rc = sdt_train_step_layout(graph->n_nodes, batch, fanouts, model, dtype, &lay);
+    StepCtx c{graph, X, ldx, dtype, labels, batch, fanouts, model, seed, lr, timing, {}};
+    int32_t rc = sdt_train_step_layout(graph->n_nodes, batch, fanouts, model, dtype, &c.lay);
     if (rc != SDT_OK) return rc;
-    const int L = model->n_layers;
-    const int32_t* d = model->dims;
-    SDT_REQUIRE(batch > 0, SDT_ERR_INVALID_ARG, "sdt_train_step: empty batch");
-    SDT_REQUIRE(X && labels && seeds && loss_d && ldx >= d[0], SDT_ERR_INVALID_ARG,
-                "sdt_train_step: null input or ldx < dims[0]");
-    SDT_REQUIRE(graph->indices || graph->n_nodes == 0, SDT_ERR_INVALID_ARG, "sdt_train_step: null indices");
-    for (int l = 0; l < L; ++l)
-        SDT_REQUIRE(model->W[l] && model->b[l], SDT_ERR_INVALID_ARG, "sdt_train_step: null weights of layer %d", l);
-    SDT_REQUIRE(ws && ws_bytes >= lay.total_bytes && aligned16(ws), SDT_ERR_WORKSPACE,
-                "sdt_train_step: workspace of %llu bytes needed, %zu given", (unsigned long long)lay.total_bytes,
+    rc = check_step_args("sdt_train_step", graph, X, ldx, labels, seeds, batch, model, loss_d);
+    if (rc != SDT_OK) return rc;
+    SDT_REQUIRE(ws && ws_bytes >= c.lay.total_bytes && aligned16(ws), SDT_ERR_WORKSPACE,
+                "sdt_train_step: workspace of %llu bytes needed, %zu given", (unsigned long long)c.lay.total_bytes,
                 ws_bytes);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    char* base = static_cast<char*>(ws);
-    auto at = [&](uint64_t off) { return static_cast<void*>(base + off); };
-
-    sdt_block blk[SDT_MAX_LAYERS];
-    for (int l = 0; l < L; ++l) {
-        blk[l].cap_dst = lay.cap_dst[l];
-        blk[l].cap_src = lay.cap_src[l];
-        blk[l].cap_nnz = lay.cap_nnz[l];
-        blk[l].reserved = 0;
-        blk[l].counts = static_cast<int32_t*>(at(lay.counts[l]));
-        blk[l].indptr = static_cast<int32_t*>(at(lay.indptr[l]));
-        blk[l].cols = static_cast<int32_t*>(at(lay.cols[l]));
-        blk[l].src_nodes = static_cast<int32_t*>(at(lay.src_nodes[l]));
-        blk[l].t_indptr = l >= 1 ? static_cast<int32_t*>(at(lay.t_indptr[l])) : nullptr;
-        blk[l].t_rows = l >= 1 ? static_cast<int32_t*>(at(lay.t_rows[l])) : nullptr;
-    }
-
+    StepBuffers b;
+    bind_buffers(c.lay, ws, ws_bytes, &b);
     if (timing) timing->slot = timing->used < timing->max_steps ? timing->used++ : -1;
-
-    // ---- sample from the seeds outwards; the node -> local-id map carries over from layer
-    // to layer, and from step to step it is handed back clean (see the gather below)
-    int32_t* header = static_cast<int32_t*>(at(lay.header));
-    SampleWs sw{};
-    sample_state_carve(at(lay.state), graph->n_nodes, &sw);
-    {
-        const int32_t* dst = seeds;
-        const int32_t* n_d = nullptr;
-        for (int l = L - 1; l >= 0; --l) {
-            StageTimer tl(timing, SDT_STAGE_SAMPLE, l, st);
-            if (l == L - 1) {
-                rc = sample_state_init(sw, graph->n_nodes, header, st);
-                if (rc != SDT_OK) return rc;
-                rc = sample_seed_map(sw, seeds, batch, nullptr, header, graph->n_nodes, st);
-                if (rc != SDT_OK) return rc;
-            }
-            Arena a(at(lay.scratch));
-            sample_tmp_carve(a, graph->n_nodes, lay.cap_dst[l], fanouts[l], &sw);
-            rc = sample_layer(*graph, dst, lay.cap_dst[l], n_d, fanouts[l], seed, step, (uint32_t)l, blk[l], sw, st);
-            if (rc != SDT_OK) return rc;
-            dst = blk[l].src_nodes;
-            n_d = blk[l].counts + 1;
-        }
-    }
-
-    // ---- gather the input features of the outermost frontier
-    {
-        StageTimer tm(timing, SDT_STAGE_GATHER, 0, st);
-        rc = gather_rows(X, ldx, d[0], dtype, blk[0].src_nodes, lay.cap_src[0], blk[0].counts + 1, at(lay.H[0]), d[0],
-                         sw.map, st);
-    }
+    rc = step_sample(c, b, seeds, step, st);
     if (rc != SDT_OK) return rc;
+    return step_compute(c, b, seeds, loss_d, st);
+}
 
-    // ---- forward
-    for (int l = 0; l < L; ++l) {
-        {
-            StageTimer tm(timing, SDT_STAGE_AGG_FWD, l, st);
-            rc = sdt_sage_aggregate_fwd(&blk[l], at(lay.H[l]), d[l], d[l], dtype, at(lay.A[l]), d[l], st);
-        }
-        if (rc != SDT_OK) return rc;
-        const bool last = l == L - 1;
-        StageTimer tm(timing, SDT_STAGE_LINEAR_FWD, l, st);
-        rc = sdt_sage_linear_fwd(at(lay.H[l]), d[l], at(lay.A[l]), d[l], lay.cap_dst[l], blk[l].counts, d[l], d[l + 1],
-                                 model->W[l], model->b[l], last ? 0 : 1, dtype, at(lay.H[l + 1]), d[l + 1],
-                                 last ? SDT_F32 : dtype, st);
-        if (rc != SDT_OK) return rc;
-    }
+extern "C" size_t sdt_train_loop_workspace_bytes(int64_t n_nodes, int32_t batch, const int32_t* fanouts,
+                                                 const sdt_model* model, int32_t dtype) {
+    sdt_step_layout lay;
+    if (sdt_train_step_layout(n_nodes, batch, fanouts, model, dtype, &lay) != SDT_OK) return 0;
+    return 2 * align_up((size_t)lay.total_bytes, 256);
+}
 
-    // ---- loss and its gradient
-    {
-        StageTimer tm(timing, SDT_STAGE_LOSS, 0, st);
-        rc = softmax_xent(static_cast<const float*>(at(lay.H[L])), d[L], batch, d[L], labels, seeds,
-                          static_cast<float*>(at(lay.dZ)), static_cast<float*>(at(lay.row_loss)), st);
-    }
+extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t ldx, int32_t dtype, const int32_t* labels,
+                                  const int32_t* seeds, int32_t batch, int32_t n_steps, const int32_t* fanouts,
+                                  const sdt_model* model, uint64_t seed, uint32_t first_step, float lr, float* losses_d,
+                                  sdt_timing* timing, void* ws, size_t ws_bytes, void* stream, void* aux_stream) {
+    SDT_REQUIRE(graph && graph->indptr, SDT_ERR_INVALID_ARG, "sdt_train_loop: null graph");
+    SDT_REQUIRE(n_steps >= 0, SDT_ERR_INVALID_ARG, "sdt_train_loop: n_steps = %d", n_steps);
+    StepCtx c{graph, X, ldx, dtype, labels, batch, fanouts, model, seed, lr, timing, {}};
+    int32_t rc = sdt_train_step_layout(graph->n_nodes, batch, fanouts, model, dtype, &c.lay);
     if (rc != SDT_OK) return rc;
+    rc = check_step_args("sdt_train_loop", graph, X, ldx, labels, seeds, batch, model, losses_d);
+    if (rc != SDT_OK) return rc;
+    const size_t one = align_up((size_t)c.lay.total_bytes, 256);
+    SDT_REQUIRE(ws && ws_bytes >= 2 * one && aligned16(ws), SDT_ERR_WORKSPACE,
+                "sdt_train_loop: workspace of %zu bytes needed, %zu given", 2 * one, ws_bytes);
+    hipStream_t main_st = static_cast<hipStream_t>(stream);
+    hipStream_t aux_st = static_cast<hipStream_t>(aux_stream);
+    const bool overlap = aux_st != main_st;
+    StepBuffers buf[2];
+    bind_buffers(c.lay, ws, one, &buf[0]);
+    bind_buffers(c.lay, static_cast<char*>(ws) + one, one, &buf[1]);
 
-    // ---- backward
-    float* dW[SDT_MAX_LAYERS];
-    float* db[SDT_MAX_LAYERS];
-    const void* dY = at(lay.dZ);
-    int32_t dy_dtype = SDT_F32;
-    for (int l = L - 1; l >= 0; --l) {
-        dW[l] = model->dW[l] ? model->dW[l] : static_cast<float*>(at(lay.dW[l]));
-        db[l] = model->db[l] ? model->db[l] : static_cast<float*>(at(lay.db[l]));
-        const bool inner = l > 0;
-        {
-        StageTimer tm(timing, SDT_STAGE_LINEAR_BWD, l, st);
-        // the SGD step of this layer (and, for the last layer, the mean of the per-seed
-        // losses) ride on the final reduction of its weight gradient
-        BwdExtras ex;
-        ex.W_upd = model->W[l];
-        ex.b_upd = model->b[l];
-        ex.lr = lr;
-        if (l == L - 1) {
-            ex.row_loss = static_cast<const float*>(at(lay.row_loss));
-            ex.n_loss = batch;
-            ex.loss_out = loss_d;
+    // ready[k]: phase 1 of the step in buffer k is complete; done[k]: its phase 2 is.
+    hipEvent_t ready[2] = {nullptr, nullptr}, done[2] = {nullptr, nullptr}, fork = nullptr;
+    auto cleanup = [&]() {
+        for (int k = 0; k < 2; ++k) {
+            if (ready[k]) (void)hipEventDestroy(ready[k]);
+            if (done[k]) (void)hipEventDestroy(done[k]);
         }
-        rc = linear_bwd(dY, d[l + 1], dy_dtype, nullptr, 0, 0, at(lay.H[l]), d[l], at(lay.A[l]), d[l], lay.cap_dst[l],
-                        blk[l].counts, d[l], d[l + 1], model->W[l], dtype, dW[l], db[l],
-                        inner ? at(lay.dSelf[l]) : nullptr, inner ? at(lay.dAgg[l]) : nullptr, d[l], at(lay.scratch),
-                        ws_bytes - lay.scratch, ex, st);
+        if (fork) (void)hipEventDestroy(fork);
+    };
+    if (overlap) {
+        bool ok = hipEventCreateWithFlags(&fork, hipEventDisableTiming) == hipSuccess;
+        for (int k = 0; k < 2 && ok; ++k)
+            ok = hipEventCreateWithFlags(&ready[k], hipEventDisableTiming) == hipSuccess &&
+                 hipEventCreateWithFlags(&done[k], hipEventDisableTiming) == hipSuccess;
+        if (!ok) {
+            cleanup();
+            set_error("sdt_train_loop: hipEventCreate failed");
+            return SDT_ERR_HIP;
         }
-        if (rc != SDT_OK) return rc;
-        if (inner) {
-            StageTimer tm(timing, SDT_STAGE_AGG_BWD, l, st);
-            // gradient w.r.t. H[l], masked by the ReLU that produced H[l]
-            rc = sdt_sage_aggregate_bwd(&blk[l], at(lay.dAgg[l]), d[l], at(lay.dSelf[l]), d[l], at(lay.H[l]), d[l], dtype,
-                                        at(lay.dH[l]), d[l], st);
-            if (rc != SDT_OK) return rc;
-            dY = at(lay.dH[l]);
-            dy_dtype = dtype;
-        }
+        // the auxiliary stream starts after whatever the caller queued on the main stream
+        (void)hipEventRecord(fork, main_st);
+        (void)hipStreamWaitEvent(aux_st, fork, 0);
     }
-
-    return SDT_OK;
+    rc = SDT_OK;
+    for (int i = 0; i < n_steps && rc == SDT_OK; ++i) {
+        const int k = i & 1;
+        const int32_t* sd = seeds + (int64_t)i * batch;
+        if (timing) timing->slot = timing->used < timing->max_steps ? timing->used++ : -1;
+        if (overlap && i >= 2) (void)hipStreamWaitEvent(aux_st, done[k], 0);   // buffer k is free again
+        rc = step_sample(c, buf[k], sd, first_step + (uint32_t)i, overlap ? aux_st : main_st);
+        if (rc != SDT_OK) break;
+        if (overlap) {
+            (void)hipEventRecord(ready[k], aux_st);
+            (void)hipStreamWaitEvent(main_st, ready[k], 0);
+        }
+        rc = step_compute(c, buf[k], sd, losses_d + i, main_st);
+        if (overlap && rc == SDT_OK) (void)hipEventRecord(done[k], main_st);
+    }
+    // every phase 1 was waited for by a phase 2 on the main stream, so synchronising the
+    // main stream covers the auxiliary one; the events may be released now (pending work keeps
+    // what it needs)
+    cleanup();
+    return rc;
 }

@@ -331,3 +331,32 @@ def test_train_step_ragged_dims_fp32():
     wl = gen.Workload("odd", "rmat", 12, 10, 37, 5, 19, 2, [4, 3], 100, 9, 1)
     inst = gen.make_instance(wl)
     _run_and_check(inst, wl, steps=1)
+
+
+@pytest.mark.parametrize("overlap", [True, False])
+def test_train_loop_equals_sequential_steps(overlap):
+    _say(f"train loop vs sequential steps, overlap={overlap}")
+    wl = gen.WORKLOADS["tiny"]
+    inst = gen.make_instance(wl)
+    n, lr = 7, 0.05
+    seq = StepRunner(inst.indptr, inst.indices, inst.X, inst.y, inst.W, inst.b, wl.fanouts, wl.batch)
+    seq_losses = [seq.step(inst.batch(i), wl.seed, 3 + i, lr) for i in range(n)]
+    loop = StepRunner(inst.indptr, inst.indices, inst.X, inst.y, inst.W, inst.b, wl.fanouts, wl.batch)
+    nbytes = B.sdt_train_loop_workspace_bytes(loop.graph.n_nodes, wl.batch, wl.fanouts, loop.model, loop.code)
+    assert nbytes >= 2 * loop.lay.total_bytes
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    seeds = dev(np.stack([inst.batch(i) for i in range(n)]))
+    losses = torch.zeros(n, dtype=torch.float32, device="cuda")
+    aux = torch.cuda.Stream() if overlap else None
+    # two calls back to back: the second continues on the state the first left in the workspace
+    B.sdt_train_loop(loop.graph, loop.X, loop.y, seeds[:3], wl.fanouts, loop.model, wl.seed, 3, lr, losses[:3], ws, aux)
+    B.sdt_train_loop(loop.graph, loop.X, loop.y, seeds[3:], wl.fanouts, loop.model, wl.seed, 6, lr, losses[3:], ws, aux)
+    torch.cuda.synchronize()
+    assert losses.cpu().tolist() == [np.float32(v) for v in seq_losses]
+    for l in range(seq.L):
+        assert torch.equal(seq.W[l], loop.W[l]) and torch.equal(seq.b[l], loop.b[l])
+    # the last step of the second call (its 4th) sits in buffer 3 % 2 and equals the sequential run's
+    off = (3 % 2) * (nbytes // 2)
+    lay = loop.lay
+    for o, nb in [(lay.dW[0], 2 * 64 * 64 * 4), (lay.H[2], 256 * 8 * 4), (lay.indptr[0], 4 * 100)]:
+        assert torch.equal(ws[off + o:off + o + nb], seq.ws[o:o + nb])

@@ -134,4 +134,17 @@ int32_t linear_bwd(const void* dY, int64_t lddy, int32_t dy_dtype, const void* Y
                    int32_t in, int32_t out, const float* W, int32_t dtype, float* dW, float* db, void* dSelf,
                    void* dAgg, int64_t ldi, void* ws, size_t ws_bytes, const BwdExtras& ex, hipStream_t st);
 
+// dW = sum of `splits` partials P[s][2in][out], db likewise from Q[s][out], plus the extras
+int32_t reduce_partials(const float* P, const float* Q, int32_t splits, int32_t in, int32_t out, float* dW, float* db,
+                        const BwdExtras& ex, hipStream_t st);
+
+// Fused last layer (projection + softmax cross-entropy + backward) for small class counts.
+bool head_supported(int32_t in, int32_t out);
+int32_t head_splits(int32_t batch);
+size_t head_workspace_bytes(int32_t batch, int32_t in, int32_t out);
+int32_t head_fwd_bwd(const void* Hself, int64_t ldh, const void* A, int64_t lda, int32_t batch, int32_t in, int32_t out,
+                     const float* W, const float* bias, int32_t dtype, const int32_t* labels, const int32_t* seeds,
+                     float* logits, float* dZ, float* row_loss, void* dSelf, void* dAgg, int64_t ldi, void* ws,
+                     size_t ws_bytes, float** P_out, float** Q_out, hipStream_t st);
+
 }  // namespace sdt

@@ -336,15 +336,18 @@ __global__ __launch_bounds__(TB) void k_linear_bwd_weight(const TH* __restrict__
     });
 }
 
-// dW[idx] = sum_s P[s][idx] (s ascending); db[o] = sum_s Q[s][o]; optionally the SGD step
-// W -= lr dW, b -= lr db in the same pass.
+// dW[idx] = sum_s P[s][idx]; db[o] = sum_s Q[s][o]; optionally the SGD step W -= lr dW,
+// b -= lr db in the same pass, and (one extra workgroup) the mean of the per-seed losses.
+// A workgroup covers 64 consecutive elements with 4 threads each: thread g adds the partials
+// g, g+4, g+8, ... and the four sums are combined in the order 0,1,2,3 -- a fixed order, so
+// the result is deterministic, with four times as many loads in flight as one thread per element.
 __global__ __launch_bounds__(TB) void k_reduce_partials(const float* __restrict__ P, const float* __restrict__ Q,
                                                         int splits, int64_t n_w, int out, float* __restrict__ dW,
                                                         float* __restrict__ db, float* W_upd, float* b_upd, float lr,
                                                         const float* __restrict__ row_loss, int n_loss,
                                                         float* loss_out) {
+    __shared__ float part[TB];
     if (loss_out && blockIdx.x == gridDim.x - 1) {  // the extra last block: mean loss in a fixed order
-        __shared__ float part[TB];
         float s = 0.f;
         for (int i = threadIdx.x; i < n_loss; i += TB) s += row_loss[i];
         part[threadIdx.x] = s;
@@ -356,18 +359,28 @@ __global__ __launch_bounds__(TB) void k_reduce_partials(const float* __restrict_
         if (threadIdx.x == 0) *loss_out = part[0] / (float)n_loss;
         return;
     }
-    const int64_t idx = (int64_t)blockIdx.x * TB + threadIdx.x;
-    if (idx < n_w) {
-        float s = 0.f;
-        for (int k = 0; k < splits; ++k) s += P[(int64_t)k * n_w + idx];
-        dW[idx] = s;
-        if (W_upd) W_upd[idx] = W_upd[idx] - lr * s;
-    } else if (idx < n_w + out) {
-        const int o = (int)(idx - n_w);
-        float s = 0.f;
-        for (int k = 0; k < splits; ++k) s += Q[(int64_t)k * out + o];
-        db[o] = s;
-        if (b_upd) b_upd[o] = b_upd[o] - lr * s;
+    const int e = threadIdx.x & 63, g = threadIdx.x >> 6;
+    const int64_t idx = (int64_t)blockIdx.x * 64 + e;
+    const bool is_w = idx < n_w, is_b = !is_w && idx < n_w + out;
+    const float* src = is_w ? P + idx : Q + (idx - n_w);
+    const int64_t stride = is_w ? n_w : out;
+    float s = 0.f;
+    if (is_w || is_b) {
+#pragma unroll 4
+        for (int k = g; k < splits; k += 4) s += src[(int64_t)k * stride];
+    }
+    part[threadIdx.x] = s;
+    __syncthreads();
+    if (g == 0 && (is_w || is_b)) {
+        const float t = ((part[e] + part[64 + e]) + part[128 + e]) + part[192 + e];
+        if (is_w) {
+            dW[idx] = t;
+            if (W_upd) W_upd[idx] = W_upd[idx] - lr * t;
+        } else {
+            const int o = (int)(idx - n_w);
+            db[o] = t;
+            if (b_upd) b_upd[o] = b_upd[o] - lr * t;
+        }
     }
 }
 
@@ -478,7 +491,7 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Ymask, int64_t ldy, co
     }
     // after the input gradients: this pass may overwrite W with the SGD step
     const int64_t n_w = (int64_t)2 * in * out;
-    hipLaunchKernelGGL(k_reduce_partials, dim3(ceil_div(n_w + out, TB) + (ex.loss_out ? 1 : 0)), dim3(TB), 0, st, P, Q,
+    hipLaunchKernelGGL(k_reduce_partials, dim3(ceil_div(n_w + out, 64) + (ex.loss_out ? 1 : 0)), dim3(TB), 0, st, P, Q,
                        splits, n_w, out, dW, db, ex.W_upd, ex.b_upd, ex.lr, ex.row_loss, ex.n_loss, ex.loss_out);
 }
 
@@ -520,6 +533,15 @@ extern "C" size_t sdt_linear_bwd_workspace_bytes(int32_t n_cap, int32_t in, int3
 }
 
 namespace sdt {
+int32_t reduce_partials(const float* P, const float* Q, int32_t splits, int32_t in, int32_t out, float* dW, float* db,
+                        const BwdExtras& ex, hipStream_t st) {
+    const int64_t n_w = (int64_t)2 * in * out;
+    hipLaunchKernelGGL(k_reduce_partials, dim3(ceil_div(n_w + out, 64) + (ex.loss_out ? 1 : 0)), dim3(TB), 0, st, P, Q,
+                       splits, n_w, out, dW, db, ex.W_upd, ex.b_upd, ex.lr, ex.row_loss, ex.n_loss, ex.loss_out);
+    SDT_CHECK_LAUNCH("reduce_partials");
+    return SDT_OK;
+}
+
 int32_t linear_bwd(const void* dY, int64_t lddy, int32_t dy_dtype, const void* Y, int64_t ldy, int32_t relu,
                    const void* Hself, int64_t ldh, const void* A, int64_t lda, int32_t n_cap, const int32_t* n_d,
                    int32_t in, int32_t out, const float* W, int32_t dtype, float* dW, float* db, void* dSelf,

@@ -163,6 +163,10 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
         Arena s(nullptr);
         size_t sb = sample_tmp_carve(s, n_nodes, c.dst[l], fanouts[l], nullptr);
         size_t lb = sdt_linear_bwd_workspace_bytes(c.dst[l], d[l], d[l + 1]);
+        if (l == L - 1 && head_supported(d[l], d[l + 1])) {
+            const size_t hb = head_workspace_bytes(batch, d[l], d[l + 1]);
+            if (hb > lb) lb = hb;
+        }
         if (sb > scratch) scratch = sb;
         if (lb > scratch) scratch = lb;
     }
@@ -271,6 +275,9 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
     const int32_t dtype = c.dtype;
     sdt_timing* timing = c.timing;
     int32_t rc;
+    // Small class counts: the last layer's projection, the loss and that layer's backward run
+    // as one fused launch (head.hip) instead of five.
+    const bool fused_head = head_supported(d[L - 1], d[L]) && aligned16(model->W[L - 1]);
     for (int l = 0; l < L; ++l) {
         {
             StageTimer tm(timing, SDT_STAGE_AGG_FWD, l, st);
@@ -278,25 +285,44 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
         }
         if (rc != SDT_OK) return rc;
         const bool last = l == L - 1;
+        if (last && fused_head) break;
         StageTimer tm(timing, SDT_STAGE_LINEAR_FWD, l, st);
         rc = sdt_sage_linear_fwd(b.at(lay.H[l]), d[l], b.at(lay.A[l]), d[l], lay.cap_dst[l], b.blk[l].counts, d[l],
                                  d[l + 1], model->W[l], model->b[l], last ? 0 : 1, dtype, b.at(lay.H[l + 1]), d[l + 1],
                                  last ? SDT_F32 : dtype, st);
         if (rc != SDT_OK) return rc;
     }
-    {
+    if (!fused_head) {
         StageTimer tm(timing, SDT_STAGE_LOSS, 0, st);
         rc = softmax_xent(static_cast<const float*>(b.at(lay.H[L])), d[L], c.batch, d[L], c.labels, seeds,
                           static_cast<float*>(b.at(lay.dZ)), static_cast<float*>(b.at(lay.row_loss)), st);
+        if (rc != SDT_OK) return rc;
     }
-    if (rc != SDT_OK) return rc;
     const void* dY = b.at(lay.dZ);
     int32_t dy_dtype = SDT_F32;
     for (int l = L - 1; l >= 0; --l) {
         float* dW = model->dW[l] ? model->dW[l] : static_cast<float*>(b.at(lay.dW[l]));
         float* db = model->db[l] ? model->db[l] : static_cast<float*>(b.at(lay.db[l]));
         const bool inner = l > 0;
-        {
+        if (l == L - 1 && fused_head) {
+            StageTimer tm(timing, SDT_STAGE_LINEAR_BWD, l, st);
+            float *P, *Q;
+            rc = head_fwd_bwd(b.at(lay.H[l]), d[l], b.at(lay.A[l]), d[l], c.batch, d[l], d[l + 1], model->W[l],
+                              model->b[l], dtype, c.labels, seeds, static_cast<float*>(b.at(lay.H[L])),
+                              static_cast<float*>(b.at(lay.dZ)), static_cast<float*>(b.at(lay.row_loss)),
+                              inner ? b.at(lay.dSelf[l]) : nullptr, inner ? b.at(lay.dAgg[l]) : nullptr, d[l],
+                              b.at(lay.scratch), b.bytes - lay.scratch, &P, &Q, st);
+            if (rc != SDT_OK) return rc;
+            BwdExtras ex;
+            ex.W_upd = model->W[l];
+            ex.b_upd = model->b[l];
+            ex.lr = c.lr;
+            ex.row_loss = static_cast<const float*>(b.at(lay.row_loss));
+            ex.n_loss = c.batch;
+            ex.loss_out = loss_d;
+            rc = reduce_partials(P, Q, head_splits(c.batch), d[l], d[l + 1], dW, db, ex, st);
+            if (rc != SDT_OK) return rc;
+        } else {
             StageTimer tm(timing, SDT_STAGE_LINEAR_BWD, l, st);
             // the SGD step of this layer (and, for the last layer, the mean of the per-seed
             // losses) ride on the final reduction of its weight gradient
@@ -313,8 +339,8 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
                             lay.cap_dst[l], b.blk[l].counts, d[l], d[l + 1], model->W[l], dtype, dW, db,
                             inner ? b.at(lay.dSelf[l]) : nullptr, inner ? b.at(lay.dAgg[l]) : nullptr, d[l],
                             b.at(lay.scratch), b.bytes - lay.scratch, ex, st);
+            if (rc != SDT_OK) return rc;
         }
-        if (rc != SDT_OK) return rc;
         if (inner) {
             // gradient w.r.t. H[l], masked by the ReLU that produced H[l]
             StageTimer tm(timing, SDT_STAGE_AGG_BWD, l, st);

@@ -326,6 +326,13 @@ def test_train_step_three_layers_bf16_small():
     _run_and_check(inst, wl, steps=2, check_float_steps=(0, 1))
 
 
+def test_train_step_many_classes_generic_last_layer():
+    _say("train step: 300 classes (last layer on the generic kernels, not the fused head)")
+    wl = gen.Workload("wide", "rmat", 12, 10, 24, 300, 32, 2, [4, 3], 96, 13, 1)
+    inst = gen.make_instance(wl)
+    _run_and_check(inst, wl, steps=2, check_float_steps=(0, 1))
+
+
 def test_train_step_ragged_dims_fp32():
     _say("train step: odd feature widths (scalar load paths)")
     wl = gen.Workload("odd", "rmat", 12, 10, 37, 5, 19, 2, [4, 3], 100, 9, 1)

@@ -254,15 +254,15 @@ int32_t sdt_train_step(const sdt_csr *graph /*host struct*/, const void *X, int6
  * Same result, bit for bit, as n_steps calls of sdt_train_step with step =
  * first_step + i, seeds + i*batch and loss_d = losses_d + i -- but the phase of
  * a step that needs no weights (sampling, frontier, gather) is enqueued on
- * `aux_stream` and runs up to two steps ahead of the forward/backward phase on
- * `stream`, double-buffered through two step workspaces (Sec. II-A: the
+ * `aux_stream` and runs up to three steps ahead of the forward/backward phase on
+ * `stream`, rotating through three step workspaces (Sec. II-A: the
  * mini-batch sub-graphs are independent of the model; Sec. III-D: a worker
  * trains many mini-batches between two synchronisations).  Ordering between
  * the two streams uses HIP events created and released inside the call.  When
  * the call returns everything is enqueued; synchronising `stream` is enough.
  * seeds is device int32[n_steps, batch]; losses_d device fp32[n_steps].  The
- * workspace (sdt_train_loop_workspace_bytes: two step workspaces, each with
- * sdt_train_step's layout, the second starting at half the size) carries
+ * workspace (sdt_train_loop_workspace_bytes: three step workspaces, each with
+ * sdt_train_step's layout, at thirds of the size) carries
  * state like sdt_train_step's.  aux_stream == stream gives the serial order.
  * Both streams must have the default priority. */
 size_t sdt_train_loop_workspace_bytes(int64_t n_nodes, int32_t batch, const int32_t *fanouts /*host*/,

@@ -378,11 +378,14 @@ extern "C" int32_t sdt_train_step(const sdt_csr* graph, const void* X, int64_t l
     return step_compute(c, b, seeds, loss_d, st);
 }
 
+// Step workspaces the loop rotates through: the sampling phase may run this many steps ahead.
+static constexpr int LOOP_BUFFERS = 3;
+
 extern "C" size_t sdt_train_loop_workspace_bytes(int64_t n_nodes, int32_t batch, const int32_t* fanouts,
                                                  const sdt_model* model, int32_t dtype) {
     sdt_step_layout lay;
     if (sdt_train_step_layout(n_nodes, batch, fanouts, model, dtype, &lay) != SDT_OK) return 0;
-    return 2 * align_up((size_t)lay.total_bytes, 256);
+    return LOOP_BUFFERS * align_up((size_t)lay.total_bytes, 256);
 }
 
 extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t ldx, int32_t dtype, const int32_t* labels,
@@ -397,19 +400,18 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
     rc = check_step_args("sdt_train_loop", graph, X, ldx, labels, seeds, batch, model, losses_d);
     if (rc != SDT_OK) return rc;
     const size_t one = align_up((size_t)c.lay.total_bytes, 256);
-    SDT_REQUIRE(ws && ws_bytes >= 2 * one && aligned16(ws), SDT_ERR_WORKSPACE,
-                "sdt_train_loop: workspace of %zu bytes needed, %zu given", 2 * one, ws_bytes);
+    SDT_REQUIRE(ws && ws_bytes >= LOOP_BUFFERS * one && aligned16(ws), SDT_ERR_WORKSPACE,
+                "sdt_train_loop: workspace of %zu bytes needed, %zu given", LOOP_BUFFERS * one, ws_bytes);
     hipStream_t main_st = static_cast<hipStream_t>(stream);
     hipStream_t aux_st = static_cast<hipStream_t>(aux_stream);
     const bool overlap = aux_st != main_st;
-    StepBuffers buf[2];
-    bind_buffers(c.lay, ws, one, &buf[0]);
-    bind_buffers(c.lay, static_cast<char*>(ws) + one, one, &buf[1]);
+    StepBuffers buf[LOOP_BUFFERS];
+    for (int k = 0; k < LOOP_BUFFERS; ++k) bind_buffers(c.lay, static_cast<char*>(ws) + k * one, one, &buf[k]);
 
     // ready[k]: phase 1 of the step in buffer k is complete; done[k]: its phase 2 is.
-    hipEvent_t ready[2] = {nullptr, nullptr}, done[2] = {nullptr, nullptr}, fork = nullptr;
+    hipEvent_t ready[LOOP_BUFFERS] = {}, done[LOOP_BUFFERS] = {}, fork = nullptr;
     auto cleanup = [&]() {
-        for (int k = 0; k < 2; ++k) {
+        for (int k = 0; k < LOOP_BUFFERS; ++k) {
             if (ready[k]) (void)hipEventDestroy(ready[k]);
             if (done[k]) (void)hipEventDestroy(done[k]);
         }
@@ -417,7 +419,7 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
     };
     if (overlap) {
         bool ok = hipEventCreateWithFlags(&fork, hipEventDisableTiming) == hipSuccess;
-        for (int k = 0; k < 2 && ok; ++k)
+        for (int k = 0; k < LOOP_BUFFERS && ok; ++k)
             ok = hipEventCreateWithFlags(&ready[k], hipEventDisableTiming) == hipSuccess &&
                  hipEventCreateWithFlags(&done[k], hipEventDisableTiming) == hipSuccess;
         if (!ok) {
@@ -431,10 +433,10 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
     }
     rc = SDT_OK;
     for (int i = 0; i < n_steps && rc == SDT_OK; ++i) {
-        const int k = i & 1;
+        const int k = i % LOOP_BUFFERS;
         const int32_t* sd = seeds + (int64_t)i * batch;
         if (timing) timing->slot = timing->used < timing->max_steps ? timing->used++ : -1;
-        if (overlap && i >= 2) (void)hipStreamWaitEvent(aux_st, done[k], 0);   // buffer k is free again
+        if (overlap && i >= LOOP_BUFFERS) (void)hipStreamWaitEvent(aux_st, done[k], 0);   // buffer k is free again
         rc = step_sample(c, buf[k], sd, first_step + (uint32_t)i, overlap ? aux_st : main_st);
         if (rc != SDT_OK) break;
         if (overlap) {

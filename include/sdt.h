@@ -234,7 +234,7 @@ enum {
     SDT_STAGE_LOSS = 4,
     SDT_STAGE_LINEAR_BWD = 5,
     SDT_STAGE_AGG_BWD = 6,
-    SDT_STAGE_UPDATE = 7 /* unused: the SGD step rides on LINEAR_BWD's final reduction */
+    SDT_STAGE_HEAD = 7 /* the fused last-layer launch alone (it also lies inside LINEAR_BWD of that layer) */
 };
 int32_t sdt_timing_create(int32_t max_steps, uint64_t stage_mask, sdt_timing **out /*host*/);
 void sdt_timing_destroy(sdt_timing *t);

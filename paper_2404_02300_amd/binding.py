@@ -86,7 +86,7 @@ EXPORTS = {
 }
 
 STAGES = {"sample": 0, "gather": 1, "aggregate_fwd": 2, "linear_fwd": 3, "loss": 4, "linear_bwd": 5,
-          "aggregate_bwd": 6, "update": 7}
+          "aggregate_bwd": 6, "head": 7}
 
 _lib = None
 

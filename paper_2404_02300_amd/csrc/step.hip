@@ -50,6 +50,7 @@ struct sdt_timing {
     uint64_t mask;
     int32_t used;                 // slots consumed so far
     int32_t slot;                 // slot of the step being recorded, -1 = none
+    uint64_t recorded;            // stages that were bracketed at least once since the last reset
     hipEvent_t* ev[64][2];        // [stage bit][begin/end][slot]
 };
 
@@ -59,8 +60,12 @@ struct StageTimer {               // records begin now, end at scope exit
     int bit;
     hipStream_t st;
     StageTimer(sdt_timing* tm, int kind, int layer, hipStream_t s) : t(tm), bit(kind * SDT_MAX_LAYERS + layer), st(s) {
-        if (t && t->slot >= 0 && ((t->mask >> bit) & 1)) (void)hipEventRecord(t->ev[bit][0][t->slot], st);
-        else t = nullptr;
+        if (t && t->slot >= 0 && ((t->mask >> bit) & 1)) {
+            (void)hipEventRecord(t->ev[bit][0][t->slot], st);
+            t->recorded |= 1ull << bit;
+        } else {
+            t = nullptr;
+        }
     }
     ~StageTimer() {
         if (t) (void)hipEventRecord(t->ev[bit][1][t->slot], st);
@@ -75,6 +80,7 @@ extern "C" int32_t sdt_timing_create(int32_t max_steps, uint64_t stage_mask, sdt
     t->mask = stage_mask;
     t->used = 0;
     t->slot = -1;
+    t->recorded = 0;
     for (int b = 0; b < 64; ++b)
         for (int k = 0; k < 2; ++k) {
             t->ev[b][k] = nullptr;
@@ -102,7 +108,7 @@ extern "C" void sdt_timing_destroy(sdt_timing* t) {
 }
 
 extern "C" void sdt_timing_reset(sdt_timing* t) {
-    if (t) { t->used = 0; t->slot = -1; }
+    if (t) { t->used = 0; t->slot = -1; t->recorded = 0; }
 }
 
 extern "C" int32_t sdt_timing_read(sdt_timing* t, int32_t kind, int32_t layer, float* ms_out, int32_t* n_out) {
@@ -110,6 +116,8 @@ extern "C" int32_t sdt_timing_read(sdt_timing* t, int32_t kind, int32_t layer, f
                 SDT_ERR_INVALID_ARG, "sdt_timing_read: bad arguments");
     const int bit = kind * SDT_MAX_LAYERS + layer;
     SDT_REQUIRE((t->mask >> bit) & 1, SDT_ERR_INVALID_ARG, "sdt_timing_read: stage (%d,%d) was not selected", kind, layer);
+    SDT_REQUIRE((t->recorded >> bit) & 1, SDT_ERR_INVALID_ARG,
+                "sdt_timing_read: stage (%d,%d) did not run as a separate stage", kind, layer);
     for (int i = 0; i < t->used; ++i) {
         if (hipEventSynchronize(t->ev[bit][1][i]) != hipSuccess ||
             hipEventElapsedTime(&ms_out[i], t->ev[bit][0][i], t->ev[bit][1][i]) != hipSuccess) {
@@ -307,11 +315,14 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
         if (l == L - 1 && fused_head) {
             StageTimer tm(timing, SDT_STAGE_LINEAR_BWD, l, st);
             float *P, *Q;
+            {
+            StageTimer th(timing, SDT_STAGE_HEAD, l, st);
             rc = head_fwd_bwd(b.at(lay.H[l]), d[l], b.at(lay.A[l]), d[l], c.batch, d[l], d[l + 1], model->W[l],
                               model->b[l], dtype, c.labels, seeds, static_cast<float*>(b.at(lay.H[L])),
                               static_cast<float*>(b.at(lay.dZ)), static_cast<float*>(b.at(lay.row_loss)),
                               inner ? b.at(lay.dSelf[l]) : nullptr, inner ? b.at(lay.dAgg[l]) : nullptr, d[l],
                               b.at(lay.scratch), b.bytes - lay.scratch, &P, &Q, st);
+            }
             if (rc != SDT_OK) return rc;
             BwdExtras ex;
             ex.W_upd = model->W[l];

@@ -170,10 +170,10 @@ def main():
         n_dst, n_src, nnz = mean_cnt[l][:3]
         if kind == "sample":      # 16 B of row offsets per destination, 4 B read + 4 B written per sampled edge
             return "hbm", n_dst * 16 + nnz * 8, "k_sample_rows + frontier scan + relabel (+ transposed block)"
-        if kind == "gather":
-            return "hbm", n_src * (2 * d[0] * es + 4), "k_gather"
-        if kind == "aggregate_fwd":
-            return "hbm", nnz * (d[l] * es + 4) + n_dst * (d[l] * es + 8), "k_aggregate_fwd"
+        if kind == "gather":      # only the destination prefix is copied; the rest is read by the aggregation
+            return "hbm", n_dst * (2 * d[0] * es + 4), "k_gather"
+        if kind == "aggregate_fwd":   # layer 0 reads X through src_nodes: 4 more index bytes per edge
+            return "hbm", nnz * (d[l] * es + (8 if l == 0 else 4)) + n_dst * (d[l] * es + 8), "k_aggregate_fwd"
         if kind == "aggregate_bwd":
             return "hbm", nnz * (d[l] * es + 4) + n_src * (d[l] * es + 8) + n_dst * d[l] * es, "k_aggregate_bwd"
         if kind == "linear_fwd":

@@ -100,8 +100,10 @@ typedef struct sdt_model {
 
 /* Byte offsets, inside the sdt_train_step workspace, of everything the step
  * produces (so a caller can inspect it), plus the capacities they were sized
- * for.  Index l is the GNN layer (0 = input-most).  H[0] is the gathered
- * input [cap_src[0], dims[0]]; H[l+1] the output of layer l (H[L] = logits,
+ * for.  Index l is the GNN layer (0 = input-most).  H[0] holds the gathered
+ * input rows of layer 0's DESTINATION nodes only, [cap_dst[0], dims[0]] (the
+ * other frontier rows are aggregated straight out of X and never copied);
+ * H[l+1] the output of layer l (H[L] = logits,
  * always fp32); A[l] the mean-aggregated neighbours; dZ the loss gradient
  * w.r.t. the logits (fp32); dH[l] (l >= 1) the gradient w.r.t. H[l] with the
  * ReLU mask of layer l-1 already applied; dSelf/dAgg[l] (l >= 1) the input
@@ -167,6 +169,11 @@ int32_t sdt_gather_features(const void *X, int64_t ldx, int32_t F, int32_t dtype
  * Uses blk->counts[0] rows. */
 int32_t sdt_sage_aggregate_fwd(const sdt_block *blk /*host struct*/, const void *H, int64_t ldh, int32_t F,
                                int32_t dtype, void *A, int64_t lda, void *stream);
+/* Gather and aggregate in one pass: A[i,:] = (1/m_i) sum_e X[src_nodes[cols[e]],:], reading the
+ * partition's feature matrix X (leading dimension ldx) through the block's frontier, so that the
+ * gathered copy of the frontier rows that are not destinations need not exist. */
+int32_t sdt_sage_aggregate_gather_fwd(const sdt_block *blk /*host struct*/, const void *X, int64_t ldx, int32_t F,
+                                      int32_t dtype, void *A, int64_t lda, void *stream);
 /* Same over a whole graph with the identity frontier (layer-wise inference):
  * row v aggregates H[indices[e],:] over its CSR row. */
 int32_t sdt_sage_aggregate_csr_fwd(const sdt_csr *graph /*host struct*/, const void *H, int64_t ldh, int32_t F,

@@ -67,6 +67,7 @@ EXPORTS = {
     "sdt_gather_features": (_i32, [_vp, _i64, _i32, _i32, _vp, _i32, _vp, _vp, _i64, _vp]),
     "sdt_sage_aggregate_fwd": (_i32, [_vp, _vp, _i64, _i32, _i32, _vp, _i64, _vp]),
     "sdt_sage_aggregate_csr_fwd": (_i32, [_vp, _vp, _i64, _i32, _i32, _vp, _i64, _vp]),
+    "sdt_sage_aggregate_gather_fwd": (_i32, [_vp, _vp, _i64, _i32, _i32, _vp, _i64, _vp]),
     "sdt_sage_aggregate_bwd": (_i32, [_vp, _vp, _i64, _vp, _i64, _vp, _i32, _i32, _vp, _i64, _vp]),
     "sdt_sage_linear_fwd": (_i32, [_vp, _i64, _vp, _i64, _i32, _vp, _i32, _i32, _vp, _vp, _i32, _i32, _vp, _i64,
                                    _i32, _vp]),
@@ -207,6 +208,11 @@ def sdt_gather_features(X: torch.Tensor, idx: torch.Tensor, out: torch.Tensor, n
 def sdt_sage_aggregate_fwd(blk: Block, H: torch.Tensor, A: torch.Tensor):
     _check(lib().sdt_sage_aggregate_fwd(ctypes.byref(blk.c), _ptr(H), H.stride(0), H.shape[1], dtype_code(H),
                                         _ptr(A), A.stride(0), _stream()))
+
+
+def sdt_sage_aggregate_gather_fwd(blk: Block, X: torch.Tensor, A: torch.Tensor):
+    _check(lib().sdt_sage_aggregate_gather_fwd(ctypes.byref(blk.c), _ptr(X), X.stride(0), X.shape[1], dtype_code(X),
+                                               _ptr(A), A.stride(0), _stream()))
 
 
 def sdt_sage_aggregate_csr_fwd(graph: Csr, H: torch.Tensor, A: torch.Tensor):

@@ -68,10 +68,15 @@ __global__ __launch_bounds__(TB) void k_gather(const char* __restrict__ X, int64
 }
 
 // ---- mean aggregation forward ---------------------------------------------------
+// row_ids (nullable): the source row of column c is H[row_ids[c]] instead of H[c] -- used to
+// aggregate straight out of the partition's feature matrix through a block's src_nodes, so the
+// gathered copy of the non-destination frontier rows is never written.  map_reset (nullable):
+// map_reset[row_ids[c]] = -1 for every column met (hands the frontier map back clean).
 template <typename T, int VE, int G, typename IP>
 __global__ __launch_bounds__(TB) void k_aggregate_fwd(const IP* __restrict__ indptr, const int32_t* __restrict__ cols,
                                                       int64_t n_cap, const int32_t* n_d, const T* __restrict__ H,
-                                                      int64_t ldh, int F, T* __restrict__ A, int64_t lda) {
+                                                      int64_t ldh, int F, T* __restrict__ A, int64_t lda,
+                                                      const int32_t* __restrict__ row_ids, int32_t* map_reset) {
     int64_t n = n_cap;
     if (n_d) n = *n_d < n_cap ? *n_d : n_cap;
     const int gl = threadIdx.x % G;
@@ -87,6 +92,16 @@ __global__ __launch_bounds__(TB) void k_aggregate_fwd(const IP* __restrict__ ind
                 int c[UNROLL];
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) c[u] = (e + u < e1) ? cols[e + u] : -1;
+                if (row_ids) {
+#pragma unroll
+                    for (int u = 0; u < UNROLL; ++u)
+                        if (c[u] >= 0) c[u] = row_ids[c[u]];
+                    if (map_reset && f0 == gl * VE && gl == 0) {
+#pragma unroll
+                        for (int u = 0; u < UNROLL; ++u)
+                            if (c[u] >= 0) map_reset[c[u]] = -1;
+                    }
+                }
                 float v[UNROLL][VE];
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) {
@@ -222,7 +237,8 @@ bool dispatch(int32_t dtype, int ve, int G, F32Fn&& f32, BF16Fn&& bf) {
 
 template <typename IP>
 int32_t launch_aggregate_fwd(const IP* indptr, const int32_t* cols, int64_t n_cap, const int32_t* n_d, const void* H,
-                             int64_t ldh, int32_t F, int32_t dtype, void* A, int64_t lda, hipStream_t st) {
+                             int64_t ldh, int32_t F, int32_t dtype, void* A, int64_t lda, const int32_t* row_ids,
+                             int32_t* map_reset, hipStream_t st) {
     if (n_cap == 0 || F == 0) return SDT_OK;
     const size_t es = dtype_size(dtype);
     const int ve = vec_bytes(es, F, {ldh, lda}, {H, A}) / (int)es;
@@ -231,7 +247,7 @@ int32_t launch_aggregate_fwd(const IP* indptr, const int32_t* cols, int64_t n_ca
         using T = decltype(t);
         constexpr int VE = decltype(vec)::value, GG = decltype(grp)::value;
         hipLaunchKernelGGL((k_aggregate_fwd<T, VE, GG, IP>), dim3(grid_rows(n_cap, GG)), dim3(TB), 0, st, indptr, cols,
-                           n_cap, n_d, static_cast<const T*>(H), ldh, F, static_cast<T*>(A), lda);
+                           n_cap, n_d, static_cast<const T*>(H), ldh, F, static_cast<T*>(A), lda, row_ids, map_reset);
     };
     if (!dispatch(dtype, ve, G, go, go)) {
         set_error("aggregate_fwd: no kernel for dtype %d vec %d group %d", dtype, ve, G);
@@ -299,7 +315,27 @@ extern "C" int32_t sdt_sage_aggregate_fwd(const sdt_block* blk, const void* H, i
     SDT_REQUIRE(blk->counts && blk->indptr && H && A && (blk->cols || blk->cap_nnz == 0), SDT_ERR_INVALID_ARG,
                 "sdt_sage_aggregate_fwd: null pointer");
     return launch_aggregate_fwd<int32_t>(blk->indptr, blk->cols, blk->cap_dst, blk->counts, H, ldh, F, dtype, A, lda,
-                                         static_cast<hipStream_t>(stream));
+                                         nullptr, nullptr, static_cast<hipStream_t>(stream));
+}
+
+namespace sdt {
+int32_t aggregate_gather_fwd(const sdt_block* blk, const void* X, int64_t ldx, int32_t F, int32_t dtype, void* A,
+                             int64_t lda, int32_t* map_reset, hipStream_t st) {
+    SDT_REQUIRE(blk, SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_gather_fwd: null block");
+    SDT_REQUIRE(dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_gather_fwd: unknown dtype %d", dtype);
+    SDT_REQUIRE(F >= 0 && blk->cap_dst >= 0 && ldx >= F && lda >= F, SDT_ERR_INVALID_ARG,
+                "sdt_sage_aggregate_gather_fwd: bad sizes");
+    if (blk->cap_dst == 0 || F == 0) return SDT_OK;
+    SDT_REQUIRE(blk->counts && blk->indptr && blk->src_nodes && X && A && (blk->cols || blk->cap_nnz == 0),
+                SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_gather_fwd: null pointer");
+    return launch_aggregate_fwd<int32_t>(blk->indptr, blk->cols, blk->cap_dst, blk->counts, X, ldx, F, dtype, A, lda,
+                                         blk->src_nodes, map_reset, st);
+}
+}  // namespace sdt
+
+extern "C" int32_t sdt_sage_aggregate_gather_fwd(const sdt_block* blk, const void* X, int64_t ldx, int32_t F,
+                                                 int32_t dtype, void* A, int64_t lda, void* stream) {
+    return aggregate_gather_fwd(blk, X, ldx, F, dtype, A, lda, nullptr, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int32_t sdt_sage_aggregate_csr_fwd(const sdt_csr* g, const void* H, int64_t ldh, int32_t F, int32_t dtype,
@@ -311,7 +347,7 @@ extern "C" int32_t sdt_sage_aggregate_csr_fwd(const sdt_csr* g, const void* H, i
     if (g->n_nodes == 0 || F == 0) return SDT_OK;
     SDT_REQUIRE(g->indptr && g->indices && H && A, SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_csr_fwd: null pointer");
     return launch_aggregate_fwd<int64_t>(g->indptr, g->indices, g->n_nodes, nullptr, H, ldh, F, dtype, A, lda,
-                                         static_cast<hipStream_t>(stream));
+                                         nullptr, nullptr, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int32_t sdt_sage_aggregate_bwd(const sdt_block* blk, const void* dAgg, int64_t ldg, const void* dSelf,

@@ -178,7 +178,7 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
         if (sb > scratch) scratch = sb;
         if (lb > scratch) scratch = lb;
     }
-    lay->H[0] = a.take_off((size_t)c.src[0] * d[0] * es);
+    lay->H[0] = a.take_off((size_t)c.dst[0] * d[0] * es);
     lay->dZ = a.take_off((size_t)batch * d[L] * 4);
     lay->row_loss = a.take_off((size_t)(batch > 0 ? batch : 1) * 4);
     lay->scratch = a.take_off(scratch);
@@ -269,9 +269,17 @@ int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds
         dst = b.blk[l].src_nodes;
         n_d = b.blk[l].counts + 1;
     }
-    StageTimer tm(c.timing, SDT_STAGE_GATHER, 0, st);
-    return gather_rows(c.X, c.ldx, d[0], c.dtype, b.blk[0].src_nodes, lay.cap_src[0], b.blk[0].counts + 1,
-                       b.at(lay.H[0]), d[0], sw.map, st);
+    // Input features: only the destination prefix of the outermost frontier is copied (the
+    // projection's "self" operand); the neighbour mean of layer 0 is taken straight out of X.
+    // Both passes hand the frontier map back clean (prefix nodes here, the rest there).
+    {
+        StageTimer tm(c.timing, SDT_STAGE_GATHER, 0, st);
+        rc = gather_rows(c.X, c.ldx, d[0], c.dtype, b.blk[0].src_nodes, lay.cap_dst[0], b.blk[0].counts,
+                         b.at(lay.H[0]), d[0], sw.map, st);
+    }
+    if (rc != SDT_OK) return rc;
+    StageTimer tm(c.timing, SDT_STAGE_AGG_FWD, 0, st);
+    return aggregate_gather_fwd(&b.blk[0], c.X, c.ldx, d[0], c.dtype, b.at(lay.A[0]), d[0], sw.map, st);
 }
 
 // Phase 2: forward, loss, backward, SGD on the blocks and features phase 1 left in `b`.
@@ -287,11 +295,11 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
     // as one fused launch (head.hip) instead of five.
     const bool fused_head = head_supported(d[L - 1], d[L]) && aligned16(model->W[L - 1]);
     for (int l = 0; l < L; ++l) {
-        {
+        if (l > 0) {   // layer 0's mean was taken in phase 1
             StageTimer tm(timing, SDT_STAGE_AGG_FWD, l, st);
             rc = sdt_sage_aggregate_fwd(&b.blk[l], b.at(lay.H[l]), d[l], d[l], dtype, b.at(lay.A[l]), d[l], st);
+            if (rc != SDT_OK) return rc;
         }
-        if (rc != SDT_OK) return rc;
         const bool last = l == L - 1;
         if (last && fused_head) break;
         StageTimer tm(timing, SDT_STAGE_LINEAR_FWD, l, st);

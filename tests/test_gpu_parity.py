@@ -161,6 +161,12 @@ def test_aggregate_fwd_bwd(F, bf16):
     assert_close(f64(A), orc.round_bf16(refA) if bf16 else refA, tol, "A")
     empty = np.diff(blk.indptr) == 0
     assert empty.any() and not A[torch.from_numpy(empty).cuda()].any()             # rows without neighbours are zero
+    # the same mean taken straight out of a feature matrix through the frontier's node ids
+    X = torch.from_numpy(rng.standard_normal((4000, F)).astype(np.float32)).to(dt).cuda()
+    A2 = torch.empty_like(A)
+    B.sdt_sage_aggregate_gather_fwd(gb, X, A2)
+    refA2 = orc.aggregate_fwd(blk.indptr, blk.cols, f64(X)[blk.src_nodes])
+    assert_close(f64(A2), orc.round_bf16(refA2) if bf16 else refA2, tol, "A gathered through src_nodes")
     dAgg = torch.from_numpy(rng.standard_normal((blk.n_dst, F)).astype(np.float32)).to(dt).cuda()
     dSelf = torch.from_numpy(rng.standard_normal((blk.n_dst, F)).astype(np.float32)).to(dt).cuda()
     dH = torch.empty(blk.n_src, F, dtype=dt, device="cuda")

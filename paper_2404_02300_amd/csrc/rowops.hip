@@ -76,13 +76,15 @@ template <typename T, int VE, int G, typename IP>
 __global__ __launch_bounds__(TB) void k_aggregate_fwd(const IP* __restrict__ indptr, const int32_t* __restrict__ cols,
                                                       int64_t n_cap, const int32_t* n_d, const T* __restrict__ H,
                                                       int64_t ldh, int F, T* __restrict__ A, int64_t lda,
-                                                      const int32_t* __restrict__ row_ids, int32_t* map_reset) {
+                                                      const int32_t* __restrict__ row_ids, int32_t* map_reset,
+                                                      int64_t skip_longer_than) {
     int64_t n = n_cap;
     if (n_d) n = *n_d < n_cap ? *n_d : n_cap;
     const int gl = threadIdx.x % G;
     const int64_t ngrp = (int64_t)gridDim.x * (TB / G);
     for (int64_t i = (int64_t)blockIdx.x * (TB / G) + threadIdx.x / G; i < n; i += ngrp) {
         const IP e0 = indptr[i], e1 = indptr[i + 1];
+        if ((int64_t)(e1 - e0) > skip_longer_than) continue;  // left to k_aggregate_long
         const float m = (float)(e1 - e0);
         for (int f0 = gl * VE; f0 < F; f0 += G * VE) {
             float acc[VE];
@@ -122,6 +124,74 @@ __global__ __launch_bounds__(TB) void k_aggregate_fwd(const IP* __restrict__ ind
                 for (int q = 0; q < VE; ++q) acc[q] = acc[q] / m;
             }
             store_f32<T, VE>(A + i * lda + f0, acc);
+        }
+    }
+}
+
+// Rows longer than `longer_than` edges (power-law hubs): one 1024-thread workgroup per row, each
+// of its 16 waves sums a contiguous sixteenth of the row's edges, the 16 partial sums are added in
+// wave order (a fixed order: deterministic).  A workgroup scans 1024 rows for long ones first.
+constexpr int LONG_TB = 1024;
+constexpr int LONG_FCH = 512;   // features per pass: 16 waves x 512 floats of LDS
+template <typename T, int VE, typename IP>
+__global__ __launch_bounds__(LONG_TB) void k_aggregate_long(const IP* __restrict__ indptr,
+                                                            const int32_t* __restrict__ cols, int64_t n,
+                                                            const T* __restrict__ H, int64_t ldh, int F,
+                                                            T* __restrict__ A, int64_t lda, int64_t longer_than) {
+    __shared__ int n_long;
+    __shared__ int64_t long_rows[LONG_TB];
+    __shared__ float part[LONG_TB / 64][LONG_FCH];
+    if (threadIdx.x == 0) n_long = 0;
+    __syncthreads();
+    const int64_t row = (int64_t)blockIdx.x * LONG_TB + threadIdx.x;
+    if (row < n && (int64_t)(indptr[row + 1] - indptr[row]) > longer_than) long_rows[atomicAdd(&n_long, 1)] = row;
+    __syncthreads();
+    const int cnt = n_long;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int NW = LONG_TB / 64;
+    for (int li = 0; li < cnt; ++li) {
+        // the list order depends on the atomics, the result of each row does not
+        const int64_t i = long_rows[li];
+        const IP e0 = indptr[i], e1 = indptr[i + 1];
+        const IP chunk = (e1 - e0 + NW - 1) / NW;
+        const IP w0 = e0 + (IP)wave * chunk, w1 = (w0 + chunk < e1) ? w0 + chunk : e1;
+        const float m = (float)(e1 - e0);
+        for (int fbase = 0; fbase < F; fbase += LONG_FCH) {
+            const int fend = min(F, fbase + LONG_FCH);
+            for (int f0 = fbase + lane * VE; f0 < fend; f0 += 64 * VE) {
+                float acc[VE];
+#pragma unroll
+                for (int q = 0; q < VE; ++q) acc[q] = 0.f;
+                for (IP e = w0; e < w1; e += UNROLL) {
+                    int c[UNROLL];
+#pragma unroll
+                    for (int u = 0; u < UNROLL; ++u) c[u] = (e + u < w1) ? cols[e + u] : -1;
+                    float v[UNROLL][VE];
+#pragma unroll
+                    for (int u = 0; u < UNROLL; ++u) {
+                        if (c[u] >= 0) {
+                            load_f32<T, VE>(H + (int64_t)c[u] * ldh + f0, v[u]);
+                        } else {
+#pragma unroll
+                            for (int q = 0; q < VE; ++q) v[u][q] = 0.f;
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+                        for (int q = 0; q < VE; ++q) acc[q] += v[u][q];
+                }
+#pragma unroll
+                for (int q = 0; q < VE; ++q) part[wave][f0 - fbase + q] = acc[q];
+            }
+            __syncthreads();
+            for (int f = fbase + threadIdx.x; f < fend; f += LONG_TB) {
+                float sum = 0.f;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) sum += part[w][f - fbase];
+                A[i * lda + f] = from_f32<T>(sum / m);
+            }
+            __syncthreads();
         }
     }
 }
@@ -243,11 +313,25 @@ int32_t launch_aggregate_fwd(const IP* indptr, const int32_t* cols, int64_t n_ca
     const size_t es = dtype_size(dtype);
     const int ve = vec_bytes(es, F, {ldh, lda}, {H, A}) / (int)es;
     const int G = group_lanes((F + ve - 1) / ve);
+    // A whole graph (64-bit offsets): one row per lane group, as many workgroups as that takes (the
+    // hardware hands them out as CUs free up, which balances power-law rows), hubs in a second launch.
+    // A sampled block is launched for its upper bound and strides; its rows are at most a fan-out long.
+    constexpr bool whole_graph = sizeof(IP) == 8;
+    const int64_t long_rows = whole_graph ? 2048 : INT64_MAX;
     auto go = [&](auto t, auto vec, auto grp) {
         using T = decltype(t);
         constexpr int VE = decltype(vec)::value, GG = decltype(grp)::value;
-        hipLaunchKernelGGL((k_aggregate_fwd<T, VE, GG, IP>), dim3(grid_rows(n_cap, GG)), dim3(TB), 0, st, indptr, cols,
-                           n_cap, n_d, static_cast<const T*>(H), ldh, F, static_cast<T*>(A), lda, row_ids, map_reset);
+        int grid = grid_rows(n_cap, GG);
+        if (whole_graph) {
+            const int64_t b = (n_cap + (TB / GG) - 1) / (TB / GG);
+            grid = (int)(b > (1 << 24) ? (1 << 24) : b);
+        }
+        hipLaunchKernelGGL((k_aggregate_fwd<T, VE, GG, IP>), dim3(grid), dim3(TB), 0, st, indptr, cols, n_cap, n_d,
+                           static_cast<const T*>(H), ldh, F, static_cast<T*>(A), lda, row_ids, map_reset, long_rows);
+        if (whole_graph)
+            hipLaunchKernelGGL((k_aggregate_long<T, VE, IP>), dim3((int)((n_cap + LONG_TB - 1) / LONG_TB)), dim3(LONG_TB),
+                               0, st, indptr, cols, n_cap, static_cast<const T*>(H), ldh, F, static_cast<T*>(A), lda,
+                               long_rows);
     };
     if (!dispatch(dtype, ve, G, go, go)) {
         set_error("aggregate_fwd: no kernel for dtype %d vec %d group %d", dtype, ve, G);

@@ -17,62 +17,61 @@
 // result is deterministic.
 #include "common.h"
 
+#include <algorithm>
+
 namespace sdt {
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int TB = 256;
-
 // ---- global -> register -> LDS staging of an [R][C] tile, C contiguous in memory ----
-template <typename T, int R, int C, int V, bool ROUND>
+template <typename T, int R, int C, int V, bool ROUND, int TB>
 struct Stage {
     static constexpr int VPR = C / V;
     static constexpr int TOTAL = R * VPR;
     static constexpr int PER = (TOTAL + TB - 1) / TB;
-    float v[PER][V];
+    static constexpr int NB = V * sizeof(T) / 4 > 0 ? V * sizeof(T) / 4 : 1;  // dwords per vector
+    uint32_t raw[PER][NB];
+    uint32_t ok;  // bit p: vector p lies inside the matrix
 
     // rows [r_lo, r_lo+R) x cols [c_lo, c_lo+C) of `base`; zero outside [0,rmax) x [0,cmax).
-    __device__ __forceinline__ void load(const T* __restrict__ base, int64_t ld, int r_lo, int rmax, int c_lo, int cmax,
-                                         const T* __restrict__ mask, int64_t ldmask) {
+    // Needs rmax >= 1 and cmax >= V.  Every load is issued unconditionally from a clamped (valid)
+    // address and nothing touches the loaded registers until store(): with no branch and no
+    // early use the compiler can count the loads in flight, so the wait before the LDS stores
+    // covers only the oldest stage and the younger prefetches keep flying.
+    __device__ __forceinline__ void load(const T* __restrict__ base, int64_t ld, int r_lo, int rmax, int c_lo, int cmax) {
+        ok = 0;
 #pragma unroll
         for (int p = 0; p < PER; ++p) {
             const int idx = threadIdx.x + p * TB;
             const int r = r_lo + idx / VPR, c = c_lo + (idx % VPR) * V;
-            const bool ok = (TOTAL % TB == 0 || idx < TOTAL) && r < rmax && c < cmax;
-            if (ok) {
-                const T* src = base + (int64_t)r * ld + c;
-                if constexpr (V * sizeof(T) == 16) {
-                    uint4 raw = *reinterpret_cast<const uint4*>(src);
-                    unpack(reinterpret_cast<const T*>(&raw), v[p]);
-                } else if constexpr (V * sizeof(T) == 8) {
-                    uint2 raw = *reinterpret_cast<const uint2*>(src);
-                    unpack(reinterpret_cast<const T*>(&raw), v[p]);
-                } else if constexpr (V * sizeof(T) == 4) {
-                    uint32_t raw = *reinterpret_cast<const uint32_t*>(src);
-                    unpack(reinterpret_cast<const T*>(&raw), v[p]);
-                } else {
-                    unpack(src, v[p]);
-                }
-                if (mask) {
-                    const T* ms = mask + (int64_t)r * ldmask + c;
-#pragma unroll
-                    for (int q = 0; q < V; ++q)
-                        if (!(to_f32<T>(ms[q]) > 0.f)) v[p][q] = 0.f;
-                }
-            } else {
-#pragma unroll
-                for (int q = 0; q < V; ++q) v[p][q] = 0.f;
+            if (r < rmax && c < cmax) ok |= 1u << p;
+            const int rr = min(r, rmax - 1), cc = min(c, cmax - V);
+            const T* src = base + (int64_t)rr * ld + cc;
+            if constexpr (V * sizeof(T) == 16) {
+                const uint4 t = *reinterpret_cast<const uint4*>(src);
+                raw[p][0] = t.x; raw[p][1] = t.y; raw[p][2] = t.z; raw[p][3] = t.w;
+            } else if constexpr (V * sizeof(T) == 8) {
+                const uint2 t = *reinterpret_cast<const uint2*>(src);
+                raw[p][0] = t.x; raw[p][1] = t.y;
+            } else if constexpr (V * sizeof(T) == 4) {
+                raw[p][0] = *reinterpret_cast<const uint32_t*>(src);
+            } else {  // one bf16
+                raw[p][0] = *reinterpret_cast<const uint16_t*>(src);
             }
         }
     }
-    __device__ __forceinline__ static void unpack(const T* s, float out[V]) {
-#pragma unroll
-        for (int q = 0; q < V; ++q) {
-            float f = to_f32<T>(s[q]);
-            if constexpr (ROUND) f = bf16_to_f32(f32_to_bf16(f));
-            out[q] = f;
+    // element q of vector p as fp32 (zero if the vector is out of range)
+    __device__ __forceinline__ float value(int p, int q) const {
+        float f;
+        if constexpr (sizeof(T) == 4) {
+            f = __uint_as_float(raw[p][q]);
+        } else {
+            const uint32_t w = raw[p][q >> 1];
+            f = bf16_to_f32((uint16_t)((q & 1) ? (w >> 16) : (w & 0xFFFFu)));
         }
+        if constexpr (ROUND) f = bf16_to_f32(f32_to_bf16(f));
+        return ((ok >> p) & 1u) ? f : 0.f;
     }
     // into lds[R][LD]
     template <int LD>
@@ -85,11 +84,12 @@ struct Stage {
                 if constexpr (V % 4 == 0) {
 #pragma unroll
                     for (int q = 0; q < V; q += 4)
-                        *reinterpret_cast<float4*>(d + q) = make_float4(v[p][q], v[p][q + 1], v[p][q + 2], v[p][q + 3]);
+                        *reinterpret_cast<float4*>(d + q) =
+                            make_float4(value(p, q), value(p, q + 1), value(p, q + 2), value(p, q + 3));
                 } else if constexpr (V == 2) {
-                    *reinterpret_cast<float2*>(d) = make_float2(v[p][0], v[p][1]);
+                    *reinterpret_cast<float2*>(d) = make_float2(value(p, 0), value(p, 1));
                 } else {
-                    d[0] = v[p][0];
+                    d[0] = value(p, 0);
                 }
             }
         }
@@ -99,14 +99,14 @@ struct Stage {
 
 // One BK-deep step of the wave's (TM*32) x (TN*32) tile.
 //  A_KC: As is [BM][LD_KC] else [BK][LDA_OC];  B_KC likewise for Bs.
+// The operand fragments of chunk c+1 are read from LDS before the MFMAs of chunk c are
+// issued, so the LDS latency hides behind matrix work even with one wave per SIMD.
 template <int BK, int TM, int TN, bool A_KC, bool B_KC, int LDA_OC, int LDB_OC>
-__device__ __forceinline__ void mma_step(const float* As, const float* Bs, int arow0, int bcol0,
-                                         floatx16 (&acc)[TM][TN]) {
-    constexpr int LD_KC = BK + 4;  // LDS row stride of a k-contiguous operand tile
-    const int lane = threadIdx.x & 63, i = lane & 31, kh = lane >> 5;
-#pragma unroll
-    for (int c = 0; c < BK / 8; ++c) {
-        float a[TM][4], b[TN][4];
+struct Frag {
+    float a[TM][4], b[TN][4];
+    __device__ __forceinline__ void load(const float* As, const float* Bs, int arow0, int bcol0, int c) {
+        constexpr int LD_KC = BK + 4;  // LDS row stride of a k-contiguous operand tile
+        const int lane = threadIdx.x & 63, i = lane & 31, kh = lane >> 5;
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
             if constexpr (A_KC) {
@@ -127,6 +127,8 @@ __device__ __forceinline__ void mma_step(const float* As, const float* Bs, int a
                 for (int s = 0; s < 4; ++s) b[tn][s] = Bs[(c * 8 + kh * 4 + s) * LDB_OC + bcol0 + tn * 32 + i];
             }
         }
+    }
+    __device__ __forceinline__ void mma(floatx16 (&acc)[TM][TN]) const {
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
@@ -135,22 +137,48 @@ __device__ __forceinline__ void mma_step(const float* As, const float* Bs, int a
                 for (int tn = 0; tn < TN; ++tn)
                     acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[tm][s], b[tn][s], acc[tm][tn], 0, 0, 0);
     }
+};
+
+template <int BK, int TM, int TN, bool A_KC, bool B_KC, int LDA_OC, int LDB_OC>
+__device__ __forceinline__ void mma_step(const float* As, const float* Bs, int arow0, int bcol0,
+                                         floatx16 (&acc)[TM][TN]) {
+    constexpr int NC = BK / 8;
+    Frag<BK, TM, TN, A_KC, B_KC, LDA_OC, LDB_OC> f[2];
+    f[0].load(As, Bs, arow0, bcol0, 0);
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        if (c + 1 < NC) f[(c + 1) & 1].load(As, Bs, arow0, bcol0, c + 1);
+        f[c & 1].mma(acc);
+    }
 }
 
 // Row/column of accumulator register r of a 32x32 MFMA tile held by `lane`.
 __device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 __device__ __forceinline__ int acc_col(int lane) { return lane & 31; }
 
-template <int BM_, int BN_>
+// Workgroup tile BM x BN, reduction depth BK per step, WM x WN wavefronts.
+template <int BM_, int BN_, int BK_, int WM_, int WN_>
 struct Tile {
-    static constexpr int BM = BM_, BN = BN_;
-    static constexpr int WM = 2, WN = 2;               // 2 x 2 wavefronts
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
+    static constexpr int NT = 64 * WM * WN;            // threads per workgroup
     static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     static constexpr int LDA_OC = BM + 4, LDB_OC = BN + 4;
-    // depth of one reduction step, sized so that two LDS buffers of both operands fit in 64 KB
-    static constexpr int BK = BM >= 128 ? 16 : 32;
     static constexpr int LD_KC = BK + 4;
+    static_assert(TM >= 1 && TN >= 1 && BK % 8 == 0, "tile shape");
 };
+
+// The hardware hands consecutive workgroup ids to the eight XCDs in turn, and every XCD has
+// an L2 of its own.  Renumber the workgroups so that each XCD works on a contiguous run of
+// tiles (x fastest): the tiles that share an operand panel then share one L2.  Only the first
+// `valid` tiles carry work (the grid is sized for an upper bound of the row count); they are
+// dealt out evenly over the XCDs.  Returns the tile id in [0, valid), or -1 for a workgroup
+// that has nothing to do.  Needs valid <= number of workgroups.
+__device__ __forceinline__ int xcd_contiguous_id(int valid) {
+    const int id = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const int xcd = id & 7, slot = id >> 3, q = valid >> 3, r = valid & 7;
+    if (slot >= q + (xcd < r ? 1 : 0)) return -1;
+    return (xcd < r ? xcd * (q + 1) : r * (q + 1) + (xcd - r) * q) + slot;
+}
 
 __device__ __forceinline__ void zero_acc(floatx16& a) {
 #pragma unroll
@@ -161,8 +189,14 @@ __device__ __forceinline__ void zero_acc(floatx16& a) {
 // steps ahead of the MFMAs (two register stages), LDS is double-buffered, and one barrier
 // per step suffices: a buffer is rewritten only after the barrier of the step in between,
 // which every wave passes after it has finished reading that buffer.
-//   fetch(it, sa, sb)  issues the global loads of step `it` into a register stage
+//   fetch(it, sa, sb)  issues the global loads of step `it` into a register stage; for it >= nit
+//                      it must still be callable (Stage::load clamps addresses and yields zeros)
 //   hook(Bs)           optional extra work on the staged B tile (bias gradient)
+// Nothing in the loop is conditional: the step count is rounded up to even (a surplus step
+// multiplies zero tiles) and the two fetches past the end re-read valid addresses and are
+// dropped.  Every path then has the same number of loads in flight at every wait, which lets
+// the compiler wait for the older register stage only (vmcnt = loads of the younger one).
+// Requires nit >= 1.
 template <typename TL, bool A_KC, bool B_KC, typename SA, typename SB, typename Fetch, typename Hook>
 __device__ __forceinline__ void gemm_mainloop(int nit, float* As, float* Bs, Fetch&& fetch, Hook&& hook,
                                               floatx16 (&acc)[TL::TM][TL::TN]) {
@@ -173,23 +207,25 @@ __device__ __forceinline__ void gemm_mainloop(int nit, float* As, float* Bs, Fet
     const int a0 = wm * (TL::BM / TL::WM), b0 = wn * (TL::BN / TL::WN);
     SA sa0, sa1;
     SB sb0, sb1;
-    if (nit > 0) fetch(0, sa0, sb0);
-    if (nit > 1) fetch(1, sa1, sb1);
+    fetch(0, sa0, sb0);
+    __builtin_amdgcn_sched_barrier(0);  // issue order = consumption order (the load counter is in-order)
+    fetch(1, sa1, sb1);
+    __builtin_amdgcn_sched_barrier(0);
     for (int it = 0; it < nit; it += 2) {
         sa0.template store<LDA>(As);
         sb0.template store<LDB>(Bs);
         __syncthreads();
-        if (it + 2 < nit) fetch(it + 2, sa0, sb0);
+        fetch(it + 2, sa0, sb0);
+        __builtin_amdgcn_sched_barrier(0);  // keep the loads here: the scheduler would sink them next to their use
         hook(Bs);
         mma_step<BK, TL::TM, TL::TN, A_KC, B_KC, TL::LDA_OC, TL::LDB_OC>(As, Bs, a0, b0, acc);
-        if (it + 1 < nit) {
-            sa1.template store<LDA>(As + A_ELEMS);
-            sb1.template store<LDB>(Bs + B_ELEMS);
-            __syncthreads();
-            if (it + 3 < nit) fetch(it + 3, sa1, sb1);
-            hook(Bs + B_ELEMS);
-            mma_step<BK, TL::TM, TL::TN, A_KC, B_KC, TL::LDA_OC, TL::LDB_OC>(As + A_ELEMS, Bs + B_ELEMS, a0, b0, acc);
-        }
+        sa1.template store<LDA>(As + A_ELEMS);
+        sb1.template store<LDB>(Bs + B_ELEMS);
+        __syncthreads();
+        fetch(it + 3, sa1, sb1);
+        __builtin_amdgcn_sched_barrier(0);
+        hook(Bs + B_ELEMS);
+        mma_step<BK, TL::TM, TL::TN, A_KC, B_KC, TL::LDA_OC, TL::LDB_OC>(As + A_ELEMS, Bs + B_ELEMS, a0, b0, acc);
     }
 }
 
@@ -210,17 +246,17 @@ __device__ __forceinline__ void for_each_acc(const floatx16 (&acc)[TL::TM][TL::T
 // ---------------------------------------------------------------------------------
 // forward: Y[n,out] = act(Hself[n,in] Wself[in,out] + A[n,in] Wneigh[in,out] + b)
 // ---------------------------------------------------------------------------------
-template <typename TH, typename TY, int BM, int BN, int VA, int VB, bool ROUNDW>
-__global__ __launch_bounds__(TB) void k_linear_fwd(const TH* __restrict__ Hself, int64_t ldh,
-                                                   const TH* __restrict__ Agg, int64_t lda, int n_cap,
-                                                   const int32_t* n_d, int in, int out, const float* __restrict__ W,
-                                                   const float* __restrict__ bias, int relu, TY* __restrict__ Y,
-                                                   int64_t ldy) {
-    using TL = Tile<BM, BN>;
-    constexpr int BK = TL::BK;
+template <typename TH, typename TY, typename TL, int VA, int VB, bool ROUNDW>
+__global__ __launch_bounds__(TL::NT) void k_linear_fwd(const TH* __restrict__ Hself, int64_t ldh,
+                                                       const TH* __restrict__ Agg, int64_t lda, int n_cap,
+                                                       const int32_t* n_d, int in, int out,
+                                                       const float* __restrict__ W, const float* __restrict__ bias,
+                                                       int relu, TY* __restrict__ Y, int64_t ldy) {
+    constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK;
     const int n = dev_count(n_cap, n_d);
-    const int row0 = blockIdx.y * BM, col0 = blockIdx.x * BN;
-    if (row0 >= n) return;
+    const int id = xcd_contiguous_id((int)gridDim.x * ((n + BM - 1) / BM));
+    if (id < 0) return;
+    const int row0 = (id / (int)gridDim.x) * BM, col0 = (id % (int)gridDim.x) * BN;
     __shared__ __align__(16) float As[2 * BM * TL::LD_KC];
     __shared__ __align__(16) float Bs[2 * BK * TL::LDB_OC];
     floatx16 acc[TL::TM][TL::TN];
@@ -228,13 +264,13 @@ __global__ __launch_bounds__(TB) void k_linear_fwd(const TH* __restrict__ Hself,
     for (int a = 0; a < TL::TM; ++a)
 #pragma unroll
         for (int b = 0; b < TL::TN; ++b) zero_acc(acc[a][b]);
-    using SA = Stage<TH, BM, BK, VA, false>;
-    using SB = Stage<float, BK, BN, VB, ROUNDW>;
+    using SA = Stage<TH, BM, BK, VA, false, TL::NT>;
+    using SB = Stage<float, BK, BN, VB, ROUNDW, TL::NT>;
     const int nk = (in + BK - 1) / BK;
     auto fetch = [&](int it, SA& sa, SB& sb) {
-        const int ph = it >= nk, k0 = (it - ph * nk) * BK;
-        sa.load(ph ? Agg : Hself, ph ? lda : ldh, row0, n, k0, in, nullptr, 0);
-        sb.load(W + (int64_t)ph * in * out, out, k0, in, col0, out, nullptr, 0);
+        const int ph = it >= nk, k0 = (it - ph * nk) * BK;  // k0 >= in past the last step: zeros
+        sa.load(ph ? Agg : Hself, ph ? lda : ldh, row0, n, k0, in);
+        sb.load(W + (int64_t)ph * in * out, out, k0, in, col0, out);
     };
     gemm_mainloop<TL, true, false, SA, SB>(2 * nk, As, Bs, fetch, [](const float*) {}, acc);
     for_each_acc<TL>(acc, [&](int r, int c, float v) {
@@ -250,17 +286,18 @@ __global__ __launch_bounds__(TB) void k_linear_fwd(const TH* __restrict__ Hself,
 // ---------------------------------------------------------------------------------
 // input gradient: dIn_h[n,in] = dZ[n,out] W_h[in,out]^T, h = blockIdx.z (0 self, 1 neigh)
 // ---------------------------------------------------------------------------------
-template <typename TD, typename TH, int BM, int BN, int VD, int VW, bool ROUND>
-__global__ __launch_bounds__(TB) void k_linear_bwd_input(const TD* __restrict__ dY, int64_t lddy,
-                                                         const TD* __restrict__ Ymask, int64_t ldy, int n_cap,
-                                                         const int32_t* n_d, int in, int out,
-                                                         const float* __restrict__ W, TH* __restrict__ dSelf,
-                                                         TH* __restrict__ dAgg, int64_t ldi) {
-    using TL = Tile<BM, BN>;
-    constexpr int BK = TL::BK;
+template <typename TD, typename TH, typename TL, int VD, int VW, bool ROUND>
+__global__ __launch_bounds__(TL::NT) void k_linear_bwd_input(const TD* __restrict__ dY, int64_t lddy, int n_cap,
+                                                             const int32_t* n_d, int in, int out,
+                                                             const float* __restrict__ W, TH* __restrict__ dSelf,
+                                                             TH* __restrict__ dAgg, int64_t ldi) {
+    constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK;
     const int n = dev_count(n_cap, n_d);
-    const int row0 = blockIdx.y * BM, col0 = blockIdx.x * BN, half = blockIdx.z;
-    if (row0 >= n) return;
+    // x fastest, then the half, then the row tile: the workgroups that read one panel of dY are neighbours
+    const int id = xcd_contiguous_id((int)gridDim.x * 2 * ((n + BM - 1) / BM));
+    if (id < 0) return;
+    const int col0 = (id % (int)gridDim.x) * BN, half = (id / (int)gridDim.x) % 2;
+    const int row0 = (id / (int)gridDim.x / 2) * BM;
     __shared__ __align__(16) float As[2 * BM * TL::LD_KC];
     __shared__ __align__(16) float Bs[2 * BN * TL::LD_KC];
     floatx16 acc[TL::TM][TL::TN];
@@ -268,12 +305,12 @@ __global__ __launch_bounds__(TB) void k_linear_bwd_input(const TD* __restrict__ 
     for (int a = 0; a < TL::TM; ++a)
 #pragma unroll
         for (int b = 0; b < TL::TN; ++b) zero_acc(acc[a][b]);
-    using SA = Stage<TD, BM, BK, VD, ROUND && sizeof(TD) == 4>;
-    using SB = Stage<float, BN, BK, VW, ROUND>;
+    using SA = Stage<TD, BM, BK, VD, ROUND && sizeof(TD) == 4, TL::NT>;
+    using SB = Stage<float, BN, BK, VW, ROUND, TL::NT>;
     const float* Wh = W + (int64_t)half * in * out;
     auto fetch = [&](int it, SA& sa, SB& sb) {
-        sa.load(dY, lddy, row0, n, it * BK, out, Ymask, ldy);
-        sb.load(Wh, out, col0, in, it * BK, out, nullptr, 0);
+        sa.load(dY, lddy, row0, n, it * BK, out);
+        sb.load(Wh, out, col0, in, it * BK, out);
     };
     gemm_mainloop<TL, true, true, SA, SB>((out + BK - 1) / BK, As, Bs, fetch, [](const float*) {}, acc);
     TH* dst = half ? dAgg : dSelf;
@@ -287,21 +324,23 @@ __global__ __launch_bounds__(TB) void k_linear_bwd_input(const TD* __restrict__ 
 // weight gradient partials: P[s][h*in + m][o] = sum over the rows r of split s of
 //   X_h[r, m] dZ[r, o],  X_0 = Hself, X_1 = A;  h = blockIdx.z % 2, s = blockIdx.z / 2
 // ---------------------------------------------------------------------------------
-template <typename TD, typename TH, int BM, int BN, int VH, int VD, bool ROUND>
-__global__ __launch_bounds__(TB) void k_linear_bwd_weight(const TH* __restrict__ Hself, int64_t ldh,
-                                                          const TH* __restrict__ Agg, int64_t lda,
-                                                          const TD* __restrict__ dY, int64_t lddy,
-                                                          const TD* __restrict__ Ymask, int64_t ldy, int n_cap,
-                                                          const int32_t* n_d, int in, int out, int splits,
-                                                          float* __restrict__ P, float* __restrict__ Q) {
-    using TL = Tile<BM, BN>;
-    constexpr int BK = TL::BK;
+template <typename TD, typename TH, typename TL, int VH, int VD, bool ROUND>
+__global__ __launch_bounds__(TL::NT) void k_linear_bwd_weight(const TH* __restrict__ Hself, int64_t ldh,
+                                                              const TH* __restrict__ Agg, int64_t lda,
+                                                              const TD* __restrict__ dY, int64_t lddy, int n_cap,
+                                                              const int32_t* n_d, int in, int out, int splits,
+                                                              float* __restrict__ P, float* __restrict__ Q) {
+    constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK;
     const int n = dev_count(n_cap, n_d);
-    const int half = blockIdx.z & 1, split = blockIdx.z >> 1;
+    // grid (out tiles, in tiles, 2 * splits); x fastest keeps the readers of one X panel on one L2
+    const int id = xcd_contiguous_id((int)(gridDim.x * gridDim.y * gridDim.z));  // every tile carries work
+    const int bx = id % (int)gridDim.x, by = (id / (int)gridDim.x) % (int)gridDim.y;
+    const int bz = id / (int)(gridDim.x * gridDim.y);
+    const int half = bz & 1, split = bz >> 1;
     // the first row-tile of the self half also sums the columns of its dZ tiles (bias gradient)
-    const bool do_bias = Q != nullptr && half == 0 && blockIdx.y == 0;
+    const bool do_bias = Q != nullptr && half == 0 && by == 0;
     float bsum = 0.f;
-    const int row0 = blockIdx.y * BM /* feature m */, col0 = blockIdx.x * BN /* output o */;
+    const int row0 = by * BM /* feature m */, col0 = bx * BN /* output o */;
     const int chunk = ((n + splits - 1) / splits + BK - 1) / BK * BK;
     const int r_begin = split * chunk, r_end = min(n, r_begin + chunk);
     __shared__ __align__(16) float As[2 * BK * TL::LDA_OC];
@@ -311,14 +350,14 @@ __global__ __launch_bounds__(TB) void k_linear_bwd_weight(const TH* __restrict__
     for (int a = 0; a < TL::TM; ++a)
 #pragma unroll
         for (int b = 0; b < TL::TN; ++b) zero_acc(acc[a][b]);
-    using SA = Stage<TH, BK, BM, VH, false>;
-    using SB = Stage<TD, BK, BN, VD, ROUND && sizeof(TD) == 4>;
+    using SA = Stage<TH, BK, BM, VH, false, TL::NT>;
+    using SB = Stage<TD, BK, BN, VD, ROUND && sizeof(TD) == 4, TL::NT>;
     const TH* X = half ? Agg : Hself;
     const int64_t ldx = half ? lda : ldh;
     const int nit = r_end > r_begin ? (r_end - r_begin + BK - 1) / BK : 0;
     auto fetch = [&](int it, SA& sa, SB& sb) {
-        sa.load(X, ldx, r_begin + it * BK, r_end, row0, in, nullptr, 0);
-        sb.load(dY, lddy, r_begin + it * BK, r_end, col0, out, Ymask, ldy);
+        sa.load(X, ldx, r_begin + it * BK, r_end, row0, in);
+        sb.load(dY, lddy, r_begin + it * BK, r_end, col0, out);
     };
     auto hook = [&](const float* Bcur) {
         if (do_bias && (int)threadIdx.x < BN) {
@@ -326,7 +365,7 @@ __global__ __launch_bounds__(TB) void k_linear_bwd_weight(const TH* __restrict__
             for (int k = 0; k < BK; ++k) bsum += Bcur[k * TL::LDB_OC + threadIdx.x];
         }
     };
-    gemm_mainloop<TL, false, false, SA, SB>(nit, As, Bs, fetch, hook, acc);
+    if (nit > 0) gemm_mainloop<TL, false, false, SA, SB>(nit, As, Bs, fetch, hook, acc);
     if (do_bias && (int)threadIdx.x < BN && col0 + (int)threadIdx.x < out)
         Q[(int64_t)split * out + col0 + threadIdx.x] = bsum;
     float* dst = P + ((int64_t)split * 2 * in + (int64_t)half * in) * out;
@@ -341,6 +380,7 @@ __global__ __launch_bounds__(TB) void k_linear_bwd_weight(const TH* __restrict__
 // A workgroup covers 64 consecutive elements with 4 threads each: thread g adds the partials
 // g, g+4, g+8, ... and the four sums are combined in the order 0,1,2,3 -- a fixed order, so
 // the result is deterministic, with four times as many loads in flight as one thread per element.
+constexpr int TB = 256;
 __global__ __launch_bounds__(TB) void k_reduce_partials(const float* __restrict__ P, const float* __restrict__ Q,
                                                         int splits, int64_t n_w, int out, float* __restrict__ dW,
                                                         float* __restrict__ db, float* W_upd, float* b_upd, float lr,
@@ -397,11 +437,33 @@ int vec_elems(size_t es, int width, std::initializer_list<int64_t> lds, std::ini
     return v > 4 && es == 4 ? 4 : v;
 }
 
+// dZ masked by the ReLU of the layer's own output: M[r][c] = Y[r][c] > 0 ? dY[r][c] : 0
+template <typename TD>
+__global__ __launch_bounds__(256) void k_relu_mask(const TD* __restrict__ dY, int64_t lddy, const TD* __restrict__ Y,
+                                                   int64_t ldy, int n_cap, const int32_t* n_d, int out,
+                                                   TD* __restrict__ M) {
+    const int n = dev_count(n_cap, n_d);
+    const int64_t total = (int64_t)n * out;
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = i / out;
+        const int c = (int)(i - r * out);
+        const TD g = dY[r * lddy + c];
+        M[i] = to_f32<TD>(Y[r * ldy + c]) > 0.f ? g : from_f32<TD>(0.f);
+    }
+}
+
+// Number of row ranges the weight gradient is split into.  The product has only
+// ceil(in/BM) * ceil(out/BN) * 2 output tiles (80 for a 602 x 256 layer), far fewer than the chip
+// has wavefront slots, so the batch rows are split until about four workgroups per CU exist;
+// bounded so that a range keeps >= 128 rows and the partial products stay within 16 MB (they are
+// written and read back once by the reduction).
 int weight_splits(int n_cap, int in, int out, int BM, int BN) {
     const int tiles = ceil_div(in, BM) * ceil_div(out, BN) * 2;
-    int s = ceil_div(256, tiles);  // about one workgroup per CU
-    const int max_s = ceil_div(n_cap > 0 ? n_cap : 1, 256);
-    if (s > max_s) s = max_s;
+    int s = ceil_div(1024, tiles);
+    const int max_rows = ceil_div(n_cap > 0 ? n_cap : 1, 128);
+    const int64_t max_bytes = ((int64_t)16 << 20) / ((int64_t)2 * in * out * 4);
+    if (s > max_rows) s = max_rows;
+    if (s > max_bytes) s = (int)max_bytes;
     if (s < 1) s = 1;
     return s;
 }
@@ -422,70 +484,62 @@ using namespace sdt;
 
 namespace {
 
-template <typename TH, typename TY, int BM, int BN>
+// Tile shapes, picked by measurement on MI355X (fp32 MFMA, out = 256):
+using TileS = Tile<64, 64, 32, 2, 2>;     // forward / input gradient of mini-batch sized layers
+using TileW = Tile<64, 64, 16, 2, 2>;     // weight gradient (short row ranges: a shallower step wins)
+using TileM = Tile<128, 128, 32, 4, 4>;   // forward from about 512 tiles of 128 x 128
+using TileL = Tile<128, 256, 16, 2, 4>;   // forward of whole-graph sized layers
+
+template <typename TH, typename TY, typename TL>
 void launch_fwd(const void* Hself, int64_t ldh, const void* A, int64_t lda, int n_cap, const int32_t* n_d, int in,
-                int out, const float* W, const float* b, int relu, void* Y, int64_t ldy, bool roundw, hipStream_t st) {
+                int out, const float* W, const float* b, int relu, void* Y, int64_t ldy, hipStream_t st) {
+    constexpr bool ROUNDW = sizeof(TH) == 2;  // bf16 activations: weights enter the product rounded to bf16
     const int va = vec_elems(sizeof(TH), in, {ldh, lda}, {Hself, A});
     const int vb = vec_elems(4, out, {(int64_t)out}, {W});
-    dim3 grid(ceil_div(out, BN), ceil_div(n_cap, BM));
+    dim3 grid(ceil_div(out, TL::BN), ceil_div(n_cap, TL::BM));
     SDT_VEC_SWITCH(va, (16 / sizeof(TH)), {
         constexpr int VA = V;
         SDT_VEC_SWITCH(vb, 4, {
             constexpr int VB = V;
-            if (roundw)
-                hipLaunchKernelGGL((k_linear_fwd<TH, TY, BM, BN, VA, VB, true>), grid, dim3(TB), 0, st,
-                                   static_cast<const TH*>(Hself), ldh, static_cast<const TH*>(A), lda, n_cap, n_d, in,
-                                   out, W, b, relu, static_cast<TY*>(Y), ldy);
-            else
-                hipLaunchKernelGGL((k_linear_fwd<TH, TY, BM, BN, VA, VB, false>), grid, dim3(TB), 0, st,
-                                   static_cast<const TH*>(Hself), ldh, static_cast<const TH*>(A), lda, n_cap, n_d, in,
-                                   out, W, b, relu, static_cast<TY*>(Y), ldy);
+            hipLaunchKernelGGL((k_linear_fwd<TH, TY, TL, VA, VB, ROUNDW>), grid, dim3(TL::NT), 0, st,
+                               static_cast<const TH*>(Hself), ldh, static_cast<const TH*>(A), lda, n_cap, n_d, in, out, W,
+                               b, relu, static_cast<TY*>(Y), ldy);
         })
     })
 }
 
-template <typename TD, typename TH, int BM, int BN>
-void launch_bwd(const void* dY, int64_t lddy, const void* Ymask, int64_t ldy, const void* Hself, int64_t ldh,
-                const void* A, int64_t lda, int n_cap, const int32_t* n_d, int in, int out, const float* W, float* dW,
-                float* db, void* dSelf, void* dAgg, int64_t ldi, float* P, float* Q, int splits, bool round,
-                const BwdExtras& ex, hipStream_t st) {
-    const int vd = vec_elems(sizeof(TD), out, {lddy, Ymask ? ldy : lddy}, {dY, Ymask});
+template <typename TD, typename TH>
+void launch_bwd(const void* dY, int64_t lddy, const void* Hself, int64_t ldh, const void* A, int64_t lda, int n_cap,
+                const int32_t* n_d, int in, int out, const float* W, float* dW, float* db, void* dSelf, void* dAgg,
+                int64_t ldi, float* P, float* Q, int splits, const BwdExtras& ex, hipStream_t st) {
+    constexpr bool ROUND = sizeof(TH) == 2;  // bf16 activations: fp32 operands enter the products rounded to bf16
+    const int vd = vec_elems(sizeof(TD), out, {lddy}, {dY});
     const int vh = vec_elems(sizeof(TH), in, {ldh, lda}, {Hself, A});
     const int vw = vec_elems(4, out, {(int64_t)out}, {W});
     const TD* dYt = static_cast<const TD*>(dY);
-    const TD* Ym = static_cast<const TD*>(Ymask);
     // weight gradient partials
     {
-        dim3 grid(ceil_div(out, BN), ceil_div(in, BM), 2 * splits);
+        using TL = TileW;
+        dim3 grid(ceil_div(out, TL::BN), ceil_div(in, TL::BM), 2 * splits);
         SDT_VEC_SWITCH(vh, (16 / sizeof(TH)), {
             constexpr int VH = V;
             SDT_VEC_SWITCH(vd, (16 / sizeof(TD)), {
                 constexpr int VD = V;
-                if (round)
-                    hipLaunchKernelGGL((k_linear_bwd_weight<TD, TH, BM, BN, VH, VD, true>), grid, dim3(TB), 0, st,
-                                       static_cast<const TH*>(Hself), ldh, static_cast<const TH*>(A), lda, dYt, lddy,
-                                       Ym, ldy, n_cap, n_d, in, out, splits, P, Q);
-                else
-                    hipLaunchKernelGGL((k_linear_bwd_weight<TD, TH, BM, BN, VH, VD, false>), grid, dim3(TB), 0, st,
-                                       static_cast<const TH*>(Hself), ldh, static_cast<const TH*>(A), lda, dYt, lddy,
-                                       Ym, ldy, n_cap, n_d, in, out, splits, P, Q);
+                hipLaunchKernelGGL((k_linear_bwd_weight<TD, TH, TL, VH, VD, ROUND>), grid, dim3(TL::NT), 0, st,
+                                   static_cast<const TH*>(Hself), ldh, static_cast<const TH*>(A), lda, dYt, lddy, n_cap,
+                                   n_d, in, out, splits, P, Q);
             })
         })
     }
-    if (dSelf) {
-        dim3 grid(ceil_div(in, BN), ceil_div(n_cap, BM), 2);
+    if (dSelf && n_cap > 0) {
+        using TL = TileS;
+        dim3 grid(ceil_div(in, TL::BN), ceil_div(n_cap, TL::BM), 2);
         SDT_VEC_SWITCH(vd, (16 / sizeof(TD)), {
             constexpr int VD = V;
             SDT_VEC_SWITCH(vw, 4, {
                 constexpr int VW = V;
-                if (round)
-                    hipLaunchKernelGGL((k_linear_bwd_input<TD, TH, BM, BN, VD, VW, true>), grid, dim3(TB), 0, st, dYt,
-                                       lddy, Ym, ldy, n_cap, n_d, in, out, W, static_cast<TH*>(dSelf),
-                                       static_cast<TH*>(dAgg), ldi);
-                else
-                    hipLaunchKernelGGL((k_linear_bwd_input<TD, TH, BM, BN, VD, VW, false>), grid, dim3(TB), 0, st, dYt,
-                                       lddy, Ym, ldy, n_cap, n_d, in, out, W, static_cast<TH*>(dSelf),
-                                       static_cast<TH*>(dAgg), ldi);
+                hipLaunchKernelGGL((k_linear_bwd_input<TD, TH, TL, VD, VW, ROUND>), grid, dim3(TL::NT), 0, st, dYt, lddy,
+                                   n_cap, n_d, in, out, W, static_cast<TH*>(dSelf), static_cast<TH*>(dAgg), ldi);
             })
         })
     }
@@ -495,7 +549,6 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Ymask, int64_t ldy, co
                        splits, n_w, out, dW, db, ex.W_upd, ex.b_upd, ex.lr, ex.row_loss, ex.n_loss, ex.loss_out);
 }
 
-constexpr int FBM = 64, FBN = 64;  // tile of the mini-batch sized products
 
 }  // namespace
 
@@ -511,25 +564,46 @@ extern "C" int32_t sdt_sage_linear_fwd(const void* Hself, int64_t ldh, const voi
     if (n_cap == 0) return SDT_OK;
     SDT_REQUIRE(Hself && A && W && Y, SDT_ERR_INVALID_ARG, "sdt_sage_linear_fwd: null pointer");
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const bool big = (int64_t)ceil_div(n_cap, 128) * ceil_div(out, 128) >= 512;
-    if (dtype == SDT_F32) {
-        if (big)
-            launch_fwd<float, float, 128, 128>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, false, st);
-        else
-            launch_fwd<float, float, FBM, FBN>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, false, st);
-    } else if (y_dtype == SDT_BF16) {
-        launch_fwd<bf16_t, bf16_t, FBM, FBN>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, true, st);
-    } else {
-        launch_fwd<bf16_t, float, FBM, FBN>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, true, st);
-    }
+    // tile by problem size: the large tiles need enough workgroups to fill 256 CUs several times over
+    const int64_t t128 = (int64_t)ceil_div(n_cap, 128) * ceil_div(out, 128);
+    const int cls = (t128 >= 2048 && out >= 256) ? 2 : t128 >= 512 ? 1 : 0;
+#define SDT_FWD(TH, TY)                                                                                            \
+    do {                                                                                                           \
+        if (cls == 2) launch_fwd<TH, TY, TileL>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, st);  \
+        else if (cls == 1) launch_fwd<TH, TY, TileM>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, st); \
+        else launch_fwd<TH, TY, TileS>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, st);           \
+    } while (0)
+    if (dtype == SDT_F32) SDT_FWD(float, float);
+#undef SDT_FWD
+    // bf16 activations are widened on the way into LDS; the small tile hides that best
+    else if (y_dtype == SDT_BF16)
+        launch_fwd<bf16_t, bf16_t, TileS>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, st);
+    else
+        launch_fwd<bf16_t, float, TileS>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, st);
     SDT_CHECK_LAUNCH("linear_fwd");
     return SDT_OK;
 }
 
+namespace {
+// workspace of the projection backward: dW partials | db partials | ReLU-masked copy of dY
+struct BwdWs {
+    int splits;
+    size_t p_off, q_off, m_off, total;
+};
+BwdWs bwd_ws(int32_t n_cap, int32_t in, int32_t out) {
+    BwdWs w;
+    w.splits = weight_splits(n_cap, in, out, TileW::BM, TileW::BN);
+    w.p_off = 0;
+    w.q_off = align_up((size_t)w.splits * 2 * in * out * sizeof(float), 256);
+    w.m_off = w.q_off + align_up((size_t)w.splits * out * sizeof(float), 256);
+    w.total = w.m_off + align_up((size_t)n_cap * out * sizeof(float), 256);
+    return w;
+}
+}  // namespace
+
 extern "C" size_t sdt_linear_bwd_workspace_bytes(int32_t n_cap, int32_t in, int32_t out) {
     if (n_cap < 0 || in <= 0 || out <= 0) return 0;
-    const int s = weight_splits(n_cap, in, out, FBM, FBN);
-    return align_up((size_t)s * 2 * in * out * sizeof(float), 256) + align_up((size_t)s * out * sizeof(float), 256);
+    return bwd_ws(n_cap, in, out).total;
 }
 
 namespace sdt {
@@ -556,22 +630,36 @@ int32_t linear_bwd(const void* dY, int64_t lddy, int32_t dy_dtype, const void* Y
                 "sdt_sage_linear_bwd: pass both input gradients (ldi >= in) or neither");
     SDT_REQUIRE(!relu || (Y && ldy >= out && dy_dtype == dtype), SDT_ERR_INVALID_ARG,
                 "sdt_sage_linear_bwd: relu needs Y in the dtype of dY");
-    const size_t need = sdt_linear_bwd_workspace_bytes(n_cap, in, out);
-    SDT_REQUIRE(ws && ws_bytes >= need && aligned16(ws), SDT_ERR_WORKSPACE,
-                "sdt_sage_linear_bwd: workspace of %zu bytes needed, %zu given", need, ws_bytes);
-    const int splits = weight_splits(n_cap, in, out, FBM, FBN);
-    float* P = static_cast<float*>(ws);
-    float* Q = reinterpret_cast<float*>(static_cast<char*>(ws) + align_up((size_t)splits * 2 * in * out * sizeof(float), 256));
-    const void* Ym = relu ? Y : nullptr;
+    const BwdWs w = bwd_ws(n_cap, in, out);
+    SDT_REQUIRE(ws && ws_bytes >= w.total && aligned16(ws), SDT_ERR_WORKSPACE,
+                "sdt_sage_linear_bwd: workspace of %zu bytes needed, %zu given", w.total, ws_bytes);
+    char* base = static_cast<char*>(ws);
+    float* P = reinterpret_cast<float*>(base + w.p_off);
+    float* Q = reinterpret_cast<float*>(base + w.q_off);
+    const void* dYm = dY;
+    int64_t ldm = lddy;
+    if (relu && n_cap > 0) {
+        // the matrix products take dZ already masked by the layer's own ReLU: one elementwise pass
+        void* M = base + w.m_off;
+        const int blocks = (int)std::min<int64_t>(((int64_t)n_cap * out + 255) / 256, 8192);
+        if (dy_dtype == SDT_F32)
+            hipLaunchKernelGGL(k_relu_mask<float>, dim3(blocks), dim3(256), 0, st, static_cast<const float*>(dY), lddy,
+                               static_cast<const float*>(Y), ldy, n_cap, n_d, out, static_cast<float*>(M));
+        else
+            hipLaunchKernelGGL(k_relu_mask<bf16_t>, dim3(blocks), dim3(256), 0, st, static_cast<const bf16_t*>(dY), lddy,
+                               static_cast<const bf16_t*>(Y), ldy, n_cap, n_d, out, static_cast<bf16_t*>(M));
+        dYm = M;
+        ldm = out;
+    }
     if (dtype == SDT_F32)
-        launch_bwd<float, float, FBM, FBN>(dY, lddy, Ym, ldy, Hself, ldh, A, lda, n_cap, n_d, in, out, W, dW, db, dSelf,
-                                           dAgg, ldi, P, Q, splits, false, ex, st);
+        launch_bwd<float, float>(dYm, ldm, Hself, ldh, A, lda, n_cap, n_d, in, out, W, dW, db, dSelf, dAgg, ldi, P, Q,
+                                 w.splits, ex, st);
     else if (dy_dtype == SDT_F32)
-        launch_bwd<float, bf16_t, FBM, FBN>(dY, lddy, Ym, ldy, Hself, ldh, A, lda, n_cap, n_d, in, out, W, dW, db,
-                                            dSelf, dAgg, ldi, P, Q, splits, true, ex, st);
+        launch_bwd<float, bf16_t>(dYm, ldm, Hself, ldh, A, lda, n_cap, n_d, in, out, W, dW, db, dSelf, dAgg, ldi, P, Q,
+                                  w.splits, ex, st);
     else
-        launch_bwd<bf16_t, bf16_t, FBM, FBN>(dY, lddy, Ym, ldy, Hself, ldh, A, lda, n_cap, n_d, in, out, W, dW, db,
-                                             dSelf, dAgg, ldi, P, Q, splits, true, ex, st);
+        launch_bwd<bf16_t, bf16_t>(dYm, ldm, Hself, ldh, A, lda, n_cap, n_d, in, out, W, dW, db, dSelf, dAgg, ldi, P, Q,
+                                   w.splits, ex, st);
     SDT_CHECK_LAUNCH("linear_bwd");
     return SDT_OK;
 }

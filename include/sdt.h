@@ -133,6 +133,7 @@ typedef struct sdt_step_layout {
     uint64_t db[SDT_MAX_LAYERS];
     uint64_t row_loss; /* fp32 [B]: per-seed loss before the mean */
     uint64_t scratch;  /* internal */
+    uint64_t wlow;     /* internal: bf16 images of the weights (bf16 workloads only) */
 } sdt_step_layout;
 
 /* Library version as "major.minor.patch" (host string, static storage). */

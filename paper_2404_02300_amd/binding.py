@@ -56,7 +56,7 @@ class sdt_step_layout(ctypes.Structure):
                 ("t_indptr", _u64 * _L), ("t_rows", _u64 * _L),
                 ("H", _u64 * (_L + 1)), ("A", _u64 * _L), ("dZ", _u64),
                 ("dH", _u64 * _L), ("dSelf", _u64 * _L), ("dAgg", _u64 * _L),
-                ("dW", _u64 * _L), ("db", _u64 * _L), ("row_loss", _u64), ("scratch", _u64)]
+                ("dW", _u64 * _L), ("db", _u64 * _L), ("row_loss", _u64), ("scratch", _u64), ("wlow", _u64)]
 
 
 EXPORTS = {

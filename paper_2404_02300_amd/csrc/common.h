@@ -86,6 +86,19 @@ __device__ __forceinline__ int dev_count(int cap, const int32_t* n_d) {
     return n < cap ? n : cap;
 }
 
+// The hardware hands consecutive workgroup ids to the eight XCDs in turn, and every XCD has
+// an L2 of its own.  Renumber the workgroups so that each XCD works on a contiguous run of
+// tiles (x fastest): the tiles that share an operand panel then share one L2.  Only the first
+// `valid` tiles carry work (the grid is sized for an upper bound of the row count); they are
+// dealt out evenly over the XCDs.  Returns the tile id in [0, valid), or -1 for a workgroup
+// that has nothing to do.  Needs valid <= number of workgroups.
+__device__ __forceinline__ int xcd_contiguous_id(int valid) {
+    const int id = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const int xcd = id & 7, slot = id >> 3, q = valid >> 3, r = valid & 7;
+    if (slot >= q + (xcd < r ? 1 : 0)) return -1;
+    return (xcd < r ? xcd * (q + 1) : r * (q + 1) + (xcd - r) * q) + slot;
+}
+
 inline size_t dtype_size(int32_t dt) { return dt == SDT_BF16 ? 2 : 4; }
 inline bool dtype_ok(int32_t dt) { return dt == SDT_F32 || dt == SDT_BF16; }
 
@@ -125,6 +138,7 @@ int32_t softmax_xent(const float* logits, int64_t ld, int32_t B, int32_t C, cons
 // Extra work the final reduction of a projection backward can carry: the SGD step on (W, b)
 // and the fixed-order mean of the per-seed losses.
 struct BwdExtras {
+    const void* Wb = nullptr;  // bf16 image of W for the input gradient on the bf16 matrix path (or null)
     float* W_upd = nullptr;
     float* b_upd = nullptr;
     float lr = 0.f;
@@ -141,6 +155,20 @@ int32_t linear_bwd(const void* dY, int64_t lddy, int32_t dy_dtype, const void* Y
 // dW = sum of `splits` partials P[s][2in][out], db likewise from Q[s][out], plus the extras
 int32_t reduce_partials(const float* P, const float* Q, int32_t splits, int32_t in, int32_t out, float* dW, float* db,
                         const BwdExtras& ex, hipStream_t st);
+
+// bf16 matrix-core path (linear_bf16.hip).  Per layer the image region holds Wt = bf16 [out][2 in]
+// followed (256-byte aligned) by Wb = bf16 [2 in][bf16_ldb(out)], layers back to back.
+int32_t bf16_ldb(int32_t out);
+size_t bf16_weights_bytes(int32_t in, int32_t out);
+int32_t convert_weights_bf16(const sdt_model* model, void* base, hipStream_t st);
+bool bf16_mfma_fwd_ok(const void* Hself, int64_t ldh, const void* A, int64_t lda, int32_t in);
+bool bf16_mfma_bwd_input_ok(const void* dY, int64_t lddy, int32_t dy_dtype, int32_t in, int32_t out, int64_t ldi);
+int32_t linear_fwd_bf16(const void* Hself, int64_t ldh, const void* A, int64_t lda, int32_t n_cap, const int32_t* n_d,
+                        int32_t in, int32_t out, const void* Wt, const float* bias, int32_t relu, void* Y, int64_t ldy,
+                        int32_t y_dtype, hipStream_t st);
+int32_t linear_bwd_input_bf16(const void* dY, int64_t lddy, int32_t dy_dtype, int32_t n_cap, const int32_t* n_d,
+                              int32_t in, int32_t out, const void* Wb, void* dSelf, void* dAgg, int64_t ldi,
+                              hipStream_t st);
 
 // Fused last layer (projection + softmax cross-entropy + backward) for small class counts.
 bool head_supported(int32_t in, int32_t out);

@@ -167,19 +167,6 @@ struct Tile {
     static_assert(TM >= 1 && TN >= 1 && BK % 8 == 0, "tile shape");
 };
 
-// The hardware hands consecutive workgroup ids to the eight XCDs in turn, and every XCD has
-// an L2 of its own.  Renumber the workgroups so that each XCD works on a contiguous run of
-// tiles (x fastest): the tiles that share an operand panel then share one L2.  Only the first
-// `valid` tiles carry work (the grid is sized for an upper bound of the row count); they are
-// dealt out evenly over the XCDs.  Returns the tile id in [0, valid), or -1 for a workgroup
-// that has nothing to do.  Needs valid <= number of workgroups.
-__device__ __forceinline__ int xcd_contiguous_id(int valid) {
-    const int id = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
-    const int xcd = id & 7, slot = id >> 3, q = valid >> 3, r = valid & 7;
-    if (slot >= q + (xcd < r ? 1 : 0)) return -1;
-    return (xcd < r ? xcd * (q + 1) : r * (q + 1) + (xcd - r) * q) + slot;
-}
-
 __device__ __forceinline__ void zero_acc(floatx16& a) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) a[r] = 0.f;
@@ -531,7 +518,12 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Hself, int64_t ldh, co
             })
         })
     }
-    if (dSelf && n_cap > 0) {
+    const bool input_on_bf16_path = ex.Wb && sizeof(TH) == 2 && dSelf &&
+                                    bf16_mfma_bwd_input_ok(dY, lddy, sizeof(TD) == 2 ? SDT_BF16 : SDT_F32, in, out, ldi);
+    if (input_on_bf16_path) {
+        (void)linear_bwd_input_bf16(dY, lddy, sizeof(TD) == 2 ? SDT_BF16 : SDT_F32, n_cap, n_d, in, out, ex.Wb, dSelf, dAgg,
+                                    ldi, st);
+    } else if (dSelf && n_cap > 0) {
         using TL = TileS;
         dim3 grid(ceil_div(in, TL::BN), ceil_div(n_cap, TL::BM), 2);
         SDT_VEC_SWITCH(vd, (16 / sizeof(TD)), {

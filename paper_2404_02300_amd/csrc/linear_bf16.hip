@@ -1,0 +1,387 @@
+// Projection of bf16 activations on the bf16 matrix cores (v_mfma_f32_32x32x16_bf16):
+// forward Y = act([Hself | A] W + b) and the input gradients [dSelf | dAgg] = dZ W^T.
+//
+// The operands of a product enter rounded to bf16 and are accumulated in fp32, which is
+// exactly what the widened fp32 path computes, at 16 times its matrix rate -- so these
+// kernels are bound by streaming the activations once, not by arithmetic.
+//
+// A bf16 MFMA operand is eight consecutive reduction indices per lane.  Activations are
+// stored with the reduction index contiguous already; the fp32 weights are not (forward)
+// and must be rounded anyway, so one small pass per step writes two bf16 images of every
+// weight matrix: Wt[out][2in] (transposed, for the forward) and Wb[2in][ldb] (straight, row
+// stride padded to 8 with zeros, for the input gradient).  Both operands of both products
+// then stage as plain 16-byte copies into LDS rows of BK+8 elements: 16 consecutive rows
+// start in 16 different 16-byte bank groups, so the 16-byte fragment reads are conflict-free.
+// The main loop is the one of the fp32 path: loads two steps ahead in two register stages,
+// nothing conditional, double-buffered LDS, one barrier per step.
+#include "common.h"
+
+#include <type_traits>
+
+namespace sdt {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+template <int BM_, int BN_, int BK_, int WM_, int WN_>
+struct TileB {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
+    static constexpr int NT = 64 * WM * WN;
+    static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    static constexpr int LDK = BK + 8;   // bf16 elements; (BK+8)*2/16 is odd for BK = 32, 64
+    static constexpr int VPR = BK / 8;   // 16-byte vectors per tile row
+    static_assert(TM >= 1 && TN >= 1 && (BK == 32 || BK == 64), "tile shape");
+};
+
+// ---- [R rows][BK] of a bf16 matrix whose reduction index is contiguous -------------------------
+template <int R, int BK, int NT>
+struct StageB {
+    static constexpr int VPR = BK / 8, TOTAL = R * VPR, PER = (TOTAL + NT - 1) / NT, LDK = BK + 8;
+    uint4 raw[PER];
+    uint32_t ok;
+    // rows [r_lo, r_lo+R) x k in [k_lo, k_lo+BK); zero outside [0,rmax) x [0,kmax).  kmax % 8 == 0,
+    // kmax >= 8, rmax >= 1.  Loads are unconditional from clamped addresses (see linear.hip).
+    __device__ __forceinline__ void load(const uint16_t* __restrict__ base, int64_t ld, int r_lo, int rmax, int k_lo,
+                                         int kmax) {
+        ok = 0;
+#pragma unroll
+        for (int p = 0; p < PER; ++p) {
+            const int idx = threadIdx.x + p * NT;
+            const int r = r_lo + idx / VPR, k = k_lo + (idx % VPR) * 8;
+            if (r < rmax && k < kmax) ok |= 1u << p;
+            const int rr = min(r, rmax - 1), kk = min(k, kmax - 8);
+            raw[p] = *reinterpret_cast<const uint4*>(base + (int64_t)rr * ld + kk);
+        }
+    }
+    __device__ __forceinline__ void store(uint16_t* lds) const {
+#pragma unroll
+        for (int p = 0; p < PER; ++p) {
+            const int idx = threadIdx.x + p * NT;
+            if (TOTAL % NT == 0 || idx < TOTAL) {
+                const bool in = (ok >> p) & 1u;
+                uint4 v = raw[p];
+                if (!in) v = make_uint4(0u, 0u, 0u, 0u);
+                *reinterpret_cast<uint4*>(lds + (idx / VPR) * LDK + (idx % VPR) * 8) = v;
+            }
+        }
+    }
+};
+
+// ---- the same tile out of an fp32 matrix, rounded to bf16 on the way (two float4 per vector) ---
+template <int R, int BK, int NT>
+struct StageF {
+    static constexpr int VPR = BK / 8, TOTAL = R * VPR, PER = (TOTAL + NT - 1) / NT, LDK = BK + 8;
+    float4 raw[PER][2];
+    uint32_t ok;  // two bits per vector
+    // kmax % 4 == 0, kmax >= 4, rmax >= 1
+    __device__ __forceinline__ void load(const float* __restrict__ base, int64_t ld, int r_lo, int rmax, int k_lo,
+                                         int kmax) {
+        ok = 0;
+#pragma unroll
+        for (int p = 0; p < PER; ++p) {
+            const int idx = threadIdx.x + p * NT;
+            const int r = r_lo + idx / VPR;
+            const int rr = min(r, rmax - 1);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int k = k_lo + (idx % VPR) * 8 + 4 * h;
+                if (r < rmax && k < kmax) ok |= 1u << (2 * p + h);
+                raw[p][h] = *reinterpret_cast<const float4*>(base + (int64_t)rr * ld + min(k, kmax - 4));
+            }
+        }
+    }
+    __device__ __forceinline__ static uint32_t pack(float lo, float hi) {
+        return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+    }
+    __device__ __forceinline__ void store(uint16_t* lds) const {
+#pragma unroll
+        for (int p = 0; p < PER; ++p) {
+            const int idx = threadIdx.x + p * NT;
+            if (TOTAL % NT == 0 || idx < TOTAL) {
+                const bool in0 = (ok >> (2 * p)) & 1u, in1 = (ok >> (2 * p + 1)) & 1u;
+                const float4 a = raw[p][0], b = raw[p][1];
+                uint4 v;
+                v.x = in0 ? pack(a.x, a.y) : 0u;
+                v.y = in0 ? pack(a.z, a.w) : 0u;
+                v.z = in1 ? pack(b.x, b.y) : 0u;
+                v.w = in1 ? pack(b.z, b.w) : 0u;
+                *reinterpret_cast<uint4*>(lds + (idx / VPR) * LDK + (idx % VPR) * 8) = v;
+            }
+        }
+    }
+};
+
+template <typename TL>
+struct FragB {
+    bf16x8 a[TL::TM], b[TL::TN];
+    // chunk c covers 16 reduction indices: lanes 0-31 take the first eight, lanes 32-63 the rest.
+    // Which eight a lane holds does not matter to the sum as long as both operands agree.
+    __device__ __forceinline__ void load(const uint16_t* As, const uint16_t* Bs, int arow0, int bcol0, int c) {
+        const int lane = threadIdx.x & 63, i = lane & 31, kg = lane >> 5;
+#pragma unroll
+        for (int tm = 0; tm < TL::TM; ++tm)
+            a[tm] = *reinterpret_cast<const bf16x8*>(As + (arow0 + tm * 32 + i) * TL::LDK + c * 16 + kg * 8);
+#pragma unroll
+        for (int tn = 0; tn < TL::TN; ++tn)
+            b[tn] = *reinterpret_cast<const bf16x8*>(Bs + (bcol0 + tn * 32 + i) * TL::LDK + c * 16 + kg * 8);
+    }
+    __device__ __forceinline__ void mma(floatx16 (&acc)[TL::TM][TL::TN]) const {
+#pragma unroll
+        for (int tm = 0; tm < TL::TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TL::TN; ++tn)
+                acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
+    }
+};
+
+template <typename TL>
+__device__ __forceinline__ void mma_step(const uint16_t* As, const uint16_t* Bs, int a0, int b0,
+                                         floatx16 (&acc)[TL::TM][TL::TN]) {
+    constexpr int NC = TL::BK / 16;
+    FragB<TL> f[2];
+    f[0].load(As, Bs, a0, b0, 0);
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        if (c + 1 < NC) f[(c + 1) & 1].load(As, Bs, a0, b0, c + 1);
+        f[c & 1].mma(acc);
+    }
+}
+
+// Requires nit >= 1; fetch(it, ...) must be callable for it up to nit + 2 (clamped loads, zero tiles).
+template <typename TL, typename SA, typename SB, typename Fetch>
+__device__ __forceinline__ void mainloop(int nit, uint16_t* As, uint16_t* Bs, Fetch&& fetch,
+                                         floatx16 (&acc)[TL::TM][TL::TN]) {
+    constexpr int A_ELEMS = TL::BM * TL::LDK, B_ELEMS = TL::BN * TL::LDK;
+    const int wave = threadIdx.x >> 6, wm = wave / TL::WN, wn = wave % TL::WN;
+    const int a0 = wm * (TL::BM / TL::WM), b0 = wn * (TL::BN / TL::WN);
+    SA sa0, sa1;
+    SB sb0, sb1;
+    fetch(0, sa0, sb0);
+    __builtin_amdgcn_sched_barrier(0);
+    fetch(1, sa1, sb1);
+    __builtin_amdgcn_sched_barrier(0);
+    for (int it = 0; it < nit; it += 2) {
+        sa0.store(As);
+        sb0.store(Bs);
+        __syncthreads();
+        fetch(it + 2, sa0, sb0);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_step<TL>(As, Bs, a0, b0, acc);
+        sa1.store(As + A_ELEMS);
+        sb1.store(Bs + B_ELEMS);
+        __syncthreads();
+        fetch(it + 3, sa1, sb1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_step<TL>(As + A_ELEMS, Bs + B_ELEMS, a0, b0, acc);
+    }
+}
+
+template <typename TL, typename F>
+__device__ __forceinline__ void for_each_acc(const floatx16 (&acc)[TL::TM][TL::TN], F&& f) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave / TL::WN, wn = wave % TL::WN;
+#pragma unroll
+    for (int tm = 0; tm < TL::TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TL::TN; ++tn) {
+            const int c = wn * (TL::BN / TL::WN) + tn * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                f(wm * (TL::BM / TL::WM) + tm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3), c, acc[tm][tn][r]);
+        }
+}
+
+template <typename TL>
+__device__ __forceinline__ void zero(floatx16 (&acc)[TL::TM][TL::TN]) {
+#pragma unroll
+    for (int a = 0; a < TL::TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TL::TN; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+}
+
+// ---- forward -------------------------------------------------------------------------------------
+// Wt: bf16 [out][2 in], column o of W as a row (self half first).
+template <typename TY, typename TL>
+__global__ __launch_bounds__(TL::NT) void k_fwd_bf16(const uint16_t* __restrict__ Hself, int64_t ldh,
+                                                     const uint16_t* __restrict__ Agg, int64_t lda, int n_cap,
+                                                     const int32_t* n_d, int in, int out,
+                                                     const uint16_t* __restrict__ Wt, const float* __restrict__ bias,
+                                                     int relu, TY* __restrict__ Y, int64_t ldy) {
+    constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK;
+    const int n = dev_count(n_cap, n_d);
+    const int id = xcd_contiguous_id((int)gridDim.x * ((n + BM - 1) / BM));
+    if (id < 0) return;
+    const int row0 = (id / (int)gridDim.x) * BM, col0 = (id % (int)gridDim.x) * BN;
+    __shared__ __align__(16) uint16_t As[2 * BM * TL::LDK];
+    __shared__ __align__(16) uint16_t Bs[2 * BN * TL::LDK];
+    floatx16 acc[TL::TM][TL::TN];
+    zero<TL>(acc);
+    using SA = StageB<BM, BK, TL::NT>;
+    using SB = StageB<BN, BK, TL::NT>;
+    const int nk = (in + BK - 1) / BK;
+    auto fetch = [&](int it, SA& sa, SB& sb) {
+        const int ph = it >= nk, k0 = (it - ph * nk) * BK;  // past the last step k0 >= in: zero tiles
+        sa.load(ph ? Agg : Hself, ph ? lda : ldh, row0, n, k0, in);
+        sb.load(Wt + (int64_t)ph * in, 2 * (int64_t)in, col0, out, k0, in);
+    };
+    mainloop<TL, SA, SB>(2 * nk, As, Bs, fetch, acc);
+    for_each_acc<TL>(acc, [&](int r, int c, float v) {
+        const int row = row0 + r, col = col0 + c;
+        if (row < n && col < out) {
+            float z = v + (bias ? bias[col] : 0.f);
+            if (relu && !(z > 0.f)) z = 0.f;
+            Y[(int64_t)row * ldy + col] = from_f32<TY>(z);
+        }
+    });
+}
+
+// ---- input gradient --------------------------------------------------------------------------------
+// dIn_h[n, in] = dZ[n, out] W_h^T.  Wb: bf16 [2 in][ldb], rows of W rounded; half h = rows h*in ...
+// TD = uint16_t (bf16 dZ) or float (fp32 dZ, rounded on the way in).
+template <typename TD, typename TL>
+__global__ __launch_bounds__(TL::NT) void k_bwd_input_bf16(const TD* __restrict__ dY, int64_t lddy, int n_cap,
+                                                           const int32_t* n_d, int in, int out,
+                                                           const uint16_t* __restrict__ Wb, int64_t ldb,
+                                                           bf16_t* __restrict__ dSelf, bf16_t* __restrict__ dAgg,
+                                                           int64_t ldi) {
+    constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK;
+    const int n = dev_count(n_cap, n_d);
+    const int id = xcd_contiguous_id((int)gridDim.x * 2 * ((n + BM - 1) / BM));
+    if (id < 0) return;
+    const int col0 = (id % (int)gridDim.x) * BN, half = (id / (int)gridDim.x) % 2;
+    const int row0 = (id / (int)gridDim.x / 2) * BM;
+    __shared__ __align__(16) uint16_t As[2 * BM * TL::LDK];
+    __shared__ __align__(16) uint16_t Bs[2 * BN * TL::LDK];
+    floatx16 acc[TL::TM][TL::TN];
+    zero<TL>(acc);
+    using SA = typename std::conditional<sizeof(TD) == 2, StageB<BM, BK, TL::NT>, StageF<BM, BK, TL::NT>>::type;
+    using SB = StageB<BN, BK, TL::NT>;
+    const uint16_t* Wh = Wb + (int64_t)half * in * ldb;
+    const int kmax_b = (int)ldb;  // the padding columns of Wb are zero
+    auto fetch = [&](int it, SA& sa, SB& sb) {
+        sa.load(dY, lddy, row0, n, it * BK, out);
+        sb.load(Wh, ldb, col0, in, it * BK, kmax_b);
+    };
+    mainloop<TL, SA, SB>((out + BK - 1) / BK, As, Bs, fetch, acc);
+    bf16_t* dst = half ? dAgg : dSelf;
+    for_each_acc<TL>(acc, [&](int r, int c, float v) {
+        const int row = row0 + r, col = col0 + c;
+        if (row < n && col < in) dst[(int64_t)row * ldi + col] = from_f32<bf16_t>(v);
+    });
+}
+
+// ---- bf16 images of the weights ----------------------------------------------------------------
+struct ConvertArgs {
+    int32_t n_layers;
+    const float* W[SDT_MAX_LAYERS];
+    uint16_t* Wt[SDT_MAX_LAYERS];
+    uint16_t* Wb[SDT_MAX_LAYERS];
+    int32_t k2[SDT_MAX_LAYERS];   // 2 * in
+    int32_t out[SDT_MAX_LAYERS];
+    int32_t ldb[SDT_MAX_LAYERS];
+    int64_t first[SDT_MAX_LAYERS + 1];  // prefix sums of k2 * ldb
+};
+
+__global__ __launch_bounds__(256) void k_convert_weights(ConvertArgs a) {
+    const int64_t total = a.first[a.n_layers];
+    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        int l = 0;
+        while (l + 1 < a.n_layers && i >= a.first[l + 1]) ++l;
+        const int64_t j = i - a.first[l];
+        const int k = (int)(j / a.ldb[l]), o = (int)(j - (int64_t)k * a.ldb[l]);
+        uint16_t v = 0;
+        if (o < a.out[l]) {
+            v = f32_to_bf16(a.W[l][(int64_t)k * a.out[l] + o]);
+            a.Wt[l][(int64_t)o * a.k2[l] + k] = v;
+        }
+        a.Wb[l][j] = v;
+    }
+}
+
+inline bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+// ---- internal entry points (declared in common.h) ----------------------------------------------
+int32_t bf16_ldb(int32_t out) { return (out + 7) / 8 * 8; }
+
+size_t bf16_weights_bytes(int32_t in, int32_t out) {
+    return align_up((size_t)2 * in * out * 2, 256) + align_up((size_t)2 * in * bf16_ldb(out) * 2, 256);
+}
+
+bool bf16_mfma_fwd_ok(const void* Hself, int64_t ldh, const void* A, int64_t lda, int32_t in) {
+    return in % 8 == 0 && ldh % 8 == 0 && lda % 8 == 0 && al16(Hself) && al16(A);
+}
+
+bool bf16_mfma_bwd_input_ok(const void* dY, int64_t lddy, int32_t dy_dtype, int32_t in, int32_t out, int64_t ldi) {
+    (void)in; (void)ldi;
+    if (!al16(dY)) return false;
+    return dy_dtype == SDT_BF16 ? (out % 8 == 0 && lddy % 8 == 0) : (out % 4 == 0 && lddy % 4 == 0);
+}
+
+int32_t convert_weights_bf16(const sdt_model* model, void* base, hipStream_t st) {
+    ConvertArgs a{};
+    a.n_layers = model->n_layers;
+    char* p = static_cast<char*>(base);
+    a.first[0] = 0;
+    for (int l = 0; l < model->n_layers; ++l) {
+        const int in = model->dims[l], out = model->dims[l + 1];
+        a.W[l] = model->W[l];
+        a.k2[l] = 2 * in;
+        a.out[l] = out;
+        a.ldb[l] = bf16_ldb(out);
+        a.Wt[l] = reinterpret_cast<uint16_t*>(p);
+        a.Wb[l] = reinterpret_cast<uint16_t*>(p + align_up((size_t)2 * in * out * 2, 256));
+        p += bf16_weights_bytes(in, out);
+        a.first[l + 1] = a.first[l] + (int64_t)a.k2[l] * a.ldb[l];
+    }
+    const int64_t total = a.first[a.n_layers];
+    const int blocks = (int)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
+    hipLaunchKernelGGL(k_convert_weights, dim3(blocks > 0 ? blocks : 1), dim3(256), 0, st, a);
+    SDT_CHECK_LAUNCH("convert_weights_bf16");
+    return SDT_OK;
+}
+
+namespace {
+using TF = TileB<64, 128, 64, 2, 2>;
+using TI = TileB<64, 128, 64, 2, 2>;
+}  // namespace
+
+int32_t linear_fwd_bf16(const void* Hself, int64_t ldh, const void* A, int64_t lda, int32_t n_cap, const int32_t* n_d,
+                        int32_t in, int32_t out, const void* Wt, const float* bias, int32_t relu, void* Y, int64_t ldy,
+                        int32_t y_dtype, hipStream_t st) {
+    if (n_cap == 0) return SDT_OK;
+    dim3 grid(ceil_div(out, TF::BN), ceil_div(n_cap, TF::BM));
+    const uint16_t* h = static_cast<const uint16_t*>(Hself);
+    const uint16_t* a = static_cast<const uint16_t*>(A);
+    const uint16_t* w = static_cast<const uint16_t*>(Wt);
+    if (y_dtype == SDT_BF16)
+        hipLaunchKernelGGL((k_fwd_bf16<bf16_t, TF>), grid, dim3(TF::NT), 0, st, h, ldh, a, lda, n_cap, n_d, in, out, w, bias,
+                           relu, static_cast<bf16_t*>(Y), ldy);
+    else
+        hipLaunchKernelGGL((k_fwd_bf16<float, TF>), grid, dim3(TF::NT), 0, st, h, ldh, a, lda, n_cap, n_d, in, out, w, bias,
+                           relu, static_cast<float*>(Y), ldy);
+    SDT_CHECK_LAUNCH("linear_fwd_bf16");
+    return SDT_OK;
+}
+
+int32_t linear_bwd_input_bf16(const void* dY, int64_t lddy, int32_t dy_dtype, int32_t n_cap, const int32_t* n_d,
+                              int32_t in, int32_t out, const void* Wb, void* dSelf, void* dAgg, int64_t ldi,
+                              hipStream_t st) {
+    if (n_cap == 0) return SDT_OK;
+    dim3 grid(ceil_div(in, TI::BN), ceil_div(n_cap, TI::BM), 2);
+    const uint16_t* w = static_cast<const uint16_t*>(Wb);
+    const int64_t ldb = bf16_ldb(out);
+    if (dy_dtype == SDT_BF16)
+        hipLaunchKernelGGL((k_bwd_input_bf16<uint16_t, TI>), grid, dim3(TI::NT), 0, st, static_cast<const uint16_t*>(dY),
+                           lddy, n_cap, n_d, in, out, w, ldb, static_cast<bf16_t*>(dSelf), static_cast<bf16_t*>(dAgg), ldi);
+    else
+        hipLaunchKernelGGL((k_bwd_input_bf16<float, TI>), grid, dim3(TI::NT), 0, st, static_cast<const float*>(dY), lddy,
+                           n_cap, n_d, in, out, w, ldb, static_cast<bf16_t*>(dSelf), static_cast<bf16_t*>(dAgg), ldi);
+    SDT_CHECK_LAUNCH("linear_bwd_input_bf16");
+    return SDT_OK;
+}
+
+}  // namespace sdt

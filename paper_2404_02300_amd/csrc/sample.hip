@@ -504,7 +504,7 @@ inline int grid_for(int64_t items, int per_block, int max_blocks) {
     return (int)g;
 }
 
-constexpr int SMALL_T_NNZ = 1 << 16;  // layers up to this many sampled edges use k_transpose_small
+constexpr int SMALL_T_NNZ = 1 << 14;  // layers up to this many sampled edges use k_transpose_small
 
 }  // namespace
 

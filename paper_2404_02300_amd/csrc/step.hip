@@ -182,6 +182,11 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
     lay->dZ = a.take_off((size_t)batch * d[L] * 4);
     lay->row_loss = a.take_off((size_t)(batch > 0 ? batch : 1) * 4);
     lay->scratch = a.take_off(scratch);
+    if (dtype == SDT_BF16) {
+        size_t wb = 0;
+        for (int l = 0; l < L; ++l) wb += bf16_weights_bytes(d[l], d[l + 1]);
+        lay->wlow = a.take_off(wb);
+    }
     lay->total_bytes = a.off;
     return SDT_OK;
 }
@@ -294,6 +299,21 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
     // Small class counts: the last layer's projection, the loss and that layer's backward run
     // as one fused launch (head.hip) instead of five.
     const bool fused_head = head_supported(d[L - 1], d[L]) && aligned16(model->W[L - 1]);
+    const size_t scratch_bytes = (size_t)((lay.wlow ? lay.wlow : lay.total_bytes) - lay.scratch);
+    // bf16 activations: the matrix products run on the bf16 matrix cores from bf16 images of the
+    // weights, rewritten here every step (the weights are the caller's and change every step)
+    const char* wt[SDT_MAX_LAYERS] = {};
+    const char* wb[SDT_MAX_LAYERS] = {};
+    if (dtype == SDT_BF16) {
+        rc = convert_weights_bf16(model, b.at(lay.wlow), st);
+        if (rc != SDT_OK) return rc;
+        const char* p = static_cast<const char*>(b.at(lay.wlow));
+        for (int l = 0; l < L; ++l) {
+            wt[l] = p;
+            wb[l] = p + align_up((size_t)2 * d[l] * d[l + 1] * 2, 256);
+            p += bf16_weights_bytes(d[l], d[l + 1]);
+        }
+    }
     for (int l = 0; l < L; ++l) {
         if (l > 0) {   // layer 0's mean was taken in phase 1
             StageTimer tm(timing, SDT_STAGE_AGG_FWD, l, st);
@@ -303,9 +323,14 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
         const bool last = l == L - 1;
         if (last && fused_head) break;
         StageTimer tm(timing, SDT_STAGE_LINEAR_FWD, l, st);
-        rc = sdt_sage_linear_fwd(b.at(lay.H[l]), d[l], b.at(lay.A[l]), d[l], lay.cap_dst[l], b.blk[l].counts, d[l],
-                                 d[l + 1], model->W[l], model->b[l], last ? 0 : 1, dtype, b.at(lay.H[l + 1]), d[l + 1],
+        if (dtype == SDT_BF16 && bf16_mfma_fwd_ok(b.at(lay.H[l]), d[l], b.at(lay.A[l]), d[l], d[l]))
+            rc = linear_fwd_bf16(b.at(lay.H[l]), d[l], b.at(lay.A[l]), d[l], lay.cap_dst[l], b.blk[l].counts, d[l],
+                                 d[l + 1], wt[l], model->b[l], last ? 0 : 1, b.at(lay.H[l + 1]), d[l + 1],
                                  last ? SDT_F32 : dtype, st);
+        else
+            rc = sdt_sage_linear_fwd(b.at(lay.H[l]), d[l], b.at(lay.A[l]), d[l], lay.cap_dst[l], b.blk[l].counts, d[l],
+                                     d[l + 1], model->W[l], model->b[l], last ? 0 : 1, dtype, b.at(lay.H[l + 1]),
+                                     d[l + 1], last ? SDT_F32 : dtype, st);
         if (rc != SDT_OK) return rc;
     }
     if (!fused_head) {
@@ -329,7 +354,7 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
                               model->b[l], dtype, c.labels, seeds, static_cast<float*>(b.at(lay.H[L])),
                               static_cast<float*>(b.at(lay.dZ)), static_cast<float*>(b.at(lay.row_loss)),
                               inner ? b.at(lay.dSelf[l]) : nullptr, inner ? b.at(lay.dAgg[l]) : nullptr, d[l],
-                              b.at(lay.scratch), b.bytes - lay.scratch, &P, &Q, st);
+                              b.at(lay.scratch), scratch_bytes, &P, &Q, st);
             }
             if (rc != SDT_OK) return rc;
             BwdExtras ex;
@@ -346,6 +371,7 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
             // the SGD step of this layer (and, for the last layer, the mean of the per-seed
             // losses) ride on the final reduction of its weight gradient
             BwdExtras ex;
+            ex.Wb = wb[l];
             ex.W_upd = model->W[l];
             ex.b_upd = model->b[l];
             ex.lr = c.lr;
@@ -357,7 +383,7 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
             rc = linear_bwd(dY, d[l + 1], dy_dtype, nullptr, 0, 0, b.at(lay.H[l]), d[l], b.at(lay.A[l]), d[l],
                             lay.cap_dst[l], b.blk[l].counts, d[l], d[l + 1], model->W[l], dtype, dW, db,
                             inner ? b.at(lay.dSelf[l]) : nullptr, inner ? b.at(lay.dAgg[l]) : nullptr, d[l],
-                            b.at(lay.scratch), b.bytes - lay.scratch, ex, st);
+                            b.at(lay.scratch), scratch_bytes, ex, st);
             if (rc != SDT_OK) return rc;
         }
         if (inner) {

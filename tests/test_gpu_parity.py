@@ -332,6 +332,13 @@ def test_train_step_three_layers_bf16_small():
     _run_and_check(inst, wl, steps=2, check_float_steps=(0, 1))
 
 
+def test_train_step_bf16_generic_last_layer():
+    _say("train step: bf16 storage, 300 classes (bf16 matrix path with an fp32 loss gradient, ragged reduction tails)")
+    wl = gen.Workload("wide_bf16", "rmat", 12, 10, 24, 300, 40, 2, [4, 3], 96, 21, 1, bf16=True)
+    inst = gen.make_instance(wl)
+    _run_and_check(inst, wl, steps=2, check_float_steps=(0, 1))
+
+
 def test_train_step_many_classes_generic_last_layer():
     _say("train step: 300 classes (last layer on the generic kernels, not the fused head)")
     wl = gen.Workload("wide", "rmat", 12, 10, 24, 300, 32, 2, [4, 3], 96, 13, 1)

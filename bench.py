@@ -21,17 +21,18 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X dense bf16 matrix, published
 
 # HBM bytes per launch (read + written) from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs whose
 # summaries are committed under profiles/ (counter x factor calibrated on a 1 GiB copy: 2 KiB per
 # FETCH_SIZE count, 1 KiB per WRITE_SIZE count).  Counters cannot be read from inside this script, so
 # the figures are carried here; a stage without a counter run reports null.
 MEASURED_TRAFFIC_BYTES = {
-    ("dense", "aggregate_fwd", 0): 709.7e6 + 25.8e6,
-    ("dense", "gather", 0): 283.6e6 + 277.5e6,
-    ("dense", "linear_fwd", 0): 208.2e6 + 10.4e6,
-    ("fullgraph", "aggregate"): 122264.2e6 + 4295.0e6,
-    ("fullgraph", "linear"): 17654.6e6 + 4295.0e6,
+    ("dense", "aggregate_fwd", 0): 727.1e6 + 33.4e6,
+    ("dense", "gather", 0): 26.0e6 + 25.3e6,
+    ("dense", "linear_fwd", 0): 60.3e6 + 10.4e6,
+    ("fullgraph", "aggregate"): 78497.7e6 + 42666.5e6 + 4285.6e6 + 9.3e6,   # both launches of the SpMM
+    ("fullgraph", "linear"): 9145.1e6 + 4295.0e6,
 }
 
 
@@ -176,12 +177,14 @@ def main():
             return "hbm", nnz * (d[l] * es + (8 if l == 0 else 4)) + n_dst * (d[l] * es + 8), "k_aggregate_fwd"
         if kind == "aggregate_bwd":
             return "hbm", nnz * (d[l] * es + 4) + n_src * (d[l] * es + 8) + n_dst * d[l] * es, "k_aggregate_bwd"
-        if kind == "linear_fwd":
-            return "mfma", 2.0 * n_dst * 2 * d[l] * d[l + 1], "k_linear_fwd"
+        if kind == "linear_fwd":    # bf16 workloads: bf16 matrix cores (priced against the bf16 peak)
+            return ("mfma_bf16" if wl.bf16 else "mfma"), 2.0 * n_dst * 2 * d[l] * d[l + 1], \
+                   ("k_fwd_bf16" if wl.bf16 else "k_linear_fwd")
         if kind == "linear_bwd":
             f = 2.0 * n_dst * 2 * d[l] * d[l + 1]
             if l == L - 1 and fused_head:   # projection + softmax + dW + input gradients in one launch
                 return "mfma", f * (3 if l > 0 else 2), "k_head + k_reduce_partials"
+            # bf16 workloads: dW on the fp32 matrix path (widened operands), input gradients on the bf16 one
             return "mfma", f * (2 if l > 0 else 1), "k_linear_bwd_weight (+ _input) + k_reduce_partials"
         if kind == "head":        # projection + dW (+ input gradients) of the last layer, one launch
             return "mfma", 2.0 * n_dst * 2 * d[l] * d[l + 1] * (3 if l > 0 else 2), "k_head"
@@ -191,6 +194,8 @@ def main():
         bound, amount, kernels = work(kind, l)
         if bound == "hbm":
             ach, peak, unit = amount / seconds / 1e9, HBM_PEAK_GBS, "GB/s"
+        elif bound == "mfma_bf16":
+            bound, ach, peak, unit = "mfma", amount / seconds / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
         else:
             ach, peak, unit = amount / seconds / 1e12, MFMA_FP32_PEAK_TFLOPS, "TFLOP/s"
         return {"stage": f"{kind}[{l}]", "kernel": kernels, "bound": bound, "achieved": round(ach, 2), "peak": peak,
@@ -298,13 +303,15 @@ def bench_fullgraph(args, wl):
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: rmat 2^{wl.log2n} nodes, {nnz} CSR entries, F={F} -> {O}, one layer, "
                                f"no sampling", "seed": wl.seed},
-        "roofline": {"kernel": "k_aggregate_fwd<float,4,64,long> (whole CSR)", "bound": "hbm",
+        "roofline": {"kernel": "k_aggregate_fwd<float,4,64,long> + k_aggregate_long (whole CSR, hub rows in the second launch)",
+                     "bound": "hbm",
                      "achieved": round(agg_bytes / agg_s / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(agg_bytes / agg_s / 1e9 / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, "aggregate")),
                      "algorithmic_bytes_per_launch": int(agg_bytes), "compulsory_bytes_per_launch": int(compulsory),
                      "compulsory_GBps": round(compulsory / agg_s / 1e9, 1), "avg_launch_us": round(agg_s * 1e6, 1)},
-        "gemm": {"kernel": "k_linear_fwd<float,float,128,128>", "bound": "mfma", "TFLOPs": round(flops / gemm_s / 1e12, 2),
+        "gemm": {"kernel": "k_linear_fwd<float, float, Tile<128, 256, 16, 2, 4>, 4, 4, false>", "bound": "mfma",
+                 "TFLOPs": round(flops / gemm_s / 1e12, 2), "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, "linear")),
                  "peak": MFMA_FP32_PEAK_TFLOPS, "frac": round(flops / gemm_s / 1e12 / MFMA_FP32_PEAK_TFLOPS, 4),
                  "flops_per_launch": flops, "avg_launch_us": round(gemm_s * 1e6, 1)},
         "cpu_baseline": cpu,

@@ -279,3 +279,34 @@ def train_step(indptr, indices, X, y, seeds, fanouts, W, b, seed: int, step: int
     W_new = [sgd(W[l], g["dW"][l], lr) for l in range(L)]
     b_new = [sgd(b[l], g["db"][l], lr) for l in range(L)]
     return dict(blocks=blocks, H=H, A=A, logits=H[L], loss=loss, dZ=dZ, W=W, W_new=W_new, b_new=b_new, **g)
+
+
+# ------------------------------------------------- beyond the mini-batch step
+def infer_layerwise(indptr, indices, X, W, b, bf16: bool = False) -> np.ndarray:
+    """Full-neighbour inference, one layer at a time over every node of the
+    partition (the evaluation pass of Sec. IV-A: a trained model is scored on
+    nodes with all of their neighbours, no sampling): for each layer,
+    A = mean over the whole CSR row, H' = act(H W_self + A W_neigh + b), ReLU on
+    all but the last layer.  Rounding points as in forward().  Returns the
+    logits of all nodes in float64."""
+    rnd = round_bf16 if bf16 else (lambda t: t)
+    H = bf16_bits_to_f64(np.asarray(X)) if bf16 else np.asarray(X, dtype=np.float64)
+    L = len(W)
+    ip = np.asarray(indptr, dtype=np.int64)
+    cols = np.asarray(indices, dtype=np.int32)
+    for l in range(L):
+        a = rnd(aggregate_fwd(ip, cols, H))
+        z = linear_fwd(H, a, rnd(np.asarray(W[l], dtype=np.float64)), np.asarray(b[l], dtype=np.float64), relu=(l < L - 1))
+        H = rnd(z) if l < L - 1 else z
+    return H
+
+
+def model_average(params: List[np.ndarray], n_train: List[float]) -> np.ndarray:
+    """Model synchronisation of Sec. III-D: w = sum_i alpha_i w_i with
+    alpha_i = n_train_i / sum_j n_train_j (each worker's share of the training
+    nodes), in float64."""
+    tot = float(sum(n_train))
+    out = np.zeros_like(np.asarray(params[0], dtype=np.float64))
+    for p, n in zip(params, n_train):
+        out = out + (float(n) / tot) * np.asarray(p, dtype=np.float64)
+    return out

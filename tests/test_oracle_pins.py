@@ -402,3 +402,62 @@ def test_bf16_step_rounds_only_where_stored():
     assert abs(out["loss"] - ref["loss"]) < 2e-2 * max(1.0, abs(ref["loss"]))
     for l in range(3):
         assert np.max(np.abs(out["dW"][l] - ref["dW"][l])) <= 3e-2 * np.max(np.abs(ref["dW"][l]))
+
+
+# ----------------------------------------------------------------- layer-wise inference, model averaging
+def test_infer_layerwise_equals_dense_matrix_chain():
+    # independent formulation: row-normalised dense adjacency, plain matrix products
+    rng = np.random.default_rng(11)
+    n, dims = 40, [6, 9, 4]
+    rows = [np.sort(rng.choice(n, size=int(rng.integers(0, 7)), replace=False)) for _ in range(n)]
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    indptr[1:] = np.cumsum([len(r) for r in rows])
+    indices = np.concatenate(rows).astype(np.int32)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    W = [rng.standard_normal((2 * dims[l], dims[l + 1])) * 0.3 for l in range(2)]
+    b = [rng.standard_normal(dims[l + 1]) * 0.1 for l in range(2)]
+    P = np.zeros((n, n))
+    for v, r in enumerate(rows):
+        for u in r:
+            P[v, u] += 1.0 / len(r)
+    H = X.astype(np.float64)
+    for l in range(2):
+        Z = H @ W[l][:dims[l]] + (P @ H) @ W[l][dims[l]:] + b[l]
+        H = np.maximum(Z, 0) if l == 0 else Z
+    got = orc.infer_layerwise(indptr, indices, X, W, b)
+    assert np.allclose(got, H, rtol=1e-12, atol=1e-12)
+    # an isolated node sees only its own features
+    iso = [v for v, r in enumerate(rows) if len(r) == 0]
+    assert iso, "the fixture should contain an isolated node"
+
+
+def test_infer_layerwise_agrees_with_a_full_fanout_training_forward():
+    # with fan-outs >= the maximum degree, sampling keeps every neighbour, so the logits of the
+    # seeds in a training step equal the layer-wise inference logits of the same nodes
+    rng = np.random.default_rng(12)
+    n, dims = 60, [5, 7, 3]
+    rows = [np.sort(rng.choice(n, size=int(rng.integers(0, 6)), replace=False)) for _ in range(n)]
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    indptr[1:] = np.cumsum([len(r) for r in rows])
+    indices = np.concatenate(rows).astype(np.int32)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    y = rng.integers(0, dims[2], size=n).astype(np.int32)
+    W = [rng.standard_normal((2 * dims[l], dims[l + 1])) * 0.3 for l in range(2)]
+    b = [rng.standard_normal(dims[l + 1]) * 0.1 for l in range(2)]
+    seeds = np.array([3, 17, 42, 0, 59], dtype=np.int32)
+    step = orc.train_step(indptr, indices, X, y, seeds, [8, 8], W, b, seed=5, step=0, lr=0.0)
+    full = orc.infer_layerwise(indptr, indices, X, W, b)
+    assert np.allclose(step["logits"], full[seeds], rtol=1e-12, atol=1e-12)
+
+
+def test_model_average_closed_forms():
+    rng = np.random.default_rng(13)
+    a, c = rng.standard_normal(50), rng.standard_normal(50)
+    assert np.array_equal(orc.model_average([a, a, a], [5, 1, 9]), a * (5 / 15) + a * (1 / 15) + a * (9 / 15))
+    assert np.allclose(orc.model_average([a, a], [3, 4]), a, rtol=1e-15)           # identical models stay put
+    assert np.array_equal(orc.model_average([a, c], [7, 0]), a)                     # a worker without training nodes
+    assert np.allclose(orc.model_average([a, c], [1, 1]), (a + c) / 2, rtol=1e-15)  # equal shares: plain mean
+    got = orc.model_average([np.array([1.0, 2.0]), np.array([5.0, -2.0])], [1, 3])  # worked by hand
+    assert np.allclose(got, [4.0, -1.0])
+    # the weights sum to one: a constant shift of every model shifts the average by the same constant
+    assert np.allclose(orc.model_average([a + 2, c + 2], [2, 5]), orc.model_average([a, c], [2, 5]) + 2)

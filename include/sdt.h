@@ -281,6 +281,58 @@ int32_t sdt_train_loop(const sdt_csr *graph /*host struct*/, const void *X, int6
                        uint32_t first_step, float lr, float *losses_d, sdt_timing *timing /*host, nullable*/,
                        void *ws, size_t ws_bytes, void *stream, void *aux_stream);
 
+/* ---- layer-wise full-neighbour inference (Sec. IV-A: trained models are scored on
+ * nodes with all of their neighbours) ----------------------------------------------
+ * For every layer l over ALL n_nodes rows: A = mean over the node's whole CSR row,
+ * H' = act(H W[l][0:in] + A W[l][in:2in] + b[l]), ReLU on all but the last layer;
+ * H_0 = X.  logits is device fp32 [n_nodes, dims[L]] with leading dimension ldl.
+ * Hidden activations are kept in `dtype` (bf16: rounded as in the training step).
+ * n_nodes must be below 2^31.  The workspace (size from the query; no state) holds
+ * the aggregated rows and two hidden-activation buffers of n_nodes rows each. */
+size_t sdt_infer_layerwise_workspace_bytes(int64_t n_nodes, const sdt_model *model /*host struct*/, int32_t dtype);
+int32_t sdt_infer_layerwise(const sdt_csr *graph /*host struct*/, const void *X, int64_t ldx, int32_t dtype,
+                            const sdt_model *model /*host struct*/, float *logits, int64_t ldl, void *ws,
+                            size_t ws_bytes, void *stream);
+
+/* ---- model synchronisation by weighted averaging (Sec. III-D) --------------------
+ * out[e] = sum_i alpha[i] * params[i][e] for e < n_elems, accumulated in fp32 in the
+ * order i = 0, 1, ... (deterministic).  In the paper alpha_i is worker i's share of
+ * the training nodes; the caller passes the weights.  params is a HOST array of
+ * n_models (1..64) device pointers, alpha a HOST array; out may be one of params[i]. */
+int32_t sdt_model_average(const float *const *params /*host array of device pointers*/,
+                          const float *alpha /*host*/, int32_t n_models, int64_t n_elems, float *out,
+                          void *stream);
+
+/* ---- one synchronisation round on a GPU that holds several partitions (Sec. III-C:
+ * with more partitions than GPUs a GPU trains the local models of its partitions one
+ * after the other; Sec. III-D: all local models are then averaged in proportion to
+ * their numbers of training nodes) ---------------------------------------------------
+ * For each partition j: local[j] <- global (weights and biases copied), then
+ * sdt_train_loop on partition j with local[j] for its n_steps mini-batches (step
+ * counter first_step + i); finally global <- sum_j alpha_j local[j] with
+ * alpha_j = n_train_j / sum n_train.  losses_d receives sum_j n_steps_j losses,
+ * partition after partition.  `locals` are caller-allocated models of the same
+ * shape as `global_model`.  ws must hold sdt_train_loop's workspace for the largest
+ * partition (sdt_train_round_workspace_bytes). */
+typedef struct sdt_partition {
+    sdt_csr graph;
+    const void *X;         /* [graph.n_nodes, dims[0]] in the round's dtype */
+    int64_t ldx;
+    const int32_t *labels; /* [graph.n_nodes] */
+    const int32_t *seeds;  /* device int32 [n_steps, batch] */
+    int32_t n_steps;
+    int32_t reserved;
+    int64_t n_train;       /* number of training nodes: the averaging weight */
+} sdt_partition;
+size_t sdt_train_round_workspace_bytes(const sdt_partition *parts /*host*/, int32_t n_parts, int32_t batch,
+                                       const int32_t *fanouts /*host*/, const sdt_model *model /*host*/,
+                                       int32_t dtype);
+int32_t sdt_train_round(const sdt_partition *parts /*host*/, int32_t n_parts, int32_t dtype, int32_t batch,
+                        const int32_t *fanouts /*host*/, const sdt_model *global_model /*host struct*/,
+                        const sdt_model *locals /*host array of n_parts structs*/, uint64_t seed,
+                        uint32_t first_step, float lr, float *losses_d, void *ws, size_t ws_bytes, void *stream,
+                        void *aux_stream);
+
 #ifdef __cplusplus
 }
 #endif

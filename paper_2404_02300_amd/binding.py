@@ -59,6 +59,11 @@ class sdt_step_layout(ctypes.Structure):
                 ("dW", _u64 * _L), ("db", _u64 * _L), ("row_loss", _u64), ("scratch", _u64), ("wlow", _u64)]
 
 
+class sdt_partition(ctypes.Structure):
+    _fields_ = [("graph", sdt_csr), ("X", _vp), ("ldx", _i64), ("labels", _vp), ("seeds", _vp),
+                ("n_steps", _i32), ("reserved", _i32), ("n_train", _i64)]
+
+
 EXPORTS = {
     "sdt_version": (ctypes.c_char_p, []),
     "sdt_last_error": (ctypes.c_char_p, []),
@@ -80,6 +85,12 @@ EXPORTS = {
     "sdt_train_loop_workspace_bytes": (_sz, [_i64, _i32, _vp, _vp, _i32]),
     "sdt_train_loop": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp, _i32, _i32, _vp, _vp, _u64, _u32, ctypes.c_float, _vp,
                               _vp, _vp, _sz, _vp, _vp]),
+    "sdt_infer_layerwise_workspace_bytes": (_sz, [_i64, _vp, _i32]),
+    "sdt_infer_layerwise": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp, _i64, _vp, _sz, _vp]),
+    "sdt_model_average": (_i32, [_vp, _vp, _i32, _i64, _vp, _vp]),
+    "sdt_train_round_workspace_bytes": (_sz, [_vp, _i32, _i32, _vp, _vp, _i32]),
+    "sdt_train_round": (_i32, [_vp, _i32, _i32, _i32, _vp, _vp, _vp, _u64, _u32, ctypes.c_float, _vp, _vp, _sz, _vp,
+                               _vp]),
     "sdt_timing_create": (_i32, [_i32, _u64, _vp]),
     "sdt_timing_destroy": (None, [_vp]),
     "sdt_timing_reset": (None, [_vp]),
@@ -302,6 +313,57 @@ def sdt_train_loop(graph: Csr, X: torch.Tensor, labels: torch.Tensor, seeds: tor
                                 _ptr(seeds), seeds.shape[1], seeds.shape[0], f, ctypes.byref(model), seed,
                                 first_step, lr, _ptr(losses), timing.handle if timing is not None else None,
                                 _ptr(ws), ws.numel() * ws.element_size(), main, aux))
+
+
+def sdt_infer_layerwise_workspace_bytes(n_nodes: int, model: sdt_model, dtype: int) -> int:
+    return lib().sdt_infer_layerwise_workspace_bytes(n_nodes, ctypes.byref(model), dtype)
+
+
+def sdt_infer_layerwise(graph: Csr, X: torch.Tensor, model: sdt_model, logits: torch.Tensor, ws: torch.Tensor):
+    """logits: fp32 [n_nodes, dims[L]] on the device."""
+    assert logits.dtype == torch.float32 and logits.stride(1) == 1
+    _check(lib().sdt_infer_layerwise(ctypes.byref(graph.c), _ptr(X), X.stride(0), dtype_code(X), ctypes.byref(model),
+                                     _ptr(logits), logits.stride(0), _ptr(ws), ws.numel() * ws.element_size(),
+                                     _stream()))
+
+
+def sdt_model_average(params: Sequence[torch.Tensor], alpha: Sequence[float], out: torch.Tensor):
+    """out = sum_i alpha[i] * params[i] (fp32 tensors of one size; out may be one of them)."""
+    n = out.numel()
+    assert all(p.dtype == torch.float32 and p.is_contiguous() and p.numel() == n for p in params)
+    assert out.dtype == torch.float32 and out.is_contiguous() and len(alpha) == len(params)
+    ptrs = (_vp * len(params))(*[p.data_ptr() for p in params])
+    al = (ctypes.c_float * len(alpha))(*alpha)
+    _check(lib().sdt_model_average(ptrs, al, len(params), n, _ptr(out), _stream()))
+
+
+def make_partition(graph: Csr, X: torch.Tensor, labels: torch.Tensor, seeds: torch.Tensor, n_train: int) -> sdt_partition:
+    """seeds: int32 [n_steps, batch] on the device."""
+    assert seeds.dim() == 2 and seeds.is_contiguous() and seeds.dtype == torch.int32
+    p = sdt_partition()
+    p.graph = graph.c
+    p.X, p.ldx, p.labels, p.seeds = X.data_ptr(), X.stride(0), labels.data_ptr(), seeds.data_ptr()
+    p.n_steps, p.reserved, p.n_train = seeds.shape[0], 0, n_train
+    return p
+
+
+def sdt_train_round_workspace_bytes(parts: Sequence[sdt_partition], batch: int, fanouts: Sequence[int],
+                                    model: sdt_model, dtype: int) -> int:
+    arr = (sdt_partition * len(parts))(*parts)
+    f = (_i32 * len(fanouts))(*fanouts)
+    return lib().sdt_train_round_workspace_bytes(arr, len(parts), batch, f, ctypes.byref(model), dtype)
+
+
+def sdt_train_round(parts: Sequence[sdt_partition], dtype: int, batch: int, fanouts: Sequence[int],
+                    global_model: sdt_model, local_models: Sequence[sdt_model], seed: int, first_step: int, lr: float,
+                    losses: torch.Tensor, ws: torch.Tensor, aux_stream: Optional[torch.cuda.Stream] = None):
+    arr = (sdt_partition * len(parts))(*parts)
+    loc = (sdt_model * len(local_models))(*local_models)
+    f = (_i32 * len(fanouts))(*fanouts)
+    main = _stream()
+    aux = ctypes.c_void_p(aux_stream.cuda_stream) if aux_stream is not None else main
+    _check(lib().sdt_train_round(arr, len(parts), dtype, batch, f, ctypes.byref(global_model), loc, seed, first_step,
+                                 lr, _ptr(losses), _ptr(ws), ws.numel() * ws.element_size(), main, aux))
 
 
 def sdt_timing_create(max_steps: int, stage_mask: int) -> ctypes.c_void_p:

@@ -1,0 +1,216 @@
+// Around the mini-batch step: layer-wise full-neighbour inference over a whole partition,
+// weighted model averaging, and one synchronisation round over several partitions held by
+// one GPU.  All three are chains of the step's own kernels plus one small averaging kernel.
+#include "common.h"
+
+namespace sdt {
+namespace {
+
+constexpr int MAX_MODELS = 64;
+struct AvgArgs {
+    const float* p[MAX_MODELS];
+    float alpha[MAX_MODELS];
+    int32_t n;
+};
+
+__global__ __launch_bounds__(256) void k_model_average(AvgArgs a, int64_t n_elems, float* __restrict__ out) {
+    for (int64_t e = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; e < n_elems; e += (int64_t)gridDim.x * blockDim.x) {
+        float acc = 0.f;
+        for (int i = 0; i < a.n; ++i) acc += a.alpha[i] * a.p[i][e];
+        out[e] = acc;
+    }
+}
+
+struct InferWs {
+    size_t a_off, h_off[2], w_off, total;
+};
+InferWs infer_ws(int64_t n_nodes, const sdt_model* m, int32_t dtype) {
+    const size_t es = dtype_size(dtype);
+    int32_t max_in = 0, max_hidden = 0;
+    size_t wb = 0;
+    for (int l = 0; l < m->n_layers; ++l) {
+        if (m->dims[l] > max_in) max_in = m->dims[l];
+        if (l + 1 < m->n_layers && m->dims[l + 1] > max_hidden) max_hidden = m->dims[l + 1];
+        if (dtype == SDT_BF16) wb += bf16_weights_bytes(m->dims[l], m->dims[l + 1]);
+    }
+    InferWs w;
+    Arena a(nullptr);
+    w.a_off = a.take_off((size_t)n_nodes * max_in * es);
+    w.h_off[0] = a.take_off((size_t)n_nodes * (max_hidden > 0 ? max_hidden : 1) * es);
+    w.h_off[1] = a.take_off((size_t)n_nodes * (max_hidden > 0 ? max_hidden : 1) * es);
+    w.w_off = a.take_off(wb);
+    w.total = a.off;
+    return w;
+}
+
+int32_t check_model_ptrs(const sdt_model* m, const char* who) {
+    SDT_REQUIRE(m && m->n_layers >= 1 && m->n_layers <= SDT_MAX_LAYERS, SDT_ERR_INVALID_ARG, "%s: bad model", who);
+    for (int l = 0; l < m->n_layers; ++l)
+        SDT_REQUIRE(m->dims[l] > 0 && m->dims[l + 1] > 0 && m->W[l] && m->b[l], SDT_ERR_INVALID_ARG,
+                    "%s: layer %d has a null tensor or an empty dimension", who, l);
+    return SDT_OK;
+}
+
+}  // namespace
+}  // namespace sdt
+
+using namespace sdt;
+
+extern "C" size_t sdt_infer_layerwise_workspace_bytes(int64_t n_nodes, const sdt_model* model, int32_t dtype) {
+    if (!model || n_nodes < 0 || !dtype_ok(dtype) || model->n_layers < 1 || model->n_layers > SDT_MAX_LAYERS) return 0;
+    return infer_ws(n_nodes, model, dtype).total;
+}
+
+extern "C" int32_t sdt_infer_layerwise(const sdt_csr* graph, const void* X, int64_t ldx, int32_t dtype,
+                                       const sdt_model* model, float* logits, int64_t ldl, void* ws, size_t ws_bytes,
+                                       void* stream) {
+    int32_t rc = check_model_ptrs(model, "sdt_infer_layerwise");
+    if (rc != SDT_OK) return rc;
+    SDT_REQUIRE(graph && graph->indptr && dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_infer_layerwise: null graph or dtype");
+    const int64_t N = graph->n_nodes;
+    SDT_REQUIRE(N >= 0 && N < 0x7FFFFFFF, SDT_ERR_INVALID_ARG, "sdt_infer_layerwise: n_nodes %lld out of range",
+                (long long)N);
+    if (N == 0) return SDT_OK;
+    const int L = model->n_layers;
+    const int32_t* d = model->dims;
+    SDT_REQUIRE(X && logits && ldx >= d[0] && ldl >= d[L], SDT_ERR_INVALID_ARG,
+                "sdt_infer_layerwise: null tensor or leading dimension too small");
+    const InferWs w = infer_ws(N, model, dtype);
+    SDT_REQUIRE(ws && ws_bytes >= w.total && aligned16(ws), SDT_ERR_WORKSPACE,
+                "sdt_infer_layerwise: workspace of %zu bytes needed, %zu given", w.total, ws_bytes);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char* base = static_cast<char*>(ws);
+    const char* wt[SDT_MAX_LAYERS] = {};
+    if (dtype == SDT_BF16) {
+        rc = convert_weights_bf16(model, base + w.w_off, st);
+        if (rc != SDT_OK) return rc;
+        const char* p = base + w.w_off;
+        for (int l = 0; l < L; ++l) {
+            wt[l] = p;
+            p += bf16_weights_bytes(d[l], d[l + 1]);
+        }
+    }
+    const void* H = X;
+    int64_t ldh = ldx;
+    for (int l = 0; l < L; ++l) {
+        void* A = base + w.a_off;
+        rc = sdt_sage_aggregate_csr_fwd(graph, H, ldh, d[l], dtype, A, d[l], stream);
+        if (rc != SDT_OK) return rc;
+        const bool last = l == L - 1;
+        void* Y = last ? static_cast<void*>(logits) : static_cast<void*>(base + w.h_off[l & 1]);
+        const int64_t ldy = last ? ldl : d[l + 1];
+        if (dtype == SDT_BF16 && bf16_mfma_fwd_ok(H, ldh, A, d[l], d[l]))
+            rc = linear_fwd_bf16(H, ldh, A, d[l], (int32_t)N, nullptr, d[l], d[l + 1], wt[l], model->b[l], last ? 0 : 1, Y, ldy,
+                                 last ? SDT_F32 : dtype, st);
+        else
+            rc = sdt_sage_linear_fwd(H, ldh, A, d[l], (int32_t)N, nullptr, d[l], d[l + 1], model->W[l], model->b[l],
+                                     last ? 0 : 1, dtype, Y, ldy, last ? SDT_F32 : dtype, stream);
+        if (rc != SDT_OK) return rc;
+        H = Y;
+        ldh = ldy;
+    }
+    return SDT_OK;
+}
+
+extern "C" int32_t sdt_model_average(const float* const* params, const float* alpha, int32_t n_models, int64_t n_elems,
+                                     float* out, void* stream) {
+    SDT_REQUIRE(params && alpha && out && n_models >= 1 && n_models <= MAX_MODELS && n_elems >= 0, SDT_ERR_INVALID_ARG,
+                "sdt_model_average: null argument or n_models outside [1,%d]", MAX_MODELS);
+    if (n_elems == 0) return SDT_OK;
+    AvgArgs a{};
+    a.n = n_models;
+    for (int i = 0; i < n_models; ++i) {
+        SDT_REQUIRE(params[i], SDT_ERR_INVALID_ARG, "sdt_model_average: params[%d] is null", i);
+        a.p[i] = params[i];
+        a.alpha[i] = alpha[i];
+    }
+    const int blocks = (int)((n_elems + 255) / 256 < 4096 ? (n_elems + 255) / 256 : 4096);
+    hipLaunchKernelGGL(k_model_average, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), a, n_elems, out);
+    SDT_CHECK_LAUNCH("model_average");
+    return SDT_OK;
+}
+
+extern "C" size_t sdt_train_round_workspace_bytes(const sdt_partition* parts, int32_t n_parts, int32_t batch,
+                                                  const int32_t* fanouts, const sdt_model* model, int32_t dtype) {
+    if (!parts || n_parts < 1) return 0;
+    size_t m = 0;
+    for (int j = 0; j < n_parts; ++j) {
+        const size_t b = sdt_train_loop_workspace_bytes(parts[j].graph.n_nodes, batch, fanouts, model, dtype);
+        if (b == 0) return 0;
+        if (b > m) m = b;
+    }
+    return m;
+}
+
+extern "C" int32_t sdt_train_round(const sdt_partition* parts, int32_t n_parts, int32_t dtype, int32_t batch,
+                                   const int32_t* fanouts, const sdt_model* global_model, const sdt_model* locals,
+                                   uint64_t seed, uint32_t first_step, float lr, float* losses_d, void* ws,
+                                   size_t ws_bytes, void* stream, void* aux_stream) {
+    int32_t rc = check_model_ptrs(global_model, "sdt_train_round");
+    if (rc != SDT_OK) return rc;
+    SDT_REQUIRE(parts && locals && n_parts >= 1 && n_parts <= MAX_MODELS, SDT_ERR_INVALID_ARG,
+                "sdt_train_round: n_parts outside [1,%d] or null argument", MAX_MODELS);
+    const int L = global_model->n_layers;
+    double total = 0;
+    for (int j = 0; j < n_parts; ++j) {
+        rc = check_model_ptrs(&locals[j], "sdt_train_round (local model)");
+        if (rc != SDT_OK) return rc;
+        SDT_REQUIRE(locals[j].n_layers == L, SDT_ERR_INVALID_ARG, "sdt_train_round: local model %d has another depth", j);
+        for (int l = 0; l <= L; ++l)
+            SDT_REQUIRE(locals[j].dims[l] == global_model->dims[l], SDT_ERR_INVALID_ARG,
+                        "sdt_train_round: local model %d has another shape", j);
+        SDT_REQUIRE(parts[j].n_train >= 0 && parts[j].n_steps >= 0, SDT_ERR_INVALID_ARG,
+                    "sdt_train_round: partition %d has a negative count", j);
+        total += (double)parts[j].n_train;
+    }
+    SDT_REQUIRE(total > 0, SDT_ERR_INVALID_ARG, "sdt_train_round: no training nodes at all");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int64_t done = 0;
+    for (int j = 0; j < n_parts; ++j) {
+        // every local model starts the round from the synchronised weights
+        for (int l = 0; l < L; ++l) {
+            const size_t wb = (size_t)2 * global_model->dims[l] * global_model->dims[l + 1] * sizeof(float);
+            const size_t bb = (size_t)global_model->dims[l + 1] * sizeof(float);
+            if (hipMemcpyAsync(locals[j].W[l], global_model->W[l], wb, hipMemcpyDeviceToDevice, st) != hipSuccess ||
+                hipMemcpyAsync(locals[j].b[l], global_model->b[l], bb, hipMemcpyDeviceToDevice, st) != hipSuccess) {
+                set_error("sdt_train_round: copying the synchronised weights failed");
+                return SDT_ERR_HIP;
+            }
+        }
+        if (parts[j].n_steps > 0) {
+            // The step workspaces carry a header that says whether their node map is clean.  The
+            // previous partition laid its buffers out differently, so invalidate the headers of the
+            // three step workspaces of this partition's layout before its first step.
+            sdt_step_layout lay;
+            rc = sdt_train_step_layout(parts[j].graph.n_nodes, batch, fanouts, &locals[j], dtype, &lay);
+            if (rc != SDT_OK) return rc;
+            const size_t one = align_up((size_t)lay.total_bytes, 256);
+            SDT_REQUIRE(ws && ws_bytes >= 3 * one, SDT_ERR_WORKSPACE, "sdt_train_round: workspace of %zu bytes needed, %zu given",
+                        3 * one, ws_bytes);
+            for (int k = 0; k < 3; ++k)
+                if (hipMemsetAsync(static_cast<char*>(ws) + k * one, 0, 256, st) != hipSuccess) {
+                    set_error("sdt_train_round: clearing a workspace header failed");
+                    return SDT_ERR_HIP;
+                }
+            rc = sdt_train_loop(&parts[j].graph, parts[j].X, parts[j].ldx, dtype, parts[j].labels, parts[j].seeds, batch,
+                                parts[j].n_steps, fanouts, &locals[j], seed, first_step, lr, losses_d + done, nullptr, ws,
+                                ws_bytes, stream, aux_stream);
+            if (rc != SDT_OK) return rc;
+        }
+        done += parts[j].n_steps;
+    }
+    // w = sum_j alpha_j w_j, tensor by tensor
+    float alpha[MAX_MODELS];
+    for (int j = 0; j < n_parts; ++j) alpha[j] = (float)((double)parts[j].n_train / total);
+    const float* src[MAX_MODELS];
+    for (int l = 0; l < L; ++l) {
+        for (int j = 0; j < n_parts; ++j) src[j] = locals[j].W[l];
+        rc = sdt_model_average(src, alpha, n_parts, (int64_t)2 * global_model->dims[l] * global_model->dims[l + 1],
+                               global_model->W[l], stream);
+        if (rc != SDT_OK) return rc;
+        for (int j = 0; j < n_parts; ++j) src[j] = locals[j].b[l];
+        rc = sdt_model_average(src, alpha, n_parts, global_model->dims[l + 1], global_model->b[l], stream);
+        if (rc != SDT_OK) return rc;
+    }
+    return SDT_OK;
+}

@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--lr", type=float, default=0.01)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial", action="store_true", help="no auxiliary stream: every step strictly in sequence")
+    ap.add_argument("--aux", type=int, default=2, help="auxiliary streams the sampling phase alternates between")
     ap.add_argument("--cpu-steps", type=int, default=2, help="oracle steps timed for cpu_baseline")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run one plain 1 GiB device copy (a reference dispatch for rocprofv3 --pmc runs)")
@@ -99,7 +100,7 @@ def main():
     loss = torch.zeros(1, dtype=torch.float32, device="cuda")
     losses = torch.zeros(Wm + K, dtype=torch.float32, device="cuda")
     seeds_all = torch.from_numpy(np.stack([inst.batch(s) for s in range(Wm + K)])).cuda()
-    aux = None if args.serial else torch.cuda.Stream()
+    aux = None if args.serial else [torch.cuda.Stream() for _ in range(max(1, min(3, args.aux)))]
     L = len(wl.fanouts)
     es = 2 if wl.bf16 else 4
 
@@ -234,7 +235,7 @@ def main():
         "sampled_edges_per_s": round(edges_per_step * K / elapsed, 1),
         "sampled_edges_per_step": round(edges_per_step, 1),
         "frontier_rows_per_step": round(float(n_src0), 1),
-        "final_loss": round(final_loss, 6), "overlap": "serial" if args.serial else "sampling of step i+1 on an auxiliary stream",
+        "final_loss": round(final_loss, 6), "overlap": "serial" if args.serial else f"sampling of the next steps on {len(aux)} auxiliary stream(s)",
         "roofline": roofline, "cpu_baseline": cpu,
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()}, "stage_rates": others,
     }

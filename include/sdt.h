@@ -262,24 +262,30 @@ int32_t sdt_train_step(const sdt_csr *graph /*host struct*/, const void *X, int6
  * Same result, bit for bit, as n_steps calls of sdt_train_step with step =
  * first_step + i, seeds + i*batch and loss_d = losses_d + i -- but the phase of
  * a step that needs no weights (sampling, frontier, gather) is enqueued on
- * `aux_stream` and runs up to three steps ahead of the forward/backward phase on
- * `stream`, rotating through three step workspaces (Sec. II-A: the
+ * the auxiliary streams (groups of consecutive steps alternate between them)
+ * and runs a few steps ahead of the forward/backward phase on `stream`, rotating
+ * through several step workspaces; streams hand over groups of steps, one pair of
+ * events per group (Sec. II-A: the
  * mini-batch sub-graphs are independent of the model; Sec. III-D: a worker
  * trains many mini-batches between two synchronisations).  Ordering between
  * the two streams uses HIP events created and released inside the call.  When
  * the call returns everything is enqueued; synchronising `stream` is enough.
  * seeds is device int32[n_steps, batch]; losses_d device fp32[n_steps].  The
- * workspace (sdt_train_loop_workspace_bytes: three step workspaces, each with
- * sdt_train_step's layout, at thirds of the size) carries
- * state like sdt_train_step's.  aux_stream == stream gives the serial order.
- * Both streams must have the default priority. */
+ * workspace (sdt_train_loop_workspace_bytes: a whole number of step workspaces,
+ * each with sdt_train_step's layout rounded up to 256 bytes, back to back;
+ * step i of a call uses workspace i modulo their number) carries
+ * state like sdt_train_step's.  aux_streams is a HOST array of n_aux (0..3)
+ * streams, all different from `stream`; n_aux = 0 gives the serial order.  The
+ * sampling chain is a sequence of small latency-bound launches, so two auxiliary
+ * streams sample twice as many steps per unit of time as one.
+ * All streams must have the default priority. */
 size_t sdt_train_loop_workspace_bytes(int64_t n_nodes, int32_t batch, const int32_t *fanouts /*host*/,
                                       const sdt_model *model /*host struct*/, int32_t dtype);
 int32_t sdt_train_loop(const sdt_csr *graph /*host struct*/, const void *X, int64_t ldx, int32_t dtype,
                        const int32_t *labels, const int32_t *seeds, int32_t batch, int32_t n_steps,
                        const int32_t *fanouts /*host*/, const sdt_model *model /*host struct*/, uint64_t seed,
                        uint32_t first_step, float lr, float *losses_d, sdt_timing *timing /*host, nullable*/,
-                       void *ws, size_t ws_bytes, void *stream, void *aux_stream);
+                       void *ws, size_t ws_bytes, void *stream, void *const *aux_streams /*host*/, int32_t n_aux);
 
 /* ---- layer-wise full-neighbour inference (Sec. IV-A: trained models are scored on
  * nodes with all of their neighbours) ----------------------------------------------
@@ -331,7 +337,7 @@ int32_t sdt_train_round(const sdt_partition *parts /*host*/, int32_t n_parts, in
                         const int32_t *fanouts /*host*/, const sdt_model *global_model /*host struct*/,
                         const sdt_model *locals /*host array of n_parts structs*/, uint64_t seed,
                         uint32_t first_step, float lr, float *losses_d, void *ws, size_t ws_bytes, void *stream,
-                        void *aux_stream);
+                        void *const *aux_streams /*host*/, int32_t n_aux);
 
 #ifdef __cplusplus
 }

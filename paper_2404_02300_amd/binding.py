@@ -84,13 +84,13 @@ EXPORTS = {
                               _vp, _sz, _vp]),
     "sdt_train_loop_workspace_bytes": (_sz, [_i64, _i32, _vp, _vp, _i32]),
     "sdt_train_loop": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp, _i32, _i32, _vp, _vp, _u64, _u32, ctypes.c_float, _vp,
-                              _vp, _vp, _sz, _vp, _vp]),
+                              _vp, _vp, _sz, _vp, _vp, _i32]),
     "sdt_infer_layerwise_workspace_bytes": (_sz, [_i64, _vp, _i32]),
     "sdt_infer_layerwise": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp, _i64, _vp, _sz, _vp]),
     "sdt_model_average": (_i32, [_vp, _vp, _i32, _i64, _vp, _vp]),
     "sdt_train_round_workspace_bytes": (_sz, [_vp, _i32, _i32, _vp, _vp, _i32]),
     "sdt_train_round": (_i32, [_vp, _i32, _i32, _i32, _vp, _vp, _vp, _u64, _u32, ctypes.c_float, _vp, _vp, _sz, _vp,
-                               _vp]),
+                               _vp, _i32]),
     "sdt_timing_create": (_i32, [_i32, _u64, _vp]),
     "sdt_timing_destroy": (None, [_vp]),
     "sdt_timing_reset": (None, [_vp]),
@@ -301,18 +301,28 @@ def sdt_train_loop_workspace_bytes(n_nodes: int, batch: int, fanouts: Sequence[i
     return lib().sdt_train_loop_workspace_bytes(n_nodes, batch, f, ctypes.byref(model), dtype)
 
 
+def _aux_array(aux_streams):
+    """None, one torch stream or a sequence of them -> (host array of stream handles, count)."""
+    if aux_streams is None:
+        return None, 0
+    if isinstance(aux_streams, torch.cuda.Stream):
+        aux_streams = [aux_streams]
+    return (_vp * len(aux_streams))(*[s.cuda_stream for s in aux_streams]), len(aux_streams)
+
+
 def sdt_train_loop(graph: Csr, X: torch.Tensor, labels: torch.Tensor, seeds: torch.Tensor, fanouts: Sequence[int],
                    model: sdt_model, seed: int, first_step: int, lr: float, losses: torch.Tensor, ws: torch.Tensor,
-                   aux_stream: Optional[torch.cuda.Stream] = None, timing: Optional["Timing"] = None):
-    """seeds: int32 [n_steps, batch] on the device; losses: fp32 [n_steps]."""
+                   aux_streams=None, timing: Optional["Timing"] = None):
+    """seeds: int32 [n_steps, batch] on the device; losses: fp32 [n_steps]; aux_streams: None (serial),
+    one torch stream or up to three."""
     assert seeds.dim() == 2 and seeds.is_contiguous() and losses.numel() >= seeds.shape[0]
     f = (_i32 * len(fanouts))(*fanouts)
     main = _stream()
-    aux = ctypes.c_void_p(aux_stream.cuda_stream) if aux_stream is not None else main
+    aux, n_aux = _aux_array(aux_streams)
     _check(lib().sdt_train_loop(ctypes.byref(graph.c), _ptr(X), X.stride(0), dtype_code(X), _ptr(labels),
                                 _ptr(seeds), seeds.shape[1], seeds.shape[0], f, ctypes.byref(model), seed,
                                 first_step, lr, _ptr(losses), timing.handle if timing is not None else None,
-                                _ptr(ws), ws.numel() * ws.element_size(), main, aux))
+                                _ptr(ws), ws.numel() * ws.element_size(), main, aux, n_aux))
 
 
 def sdt_infer_layerwise_workspace_bytes(n_nodes: int, model: sdt_model, dtype: int) -> int:
@@ -356,14 +366,14 @@ def sdt_train_round_workspace_bytes(parts: Sequence[sdt_partition], batch: int, 
 
 def sdt_train_round(parts: Sequence[sdt_partition], dtype: int, batch: int, fanouts: Sequence[int],
                     global_model: sdt_model, local_models: Sequence[sdt_model], seed: int, first_step: int, lr: float,
-                    losses: torch.Tensor, ws: torch.Tensor, aux_stream: Optional[torch.cuda.Stream] = None):
+                    losses: torch.Tensor, ws: torch.Tensor, aux_streams=None):
     arr = (sdt_partition * len(parts))(*parts)
     loc = (sdt_model * len(local_models))(*local_models)
     f = (_i32 * len(fanouts))(*fanouts)
     main = _stream()
-    aux = ctypes.c_void_p(aux_stream.cuda_stream) if aux_stream is not None else main
+    aux, n_aux = _aux_array(aux_streams)
     _check(lib().sdt_train_round(arr, len(parts), dtype, batch, f, ctypes.byref(global_model), loc, seed, first_step,
-                                 lr, _ptr(losses), _ptr(ws), ws.numel() * ws.element_size(), main, aux))
+                                 lr, _ptr(losses), _ptr(ws), ws.numel() * ws.element_size(), main, aux, n_aux))
 
 
 def sdt_timing_create(max_steps: int, stage_mask: int) -> ctypes.c_void_p:

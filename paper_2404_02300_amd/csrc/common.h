@@ -137,7 +137,19 @@ int32_t softmax_xent(const float* logits, int64_t ld, int32_t B, int32_t C, cons
                      const int32_t* seeds, float* dZ, float* row_loss, hipStream_t st);
 // Extra work the final reduction of a projection backward can carry: the SGD step on (W, b)
 // and the fixed-order mean of the per-seed losses.
+// A fixed-order sum of split partial products that is still to be done: dW[idx] = sum_s P[s][idx],
+// db[o] = sum_s Q[s][o], then (optionally) the SGD step W -= lr dW, b -= lr db.
+struct PendingReduce {
+    const float* P = nullptr;
+    const float* Q = nullptr;
+    int32_t splits = 0, in = 0, out = 0;
+    float* dW = nullptr;
+    float* db = nullptr;
+    float* W_upd = nullptr;
+    float* b_upd = nullptr;
+};
 struct BwdExtras {
+    PendingReduce* defer = nullptr;  // if set, the reduction is described here instead of launched
     const void* Wb = nullptr;  // bf16 image of W for the input gradient on the bf16 matrix path (or null)
     float* W_upd = nullptr;
     float* b_upd = nullptr;
@@ -155,6 +167,9 @@ int32_t linear_bwd(const void* dY, int64_t lddy, int32_t dy_dtype, const void* Y
 // dW = sum of `splits` partials P[s][2in][out], db likewise from Q[s][out], plus the extras
 int32_t reduce_partials(const float* P, const float* Q, int32_t splits, int32_t in, int32_t out, float* dW, float* db,
                         const BwdExtras& ex, hipStream_t st);
+// the pending reductions of several layers (and the mean of the per-seed losses) in ONE launch
+int32_t reduce_all(const PendingReduce* r, int32_t n, float lr, const float* row_loss, int32_t n_loss, float* loss_out,
+                   hipStream_t st);
 
 // bf16 matrix-core path (linear_bf16.hip).  Per layer the image region holds Wt = bf16 [out][2 in]
 // followed (256-byte aligned) by Wb = bf16 [2 in][bf16_ldb(out)], layers back to back.
@@ -169,6 +184,9 @@ int32_t linear_fwd_bf16(const void* Hself, int64_t ldh, const void* A, int64_t l
 int32_t linear_bwd_input_bf16(const void* dY, int64_t lddy, int32_t dy_dtype, int32_t n_cap, const int32_t* n_d,
                               int32_t in, int32_t out, const void* Wb, void* dSelf, void* dAgg, int64_t ldi,
                               hipStream_t st);
+
+// number of step workspaces sdt_train_loop rotates through (its workspace is that many step layouts)
+int32_t train_loop_buffers();
 
 // Fused last layer (projection + softmax cross-entropy + backward) for small class counts.
 bool head_supported(int32_t in, int32_t out);

@@ -145,7 +145,7 @@ extern "C" size_t sdt_train_round_workspace_bytes(const sdt_partition* parts, in
 extern "C" int32_t sdt_train_round(const sdt_partition* parts, int32_t n_parts, int32_t dtype, int32_t batch,
                                    const int32_t* fanouts, const sdt_model* global_model, const sdt_model* locals,
                                    uint64_t seed, uint32_t first_step, float lr, float* losses_d, void* ws,
-                                   size_t ws_bytes, void* stream, void* aux_stream) {
+                                   size_t ws_bytes, void* stream, void* const* aux_streams, int32_t n_aux) {
     int32_t rc = check_model_ptrs(global_model, "sdt_train_round");
     if (rc != SDT_OK) return rc;
     SDT_REQUIRE(parts && locals && n_parts >= 1 && n_parts <= MAX_MODELS, SDT_ERR_INVALID_ARG,
@@ -180,21 +180,22 @@ extern "C" int32_t sdt_train_round(const sdt_partition* parts, int32_t n_parts, 
         if (parts[j].n_steps > 0) {
             // The step workspaces carry a header that says whether their node map is clean.  The
             // previous partition laid its buffers out differently, so invalidate the headers of the
-            // three step workspaces of this partition's layout before its first step.
+            // step workspaces of this partition's layout before its first step.
             sdt_step_layout lay;
             rc = sdt_train_step_layout(parts[j].graph.n_nodes, batch, fanouts, &locals[j], dtype, &lay);
             if (rc != SDT_OK) return rc;
             const size_t one = align_up((size_t)lay.total_bytes, 256);
-            SDT_REQUIRE(ws && ws_bytes >= 3 * one, SDT_ERR_WORKSPACE, "sdt_train_round: workspace of %zu bytes needed, %zu given",
-                        3 * one, ws_bytes);
-            for (int k = 0; k < 3; ++k)
+            const int nb = train_loop_buffers();
+            SDT_REQUIRE(ws && ws_bytes >= nb * one, SDT_ERR_WORKSPACE, "sdt_train_round: workspace of %zu bytes needed, %zu given",
+                        nb * one, ws_bytes);
+            for (int k = 0; k < nb; ++k)
                 if (hipMemsetAsync(static_cast<char*>(ws) + k * one, 0, 256, st) != hipSuccess) {
                     set_error("sdt_train_round: clearing a workspace header failed");
                     return SDT_ERR_HIP;
                 }
             rc = sdt_train_loop(&parts[j].graph, parts[j].X, parts[j].ldx, dtype, parts[j].labels, parts[j].seeds, batch,
                                 parts[j].n_steps, fanouts, &locals[j], seed, first_step, lr, losses_d + done, nullptr, ws,
-                                ws_bytes, stream, aux_stream);
+                                ws_bytes, stream, aux_streams, n_aux);
             if (rc != SDT_OK) return rc;
         }
         done += parts[j].n_steps;

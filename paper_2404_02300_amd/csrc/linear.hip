@@ -363,18 +363,21 @@ __global__ __launch_bounds__(TL::NT) void k_linear_bwd_weight(const TH* __restri
 }
 
 // dW[idx] = sum_s P[s][idx]; db[o] = sum_s Q[s][o]; optionally the SGD step W -= lr dW,
-// b -= lr db in the same pass, and (one extra workgroup) the mean of the per-seed losses.
+// b -= lr db in the same pass, and (one extra workgroup) the mean of the per-seed losses --
+// for up to SDT_MAX_LAYERS layers in one launch (a launch costs more than this work).
 // A workgroup covers 64 consecutive elements with 4 threads each: thread g adds the partials
 // g, g+4, g+8, ... and the four sums are combined in the order 0,1,2,3 -- a fixed order, so
 // the result is deterministic, with four times as many loads in flight as one thread per element.
 constexpr int TB = 256;
-__global__ __launch_bounds__(TB) void k_reduce_partials(const float* __restrict__ P, const float* __restrict__ Q,
-                                                        int splits, int64_t n_w, int out, float* __restrict__ dW,
-                                                        float* __restrict__ db, float* W_upd, float* b_upd, float lr,
-                                                        const float* __restrict__ row_loss, int n_loss,
-                                                        float* loss_out) {
+struct ReduceArgs {
+    int32_t n;
+    int32_t first[SDT_MAX_LAYERS + 1];  // first workgroup of each layer
+    PendingReduce r[SDT_MAX_LAYERS];
+};
+__global__ __launch_bounds__(TB) void k_reduce_partials(ReduceArgs a, float lr, const float* __restrict__ row_loss,
+                                                        int n_loss, float* loss_out) {
     __shared__ float part[TB];
-    if (loss_out && blockIdx.x == gridDim.x - 1) {  // the extra last block: mean loss in a fixed order
+    if ((int)blockIdx.x == a.first[a.n]) {  // the extra last block: mean loss in a fixed order
         float s = 0.f;
         for (int i = threadIdx.x; i < n_loss; i += TB) s += row_loss[i];
         part[threadIdx.x] = s;
@@ -386,10 +389,15 @@ __global__ __launch_bounds__(TB) void k_reduce_partials(const float* __restrict_
         if (threadIdx.x == 0) *loss_out = part[0] / (float)n_loss;
         return;
     }
+    int l = 0;
+    while (l + 1 < a.n && (int)blockIdx.x >= a.first[l + 1]) ++l;
+    const PendingReduce& r = a.r[l];
+    const int64_t n_w = (int64_t)2 * r.in * r.out;
+    const int out = r.out, splits = r.splits;
     const int e = threadIdx.x & 63, g = threadIdx.x >> 6;
-    const int64_t idx = (int64_t)blockIdx.x * 64 + e;
+    const int64_t idx = (int64_t)((int)blockIdx.x - a.first[l]) * 64 + e;
     const bool is_w = idx < n_w, is_b = !is_w && idx < n_w + out;
-    const float* src = is_w ? P + idx : Q + (idx - n_w);
+    const float* src = is_w ? r.P + idx : r.Q + (idx - n_w);
     const int64_t stride = is_w ? n_w : out;
     float s = 0.f;
     if (is_w || is_b) {
@@ -401,12 +409,12 @@ __global__ __launch_bounds__(TB) void k_reduce_partials(const float* __restrict_
     if (g == 0 && (is_w || is_b)) {
         const float t = ((part[e] + part[64 + e]) + part[128 + e]) + part[192 + e];
         if (is_w) {
-            dW[idx] = t;
-            if (W_upd) W_upd[idx] = W_upd[idx] - lr * t;
+            r.dW[idx] = t;
+            if (r.W_upd) r.W_upd[idx] = r.W_upd[idx] - lr * t;
         } else {
             const int o = (int)(idx - n_w);
-            db[o] = t;
-            if (b_upd) b_upd[o] = b_upd[o] - lr * t;
+            r.db[o] = t;
+            if (r.b_upd) r.b_upd[o] = r.b_upd[o] - lr * t;
         }
     }
 }
@@ -536,9 +544,11 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Hself, int64_t ldh, co
         })
     }
     // after the input gradients: this pass may overwrite W with the SGD step
-    const int64_t n_w = (int64_t)2 * in * out;
-    hipLaunchKernelGGL(k_reduce_partials, dim3(ceil_div(n_w + out, 64) + (ex.loss_out ? 1 : 0)), dim3(TB), 0, st, P, Q,
-                       splits, n_w, out, dW, db, ex.W_upd, ex.b_upd, ex.lr, ex.row_loss, ex.n_loss, ex.loss_out);
+    PendingReduce pr;
+    pr.P = P; pr.Q = Q; pr.splits = splits; pr.in = in; pr.out = out;
+    pr.dW = dW; pr.db = db; pr.W_upd = ex.W_upd; pr.b_upd = ex.b_upd;
+    if (ex.defer) *ex.defer = pr;
+    else (void)reduce_all(&pr, 1, ex.lr, ex.row_loss, ex.n_loss, ex.loss_out, st);
 }
 
 
@@ -599,13 +609,32 @@ extern "C" size_t sdt_linear_bwd_workspace_bytes(int32_t n_cap, int32_t in, int3
 }
 
 namespace sdt {
-int32_t reduce_partials(const float* P, const float* Q, int32_t splits, int32_t in, int32_t out, float* dW, float* db,
-                        const BwdExtras& ex, hipStream_t st) {
-    const int64_t n_w = (int64_t)2 * in * out;
-    hipLaunchKernelGGL(k_reduce_partials, dim3(ceil_div(n_w + out, 64) + (ex.loss_out ? 1 : 0)), dim3(TB), 0, st, P, Q,
-                       splits, n_w, out, dW, db, ex.W_upd, ex.b_upd, ex.lr, ex.row_loss, ex.n_loss, ex.loss_out);
+int32_t reduce_all(const PendingReduce* r, int32_t n, float lr, const float* row_loss, int32_t n_loss, float* loss_out,
+                   hipStream_t st) {
+    SDT_REQUIRE(r && n >= 1 && n <= SDT_MAX_LAYERS, SDT_ERR_INVALID_ARG, "reduce_all: %d reductions", n);
+    ReduceArgs a{};
+    a.n = n;
+    a.first[0] = 0;
+    for (int l = 0; l < n; ++l) {
+        a.r[l] = r[l];
+        a.first[l + 1] = a.first[l] + ceil_div((int64_t)2 * r[l].in * r[l].out + r[l].out, 64);
+    }
+    hipLaunchKernelGGL(k_reduce_partials, dim3(a.first[n] + (loss_out ? 1 : 0)), dim3(TB), 0, st, a, lr, row_loss, n_loss,
+                       loss_out);
     SDT_CHECK_LAUNCH("reduce_partials");
     return SDT_OK;
+}
+
+int32_t reduce_partials(const float* P, const float* Q, int32_t splits, int32_t in, int32_t out, float* dW, float* db,
+                        const BwdExtras& ex, hipStream_t st) {
+    PendingReduce pr;
+    pr.P = P; pr.Q = Q; pr.splits = splits; pr.in = in; pr.out = out;
+    pr.dW = dW; pr.db = db; pr.W_upd = ex.W_upd; pr.b_upd = ex.b_upd;
+    if (ex.defer) {
+        *ex.defer = pr;
+        return SDT_OK;
+    }
+    return reduce_all(&pr, 1, ex.lr, ex.row_loss, ex.n_loss, ex.loss_out, st);
 }
 
 int32_t linear_bwd(const void* dY, int64_t lddy, int32_t dy_dtype, const void* Y, int64_t ldy, int32_t relu,

@@ -27,6 +27,16 @@ bool compute_caps(int64_t n_nodes, int32_t batch, const int32_t* fanouts, int L,
     return true;
 }
 
+// scratch of one layer's projection backward (split partials of dW/db, or the fused head's)
+size_t bwd_scratch_bytes(int32_t batch, int32_t cap_dst, int32_t in, int32_t out, bool last) {
+    size_t lb = sdt_linear_bwd_workspace_bytes(cap_dst, in, out);
+    if (last && head_supported(in, out)) {
+        const size_t hb = head_workspace_bytes(batch, in, out);
+        if (hb > lb) lb = hb;
+    }
+    return align_up(lb, 256);
+}
+
 int32_t check_model(const sdt_model* m, const int32_t* fanouts, const char* who) {
     SDT_REQUIRE(m && fanouts, SDT_ERR_INVALID_ARG, "%s: null model or fanouts", who);
     SDT_REQUIRE(m->n_layers >= 1 && m->n_layers <= SDT_MAX_LAYERS, SDT_ERR_INVALID_ARG, "%s: n_layers %d outside [1,%d]",
@@ -146,7 +156,7 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
     *lay = sdt_step_layout{};
     lay->n_layers = L;
     Arena a(nullptr);
-    size_t scratch = 0;
+    size_t scratch = 0, bwd_scratch = 0;
     lay->header = a.take_off(64 * sizeof(int32_t));
     lay->state = a.take_off(sample_state_bytes(n_nodes));
     for (int l = 0; l < L; ++l) {
@@ -170,14 +180,12 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
         lay->db[l] = a.take_off((size_t)d[l + 1] * 4);
         Arena s(nullptr);
         size_t sb = sample_tmp_carve(s, n_nodes, c.dst[l], fanouts[l], nullptr);
-        size_t lb = sdt_linear_bwd_workspace_bytes(c.dst[l], d[l], d[l + 1]);
-        if (l == L - 1 && head_supported(d[l], d[l + 1])) {
-            const size_t hb = head_workspace_bytes(batch, d[l], d[l + 1]);
-            if (hb > lb) lb = hb;
-        }
         if (sb > scratch) scratch = sb;
-        if (lb > scratch) scratch = lb;
+        bwd_scratch += bwd_scratch_bytes(batch, c.dst[l], d[l], d[l + 1], l == L - 1);
     }
+    // the sampling scratch is dead once phase 2 starts; the backward keeps one region per layer
+    // alive until the single reduction launch at the end of the step
+    if (bwd_scratch > scratch) scratch = bwd_scratch;
     lay->H[0] = a.take_off((size_t)c.dst[0] * d[0] * es);
     lay->dZ = a.take_off((size_t)batch * d[L] * 4);
     lay->row_loss = a.take_off((size_t)(batch > 0 ? batch : 1) * 4);
@@ -248,7 +256,8 @@ void bind_buffers(const sdt_step_layout& lay, void* ws, size_t bytes, StepBuffer
 // Phase 1 (needs no weights): sample from the seeds outwards, then gather the input features
 // of the outermost frontier.  The node -> local-id map carries over from layer to layer; the
 // gather hands it back clean for the next step that uses this workspace.
-int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds, uint32_t step, hipStream_t st) {
+int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds, uint32_t step, hipStream_t st,
+                    bool check_state = true) {
     const sdt_step_layout& lay = c.lay;
     const int L = c.model->n_layers;
     const int32_t* d = c.model->dims;
@@ -262,8 +271,12 @@ int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds
     for (int l = L - 1; l >= 0; --l) {
         StageTimer tl(c.timing, SDT_STAGE_SAMPLE, l, st);
         if (l == L - 1) {
-            rc = sample_state_init(sw, N, header, st);
-            if (rc != SDT_OK) return rc;
+            // the state check is skipped when the caller knows this workspace's previous user was an
+            // earlier step of the same run (which left the map clean and the header stamped)
+            if (check_state) {
+                rc = sample_state_init(sw, N, header, st);
+                if (rc != SDT_OK) return rc;
+            }
             rc = sample_seed_map(sw, seeds, c.batch, nullptr, header, N, st);
             if (rc != SDT_OK) return rc;
         }
@@ -299,7 +312,18 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
     // Small class counts: the last layer's projection, the loss and that layer's backward run
     // as one fused launch (head.hip) instead of five.
     const bool fused_head = head_supported(d[L - 1], d[L]) && aligned16(model->W[L - 1]);
-    const size_t scratch_bytes = (size_t)((lay.wlow ? lay.wlow : lay.total_bytes) - lay.scratch);
+    // one scratch region per layer, laid end to end (see sdt_train_step_layout)
+    size_t scr_off[SDT_MAX_LAYERS], scr_len[SDT_MAX_LAYERS];
+    {
+        size_t o = lay.scratch;
+        for (int l = 0; l < L; ++l) {
+            scr_len[l] = bwd_scratch_bytes(c.batch, lay.cap_dst[l], d[l], d[l + 1], l == L - 1);
+            scr_off[l] = o;
+            o += scr_len[l];
+        }
+    }
+    PendingReduce pending[SDT_MAX_LAYERS];
+    int n_pending = 0;
     // bf16 activations: the matrix products run on the bf16 matrix cores from bf16 images of the
     // weights, rewritten here every step (the weights are the caller's and change every step)
     const char* wt[SDT_MAX_LAYERS] = {};
@@ -354,36 +378,26 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
                               model->b[l], dtype, c.labels, seeds, static_cast<float*>(b.at(lay.H[L])),
                               static_cast<float*>(b.at(lay.dZ)), static_cast<float*>(b.at(lay.row_loss)),
                               inner ? b.at(lay.dSelf[l]) : nullptr, inner ? b.at(lay.dAgg[l]) : nullptr, d[l],
-                              b.at(lay.scratch), scratch_bytes, &P, &Q, st);
+                              b.at(scr_off[l]), scr_len[l], &P, &Q, st);
             }
             if (rc != SDT_OK) return rc;
             BwdExtras ex;
+            ex.defer = &pending[n_pending++];
             ex.W_upd = model->W[l];
             ex.b_upd = model->b[l];
-            ex.lr = c.lr;
-            ex.row_loss = static_cast<const float*>(b.at(lay.row_loss));
-            ex.n_loss = c.batch;
-            ex.loss_out = loss_d;
             rc = reduce_partials(P, Q, head_splits(c.batch), d[l], d[l + 1], dW, db, ex, st);
             if (rc != SDT_OK) return rc;
         } else {
             StageTimer tm(timing, SDT_STAGE_LINEAR_BWD, l, st);
-            // the SGD step of this layer (and, for the last layer, the mean of the per-seed
-            // losses) ride on the final reduction of its weight gradient
             BwdExtras ex;
+            ex.defer = &pending[n_pending++];
             ex.Wb = wb[l];
             ex.W_upd = model->W[l];
             ex.b_upd = model->b[l];
-            ex.lr = c.lr;
-            if (l == L - 1) {
-                ex.row_loss = static_cast<const float*>(b.at(lay.row_loss));
-                ex.n_loss = c.batch;
-                ex.loss_out = loss_d;
-            }
             rc = linear_bwd(dY, d[l + 1], dy_dtype, nullptr, 0, 0, b.at(lay.H[l]), d[l], b.at(lay.A[l]), d[l],
                             lay.cap_dst[l], b.blk[l].counts, d[l], d[l + 1], model->W[l], dtype, dW, db,
                             inner ? b.at(lay.dSelf[l]) : nullptr, inner ? b.at(lay.dAgg[l]) : nullptr, d[l],
-                            b.at(lay.scratch), scratch_bytes, ex, st);
+                            b.at(scr_off[l]), scr_len[l], ex, st);
             if (rc != SDT_OK) return rc;
         }
         if (inner) {
@@ -396,7 +410,11 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
             dy_dtype = dtype;
         }
     }
-    return SDT_OK;
+    // One launch finishes every layer: the split partial products of all weight gradients are
+    // summed in a fixed order, the SGD step is applied, and the per-seed losses are averaged.
+    // (No layer's weights were touched before this point, so every product above saw the
+    // weights the step started with.)
+    return reduce_all(pending, n_pending, c.lr, static_cast<const float*>(b.at(lay.row_loss)), c.batch, loss_d, st);
 }
 
 }  // namespace
@@ -424,7 +442,16 @@ extern "C" int32_t sdt_train_step(const sdt_csr* graph, const void* X, int64_t l
 }
 
 // Step workspaces the loop rotates through: the sampling phase may run this many steps ahead.
-static constexpr int LOOP_BUFFERS = 3;
+// The loop hands the two streams whole groups of steps: one pair of events per LOOP_GROUP steps instead
+// of per step (every cross-stream wait costs a few microseconds of an ~100 us step).
+static constexpr int LOOP_GROUP = 2;     // steps per hand-over
+static constexpr int LOOP_SLOTS = 4;     // groups in flight: up to three being sampled, one being trained on
+static constexpr int LOOP_MAX_AUX = LOOP_SLOTS - 1;
+static constexpr int LOOP_BUFFERS = LOOP_GROUP * LOOP_SLOTS;
+
+namespace sdt {
+int32_t train_loop_buffers() { return LOOP_BUFFERS; }
+}  // namespace sdt
 
 extern "C" size_t sdt_train_loop_workspace_bytes(int64_t n_nodes, int32_t batch, const int32_t* fanouts,
                                                  const sdt_model* model, int32_t dtype) {
@@ -436,7 +463,7 @@ extern "C" size_t sdt_train_loop_workspace_bytes(int64_t n_nodes, int32_t batch,
 extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t ldx, int32_t dtype, const int32_t* labels,
                                   const int32_t* seeds, int32_t batch, int32_t n_steps, const int32_t* fanouts,
                                   const sdt_model* model, uint64_t seed, uint32_t first_step, float lr, float* losses_d,
-                                  sdt_timing* timing, void* ws, size_t ws_bytes, void* stream, void* aux_stream) {
+                                  sdt_timing* timing, void* ws, size_t ws_bytes, void* stream, void* const* aux_streams, int32_t n_aux) {
     SDT_REQUIRE(graph && graph->indptr, SDT_ERR_INVALID_ARG, "sdt_train_loop: null graph");
     SDT_REQUIRE(n_steps >= 0, SDT_ERR_INVALID_ARG, "sdt_train_loop: n_steps = %d", n_steps);
     StepCtx c{graph, X, ldx, dtype, labels, batch, fanouts, model, seed, lr, timing, {}};
@@ -447,16 +474,22 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
     const size_t one = align_up((size_t)c.lay.total_bytes, 256);
     SDT_REQUIRE(ws && ws_bytes >= LOOP_BUFFERS * one && aligned16(ws), SDT_ERR_WORKSPACE,
                 "sdt_train_loop: workspace of %zu bytes needed, %zu given", LOOP_BUFFERS * one, ws_bytes);
+    SDT_REQUIRE(n_aux >= 0 && n_aux <= LOOP_MAX_AUX && (n_aux == 0 || aux_streams), SDT_ERR_INVALID_ARG,
+                "sdt_train_loop: n_aux = %d outside [0,%d] or null stream array", n_aux, LOOP_MAX_AUX);
     hipStream_t main_st = static_cast<hipStream_t>(stream);
-    hipStream_t aux_st = static_cast<hipStream_t>(aux_stream);
-    const bool overlap = aux_st != main_st;
+    hipStream_t aux[LOOP_MAX_AUX] = {};
+    for (int k = 0; k < n_aux; ++k) {
+        aux[k] = static_cast<hipStream_t>(aux_streams[k]);
+        SDT_REQUIRE(aux[k] != main_st, SDT_ERR_INVALID_ARG, "sdt_train_loop: auxiliary stream %d is the main stream", k);
+    }
+    const bool overlap = n_aux > 0;
     StepBuffers buf[LOOP_BUFFERS];
     for (int k = 0; k < LOOP_BUFFERS; ++k) bind_buffers(c.lay, static_cast<char*>(ws) + k * one, one, &buf[k]);
 
-    // ready[k]: phase 1 of the step in buffer k is complete; done[k]: its phase 2 is.
-    hipEvent_t ready[LOOP_BUFFERS] = {}, done[LOOP_BUFFERS] = {}, fork = nullptr;
+    // ready[s]: phase 1 of every step of the group in slot s is complete; done[s]: their phase 2 is.
+    hipEvent_t ready[LOOP_SLOTS] = {}, done[LOOP_SLOTS] = {}, fork = nullptr;
     auto cleanup = [&]() {
-        for (int k = 0; k < LOOP_BUFFERS; ++k) {
+        for (int k = 0; k < LOOP_SLOTS; ++k) {
             if (ready[k]) (void)hipEventDestroy(ready[k]);
             if (done[k]) (void)hipEventDestroy(done[k]);
         }
@@ -464,7 +497,7 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
     };
     if (overlap) {
         bool ok = hipEventCreateWithFlags(&fork, hipEventDisableTiming) == hipSuccess;
-        for (int k = 0; k < LOOP_BUFFERS && ok; ++k)
+        for (int k = 0; k < LOOP_SLOTS && ok; ++k)
             ok = hipEventCreateWithFlags(&ready[k], hipEventDisableTiming) == hipSuccess &&
                  hipEventCreateWithFlags(&done[k], hipEventDisableTiming) == hipSuccess;
         if (!ok) {
@@ -472,24 +505,38 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
             set_error("sdt_train_loop: hipEventCreate failed");
             return SDT_ERR_HIP;
         }
-        // the auxiliary stream starts after whatever the caller queued on the main stream
+        // the auxiliary streams start after whatever the caller queued on the main stream
         (void)hipEventRecord(fork, main_st);
-        (void)hipStreamWaitEvent(aux_st, fork, 0);
+        for (int k = 0; k < n_aux; ++k) (void)hipStreamWaitEvent(aux[k], fork, 0);
     }
     rc = SDT_OK;
-    for (int i = 0; i < n_steps && rc == SDT_OK; ++i) {
-        const int k = i % LOOP_BUFFERS;
-        const int32_t* sd = seeds + (int64_t)i * batch;
-        if (timing) timing->slot = timing->used < timing->max_steps ? timing->used++ : -1;
-        if (overlap && i >= LOOP_BUFFERS) (void)hipStreamWaitEvent(aux_st, done[k], 0);   // buffer k is free again
-        rc = step_sample(c, buf[k], sd, first_step + (uint32_t)i, overlap ? aux_st : main_st);
-        if (rc != SDT_OK) break;
-        if (overlap) {
-            (void)hipEventRecord(ready[k], aux_st);
-            (void)hipStreamWaitEvent(main_st, ready[k], 0);
+    const int slot0 = timing ? timing->used : 0;
+    auto timing_slot = [&](int i) {
+        if (timing) timing->slot = slot0 + i < timing->max_steps ? slot0 + i : -1;
+    };
+    for (int g0 = 0, g = 0; g0 < n_steps && rc == SDT_OK; g0 += LOOP_GROUP, ++g) {
+        const int s = g % LOOP_SLOTS, g1 = g0 + LOOP_GROUP < n_steps ? g0 + LOOP_GROUP : n_steps;
+        hipStream_t aux_st = overlap ? aux[g % n_aux] : main_st;   // sampling of consecutive groups on alternating streams
+        if (overlap && g >= LOOP_SLOTS) (void)hipStreamWaitEvent(aux_st, done[s], 0);   // the slot's buffers are free again
+        for (int i = g0; i < g1 && rc == SDT_OK; ++i) {
+            timing_slot(i);
+            rc = step_sample(c, buf[s * LOOP_GROUP + (i - g0)], seeds + (int64_t)i * batch, first_step + (uint32_t)i,
+                             aux_st, /*check_state=*/i < LOOP_BUFFERS);
+            if (!overlap && rc == SDT_OK)   // one stream: keep the order of sdt_train_step
+                rc = step_compute(c, buf[s * LOOP_GROUP + (i - g0)], seeds + (int64_t)i * batch, losses_d + i, main_st);
         }
-        rc = step_compute(c, buf[k], sd, losses_d + i, main_st);
-        if (overlap && rc == SDT_OK) (void)hipEventRecord(done[k], main_st);
+        if (!overlap || rc != SDT_OK) continue;
+        (void)hipEventRecord(ready[s], aux_st);
+        (void)hipStreamWaitEvent(main_st, ready[s], 0);
+        for (int i = g0; i < g1 && rc == SDT_OK; ++i) {
+            timing_slot(i);
+            rc = step_compute(c, buf[s * LOOP_GROUP + (i - g0)], seeds + (int64_t)i * batch, losses_d + i, main_st);
+        }
+        if (rc == SDT_OK) (void)hipEventRecord(done[s], main_st);
+    }
+    if (timing) {
+        timing->used = slot0 + n_steps < timing->max_steps ? slot0 + n_steps : timing->max_steps;
+        timing->slot = -1;
     }
     // every phase 1 was waited for by a phase 2 on the main stream, so synchronising the
     // main stream covers the auxiliary one; the events may be released now (pending work keeps

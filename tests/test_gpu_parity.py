@@ -353,9 +353,9 @@ def test_train_step_ragged_dims_fp32():
     _run_and_check(inst, wl, steps=1)
 
 
-@pytest.mark.parametrize("overlap", [True, False])
-def test_train_loop_equals_sequential_steps(overlap):
-    _say(f"train loop vs sequential steps, overlap={overlap}")
+@pytest.mark.parametrize("n_aux", [0, 1, 2, 3])
+def test_train_loop_equals_sequential_steps(n_aux):
+    _say(f"train loop vs sequential steps, {n_aux} auxiliary streams")
     wl = gen.WORKLOADS["tiny"]
     inst = gen.make_instance(wl)
     n, lr = 7, 0.05
@@ -363,11 +363,13 @@ def test_train_loop_equals_sequential_steps(overlap):
     seq_losses = [seq.step(inst.batch(i), wl.seed, 3 + i, lr) for i in range(n)]
     loop = StepRunner(inst.indptr, inst.indices, inst.X, inst.y, inst.W, inst.b, wl.fanouts, wl.batch)
     nbytes = B.sdt_train_loop_workspace_bytes(loop.graph.n_nodes, wl.batch, wl.fanouts, loop.model, loop.code)
-    assert nbytes >= 3 * loop.lay.total_bytes
+    one = (loop.lay.total_bytes + 255) // 256 * 256            # the loop rotates through nbuf step workspaces
+    nbuf = nbytes // one
+    assert nbuf >= 2 and nbytes == nbuf * one
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
     seeds = dev(np.stack([inst.batch(i) for i in range(n)]))
     losses = torch.zeros(n, dtype=torch.float32, device="cuda")
-    aux = torch.cuda.Stream() if overlap else None
+    aux = [torch.cuda.Stream() for _ in range(n_aux)] if n_aux else None
     # two calls back to back: the second continues on the state the first left in the workspace
     B.sdt_train_loop(loop.graph, loop.X, loop.y, seeds[:3], wl.fanouts, loop.model, wl.seed, 3, lr, losses[:3], ws, aux)
     B.sdt_train_loop(loop.graph, loop.X, loop.y, seeds[3:], wl.fanouts, loop.model, wl.seed, 6, lr, losses[3:], ws, aux)
@@ -375,8 +377,8 @@ def test_train_loop_equals_sequential_steps(overlap):
     assert losses.cpu().tolist() == [np.float32(v) for v in seq_losses]
     for l in range(seq.L):
         assert torch.equal(seq.W[l], loop.W[l]) and torch.equal(seq.b[l], loop.b[l])
-    # the last step of the second call (its 4th) sits in buffer 3 % 3 and equals the sequential run's
-    off = (3 % 3) * (nbytes // 3)
+    # the last step of the second call (its 4th) sits in buffer 3 % nbuf and equals the sequential run's
+    off = (3 % nbuf) * one
     lay = loop.lay
     for o, nb in [(lay.dW[0], 2 * 64 * 64 * 4), (lay.H[2], 256 * 8 * 4), (lay.indptr[0], 4 * 100)]:
         assert torch.equal(ws[off + o:off + o + nb], seq.ws[o:o + nb])

@@ -184,9 +184,10 @@ def main():
         if kind == "linear_bwd":
             f = 2.0 * n_dst * 2 * d[l] * d[l + 1]
             if l == L - 1 and fused_head:   # projection + softmax + dW + input gradients in one launch
-                return "mfma", f * (3 if l > 0 else 2), "k_head + k_reduce_partials"
-            # bf16 workloads: dW on the fp32 matrix path (widened operands), input gradients on the bf16 one
-            return "mfma", f * (2 if l > 0 else 1), "k_linear_bwd_weight (+ _input) + k_reduce_partials"
+                return "mfma", f * (3 if l > 0 else 2), "k_head"
+            if wl.bf16:   # both backward products on the bf16 matrix cores
+                return "mfma_bf16", f * (2 if l > 0 else 1), "k_bwd_weight_bf16 (+ k_bwd_input_bf16)"
+            return "mfma", f * (2 if l > 0 else 1), "k_linear_bwd_weight (+ _input)"
         if kind == "head":        # projection + dW (+ input gradients) of the last layer, one launch
             return "mfma", 2.0 * n_dst * 2 * d[l] * d[l + 1] * (3 if l > 0 else 2), "k_head"
         return "hbm", wl.batch * d[L] * 8, "k_softmax_xent"

@@ -181,6 +181,13 @@ bool bf16_mfma_bwd_input_ok(const void* dY, int64_t lddy, int32_t dy_dtype, int3
 int32_t linear_fwd_bf16(const void* Hself, int64_t ldh, const void* A, int64_t lda, int32_t n_cap, const int32_t* n_d,
                         int32_t in, int32_t out, const void* Wt, const float* bias, int32_t relu, void* Y, int64_t ldy,
                         int32_t y_dtype, hipStream_t st);
+bool bf16_mfma_bwd_weight_ok(const void* Hself, int64_t ldh, const void* A, int64_t lda, const void* dY, int64_t lddy,
+                             int32_t dy_dtype, int32_t in, int32_t out);
+int32_t bf16_weight_splits(int32_t n_cap, int32_t in, int32_t out);
+// partial products P[splits][2 in][out], Q[splits][out] of the weight gradient, in the layout reduce_all expects
+int32_t linear_bwd_weight_bf16(const void* Hself, int64_t ldh, const void* A, int64_t lda, const void* dY, int64_t lddy,
+                               int32_t dy_dtype, int32_t n_cap, const int32_t* n_d, int32_t in, int32_t out,
+                               int32_t splits, float* P, float* Q, hipStream_t st);
 int32_t linear_bwd_input_bf16(const void* dY, int64_t lddy, int32_t dy_dtype, int32_t n_cap, const int32_t* n_d,
                               int32_t in, int32_t out, const void* Wb, void* dSelf, void* dAgg, int64_t ldi,
                               hipStream_t st);

@@ -512,8 +512,11 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Hself, int64_t ldh, co
     const int vh = vec_elems(sizeof(TH), in, {ldh, lda}, {Hself, A});
     const int vw = vec_elems(4, out, {(int64_t)out}, {W});
     const TD* dYt = static_cast<const TD*>(dY);
-    // weight gradient partials
-    {
+    // weight gradient partials (bf16 activations inside a step: on the bf16 matrix cores)
+    const int32_t dy_code = sizeof(TD) == 2 ? SDT_BF16 : SDT_F32;
+    if (ex.Wb && sizeof(TH) == 2 && bf16_mfma_bwd_weight_ok(Hself, ldh, A, lda, dY, lddy, dy_code, in, out)) {
+        (void)linear_bwd_weight_bf16(Hself, ldh, A, lda, dY, lddy, dy_code, n_cap, n_d, in, out, splits, P, Q, st);
+    } else {
         using TL = TileW;
         dim3 grid(ceil_div(out, TL::BN), ceil_div(in, TL::BM), 2 * splits);
         SDT_VEC_SWITCH(vh, (16 / sizeof(TH)), {
@@ -526,11 +529,9 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Hself, int64_t ldh, co
             })
         })
     }
-    const bool input_on_bf16_path = ex.Wb && sizeof(TH) == 2 && dSelf &&
-                                    bf16_mfma_bwd_input_ok(dY, lddy, sizeof(TD) == 2 ? SDT_BF16 : SDT_F32, in, out, ldi);
+    const bool input_on_bf16_path = ex.Wb && sizeof(TH) == 2 && dSelf && bf16_mfma_bwd_input_ok(dY, lddy, dy_code, in, out, ldi);
     if (input_on_bf16_path) {
-        (void)linear_bwd_input_bf16(dY, lddy, sizeof(TD) == 2 ? SDT_BF16 : SDT_F32, n_cap, n_d, in, out, ex.Wb, dSelf, dAgg,
-                                    ldi, st);
+        (void)linear_bwd_input_bf16(dY, lddy, dy_code, n_cap, n_d, in, out, ex.Wb, dSelf, dAgg, ldi, st);
     } else if (dSelf && n_cap > 0) {
         using TL = TileS;
         dim3 grid(ceil_div(in, TL::BN), ceil_div(n_cap, TL::BM), 2);

@@ -135,11 +135,42 @@ struct FragB {
     }
 };
 
+// Fragments out of tiles stored with the reduction index as the ROW ([BK][cols + 8], the layout the
+// weight gradient's operands have in memory): a lane picks its eight values one 2-byte read at a
+// time.  Rows 8 apart are 32 banks apart (row stride 36 dwords for 64 columns), so the two halves of
+// a wave never collide; the 32 lanes of a half read 32 consecutive columns.
 template <typename TL>
+struct FragT {
+    bf16x8 a[TL::TM], b[TL::TN];
+    static constexpr int LDA = TL::BM + 8, LDB = TL::BN + 8;
+    __device__ __forceinline__ static bf16x8 gather(const uint16_t* t, int ld, int r0, int col) {
+        uint32_t w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            w[j] = (uint32_t)t[(r0 + 2 * j) * ld + col] | ((uint32_t)t[(r0 + 2 * j + 1) * ld + col] << 16);
+        return __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+    }
+    __device__ __forceinline__ void load(const uint16_t* As, const uint16_t* Bs, int arow0, int bcol0, int c) {
+        const int lane = threadIdx.x & 63, i = lane & 31, kg = lane >> 5;
+#pragma unroll
+        for (int tm = 0; tm < TL::TM; ++tm) a[tm] = gather(As, LDA, c * 16 + kg * 8, arow0 + tm * 32 + i);
+#pragma unroll
+        for (int tn = 0; tn < TL::TN; ++tn) b[tn] = gather(Bs, LDB, c * 16 + kg * 8, bcol0 + tn * 32 + i);
+    }
+    __device__ __forceinline__ void mma(floatx16 (&acc)[TL::TM][TL::TN]) const {
+#pragma unroll
+        for (int tm = 0; tm < TL::TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TL::TN; ++tn)
+                acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
+    }
+};
+
+template <typename TL, typename FRAG = FragB<TL>>
 __device__ __forceinline__ void mma_step(const uint16_t* As, const uint16_t* Bs, int a0, int b0,
                                          floatx16 (&acc)[TL::TM][TL::TN]) {
     constexpr int NC = TL::BK / 16;
-    FragB<TL> f[2];
+    FRAG f[2];
     f[0].load(As, Bs, a0, b0, 0);
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
@@ -149,10 +180,10 @@ __device__ __forceinline__ void mma_step(const uint16_t* As, const uint16_t* Bs,
 }
 
 // Requires nit >= 1; fetch(it, ...) must be callable for it up to nit + 2 (clamped loads, zero tiles).
-template <typename TL, typename SA, typename SB, typename Fetch>
-__device__ __forceinline__ void mainloop(int nit, uint16_t* As, uint16_t* Bs, Fetch&& fetch,
+template <typename TL, typename SA, typename SB, typename FRAG = FragB<TL>, int A_ELEMS = TL::BM * TL::LDK,
+          int B_ELEMS = TL::BN * TL::LDK, typename Fetch, typename Hook>
+__device__ __forceinline__ void mainloop(int nit, uint16_t* As, uint16_t* Bs, Fetch&& fetch, Hook&& hook,
                                          floatx16 (&acc)[TL::TM][TL::TN]) {
-    constexpr int A_ELEMS = TL::BM * TL::LDK, B_ELEMS = TL::BN * TL::LDK;
     const int wave = threadIdx.x >> 6, wm = wave / TL::WN, wn = wave % TL::WN;
     const int a0 = wm * (TL::BM / TL::WM), b0 = wn * (TL::BN / TL::WN);
     SA sa0, sa1;
@@ -167,13 +198,15 @@ __device__ __forceinline__ void mainloop(int nit, uint16_t* As, uint16_t* Bs, Fe
         __syncthreads();
         fetch(it + 2, sa0, sb0);
         __builtin_amdgcn_sched_barrier(0);
-        mma_step<TL>(As, Bs, a0, b0, acc);
+        hook(Bs);
+        mma_step<TL, FRAG>(As, Bs, a0, b0, acc);
         sa1.store(As + A_ELEMS);
         sb1.store(Bs + B_ELEMS);
         __syncthreads();
         fetch(it + 3, sa1, sb1);
         __builtin_amdgcn_sched_barrier(0);
-        mma_step<TL>(As + A_ELEMS, Bs + B_ELEMS, a0, b0, acc);
+        hook(Bs + B_ELEMS);
+        mma_step<TL, FRAG>(As + A_ELEMS, Bs + B_ELEMS, a0, b0, acc);
     }
 }
 
@@ -226,7 +259,7 @@ __global__ __launch_bounds__(TL::NT) void k_fwd_bf16(const uint16_t* __restrict_
         sa.load(ph ? Agg : Hself, ph ? lda : ldh, row0, n, k0, in);
         sb.load(Wt + (int64_t)ph * in, 2 * (int64_t)in, col0, out, k0, in);
     };
-    mainloop<TL, SA, SB>(2 * nk, As, Bs, fetch, acc);
+    mainloop<TL, SA, SB>(2 * nk, As, Bs, fetch, [](const uint16_t*) {}, acc);
     for_each_acc<TL>(acc, [&](int r, int c, float v) {
         const int row = row0 + r, col = col0 + c;
         if (row < n && col < out) {
@@ -264,11 +297,131 @@ __global__ __launch_bounds__(TL::NT) void k_bwd_input_bf16(const TD* __restrict_
         sa.load(dY, lddy, row0, n, it * BK, out);
         sb.load(Wh, ldb, col0, in, it * BK, kmax_b);
     };
-    mainloop<TL, SA, SB>((out + BK - 1) / BK, As, Bs, fetch, acc);
+    mainloop<TL, SA, SB>((out + BK - 1) / BK, As, Bs, fetch, [](const uint16_t*) {}, acc);
     bf16_t* dst = half ? dAgg : dSelf;
     for_each_acc<TL>(acc, [&](int r, int c, float v) {
         const int row = row0 + r, col = col0 + c;
         if (row < n && col < in) dst[(int64_t)row * ldi + col] = from_f32<bf16_t>(v);
+    });
+}
+
+// ---- weight gradient partials ------------------------------------------------------------------
+// [BK rows][C cols] of a matrix whose COLUMNS are contiguous (the reduction index is the row):
+// stored to LDS as it is, rows of C + 8 elements.
+template <int BK, int C, int NT>
+struct StageRowsB {
+    static constexpr int VPR = C / 8, TOTAL = BK * VPR, PER = (TOTAL + NT - 1) / NT, LD = C + 8;
+    uint4 raw[PER];
+    uint32_t ok;
+    // cmax % 8 == 0, cmax >= 8, rmax >= 1
+    __device__ __forceinline__ void load(const uint16_t* __restrict__ base, int64_t ld, int r_lo, int rmax, int c_lo,
+                                         int cmax) {
+        ok = 0;
+#pragma unroll
+        for (int p = 0; p < PER; ++p) {
+            const int idx = threadIdx.x + p * NT;
+            const int r = r_lo + idx / VPR, c = c_lo + (idx % VPR) * 8;
+            if (r < rmax && c < cmax) ok |= 1u << p;
+            raw[p] = *reinterpret_cast<const uint4*>(base + (int64_t)min(r, rmax - 1) * ld + min(c, cmax - 8));
+        }
+    }
+    __device__ __forceinline__ void store(uint16_t* lds) const {
+#pragma unroll
+        for (int p = 0; p < PER; ++p) {
+            const int idx = threadIdx.x + p * NT;
+            if (TOTAL % NT == 0 || idx < TOTAL) {
+                uint4 v = raw[p];
+                if (!((ok >> p) & 1u)) v = make_uint4(0u, 0u, 0u, 0u);
+                *reinterpret_cast<uint4*>(lds + (idx / VPR) * LD + (idx % VPR) * 8) = v;
+            }
+        }
+    }
+};
+template <int BK, int C, int NT>
+struct StageRowsF {  // fp32 source, rounded to bf16 on the way (cmax % 4 == 0, cmax >= 4)
+    static constexpr int VPR = C / 8, TOTAL = BK * VPR, PER = (TOTAL + NT - 1) / NT, LD = C + 8;
+    float4 raw[PER][2];
+    uint32_t ok;
+    __device__ __forceinline__ void load(const float* __restrict__ base, int64_t ld, int r_lo, int rmax, int c_lo,
+                                         int cmax) {
+        ok = 0;
+#pragma unroll
+        for (int p = 0; p < PER; ++p) {
+            const int idx = threadIdx.x + p * NT;
+            const int r = r_lo + idx / VPR;
+            const int64_t row = (int64_t)min(r, rmax - 1) * ld;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int c = c_lo + (idx % VPR) * 8 + 4 * h;
+                if (r < rmax && c < cmax) ok |= 1u << (2 * p + h);
+                raw[p][h] = *reinterpret_cast<const float4*>(base + row + min(c, cmax - 4));
+            }
+        }
+    }
+    __device__ __forceinline__ void store(uint16_t* lds) const {
+#pragma unroll
+        for (int p = 0; p < PER; ++p) {
+            const int idx = threadIdx.x + p * NT;
+            if (TOTAL % NT == 0 || idx < TOTAL) {
+                const bool in0 = (ok >> (2 * p)) & 1u, in1 = (ok >> (2 * p + 1)) & 1u;
+                const float4 a = raw[p][0], b = raw[p][1];
+                uint4 v;
+                v.x = in0 ? StageF<8, 32, 64>::pack(a.x, a.y) : 0u;
+                v.y = in0 ? StageF<8, 32, 64>::pack(a.z, a.w) : 0u;
+                v.z = in1 ? StageF<8, 32, 64>::pack(b.x, b.y) : 0u;
+                v.w = in1 ? StageF<8, 32, 64>::pack(b.z, b.w) : 0u;
+                *reinterpret_cast<uint4*>(lds + (idx / VPR) * LD + (idx % VPR) * 8) = v;
+            }
+        }
+    }
+};
+
+// P[s][h*in + m][o] = sum over the rows r of split s of X_h[r, m] dZ[r, o]  (X_0 = Hself, X_1 = A),
+// Q[s][o] = column sums of (rounded) dZ; grid (out tiles, in tiles, 2 * splits) as in the fp32 path.
+template <typename TD, typename TL>
+__global__ __launch_bounds__(TL::NT) void k_bwd_weight_bf16(const uint16_t* __restrict__ Hself, int64_t ldh,
+                                                            const uint16_t* __restrict__ Agg, int64_t lda,
+                                                            const TD* __restrict__ dY, int64_t lddy, int n_cap,
+                                                            const int32_t* n_d, int in, int out, int splits,
+                                                            float* __restrict__ P, float* __restrict__ Q) {
+    constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK;
+    constexpr int LDA = BM + 8, LDB = BN + 8;
+    const int n = dev_count(n_cap, n_d);
+    const int id = xcd_contiguous_id((int)(gridDim.x * gridDim.y * gridDim.z));
+    const int bx = id % (int)gridDim.x, by = (id / (int)gridDim.x) % (int)gridDim.y;
+    const int bz = id / (int)(gridDim.x * gridDim.y);
+    const int half = bz & 1, split = bz >> 1;
+    const bool do_bias = Q != nullptr && half == 0 && by == 0;
+    float bsum = 0.f;
+    const int row0 = by * BM /* feature m */, col0 = bx * BN /* output o */;
+    const int chunk = ((n + splits - 1) / splits + BK - 1) / BK * BK;
+    const int r_begin = split * chunk, r_end = min(n, r_begin + chunk);
+    __shared__ __align__(16) uint16_t As[2 * BK * LDA];
+    __shared__ __align__(16) uint16_t Bs[2 * BK * LDB];
+    floatx16 acc[TL::TM][TL::TN];
+    zero<TL>(acc);
+    using SA = StageRowsB<BK, BM, TL::NT>;
+    using SB = typename std::conditional<sizeof(TD) == 2, StageRowsB<BK, BN, TL::NT>, StageRowsF<BK, BN, TL::NT>>::type;
+    const uint16_t* X = half ? Agg : Hself;
+    const int64_t ldx = half ? lda : ldh;
+    const int nit = r_end > r_begin ? (r_end - r_begin + BK - 1) / BK : 0;
+    auto fetch = [&](int it, SA& sa, SB& sb) {
+        sa.load(X, ldx, r_begin + it * BK, r_end, row0, in);
+        sb.load(dY, lddy, r_begin + it * BK, r_end, col0, out);
+    };
+    auto hook = [&](const uint16_t* Bcur) {
+        if (do_bias && (int)threadIdx.x < BN) {
+#pragma unroll 8
+            for (int k = 0; k < BK; ++k) bsum += bf16_to_f32(Bcur[k * LDB + threadIdx.x]);
+        }
+    };
+    if (nit > 0) mainloop<TL, SA, SB, FragT<TL>, BK * LDA, BK * LDB>(nit, As, Bs, fetch, hook, acc);
+    if (do_bias && (int)threadIdx.x < BN && col0 + (int)threadIdx.x < out)
+        Q[(int64_t)split * out + col0 + threadIdx.x] = bsum;
+    float* dst = P + ((int64_t)split * 2 * in + (int64_t)half * in) * out;
+    for_each_acc<TL>(acc, [&](int r, int c, float v) {
+        const int row = row0 + r, col = col0 + c;
+        if (row < in && col < out) dst[(int64_t)row * out + col] = v;
     });
 }
 
@@ -364,6 +517,39 @@ int32_t linear_fwd_bf16(const void* Hself, int64_t ldh, const void* A, int64_t l
         hipLaunchKernelGGL((k_fwd_bf16<float, TF>), grid, dim3(TF::NT), 0, st, h, ldh, a, lda, n_cap, n_d, in, out, w, bias,
                            relu, static_cast<float*>(Y), ldy);
     SDT_CHECK_LAUNCH("linear_fwd_bf16");
+    return SDT_OK;
+}
+
+bool bf16_mfma_bwd_weight_ok(const void* Hself, int64_t ldh, const void* A, int64_t lda, const void* dY, int64_t lddy,
+                             int32_t dy_dtype, int32_t in, int32_t out) {
+    if (!(in % 8 == 0 && ldh % 8 == 0 && lda % 8 == 0 && al16(Hself) && al16(A) && al16(dY))) return false;
+    return dy_dtype == SDT_BF16 ? (out % 8 == 0 && lddy % 8 == 0) : (out % 4 == 0 && lddy % 4 == 0);
+}
+
+int32_t bf16_weight_splits(int32_t n_cap, int32_t in, int32_t out) {
+    const int tiles = ceil_div(in, 64) * ceil_div(out, 64) * 2;
+    int s = ceil_div(1024, tiles);
+    const int max_rows = ceil_div(n_cap > 0 ? n_cap : 1, 256);
+    const int64_t max_bytes = ((int64_t)16 << 20) / ((int64_t)2 * in * out * 4);
+    if (s > max_rows) s = max_rows;
+    if (s > max_bytes) s = (int)max_bytes;
+    return s < 1 ? 1 : s;
+}
+
+int32_t linear_bwd_weight_bf16(const void* Hself, int64_t ldh, const void* A, int64_t lda, const void* dY, int64_t lddy,
+                               int32_t dy_dtype, int32_t n_cap, const int32_t* n_d, int32_t in, int32_t out,
+                               int32_t splits, float* P, float* Q, hipStream_t st) {
+    using TW = TileB<64, 64, 64, 2, 2>;
+    dim3 grid(ceil_div(out, TW::BN), ceil_div(in, TW::BM), 2 * splits);
+    const uint16_t* h = static_cast<const uint16_t*>(Hself);
+    const uint16_t* a = static_cast<const uint16_t*>(A);
+    if (dy_dtype == SDT_BF16)
+        hipLaunchKernelGGL((k_bwd_weight_bf16<uint16_t, TW>), grid, dim3(TW::NT), 0, st, h, ldh, a, lda,
+                           static_cast<const uint16_t*>(dY), lddy, n_cap, n_d, in, out, splits, P, Q);
+    else
+        hipLaunchKernelGGL((k_bwd_weight_bf16<float, TW>), grid, dim3(TW::NT), 0, st, h, ldh, a, lda,
+                           static_cast<const float*>(dY), lddy, n_cap, n_d, in, out, splits, P, Q);
+    SDT_CHECK_LAUNCH("linear_bwd_weight_bf16");
     return SDT_OK;
 }
 

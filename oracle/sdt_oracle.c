@@ -280,6 +280,41 @@ void orc_aggregate_bwd(int64_t n_dst, int64_t n_src, const int64_t *b_indptr, co
     }
 }
 
+/* GCN aggregation on a sampled block (Sec. III-E lists GCN among the integrated models):
+ * A[i,:] = s[i] * sum over the row's edges of c[col] * H[col,:]  +  selfw[i] * H[i,:].
+ * s, selfw are per destination row, c per source row (see gcn_weights in the Python part). */
+void orc_gcn_aggregate_fwd(int64_t n_dst, const int64_t *b_indptr, const int32_t *b_cols, const double *H,
+                           int64_t F, const double *s, const double *c, const double *selfw, double *A)
+{
+    for (int64_t i = 0; i < n_dst; ++i) {
+        double *a = A + i * F;
+        for (int64_t f = 0; f < F; ++f) a[f] = 0.0;
+        for (int64_t e = b_indptr[i]; e < b_indptr[i + 1]; ++e) {
+            const double *h = H + (int64_t)b_cols[e] * F;
+            const double w = c[b_cols[e]];
+            for (int64_t f = 0; f < F; ++f) a[f] += w * h[f];
+        }
+        for (int64_t f = 0; f < F; ++f) a[f] = s[i] * a[f] + selfw[i] * H[i * F + f];
+    }
+}
+
+/* Its transpose: dH[j,:] = c[j] * sum over edges (i -> j) of s[i] * dA[i,:]  +  [j < n_dst] selfw[j] * dA[j,:]. */
+void orc_gcn_aggregate_bwd(int64_t n_dst, int64_t n_src, const int64_t *b_indptr, const int32_t *b_cols,
+                           const double *dA, int64_t F, const double *s, const double *c, const double *selfw,
+                           double *dH)
+{
+    for (int64_t j = 0; j < n_src; ++j)
+        for (int64_t f = 0; f < F; ++f) dH[j * F + f] = 0.0;
+    for (int64_t i = 0; i < n_dst; ++i)
+        for (int64_t e = b_indptr[i]; e < b_indptr[i + 1]; ++e)
+            for (int64_t f = 0; f < F; ++f) dH[(int64_t)b_cols[e] * F + f] += s[i] * dA[i * F + f];
+    for (int64_t j = 0; j < n_src; ++j)
+        for (int64_t f = 0; f < F; ++f) {
+            dH[j * F + f] *= c[j];
+            if (j < n_dst) dH[j * F + f] += selfw[j] * dA[j * F + f];
+        }
+}
+
 /* Plain SGD: w <- w - lr * g.                                           */
 void orc_sgd(int64_t n, double *w, const double *g, double lr)
 {

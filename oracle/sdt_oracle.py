@@ -62,6 +62,10 @@ def _load():
     L.orc_softmax_xent.argtypes = [i64, i64, vp, vp, vp]
     L.orc_linear_bwd.restype = None
     L.orc_linear_bwd.argtypes = [i64, i64, i64, vp, vp, i32, vp, i64, vp, vp, vp, vp, vp, vp]
+    L.orc_gcn_aggregate_fwd.restype = None
+    L.orc_gcn_aggregate_fwd.argtypes = [i64, vp, vp, vp, i64, vp, vp, vp, vp]
+    L.orc_gcn_aggregate_bwd.restype = None
+    L.orc_gcn_aggregate_bwd.argtypes = [i64, i64, vp, vp, vp, i64, vp, vp, vp, vp]
     L.orc_aggregate_bwd.restype = None
     L.orc_aggregate_bwd.argtypes = [i64, i64, vp, vp, vp, vp, i64, vp]
     L.orc_sgd.restype = None
@@ -310,3 +314,93 @@ def model_average(params: List[np.ndarray], n_train: List[float]) -> np.ndarray:
     for p, n in zip(params, n_train):
         out = out + (float(n) / tot) * np.asarray(p, dtype=np.float64)
     return out
+
+
+# ------------------------------------------------------------------ GCN (Sec. III-E: one of the integrated models)
+def gcn_weights(indptr, src_nodes, b_indptr):
+    """Edge and self weights of the GCN aggregation on a sampled block, from the degrees of
+    the partition graph: with deg(v) the length of v's CSR row and m_i the number of sampled
+    neighbours of destination i,
+        c_j    = 1 / sqrt(deg(j) + 1)                    per source row j,
+        s_i    = (deg(i) / m_i) / sqrt(deg(i) + 1)       per destination row i (0 if m_i = 0),
+        self_i = 1 / (deg(i) + 1).
+    A_i = s_i sum_e c_col h_col + self_i h_i is the sampled estimate of row i of
+    D~^-1/2 (Adj + I) D~^-1/2 H with D~ = D + I; with every neighbour sampled (m_i = deg(i))
+    it is that row exactly.  (The paper does not say how its GCN is normalised on sampled
+    blocks; this is the reading used here.)"""
+    ip = np.asarray(indptr, dtype=np.int64)
+    src = np.asarray(src_nodes, dtype=np.int64)
+    bip = np.asarray(b_indptr, dtype=np.int64)
+    n_dst = len(bip) - 1
+    deg = (ip[src + 1] - ip[src]).astype(np.float64)
+    c = 1.0 / np.sqrt(deg + 1.0)
+    m = np.diff(bip).astype(np.float64)
+    d = deg[:n_dst]
+    s = np.where(m > 0, (d / np.maximum(m, 1.0)) / np.sqrt(d + 1.0), 0.0)
+    selfw = 1.0 / (d + 1.0)
+    return s, c, selfw
+
+
+def gcn_aggregate_fwd(b_indptr, b_cols, H, s, c, selfw) -> np.ndarray:
+    ip, cols = _c(b_indptr, np.int64), _c(b_cols, np.int32)
+    H = _c(H, np.float64)
+    n_dst = len(ip) - 1
+    A = np.zeros((n_dst, H.shape[1]), dtype=np.float64)
+    s, c, selfw = _c(s, np.float64), _c(c, np.float64), _c(selfw, np.float64)
+    _load().orc_gcn_aggregate_fwd(n_dst, _p(ip), _p(cols), _p(H), H.shape[1], _p(s), _p(c), _p(selfw), _p(A))
+    return A
+
+
+def gcn_aggregate_bwd(b_indptr, b_cols, n_src: int, dA, s, c, selfw) -> np.ndarray:
+    ip, cols = _c(b_indptr, np.int64), _c(b_cols, np.int32)
+    dA = _c(dA, np.float64)
+    n_dst, F = len(ip) - 1, dA.shape[1]
+    dH = np.zeros((n_src, F), dtype=np.float64)
+    s, c, selfw = _c(s, np.float64), _c(c, np.float64), _c(selfw, np.float64)
+    _load().orc_gcn_aggregate_bwd(n_dst, n_src, _p(ip), _p(cols), _p(dA), F, _p(s), _p(c), _p(selfw), _p(dH))
+    return dH
+
+
+def gcn_linear_fwd(A, W, b, relu: bool) -> np.ndarray:
+    """Z = A W + b with W [in, out] (one weight matrix, no separate self operand)."""
+    Z = np.asarray(A, dtype=np.float64) @ np.asarray(W, dtype=np.float64) + np.asarray(b, dtype=np.float64)
+    return np.maximum(Z, 0.0) if relu else Z
+
+
+def gcn_train_step(indptr, indices, X, y, seeds, fanouts, W, b, seed: int, step: int, lr: float,
+                   blocks: Optional[List[Block]] = None, relu_masks=None):
+    """One mini-batch step of a GCN: layer l is H' = act(Agcn(H) W_l + b_l), W_l [in_l, out_l], ReLU on
+    all but the last layer; sampling, loss and SGD as in train_step.  fp32 storage only."""
+    L = len(fanouts)
+    if blocks is None:
+        blocks = sample_blocks(indptr, indices, seeds, fanouts, seed, step)
+    H = [gather_rows(X, blocks[0].src_nodes).astype(np.float64)]
+    W = [np.asarray(w, dtype=np.float64) for w in W]
+    b = [np.asarray(v, dtype=np.float64) for v in b]
+    A, wts = [], []
+    for l, blk in enumerate(blocks):
+        wt = gcn_weights(indptr, blk.src_nodes, blk.indptr)
+        a = gcn_aggregate_fwd(blk.indptr, blk.cols, H[l], *wt)
+        A.append(a)
+        wts.append(wt)
+        H.append(gcn_linear_fwd(a, W[l], b[l], relu=(l < L - 1)))
+    loss, dZ = softmax_xent(H[L], np.asarray(y)[np.asarray(seeds)])
+    dW, db, dA, dHs = [None] * L, [None] * L, [None] * L, [None] * L
+    dY = dZ
+    for l in range(L - 1, -1, -1):
+        blk = blocks[l]
+        if l < L - 1:
+            keep = H[l + 1] > 0
+            if relu_masks is not None and relu_masks[l] is not None:
+                keep = np.asarray(relu_masks[l], dtype=bool)
+            dY = dY * keep
+        dW[l] = A[l].T @ dY
+        db[l] = dY.sum(axis=0)
+        if l > 0:
+            dA[l] = dY @ W[l].T
+            dY = gcn_aggregate_bwd(blk.indptr, blk.cols, blk.n_src, dA[l], *wts[l])
+            dHs[l] = dY
+    W_new = [sgd(W[l], dW[l], lr) for l in range(L)]
+    b_new = [sgd(b[l], db[l], lr) for l in range(L)]
+    return dict(blocks=blocks, H=H, A=A, logits=H[L], loss=loss, dZ=dZ, W=W, W_new=W_new, b_new=b_new, dW=dW, db=db,
+                dA=dA, dH=dHs, weights=wts)

@@ -461,3 +461,82 @@ def test_model_average_closed_forms():
     assert np.allclose(got, [4.0, -1.0])
     # the weights sum to one: a constant shift of every model shifts the average by the same constant
     assert np.allclose(orc.model_average([a + 2, c + 2], [2, 5]), orc.model_average([a, c], [2, 5]) + 2)
+
+
+# ----------------------------------------------------------------- GCN
+def _small_graph(rng, n, max_deg):
+    rows = [np.sort(rng.choice(n, size=int(rng.integers(0, max_deg + 1)), replace=False)) for _ in range(n)]
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    indptr[1:] = np.cumsum([len(r) for r in rows])
+    return rows, indptr, np.concatenate(rows).astype(np.int32)
+
+
+def test_gcn_full_fanout_equals_symmetric_normalised_adjacency():
+    # every neighbour sampled: the block aggregation is D~^-1/2 (Adj + I) D~^-1/2 H, rows of the seeds
+    rng = np.random.default_rng(21)
+    n, F = 50, 7
+    rows, indptr, indices = _small_graph(rng, n, 6)
+    H = rng.standard_normal((n, F))
+    Adj = np.zeros((n, n))
+    for v, r in enumerate(rows):
+        Adj[v, r] = 1.0
+    deg = Adj.sum(axis=1)
+    Dm = np.diag(1.0 / np.sqrt(deg + 1.0))
+    dense = Dm @ (Adj + np.eye(n)) @ Dm @ H          # uses deg(j) of the SOURCE's own row, as gcn_weights does
+    dst = np.array([4, 9, 23, 0, 49, 31], dtype=np.int32)
+    blk = orc.sample_block(indptr, indices, dst, 8, 3, 0, 0)
+    s, c, selfw = orc.gcn_weights(indptr, blk.src_nodes, blk.indptr)
+    got = orc.gcn_aggregate_fwd(blk.indptr, blk.cols, H[blk.src_nodes], s, c, selfw)
+    assert np.allclose(got, dense[dst], rtol=1e-12, atol=1e-13)
+    # sampling fewer neighbours rescales the neighbour sum by deg/m: constant features stay put
+    blk2 = orc.sample_block(indptr, indices, dst, 2, 3, 0, 0)
+    s2, c2, self2 = orc.gcn_weights(indptr, blk2.src_nodes, blk2.indptr)
+    m = np.diff(blk2.indptr)
+    assert np.allclose(s2[m > 0] * m[m > 0], deg[dst][m > 0] / np.sqrt(deg[dst][m > 0] + 1))
+    assert np.allclose(self2, 1.0 / (deg[dst] + 1))
+
+
+def test_gcn_aggregate_bwd_is_the_transpose_of_fwd():
+    rng = np.random.default_rng(22)
+    n, F = 80, 5
+    rows, indptr, indices = _small_graph(rng, n, 9)
+    dst = rng.choice(n, size=20, replace=False).astype(np.int32)
+    blk = orc.sample_block(indptr, indices, dst, 4, 1, 2, 1)
+    wt = orc.gcn_weights(indptr, blk.src_nodes, blk.indptr)
+    h = rng.standard_normal((blk.n_src, F))
+    g = rng.standard_normal((blk.n_dst, F))
+    lhs = np.sum(orc.gcn_aggregate_fwd(blk.indptr, blk.cols, h, *wt) * g)
+    rhs = np.sum(h * orc.gcn_aggregate_bwd(blk.indptr, blk.cols, blk.n_src, g, *wt))
+    assert abs(lhs - rhs) <= 1e-12 * max(1.0, abs(lhs))
+
+
+def test_gcn_step_gradients_match_autograd_on_a_dense_formulation():
+    rng = np.random.default_rng(23)
+    n, dims = 40, [6, 8, 3]
+    rows, indptr, indices = _small_graph(rng, n, 5)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    y = rng.integers(0, dims[2], size=n).astype(np.int32)
+    W = [rng.standard_normal((dims[l], dims[l + 1])) * 0.4 for l in range(2)]
+    b = [rng.standard_normal(dims[l + 1]) * 0.1 for l in range(2)]
+    seeds = np.array([1, 5, 17, 33, 8], dtype=np.int32)
+    ref = orc.gcn_train_step(indptr, indices, X, y, seeds, [3, 2], W, b, seed=9, step=4, lr=0.1)
+    # the same computation with dense per-block operators and torch autograd in float64
+    Wt = [torch.tensor(w, dtype=torch.float64, requires_grad=True) for w in W]
+    bt = [torch.tensor(v, dtype=torch.float64, requires_grad=True) for v in b]
+    H = torch.tensor(X[ref["blocks"][0].src_nodes].astype(np.float64))
+    for l, blk in enumerate(ref["blocks"]):
+        s, c, selfw = ref["weights"][l]
+        Pm = np.zeros((blk.n_dst, blk.n_src))
+        for i in range(blk.n_dst):
+            for e in range(blk.indptr[i], blk.indptr[i + 1]):
+                Pm[i, blk.cols[e]] += s[i] * c[blk.cols[e]]
+            Pm[i, i] += selfw[i]
+        Z = torch.tensor(Pm) @ H @ Wt[l] + bt[l]
+        H = torch.relu(Z) if l == 0 else Z
+    loss = torch.nn.functional.cross_entropy(H, torch.tensor(y[seeds].astype(np.int64)))
+    loss.backward()
+    assert abs(loss.item() - ref["loss"]) < 1e-12
+    for l in range(2):
+        assert np.allclose(ref["dW"][l], Wt[l].grad.numpy(), rtol=1e-10, atol=1e-12)
+        assert np.allclose(ref["db"][l], bt[l].grad.numpy(), rtol=1e-10, atol=1e-12)
+        assert np.allclose(ref["W_new"][l], W[l] - 0.1 * Wt[l].grad.numpy(), rtol=1e-12, atol=1e-13)

@@ -96,7 +96,13 @@ typedef struct sdt_model {
     float *b[SDT_MAX_LAYERS];
     float *dW[SDT_MAX_LAYERS];
     float *db[SDT_MAX_LAYERS];
+    /* SDT_MODEL_SAGE_MEAN (0, the default) or SDT_MODEL_GCN: layer l is
+     * H' = act(Agcn(H) W[l] + b[l]) with ONE weight matrix W[l] fp32 [dims[l], dims[l+1]]
+     * and the aggregation of sdt_gcn_aggregate_fwd; fp32 storage and even dims[0..L-1] only. */
+    int32_t kind;
+    int32_t reserved;
 } sdt_model;
+enum { SDT_MODEL_SAGE_MEAN = 0, SDT_MODEL_GCN = 1 };
 
 /* Byte offsets, inside the sdt_train_step workspace, of everything the step
  * produces (so a caller can inspect it), plus the capacities they were sized
@@ -134,6 +140,7 @@ typedef struct sdt_step_layout {
     uint64_t row_loss; /* fp32 [B]: per-seed loss before the mean */
     uint64_t scratch;  /* internal */
     uint64_t wlow;     /* internal: bf16 images of the weights (bf16 workloads only) */
+    uint64_t norm[SDT_MAX_LAYERS]; /* GCN only: fp32 c[cap_src] | s[cap_dst] | selfw[cap_dst], each 256-byte aligned */
 } sdt_step_layout;
 
 /* Library version as "major.minor.patch" (host string, static storage). */
@@ -188,6 +195,27 @@ int32_t sdt_sage_aggregate_csr_fwd(const sdt_csr *graph /*host struct*/, const v
 int32_t sdt_sage_aggregate_bwd(const sdt_block *blk /*host struct*/, const void *dAgg, int64_t ldg,
                                const void *dSelf, int64_t lds, const void *relu_of, int32_t F, int32_t dtype,
                                void *dH, int64_t ldd, void *stream);
+
+/* ---- GCN aggregation on a sampled block (Sec. III-E: GCN is one of the integrated models;
+ * the paper does not say how it is normalised on sampled blocks) -------------------
+ * With deg(v) the length of v's row in the partition graph and m_i the number of
+ * sampled neighbours of destination i:
+ *   c[j] = 1/sqrt(deg(j)+1) per source row, s[i] = (deg(i)/m_i)/sqrt(deg(i)+1) (0 if
+ *   m_i = 0) and selfw[i] = 1/(deg(i)+1) per destination row           (sdt_gcn_norm)
+ *   A[i,:] = s[i] * sum_{e in row i} c[col_e] * H[col_e,:] + selfw[i] * H[i,:]    (fwd)
+ *   dH[j,:] = c[j] * sum_{(i -> j)} s[i] * dA[i,:] + [j < n_dst] selfw[j] * dA[j,:]  (bwd,
+ *   through the transposed block; zeroed where relu_of <= 0 if relu_of != NULL).
+ * With every neighbour sampled this is a row of D~^-1/2 (Adj + I) D~^-1/2 H.  fp32 only.
+ * c has blk->cap_src floats, s and selfw blk->cap_dst.  through_src_nodes != 0: row r of
+ * the block lives at H[src_nodes[r]] (H is the partition's feature matrix). */
+int32_t sdt_gcn_norm(const sdt_csr *graph /*host struct*/, const sdt_block *blk /*host struct*/, float *c, float *s,
+                     float *selfw, void *stream);
+int32_t sdt_gcn_aggregate_fwd(const sdt_block *blk /*host struct*/, const void *H, int64_t ldh,
+                              int32_t through_src_nodes, int32_t F, int32_t dtype, const float *c, const float *s,
+                              const float *selfw, void *A, int64_t lda, void *stream);
+int32_t sdt_gcn_aggregate_bwd(const sdt_block *blk /*host struct*/, const void *dA, int64_t lda, const void *relu_of,
+                              int32_t F, int32_t dtype, const float *c, const float *s, const float *selfw, void *dH,
+                              int64_t ldd, void *stream);
 
 /* ---- GraphSAGE projection (Sec. III-E / IV-A: GraphSAGE is the model trained)
  * Y = act(Hself W[0:in,:] + A W[in:2in,:] + b), act = ReLU if relu else id.

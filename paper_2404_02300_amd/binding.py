@@ -21,6 +21,7 @@ SDT_OK, SDT_ERR_INVALID_ARG, SDT_ERR_WORKSPACE, SDT_ERR_HIP = 0, -1, -2, -3
 SDT_F32, SDT_BF16 = 0, 1
 SDT_MAX_LAYERS = 8
 SDT_MAX_FANOUT = 64
+SDT_MODEL_SAGE_MEAN, SDT_MODEL_GCN = 0, 1
 
 _vp, _i32, _i64, _u32, _u64, _sz = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32,
                                     ctypes.c_uint64, ctypes.c_size_t)
@@ -45,7 +46,7 @@ class sdt_block(ctypes.Structure):
 class sdt_model(ctypes.Structure):
     _fields_ = [("n_layers", _i32), ("dims", _i32 * (SDT_MAX_LAYERS + 1)),
                 ("W", _vp * SDT_MAX_LAYERS), ("b", _vp * SDT_MAX_LAYERS),
-                ("dW", _vp * SDT_MAX_LAYERS), ("db", _vp * SDT_MAX_LAYERS)]
+                ("dW", _vp * SDT_MAX_LAYERS), ("db", _vp * SDT_MAX_LAYERS), ("kind", _i32), ("reserved", _i32)]
 
 
 class sdt_step_layout(ctypes.Structure):
@@ -56,7 +57,7 @@ class sdt_step_layout(ctypes.Structure):
                 ("t_indptr", _u64 * _L), ("t_rows", _u64 * _L),
                 ("H", _u64 * (_L + 1)), ("A", _u64 * _L), ("dZ", _u64),
                 ("dH", _u64 * _L), ("dSelf", _u64 * _L), ("dAgg", _u64 * _L),
-                ("dW", _u64 * _L), ("db", _u64 * _L), ("row_loss", _u64), ("scratch", _u64), ("wlow", _u64)]
+                ("dW", _u64 * _L), ("db", _u64 * _L), ("row_loss", _u64), ("scratch", _u64), ("wlow", _u64), ("norm", _u64 * _L)]
 
 
 class sdt_partition(ctypes.Structure):
@@ -85,6 +86,9 @@ EXPORTS = {
     "sdt_train_loop_workspace_bytes": (_sz, [_i64, _i32, _vp, _vp, _i32]),
     "sdt_train_loop": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp, _i32, _i32, _vp, _vp, _u64, _u32, ctypes.c_float, _vp,
                               _vp, _vp, _sz, _vp, _vp, _i32]),
+    "sdt_gcn_norm": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp]),
+    "sdt_gcn_aggregate_fwd": (_i32, [_vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _i64, _vp]),
+    "sdt_gcn_aggregate_bwd": (_i32, [_vp, _vp, _i64, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _i64, _vp]),
     "sdt_infer_layerwise_workspace_bytes": (_sz, [_i64, _vp, _i32]),
     "sdt_infer_layerwise": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp, _i64, _vp, _sz, _vp]),
     "sdt_model_average": (_i32, [_vp, _vp, _i32, _i64, _vp, _vp]),
@@ -264,13 +268,16 @@ def sdt_sage_linear_bwd(dY: torch.Tensor, Y: Optional[torch.Tensor], relu: bool,
 
 
 def make_model(dims: Sequence[int], W: List[torch.Tensor], b: List[torch.Tensor],
-               dW: Optional[List[torch.Tensor]] = None, db: Optional[List[torch.Tensor]] = None) -> sdt_model:
+               dW: Optional[List[torch.Tensor]] = None, db: Optional[List[torch.Tensor]] = None,
+               kind: int = SDT_MODEL_SAGE_MEAN) -> sdt_model:
     m = sdt_model()
+    m.kind = kind
     m.n_layers = len(dims) - 1
     for i, d in enumerate(dims):
         m.dims[i] = d
     for l in range(m.n_layers):
-        assert W[l].dtype == torch.float32 and W[l].is_contiguous() and tuple(W[l].shape) == (2 * dims[l], dims[l + 1])
+        rows = dims[l] if kind == SDT_MODEL_GCN else 2 * dims[l]
+        assert W[l].dtype == torch.float32 and W[l].is_contiguous() and tuple(W[l].shape) == (rows, dims[l + 1])
         m.W[l], m.b[l] = W[l].data_ptr(), b[l].data_ptr()
         m.dW[l] = dW[l].data_ptr() if dW is not None else None
         m.db[l] = db[l].data_ptr() if db is not None else None
@@ -323,6 +330,23 @@ def sdt_train_loop(graph: Csr, X: torch.Tensor, labels: torch.Tensor, seeds: tor
                                 _ptr(seeds), seeds.shape[1], seeds.shape[0], f, ctypes.byref(model), seed,
                                 first_step, lr, _ptr(losses), timing.handle if timing is not None else None,
                                 _ptr(ws), ws.numel() * ws.element_size(), main, aux, n_aux))
+
+
+def sdt_gcn_norm(graph: Csr, blk: Block, c: torch.Tensor, s: torch.Tensor, selfw: torch.Tensor):
+    _check(lib().sdt_gcn_norm(ctypes.byref(graph.c), ctypes.byref(blk.c), _ptr(c), _ptr(s), _ptr(selfw), _stream()))
+
+
+def sdt_gcn_aggregate_fwd(blk: Block, H: torch.Tensor, c: torch.Tensor, s: torch.Tensor, selfw: torch.Tensor,
+                          A: torch.Tensor, through_src_nodes: bool = False):
+    _check(lib().sdt_gcn_aggregate_fwd(ctypes.byref(blk.c), _ptr(H), H.stride(0), int(through_src_nodes), H.shape[1],
+                                       dtype_code(H), _ptr(c), _ptr(s), _ptr(selfw), _ptr(A), A.stride(0), _stream()))
+
+
+def sdt_gcn_aggregate_bwd(blk: Block, dA: torch.Tensor, c: torch.Tensor, s: torch.Tensor, selfw: torch.Tensor,
+                          dH: torch.Tensor, relu_of: Optional[torch.Tensor] = None):
+    _check(lib().sdt_gcn_aggregate_bwd(ctypes.byref(blk.c), _ptr(dA), dA.stride(0),
+                                       _ptr(relu_of) if relu_of is not None else None, dA.shape[1], dtype_code(dA),
+                                       _ptr(c), _ptr(s), _ptr(selfw), _ptr(dH), dH.stride(0), _stream()))
 
 
 def sdt_infer_layerwise_workspace_bytes(n_nodes: int, model: sdt_model, dtype: int) -> int:

@@ -192,6 +192,11 @@ int32_t linear_bwd_input_bf16(const void* dY, int64_t lddy, int32_t dy_dtype, in
                               int32_t in, int32_t out, const void* Wb, void* dSelf, void* dAgg, int64_t ldi,
                               hipStream_t st);
 
+// GCN aggregation (gcn.hip); map_reset as in aggregate_gather_fwd
+int32_t gcn_aggregate_fwd(const sdt_block* blk, const float* H, int64_t ldh, bool through_src_nodes, int32_t F,
+                          const float* c, const float* s, const float* selfw, float* A, int64_t lda, int32_t* map_reset,
+                          hipStream_t stm);
+
 // number of step workspaces sdt_train_loop rotates through (its workspace is that many step layouts)
 int32_t train_loop_buffers();
 

@@ -43,6 +43,9 @@ InferWs infer_ws(int64_t n_nodes, const sdt_model* m, int32_t dtype) {
     return w;
 }
 
+// rows of layer l's weight matrix: [self | neighbour] halves for GraphSAGE, one block for GCN
+inline int64_t weight_rows(const sdt_model* m, int l) { return (m->kind == SDT_MODEL_GCN ? 1 : 2) * (int64_t)m->dims[l]; }
+
 int32_t check_model_ptrs(const sdt_model* m, const char* who) {
     SDT_REQUIRE(m && m->n_layers >= 1 && m->n_layers <= SDT_MAX_LAYERS, SDT_ERR_INVALID_ARG, "%s: bad model", who);
     for (int l = 0; l < m->n_layers; ++l)
@@ -67,6 +70,7 @@ extern "C" int32_t sdt_infer_layerwise(const sdt_csr* graph, const void* X, int6
     int32_t rc = check_model_ptrs(model, "sdt_infer_layerwise");
     if (rc != SDT_OK) return rc;
     SDT_REQUIRE(graph && graph->indptr && dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_infer_layerwise: null graph or dtype");
+    SDT_REQUIRE(model->kind == SDT_MODEL_SAGE_MEAN, SDT_ERR_INVALID_ARG, "sdt_infer_layerwise: GraphSAGE-mean models only");
     const int64_t N = graph->n_nodes;
     SDT_REQUIRE(N >= 0 && N < 0x7FFFFFFF, SDT_ERR_INVALID_ARG, "sdt_infer_layerwise: n_nodes %lld out of range",
                 (long long)N);
@@ -155,7 +159,8 @@ extern "C" int32_t sdt_train_round(const sdt_partition* parts, int32_t n_parts, 
     for (int j = 0; j < n_parts; ++j) {
         rc = check_model_ptrs(&locals[j], "sdt_train_round (local model)");
         if (rc != SDT_OK) return rc;
-        SDT_REQUIRE(locals[j].n_layers == L, SDT_ERR_INVALID_ARG, "sdt_train_round: local model %d has another depth", j);
+        SDT_REQUIRE(locals[j].n_layers == L && locals[j].kind == global_model->kind, SDT_ERR_INVALID_ARG,
+                    "sdt_train_round: local model %d has another depth or kind", j);
         for (int l = 0; l <= L; ++l)
             SDT_REQUIRE(locals[j].dims[l] == global_model->dims[l], SDT_ERR_INVALID_ARG,
                         "sdt_train_round: local model %d has another shape", j);
@@ -169,7 +174,7 @@ extern "C" int32_t sdt_train_round(const sdt_partition* parts, int32_t n_parts, 
     for (int j = 0; j < n_parts; ++j) {
         // every local model starts the round from the synchronised weights
         for (int l = 0; l < L; ++l) {
-            const size_t wb = (size_t)2 * global_model->dims[l] * global_model->dims[l + 1] * sizeof(float);
+            const size_t wb = (size_t)weight_rows(global_model, l) * global_model->dims[l + 1] * sizeof(float);
             const size_t bb = (size_t)global_model->dims[l + 1] * sizeof(float);
             if (hipMemcpyAsync(locals[j].W[l], global_model->W[l], wb, hipMemcpyDeviceToDevice, st) != hipSuccess ||
                 hipMemcpyAsync(locals[j].b[l], global_model->b[l], bb, hipMemcpyDeviceToDevice, st) != hipSuccess) {
@@ -206,7 +211,7 @@ extern "C" int32_t sdt_train_round(const sdt_partition* parts, int32_t n_parts, 
     const float* src[MAX_MODELS];
     for (int l = 0; l < L; ++l) {
         for (int j = 0; j < n_parts; ++j) src[j] = locals[j].W[l];
-        rc = sdt_model_average(src, alpha, n_parts, (int64_t)2 * global_model->dims[l] * global_model->dims[l + 1],
+        rc = sdt_model_average(src, alpha, n_parts, weight_rows(global_model, l) * global_model->dims[l + 1],
                                global_model->W[l], stream);
         if (rc != SDT_OK) return rc;
         for (int j = 0; j < n_parts; ++j) src[j] = locals[j].b[l];

@@ -1,0 +1,278 @@
+// GCN aggregation on sampled blocks (fp32): the degree-normalised neighbour sum with a self term,
+//   A[i,:] = s[i] * sum_{e in row i} c[col_e] * H[col_e,:] + selfw[i] * H[i,:],
+// its transpose through the transposed block, and the kernel that derives c, s, selfw from the
+// degrees of the partition graph.  Same row-group scheme as the mean aggregation: a group of
+// lanes per row, 16-byte vectors when the alignment allows, eight row loads in flight, fp32 sums
+// in edge order (forward) / ascending destination order (backward) -- deterministic.
+#include "common.h"
+
+namespace sdt {
+namespace {
+
+constexpr int TB = 256;
+constexpr int U = 8;
+
+template <int VE>
+__device__ __forceinline__ void ld(const float* p, float (&v)[VE]) {
+    if constexpr (VE == 4) {
+        const float4 t = *reinterpret_cast<const float4*>(p);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    } else if constexpr (VE == 2) {
+        const float2 t = *reinterpret_cast<const float2*>(p);
+        v[0] = t.x; v[1] = t.y;
+    } else {
+        v[0] = *p;
+    }
+}
+template <int VE>
+__device__ __forceinline__ void st(float* p, const float (&v)[VE]) {
+    if constexpr (VE == 4) *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    else if constexpr (VE == 2) *reinterpret_cast<float2*>(p) = make_float2(v[0], v[1]);
+    else *p = v[0];
+}
+
+// c[j] = 1/sqrt(deg_j + 1) for every source row; s[i] = (deg_i / m_i) / sqrt(deg_i + 1) (0 if the row
+// sampled nothing) and selfw[i] = 1/(deg_i + 1) for every destination row; deg from the graph's CSR.
+__global__ __launch_bounds__(TB) void k_gcn_norm(const int64_t* __restrict__ g_indptr,
+                                                 const int32_t* __restrict__ src_nodes,
+                                                 const int32_t* __restrict__ b_indptr, const int32_t* counts,
+                                                 float* __restrict__ c, float* __restrict__ s,
+                                                 float* __restrict__ selfw) {
+    const int n_dst = counts[0], n_src = counts[1];
+    for (int j = blockIdx.x * TB + threadIdx.x; j < n_src; j += gridDim.x * TB) {
+        const int64_t v = src_nodes[j];
+        const float deg = (float)(g_indptr[v + 1] - g_indptr[v]);
+        const float r = 1.0f / sqrtf(deg + 1.0f);
+        c[j] = r;
+        if (j < n_dst) {
+            const float m = (float)(b_indptr[j + 1] - b_indptr[j]);
+            s[j] = m > 0.f ? (deg / m) * r : 0.f;
+            selfw[j] = 1.0f / (deg + 1.0f);
+        }
+    }
+}
+
+// row_ids (nullable): local row r lives at H[row_ids[r]] (aggregating straight out of the feature
+// matrix through the block's src_nodes); map_reset (nullable, with row_ids): the node map entry of
+// every frontier node met is set back to -1.
+template <int VE, int G>
+__global__ __launch_bounds__(TB) void k_gcn_aggregate_fwd(const int32_t* __restrict__ b_indptr,
+                                                          const int32_t* __restrict__ cols, const int32_t* counts,
+                                                          const float* __restrict__ H, int64_t ldh,
+                                                          const int32_t* __restrict__ row_ids, int F,
+                                                          const float* __restrict__ c, const float* __restrict__ s,
+                                                          const float* __restrict__ selfw, float* __restrict__ A,
+                                                          int64_t lda, int32_t* map_reset) {
+    const int n = counts[0];
+    const int gl = threadIdx.x % G;
+    const int ngrp = gridDim.x * (TB / G);
+    for (int i = blockIdx.x * (TB / G) + threadIdx.x / G; i < n; i += ngrp) {
+        const int e0 = b_indptr[i], e1 = b_indptr[i + 1];
+        const int64_t own = row_ids ? row_ids[i] : i;
+        if (map_reset && gl == 0) map_reset[own] = -1;
+        const float si = s[i], wi = selfw[i];
+        for (int f0 = gl * VE; f0 < F; f0 += G * VE) {
+            float acc[VE];
+#pragma unroll
+            for (int q = 0; q < VE; ++q) acc[q] = 0.f;
+            for (int e = e0; e < e1; e += U) {
+                int64_t r[U];
+                float w[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int col = (e + u < e1) ? cols[e + u] : -1;
+                    w[u] = col >= 0 ? c[col] : 0.f;
+                    r[u] = col < 0 ? -1 : (row_ids ? (int64_t)row_ids[col] : (int64_t)col);
+                }
+                if (map_reset && f0 == gl * VE && gl == 0) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+                        if (r[u] >= 0) map_reset[r[u]] = -1;
+                }
+                float v[U][VE];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (r[u] >= 0) {
+                        ld<VE>(H + r[u] * ldh + f0, v[u]);
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < VE; ++q) v[u][q] = 0.f;
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int q = 0; q < VE; ++q) acc[q] += w[u] * v[u][q];
+            }
+            float h[VE];
+            ld<VE>(H + own * ldh + f0, h);
+#pragma unroll
+            for (int q = 0; q < VE; ++q) acc[q] = si * acc[q] + wi * h[q];
+            st<VE>(A + (int64_t)i * lda + f0, acc);
+        }
+    }
+}
+
+// dH[j,:] = c[j] * sum over the transposed segment of j of s[i] * dA[i,:] + [j < n_dst] selfw[j] * dA[j,:],
+// zeroed where relu_of[j,:] <= 0 (nullable).
+template <int VE, int G>
+__global__ __launch_bounds__(TB) void k_gcn_aggregate_bwd(const int32_t* __restrict__ t_indptr,
+                                                          const int32_t* __restrict__ t_rows, const int32_t* counts,
+                                                          const float* __restrict__ dA, int64_t lda, int F,
+                                                          const float* __restrict__ c, const float* __restrict__ s,
+                                                          const float* __restrict__ selfw,
+                                                          const float* __restrict__ relu_of, float* __restrict__ dH,
+                                                          int64_t ldd) {
+    const int n_dst = counts[0], n_src = counts[1];
+    const int gl = threadIdx.x % G;
+    const int ngrp = gridDim.x * (TB / G);
+    for (int j = blockIdx.x * (TB / G) + threadIdx.x / G; j < n_src; j += ngrp) {
+        const int e0 = t_indptr[j], e1 = t_indptr[j + 1];
+        const float cj = c[j];
+        for (int f0 = gl * VE; f0 < F; f0 += G * VE) {
+            float acc[VE];
+#pragma unroll
+            for (int q = 0; q < VE; ++q) acc[q] = 0.f;
+            for (int e = e0; e < e1; e += U) {
+                int r[U];
+                float w[U];
+                float v[U][VE];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    r[u] = (e + u < e1) ? t_rows[e + u] : -1;
+                    w[u] = r[u] >= 0 ? s[r[u]] : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (r[u] >= 0) {
+                        ld<VE>(dA + (int64_t)r[u] * lda + f0, v[u]);
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < VE; ++q) v[u][q] = 0.f;
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int q = 0; q < VE; ++q) acc[q] += w[u] * v[u][q];
+            }
+#pragma unroll
+            for (int q = 0; q < VE; ++q) acc[q] *= cj;
+            if (j < n_dst) {
+                float g[VE];
+                ld<VE>(dA + (int64_t)j * lda + f0, g);
+                const float wj = selfw[j];
+#pragma unroll
+                for (int q = 0; q < VE; ++q) acc[q] += wj * g[q];
+            }
+            if (relu_of) {
+                float y[VE];
+                ld<VE>(relu_of + (int64_t)j * ldd + f0, y);
+#pragma unroll
+                for (int q = 0; q < VE; ++q)
+                    if (!(y[q] > 0.f)) acc[q] = 0.f;
+            }
+            st<VE>(dH + (int64_t)j * ldd + f0, acc);
+        }
+    }
+}
+
+int vec_floats(int F, std::initializer_list<int64_t> lds, std::initializer_list<const void*> ptrs) {
+    int v = 4;
+    auto fit = [&](uint64_t bytes) {
+        while (v > 1 && bytes % (v * 4) != 0) v >>= 1;
+    };
+    fit((uint64_t)F * 4);
+    for (int64_t l : lds) fit((uint64_t)l * 4);
+    for (const void* p : ptrs) fit(reinterpret_cast<uintptr_t>(p));
+    return v;
+}
+
+inline int rows_grid(int64_t rows, int G) {
+    int64_t b = (rows + (TB / G) - 1) / (TB / G);
+    if (b < 1) b = 1;
+    return (int)(b > 2048 ? 2048 : b);
+}
+
+#define SDT_GCN_DISPATCH(ve, G, body)                                     \
+    do {                                                                  \
+        if (G == 64) {                                                    \
+            constexpr int GG = 64;                                        \
+            if (ve == 4) { constexpr int VE = 4; body; }                  \
+            else if (ve == 2) { constexpr int VE = 2; body; }             \
+            else { constexpr int VE = 1; body; }                          \
+        } else {                                                          \
+            constexpr int GG = 16;                                        \
+            if (ve == 4) { constexpr int VE = 4; body; }                  \
+            else if (ve == 2) { constexpr int VE = 2; body; }             \
+            else { constexpr int VE = 1; body; }                          \
+        }                                                                 \
+    } while (0)
+
+}  // namespace
+
+int32_t gcn_aggregate_fwd(const sdt_block* blk, const float* H, int64_t ldh, bool through_src_nodes, int32_t F,
+                          const float* c, const float* s, const float* selfw, float* A, int64_t lda, int32_t* map_reset,
+                          hipStream_t stm) {
+    const int ve = vec_floats(F, {ldh, lda}, {H, A});
+    const int G = (F + ve - 1) / ve > 16 ? 64 : 16;
+    SDT_GCN_DISPATCH(ve, G, hipLaunchKernelGGL((k_gcn_aggregate_fwd<VE, GG>), dim3(rows_grid(blk->cap_dst, GG)), dim3(TB),
+                                               0, stm, blk->indptr, blk->cols, blk->counts, H, ldh,
+                                               through_src_nodes ? blk->src_nodes : nullptr, F, c, s, selfw, A, lda,
+                                               through_src_nodes ? map_reset : nullptr));
+    SDT_CHECK_LAUNCH("gcn_aggregate_fwd");
+    return SDT_OK;
+}
+
+}  // namespace sdt
+
+using namespace sdt;
+
+extern "C" int32_t sdt_gcn_norm(const sdt_csr* graph, const sdt_block* blk, float* c, float* s, float* selfw,
+                                void* stream) {
+    SDT_REQUIRE(graph && graph->indptr && blk, SDT_ERR_INVALID_ARG, "sdt_gcn_norm: null graph or block");
+    if (blk->cap_src == 0) return SDT_OK;
+    SDT_REQUIRE(blk->counts && blk->indptr && blk->src_nodes && c && s && selfw, SDT_ERR_INVALID_ARG,
+                "sdt_gcn_norm: null pointer");
+    const int blocks = (blk->cap_src + TB - 1) / TB;
+    hipLaunchKernelGGL(k_gcn_norm, dim3(blocks > 1024 ? 1024 : blocks), dim3(TB), 0, static_cast<hipStream_t>(stream),
+                       graph->indptr, blk->src_nodes, blk->indptr, blk->counts, c, s, selfw);
+    SDT_CHECK_LAUNCH("gcn_norm");
+    return SDT_OK;
+}
+
+extern "C" int32_t sdt_gcn_aggregate_fwd(const sdt_block* blk, const void* H, int64_t ldh, int32_t through_src_nodes,
+                                         int32_t F, int32_t dtype, const float* c, const float* s, const float* selfw,
+                                         void* A, int64_t lda, void* stream) {
+    SDT_REQUIRE(blk, SDT_ERR_INVALID_ARG, "sdt_gcn_aggregate_fwd: null block");
+    SDT_REQUIRE(dtype == SDT_F32, SDT_ERR_INVALID_ARG, "sdt_gcn_aggregate_fwd: fp32 only");
+    SDT_REQUIRE(F >= 0 && ldh >= F && lda >= F, SDT_ERR_INVALID_ARG, "sdt_gcn_aggregate_fwd: bad sizes");
+    if (blk->cap_dst == 0 || F == 0) return SDT_OK;
+    SDT_REQUIRE(blk->counts && blk->indptr && blk->cols && H && A && c && s && selfw &&
+                    (!through_src_nodes || blk->src_nodes),
+                SDT_ERR_INVALID_ARG, "sdt_gcn_aggregate_fwd: null pointer");
+    return gcn_aggregate_fwd(blk, static_cast<const float*>(H), ldh, through_src_nodes != 0, F, c, s, selfw,
+                             static_cast<float*>(A), lda, nullptr, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int32_t sdt_gcn_aggregate_bwd(const sdt_block* blk, const void* dA, int64_t lda, const void* relu_of,
+                                         int32_t F, int32_t dtype, const float* c, const float* s, const float* selfw,
+                                         void* dH, int64_t ldd, void* stream) {
+    SDT_REQUIRE(blk, SDT_ERR_INVALID_ARG, "sdt_gcn_aggregate_bwd: null block");
+    SDT_REQUIRE(dtype == SDT_F32, SDT_ERR_INVALID_ARG, "sdt_gcn_aggregate_bwd: fp32 only");
+    SDT_REQUIRE(F >= 0 && lda >= F && ldd >= F, SDT_ERR_INVALID_ARG, "sdt_gcn_aggregate_bwd: bad sizes");
+    if (blk->cap_src == 0 || F == 0) return SDT_OK;
+    SDT_REQUIRE(blk->counts && blk->t_indptr && blk->t_rows && dA && dH && c && s && selfw, SDT_ERR_INVALID_ARG,
+                "sdt_gcn_aggregate_bwd: null pointer (the block needs its transposed arrays)");
+    const float* g = static_cast<const float*>(dA);
+    const float* y = static_cast<const float*>(relu_of);
+    float* out = static_cast<float*>(dH);
+    const int ve = vec_floats(F, {lda, ldd}, {dA, dH, relu_of});
+    const int G = (F + ve - 1) / ve > 16 ? 64 : 16;
+    hipStream_t stm = static_cast<hipStream_t>(stream);
+    SDT_GCN_DISPATCH(ve, G, hipLaunchKernelGGL((k_gcn_aggregate_bwd<VE, GG>), dim3(rows_grid(blk->cap_src, GG)), dim3(TB),
+                                               0, stm, blk->t_indptr, blk->t_rows, blk->counts, g, lda, F, c, s, selfw, y,
+                                               out, ldd));
+    SDT_CHECK_LAUNCH("gcn_aggregate_bwd");
+    return SDT_OK;
+}

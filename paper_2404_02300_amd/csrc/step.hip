@@ -27,6 +27,10 @@ bool compute_caps(int64_t n_nodes, int32_t batch, const int32_t* fanouts, int L,
     return true;
 }
 
+// width of one of the two operands the projection kernels take: [Hself | A] for GraphSAGE, the two
+// halves of the aggregated row for GCN (whose single weight matrix [in, out] is then [2 * in/2, out])
+inline int32_t operand_width(const sdt_model* m, int l) { return m->kind == SDT_MODEL_GCN ? m->dims[l] / 2 : m->dims[l]; }
+
 // scratch of one layer's projection backward (split partials of dW/db, or the fused head's)
 size_t bwd_scratch_bytes(int32_t batch, int32_t cap_dst, int32_t in, int32_t out, bool last) {
     size_t lb = sdt_linear_bwd_workspace_bytes(cap_dst, in, out);
@@ -46,6 +50,13 @@ int32_t check_model(const sdt_model* m, const int32_t* fanouts, const char* who)
     for (int l = 0; l < m->n_layers; ++l)
         SDT_REQUIRE(fanouts[l] >= 0 && fanouts[l] <= SDT_MAX_FANOUT, SDT_ERR_INVALID_ARG,
                     "%s: fanouts[%d] = %d outside [0,%d]", who, l, fanouts[l], SDT_MAX_FANOUT);
+    SDT_REQUIRE(m->kind == SDT_MODEL_SAGE_MEAN || m->kind == SDT_MODEL_GCN, SDT_ERR_INVALID_ARG, "%s: unknown model kind %d",
+                who, m->kind);
+    if (m->kind == SDT_MODEL_GCN)
+        for (int l = 0; l < m->n_layers; ++l)
+            SDT_REQUIRE(m->dims[l] % 2 == 0, SDT_ERR_INVALID_ARG,
+                        "%s: GCN needs even layer input widths (dims[%d] = %d): the projection runs as two half-width operands",
+                        who, l, m->dims[l]);
     return SDT_OK;
 }
 
@@ -145,6 +156,8 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
     int32_t rc = check_model(model, fanouts, "sdt_train_step_layout");
     if (rc != SDT_OK) return rc;
     SDT_REQUIRE(dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_train_step_layout: unknown dtype %d", dtype);
+    SDT_REQUIRE(model->kind != SDT_MODEL_GCN || dtype == SDT_F32, SDT_ERR_INVALID_ARG,
+                "sdt_train_step_layout: the GCN model is fp32 only");
     SDT_REQUIRE(n_nodes >= 0 && n_nodes <= 0x7FFFFFFF && batch >= 0 && batch <= n_nodes, SDT_ERR_INVALID_ARG,
                 "sdt_train_step_layout: n_nodes=%lld batch=%d", (long long)n_nodes, batch);
     const int L = model->n_layers;
@@ -181,7 +194,7 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
         Arena s(nullptr);
         size_t sb = sample_tmp_carve(s, n_nodes, c.dst[l], fanouts[l], nullptr);
         if (sb > scratch) scratch = sb;
-        bwd_scratch += bwd_scratch_bytes(batch, c.dst[l], d[l], d[l + 1], l == L - 1);
+        bwd_scratch += bwd_scratch_bytes(batch, c.dst[l], operand_width(model, l), d[l + 1], l == L - 1);
     }
     // the sampling scratch is dead once phase 2 starts; the backward keeps one region per layer
     // alive until the single reduction launch at the end of the step
@@ -195,6 +208,10 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
         for (int l = 0; l < L; ++l) wb += bf16_weights_bytes(d[l], d[l + 1]);
         lay->wlow = a.take_off(wb);
     }
+    if (model->kind == SDT_MODEL_GCN)
+        for (int l = 0; l < L; ++l)
+            lay->norm[l] = a.take_off(align_up((size_t)(c.src[l] > 0 ? c.src[l] : 1) * 4, 256) +
+                                      2 * align_up((size_t)(c.dst[l] > 0 ? c.dst[l] : 1) * 4, 256));
     lay->total_bytes = a.off;
     return SDT_OK;
 }
@@ -222,6 +239,15 @@ struct StepBuffers {
     size_t bytes;
     sdt_block blk[SDT_MAX_LAYERS];
     void* at(uint64_t off) const { return base + off; }
+    // GCN normalisation vectors of layer l (see sdt_step_layout::norm)
+    float* gcn_c(const sdt_step_layout& lay, int l) const { return static_cast<float*>(at(lay.norm[l])); }
+    float* gcn_s(const sdt_step_layout& lay, int l) const {
+        return reinterpret_cast<float*>(base + lay.norm[l] + align_up((size_t)(lay.cap_src[l] > 0 ? lay.cap_src[l] : 1) * 4, 256));
+    }
+    float* gcn_self(const sdt_step_layout& lay, int l) const {
+        return reinterpret_cast<float*>(reinterpret_cast<char*>(gcn_s(lay, l)) +
+                                        align_up((size_t)(lay.cap_dst[l] > 0 ? lay.cap_dst[l] : 1) * 4, 256));
+    }
 };
 
 int32_t check_step_args(const char* who, const sdt_csr* graph, const void* X, int64_t ldx, const int32_t* labels,
@@ -287,6 +313,18 @@ int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds
         dst = b.blk[l].src_nodes;
         n_d = b.blk[l].counts + 1;
     }
+    if (c.model->kind == SDT_MODEL_GCN) {
+        // normalisation vectors of every block, then layer 0's aggregation straight out of X (it also
+        // hands the frontier map back clean: every frontier node is a row or a column of block 0)
+        for (int l = 0; l < L; ++l) {
+            rc = sdt_gcn_norm(c.graph, &b.blk[l], b.gcn_c(lay, l), b.gcn_s(lay, l), b.gcn_self(lay, l), st);
+            if (rc != SDT_OK) return rc;
+        }
+        SDT_REQUIRE(lay.cap_dst[0] == 0 || aligned16(c.X), SDT_ERR_INVALID_ARG, "sdt_train_step: X must be 16-byte aligned");
+        StageTimer tm(c.timing, SDT_STAGE_AGG_FWD, 0, st);
+        return gcn_aggregate_fwd(&b.blk[0], static_cast<const float*>(c.X), c.ldx, true, d[0], b.gcn_c(lay, 0),
+                                 b.gcn_s(lay, 0), b.gcn_self(lay, 0), static_cast<float*>(b.at(lay.A[0])), d[0], sw.map, st);
+    }
     // Input features: only the destination prefix of the outermost frontier is copied (the
     // projection's "self" operand); the neighbour mean of layer 0 is taken straight out of X.
     // Both passes hand the frontier map back clean (prefix nodes here, the rest there).
@@ -300,8 +338,95 @@ int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds
     return aggregate_gather_fwd(&b.blk[0], c.X, c.ldx, d[0], c.dtype, b.at(lay.A[0]), d[0], sw.map, st);
 }
 
+// Phase 2 of a GCN step.  The projection kernels take two operands of equal width; here they are
+// the two halves of the aggregated row, so W[l] = [in, out] is exactly their [2 * in/2, out] weight
+// and their two input gradients land side by side as the gradient w.r.t. the aggregated row.
+int32_t step_compute_gcn(const StepCtx& c, const StepBuffers& b, const int32_t* seeds, float* loss_d, hipStream_t st) {
+    const sdt_step_layout& lay = c.lay;
+    const sdt_model* model = c.model;
+    const int L = model->n_layers;
+    const int32_t* d = model->dims;
+    sdt_timing* timing = c.timing;
+    int32_t rc;
+    const int hl = d[L - 1] / 2;
+    const bool fused_head = head_supported(hl, d[L]) && aligned16(model->W[L - 1]);
+    size_t scr_off[SDT_MAX_LAYERS], scr_len[SDT_MAX_LAYERS];
+    {
+        size_t o = lay.scratch;
+        for (int l = 0; l < L; ++l) {
+            scr_len[l] = bwd_scratch_bytes(c.batch, lay.cap_dst[l], d[l] / 2, d[l + 1], l == L - 1);
+            scr_off[l] = o;
+            o += scr_len[l];
+        }
+    }
+    PendingReduce pending[SDT_MAX_LAYERS];
+    int n_pending = 0;
+    auto half0 = [&](int l) { return static_cast<float*>(b.at(lay.A[l])); };
+    auto half1 = [&](int l) { return static_cast<float*>(b.at(lay.A[l])) + d[l] / 2; };
+    for (int l = 0; l < L; ++l) {
+        if (l > 0) {
+            StageTimer tm(timing, SDT_STAGE_AGG_FWD, l, st);
+            rc = sdt_gcn_aggregate_fwd(&b.blk[l], b.at(lay.H[l]), d[l], 0, d[l], SDT_F32, b.gcn_c(lay, l), b.gcn_s(lay, l),
+                                       b.gcn_self(lay, l), b.at(lay.A[l]), d[l], st);
+            if (rc != SDT_OK) return rc;
+        }
+        const bool last = l == L - 1;
+        if (last && fused_head) break;
+        StageTimer tm(timing, SDT_STAGE_LINEAR_FWD, l, st);
+        rc = sdt_sage_linear_fwd(half0(l), d[l], half1(l), d[l], lay.cap_dst[l], b.blk[l].counts, d[l] / 2, d[l + 1],
+                                 model->W[l], model->b[l], last ? 0 : 1, SDT_F32, b.at(lay.H[l + 1]), d[l + 1], SDT_F32, st);
+        if (rc != SDT_OK) return rc;
+    }
+    if (!fused_head) {
+        StageTimer tm(timing, SDT_STAGE_LOSS, 0, st);
+        rc = softmax_xent(static_cast<const float*>(b.at(lay.H[L])), d[L], c.batch, d[L], c.labels, seeds,
+                          static_cast<float*>(b.at(lay.dZ)), static_cast<float*>(b.at(lay.row_loss)), st);
+        if (rc != SDT_OK) return rc;
+    }
+    const void* dY = b.at(lay.dZ);
+    for (int l = L - 1; l >= 0; --l) {
+        float* dW = model->dW[l] ? model->dW[l] : static_cast<float*>(b.at(lay.dW[l]));
+        float* db = model->db[l] ? model->db[l] : static_cast<float*>(b.at(lay.db[l]));
+        const bool inner = l > 0;
+        float* dA = inner ? static_cast<float*>(b.at(lay.dAgg[l])) : nullptr;   // gradient w.r.t. the aggregated row
+        BwdExtras ex;
+        ex.defer = &pending[n_pending++];
+        ex.W_upd = model->W[l];
+        ex.b_upd = model->b[l];
+        {
+            StageTimer tm(timing, SDT_STAGE_LINEAR_BWD, l, st);
+            if (l == L - 1 && fused_head) {
+                float *P, *Q;
+                {
+                    StageTimer th(timing, SDT_STAGE_HEAD, l, st);
+                    rc = head_fwd_bwd(half0(l), d[l], half1(l), d[l], c.batch, hl, d[l + 1], model->W[l], model->b[l], SDT_F32,
+                                      c.labels, seeds, static_cast<float*>(b.at(lay.H[L])), static_cast<float*>(b.at(lay.dZ)),
+                                      static_cast<float*>(b.at(lay.row_loss)), dA, inner ? dA + hl : nullptr, d[l],
+                                      b.at(scr_off[l]), scr_len[l], &P, &Q, st);
+                }
+                if (rc != SDT_OK) return rc;
+                rc = reduce_partials(P, Q, head_splits(c.batch), hl, d[l + 1], dW, db, ex, st);
+            } else {
+                rc = linear_bwd(dY, d[l + 1], SDT_F32, nullptr, 0, 0, half0(l), d[l], half1(l), d[l], lay.cap_dst[l],
+                                b.blk[l].counts, d[l] / 2, d[l + 1], model->W[l], SDT_F32, dW, db, dA,
+                                inner ? dA + d[l] / 2 : nullptr, d[l], b.at(scr_off[l]), scr_len[l], ex, st);
+            }
+            if (rc != SDT_OK) return rc;
+        }
+        if (inner) {
+            StageTimer tm(timing, SDT_STAGE_AGG_BWD, l, st);
+            rc = sdt_gcn_aggregate_bwd(&b.blk[l], dA, d[l], b.at(lay.H[l]), d[l], SDT_F32, b.gcn_c(lay, l), b.gcn_s(lay, l),
+                                       b.gcn_self(lay, l), b.at(lay.dH[l]), d[l], st);
+            if (rc != SDT_OK) return rc;
+            dY = b.at(lay.dH[l]);
+        }
+    }
+    return reduce_all(pending, n_pending, c.lr, static_cast<const float*>(b.at(lay.row_loss)), c.batch, loss_d, st);
+}
+
 // Phase 2: forward, loss, backward, SGD on the blocks and features phase 1 left in `b`.
 int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seeds, float* loss_d, hipStream_t st) {
+    if (c.model->kind == SDT_MODEL_GCN) return step_compute_gcn(c, b, seeds, loss_d, st);
     const sdt_step_layout& lay = c.lay;
     const sdt_model* model = c.model;
     const int L = model->n_layers;

@@ -47,6 +47,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="products",
                     choices=["tiny", "products", "dense", "sparse_bf16", "fullgraph"])
+    ap.add_argument("--model", default="sage", choices=["sage", "gcn"],
+                    help="gcn: the same step with the GCN model kind (fp32 workloads; not the headline metric)")
     ap.add_argument("--lr", type=float, default=0.01)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial", action="store_true", help="no auxiliary stream: every step strictly in sequence")
@@ -90,9 +92,17 @@ def main():
     else:
         X = torch.from_numpy(inst.X).cuda()
     y = torch.from_numpy(inst.y).cuda()
-    W = [torch.from_numpy(w).cuda() for w in inst.W]
+    gcn = args.model == "gcn"
+    if gcn:     # one [in, out] matrix per layer, Glorot-uniform from the workload's seed
+        assert not wl.bf16, "the GCN model kind is fp32 only"
+        rng = np.random.default_rng(wl.seed)
+        Wh = [(rng.uniform(-1, 1, size=(wl.dims[l], wl.dims[l + 1])) *
+               np.sqrt(6.0 / (wl.dims[l] + wl.dims[l + 1]))).astype(np.float32) for l in range(len(wl.fanouts))]
+    else:
+        Wh = inst.W
+    W = [torch.from_numpy(w).cuda() for w in Wh]
     b = [torch.from_numpy(v).cuda() for v in inst.b]
-    model = sdt.make_model(wl.dims, W, b)
+    model = sdt.make_model(wl.dims, W, b, kind=sdt.SDT_MODEL_GCN if gcn else sdt.SDT_MODEL_SAGE_MEAN)
     code = sdt.SDT_BF16 if wl.bf16 else sdt.SDT_F32
     lay = sdt.sdt_train_step_layout(graph.n_nodes, wl.batch, wl.fanouts, model, code)
     ws = torch.empty(sdt.sdt_train_loop_workspace_bytes(graph.n_nodes, wl.batch, wl.fanouts, model, code),
@@ -116,7 +126,7 @@ def main():
             if per_step is not None:
                 per_step(i)
 
-    stages = [("sample", l) for l in range(L)] + [("gather", 0)] + [("aggregate_fwd", l) for l in range(L)] + \
+    stages = [("sample", l) for l in range(L)] + ([] if gcn else [("gather", 0)]) + [("aggregate_fwd", l) for l in range(L)] + \
              [("linear_fwd", l) for l in range(L)] + [("loss", 0)] + [("linear_bwd", l) for l in range(L)] + \
              [("aggregate_bwd", l) for l in range(1, L)] + [("head", L - 1)]
     single_kernel = {"gather", "aggregate_fwd", "linear_fwd", "aggregate_bwd", "head"}   # one launch per stage
@@ -170,6 +180,7 @@ def main():
     def work(kind, l):
         """Algorithmic work of one launch of a stage: (bound, amount, unit of the rate, kernels)."""
         n_dst, n_src, nnz = mean_cnt[l][:3]
+        wf = 1.0 if gcn else 2.0      # rows of W per input feature: GraphSAGE stacks a self and a neighbour block
         if kind == "sample":      # 16 B of row offsets per destination, 4 B read + 4 B written per sampled edge
             return "hbm", n_dst * 16 + nnz * 8, "k_sample_rows + frontier scan + relabel (+ transposed block)"
         if kind == "gather":      # only the destination prefix is copied; the rest is read by the aggregation
@@ -179,17 +190,17 @@ def main():
         if kind == "aggregate_bwd":
             return "hbm", nnz * (d[l] * es + 4) + n_src * (d[l] * es + 8) + n_dst * d[l] * es, "k_aggregate_bwd"
         if kind == "linear_fwd":    # bf16 workloads: bf16 matrix cores (priced against the bf16 peak)
-            return ("mfma_bf16" if wl.bf16 else "mfma"), 2.0 * n_dst * 2 * d[l] * d[l + 1], \
+            return ("mfma_bf16" if wl.bf16 else "mfma"), 2.0 * n_dst * wf * d[l] * d[l + 1], \
                    ("k_fwd_bf16" if wl.bf16 else "k_linear_fwd")
         if kind == "linear_bwd":
-            f = 2.0 * n_dst * 2 * d[l] * d[l + 1]
+            f = 2.0 * n_dst * wf * d[l] * d[l + 1]
             if l == L - 1 and fused_head:   # projection + softmax + dW + input gradients in one launch
                 return "mfma", f * (3 if l > 0 else 2), "k_head"
             if wl.bf16:   # both backward products on the bf16 matrix cores
                 return "mfma_bf16", f * (2 if l > 0 else 1), "k_bwd_weight_bf16 (+ k_bwd_input_bf16)"
             return "mfma", f * (2 if l > 0 else 1), "k_linear_bwd_weight (+ _input)"
         if kind == "head":        # projection + dW (+ input gradients) of the last layer, one launch
-            return "mfma", 2.0 * n_dst * 2 * d[l] * d[l + 1] * (3 if l > 0 else 2), "k_head"
+            return "mfma", 2.0 * n_dst * wf * d[l] * d[l + 1] * (3 if l > 0 else 2), "k_head"
         return "hbm", wl.batch * d[L] * 8, "k_softmax_xent"
 
     def rate(kind, l, seconds):
@@ -217,15 +228,26 @@ def main():
         ns = max(1, args.cpu_steps)
         tc = time.perf_counter()
         for s in range(ns):
-            orc.train_step(inst.indptr, inst.indices, inst.X, inst.y, inst.batch(s), wl.fanouts, inst.W, inst.b,
-                           wl.seed, s, args.lr, bf16=wl.bf16)
+            if gcn:
+                orc.gcn_train_step(inst.indptr, inst.indices, inst.X, inst.y, inst.batch(s), wl.fanouts, Wh, inst.b,
+                                   wl.seed, s, args.lr)
+            else:
+                orc.train_step(inst.indptr, inst.indices, inst.X, inst.y, inst.batch(s), wl.fanouts, inst.W, inst.b,
+                               wl.seed, s, args.lr, bf16=wl.bf16)
         tc = time.perf_counter() - tc
-        cpu = {"value": round(ns / tc, 4), "unit": "steps/s", "cores": 1, "kind": "oracle",
+        cores = 1
+        if gcn:     # the GCN oracle's projections are numpy matrix products: count the BLAS threads
+            try:
+                from threadpoolctl import threadpool_info
+                cores = max([1] + [int(p.get("num_threads", 1)) for p in threadpool_info()])
+            except Exception:
+                cores = os.cpu_count()
+        cpu = {"value": round(ns / tc, 4), "unit": "steps/s", "cores": cores, "kind": "oracle",
                "sample": f"{ns} full mini-batch steps of the same workload (batches 0..{ns - 1}, initial weights)",
                "host_cpus": os.cpu_count()}
 
     out = {
-        "metric": "train steps/s per GPU (sample + gather + forward + backward + SGD)",
+        "metric": "train steps/s per GPU (sample + gather + forward + backward + SGD)" + (" [GCN model kind]" if gcn else ""),
         "value": round(K / elapsed, 2), "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": round(elapsed / K * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if wl.bf16 else "f32", "data": "synthetic",

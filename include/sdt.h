@@ -256,7 +256,8 @@ int32_t sdt_sage_linear_bwd(const void *dY, int64_t lddy, int32_t dy_dtype, cons
  * step's own stream (for measurement; adds two event records per selected
  * stage).  A stage is (kind, layer); its bit in `stage_mask` is
  * kind * SDT_MAX_LAYERS + layer.  SAMPLE spans all kernels of one layer's
- * sampling; GATHER, LOSS and UPDATE use layer 0.  Each timed step consumes one
+ * sampling; GATHER and LOSS use layer 0; LINEAR_BWD covers a layer's backward
+ * products (the single reduction + SGD launch at the end of the step is not timed).  Each timed step consumes one
  * slot (at most max_steps; further steps are not timed).  sdt_timing_read
  * waits for the recorded events and writes one duration in milliseconds per
  * timed step to ms_out (host, capacity max_steps) and their number to *n_out.

@@ -25,7 +25,8 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr int TB = 256;
 constexpr int HB = 16;     // seed rows per workgroup
 constexpr int MAXCT = 16;  // logits column tiles of 16: C <= 256
-constexpr int U = 8;       // global loads a thread keeps in flight while staging
+constexpr int U = 8;       // global loads a thread keeps in flight while staging the feature rows
+constexpr int UW = 24;     // ... and while staging W: 24 x 16 B x 256 threads = 96 KB, a 512 x 47 matrix in ONE round trip
 
 __device__ __forceinline__ float maybe_round(float x, bool r) { return r ? bf16_to_f32(f32_to_bf16(x)) : x; }
 
@@ -62,13 +63,13 @@ __global__ __launch_bounds__(TB) void k_head(const TH* __restrict__ Hself, int64
         const int n4 = (K2 * C) >> 2;
         const float4* W4 = reinterpret_cast<const float4*>(W);
         float4* Ws4 = reinterpret_cast<float4*>(Ws);
-        for (int base = threadIdx.x; base < n4; base += TB * U) {
-            float4 v[U];
+        for (int base = threadIdx.x; base < n4; base += TB * UW) {
+            float4 v[UW];
 #pragma unroll
-            for (int u = 0; u < U; ++u)
+            for (int u = 0; u < UW; ++u)
                 if (base + u * TB < n4) v[u] = W4[base + u * TB];
 #pragma unroll
-            for (int u = 0; u < U; ++u)
+            for (int u = 0; u < UW; ++u)
                 if (base + u * TB < n4) {
                     float4 x = v[u];
                     if (rnd) {

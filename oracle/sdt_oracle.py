@@ -404,3 +404,16 @@ def gcn_train_step(indptr, indices, X, y, seeds, fanouts, W, b, seed: int, step:
     b_new = [sgd(b[l], db[l], lr) for l in range(L)]
     return dict(blocks=blocks, H=H, A=A, logits=H[L], loss=loss, dZ=dZ, W=W, W_new=W_new, b_new=b_new, dW=dW, db=db,
                 dA=dA, dH=dHs, weights=wts)
+
+
+# ------------------------------------------------------------------ Adam
+def adam(w, g, m, v, t: int, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8):
+    """One Adam update (Kingma & Ba) in float64: m <- b1 m + (1-b1) g, v <- b2 v + (1-b2) g^2,
+    w <- w - lr * (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps); t counts updates from 1.
+    Returns (w, m, v).  (The paper does not name its optimiser; plain SGD is the default here.)"""
+    w, g = np.asarray(w, dtype=np.float64), np.asarray(g, dtype=np.float64)
+    m = beta1 * np.asarray(m, dtype=np.float64) + (1.0 - beta1) * g
+    v = beta2 * np.asarray(v, dtype=np.float64) + (1.0 - beta2) * g * g
+    mhat = m / (1.0 - beta1 ** t)
+    vhat = v / (1.0 - beta2 ** t)
+    return w - lr * mhat / (np.sqrt(vhat) + eps), m, v

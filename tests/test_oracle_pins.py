@@ -540,3 +540,21 @@ def test_gcn_step_gradients_match_autograd_on_a_dense_formulation():
         assert np.allclose(ref["dW"][l], Wt[l].grad.numpy(), rtol=1e-10, atol=1e-12)
         assert np.allclose(ref["db"][l], bt[l].grad.numpy(), rtol=1e-10, atol=1e-12)
         assert np.allclose(ref["W_new"][l], W[l] - 0.1 * Wt[l].grad.numpy(), rtol=1e-12, atol=1e-13)
+
+
+# ----------------------------------------------------------------- Adam
+def test_adam_matches_library_optimiser():
+    rng = np.random.default_rng(31)
+    w0 = rng.standard_normal((7, 5))
+    grads = [rng.standard_normal((7, 5)) * s for s in (1.0, 0.1, 3.0, 1e-4)]
+    p = torch.nn.Parameter(torch.tensor(w0, dtype=torch.float64))
+    opt = torch.optim.Adam([p], lr=0.02, betas=(0.8, 0.95), eps=1e-7)
+    w, m, v = w0, np.zeros_like(w0), np.zeros_like(w0)
+    for t, g in enumerate(grads, start=1):
+        p.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        w, m, v = orc.adam(w, g, m, v, t, 0.02, 0.8, 0.95, 1e-7)
+        assert np.allclose(w, p.detach().numpy(), rtol=1e-12, atol=1e-14)
+    # first update from zero moments: a step of lr * sign(g) (up to eps)
+    w1, _, _ = orc.adam(np.zeros(4), np.array([2.0, -3.0, 0.5, -1e-3]), np.zeros(4), np.zeros(4), 1, 0.1)
+    assert np.allclose(w1, [-0.1, 0.1, -0.1, 0.1], rtol=1e-4)

@@ -100,9 +100,22 @@ typedef struct sdt_model {
      * H' = act(Agcn(H) W[l] + b[l]) with ONE weight matrix W[l] fp32 [dims[l], dims[l+1]]
      * and the aggregation of sdt_gcn_aggregate_fwd; fp32 storage and even dims[0..L-1] only. */
     int32_t kind;
+    /* Optimiser of sdt_train_step: SDT_OPT_SGD (0, the default; w -= lr g) or SDT_OPT_ADAM:
+     * m = beta1 m + (1-beta1) g, v = beta2 v + (1-beta2) g^2,
+     * w -= lr (m / (1-beta1^t)) / (sqrt(v / (1-beta2^t)) + eps) with t = step + 1 (the step
+     * argument of sdt_train_step counts updates from 0).  mW/vW (like W) and mb/vb (like b)
+     * are the caller's fp32 moment buffers, zero before the first step.  (The paper does not
+     * name its optimiser.) */
+    int32_t optimizer;
+    float beta1, beta2, eps;
     int32_t reserved;
+    float *mW[SDT_MAX_LAYERS];
+    float *vW[SDT_MAX_LAYERS];
+    float *mb[SDT_MAX_LAYERS];
+    float *vb[SDT_MAX_LAYERS];
 } sdt_model;
 enum { SDT_MODEL_SAGE_MEAN = 0, SDT_MODEL_GCN = 1 };
+enum { SDT_OPT_SGD = 0, SDT_OPT_ADAM = 1 };
 
 /* Byte offsets, inside the sdt_train_step workspace, of everything the step
  * produces (so a caller can inspect it), plus the capacities they were sized

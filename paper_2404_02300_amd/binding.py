@@ -22,6 +22,7 @@ SDT_F32, SDT_BF16 = 0, 1
 SDT_MAX_LAYERS = 8
 SDT_MAX_FANOUT = 64
 SDT_MODEL_SAGE_MEAN, SDT_MODEL_GCN = 0, 1
+SDT_OPT_SGD, SDT_OPT_ADAM = 0, 1
 
 _vp, _i32, _i64, _u32, _u64, _sz = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32,
                                     ctypes.c_uint64, ctypes.c_size_t)
@@ -46,7 +47,10 @@ class sdt_block(ctypes.Structure):
 class sdt_model(ctypes.Structure):
     _fields_ = [("n_layers", _i32), ("dims", _i32 * (SDT_MAX_LAYERS + 1)),
                 ("W", _vp * SDT_MAX_LAYERS), ("b", _vp * SDT_MAX_LAYERS),
-                ("dW", _vp * SDT_MAX_LAYERS), ("db", _vp * SDT_MAX_LAYERS), ("kind", _i32), ("reserved", _i32)]
+                ("dW", _vp * SDT_MAX_LAYERS), ("db", _vp * SDT_MAX_LAYERS), ("kind", _i32), ("optimizer", _i32),
+                ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float), ("reserved", _i32),
+                ("mW", _vp * SDT_MAX_LAYERS), ("vW", _vp * SDT_MAX_LAYERS), ("mb", _vp * SDT_MAX_LAYERS),
+                ("vb", _vp * SDT_MAX_LAYERS)]
 
 
 class sdt_step_layout(ctypes.Structure):
@@ -282,6 +286,19 @@ def make_model(dims: Sequence[int], W: List[torch.Tensor], b: List[torch.Tensor]
         m.dW[l] = dW[l].data_ptr() if dW is not None else None
         m.db[l] = db[l].data_ptr() if db is not None else None
     return m
+
+
+def use_adam(model: sdt_model, mW: List[torch.Tensor], vW: List[torch.Tensor], mb: List[torch.Tensor],
+             vb: List[torch.Tensor], beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8) -> sdt_model:
+    """Switch a model to Adam; the moment tensors (fp32, shaped like W / b, zero before the first step)
+    stay owned by the caller."""
+    model.optimizer, model.beta1, model.beta2, model.eps = SDT_OPT_ADAM, beta1, beta2, eps
+    for l in range(model.n_layers):
+        for t in (mW[l], vW[l], mb[l], vb[l]):
+            assert t.dtype == torch.float32 and t.is_contiguous()
+        model.mW[l], model.vW[l], model.mb[l], model.vb[l] = (mW[l].data_ptr(), vW[l].data_ptr(), mb[l].data_ptr(),
+                                                              vb[l].data_ptr())
+    return model
 
 
 def sdt_train_step_layout(n_nodes: int, batch: int, fanouts: Sequence[int], model: sdt_model,

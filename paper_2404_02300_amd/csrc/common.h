@@ -147,6 +147,17 @@ struct PendingReduce {
     float* db = nullptr;
     float* W_upd = nullptr;
     float* b_upd = nullptr;
+    // Adam moments (all four or none)
+    float* mW = nullptr;
+    float* vW = nullptr;
+    float* mb = nullptr;
+    float* vb = nullptr;
+};
+// How the update is applied once a gradient is final.  adam: c1 = 1/(1-beta1^t), c2 = 1/(1-beta2^t).
+struct OptArgs {
+    float lr = 0.f;
+    int32_t adam = 0;
+    float beta1 = 0.f, beta2 = 0.f, eps = 0.f, c1 = 1.f, c2 = 1.f;
 };
 struct BwdExtras {
     PendingReduce* defer = nullptr;  // if set, the reduction is described here instead of launched
@@ -168,8 +179,8 @@ int32_t linear_bwd(const void* dY, int64_t lddy, int32_t dy_dtype, const void* Y
 int32_t reduce_partials(const float* P, const float* Q, int32_t splits, int32_t in, int32_t out, float* dW, float* db,
                         const BwdExtras& ex, hipStream_t st);
 // the pending reductions of several layers (and the mean of the per-seed losses) in ONE launch
-int32_t reduce_all(const PendingReduce* r, int32_t n, float lr, const float* row_loss, int32_t n_loss, float* loss_out,
-                   hipStream_t st);
+int32_t reduce_all(const PendingReduce* r, int32_t n, const OptArgs& opt, const float* row_loss, int32_t n_loss,
+                   float* loss_out, hipStream_t st);
 
 // bf16 matrix-core path (linear_bf16.hip).  Per layer the image region holds Wt = bf16 [out][2 in]
 // followed (256-byte aligned) by Wb = bf16 [2 in][bf16_ldb(out)], layers back to back.

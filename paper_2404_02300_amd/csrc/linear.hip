@@ -374,7 +374,20 @@ struct ReduceArgs {
     int32_t first[SDT_MAX_LAYERS + 1];  // first workgroup of each layer
     PendingReduce r[SDT_MAX_LAYERS];
 };
-__global__ __launch_bounds__(TB) void k_reduce_partials(ReduceArgs a, float lr, const float* __restrict__ row_loss,
+// w <- w - lr g (SGD) or the Adam update with the moments m, v kept beside w
+__device__ __forceinline__ void apply_update(float* w, float g, float* m, float* v, const OptArgs& o) {
+    if (o.adam && m) {
+        const float mn = o.beta1 * *m + (1.0f - o.beta1) * g;
+        const float vn = o.beta2 * *v + (1.0f - o.beta2) * g * g;
+        *m = mn;
+        *v = vn;
+        *w = *w - o.lr * (mn * o.c1) / (sqrtf(vn * o.c2) + o.eps);
+    } else {
+        *w = *w - o.lr * g;
+    }
+}
+
+__global__ __launch_bounds__(TB) void k_reduce_partials(ReduceArgs a, OptArgs opt, const float* __restrict__ row_loss,
                                                         int n_loss, float* loss_out) {
     __shared__ float part[TB];
     if ((int)blockIdx.x == a.first[a.n]) {  // the extra last block: mean loss in a fixed order
@@ -410,11 +423,11 @@ __global__ __launch_bounds__(TB) void k_reduce_partials(ReduceArgs a, float lr, 
         const float t = ((part[e] + part[64 + e]) + part[128 + e]) + part[192 + e];
         if (is_w) {
             r.dW[idx] = t;
-            if (r.W_upd) r.W_upd[idx] = r.W_upd[idx] - lr * t;
+            if (r.W_upd) apply_update(r.W_upd + idx, t, r.mW ? r.mW + idx : nullptr, r.vW ? r.vW + idx : nullptr, opt);
         } else {
             const int o = (int)(idx - n_w);
             r.db[o] = t;
-            if (r.b_upd) r.b_upd[o] = r.b_upd[o] - lr * t;
+            if (r.b_upd) apply_update(r.b_upd + o, t, r.mb ? r.mb + o : nullptr, r.vb ? r.vb + o : nullptr, opt);
         }
     }
 }
@@ -549,7 +562,11 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Hself, int64_t ldh, co
     pr.P = P; pr.Q = Q; pr.splits = splits; pr.in = in; pr.out = out;
     pr.dW = dW; pr.db = db; pr.W_upd = ex.W_upd; pr.b_upd = ex.b_upd;
     if (ex.defer) *ex.defer = pr;
-    else (void)reduce_all(&pr, 1, ex.lr, ex.row_loss, ex.n_loss, ex.loss_out, st);
+    else {
+        OptArgs opt;
+        opt.lr = ex.lr;
+        (void)reduce_all(&pr, 1, opt, ex.row_loss, ex.n_loss, ex.loss_out, st);
+    }
 }
 
 
@@ -610,8 +627,8 @@ extern "C" size_t sdt_linear_bwd_workspace_bytes(int32_t n_cap, int32_t in, int3
 }
 
 namespace sdt {
-int32_t reduce_all(const PendingReduce* r, int32_t n, float lr, const float* row_loss, int32_t n_loss, float* loss_out,
-                   hipStream_t st) {
+int32_t reduce_all(const PendingReduce* r, int32_t n, const OptArgs& opt, const float* row_loss, int32_t n_loss,
+                   float* loss_out, hipStream_t st) {
     SDT_REQUIRE(r && n >= 1 && n <= SDT_MAX_LAYERS, SDT_ERR_INVALID_ARG, "reduce_all: %d reductions", n);
     ReduceArgs a{};
     a.n = n;
@@ -620,7 +637,7 @@ int32_t reduce_all(const PendingReduce* r, int32_t n, float lr, const float* row
         a.r[l] = r[l];
         a.first[l + 1] = a.first[l] + ceil_div((int64_t)2 * r[l].in * r[l].out + r[l].out, 64);
     }
-    hipLaunchKernelGGL(k_reduce_partials, dim3(a.first[n] + (loss_out ? 1 : 0)), dim3(TB), 0, st, a, lr, row_loss, n_loss,
+    hipLaunchKernelGGL(k_reduce_partials, dim3(a.first[n] + (loss_out ? 1 : 0)), dim3(TB), 0, st, a, opt, row_loss, n_loss,
                        loss_out);
     SDT_CHECK_LAUNCH("reduce_partials");
     return SDT_OK;
@@ -635,7 +652,9 @@ int32_t reduce_partials(const float* P, const float* Q, int32_t splits, int32_t 
         *ex.defer = pr;
         return SDT_OK;
     }
-    return reduce_all(&pr, 1, ex.lr, ex.row_loss, ex.n_loss, ex.loss_out, st);
+    OptArgs opt;
+    opt.lr = ex.lr;
+    return reduce_all(&pr, 1, opt, ex.row_loss, ex.n_loss, ex.loss_out, st);
 }
 
 int32_t linear_bwd(const void* dY, int64_t lddy, int32_t dy_dtype, const void* Y, int64_t ldy, int32_t relu,

@@ -219,6 +219,29 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
 namespace {
 
 // Everything one step needs, resolved once per call.
+// SGD or Adam, from the model struct; `step` is the 0-based update counter
+OptArgs optimizer_args(const sdt_model* m, float lr, uint32_t step) {
+    OptArgs o;
+    o.lr = lr;
+    if (m->optimizer == SDT_OPT_ADAM) {
+        o.adam = 1;
+        o.beta1 = m->beta1;
+        o.beta2 = m->beta2;
+        o.eps = m->eps;
+        const double t = (double)step + 1.0;
+        o.c1 = (float)(1.0 / (1.0 - pow((double)m->beta1, t)));
+        o.c2 = (float)(1.0 / (1.0 - pow((double)m->beta2, t)));
+    }
+    return o;
+}
+void attach_moments(PendingReduce* pr, const sdt_model* m, int l) {
+    if (m->optimizer != SDT_OPT_ADAM) return;
+    pr->mW = m->mW[l];
+    pr->vW = m->vW[l];
+    pr->mb = m->mb[l];
+    pr->vb = m->vb[l];
+}
+
 struct StepCtx {
     const sdt_csr* graph;
     const void* X;
@@ -258,6 +281,15 @@ int32_t check_step_args(const char* who, const sdt_csr* graph, const void* X, in
     SDT_REQUIRE(graph->indices || graph->n_nodes == 0, SDT_ERR_INVALID_ARG, "%s: null indices", who);
     for (int l = 0; l < model->n_layers; ++l)
         SDT_REQUIRE(model->W[l] && model->b[l], SDT_ERR_INVALID_ARG, "%s: null weights of layer %d", who, l);
+    SDT_REQUIRE(model->optimizer == SDT_OPT_SGD || model->optimizer == SDT_OPT_ADAM, SDT_ERR_INVALID_ARG,
+                "%s: unknown optimizer %d", who, model->optimizer);
+    if (model->optimizer == SDT_OPT_ADAM) {
+        SDT_REQUIRE(model->beta1 >= 0.f && model->beta1 < 1.f && model->beta2 >= 0.f && model->beta2 < 1.f && model->eps > 0.f,
+                    SDT_ERR_INVALID_ARG, "%s: Adam needs 0 <= beta < 1 and eps > 0", who);
+        for (int l = 0; l < model->n_layers; ++l)
+            SDT_REQUIRE(model->mW[l] && model->vW[l] && model->mb[l] && model->vb[l], SDT_ERR_INVALID_ARG,
+                        "%s: Adam needs the moment buffers of layer %d", who, l);
+    }
     return SDT_OK;
 }
 
@@ -341,7 +373,8 @@ int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds
 // Phase 2 of a GCN step.  The projection kernels take two operands of equal width; here they are
 // the two halves of the aggregated row, so W[l] = [in, out] is exactly their [2 * in/2, out] weight
 // and their two input gradients land side by side as the gradient w.r.t. the aggregated row.
-int32_t step_compute_gcn(const StepCtx& c, const StepBuffers& b, const int32_t* seeds, float* loss_d, hipStream_t st) {
+int32_t step_compute_gcn(const StepCtx& c, const StepBuffers& b, const int32_t* seeds, uint32_t step, float* loss_d,
+                         hipStream_t st) {
     const sdt_step_layout& lay = c.lay;
     const sdt_model* model = c.model;
     const int L = model->n_layers;
@@ -421,12 +454,16 @@ int32_t step_compute_gcn(const StepCtx& c, const StepBuffers& b, const int32_t* 
             dY = b.at(lay.dH[l]);
         }
     }
-    return reduce_all(pending, n_pending, c.lr, static_cast<const float*>(b.at(lay.row_loss)), c.batch, loss_d, st);
+    for (int k = 0; k < n_pending; ++k) attach_moments(&pending[k], model, L - 1 - k);   // queued last layer first
+    return reduce_all(pending, n_pending, optimizer_args(model, c.lr, step), static_cast<const float*>(b.at(lay.row_loss)),
+                      c.batch, loss_d, st);
 }
 
 // Phase 2: forward, loss, backward, SGD on the blocks and features phase 1 left in `b`.
-int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seeds, float* loss_d, hipStream_t st) {
-    if (c.model->kind == SDT_MODEL_GCN) return step_compute_gcn(c, b, seeds, loss_d, st);
+// `step` is the update counter (Adam's bias correction uses step + 1).
+int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seeds, uint32_t step, float* loss_d,
+                     hipStream_t st) {
+    if (c.model->kind == SDT_MODEL_GCN) return step_compute_gcn(c, b, seeds, step, loss_d, st);
     const sdt_step_layout& lay = c.lay;
     const sdt_model* model = c.model;
     const int L = model->n_layers;
@@ -539,7 +576,9 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
     // summed in a fixed order, the SGD step is applied, and the per-seed losses are averaged.
     // (No layer's weights were touched before this point, so every product above saw the
     // weights the step started with.)
-    return reduce_all(pending, n_pending, c.lr, static_cast<const float*>(b.at(lay.row_loss)), c.batch, loss_d, st);
+    for (int k = 0; k < n_pending; ++k) attach_moments(&pending[k], model, L - 1 - k);   // queued last layer first
+    return reduce_all(pending, n_pending, optimizer_args(model, c.lr, step), static_cast<const float*>(b.at(lay.row_loss)),
+                      c.batch, loss_d, st);
 }
 
 }  // namespace
@@ -563,7 +602,7 @@ extern "C" int32_t sdt_train_step(const sdt_csr* graph, const void* X, int64_t l
     if (timing) timing->slot = timing->used < timing->max_steps ? timing->used++ : -1;
     rc = step_sample(c, b, seeds, step, st);
     if (rc != SDT_OK) return rc;
-    return step_compute(c, b, seeds, loss_d, st);
+    return step_compute(c, b, seeds, step, loss_d, st);
 }
 
 // Step workspaces the loop rotates through: the sampling phase may run this many steps ahead.
@@ -648,14 +687,16 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
             rc = step_sample(c, buf[s * LOOP_GROUP + (i - g0)], seeds + (int64_t)i * batch, first_step + (uint32_t)i,
                              aux_st, /*check_state=*/i < LOOP_BUFFERS);
             if (!overlap && rc == SDT_OK)   // one stream: keep the order of sdt_train_step
-                rc = step_compute(c, buf[s * LOOP_GROUP + (i - g0)], seeds + (int64_t)i * batch, losses_d + i, main_st);
+                rc = step_compute(c, buf[s * LOOP_GROUP + (i - g0)], seeds + (int64_t)i * batch, first_step + (uint32_t)i,
+                                  losses_d + i, main_st);
         }
         if (!overlap || rc != SDT_OK) continue;
         (void)hipEventRecord(ready[s], aux_st);
         (void)hipStreamWaitEvent(main_st, ready[s], 0);
         for (int i = g0; i < g1 && rc == SDT_OK; ++i) {
             timing_slot(i);
-            rc = step_compute(c, buf[s * LOOP_GROUP + (i - g0)], seeds + (int64_t)i * batch, losses_d + i, main_st);
+            rc = step_compute(c, buf[s * LOOP_GROUP + (i - g0)], seeds + (int64_t)i * batch, first_step + (uint32_t)i,
+                                  losses_d + i, main_st);
         }
         if (rc == SDT_OK) (void)hipEventRecord(done[s], main_st);
     }

@@ -22,11 +22,13 @@ namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int TB = 256;
+constexpr int TB = 512;     // eight waves: every phase is a short latency chain, two waves per SIMD overlap them
+                            // (sixteen would not leave room for W in LDS: the per-wave partial logits grow with them)
+constexpr int NW = TB / 64;
 constexpr int HB = 16;     // seed rows per workgroup
 constexpr int MAXCT = 16;  // logits column tiles of 16: C <= 256
 constexpr int U = 8;       // global loads a thread keeps in flight while staging the feature rows
-constexpr int UW = 24;     // ... and while staging W: 24 x 16 B x 256 threads = 96 KB, a 512 x 47 matrix in ONE round trip
+constexpr int UW = 12;     // ... and while staging W: 12 x 16 B x 512 threads = 96 KB, a 512 x 47 matrix in ONE round trip
 
 __device__ __forceinline__ float maybe_round(float x, bool r) { return r ? bf16_to_f32(f32_to_bf16(x)) : x; }
 
@@ -34,7 +36,7 @@ __device__ __forceinline__ floatx4 mfma16(float a, float b, floatx4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
-// LDS map (floats): Hc [16][2in+4] | Zs [16][CT*16+4] | Part [4][16][CT*16] | Ws [2in*C + 16]
+// LDS map (floats): Hc [16][2in+4] | Zs [16][CT*16+4] | Part [NW][16][CT*16] | Ws [2in*C + 16]
 template <typename TH>
 __global__ __launch_bounds__(TB) void k_head(const TH* __restrict__ Hself, int64_t ldh, const TH* __restrict__ Agg,
                                              int64_t lda, int B, int in, int C, const float* __restrict__ W,
@@ -44,15 +46,15 @@ __global__ __launch_bounds__(TB) void k_head(const TH* __restrict__ Hself, int64
                                              TH* __restrict__ dSelf, TH* __restrict__ dAgg, int64_t ldi,
                                              float* __restrict__ P, float* __restrict__ Q, int round_ops) {
     extern __shared__ __align__(16) float lds[];
-    const int K2 = 2 * in;            // multiple of 16 (the launcher checks in % 8 == 0)
+    const int K2 = 2 * in;            // multiple of 32 (the launcher checks in % 16 == 0)
     const int LDH = K2 + 4;           // row stride = 4 mod 32 banks: 16-byte LDS reads conflict-free
     const int CT = (C + 15) >> 4;     // column tiles
     const int CP = CT * 16;
     const int LDZ = CP + 4;
     float* Hc = lds;                  // [HB][LDH]  [self | mean] features of the block's rows
     float* Zs = Hc + HB * LDH;        // [HB][LDZ]  logits, then the loss gradient (zero beyond C)
-    float* Part = Zs + HB * LDZ;      // [4][HB][CP] per-wave partial logits
-    float* Ws = Part + 4 * HB * CP;   // [K2][C] exact flat copy of W (+16 floats of zero slack)
+    float* Part = Zs + HB * LDZ;      // [NW][HB][CP] per-wave partial logits
+    float* Ws = Part + NW * HB * CP;   // [K2][C] exact flat copy of W (+16 floats of zero slack)
     const int row0 = blockIdx.x * HB;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int li = lane & 15, kg = lane >> 4;
@@ -115,11 +117,11 @@ __global__ __launch_bounds__(TB) void k_head(const TH* __restrict__ Hself, int64
     }
     __syncthreads();
 
-    // ---- (a) logits.  Every wave takes a quarter of the reduction range for ALL column tiles
-    // (balanced whatever CT is, and the A operand is read once per step for all tiles); the four
+    // ---- (a) logits.  Every wave takes an eighth of the reduction range for ALL column tiles
+    // (balanced whatever CT is, and the A operand is read once per step for all tiles); the
     // partial tiles are then added in a fixed order.
     {
-        const int kq = K2 / 4;  // multiple of 4; steps of 16 with a tail of 0, 4, 8 or 12
+        const int kq = K2 / NW;  // multiple of 4; steps of 16 with a tail of 0, 4, 8 or 12
         const int k_lo = wave * kq;
         for (int ct0 = 0; ct0 < CT; ct0 += 4) {  // at most 4 tiles' accumulators live at a time
             floatx4 acc[4];
@@ -159,7 +161,9 @@ __global__ __launch_bounds__(TB) void k_head(const TH* __restrict__ Hself, int64
         const int row = idx / CP, col = idx - row * CP;
         float z = 0.f;
         if (col < C) {
-            z = ((Part[idx] + Part[HB * CP + idx]) + Part[2 * HB * CP + idx]) + Part[3 * HB * CP + idx];
+            z = Part[idx];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) z += Part[w * HB * CP + idx];
             z += bias ? bias[col] : 0.f;
             if (row0 + row < B) logits[(int64_t)(row0 + row) * C + col] = z;
         }
@@ -167,8 +171,8 @@ __global__ __launch_bounds__(TB) void k_head(const TH* __restrict__ Hself, int64
     }
     __syncthreads();
 
-    // ---- (b) softmax cross-entropy: 16 lanes per row, four rows per wave at once
-    {
+    // ---- (b) softmax cross-entropy: 16 lanes per row, four rows per wave at once (waves 0-3)
+    if (wave < 4) {
         const int row = wave * 4 + kg;
         const bool live = row0 + row < B;
         float* z = Zs + row * LDZ;
@@ -196,21 +200,22 @@ __global__ __launch_bounds__(TB) void k_head(const TH* __restrict__ Hself, int64
     }
     __syncthreads();
 
-    // ---- (c) input gradients [dSelf | dAgg] = dZ W^T: tiles of 16 input columns, 8 at a time per wave
+    // ---- (c) input gradients [dSelf | dAgg] = dZ W^T: tiles of 16 input columns, 4 at a time per wave
     if (dSelf) {
         const int MT = K2 >> 4;
-        for (int mt0 = wave * 8; mt0 < MT; mt0 += 32) {
-            floatx4 acc[8];
+        constexpr int TPW = 4;
+        for (int mt0 = wave * TPW; mt0 < MT; mt0 += NW * TPW) {
+            floatx4 acc[TPW];
 #pragma unroll
-            for (int t = 0; t < 8; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
-            const int nt = min(8, MT - mt0);
+            for (int t = 0; t < TPW; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+            const int nt = min(TPW, MT - mt0);
             for (int c = 0; c < CP; c += 16) {
                 const float4 a4 = *reinterpret_cast<const float4*>(Zs + li * LDZ + c + kg * 4);
                 const float a[4] = {a4.x, a4.y, a4.z, a4.w};
                 // B[k = o][j = m] = W[m][o]; columns o >= C multiply the zero padding of dZ
                 const float* wp = Ws + (int64_t)(mt0 * 16 + li) * C + c + kg * 4;
 #pragma unroll
-                for (int t = 0; t < 8; ++t)
+                for (int t = 0; t < TPW; ++t)
                     if (t < nt) {
                         float b[4];
 #pragma unroll
@@ -220,7 +225,7 @@ __global__ __launch_bounds__(TB) void k_head(const TH* __restrict__ Hself, int64
                     }
             }
 #pragma unroll
-            for (int t = 0; t < 8; ++t)
+            for (int t = 0; t < TPW; ++t)
                 if (t < nt) {
                     const int m = (mt0 + t) * 16 + li;
 #pragma unroll
@@ -244,7 +249,7 @@ __global__ __launch_bounds__(TB) void k_head(const TH* __restrict__ Hself, int64
 #pragma unroll
             for (int s = 0; s < 4; ++s) b[s] = Zs[(kg * 4 + s) * LDZ + ct * 16 + li];
             const int col = ct * 16 + li;
-            for (int mt = wave; mt < MT; mt += 4) {
+            for (int mt = wave; mt < MT; mt += NW) {
                 floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int s = 0; s < 4; ++s) acc = mfma16(Hc[(kg * 4 + s) * LDH + mt * 16 + li], b[s], acc);
@@ -265,7 +270,7 @@ __global__ __launch_bounds__(TB) void k_head(const TH* __restrict__ Hself, int64
 
 size_t head_lds_bytes(int in, int C) {
     const size_t cp = (size_t)((C + 15) >> 4) * 16;
-    return sizeof(float) * ((size_t)HB * (2 * in + 4) + HB * (cp + 4) + 4 * HB * cp + (size_t)2 * in * C + 16);
+    return sizeof(float) * ((size_t)HB * (2 * in + 4) + HB * (cp + 4) + NW * HB * cp + (size_t)2 * in * C + 16);
 }
 
 constexpr size_t HEAD_LDS_MAX = 156 * 1024;  // of the 160 KB a gfx950 workgroup may allocate
@@ -273,7 +278,7 @@ constexpr size_t HEAD_LDS_MAX = 156 * 1024;  // of the 160 KB a gfx950 workgroup
 }  // namespace
 
 bool head_supported(int32_t in, int32_t out) {
-    return in % 8 == 0 && out <= MAXCT * 16 && head_lds_bytes(in, out) <= HEAD_LDS_MAX;
+    return in % 16 == 0 && out <= MAXCT * 16 && head_lds_bytes(in, out) <= HEAD_LDS_MAX;
 }
 
 int32_t head_splits(int32_t batch) { return ceil_div(batch, HB); }

@@ -71,7 +71,7 @@ def _view(ws, off, rows_cap, rows, cols):
 @pytest.mark.parametrize("classes", [8, 300])
 def test_gcn_train_step(classes):
     _say(f"GCN train step, {classes} classes")
-    wl = gen.Workload("gcn", "rmat", 13, 12, 64, classes, 48, 2, [8, 5], 128, 41, 1, owned_frac=0.5)
+    wl = gen.Workload("gcn", "rmat", 13, 12, 64, classes, 64, 2, [8, 5], 128, 41, 1, owned_frac=0.5)
     inst = gen.make_instance(wl)
     rng = np.random.default_rng(1)
     d = wl.dims

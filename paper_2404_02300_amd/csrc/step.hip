@@ -4,6 +4,10 @@
 // every kernel is launched for the upper bound and reads the true count.
 #include "common.h"
 
+#include <atomic>
+#include <string>
+#include <thread>
+
 namespace sdt {
 namespace {
 
@@ -78,18 +82,21 @@ struct sdt_timing {
 namespace {
 struct StageTimer {               // records begin now, end at scope exit
     sdt_timing* t;
-    int bit;
+    int bit, slot;
     hipStream_t st;
-    StageTimer(sdt_timing* tm, int kind, int layer, hipStream_t s) : t(tm), bit(kind * SDT_MAX_LAYERS + layer), st(s) {
-        if (t && t->slot >= 0 && ((t->mask >> bit) & 1)) {
-            (void)hipEventRecord(t->ev[bit][0][t->slot], st);
-            t->recorded |= 1ull << bit;
+    // `slot` is the timing slot of the step being enqueued (-1: not timed); it is passed in rather
+    // than read from the object because two host threads may be enqueueing different steps
+    StageTimer(sdt_timing* tm, int slot_, int kind, int layer, hipStream_t s)
+        : t(tm), bit(kind * SDT_MAX_LAYERS + layer), slot(slot_), st(s) {
+        if (t && slot >= 0 && ((t->mask >> bit) & 1)) {
+            (void)hipEventRecord(t->ev[bit][0][slot], st);
+            __atomic_fetch_or(&t->recorded, 1ull << bit, __ATOMIC_RELAXED);
         } else {
             t = nullptr;
         }
     }
     ~StageTimer() {
-        if (t) (void)hipEventRecord(t->ev[bit][1][t->slot], st);
+        if (t) (void)hipEventRecord(t->ev[bit][1][slot], st);
     }
 };
 }  // namespace
@@ -255,6 +262,7 @@ struct StepCtx {
     float lr;
     sdt_timing* timing;
     sdt_step_layout lay;
+    int32_t slot = -1;   // timing slot of the step being enqueued (each enqueueing thread has its own copy)
 };
 
 struct StepBuffers {
@@ -327,7 +335,7 @@ int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds
     const int32_t* dst = seeds;
     const int32_t* n_d = nullptr;
     for (int l = L - 1; l >= 0; --l) {
-        StageTimer tl(c.timing, SDT_STAGE_SAMPLE, l, st);
+        StageTimer tl(c.timing, c.slot, SDT_STAGE_SAMPLE, l, st);
         if (l == L - 1) {
             // the state check is skipped when the caller knows this workspace's previous user was an
             // earlier step of the same run (which left the map clean and the header stamped)
@@ -353,7 +361,7 @@ int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds
             if (rc != SDT_OK) return rc;
         }
         SDT_REQUIRE(lay.cap_dst[0] == 0 || aligned16(c.X), SDT_ERR_INVALID_ARG, "sdt_train_step: X must be 16-byte aligned");
-        StageTimer tm(c.timing, SDT_STAGE_AGG_FWD, 0, st);
+        StageTimer tm(c.timing, c.slot, SDT_STAGE_AGG_FWD, 0, st);
         return gcn_aggregate_fwd(&b.blk[0], static_cast<const float*>(c.X), c.ldx, true, d[0], b.gcn_c(lay, 0),
                                  b.gcn_s(lay, 0), b.gcn_self(lay, 0), static_cast<float*>(b.at(lay.A[0])), d[0], sw.map, st);
     }
@@ -361,12 +369,12 @@ int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds
     // projection's "self" operand); the neighbour mean of layer 0 is taken straight out of X.
     // Both passes hand the frontier map back clean (prefix nodes here, the rest there).
     {
-        StageTimer tm(c.timing, SDT_STAGE_GATHER, 0, st);
+        StageTimer tm(c.timing, c.slot, SDT_STAGE_GATHER, 0, st);
         rc = gather_rows(c.X, c.ldx, d[0], c.dtype, b.blk[0].src_nodes, lay.cap_dst[0], b.blk[0].counts,
                          b.at(lay.H[0]), d[0], sw.map, st);
     }
     if (rc != SDT_OK) return rc;
-    StageTimer tm(c.timing, SDT_STAGE_AGG_FWD, 0, st);
+    StageTimer tm(c.timing, c.slot, SDT_STAGE_AGG_FWD, 0, st);
     return aggregate_gather_fwd(&b.blk[0], c.X, c.ldx, d[0], c.dtype, b.at(lay.A[0]), d[0], sw.map, st);
 }
 
@@ -398,20 +406,20 @@ int32_t step_compute_gcn(const StepCtx& c, const StepBuffers& b, const int32_t* 
     auto half1 = [&](int l) { return static_cast<float*>(b.at(lay.A[l])) + d[l] / 2; };
     for (int l = 0; l < L; ++l) {
         if (l > 0) {
-            StageTimer tm(timing, SDT_STAGE_AGG_FWD, l, st);
+            StageTimer tm(timing, c.slot, SDT_STAGE_AGG_FWD, l, st);
             rc = sdt_gcn_aggregate_fwd(&b.blk[l], b.at(lay.H[l]), d[l], 0, d[l], SDT_F32, b.gcn_c(lay, l), b.gcn_s(lay, l),
                                        b.gcn_self(lay, l), b.at(lay.A[l]), d[l], st);
             if (rc != SDT_OK) return rc;
         }
         const bool last = l == L - 1;
         if (last && fused_head) break;
-        StageTimer tm(timing, SDT_STAGE_LINEAR_FWD, l, st);
+        StageTimer tm(timing, c.slot, SDT_STAGE_LINEAR_FWD, l, st);
         rc = sdt_sage_linear_fwd(half0(l), d[l], half1(l), d[l], lay.cap_dst[l], b.blk[l].counts, d[l] / 2, d[l + 1],
                                  model->W[l], model->b[l], last ? 0 : 1, SDT_F32, b.at(lay.H[l + 1]), d[l + 1], SDT_F32, st);
         if (rc != SDT_OK) return rc;
     }
     if (!fused_head) {
-        StageTimer tm(timing, SDT_STAGE_LOSS, 0, st);
+        StageTimer tm(timing, c.slot, SDT_STAGE_LOSS, 0, st);
         rc = softmax_xent(static_cast<const float*>(b.at(lay.H[L])), d[L], c.batch, d[L], c.labels, seeds,
                           static_cast<float*>(b.at(lay.dZ)), static_cast<float*>(b.at(lay.row_loss)), st);
         if (rc != SDT_OK) return rc;
@@ -427,11 +435,11 @@ int32_t step_compute_gcn(const StepCtx& c, const StepBuffers& b, const int32_t* 
         ex.W_upd = model->W[l];
         ex.b_upd = model->b[l];
         {
-            StageTimer tm(timing, SDT_STAGE_LINEAR_BWD, l, st);
+            StageTimer tm(timing, c.slot, SDT_STAGE_LINEAR_BWD, l, st);
             if (l == L - 1 && fused_head) {
                 float *P, *Q;
                 {
-                    StageTimer th(timing, SDT_STAGE_HEAD, l, st);
+                    StageTimer th(timing, c.slot, SDT_STAGE_HEAD, l, st);
                     rc = head_fwd_bwd(half0(l), d[l], half1(l), d[l], c.batch, hl, d[l + 1], model->W[l], model->b[l], SDT_F32,
                                       c.labels, seeds, static_cast<float*>(b.at(lay.H[L])), static_cast<float*>(b.at(lay.dZ)),
                                       static_cast<float*>(b.at(lay.row_loss)), dA, inner ? dA + hl : nullptr, d[l],
@@ -447,7 +455,7 @@ int32_t step_compute_gcn(const StepCtx& c, const StepBuffers& b, const int32_t* 
             if (rc != SDT_OK) return rc;
         }
         if (inner) {
-            StageTimer tm(timing, SDT_STAGE_AGG_BWD, l, st);
+            StageTimer tm(timing, c.slot, SDT_STAGE_AGG_BWD, l, st);
             rc = sdt_gcn_aggregate_bwd(&b.blk[l], dA, d[l], b.at(lay.H[l]), d[l], SDT_F32, b.gcn_c(lay, l), b.gcn_s(lay, l),
                                        b.gcn_self(lay, l), b.at(lay.dH[l]), d[l], st);
             if (rc != SDT_OK) return rc;
@@ -502,13 +510,13 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
     }
     for (int l = 0; l < L; ++l) {
         if (l > 0) {   // layer 0's mean was taken in phase 1
-            StageTimer tm(timing, SDT_STAGE_AGG_FWD, l, st);
+            StageTimer tm(timing, c.slot, SDT_STAGE_AGG_FWD, l, st);
             rc = sdt_sage_aggregate_fwd(&b.blk[l], b.at(lay.H[l]), d[l], d[l], dtype, b.at(lay.A[l]), d[l], st);
             if (rc != SDT_OK) return rc;
         }
         const bool last = l == L - 1;
         if (last && fused_head) break;
-        StageTimer tm(timing, SDT_STAGE_LINEAR_FWD, l, st);
+        StageTimer tm(timing, c.slot, SDT_STAGE_LINEAR_FWD, l, st);
         if (dtype == SDT_BF16 && bf16_mfma_fwd_ok(b.at(lay.H[l]), d[l], b.at(lay.A[l]), d[l], d[l]))
             rc = linear_fwd_bf16(b.at(lay.H[l]), d[l], b.at(lay.A[l]), d[l], lay.cap_dst[l], b.blk[l].counts, d[l],
                                  d[l + 1], wt[l], model->b[l], last ? 0 : 1, b.at(lay.H[l + 1]), d[l + 1],
@@ -520,7 +528,7 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
         if (rc != SDT_OK) return rc;
     }
     if (!fused_head) {
-        StageTimer tm(timing, SDT_STAGE_LOSS, 0, st);
+        StageTimer tm(timing, c.slot, SDT_STAGE_LOSS, 0, st);
         rc = softmax_xent(static_cast<const float*>(b.at(lay.H[L])), d[L], c.batch, d[L], c.labels, seeds,
                           static_cast<float*>(b.at(lay.dZ)), static_cast<float*>(b.at(lay.row_loss)), st);
         if (rc != SDT_OK) return rc;
@@ -532,10 +540,10 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
         float* db = model->db[l] ? model->db[l] : static_cast<float*>(b.at(lay.db[l]));
         const bool inner = l > 0;
         if (l == L - 1 && fused_head) {
-            StageTimer tm(timing, SDT_STAGE_LINEAR_BWD, l, st);
+            StageTimer tm(timing, c.slot, SDT_STAGE_LINEAR_BWD, l, st);
             float *P, *Q;
             {
-            StageTimer th(timing, SDT_STAGE_HEAD, l, st);
+            StageTimer th(timing, c.slot, SDT_STAGE_HEAD, l, st);
             rc = head_fwd_bwd(b.at(lay.H[l]), d[l], b.at(lay.A[l]), d[l], c.batch, d[l], d[l + 1], model->W[l],
                               model->b[l], dtype, c.labels, seeds, static_cast<float*>(b.at(lay.H[L])),
                               static_cast<float*>(b.at(lay.dZ)), static_cast<float*>(b.at(lay.row_loss)),
@@ -550,7 +558,7 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
             rc = reduce_partials(P, Q, head_splits(c.batch), d[l], d[l + 1], dW, db, ex, st);
             if (rc != SDT_OK) return rc;
         } else {
-            StageTimer tm(timing, SDT_STAGE_LINEAR_BWD, l, st);
+            StageTimer tm(timing, c.slot, SDT_STAGE_LINEAR_BWD, l, st);
             BwdExtras ex;
             ex.defer = &pending[n_pending++];
             ex.Wb = wb[l];
@@ -564,7 +572,7 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
         }
         if (inner) {
             // gradient w.r.t. H[l], masked by the ReLU that produced H[l]
-            StageTimer tm(timing, SDT_STAGE_AGG_BWD, l, st);
+            StageTimer tm(timing, c.slot, SDT_STAGE_AGG_BWD, l, st);
             rc = sdt_sage_aggregate_bwd(&b.blk[l], b.at(lay.dAgg[l]), d[l], b.at(lay.dSelf[l]), d[l], b.at(lay.H[l]), d[l],
                                         dtype, b.at(lay.dH[l]), d[l], st);
             if (rc != SDT_OK) return rc;
@@ -599,7 +607,7 @@ extern "C" int32_t sdt_train_step(const sdt_csr* graph, const void* X, int64_t l
     hipStream_t st = static_cast<hipStream_t>(stream);
     StepBuffers b;
     bind_buffers(c.lay, ws, ws_bytes, &b);
-    if (timing) timing->slot = timing->used < timing->max_steps ? timing->used++ : -1;
+    c.slot = timing && timing->used < timing->max_steps ? timing->used++ : -1;
     rc = step_sample(c, b, seeds, step, st);
     if (rc != SDT_OK) return rc;
     return step_compute(c, b, seeds, step, loss_d, st);
@@ -675,35 +683,84 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
     }
     rc = SDT_OK;
     const int slot0 = timing ? timing->used : 0;
-    auto timing_slot = [&](int i) {
-        if (timing) timing->slot = slot0 + i < timing->max_steps ? slot0 + i : -1;
-    };
-    for (int g0 = 0, g = 0; g0 < n_steps && rc == SDT_OK; g0 += LOOP_GROUP, ++g) {
-        const int s = g % LOOP_SLOTS, g1 = g0 + LOOP_GROUP < n_steps ? g0 + LOOP_GROUP : n_steps;
-        hipStream_t aux_st = overlap ? aux[g % n_aux] : main_st;   // sampling of consecutive groups on alternating streams
-        if (overlap && g >= LOOP_SLOTS) (void)hipStreamWaitEvent(aux_st, done[s], 0);   // the slot's buffers are free again
-        for (int i = g0; i < g1 && rc == SDT_OK; ++i) {
-            timing_slot(i);
-            rc = step_sample(c, buf[s * LOOP_GROUP + (i - g0)], seeds + (int64_t)i * batch, first_step + (uint32_t)i,
-                             aux_st, /*check_state=*/i < LOOP_BUFFERS);
-            if (!overlap && rc == SDT_OK)   // one stream: keep the order of sdt_train_step
-                rc = step_compute(c, buf[s * LOOP_GROUP + (i - g0)], seeds + (int64_t)i * batch, first_step + (uint32_t)i,
-                                  losses_d + i, main_st);
+    auto slot_of = [&](int i) { return timing && slot0 + i < timing->max_steps ? slot0 + i : -1; };
+    const int n_groups = (n_steps + LOOP_GROUP - 1) / LOOP_GROUP;
+    auto group_end = [&](int g) { return (g + 1) * LOOP_GROUP < n_steps ? (g + 1) * LOOP_GROUP : n_steps; };
+    if (!overlap) {
+        for (int i = 0; i < n_steps && rc == SDT_OK; ++i) {
+            c.slot = slot_of(i);
+            const StepBuffers& bi = buf[i % LOOP_BUFFERS];
+            rc = step_sample(c, bi, seeds + (int64_t)i * batch, first_step + (uint32_t)i, main_st, /*check_state=*/i < LOOP_BUFFERS);
+            if (rc == SDT_OK)
+                rc = step_compute(c, bi, seeds + (int64_t)i * batch, first_step + (uint32_t)i, losses_d + i, main_st);
         }
-        if (!overlap || rc != SDT_OK) continue;
-        (void)hipEventRecord(ready[s], aux_st);
-        (void)hipStreamWaitEvent(main_st, ready[s], 0);
-        for (int i = g0; i < g1 && rc == SDT_OK; ++i) {
-            timing_slot(i);
-            rc = step_compute(c, buf[s * LOOP_GROUP + (i - g0)], seeds + (int64_t)i * batch, first_step + (uint32_t)i,
-                                  losses_d + i, main_st);
+    } else {
+        // A step is about twenty launches and the host needs a few microseconds for each: one thread
+        // cannot feed the GPU fast enough when the kernels are small.  So the sampling side is
+        // enqueued by helper threads (one per auxiliary stream) and the model side by the calling thread.  A stream wait
+        // refers to the event's latest record at the time of the CALL, so each side publishes
+        // (group counters below) that it has recorded an event before the other side waits on it.
+        std::atomic<int> ready_gen[LOOP_SLOTS], done_groups{0}, failed{0};
+        for (int k = 0; k < LOOP_SLOTS; ++k) ready_gen[k].store(0);
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        int32_t aux_rc[LOOP_MAX_AUX] = {};
+        std::string aux_msg[LOOP_MAX_AUX];
+        // one helper per auxiliary stream: helper a enqueues the groups g = a, a + n_aux, ...
+        auto helper_fn = [&](int a) {
+            (void)hipSetDevice(dev);
+            StepCtx ca = c;
+            hipStream_t aux_st = aux[a];
+            for (int g = a; g < n_groups; g += n_aux) {
+                const int s = g % LOOP_SLOTS;
+                if (g >= LOOP_SLOTS) {
+                    while (done_groups.load(std::memory_order_acquire) <= g - LOOP_SLOTS && !failed.load()) std::this_thread::yield();
+                    if (failed.load()) return;
+                    (void)hipStreamWaitEvent(aux_st, done[s], 0);   // the slot's buffers are free again
+                }
+                for (int i = g * LOOP_GROUP; i < group_end(g); ++i) {
+                    ca.slot = slot_of(i);
+                    const int32_t r = step_sample(ca, buf[i % LOOP_BUFFERS], seeds + (int64_t)i * batch, first_step + (uint32_t)i,
+                                                  aux_st, /*check_state=*/i < LOOP_BUFFERS);
+                    if (r != SDT_OK) {
+                        aux_rc[a] = r;
+                        aux_msg[a] = sdt_last_error();
+                        failed.store(1);
+                        return;
+                    }
+                }
+                (void)hipEventRecord(ready[s], aux_st);
+                ready_gen[s].store(g + 1, std::memory_order_release);
+            }
+        };
+        std::thread helpers[LOOP_MAX_AUX];
+        for (int a = 0; a < n_aux; ++a) helpers[a] = std::thread(helper_fn, a);
+        for (int g = 0; g < n_groups && rc == SDT_OK; ++g) {
+            const int s = g % LOOP_SLOTS;
+            while (ready_gen[s].load(std::memory_order_acquire) != g + 1 && !failed.load()) std::this_thread::yield();
+            if (failed.load()) break;
+            (void)hipStreamWaitEvent(main_st, ready[s], 0);
+            for (int i = g * LOOP_GROUP; i < group_end(g) && rc == SDT_OK; ++i) {
+                c.slot = slot_of(i);
+                rc = step_compute(c, buf[i % LOOP_BUFFERS], seeds + (int64_t)i * batch, first_step + (uint32_t)i, losses_d + i,
+                                  main_st);
+            }
+            if (rc != SDT_OK) {
+                failed.store(1);
+                break;
+            }
+            (void)hipEventRecord(done[s], main_st);
+            done_groups.store(g + 1, std::memory_order_release);
         }
-        if (rc == SDT_OK) (void)hipEventRecord(done[s], main_st);
+        if (rc != SDT_OK) failed.store(1);
+        for (int a = 0; a < n_aux; ++a) helpers[a].join();
+        for (int a = 0; a < n_aux; ++a)
+            if (rc == SDT_OK && aux_rc[a] != SDT_OK) {
+                rc = aux_rc[a];
+                set_error("%s", aux_msg[a].c_str());
+            }
     }
-    if (timing) {
-        timing->used = slot0 + n_steps < timing->max_steps ? slot0 + n_steps : timing->max_steps;
-        timing->slot = -1;
-    }
+    if (timing) timing->used = slot0 + n_steps < timing->max_steps ? slot0 + n_steps : timing->max_steps;
     // every phase 1 was waited for by a phase 2 on the main stream, so synchronising the
     // main stream covers the auxiliary one; the events may be released now (pending work keeps
     // what it needs)

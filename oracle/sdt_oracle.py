@@ -417,3 +417,60 @@ def adam(w, g, m, v, t: int, lr: float, beta1: float = 0.9, beta2: float = 0.999
     mhat = m / (1.0 - beta1 ** t)
     vhat = v / (1.0 - beta2 ** t)
     return w - lr * mhat / (np.sqrt(vhat) + eps), m, v
+
+
+# ------------------------------------------------------------------ GAT attention aggregation (Sec. III-E: GAT is one of the integrated models)
+def _leaky(x, slope):
+    return np.where(x > 0, x, slope * x)
+
+
+def gat_aggregate_fwd(b_indptr, b_cols, z, a_src, a_dst, slope: float = 0.2):
+    """Single-head graph attention over a sampled block (Velickovic et al.), on already projected
+    features z [n_src, F] (row i < n_dst is destination i itself):
+        s_(i<-j) = LeakyReLU(a_dst . z_i + a_src . z_j),   j over row i's edges and j = i (a self edge,
+        so that no softmax is empty), alpha = softmax over that set, out_i = sum alpha_(i<-j) z_j.
+    Returns (out [n_dst, F], alpha per edge [nnz], alpha of the self edge [n_dst]).  float64.
+    (The paper does not describe its GAT variant; one head, slope 0.2 and the self edge are this
+    build's reading.)"""
+    ip = np.asarray(b_indptr, dtype=np.int64)
+    cols = np.asarray(b_cols, dtype=np.int64)
+    z = np.asarray(z, dtype=np.float64)
+    a_src, a_dst = np.asarray(a_src, dtype=np.float64), np.asarray(a_dst, dtype=np.float64)
+    n_dst = len(ip) - 1
+    el, er = z @ a_src, z[:n_dst] @ a_dst
+    out = np.zeros((n_dst, z.shape[1]))
+    alpha, alpha_self = np.zeros(len(cols)), np.zeros(n_dst)
+    for i in range(n_dst):
+        c = cols[ip[i]:ip[i + 1]]
+        s = _leaky(er[i] + np.concatenate([el[c], el[i:i + 1]]), slope)
+        p = np.exp(s - s.max())
+        a = p / p.sum()
+        alpha[ip[i]:ip[i + 1]], alpha_self[i] = a[:-1], a[-1]
+        out[i] = a[:-1] @ z[c] + a[-1] * z[i]
+    return out, alpha, alpha_self
+
+
+def gat_aggregate_bwd(b_indptr, b_cols, z, a_src, a_dst, g, slope: float = 0.2):
+    """Gradients of gat_aggregate_fwd's output w.r.t. z, a_src, a_dst given g = d loss / d out [n_dst, F]."""
+    ip = np.asarray(b_indptr, dtype=np.int64)
+    cols = np.asarray(b_cols, dtype=np.int64)
+    z, g = np.asarray(z, dtype=np.float64), np.asarray(g, dtype=np.float64)
+    a_src, a_dst = np.asarray(a_src, dtype=np.float64), np.asarray(a_dst, dtype=np.float64)
+    n_dst = len(ip) - 1
+    _, alpha, alpha_self = gat_aggregate_fwd(ip, cols, z, a_src, a_dst, slope)
+    el, er = z @ a_src, z[:n_dst] @ a_dst
+    dz = np.zeros_like(z)
+    d_el, d_er = np.zeros(z.shape[0]), np.zeros(n_dst)
+    for i in range(n_dst):
+        c = np.concatenate([cols[ip[i]:ip[i + 1]], [i]])
+        a = np.concatenate([alpha[ip[i]:ip[i + 1]], alpha_self[i:i + 1]])
+        d_alpha = z[c] @ g[i]                          # d out_i / d alpha_e = z_col
+        np.add.at(dz, c, a[:, None] * g[i][None, :])   # through the weighted sum
+        d_s = a * (d_alpha - a @ d_alpha)              # softmax
+        pre = er[i] + el[c]
+        d_pre = d_s * np.where(pre > 0, 1.0, slope)    # LeakyReLU
+        d_er[i] = d_pre.sum()
+        np.add.at(d_el, c, d_pre)
+    dz += d_el[:, None] * a_src[None, :]
+    dz[:n_dst] += d_er[:, None] * a_dst[None, :]
+    return dz, z.T @ d_el, z[:n_dst].T @ d_er

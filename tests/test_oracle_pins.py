@@ -558,3 +558,39 @@ def test_adam_matches_library_optimiser():
     # first update from zero moments: a step of lr * sign(g) (up to eps)
     w1, _, _ = orc.adam(np.zeros(4), np.array([2.0, -3.0, 0.5, -1e-3]), np.zeros(4), np.zeros(4), 1, 0.1)
     assert np.allclose(w1, [-0.1, 0.1, -0.1, 0.1], rtol=1e-4)
+
+
+# ----------------------------------------------------------------- GAT attention aggregation
+def test_gat_aggregate_matches_autograd_and_closed_forms():
+    rng = np.random.default_rng(41)
+    n, F = 60, 6
+    rows, indptr, indices = _small_graph(rng, n, 7)
+    dst = rng.choice(n, size=15, replace=False).astype(np.int32)
+    blk = orc.sample_block(indptr, indices, dst, 4, 2, 0, 1)
+    z = rng.standard_normal((blk.n_src, F))
+    a_src, a_dst = rng.standard_normal(F), rng.standard_normal(F)
+    g = rng.standard_normal((blk.n_dst, F))
+    out, alpha, alpha_self = orc.gat_aggregate_fwd(blk.indptr, blk.cols, z, a_src, a_dst)
+    # every row's attention (edges + self edge) sums to one
+    for i in range(blk.n_dst):
+        assert abs(alpha[blk.indptr[i]:blk.indptr[i + 1]].sum() + alpha_self[i] - 1.0) < 1e-14
+    # zero attention vectors: uniform attention = plain mean over the neighbours and the node itself
+    out0, _, _ = orc.gat_aggregate_fwd(blk.indptr, blk.cols, z, 0 * a_src, 0 * a_dst)
+    for i in range(blk.n_dst):
+        c = list(blk.cols[blk.indptr[i]:blk.indptr[i + 1]]) + [i]
+        assert np.allclose(out0[i], z[c].mean(axis=0))
+    # independent formulation in torch (float64) with autograd
+    zt = torch.tensor(z, requires_grad=True)
+    at, bt = torch.tensor(a_src, requires_grad=True), torch.tensor(a_dst, requires_grad=True)
+    outs = []
+    for i in range(blk.n_dst):
+        c = torch.tensor(list(blk.cols[blk.indptr[i]:blk.indptr[i + 1]]) + [i], dtype=torch.long)
+        s = torch.nn.functional.leaky_relu(zt[i] @ bt + zt[c] @ at, 0.2)
+        outs.append(torch.softmax(s, 0) @ zt[c])
+    ot = torch.stack(outs)
+    assert np.allclose(out, ot.detach().numpy(), rtol=1e-12, atol=1e-13)
+    (ot * torch.tensor(g)).sum().backward()
+    dz, da_src, da_dst = orc.gat_aggregate_bwd(blk.indptr, blk.cols, z, a_src, a_dst, g)
+    assert np.allclose(dz, zt.grad.numpy(), rtol=1e-10, atol=1e-12)
+    assert np.allclose(da_src, at.grad.numpy(), rtol=1e-10, atol=1e-12)
+    assert np.allclose(da_dst, bt.grad.numpy(), rtol=1e-10, atol=1e-12)

@@ -230,6 +230,26 @@ int32_t sdt_gcn_aggregate_bwd(const sdt_block *blk /*host struct*/, const void *
                               int32_t F, int32_t dtype, const float *c, const float *s, const float *selfw, void *dH,
                               int64_t ldd, void *stream);
 
+/* ---- GAT attention aggregation on a sampled block (Sec. III-E: GAT is one of the
+ * integrated models; the variant is not described: one head, LeakyReLU slope argument,
+ * and a self edge so that no softmax is empty) ----------------------------------------
+ * z is the already projected feature matrix, fp32 [n_src, F] (row i < n_dst is
+ * destination i itself); a_src, a_dst are fp32 [F].
+ *   s_(i<-j) = LeakyReLU(a_dst . z_i + a_src . z_j) over row i's edges and j = i,
+ *   alpha = softmax over that set, out[i,:] = sum alpha_(i<-j) z[j,:]          (forward)
+ * The backward takes g = d loss / d out [n_dst, F] and writes dz [n_src, F] (overwritten),
+ * da_src [F], da_dst [F]; it needs the transposed block and the SAME workspace, untouched,
+ * that the matching forward call used (the forward leaves z a_src, z a_dst and each row's
+ * log-sum-exp there).  Deterministic: no atomics, fixed summation orders. */
+size_t sdt_gat_workspace_bytes(int32_t cap_src, int32_t cap_dst, int32_t F);
+int32_t sdt_gat_aggregate_fwd(const sdt_block *blk /*host struct*/, const float *z, int64_t ldz, int32_t F,
+                              const float *a_src, const float *a_dst, float slope, float *out, int64_t ldo, void *ws,
+                              size_t ws_bytes, void *stream);
+int32_t sdt_gat_aggregate_bwd(const sdt_block *blk /*host struct*/, const float *z, int64_t ldz, int32_t F,
+                              const float *a_src, const float *a_dst, float slope, const float *g, int64_t ldg,
+                              float *dz, int64_t lddz, float *da_src, float *da_dst, void *ws, size_t ws_bytes,
+                              void *stream);
+
 /* ---- GraphSAGE projection (Sec. III-E / IV-A: GraphSAGE is the model trained)
  * Y = act(Hself W[0:in,:] + A W[in:2in,:] + b), act = ReLU if relu else id.
  * Hself, A are `dtype`; W, b fp32 (rounded to bf16 as MFMA operands when

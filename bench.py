@@ -157,7 +157,7 @@ def main():
 
     # ---- the timed region: exactly K steps between two synchronisations; only the dominant
     # stage is bracketed by HIP events (on the stream its kernels are launched on)
-    tim = sdt.Timing(K, [dominant])
+    tim = sdt.Timing(K, [dominant], stride=8)    # every 8th launch: an event record costs the stream microseconds
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     run_loop(Wm, K, tim)

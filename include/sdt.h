@@ -309,6 +309,10 @@ enum {
 int32_t sdt_timing_create(int32_t max_steps, uint64_t stage_mask, sdt_timing **out /*host*/);
 void sdt_timing_destroy(sdt_timing *t);
 void sdt_timing_reset(sdt_timing *t);
+/* Time only every stride-th step (default 1: all).  An event record costs the stream a few
+ * microseconds, which matters when a whole step takes under a hundred.  Call before the first
+ * timed step or right after a reset. */
+int32_t sdt_timing_set_stride(sdt_timing *t, int32_t stride);
 int32_t sdt_timing_read(sdt_timing *t, int32_t kind, int32_t layer, float *ms_out /*host*/, int32_t *n_out /*host*/);
 
 int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const int32_t *fanouts /*host*/,

@@ -106,6 +106,7 @@ EXPORTS = {
     "sdt_timing_create": (_i32, [_i32, _u64, _vp]),
     "sdt_timing_destroy": (None, [_vp]),
     "sdt_timing_reset": (None, [_vp]),
+    "sdt_timing_set_stride": (_i32, [_vp, _i32]),
     "sdt_timing_read": (_i32, [_vp, _i32, _i32, _vp, _vp]),
 }
 
@@ -454,6 +455,10 @@ def sdt_timing_reset(handle):
     lib().sdt_timing_reset(handle)
 
 
+def sdt_timing_set_stride(handle, stride: int):
+    _check(lib().sdt_timing_set_stride(handle, stride))
+
+
 def sdt_timing_read(handle, kind: int, layer: int, max_steps: int) -> List[float]:
     buf = (ctypes.c_float * max_steps)()
     n = _i32(0)
@@ -464,12 +469,14 @@ def sdt_timing_read(handle, kind: int, layer: int, max_steps: int) -> List[float
 class Timing:
     """Owner of an sdt_timing object: HIP events around selected (stage, layer) pairs."""
 
-    def __init__(self, max_steps: int, stages: Sequence):
+    def __init__(self, max_steps: int, stages: Sequence, stride: int = 1):
         mask = 0
         for kind, layer in stages:
             mask |= 1 << (STAGES[kind] * SDT_MAX_LAYERS + layer)
         self.max_steps = max_steps
         self.handle = sdt_timing_create(max_steps, mask)
+        if stride != 1:
+            sdt_timing_set_stride(self.handle, stride)
 
     def reset(self):
         sdt_timing_reset(self.handle)

@@ -73,6 +73,8 @@ using namespace sdt;
 struct sdt_timing {
     int32_t max_steps;
     uint64_t mask;
+    int32_t stride;               // every stride-th step is timed (1 = all)
+    int32_t seen;                 // steps observed so far
     int32_t used;                 // slots consumed so far
     int32_t slot;                 // slot of the step being recorded, -1 = none
     uint64_t recorded;            // stages that were bracketed at least once since the last reset
@@ -106,6 +108,8 @@ extern "C" int32_t sdt_timing_create(int32_t max_steps, uint64_t stage_mask, sdt
     sdt_timing* t = new sdt_timing();
     t->max_steps = max_steps;
     t->mask = stage_mask;
+    t->stride = 1;
+    t->seen = 0;
     t->used = 0;
     t->slot = -1;
     t->recorded = 0;
@@ -136,7 +140,14 @@ extern "C" void sdt_timing_destroy(sdt_timing* t) {
 }
 
 extern "C" void sdt_timing_reset(sdt_timing* t) {
-    if (t) { t->used = 0; t->slot = -1; t->recorded = 0; }
+    if (t) { t->seen = 0; t->used = 0; t->slot = -1; t->recorded = 0; }
+}
+
+extern "C" int32_t sdt_timing_set_stride(sdt_timing* t, int32_t stride) {
+    SDT_REQUIRE(t && stride >= 1, SDT_ERR_INVALID_ARG, "sdt_timing_set_stride: null object or stride < 1");
+    SDT_REQUIRE(t->seen == 0, SDT_ERR_INVALID_ARG, "sdt_timing_set_stride: set the stride before the first timed step (or after a reset)");
+    t->stride = stride;
+    return SDT_OK;
 }
 
 extern "C" int32_t sdt_timing_read(sdt_timing* t, int32_t kind, int32_t layer, float* ms_out, int32_t* n_out) {
@@ -607,7 +618,11 @@ extern "C" int32_t sdt_train_step(const sdt_csr* graph, const void* X, int64_t l
     hipStream_t st = static_cast<hipStream_t>(stream);
     StepBuffers b;
     bind_buffers(c.lay, ws, ws_bytes, &b);
-    c.slot = timing && timing->used < timing->max_steps ? timing->used++ : -1;
+    c.slot = -1;
+    if (timing) {
+        if (timing->seen % timing->stride == 0 && timing->used < timing->max_steps) c.slot = timing->used++;
+        ++timing->seen;
+    }
     rc = step_sample(c, b, seeds, step, st);
     if (rc != SDT_OK) return rc;
     return step_compute(c, b, seeds, step, loss_d, st);
@@ -682,8 +697,15 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
         for (int k = 0; k < n_aux; ++k) (void)hipStreamWaitEvent(aux[k], fork, 0);
     }
     rc = SDT_OK;
-    const int slot0 = timing ? timing->used : 0;
-    auto slot_of = [&](int i) { return timing && slot0 + i < timing->max_steps ? slot0 + i : -1; };
+    // step i of this call is timed if it is a multiple of the stride among all steps the object has seen
+    const int seen0 = timing ? timing->seen : 0, stride = timing ? timing->stride : 1;
+    const int used0 = timing ? timing->used : 0;
+    const int first_timed = (stride - seen0 % stride) % stride;   // first i with (seen0 + i) % stride == 0
+    auto slot_of = [&](int i) {
+        if (!timing || i < first_timed || (i - first_timed) % stride != 0) return -1;
+        const int sl = used0 + (i - first_timed) / stride;
+        return sl < timing->max_steps ? sl : -1;
+    };
     const int n_groups = (n_steps + LOOP_GROUP - 1) / LOOP_GROUP;
     auto group_end = [&](int g) { return (g + 1) * LOOP_GROUP < n_steps ? (g + 1) * LOOP_GROUP : n_steps; };
     if (!overlap) {
@@ -760,7 +782,11 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
                 set_error("%s", aux_msg[a].c_str());
             }
     }
-    if (timing) timing->used = slot0 + n_steps < timing->max_steps ? slot0 + n_steps : timing->max_steps;
+    if (timing) {
+        const int timed = n_steps > first_timed ? (n_steps - first_timed + stride - 1) / stride : 0;
+        timing->used = used0 + timed < timing->max_steps ? used0 + timed : timing->max_steps;
+        timing->seen = seen0 + n_steps;
+    }
     // every phase 1 was waited for by a phase 2 on the main stream, so synchronising the
     // main stream covers the auxiliary one; the events may be released now (pending work keeps
     // what it needs)

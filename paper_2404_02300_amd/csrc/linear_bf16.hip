@@ -498,8 +498,8 @@ int32_t convert_weights_bf16(const sdt_model* model, void* base, hipStream_t st)
 }
 
 namespace {
-using TF = TileB<64, 128, 64, 2, 2>;
-using TI = TileB<64, 128, 64, 2, 2>;
+using TF = TileB<64, 128, 32, 2, 2>;
+using TI = TileB<64, 128, 32, 2, 2>;
 }  // namespace
 
 int32_t linear_fwd_bf16(const void* Hself, int64_t ldh, const void* A, int64_t lda, int32_t n_cap, const int32_t* n_d,

@@ -164,6 +164,7 @@ struct Tile {
     static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     static constexpr int LDA_OC = BM + 4, LDB_OC = BN + 4;
     static constexpr int LD_KC = BK + 4;
+    static constexpr int NS = 2;  // register stages of the global-load prefetch (four were measured: no faster)
     static_assert(TM >= 1 && TN >= 1 && BK % 8 == 0, "tile shape");
 };
 
@@ -172,47 +173,51 @@ __device__ __forceinline__ void zero_acc(floatx16& a) {
     for (int r = 0; r < 16; ++r) a[r] = 0.f;
 }
 
-// Software-pipelined reduction loop shared by the three products.  Global loads run two
-// steps ahead of the MFMAs (two register stages), LDS is double-buffered, and one barrier
-// per step suffices: a buffer is rewritten only after the barrier of the step in between,
-// which every wave passes after it has finished reading that buffer.
+// Software-pipelined reduction loop shared by the three products.  Global loads run NS steps
+// ahead of the MFMAs (NS register stages), LDS is double-buffered, and one barrier per step
+// suffices: a buffer is rewritten only after the barrier of the step in between, which every
+// wave passes after it has finished reading that buffer.
 //   fetch(it, sa, sb)  issues the global loads of step `it` into a register stage; for it >= nit
 //                      it must still be callable (Stage::load clamps addresses and yields zeros)
 //   hook(Bs)           optional extra work on the staged B tile (bias gradient)
-// Nothing in the loop is conditional: the step count is rounded up to even (a surplus step
-// multiplies zero tiles) and the two fetches past the end re-read valid addresses and are
-// dropped.  Every path then has the same number of loads in flight at every wait, which lets
-// the compiler wait for the older register stage only (vmcnt = loads of the younger one).
+// No load is conditional: the fetches past the end re-read valid addresses and are dropped.
+// Every path then has the same number of loads in flight at every wait, which lets the compiler
+// wait for the oldest register stage only (vmcnt = loads of the younger ones).
 // Requires nit >= 1.
 template <typename TL, bool A_KC, bool B_KC, typename SA, typename SB, typename Fetch, typename Hook>
 __device__ __forceinline__ void gemm_mainloop(int nit, float* As, float* Bs, Fetch&& fetch, Hook&& hook,
                                               floatx16 (&acc)[TL::TM][TL::TN]) {
-    constexpr int BK = TL::BK;
+    constexpr int BK = TL::BK, NS = TL::NS;
+    static_assert(NS % 2 == 0, "the LDS buffer of a stage is its index modulo two");
     constexpr int LDA = A_KC ? TL::LD_KC : TL::LDA_OC, LDB = B_KC ? TL::LD_KC : TL::LDB_OC;
     constexpr int A_ELEMS = (A_KC ? TL::BM : BK) * LDA, B_ELEMS = (B_KC ? TL::BN : BK) * LDB;
     const int wave = threadIdx.x >> 6, wm = wave / TL::WN, wn = wave % TL::WN;
     const int a0 = wm * (TL::BM / TL::WM), b0 = wn * (TL::BN / TL::WN);
-    SA sa0, sa1;
-    SB sb0, sb1;
-    fetch(0, sa0, sb0);
-    __builtin_amdgcn_sched_barrier(0);  // issue order = consumption order (the load counter is in-order)
-    fetch(1, sa1, sb1);
-    __builtin_amdgcn_sched_barrier(0);
-    for (int it = 0; it < nit; it += 2) {
-        sa0.template store<LDA>(As);
-        sb0.template store<LDB>(Bs);
-        __syncthreads();
-        fetch(it + 2, sa0, sb0);
-        __builtin_amdgcn_sched_barrier(0);  // keep the loads here: the scheduler would sink them next to their use
-        hook(Bs);
-        mma_step<BK, TL::TM, TL::TN, A_KC, B_KC, TL::LDA_OC, TL::LDB_OC>(As, Bs, a0, b0, acc);
-        sa1.template store<LDA>(As + A_ELEMS);
-        sb1.template store<LDB>(Bs + B_ELEMS);
-        __syncthreads();
-        fetch(it + 3, sa1, sb1);
-        __builtin_amdgcn_sched_barrier(0);
-        hook(Bs + B_ELEMS);
-        mma_step<BK, TL::TM, TL::TN, A_KC, B_KC, TL::LDA_OC, TL::LDB_OC>(As + A_ELEMS, Bs + B_ELEMS, a0, b0, acc);
+    SA sa[NS];
+    SB sb[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        fetch(s, sa[s], sb[s]);
+        __builtin_amdgcn_sched_barrier(0);  // issue order = consumption order (the load counter is in-order)
+    }
+    for (int it = 0; it < nit; it += NS) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            float* Ab = As + (s & 1) * A_ELEMS;
+            float* Bb = Bs + (s & 1) * B_ELEMS;
+            const bool live = s == 0 || it + s < nit;   // the step count need not be a multiple of NS
+            if (live) {
+                sa[s].template store<LDA>(Ab);
+                sb[s].template store<LDB>(Bb);
+                __syncthreads();
+            }
+            fetch(it + s + NS, sa[s], sb[s]);
+            __builtin_amdgcn_sched_barrier(0);  // keep the loads here: the scheduler would sink them next to their use
+            if (live) {
+                hook(Bb);
+                mma_step<BK, TL::TM, TL::TN, A_KC, B_KC, TL::LDA_OC, TL::LDB_OC>(Ab, Bb, a0, b0, acc);
+            }
+        }
     }
 }
 

@@ -498,24 +498,32 @@ int32_t convert_weights_bf16(const sdt_model* model, void* base, hipStream_t st)
 }
 
 namespace {
-using TF = TileB<64, 128, 32, 2, 2>;
-using TI = TileB<64, 128, 32, 2, 2>;
+// Many rows: 32-deep steps keep more workgroups resident (the kernels are bound by streaming the
+// activations).  Few rows: every workgroup is one short dependent chain, and 64-deep steps halve it.
+using TFbig = TileB<64, 128, 32, 2, 2>;
+using TFsmall = TileB<64, 128, 64, 2, 2>;
+constexpr int32_t SMALL_ROWS = 16384;
 }  // namespace
 
 int32_t linear_fwd_bf16(const void* Hself, int64_t ldh, const void* A, int64_t lda, int32_t n_cap, const int32_t* n_d,
                         int32_t in, int32_t out, const void* Wt, const float* bias, int32_t relu, void* Y, int64_t ldy,
                         int32_t y_dtype, hipStream_t st) {
     if (n_cap == 0) return SDT_OK;
-    dim3 grid(ceil_div(out, TF::BN), ceil_div(n_cap, TF::BM));
     const uint16_t* h = static_cast<const uint16_t*>(Hself);
     const uint16_t* a = static_cast<const uint16_t*>(A);
     const uint16_t* w = static_cast<const uint16_t*>(Wt);
-    if (y_dtype == SDT_BF16)
-        hipLaunchKernelGGL((k_fwd_bf16<bf16_t, TF>), grid, dim3(TF::NT), 0, st, h, ldh, a, lda, n_cap, n_d, in, out, w, bias,
-                           relu, static_cast<bf16_t*>(Y), ldy);
-    else
-        hipLaunchKernelGGL((k_fwd_bf16<float, TF>), grid, dim3(TF::NT), 0, st, h, ldh, a, lda, n_cap, n_d, in, out, w, bias,
-                           relu, static_cast<float*>(Y), ldy);
+    auto go = [&](auto tile) {
+        using TF = decltype(tile);
+        dim3 grid(ceil_div(out, TF::BN), ceil_div(n_cap, TF::BM));
+        if (y_dtype == SDT_BF16)
+            hipLaunchKernelGGL((k_fwd_bf16<bf16_t, TF>), grid, dim3(TF::NT), 0, st, h, ldh, a, lda, n_cap, n_d, in, out, w,
+                               bias, relu, static_cast<bf16_t*>(Y), ldy);
+        else
+            hipLaunchKernelGGL((k_fwd_bf16<float, TF>), grid, dim3(TF::NT), 0, st, h, ldh, a, lda, n_cap, n_d, in, out, w,
+                               bias, relu, static_cast<float*>(Y), ldy);
+    };
+    if (n_cap >= SMALL_ROWS) go(TFbig{});
+    else go(TFsmall{});
     SDT_CHECK_LAUNCH("linear_fwd_bf16");
     return SDT_OK;
 }
@@ -557,15 +565,20 @@ int32_t linear_bwd_input_bf16(const void* dY, int64_t lddy, int32_t dy_dtype, in
                               int32_t in, int32_t out, const void* Wb, void* dSelf, void* dAgg, int64_t ldi,
                               hipStream_t st) {
     if (n_cap == 0) return SDT_OK;
-    dim3 grid(ceil_div(in, TI::BN), ceil_div(n_cap, TI::BM), 2);
     const uint16_t* w = static_cast<const uint16_t*>(Wb);
     const int64_t ldb = bf16_ldb(out);
-    if (dy_dtype == SDT_BF16)
-        hipLaunchKernelGGL((k_bwd_input_bf16<uint16_t, TI>), grid, dim3(TI::NT), 0, st, static_cast<const uint16_t*>(dY),
-                           lddy, n_cap, n_d, in, out, w, ldb, static_cast<bf16_t*>(dSelf), static_cast<bf16_t*>(dAgg), ldi);
-    else
-        hipLaunchKernelGGL((k_bwd_input_bf16<float, TI>), grid, dim3(TI::NT), 0, st, static_cast<const float*>(dY), lddy,
-                           n_cap, n_d, in, out, w, ldb, static_cast<bf16_t*>(dSelf), static_cast<bf16_t*>(dAgg), ldi);
+    auto go = [&](auto tile) {
+        using TI = decltype(tile);
+        dim3 grid(ceil_div(in, TI::BN), ceil_div(n_cap, TI::BM), 2);
+        if (dy_dtype == SDT_BF16)
+            hipLaunchKernelGGL((k_bwd_input_bf16<uint16_t, TI>), grid, dim3(TI::NT), 0, st, static_cast<const uint16_t*>(dY),
+                               lddy, n_cap, n_d, in, out, w, ldb, static_cast<bf16_t*>(dSelf), static_cast<bf16_t*>(dAgg), ldi);
+        else
+            hipLaunchKernelGGL((k_bwd_input_bf16<float, TI>), grid, dim3(TI::NT), 0, st, static_cast<const float*>(dY), lddy,
+                               n_cap, n_d, in, out, w, ldb, static_cast<bf16_t*>(dSelf), static_cast<bf16_t*>(dAgg), ldi);
+    };
+    if (n_cap >= SMALL_ROWS) go(TFbig{});
+    else go(TFsmall{});
     SDT_CHECK_LAUNCH("linear_bwd_input_bf16");
     return SDT_OK;
 }

@@ -474,3 +474,50 @@ def gat_aggregate_bwd(b_indptr, b_cols, z, a_src, a_dst, g, slope: float = 0.2):
     dz += d_el[:, None] * a_src[None, :]
     dz[:n_dst] += d_er[:, None] * a_dst[None, :]
     return dz, z.T @ d_el, z[:n_dst].T @ d_er
+
+
+def gat_train_step(indptr, indices, X, y, seeds, fanouts, W, b, att, seed: int, step: int, lr: float,
+                   slope: float = 0.2, blocks: Optional[List[Block]] = None, relu_masks=None):
+    """One mini-batch step of a single-head GAT (Sec. III-E names GAT as an integrated model and
+    Sec. III-C as the most expensive one; the variant is not described).  Layer l projects EVERY
+    frontier row, z = H_l W_l (W_l [in_l, out_l], no bias inside the attention), aggregates with
+    gat_aggregate_fwd using att[l] = [a_src | a_dst] (2 out_l values), adds b_l and applies ReLU on
+    all but the last layer; sampling, loss and SGD as in train_step.  fp32 storage only."""
+    L = len(fanouts)
+    if blocks is None:
+        blocks = sample_blocks(indptr, indices, seeds, fanouts, seed, step)
+    H = [gather_rows(X, blocks[0].src_nodes).astype(np.float64)]
+    W = [np.asarray(w, dtype=np.float64) for w in W]
+    b = [np.asarray(v, dtype=np.float64) for v in b]
+    att = [np.asarray(v, dtype=np.float64) for v in att]
+    Z = []
+    for l, blk in enumerate(blocks):
+        F = W[l].shape[1]
+        z = H[l] @ W[l]
+        out, _, _ = gat_aggregate_fwd(blk.indptr, blk.cols, z, att[l][:F], att[l][F:], slope)
+        pre = out + b[l]
+        Z.append(z)
+        H.append(np.maximum(pre, 0.0) if l < L - 1 else pre)
+    loss, dZ = softmax_xent(H[L], np.asarray(y)[np.asarray(seeds)])
+    dW, db, datt, dz, dHs = [None] * L, [None] * L, [None] * L, [None] * L, [None] * L
+    g = dZ
+    for l in range(L - 1, -1, -1):
+        blk = blocks[l]
+        F = W[l].shape[1]
+        if l < L - 1:
+            keep = H[l + 1] > 0
+            if relu_masks is not None and relu_masks[l] is not None:
+                keep = np.asarray(relu_masks[l], dtype=bool)
+            g = g * keep
+        db[l] = g.sum(axis=0)
+        dz[l], da_src, da_dst = gat_aggregate_bwd(blk.indptr, blk.cols, Z[l], att[l][:F], att[l][F:], g, slope)
+        datt[l] = np.concatenate([da_src, da_dst])
+        dW[l] = H[l].T @ dz[l]
+        if l > 0:
+            g = dz[l] @ W[l].T
+            dHs[l] = g
+    W_new = [sgd(W[l], dW[l], lr) for l in range(L)]
+    b_new = [sgd(b[l], db[l], lr) for l in range(L)]
+    att_new = [sgd(att[l], datt[l], lr) for l in range(L)]
+    return dict(blocks=blocks, H=H, Z=Z, logits=H[L], loss=loss, dZ=dZ, W=W, W_new=W_new, b_new=b_new, att_new=att_new,
+                dW=dW, db=db, datt=datt, dz=dz, dH=dHs)

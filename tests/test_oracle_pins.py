@@ -594,3 +594,57 @@ def test_gat_aggregate_matches_autograd_and_closed_forms():
     assert np.allclose(dz, zt.grad.numpy(), rtol=1e-10, atol=1e-12)
     assert np.allclose(da_src, at.grad.numpy(), rtol=1e-10, atol=1e-12)
     assert np.allclose(da_dst, bt.grad.numpy(), rtol=1e-10, atol=1e-12)
+
+
+def test_gat_step_gradients_match_autograd_and_central_differences():
+    rng = np.random.default_rng(43)
+    n, dims = 40, [5, 6, 3]
+    rows, indptr, indices = _small_graph(rng, n, 5)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    y = rng.integers(0, dims[2], size=n).astype(np.int32)
+    W = [rng.standard_normal((dims[l], dims[l + 1])) * 0.5 for l in range(2)]
+    b = [rng.standard_normal(dims[l + 1]) * 0.2 for l in range(2)]
+    att = [rng.standard_normal(2 * dims[l + 1]) * 0.6 for l in range(2)]
+    seeds = np.array([2, 7, 19, 31, 11, 0], dtype=np.int32)
+    ref = orc.gat_train_step(indptr, indices, X, y, seeds, [3, 2], W, b, att, seed=4, step=2, lr=0.05)
+    blocks = ref["blocks"]
+
+    def model(Wt, bt, at):   # the same model row by row in torch (float64)
+        H = torch.tensor(X[blocks[0].src_nodes].astype(np.float64))
+        for l, blk in enumerate(blocks):
+            F = dims[l + 1]
+            z = H @ Wt[l]
+            outs = []
+            for i in range(blk.n_dst):
+                c = torch.tensor(list(blk.cols[blk.indptr[i]:blk.indptr[i + 1]]) + [i], dtype=torch.long)
+                s = torch.nn.functional.leaky_relu(z[i] @ at[l][F:] + z[c] @ at[l][:F], 0.2)
+                outs.append(torch.softmax(s, 0) @ z[c])
+            pre = torch.stack(outs) + bt[l]
+            H = torch.relu(pre) if l == 0 else pre
+        return torch.nn.functional.cross_entropy(H, torch.tensor(y[seeds].astype(np.int64)))
+
+    Wt = [torch.tensor(w, dtype=torch.float64, requires_grad=True) for w in W]
+    bt = [torch.tensor(v, dtype=torch.float64, requires_grad=True) for v in b]
+    at = [torch.tensor(v, dtype=torch.float64, requires_grad=True) for v in att]
+    loss = model(Wt, bt, at)
+    loss.backward()
+    assert abs(loss.item() - ref["loss"]) < 1e-12
+    for l in range(2):
+        assert np.allclose(ref["dW"][l], Wt[l].grad.numpy(), rtol=1e-10, atol=1e-12)
+        assert np.allclose(ref["db"][l], bt[l].grad.numpy(), rtol=1e-10, atol=1e-12)
+        assert np.allclose(ref["datt"][l], at[l].grad.numpy(), rtol=1e-10, atol=1e-12)
+        assert np.allclose(ref["att_new"][l], att[l] - 0.05 * at[l].grad.numpy(), rtol=1e-12, atol=1e-13)
+        assert np.allclose(ref["W_new"][l], W[l] - 0.05 * Wt[l].grad.numpy(), rtol=1e-12, atol=1e-13)
+    # central differences of the oracle's own loss on a few coordinates of every parameter
+    h = 1e-6
+    for l in range(2):
+        for P, G in ((W, ref["dW"]), (b, ref["db"]), (att, ref["datt"])):
+            flat, g = P[l].reshape(-1), G[l].reshape(-1)
+            for idx in range(0, flat.size, max(1, flat.size // 5)):
+                keep = flat[idx]
+                flat[idx] = keep + h
+                lp = orc.gat_train_step(indptr, indices, X, y, seeds, [3, 2], W, b, att, 4, 2, 0.0, blocks=blocks)["loss"]
+                flat[idx] = keep - h
+                lm = orc.gat_train_step(indptr, indices, X, y, seeds, [3, 2], W, b, att, 4, 2, 0.0, blocks=blocks)["loss"]
+                flat[idx] = keep
+                assert abs((lp - lm) / (2 * h) - g[idx]) <= 1e-6 * max(1.0, abs(g[idx])) + 1e-8, (l, idx)

@@ -47,8 +47,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="products",
                     choices=["tiny", "products", "dense", "sparse_bf16", "fullgraph"])
-    ap.add_argument("--model", default="sage", choices=["sage", "gcn"],
-                    help="gcn: the same step with the GCN model kind (fp32 workloads; not the headline metric)")
+    ap.add_argument("--model", default="sage", choices=["sage", "gcn", "gat"],
+                    help="gcn / gat: the same step with the GCN or GAT model kind (fp32 workloads; not the headline metric)")
     ap.add_argument("--lr", type=float, default=0.01)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial", action="store_true", help="no auxiliary stream: every step strictly in sequence")
@@ -92,17 +92,24 @@ def main():
     else:
         X = torch.from_numpy(inst.X).cuda()
     y = torch.from_numpy(inst.y).cuda()
-    gcn = args.model == "gcn"
+    gat = args.model == "gat"
+    gcn = args.model == "gcn" or gat      # one weight matrix per layer
+    att_h = att = None
     if gcn:     # one [in, out] matrix per layer, Glorot-uniform from the workload's seed
-        assert not wl.bf16, "the GCN model kind is fp32 only"
+        assert not wl.bf16, "the GCN and GAT model kinds are fp32 only"
         rng = np.random.default_rng(wl.seed)
         Wh = [(rng.uniform(-1, 1, size=(wl.dims[l], wl.dims[l + 1])) *
                np.sqrt(6.0 / (wl.dims[l] + wl.dims[l + 1]))).astype(np.float32) for l in range(len(wl.fanouts))]
+        if gat:  # attention vectors [a_src | a_dst] per layer
+            att_h = [(rng.uniform(-1, 1, size=2 * wl.dims[l + 1]) * np.sqrt(6.0 / (wl.dims[l + 1] + 1))).astype(np.float32)
+                     for l in range(len(wl.fanouts))]
+            att = [torch.from_numpy(v).cuda() for v in att_h]
     else:
         Wh = inst.W
     W = [torch.from_numpy(w).cuda() for w in Wh]
     b = [torch.from_numpy(v).cuda() for v in inst.b]
-    model = sdt.make_model(wl.dims, W, b, kind=sdt.SDT_MODEL_GCN if gcn else sdt.SDT_MODEL_SAGE_MEAN)
+    model = sdt.make_model(wl.dims, W, b, kind=sdt.SDT_MODEL_GAT if gat else sdt.SDT_MODEL_GCN if gcn else sdt.SDT_MODEL_SAGE_MEAN,
+                           att=att)
     code = sdt.SDT_BF16 if wl.bf16 else sdt.SDT_F32
     lay = sdt.sdt_train_step_layout(graph.n_nodes, wl.batch, wl.fanouts, model, code)
     ws = torch.empty(sdt.sdt_train_loop_workspace_bytes(graph.n_nodes, wl.batch, wl.fanouts, model, code),
@@ -126,9 +133,10 @@ def main():
             if per_step is not None:
                 per_step(i)
 
-    stages = [("sample", l) for l in range(L)] + ([] if gcn else [("gather", 0)]) + [("aggregate_fwd", l) for l in range(L)] + \
+    stages = [("sample", l) for l in range(L)] + ([] if gcn and not gat else [("gather", 0)]) + \
+             [("aggregate_fwd", l) for l in range(L)] + \
              [("linear_fwd", l) for l in range(L)] + [("loss", 0)] + [("linear_bwd", l) for l in range(L)] + \
-             [("aggregate_bwd", l) for l in range(1, L)] + [("head", L - 1)]
+             [("aggregate_bwd", l) for l in range(0 if gat else 1, L)] + [("head", L - 1)]
     single_kernel = {"gather", "aggregate_fwd", "linear_fwd", "aggregate_bwd", "head"}   # one launch per stage
 
     def staged_pass(first, count, with_counts):
@@ -181,6 +189,19 @@ def main():
         """Algorithmic work of one launch of a stage: (bound, amount, unit of the rate, kernels)."""
         n_dst, n_src, nnz = mean_cnt[l][:3]
         wf = 1.0 if gcn else 2.0      # rows of W per input feature: GraphSAGE stacks a self and a neighbour block
+        if gat:     # every frontier row is gathered and projected; the attention passes read projected rows
+            F = d[l + 1]
+            if kind == "gather":
+                return "hbm", n_src * (2 * d[0] * es + 4), "k_gather"
+            if kind == "aggregate_fwd":   # scores over every source row, then two score passes and one row pass per edge
+                return "hbm", n_src * F * 4 + nnz * (F * 4 + 12) + n_dst * (2 * F * 4 + 16), "k_gat_scores + k_gat_fwd"
+            if kind == "aggregate_bwd":   # two dot-product passes per edge on each side + the weighted sums
+                return "hbm", nnz * (5 * F * 4 + 16) + n_src * 3 * F * 4 + n_dst * 3 * F * 4, \
+                       "k_gat_mask_bias + k_gat_bwd_dst + k_gat_bwd_src + k_gat_vec_partials"
+            if kind == "linear_fwd":
+                return "mfma", 2.0 * n_src * d[l] * F, "k_linear_fwd"
+            if kind == "linear_bwd":
+                return "mfma", 2.0 * n_src * d[l] * F * (2 if l > 0 else 1), "k_linear_bwd_weight (+ _input)"
         if kind == "sample":      # 16 B of row offsets per destination, 4 B read + 4 B written per sampled edge
             return "hbm", n_dst * 16 + nnz * 8, "k_sample_rows + frontier scan + relabel (+ transposed block)"
         if kind == "gather":      # only the destination prefix is copied; the rest is read by the aggregation
@@ -228,7 +249,10 @@ def main():
         ns = max(1, args.cpu_steps)
         tc = time.perf_counter()
         for s in range(ns):
-            if gcn:
+            if gat:
+                orc.gat_train_step(inst.indptr, inst.indices, inst.X, inst.y, inst.batch(s), wl.fanouts, Wh, inst.b, att_h,
+                                   wl.seed, s, args.lr)
+            elif gcn:
                 orc.gcn_train_step(inst.indptr, inst.indices, inst.X, inst.y, inst.batch(s), wl.fanouts, Wh, inst.b,
                                    wl.seed, s, args.lr)
             else:
@@ -247,12 +271,12 @@ def main():
                "host_cpus": os.cpu_count()}
 
     out = {
-        "metric": "train steps/s per GPU (sample + gather + forward + backward + SGD)" + (" [GCN model kind]" if gcn else ""),
+        "metric": "train steps/s per GPU (sample + gather + forward + backward + SGD)" + (" [GAT model kind]" if gat else " [GCN model kind]" if gcn else ""),
         "value": round(K / elapsed, 2), "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": round(elapsed / K * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if wl.bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.kind} 2^{wl.log2n} nodes, {nnz_graph} CSR entries, F={wl.feat}, "
-                               f"C={wl.classes}, {L}-layer GraphSAGE-mean hidden {wl.hidden}, fanout {wl.fanouts}, "
+                               f"C={wl.classes}, {L}-layer {'GAT' if gat else 'GCN' if gcn else 'GraphSAGE-mean'} hidden {wl.hidden}, fanout {wl.fanouts}, "
                                f"batch {wl.batch}, seeds from the first {wl.owned_frac:g} of the ids",
                    "lr": args.lr, "seed": wl.seed},
         "sampled_edges_per_s": round(edges_per_step * K / elapsed, 1),

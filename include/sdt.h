@@ -108,13 +108,23 @@ typedef struct sdt_model {
      * name its optimiser.) */
     int32_t optimizer;
     float beta1, beta2, eps;
-    int32_t reserved;
+    float gat_slope; /* SDT_MODEL_GAT: negative slope of the LeakyReLU on the attention scores (e.g. 0.2) */
     float *mW[SDT_MAX_LAYERS];
     float *vW[SDT_MAX_LAYERS];
     float *mb[SDT_MAX_LAYERS];
     float *vb[SDT_MAX_LAYERS];
+    /* SDT_MODEL_GAT (Sec. III-E: GAT is one of the integrated models; one head): layer l is
+     * H' = act(GATagg(H W[l]) + b[l]) with W[l] fp32 [dims[l], dims[l+1]] applied to EVERY
+     * frontier row, the attention aggregation of sdt_gat_aggregate_fwd with
+     * a_src = att[l][0:out], a_dst = att[l][out:2out], ReLU on all but the last layer.
+     * att[l] fp32 [2*dims[l+1]] is trained like a bias: datt (nullable) receives its gradient,
+     * matt/vatt are its Adam moments.  fp32 storage and even dims[0..L-1] only. */
+    float *att[SDT_MAX_LAYERS];
+    float *datt[SDT_MAX_LAYERS];
+    float *matt[SDT_MAX_LAYERS];
+    float *vatt[SDT_MAX_LAYERS];
 } sdt_model;
-enum { SDT_MODEL_SAGE_MEAN = 0, SDT_MODEL_GCN = 1 };
+enum { SDT_MODEL_SAGE_MEAN = 0, SDT_MODEL_GCN = 1, SDT_MODEL_GAT = 2 };
 enum { SDT_OPT_SGD = 0, SDT_OPT_ADAM = 1 };
 
 /* Byte offsets, inside the sdt_train_step workspace, of everything the step
@@ -154,6 +164,14 @@ typedef struct sdt_step_layout {
     uint64_t scratch;  /* internal */
     uint64_t wlow;     /* internal: bf16 images of the weights (bf16 workloads only) */
     uint64_t norm[SDT_MAX_LAYERS]; /* GCN only: fp32 c[cap_src] | s[cap_dst] | selfw[cap_dst], each 256-byte aligned */
+    /* GAT only.  H[0] then holds EVERY frontier row of layer 0, [cap_src[0], dims[0]], H[l+1] is
+     * act(attention output + b); z[l] = H[l] W[l] and dz[l] = d loss / d z[l] are fp32
+     * [cap_src[l], dims[l+1]]; dH[l] (l >= 1) is d loss / d H[l] with the ReLU mask applied;
+     * datt[l] fp32 [2*dims[l+1]]; t_indptr/t_rows exist for every layer; A, dSelf, dAgg are unused. */
+    uint64_t z[SDT_MAX_LAYERS];
+    uint64_t dz[SDT_MAX_LAYERS];
+    uint64_t datt[SDT_MAX_LAYERS];
+    uint64_t gatws[SDT_MAX_LAYERS]; /* internal */
 } sdt_step_layout;
 
 /* Library version as "major.minor.patch" (host string, static storage). */

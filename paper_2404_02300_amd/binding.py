@@ -21,7 +21,7 @@ SDT_OK, SDT_ERR_INVALID_ARG, SDT_ERR_WORKSPACE, SDT_ERR_HIP = 0, -1, -2, -3
 SDT_F32, SDT_BF16 = 0, 1
 SDT_MAX_LAYERS = 8
 SDT_MAX_FANOUT = 64
-SDT_MODEL_SAGE_MEAN, SDT_MODEL_GCN = 0, 1
+SDT_MODEL_SAGE_MEAN, SDT_MODEL_GCN, SDT_MODEL_GAT = 0, 1, 2
 SDT_OPT_SGD, SDT_OPT_ADAM = 0, 1
 
 _vp, _i32, _i64, _u32, _u64, _sz = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32,
@@ -48,9 +48,10 @@ class sdt_model(ctypes.Structure):
     _fields_ = [("n_layers", _i32), ("dims", _i32 * (SDT_MAX_LAYERS + 1)),
                 ("W", _vp * SDT_MAX_LAYERS), ("b", _vp * SDT_MAX_LAYERS),
                 ("dW", _vp * SDT_MAX_LAYERS), ("db", _vp * SDT_MAX_LAYERS), ("kind", _i32), ("optimizer", _i32),
-                ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float), ("reserved", _i32),
+                ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float), ("gat_slope", ctypes.c_float),
                 ("mW", _vp * SDT_MAX_LAYERS), ("vW", _vp * SDT_MAX_LAYERS), ("mb", _vp * SDT_MAX_LAYERS),
-                ("vb", _vp * SDT_MAX_LAYERS)]
+                ("vb", _vp * SDT_MAX_LAYERS), ("att", _vp * SDT_MAX_LAYERS), ("datt", _vp * SDT_MAX_LAYERS),
+                ("matt", _vp * SDT_MAX_LAYERS), ("vatt", _vp * SDT_MAX_LAYERS)]
 
 
 class sdt_step_layout(ctypes.Structure):
@@ -61,7 +62,8 @@ class sdt_step_layout(ctypes.Structure):
                 ("t_indptr", _u64 * _L), ("t_rows", _u64 * _L),
                 ("H", _u64 * (_L + 1)), ("A", _u64 * _L), ("dZ", _u64),
                 ("dH", _u64 * _L), ("dSelf", _u64 * _L), ("dAgg", _u64 * _L),
-                ("dW", _u64 * _L), ("db", _u64 * _L), ("row_loss", _u64), ("scratch", _u64), ("wlow", _u64), ("norm", _u64 * _L)]
+                ("dW", _u64 * _L), ("db", _u64 * _L), ("row_loss", _u64), ("scratch", _u64), ("wlow", _u64), ("norm", _u64 * _L),
+                ("z", _u64 * _L), ("dz", _u64 * _L), ("datt", _u64 * _L), ("gatws", _u64 * _L)]
 
 
 class sdt_partition(ctypes.Structure):
@@ -278,23 +280,31 @@ def sdt_sage_linear_bwd(dY: torch.Tensor, Y: Optional[torch.Tensor], relu: bool,
 
 def make_model(dims: Sequence[int], W: List[torch.Tensor], b: List[torch.Tensor],
                dW: Optional[List[torch.Tensor]] = None, db: Optional[List[torch.Tensor]] = None,
-               kind: int = SDT_MODEL_SAGE_MEAN) -> sdt_model:
+               kind: int = SDT_MODEL_SAGE_MEAN, att: Optional[List[torch.Tensor]] = None,
+               datt: Optional[List[torch.Tensor]] = None, gat_slope: float = 0.2) -> sdt_model:
+    """GAT (kind = SDT_MODEL_GAT) also takes att[l], fp32 [2 * dims[l+1]] = [a_src | a_dst]."""
     m = sdt_model()
     m.kind = kind
+    m.gat_slope = gat_slope
     m.n_layers = len(dims) - 1
     for i, d in enumerate(dims):
         m.dims[i] = d
     for l in range(m.n_layers):
-        rows = dims[l] if kind == SDT_MODEL_GCN else 2 * dims[l]
+        rows = 2 * dims[l] if kind == SDT_MODEL_SAGE_MEAN else dims[l]
         assert W[l].dtype == torch.float32 and W[l].is_contiguous() and tuple(W[l].shape) == (rows, dims[l + 1])
         m.W[l], m.b[l] = W[l].data_ptr(), b[l].data_ptr()
         m.dW[l] = dW[l].data_ptr() if dW is not None else None
         m.db[l] = db[l].data_ptr() if db is not None else None
+        if kind == SDT_MODEL_GAT:
+            assert att is not None and att[l].dtype == torch.float32 and att[l].is_contiguous() and att[l].numel() == 2 * dims[l + 1]
+            m.att[l] = att[l].data_ptr()
+            m.datt[l] = datt[l].data_ptr() if datt is not None else None
     return m
 
 
 def use_adam(model: sdt_model, mW: List[torch.Tensor], vW: List[torch.Tensor], mb: List[torch.Tensor],
-             vb: List[torch.Tensor], beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8) -> sdt_model:
+             vb: List[torch.Tensor], beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
+             matt: Optional[List[torch.Tensor]] = None, vatt: Optional[List[torch.Tensor]] = None) -> sdt_model:
     """Switch a model to Adam; the moment tensors (fp32, shaped like W / b, zero before the first step)
     stay owned by the caller."""
     model.optimizer, model.beta1, model.beta2, model.eps = SDT_OPT_ADAM, beta1, beta2, eps
@@ -303,6 +313,8 @@ def use_adam(model: sdt_model, mW: List[torch.Tensor], vW: List[torch.Tensor], m
             assert t.dtype == torch.float32 and t.is_contiguous()
         model.mW[l], model.vW[l], model.mb[l], model.vb[l] = (mW[l].data_ptr(), vW[l].data_ptr(), mb[l].data_ptr(),
                                                               vb[l].data_ptr())
+        if matt is not None:
+            model.matt[l], model.vatt[l] = matt[l].data_ptr(), vatt[l].data_ptr()
     return model
 
 

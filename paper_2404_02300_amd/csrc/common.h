@@ -143,6 +143,7 @@ struct PendingReduce {
     const float* P = nullptr;
     const float* Q = nullptr;
     int32_t splits = 0, in = 0, out = 0;
+    int32_t q_splits = -1;   // number of Q partials if it differs from `splits` (-1: the same)
     float* dW = nullptr;
     float* db = nullptr;
     float* W_upd = nullptr;
@@ -207,6 +208,20 @@ int32_t linear_bwd_input_bf16(const void* dY, int64_t lddy, int32_t dy_dtype, in
 int32_t gcn_aggregate_fwd(const sdt_block* blk, const float* H, int64_t ldh, bool through_src_nodes, int32_t F,
                           const float* c, const float* s, const float* selfw, float* A, int64_t lda, int32_t* map_reset,
                           hipStream_t stm);
+
+// GAT attention aggregation inside a training step (gat.hip).  The forward adds `bias` (may be null) and
+// applies ReLU if asked; the backward leaves the attention-vector partial sums part[n_part][2 F]
+// (a_src half, a_dst half) in the workspace for the step's single reduction launch.
+int32_t gat_forward(const sdt_block* blk, const float* z, int64_t ldz, int32_t F, const float* a_src, const float* a_dst,
+                    float slope, const float* bias, int32_t relu, float* out, int64_t ldo, void* ws, size_t ws_bytes,
+                    hipStream_t st);
+int32_t gat_backward(const sdt_block* blk, const float* z, int64_t ldz, int32_t F, const float* a_src, const float* a_dst,
+                     float slope, const float* g, int64_t ldg, float* dz, int64_t lddz, void* ws, size_t ws_bytes,
+                     const float** part, int32_t* n_part, hipStream_t st);
+// g[r, :] = 0 where Y[r, :] <= 0 (Y may be null: no mask), in place, and the column sums of the result over
+// chunks of rows: Qb[n_chunks][F] in the workspace (rows beyond the block's n_dst count as zero)
+int32_t gat_mask_bias(const sdt_block* blk, float* g, int64_t ldg, const float* Y, int64_t ldy, int32_t F, void* ws,
+                      size_t ws_bytes, const float** Qb, int32_t* n_chunks, hipStream_t st);
 
 // number of step workspaces sdt_train_loop rotates through (its workspace is that many step layouts)
 int32_t train_loop_buffers();

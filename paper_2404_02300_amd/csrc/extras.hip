@@ -154,6 +154,8 @@ extern "C" int32_t sdt_train_round(const sdt_partition* parts, int32_t n_parts, 
     if (rc != SDT_OK) return rc;
     SDT_REQUIRE(parts && locals && n_parts >= 1 && n_parts <= MAX_MODELS, SDT_ERR_INVALID_ARG,
                 "sdt_train_round: n_parts outside [1,%d] or null argument", MAX_MODELS);
+    SDT_REQUIRE(global_model->kind != SDT_MODEL_GAT, SDT_ERR_INVALID_ARG,
+                "sdt_train_round: GAT models are not supported (their attention vectors are not averaged here)");
     const int L = global_model->n_layers;
     double total = 0;
     for (int j = 0; j < n_parts; ++j) {

@@ -27,8 +27,8 @@ __device__ __forceinline__ float wave_max(float v) {
 __device__ __forceinline__ float leaky(float x, float slope) { return x > 0.f ? x : slope * x; }
 
 struct GatWs {
-    float *el, *er, *lse, *t, *der, *del, *part;
-    int nblk;
+    float *el, *er, *lse, *t, *der, *del, *part, *biasq;
+    int nblk, nchunk;
     size_t total;
 };
 constexpr int VEC_ROWS = 256;  // rows per partial sum of the attention-vector gradients
@@ -43,6 +43,8 @@ GatWs gat_ws(void* base, int32_t cap_src, int32_t cap_dst, int32_t F) {
     w.del = a.take<float>(cap_src > 0 ? cap_src : 1);
     w.nblk = ceil_div(cap_src > 0 ? cap_src : 1, VEC_ROWS);
     w.part = a.take<float>((size_t)w.nblk * 2 * (F > 0 ? F : 1));
+    w.nchunk = ceil_div(cap_dst > 0 ? cap_dst : 1, VEC_ROWS);
+    w.biasq = a.take<float>((size_t)w.nchunk * (F > 0 ? F : 1));
     w.total = a.off;
     return w;
 }
@@ -72,7 +74,8 @@ __global__ __launch_bounds__(TB) void k_gat_scores(const int32_t* counts, const 
 __global__ __launch_bounds__(TB) void k_gat_fwd(const int32_t* __restrict__ b_indptr, const int32_t* __restrict__ cols,
                                                 const int32_t* counts, const float* __restrict__ z, int64_t ldz, int F,
                                                 const float* __restrict__ el, const float* __restrict__ er, float slope,
-                                                float* __restrict__ lse, float* __restrict__ out, int64_t ldo) {
+                                                float* __restrict__ lse, const float* __restrict__ bias, int relu,
+                                                float* __restrict__ out, int64_t ldo) {
     const int n = counts[0];
     const int lane = threadIdx.x & 63;
     for (int i = blockIdx.x * WPB + (threadIdx.x >> 6); i < n; i += gridDim.x * WPB) {
@@ -94,7 +97,10 @@ __global__ __launch_bounds__(TB) void k_gat_fwd(const int32_t* __restrict__ b_in
                 const int c = cols[e];
                 acc += expf(leaky(ri + el[c], slope) - l) * z[(int64_t)c * ldz + f];
             }
-            out[(int64_t)i * ldo + f] = acc + a_self * z[(int64_t)i * ldz + f];
+            float v = acc + a_self * z[(int64_t)i * ldz + f];
+            if (bias) v += bias[f];
+            if (relu && !(v > 0.f)) v = 0.f;
+            out[(int64_t)i * ldo + f] = v;
         }
     }
 }
@@ -217,6 +223,27 @@ __global__ __launch_bounds__(TB) void k_gat_vec_final(const float* __restrict__ 
     }
 }
 
+// In place: g[r][f] = 0 where Y[r][f] <= 0 (Y may be null), and Qb[chunk][f] = column sum of the
+// masked g over the chunk's rows (zero for chunks past the row count).
+__global__ __launch_bounds__(TB) void k_gat_mask_bias(const int32_t* counts, float* __restrict__ g, int64_t ldg,
+                                                      const float* __restrict__ Y, int64_t ldy, int F,
+                                                      float* __restrict__ Qb) {
+    const int n = counts[0];
+    const int r0 = blockIdx.x * VEC_ROWS, r1 = min(n, r0 + VEC_ROWS);
+    for (int f = threadIdx.x; f < F; f += TB) {
+        float s = 0.f;
+        for (int r = r0; r < r1; ++r) {
+            float v = g[(int64_t)r * ldg + f];
+            if (Y && !(Y[(int64_t)r * ldy + f] > 0.f)) {
+                v = 0.f;
+                g[(int64_t)r * ldg + f] = 0.f;
+            }
+            s += v;
+        }
+        Qb[(int64_t)blockIdx.x * F + f] = s;
+    }
+}
+
 inline int rows_grid(int rows) {
     const int b = ceil_div(rows > 0 ? rows : 1, WPB);
     return b > 4096 ? 4096 : b;
@@ -235,6 +262,12 @@ extern "C" size_t sdt_gat_workspace_bytes(int32_t cap_src, int32_t cap_dst, int3
 extern "C" int32_t sdt_gat_aggregate_fwd(const sdt_block* blk, const float* z, int64_t ldz, int32_t F, const float* a_src,
                                          const float* a_dst, float slope, float* out, int64_t ldo, void* ws, size_t ws_bytes,
                                          void* stream) {
+    return gat_forward(blk, z, ldz, F, a_src, a_dst, slope, nullptr, 0, out, ldo, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+int32_t sdt::gat_forward(const sdt_block* blk, const float* z, int64_t ldz, int32_t F, const float* a_src, const float* a_dst,
+                         float slope, const float* bias, int32_t relu, float* out, int64_t ldo, void* ws, size_t ws_bytes,
+                         hipStream_t st) {
     SDT_REQUIRE(blk, SDT_ERR_INVALID_ARG, "sdt_gat_aggregate_fwd: null block");
     SDT_REQUIRE(F >= 0 && ldz >= F && ldo >= F && blk->cap_src >= blk->cap_dst, SDT_ERR_INVALID_ARG,
                 "sdt_gat_aggregate_fwd: bad sizes");
@@ -244,12 +277,11 @@ extern "C" int32_t sdt_gat_aggregate_fwd(const sdt_block* blk, const float* z, i
     const GatWs w = gat_ws(ws, blk->cap_src, blk->cap_dst, F);
     SDT_REQUIRE(ws && ws_bytes >= w.total && aligned16(ws), SDT_ERR_WORKSPACE,
                 "sdt_gat_aggregate_fwd: workspace of %zu bytes needed, %zu given", w.total, ws_bytes);
-    hipStream_t st = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(k_gat_scores, dim3(rows_grid(blk->cap_src)), dim3(TB), 0, st, blk->counts, z, ldz, F, a_src, a_dst, w.el,
                        w.er);
     SDT_CHECK_LAUNCH("gat scores");
     hipLaunchKernelGGL(k_gat_fwd, dim3(rows_grid(blk->cap_dst)), dim3(TB), 0, st, blk->indptr, blk->cols, blk->counts, z, ldz, F,
-                       w.el, w.er, slope, w.lse, out, ldo);
+                       w.el, w.er, slope, w.lse, bias, relu, out, ldo);
     SDT_CHECK_LAUNCH("gat forward");
     return SDT_OK;
 }
@@ -257,17 +289,31 @@ extern "C" int32_t sdt_gat_aggregate_fwd(const sdt_block* blk, const float* z, i
 extern "C" int32_t sdt_gat_aggregate_bwd(const sdt_block* blk, const float* z, int64_t ldz, int32_t F, const float* a_src,
                                          const float* a_dst, float slope, const float* g, int64_t ldg, float* dz,
                                          int64_t lddz, float* da_src, float* da_dst, void* ws, size_t ws_bytes, void* stream) {
+    SDT_REQUIRE(da_src && da_dst, SDT_ERR_INVALID_ARG, "sdt_gat_aggregate_bwd: null attention-vector gradient");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const float* part = nullptr;
+    int32_t n_part = 0;
+    const int32_t rc = gat_backward(blk, z, ldz, F, a_src, a_dst, slope, g, ldg, dz, lddz, ws, ws_bytes, &part, &n_part, st);
+    if (rc != SDT_OK || !part) return rc;
+    hipLaunchKernelGGL(k_gat_vec_final, dim3(ceil_div(F, TB)), dim3(TB), 0, st, part, n_part, F, da_src, da_dst);
+    SDT_CHECK_LAUNCH("gat attention-vector reduction");
+    return SDT_OK;
+}
+
+int32_t sdt::gat_backward(const sdt_block* blk, const float* z, int64_t ldz, int32_t F, const float* a_src,
+                          const float* a_dst, float slope, const float* g, int64_t ldg, float* dz, int64_t lddz, void* ws,
+                          size_t ws_bytes, const float** part, int32_t* n_part, hipStream_t st) {
+    *part = nullptr;
+    *n_part = 0;
     SDT_REQUIRE(blk, SDT_ERR_INVALID_ARG, "sdt_gat_aggregate_bwd: null block");
     SDT_REQUIRE(F >= 0 && ldz >= F && ldg >= F && lddz >= F && blk->cap_src >= blk->cap_dst, SDT_ERR_INVALID_ARG,
                 "sdt_gat_aggregate_bwd: bad sizes");
     if (blk->cap_src == 0 || F == 0) return SDT_OK;
-    SDT_REQUIRE(blk->counts && blk->indptr && blk->cols && blk->t_indptr && blk->t_rows && z && a_src && a_dst && g && dz &&
-                    da_src && da_dst,
+    SDT_REQUIRE(blk->counts && blk->indptr && blk->cols && blk->t_indptr && blk->t_rows && z && a_src && a_dst && g && dz,
                 SDT_ERR_INVALID_ARG, "sdt_gat_aggregate_bwd: null pointer (the block needs its transposed arrays)");
     const GatWs w = gat_ws(ws, blk->cap_src, blk->cap_dst, F);
     SDT_REQUIRE(ws && ws_bytes >= w.total && aligned16(ws), SDT_ERR_WORKSPACE,
                 "sdt_gat_aggregate_bwd: workspace of %zu bytes needed, %zu given", w.total, ws_bytes);
-    hipStream_t st = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(k_gat_bwd_dst, dim3(rows_grid(blk->cap_dst)), dim3(TB), 0, st, blk->indptr, blk->cols, blk->counts, z, ldz,
                        F, w.el, w.er, w.lse, slope, g, ldg, w.t, w.der);
     SDT_CHECK_LAUNCH("gat backward (destinations)");
@@ -276,7 +322,20 @@ extern "C" int32_t sdt_gat_aggregate_bwd(const sdt_block* blk, const float* z, i
     SDT_CHECK_LAUNCH("gat backward (sources)");
     hipLaunchKernelGGL(k_gat_vec_partials, dim3(w.nblk), dim3(TB), 0, st, blk->counts, z, ldz, F, w.del, w.der, w.part);
     SDT_CHECK_LAUNCH("gat attention-vector partials");
-    hipLaunchKernelGGL(k_gat_vec_final, dim3(ceil_div(F, TB)), dim3(TB), 0, st, w.part, w.nblk, F, da_src, da_dst);
-    SDT_CHECK_LAUNCH("gat attention-vector reduction");
+    *part = w.part;
+    *n_part = w.nblk;
+    return SDT_OK;
+}
+
+int32_t sdt::gat_mask_bias(const sdt_block* blk, float* g, int64_t ldg, const float* Y, int64_t ldy, int32_t F, void* ws,
+                           size_t ws_bytes, const float** Qb, int32_t* n_chunks, hipStream_t st) {
+    SDT_REQUIRE(blk && blk->counts && g && F > 0 && ldg >= F && (!Y || ldy >= F), SDT_ERR_INVALID_ARG, "gat_mask_bias: bad arguments");
+    const GatWs w = gat_ws(ws, blk->cap_src, blk->cap_dst, F);
+    SDT_REQUIRE(ws && ws_bytes >= w.total && aligned16(ws), SDT_ERR_WORKSPACE, "gat_mask_bias: workspace of %zu bytes needed, %zu given",
+                w.total, ws_bytes);
+    hipLaunchKernelGGL(k_gat_mask_bias, dim3(w.nchunk), dim3(TB), 0, st, blk->counts, g, ldg, Y, ldy, F, w.biasq);
+    SDT_CHECK_LAUNCH("gat mask + bias partials");
+    *Qb = w.biasq;
+    *n_chunks = w.nchunk;
     return SDT_OK;
 }

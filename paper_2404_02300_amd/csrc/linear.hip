@@ -374,10 +374,11 @@ __global__ __launch_bounds__(TL::NT) void k_linear_bwd_weight(const TH* __restri
 // g, g+4, g+8, ... and the four sums are combined in the order 0,1,2,3 -- a fixed order, so
 // the result is deterministic, with four times as many loads in flight as one thread per element.
 constexpr int TB = 256;
+constexpr int SDT_MAX_REDUCE = 2 * SDT_MAX_LAYERS;   // a GAT layer queues two (weights + bias, attention vectors)
 struct ReduceArgs {
     int32_t n;
-    int32_t first[SDT_MAX_LAYERS + 1];  // first workgroup of each layer
-    PendingReduce r[SDT_MAX_LAYERS];
+    int32_t first[SDT_MAX_REDUCE + 1];  // first workgroup of each reduction
+    PendingReduce r[SDT_MAX_REDUCE];
 };
 // w <- w - lr g (SGD) or the Adam update with the moments m, v kept beside w
 __device__ __forceinline__ void apply_update(float* w, float g, float* m, float* v, const OptArgs& o) {
@@ -411,12 +412,13 @@ __global__ __launch_bounds__(TB) void k_reduce_partials(ReduceArgs a, OptArgs op
     while (l + 1 < a.n && (int)blockIdx.x >= a.first[l + 1]) ++l;
     const PendingReduce& r = a.r[l];
     const int64_t n_w = (int64_t)2 * r.in * r.out;
-    const int out = r.out, splits = r.splits;
+    const int out = r.out;
     const int e = threadIdx.x & 63, g = threadIdx.x >> 6;
     const int64_t idx = (int64_t)((int)blockIdx.x - a.first[l]) * 64 + e;
     const bool is_w = idx < n_w, is_b = !is_w && idx < n_w + out;
     const float* src = is_w ? r.P + idx : r.Q + (idx - n_w);
     const int64_t stride = is_w ? n_w : out;
+    const int splits = is_w || r.q_splits < 0 ? r.splits : r.q_splits;
     float s = 0.f;
     if (is_w || is_b) {
 #pragma unroll 4
@@ -634,7 +636,7 @@ extern "C" size_t sdt_linear_bwd_workspace_bytes(int32_t n_cap, int32_t in, int3
 namespace sdt {
 int32_t reduce_all(const PendingReduce* r, int32_t n, const OptArgs& opt, const float* row_loss, int32_t n_loss,
                    float* loss_out, hipStream_t st) {
-    SDT_REQUIRE(r && n >= 1 && n <= SDT_MAX_LAYERS, SDT_ERR_INVALID_ARG, "reduce_all: %d reductions", n);
+    SDT_REQUIRE(r && n >= 1 && n <= SDT_MAX_REDUCE, SDT_ERR_INVALID_ARG, "reduce_all: %d reductions", n);
     ReduceArgs a{};
     a.n = n;
     a.first[0] = 0;

@@ -33,7 +33,7 @@ bool compute_caps(int64_t n_nodes, int32_t batch, const int32_t* fanouts, int L,
 
 // width of one of the two operands the projection kernels take: [Hself | A] for GraphSAGE, the two
 // halves of the aggregated row for GCN (whose single weight matrix [in, out] is then [2 * in/2, out])
-inline int32_t operand_width(const sdt_model* m, int l) { return m->kind == SDT_MODEL_GCN ? m->dims[l] / 2 : m->dims[l]; }
+inline int32_t operand_width(const sdt_model* m, int l) { return m->kind != SDT_MODEL_SAGE_MEAN ? m->dims[l] / 2 : m->dims[l]; }
 
 // scratch of one layer's projection backward (split partials of dW/db, or the fused head's)
 size_t bwd_scratch_bytes(int32_t batch, int32_t cap_dst, int32_t in, int32_t out, bool last) {
@@ -54,13 +54,16 @@ int32_t check_model(const sdt_model* m, const int32_t* fanouts, const char* who)
     for (int l = 0; l < m->n_layers; ++l)
         SDT_REQUIRE(fanouts[l] >= 0 && fanouts[l] <= SDT_MAX_FANOUT, SDT_ERR_INVALID_ARG,
                     "%s: fanouts[%d] = %d outside [0,%d]", who, l, fanouts[l], SDT_MAX_FANOUT);
-    SDT_REQUIRE(m->kind == SDT_MODEL_SAGE_MEAN || m->kind == SDT_MODEL_GCN, SDT_ERR_INVALID_ARG, "%s: unknown model kind %d",
-                who, m->kind);
-    if (m->kind == SDT_MODEL_GCN)
+    SDT_REQUIRE(m->kind == SDT_MODEL_SAGE_MEAN || m->kind == SDT_MODEL_GCN || m->kind == SDT_MODEL_GAT, SDT_ERR_INVALID_ARG,
+                "%s: unknown model kind %d", who, m->kind);
+    if (m->kind != SDT_MODEL_SAGE_MEAN)
         for (int l = 0; l < m->n_layers; ++l)
             SDT_REQUIRE(m->dims[l] % 2 == 0, SDT_ERR_INVALID_ARG,
-                        "%s: GCN needs even layer input widths (dims[%d] = %d): the projection runs as two half-width operands",
+                        "%s: GCN and GAT need even layer input widths (dims[%d] = %d): the projection runs as two half-width operands",
                         who, l, m->dims[l]);
+    if (m->kind == SDT_MODEL_GAT)
+        SDT_REQUIRE(m->gat_slope >= 0.f && m->gat_slope <= 1.f, SDT_ERR_INVALID_ARG, "%s: gat_slope %g outside [0,1]", who,
+                    (double)m->gat_slope);
     return SDT_OK;
 }
 
@@ -174,8 +177,8 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
     int32_t rc = check_model(model, fanouts, "sdt_train_step_layout");
     if (rc != SDT_OK) return rc;
     SDT_REQUIRE(dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_train_step_layout: unknown dtype %d", dtype);
-    SDT_REQUIRE(model->kind != SDT_MODEL_GCN || dtype == SDT_F32, SDT_ERR_INVALID_ARG,
-                "sdt_train_step_layout: the GCN model is fp32 only");
+    SDT_REQUIRE(model->kind == SDT_MODEL_SAGE_MEAN || dtype == SDT_F32, SDT_ERR_INVALID_ARG,
+                "sdt_train_step_layout: the GCN and GAT models are fp32 only");
     SDT_REQUIRE(n_nodes >= 0 && n_nodes <= 0x7FFFFFFF && batch >= 0 && batch <= n_nodes, SDT_ERR_INVALID_ARG,
                 "sdt_train_step_layout: n_nodes=%lld batch=%d", (long long)n_nodes, batch);
     const int L = model->n_layers;
@@ -190,6 +193,38 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
     size_t scratch = 0, bwd_scratch = 0;
     lay->header = a.take_off(64 * sizeof(int32_t));
     lay->state = a.take_off(sample_state_bytes(n_nodes));
+    if (model->kind == SDT_MODEL_GAT) {
+        for (int l = 0; l < L; ++l) {
+            lay->cap_dst[l] = c.dst[l];
+            lay->cap_src[l] = c.src[l];
+            lay->cap_nnz[l] = c.nnz[l];
+            lay->counts[l] = a.take_off(4 * sizeof(int32_t));
+            lay->indptr[l] = a.take_off(((size_t)c.dst[l] + 1) * 4);
+            lay->cols[l] = a.take_off((size_t)(c.nnz[l] > 0 ? c.nnz[l] : 1) * 4);
+            lay->src_nodes[l] = a.take_off((size_t)(c.src[l] > 0 ? c.src[l] : 1) * 4);
+            lay->t_indptr[l] = a.take_off(((size_t)c.src[l] + 1) * 4);
+            lay->t_rows[l] = a.take_off((size_t)(c.nnz[l] > 0 ? c.nnz[l] : 1) * 4);
+            if (l >= 1) lay->dH[l] = a.take_off((size_t)c.src[l] * d[l] * 4);
+            lay->H[l + 1] = a.take_off((size_t)c.dst[l] * d[l + 1] * 4);
+            lay->z[l] = a.take_off((size_t)c.src[l] * d[l + 1] * 4);
+            lay->dz[l] = a.take_off((size_t)c.src[l] * d[l + 1] * 4);
+            lay->dW[l] = a.take_off((size_t)d[l] * d[l + 1] * 4);
+            lay->db[l] = a.take_off((size_t)d[l + 1] * 4);
+            lay->datt[l] = a.take_off((size_t)2 * d[l + 1] * 4);
+            lay->gatws[l] = a.take_off(sdt_gat_workspace_bytes(c.src[l], c.dst[l], d[l + 1]));
+            Arena s(nullptr);
+            size_t sb = sample_tmp_carve(s, n_nodes, c.dst[l], fanouts[l], nullptr);
+            if (sb > scratch) scratch = sb;
+            bwd_scratch += align_up(sdt_linear_bwd_workspace_bytes(c.src[l], d[l] / 2, d[l + 1]), 256);
+        }
+        if (bwd_scratch > scratch) scratch = bwd_scratch;
+        lay->H[0] = a.take_off((size_t)c.src[0] * d[0] * 4);
+        lay->dZ = a.take_off((size_t)batch * d[L] * 4);
+        lay->row_loss = a.take_off((size_t)(batch > 0 ? batch : 1) * 4);
+        lay->scratch = a.take_off(scratch);
+        lay->total_bytes = a.off;
+        return SDT_OK;
+    }
     for (int l = 0; l < L; ++l) {
         lay->cap_dst[l] = c.dst[l];
         lay->cap_src[l] = c.src[l];
@@ -252,6 +287,7 @@ OptArgs optimizer_args(const sdt_model* m, float lr, uint32_t step) {
     }
     return o;
 }
+// Adam moments of a layer's (W, b) reduction
 void attach_moments(PendingReduce* pr, const sdt_model* m, int l) {
     if (m->optimizer != SDT_OPT_ADAM) return;
     pr->mW = m->mW[l];
@@ -306,9 +342,13 @@ int32_t check_step_args(const char* who, const sdt_csr* graph, const void* X, in
         SDT_REQUIRE(model->beta1 >= 0.f && model->beta1 < 1.f && model->beta2 >= 0.f && model->beta2 < 1.f && model->eps > 0.f,
                     SDT_ERR_INVALID_ARG, "%s: Adam needs 0 <= beta < 1 and eps > 0", who);
         for (int l = 0; l < model->n_layers; ++l)
-            SDT_REQUIRE(model->mW[l] && model->vW[l] && model->mb[l] && model->vb[l], SDT_ERR_INVALID_ARG,
-                        "%s: Adam needs the moment buffers of layer %d", who, l);
+            SDT_REQUIRE(model->mW[l] && model->vW[l] && model->mb[l] && model->vb[l] &&
+                            (model->kind != SDT_MODEL_GAT || (model->matt[l] && model->vatt[l])),
+                        SDT_ERR_INVALID_ARG, "%s: Adam needs the moment buffers of layer %d", who, l);
     }
+    if (model->kind == SDT_MODEL_GAT)
+        for (int l = 0; l < model->n_layers; ++l)
+            SDT_REQUIRE(model->att[l], SDT_ERR_INVALID_ARG, "%s: null attention vectors of layer %d", who, l);
     return SDT_OK;
 }
 
@@ -325,8 +365,9 @@ void bind_buffers(const sdt_step_layout& lay, void* ws, size_t bytes, StepBuffer
         k.indptr = static_cast<int32_t*>(b->at(lay.indptr[l]));
         k.cols = static_cast<int32_t*>(b->at(lay.cols[l]));
         k.src_nodes = static_cast<int32_t*>(b->at(lay.src_nodes[l]));
-        k.t_indptr = l >= 1 ? static_cast<int32_t*>(b->at(lay.t_indptr[l])) : nullptr;
-        k.t_rows = l >= 1 ? static_cast<int32_t*>(b->at(lay.t_rows[l])) : nullptr;
+        // the transposed block exists where an input gradient flows through the block (offset 0 = absent)
+        k.t_indptr = lay.t_indptr[l] ? static_cast<int32_t*>(b->at(lay.t_indptr[l])) : nullptr;
+        k.t_rows = lay.t_rows[l] ? static_cast<int32_t*>(b->at(lay.t_rows[l])) : nullptr;
     }
 }
 
@@ -375,6 +416,12 @@ int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds
         StageTimer tm(c.timing, c.slot, SDT_STAGE_AGG_FWD, 0, st);
         return gcn_aggregate_fwd(&b.blk[0], static_cast<const float*>(c.X), c.ldx, true, d[0], b.gcn_c(lay, 0),
                                  b.gcn_s(lay, 0), b.gcn_self(lay, 0), static_cast<float*>(b.at(lay.A[0])), d[0], sw.map, st);
+    }
+    if (c.model->kind == SDT_MODEL_GAT) {
+        // every frontier row is projected, so every one is gathered (which also hands the whole map back clean)
+        StageTimer tm(c.timing, c.slot, SDT_STAGE_GATHER, 0, st);
+        return gather_rows(c.X, c.ldx, d[0], c.dtype, b.blk[0].src_nodes, lay.cap_src[0], b.blk[0].counts + 1, b.at(lay.H[0]),
+                           d[0], sw.map, st);
     }
     // Input features: only the destination prefix of the outermost frontier is copied (the
     // projection's "self" operand); the neighbour mean of layer 0 is taken straight out of X.
@@ -478,11 +525,115 @@ int32_t step_compute_gcn(const StepCtx& c, const StepBuffers& b, const int32_t* 
                       c.batch, loss_d, st);
 }
 
+// Phase 2 of a GAT step.  The projection z = H W covers every frontier row (the attention needs the
+// projected neighbours) and runs on the GraphSAGE kernels with the two halves of a row as operands;
+// the bias is added after the aggregation, so its gradient (column sums of the masked output
+// gradient) and the attention vectors' are summed by the step's single reduction launch from
+// per-chunk partials: the former replaces the projection kernels' own column sums, the latter is
+// queued as a second reduction of the layer with no weight part.
+int32_t step_compute_gat(const StepCtx& c, const StepBuffers& b, const int32_t* seeds, uint32_t step, float* loss_d,
+                         hipStream_t st) {
+    const sdt_step_layout& lay = c.lay;
+    const sdt_model* model = c.model;
+    const int L = model->n_layers;
+    const int32_t* d = model->dims;
+    sdt_timing* timing = c.timing;
+    const float slope = model->gat_slope;
+    int32_t rc;
+    size_t scr_off[SDT_MAX_LAYERS], scr_len[SDT_MAX_LAYERS], gws_len[SDT_MAX_LAYERS];
+    {
+        size_t o = lay.scratch;
+        for (int l = 0; l < L; ++l) {
+            scr_len[l] = align_up(sdt_linear_bwd_workspace_bytes(lay.cap_src[l], d[l] / 2, d[l + 1]), 256);
+            scr_off[l] = o;
+            o += scr_len[l];
+            gws_len[l] = sdt_gat_workspace_bytes(lay.cap_src[l], lay.cap_dst[l], d[l + 1]);
+        }
+    }
+    auto H = [&](int l) { return static_cast<float*>(b.at(lay.H[l])); };
+    auto Z = [&](int l) { return static_cast<float*>(b.at(lay.z[l])); };
+    for (int l = 0; l < L; ++l) {
+        const int F = d[l + 1];
+        {
+            StageTimer tm(timing, c.slot, SDT_STAGE_LINEAR_FWD, l, st);
+            rc = sdt_sage_linear_fwd(H(l), d[l], H(l) + d[l] / 2, d[l], lay.cap_src[l], b.blk[l].counts + 1, d[l] / 2, F,
+                                     model->W[l], nullptr, 0, SDT_F32, Z(l), F, SDT_F32, st);
+            if (rc != SDT_OK) return rc;
+        }
+        StageTimer tm(timing, c.slot, SDT_STAGE_AGG_FWD, l, st);
+        rc = gat_forward(&b.blk[l], Z(l), F, F, model->att[l], model->att[l] + F, slope, model->b[l], l < L - 1 ? 1 : 0,
+                         H(l + 1), F, b.at(lay.gatws[l]), gws_len[l], st);
+        if (rc != SDT_OK) return rc;
+    }
+    {
+        StageTimer tm(timing, c.slot, SDT_STAGE_LOSS, 0, st);
+        rc = softmax_xent(H(L), d[L], c.batch, d[L], c.labels, seeds, static_cast<float*>(b.at(lay.dZ)),
+                          static_cast<float*>(b.at(lay.row_loss)), st);
+        if (rc != SDT_OK) return rc;
+    }
+    PendingReduce pending[2 * SDT_MAX_LAYERS];
+    int n_pending = 0;
+    float* g = static_cast<float*>(b.at(lay.dZ));
+    for (int l = L - 1; l >= 0; --l) {
+        const int F = d[l + 1];
+        float* dW = model->dW[l] ? model->dW[l] : static_cast<float*>(b.at(lay.dW[l]));
+        float* db = model->db[l] ? model->db[l] : static_cast<float*>(b.at(lay.db[l]));
+        float* datt = model->datt[l] ? model->datt[l] : static_cast<float*>(b.at(lay.datt[l]));
+        float* dz = static_cast<float*>(b.at(lay.dz[l]));
+        const bool inner = l > 0;
+        const float *Qb, *part;
+        int32_t n_chunks, n_part;
+        {
+            StageTimer tm(timing, c.slot, SDT_STAGE_AGG_BWD, l, st);
+            // g: gradient w.r.t. this layer's output; masked in place by the layer's own ReLU (not the last layer)
+            rc = gat_mask_bias(&b.blk[l], g, F, l < L - 1 ? H(l + 1) : nullptr, F, F, b.at(lay.gatws[l]), gws_len[l], &Qb,
+                               &n_chunks, st);
+            if (rc != SDT_OK) return rc;
+            rc = gat_backward(&b.blk[l], Z(l), F, F, model->att[l], model->att[l] + F, slope, g, F, dz, F, b.at(lay.gatws[l]),
+                              gws_len[l], &part, &n_part, st);
+            if (rc != SDT_OK) return rc;
+        }
+        PendingReduce* pw = &pending[n_pending++];
+        {
+            StageTimer tm(timing, c.slot, SDT_STAGE_LINEAR_BWD, l, st);
+            BwdExtras ex;
+            ex.defer = pw;
+            ex.W_upd = model->W[l];
+            float* dH = inner ? static_cast<float*>(b.at(lay.dH[l])) : nullptr;
+            rc = linear_bwd(dz, F, SDT_F32, nullptr, 0, 0, H(l), d[l], H(l) + d[l] / 2, d[l], lay.cap_src[l],
+                            b.blk[l].counts + 1, d[l] / 2, F, model->W[l], SDT_F32, dW, db, dH, inner ? dH + d[l] / 2 : nullptr,
+                            d[l], b.at(scr_off[l]), scr_len[l], ex, st);
+            if (rc != SDT_OK) return rc;
+            g = dH;
+        }
+        // the bias gradient is the column sum of the masked output gradient, not of dz
+        pw->Q = Qb;
+        pw->q_splits = n_chunks;
+        pw->db = db;
+        pw->b_upd = model->b[l];
+        attach_moments(pw, model, l);
+        PendingReduce* pa = &pending[n_pending++];
+        pa->Q = part;
+        pa->q_splits = n_part;
+        pa->in = 0;
+        pa->out = 2 * F;
+        pa->db = datt;
+        pa->b_upd = model->att[l];
+        if (model->optimizer == SDT_OPT_ADAM) {
+            pa->mb = model->matt[l];
+            pa->vb = model->vatt[l];
+        }
+    }
+    return reduce_all(pending, n_pending, optimizer_args(model, c.lr, step), static_cast<const float*>(b.at(lay.row_loss)),
+                      c.batch, loss_d, st);
+}
+
 // Phase 2: forward, loss, backward, SGD on the blocks and features phase 1 left in `b`.
 // `step` is the update counter (Adam's bias correction uses step + 1).
 int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seeds, uint32_t step, float* loss_d,
                      hipStream_t st) {
     if (c.model->kind == SDT_MODEL_GCN) return step_compute_gcn(c, b, seeds, step, loss_d, st);
+    if (c.model->kind == SDT_MODEL_GAT) return step_compute_gat(c, b, seeds, step, loss_d, st);
     const sdt_step_layout& lay = c.lay;
     const sdt_model* model = c.model;
     const int L = model->n_layers;

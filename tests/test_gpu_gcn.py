@@ -156,3 +156,115 @@ def test_gat_attention_aggregation(F, fanout):
     with pytest.raises(B.SdtError) as e:
         B.sdt_gat_aggregate_fwd(gb, dzz, das, dad, 0.2, out, ws[:64])
     assert e.value.code == B.SDT_ERR_WORKSPACE
+
+
+def _gat_setup(classes, seed):
+    wl = gen.Workload("gat", "rmat", 13, 12, 64, classes, 64, 2, [8, 5], 128, 43, 1, owned_frac=0.5)
+    inst = gen.make_instance(wl)
+    rng = np.random.default_rng(seed)
+    d = wl.dims
+    W = [(rng.standard_normal((d[l], d[l + 1])) * (1.0 / np.sqrt(d[l]))).astype(np.float32) for l in range(2)]
+    b = [(rng.standard_normal(d[l + 1]) * 0.05).astype(np.float32) for l in range(2)]
+    att = [(rng.standard_normal(2 * d[l + 1]) * 0.3).astype(np.float32) for l in range(2)]
+    return wl, inst, W, b, att
+
+
+@pytest.mark.parametrize("classes,adam", [(8, False), (300, False), (8, True)])
+def test_gat_train_step(classes, adam):
+    _say(f"GAT train step, {classes} classes, {'Adam' if adam else 'SGD'}")
+    wl, inst, W, b, att = _gat_setup(classes, 3)
+    d = wl.dims
+    g = B.Csr(dev(inst.indptr), dev(inst.indices))
+    X, y = dev(inst.X), dev(inst.y)
+    Wd, bd, ad = [dev(w) for w in W], [dev(v) for v in b], [dev(v) for v in att]
+    model = B.make_model(d, Wd, bd, kind=B.SDT_MODEL_GAT, att=ad, gat_slope=0.2)
+    if adam:
+        zeros = lambda ts: [torch.zeros_like(t) for t in ts]
+        mom = dict(mW=zeros(Wd), vW=zeros(Wd), mb=zeros(bd), vb=zeros(bd), matt=zeros(ad), vatt=zeros(ad))
+        B.use_adam(model, mom["mW"], mom["vW"], mom["mb"], mom["vb"], 0.9, 0.999, 1e-8, mom["matt"], mom["vatt"])
+    lay = B.sdt_train_step_layout(g.n_nodes, wl.batch, wl.fanouts, model, B.SDT_F32)
+    ws = torch.empty(int(lay.total_bytes), dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    lr = 0.05
+    for step in range(2):
+        seeds = inst.batch(step)
+        W0, b0, a0 = [f64(w) for w in Wd], [f64(v) for v in bd], [f64(v) for v in ad]
+        if adam:
+            m0 = {k: [f64(t) for t in v] for k, v in mom.items()}
+        B.sdt_train_step(g, X, y, dev(seeds.astype(np.int32)), wl.fanouts, model, wl.seed, step, lr, loss, ws)
+        torch.cuda.synchronize()
+        ref = orc.gat_train_step(inst.indptr, inst.indices, inst.X, inst.y, seeds, wl.fanouts, W0, b0, a0, wl.seed, step, lr, 0.2)
+        blocks = ref["blocks"]
+        # ReLU decisions within rounding of zero may differ between fp32 and fp64: adopt the GPU's, check they are borderline
+        H1 = _view(ws, lay.H[1], lay.cap_dst[0], blocks[0].n_dst, d[1])
+        diff = (H1 > 0) != (ref["H"][1] > 0)
+        if diff.any():
+            assert np.all(np.abs(ref["H"][1][diff]) <= TOL * np.max(np.abs(ref["H"][1]))) and np.all(np.abs(H1[diff]) <= TOL * np.max(np.abs(H1)))
+            ref = orc.gat_train_step(inst.indptr, inst.indices, inst.X, inst.y, seeds, wl.fanouts, W0, b0, a0, wl.seed, step, lr,
+                                     0.2, blocks=blocks, relu_masks=[H1 > 0, None])
+        for l in range(2):
+            cnt = B.ws_view(ws, lay.counts[l], (4,), torch.int32).cpu().tolist()
+            assert cnt[:3] == [blocks[l].n_dst, blocks[l].n_src, blocks[l].nnz]
+            cols = B.ws_view(ws, lay.cols[l], (max(lay.cap_nnz[l], 1),), torch.int32)[:blocks[l].nnz].cpu().numpy()
+            assert np.array_equal(cols, blocks[l].cols)
+            assert_close(_view(ws, lay.z[l], lay.cap_src[l], blocks[l].n_src, d[l + 1]), ref["Z"][l], TOL, f"z[{l}]")
+            assert_close(_view(ws, lay.H[l + 1], lay.cap_dst[l], blocks[l].n_dst, d[l + 1]), ref["H"][l + 1], TOL, f"H[{l + 1}]")
+            assert_close(_view(ws, lay.dz[l], lay.cap_src[l], blocks[l].n_src, d[l + 1]), ref["dz"][l], TOL, f"dz[{l}]")
+            gW = _view(ws, lay.dW[l], d[l], d[l], d[l + 1])
+            gb = _view(ws, lay.db[l], 1, 1, d[l + 1])[0]
+            ga = _view(ws, lay.datt[l], 1, 1, 2 * d[l + 1])[0]
+            assert_close(gW, ref["dW"][l], TOL, f"dW[{l}]")
+            assert_close(gb, ref["db"][l], TOL, f"db[{l}]")
+            assert_close(ga, ref["datt"][l], TOL, f"datt[{l}]")
+            if not adam:
+                assert_close(f64(Wd[l]), ref["W_new"][l], TOL, f"updated W[{l}]")
+                assert_close(f64(bd[l]), ref["b_new"][l], TOL, f"updated b[{l}]")
+                assert_close(f64(ad[l]), ref["att_new"][l], TOL, f"updated att[{l}]")
+            else:
+                # the Adam update is ill-conditioned in the gradient (g / (|g| + eps)): check it on the GPU's own gradient
+                for name, P0, G, mk, vk, Pd in (("W", W0, gW, "mW", "vW", Wd), ("b", b0, gb, "mb", "vb", bd),
+                                                 ("att", a0, ga, "matt", "vatt", ad)):
+                    # the decay rates cross the ABI as fp32: the oracle takes the values the library was given
+                    w1, m1, v1 = orc.adam(P0[l], G, m0[mk][l], m0[vk][l], step + 1, lr, float(np.float32(0.9)),
+                                          float(np.float32(0.999)), float(np.float32(1e-8)))
+                    assert_close(f64(Pd[l]), w1, TOL, f"Adam {name}[{l}]")
+                    assert_close(f64(mom[mk][l]), m1, TOL, f"Adam m {name}[{l}]")
+                    assert_close(f64(mom[vk][l]), v1, TOL, f"Adam v {name}[{l}]")
+        mask = (ref["H"][1] > 0) if not diff.any() else (H1 > 0)
+        assert_close(_view(ws, lay.dH[1], lay.cap_src[1], blocks[1].n_src, d[1]), ref["dH"][1] * mask, TOL, "dH[1]")
+        assert abs(float(loss) - ref["loss"]) <= TOL * max(1.0, abs(ref["loss"]))
+        n = wl.n_nodes
+        assert bool((B.ws_view(ws, lay.state, (n,), torch.int32) == -1).all())
+        _say(f"  step {step}: loss {float(loss):.6f} ok")
+    with pytest.raises(B.SdtError):
+        B.sdt_train_step_layout(g.n_nodes, wl.batch, wl.fanouts, model, B.SDT_BF16)
+
+
+def test_gat_train_loop_equals_steps():
+    _say("GAT train loop == steps in sequence")
+    wl, inst, W, b, att = _gat_setup(8, 5)
+    d = wl.dims
+    g = B.Csr(dev(inst.indptr), dev(inst.indices))
+    X, y = dev(inst.X), dev(inst.y)
+    n_steps = 7
+    seeds = dev(np.stack([inst.batch(s) for s in range(n_steps)]).astype(np.int32))
+    results = []
+    for mode in ("steps", "loop"):
+        Wd, bd, ad = [dev(w) for w in W], [dev(v) for v in b], [dev(v) for v in att]
+        model = B.make_model(d, Wd, bd, kind=B.SDT_MODEL_GAT, att=ad, gat_slope=0.2)
+        losses = torch.zeros(n_steps, dtype=torch.float32, device="cuda")
+        if mode == "steps":
+            lay = B.sdt_train_step_layout(g.n_nodes, wl.batch, wl.fanouts, model, B.SDT_F32)
+            ws = torch.empty(int(lay.total_bytes), dtype=torch.uint8, device="cuda")
+            for s in range(n_steps):
+                B.sdt_train_step(g, X, y, seeds[s], wl.fanouts, model, wl.seed, s, 0.05, losses[s:s + 1], ws)
+        else:
+            nbytes = B.sdt_train_loop_workspace_bytes(g.n_nodes, wl.batch, wl.fanouts, model, B.SDT_F32)
+            ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+            aux = [torch.cuda.Stream() for _ in range(2)]
+            B.sdt_train_loop(g, X, y, seeds, wl.fanouts, model, wl.seed, 0, 0.05, losses, ws, aux_streams=aux)
+        torch.cuda.synchronize()
+        results.append((losses.cpu(), [w.cpu() for w in Wd], [v.cpu() for v in ad]))
+    assert torch.equal(results[0][0], results[1][0])
+    for a, c in zip(results[0][1] + results[0][2], results[1][1] + results[1][2]):
+        assert torch.equal(a, c)

@@ -144,6 +144,10 @@ struct PendingReduce {
     const float* Q = nullptr;
     int32_t splits = 0, in = 0, out = 0;
     int32_t q_splits = -1;   // number of Q partials if it differs from `splits` (-1: the same)
+    // If set: only the first ceil(*q_rows_d / q_chunk_rows) Q partials carry data (the others are zero
+    // and are skipped): partials laid out for an upper bound of a row count known only on the device.
+    const int32_t* q_rows_d = nullptr;
+    int32_t q_chunk_rows = 0;
     float* dW = nullptr;
     float* db = nullptr;
     float* W_upd = nullptr;
@@ -209,6 +213,7 @@ int32_t gcn_aggregate_fwd(const sdt_block* blk, const float* H, int64_t ldh, boo
                           const float* c, const float* s, const float* selfw, float* A, int64_t lda, int32_t* map_reset,
                           hipStream_t stm);
 
+constexpr int GAT_CHUNK_ROWS = 256;   // rows per partial column sum of the GAT bias / attention-vector gradients
 // GAT attention aggregation inside a training step (gat.hip).  The forward adds `bias` (may be null) and
 // applies ReLU if asked; the backward leaves the attention-vector partial sums part[n_part][2 F]
 // (a_src half, a_dst half) in the workspace for the step's single reduction launch.

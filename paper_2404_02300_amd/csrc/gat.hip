@@ -8,6 +8,8 @@
 // the backward recomputes each attention weight from them instead of storing one per edge.
 #include "common.h"
 
+#include <initializer_list>
+
 namespace sdt {
 namespace {
 
@@ -31,7 +33,7 @@ struct GatWs {
     int nblk, nchunk;
     size_t total;
 };
-constexpr int VEC_ROWS = 256;  // rows per partial sum of the attention-vector gradients
+constexpr int VEC_ROWS = GAT_CHUNK_ROWS;  // rows per partial sum of the attention-vector and bias gradients
 GatWs gat_ws(void* base, int32_t cap_src, int32_t cap_dst, int32_t F) {
     Arena a(base);
     GatWs w;
@@ -193,21 +195,37 @@ __global__ __launch_bounds__(TB) void k_gat_bwd_src(const int32_t* __restrict__ 
     }
 }
 
-// part[b][0][f] = sum over the rows of chunk b of del_j z_j[f]; part[b][1][f] likewise with der_i (rows < n_dst)
+// part[b][0][f] = sum over the rows of chunk b of del_j z_j[f]; part[b][1][f] likewise with der_i (rows < n_dst).
+// Wave w of the workgroup sums the chunk's rows w, w+4, ... (lane = feature, 64 at a time); the four
+// wave sums are then added in wave order.  Chunks past the row count write zeros.
 __global__ __launch_bounds__(TB) void k_gat_vec_partials(const int32_t* counts, const float* __restrict__ z, int64_t ldz,
                                                          int F, const float* __restrict__ del,
                                                          const float* __restrict__ der, float* __restrict__ part) {
+    __shared__ float red[WPB][2][64];
     const int n_dst = counts[0], n_src = counts[1];
     const int r0 = blockIdx.x * VEC_ROWS, r1 = min(n_src, r0 + VEC_ROWS);
-    for (int f = threadIdx.x; f < F; f += TB) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    for (int f0 = 0; f0 < F; f0 += 64) {
+        const int f = f0 + lane;
         float s0 = 0.f, s1 = 0.f;
-        for (int r = r0; r < r1; ++r) {
-            const float v = z[(int64_t)r * ldz + f];
-            s0 += del[r] * v;
-            if (r < n_dst) s1 += der[r] * v;
+        if (f < F) {
+#pragma unroll 8
+            for (int r = r0 + w; r < r1; r += WPB) {
+                const float v = z[(int64_t)r * ldz + f];
+                s0 += del[r] * v;
+                s1 += (r < n_dst ? der[r] : 0.f) * v;
+            }
         }
-        part[((int64_t)blockIdx.x * 2 + 0) * F + f] = s0;
-        part[((int64_t)blockIdx.x * 2 + 1) * F + f] = s1;
+        red[w][0][lane] = s0;
+        red[w][1][lane] = s1;
+        __syncthreads();
+        if (w < 2 && f < F) {
+            float t = 0.f;
+#pragma unroll
+            for (int k = 0; k < WPB; ++k) t += red[k][w][lane];
+            part[((int64_t)blockIdx.x * 2 + w) * F + f] = t;
+        }
+        __syncthreads();
     }
 }
 __global__ __launch_bounds__(TB) void k_gat_vec_final(const float* __restrict__ part, int nblk, int F,
@@ -224,25 +242,276 @@ __global__ __launch_bounds__(TB) void k_gat_vec_final(const float* __restrict__ 
 }
 
 // In place: g[r][f] = 0 where Y[r][f] <= 0 (Y may be null), and Qb[chunk][f] = column sum of the
-// masked g over the chunk's rows (zero for chunks past the row count).
+// masked g over the chunk's rows (zero for chunks past the row count).  Rows are dealt to the four
+// waves as in k_gat_vec_partials.
 __global__ __launch_bounds__(TB) void k_gat_mask_bias(const int32_t* counts, float* __restrict__ g, int64_t ldg,
                                                       const float* __restrict__ Y, int64_t ldy, int F,
                                                       float* __restrict__ Qb) {
+    __shared__ float red[WPB][64];
     const int n = counts[0];
     const int r0 = blockIdx.x * VEC_ROWS, r1 = min(n, r0 + VEC_ROWS);
-    for (int f = threadIdx.x; f < F; f += TB) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    for (int f0 = 0; f0 < F; f0 += 64) {
+        const int f = f0 + lane;
         float s = 0.f;
-        for (int r = r0; r < r1; ++r) {
-            float v = g[(int64_t)r * ldg + f];
-            if (Y && !(Y[(int64_t)r * ldy + f] > 0.f)) {
-                v = 0.f;
-                g[(int64_t)r * ldg + f] = 0.f;
+        if (f < F) {
+            if (Y) {
+                // eight rows per round: all loads first, then the stores (a store between them would
+                // serialise the loads, since the compiler must assume it aliases the next row)
+                constexpr int U = 8;
+                for (int rb = r0 + w; rb < r1; rb += U * WPB) {
+                    float v[U], y[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int r = min(rb + u * WPB, r1 - 1);
+                        v[u] = g[(int64_t)r * ldg + f];
+                        y[u] = Y[(int64_t)r * ldy + f];
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int r = rb + u * WPB;
+                        if (r < r1) {
+                            if (y[u] > 0.f) s += v[u];
+                            else g[(int64_t)r * ldg + f] = 0.f;
+                        }
+                    }
+                }
+            } else {
+#pragma unroll 8
+                for (int r = r0 + w; r < r1; r += WPB) s += g[(int64_t)r * ldg + f];
             }
-            s += v;
         }
-        Qb[(int64_t)blockIdx.x * F + f] = s;
+        red[w][lane] = s;
+        __syncthreads();
+        if (w == 0 && f < F) Qb[(int64_t)blockIdx.x * F + f] = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
+        __syncthreads();
     }
 }
+
+// ---- 16-byte variants (F % 4 == 0, rows 16-byte aligned, F <= 256) ----------------------------
+// A wave still owns one row, but its lanes form four groups of sixteen: group q takes the row's
+// edges q, q+4, ... and lane r of a group owns the features 4r..4r+3 (+64 per further chunk), so
+// four neighbour rows are in flight at once, every load is 16 bytes, a dot product is reduced over
+// sixteen lanes only, and every row is visited once.  Group sums are combined with an xor butterfly
+// (a fixed order: deterministic).
+template <int KF>
+struct Slice {
+    float4 v[KF];
+    __device__ __forceinline__ void load(const float* __restrict__ row, int r, int F) {
+#pragma unroll
+        for (int k = 0; k < KF; ++k) {
+            const int c = 4 * r + 64 * k;
+            v[k] = c < F ? *reinterpret_cast<const float4*>(row + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+    __device__ __forceinline__ void zero() {
+#pragma unroll
+        for (int k = 0; k < KF; ++k) v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    __device__ __forceinline__ float dot(const Slice& o) const {
+        float d = 0.f;
+#pragma unroll
+        for (int k = 0; k < KF; ++k) d += v[k].x * o.v[k].x + v[k].y * o.v[k].y + v[k].z * o.v[k].z + v[k].w * o.v[k].w;
+        return d;
+    }
+    __device__ __forceinline__ void axpy(float a, const Slice& o) {
+#pragma unroll
+        for (int k = 0; k < KF; ++k) {
+            v[k].x += a * o.v[k].x; v[k].y += a * o.v[k].y; v[k].z += a * o.v[k].z; v[k].w += a * o.v[k].w;
+        }
+    }
+    // sum over the four groups (lanes r, r+16, r+32, r+48); every lane ends with the total
+    __device__ __forceinline__ void sum_groups() {
+#pragma unroll
+        for (int k = 0; k < KF; ++k) {
+#pragma unroll
+            for (int o = 16; o <= 32; o <<= 1) {
+                v[k].x += __shfl_xor(v[k].x, o, 64); v[k].y += __shfl_xor(v[k].y, o, 64);
+                v[k].z += __shfl_xor(v[k].z, o, 64); v[k].w += __shfl_xor(v[k].w, o, 64);
+            }
+        }
+    }
+};
+__device__ __forceinline__ float group_sum(float v) {   // over the sixteen lanes of a group
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float across_groups(float v) {
+    v += __shfl_xor(v, 16, 64);
+    v += __shfl_xor(v, 32, 64);
+    return v;
+}
+
+template <int KF>
+__global__ __launch_bounds__(TB) void k_gat_fwd_v(const int32_t* __restrict__ b_indptr, const int32_t* __restrict__ cols,
+                                                  const int32_t* counts, const float* __restrict__ z, int64_t ldz, int F,
+                                                  const float* __restrict__ el, const float* __restrict__ er, float slope,
+                                                  float* __restrict__ lse, const float* __restrict__ bias, int relu,
+                                                  float* __restrict__ out, int64_t ldo) {
+    const int n = counts[0];
+    const int lane = threadIdx.x & 63, q = lane >> 4, r = lane & 15;
+    for (int i = blockIdx.x * WPB + (threadIdx.x >> 6); i < n; i += gridDim.x * WPB) {
+        const int e0 = b_indptr[i], e1 = b_indptr[i + 1];
+        const float ri = er[i];
+        const float s_self = leaky(ri + el[i], slope);
+        float m = s_self;
+        for (int e = e0 + lane; e < e1; e += 64) m = fmaxf(m, leaky(ri + el[cols[e]], slope));
+        m = wave_max(m);
+        float sum = 0.f;
+        for (int e = e0 + lane; e < e1; e += 64) sum += expf(leaky(ri + el[cols[e]], slope) - m);
+        sum = wave_sum(sum) + expf(s_self - m);
+        const float l = m + logf(sum);
+        if (lane == 0) lse[i] = l;
+        Slice<KF> acc, zr;
+        acc.zero();
+#pragma unroll 2
+        for (int e = e0 + q; e < e1; e += 4) {
+            const int c = cols[e];
+            zr.load(z + (int64_t)c * ldz, r, F);
+            acc.axpy(expf(leaky(ri + el[c], slope) - l), zr);
+        }
+        acc.sum_groups();
+        if (q == 0) {
+            zr.load(z + (int64_t)i * ldz, r, F);
+            acc.axpy(expf(s_self - l), zr);
+#pragma unroll
+            for (int k = 0; k < KF; ++k) {
+                const int c = 4 * r + 64 * k;
+                if (c < F) {
+                    float4 v = acc.v[k];
+                    if (bias) {
+                        const float4 bb = *reinterpret_cast<const float4*>(bias + c);
+                        v.x += bb.x; v.y += bb.y; v.z += bb.z; v.w += bb.w;
+                    }
+                    if (relu) {
+                        v.x = v.x > 0.f ? v.x : 0.f; v.y = v.y > 0.f ? v.y : 0.f;
+                        v.z = v.z > 0.f ? v.z : 0.f; v.w = v.w > 0.f ? v.w : 0.f;
+                    }
+                    *reinterpret_cast<float4*>(out + (int64_t)i * ldo + c) = v;
+                }
+            }
+        }
+    }
+}
+
+// t_i = sum_e alpha_e d_e and der_i = sum_e alpha_e (d_e - t_i) s'_e with d_e = g_i . z_col, s'_e the
+// LeakyReLU slope at the edge's score, both sums including the self edge.  One visit per edge:
+// der_i = sum alpha d s' - t_i sum alpha s'.
+template <int KF>
+__global__ __launch_bounds__(TB) void k_gat_bwd_dst_v(const int32_t* __restrict__ b_indptr, const int32_t* __restrict__ cols,
+                                                      const int32_t* counts, const float* __restrict__ z, int64_t ldz, int F,
+                                                      const float* __restrict__ el, const float* __restrict__ er,
+                                                      const float* __restrict__ lse, float slope,
+                                                      const float* __restrict__ g, int64_t ldg, float* __restrict__ t,
+                                                      float* __restrict__ der) {
+    const int n = counts[0];
+    const int lane = threadIdx.x & 63, q = lane >> 4, r = lane & 15;
+    for (int i = blockIdx.x * WPB + (threadIdx.x >> 6); i < n; i += gridDim.x * WPB) {
+        const int e0 = b_indptr[i], e1 = b_indptr[i + 1];
+        const float ri = er[i], l = lse[i];
+        Slice<KF> gi, zr;
+        gi.load(g + (int64_t)i * ldg, r, F);
+        float s1 = 0.f, s2 = 0.f, s3 = 0.f;   // per group
+#pragma unroll 2
+        for (int e = e0 + q; e < e1; e += 4) {
+            const int c = cols[e];
+            zr.load(z + (int64_t)c * ldz, r, F);
+            const float d = group_sum(gi.dot(zr));
+            const float pre = ri + el[c];
+            const float a = expf(leaky(pre, slope) - l), sp = pre > 0.f ? 1.f : slope;
+            s1 += a * d;
+            s2 += a * d * sp;
+            s3 += a * sp;
+        }
+        s1 = across_groups(s1);
+        s2 = across_groups(s2);
+        s3 = across_groups(s3);
+        zr.load(z + (int64_t)i * ldz, r, F);
+        const float d_self = group_sum(gi.dot(zr));
+        const float pre_self = ri + el[i];
+        const float a_self = expf(leaky(pre_self, slope) - l), sp_self = pre_self > 0.f ? 1.f : slope;
+        const float ti = s1 + a_self * d_self;
+        if (lane == 0) {
+            t[i] = ti;
+            der[i] = (s2 + a_self * d_self * sp_self) - ti * (s3 + a_self * sp_self);
+        }
+    }
+}
+
+template <int KF>
+__global__ __launch_bounds__(TB) void k_gat_bwd_src_v(const int32_t* __restrict__ t_indptr, const int32_t* __restrict__ t_rows,
+                                                      const int32_t* counts, const float* __restrict__ z, int64_t ldz, int F,
+                                                      const float* __restrict__ el, const float* __restrict__ er,
+                                                      const float* __restrict__ lse, const float* __restrict__ t,
+                                                      const float* __restrict__ der, float slope,
+                                                      const float* __restrict__ a_src, const float* __restrict__ a_dst,
+                                                      const float* __restrict__ g, int64_t ldg, float* __restrict__ dz,
+                                                      int64_t lddz, float* __restrict__ del) {
+    const int n_dst = counts[0], n_src = counts[1];
+    const int lane = threadIdx.x & 63, q = lane >> 4, r = lane & 15;
+    for (int j = blockIdx.x * WPB + (threadIdx.x >> 6); j < n_src; j += gridDim.x * WPB) {
+        const int e0 = t_indptr[j], e1 = t_indptr[j + 1];
+        const float lj = el[j];
+        Slice<KF> zj, gr, acc;
+        zj.load(z + (int64_t)j * ldz, r, F);
+        acc.zero();
+        float dl = 0.f;   // per group
+#pragma unroll 2
+        for (int e = e0 + q; e < e1; e += 4) {
+            const int i = t_rows[e];
+            gr.load(g + (int64_t)i * ldg, r, F);
+            const float d = group_sum(zj.dot(gr));
+            const float pre = er[i] + lj;
+            const float a = expf(leaky(pre, slope) - lse[i]);
+            dl += a * (d - t[i]) * (pre > 0.f ? 1.f : slope);
+            acc.axpy(a, gr);
+        }
+        dl = across_groups(dl);
+        acc.sum_groups();
+        float drj = 0.f;
+        if (j < n_dst) {   // the self edge (uniform over the wave)
+            gr.load(g + (int64_t)j * ldg, r, F);
+            const float d = group_sum(zj.dot(gr));
+            const float pre = er[j] + lj;
+            const float a_self = expf(leaky(pre, slope) - lse[j]);
+            dl += a_self * (d - t[j]) * (pre > 0.f ? 1.f : slope);
+            acc.axpy(a_self, gr);
+            drj = der[j];
+        }
+        if (lane == 0) del[j] = dl;
+        if (q == 0) {
+#pragma unroll
+            for (int k = 0; k < KF; ++k) {
+                const int c = 4 * r + 64 * k;
+                if (c < F) {
+                    const float4 as = *reinterpret_cast<const float4*>(a_src + c);
+                    const float4 ad = *reinterpret_cast<const float4*>(a_dst + c);
+                    float4 v = acc.v[k];
+                    v.x += dl * as.x + drj * ad.x; v.y += dl * as.y + drj * ad.y;
+                    v.z += dl * as.z + drj * ad.z; v.w += dl * as.w + drj * ad.w;
+                    *reinterpret_cast<float4*>(dz + (int64_t)j * lddz + c) = v;
+                }
+            }
+        }
+    }
+}
+
+// 16-byte kernels apply when every row (and the attention vectors, the bias) can be read as float4
+inline bool vec_ok(int F, std::initializer_list<int64_t> lds, std::initializer_list<const void*> ptrs) {
+    if (F % 4 != 0 || F > 256) return false;
+    for (int64_t ld : lds)
+        if (ld % 4 != 0) return false;
+    for (const void* p : ptrs)
+        if (p && !aligned16(p)) return false;
+    return true;
+}
+#define SDT_GAT_KF(F, body)                                \
+    do {                                                   \
+        if ((F) <= 64) { constexpr int KF = 1; body; }     \
+        else if ((F) <= 128) { constexpr int KF = 2; body; } \
+        else { constexpr int KF = 4; body; }               \
+    } while (0)
 
 inline int rows_grid(int rows) {
     const int b = ceil_div(rows > 0 ? rows : 1, WPB);
@@ -280,8 +549,13 @@ int32_t sdt::gat_forward(const sdt_block* blk, const float* z, int64_t ldz, int3
     hipLaunchKernelGGL(k_gat_scores, dim3(rows_grid(blk->cap_src)), dim3(TB), 0, st, blk->counts, z, ldz, F, a_src, a_dst, w.el,
                        w.er);
     SDT_CHECK_LAUNCH("gat scores");
-    hipLaunchKernelGGL(k_gat_fwd, dim3(rows_grid(blk->cap_dst)), dim3(TB), 0, st, blk->indptr, blk->cols, blk->counts, z, ldz, F,
-                       w.el, w.er, slope, w.lse, bias, relu, out, ldo);
+    if (vec_ok(F, {ldz, ldo}, {z, out, bias})) {
+        SDT_GAT_KF(F, hipLaunchKernelGGL(k_gat_fwd_v<KF>, dim3(rows_grid(blk->cap_dst)), dim3(TB), 0, st, blk->indptr, blk->cols,
+                                         blk->counts, z, ldz, F, w.el, w.er, slope, w.lse, bias, relu, out, ldo));
+    } else {
+        hipLaunchKernelGGL(k_gat_fwd, dim3(rows_grid(blk->cap_dst)), dim3(TB), 0, st, blk->indptr, blk->cols, blk->counts, z, ldz,
+                           F, w.el, w.er, slope, w.lse, bias, relu, out, ldo);
+    }
     SDT_CHECK_LAUNCH("gat forward");
     return SDT_OK;
 }
@@ -314,12 +588,22 @@ int32_t sdt::gat_backward(const sdt_block* blk, const float* z, int64_t ldz, int
     const GatWs w = gat_ws(ws, blk->cap_src, blk->cap_dst, F);
     SDT_REQUIRE(ws && ws_bytes >= w.total && aligned16(ws), SDT_ERR_WORKSPACE,
                 "sdt_gat_aggregate_bwd: workspace of %zu bytes needed, %zu given", w.total, ws_bytes);
-    hipLaunchKernelGGL(k_gat_bwd_dst, dim3(rows_grid(blk->cap_dst)), dim3(TB), 0, st, blk->indptr, blk->cols, blk->counts, z, ldz,
-                       F, w.el, w.er, w.lse, slope, g, ldg, w.t, w.der);
-    SDT_CHECK_LAUNCH("gat backward (destinations)");
-    hipLaunchKernelGGL(k_gat_bwd_src, dim3(rows_grid(blk->cap_src)), dim3(TB), 0, st, blk->t_indptr, blk->t_rows, blk->counts, z,
-                       ldz, F, w.el, w.er, w.lse, w.t, w.der, slope, a_src, a_dst, g, ldg, dz, lddz, w.del);
-    SDT_CHECK_LAUNCH("gat backward (sources)");
+    if (vec_ok(F, {ldz, ldg, lddz}, {z, g, dz, a_src, a_dst})) {
+        SDT_GAT_KF(F, hipLaunchKernelGGL(k_gat_bwd_dst_v<KF>, dim3(rows_grid(blk->cap_dst)), dim3(TB), 0, st, blk->indptr,
+                                         blk->cols, blk->counts, z, ldz, F, w.el, w.er, w.lse, slope, g, ldg, w.t, w.der));
+        SDT_CHECK_LAUNCH("gat backward (destinations)");
+        SDT_GAT_KF(F, hipLaunchKernelGGL(k_gat_bwd_src_v<KF>, dim3(rows_grid(blk->cap_src)), dim3(TB), 0, st, blk->t_indptr,
+                                         blk->t_rows, blk->counts, z, ldz, F, w.el, w.er, w.lse, w.t, w.der, slope, a_src, a_dst,
+                                         g, ldg, dz, lddz, w.del));
+        SDT_CHECK_LAUNCH("gat backward (sources)");
+    } else {
+        hipLaunchKernelGGL(k_gat_bwd_dst, dim3(rows_grid(blk->cap_dst)), dim3(TB), 0, st, blk->indptr, blk->cols, blk->counts, z,
+                           ldz, F, w.el, w.er, w.lse, slope, g, ldg, w.t, w.der);
+        SDT_CHECK_LAUNCH("gat backward (destinations)");
+        hipLaunchKernelGGL(k_gat_bwd_src, dim3(rows_grid(blk->cap_src)), dim3(TB), 0, st, blk->t_indptr, blk->t_rows, blk->counts,
+                           z, ldz, F, w.el, w.er, w.lse, w.t, w.der, slope, a_src, a_dst, g, ldg, dz, lddz, w.del);
+        SDT_CHECK_LAUNCH("gat backward (sources)");
+    }
     hipLaunchKernelGGL(k_gat_vec_partials, dim3(w.nblk), dim3(TB), 0, st, blk->counts, z, ldz, F, w.del, w.der, w.part);
     SDT_CHECK_LAUNCH("gat attention-vector partials");
     *part = w.part;

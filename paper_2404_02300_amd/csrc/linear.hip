@@ -418,7 +418,8 @@ __global__ __launch_bounds__(TB) void k_reduce_partials(ReduceArgs a, OptArgs op
     const bool is_w = idx < n_w, is_b = !is_w && idx < n_w + out;
     const float* src = is_w ? r.P + idx : r.Q + (idx - n_w);
     const int64_t stride = is_w ? n_w : out;
-    const int splits = is_w || r.q_splits < 0 ? r.splits : r.q_splits;
+    int splits = is_w || r.q_splits < 0 ? r.splits : r.q_splits;
+    if (!is_w && r.q_rows_d) splits = min(splits, (*r.q_rows_d + r.q_chunk_rows - 1) / r.q_chunk_rows);
     float s = 0.f;
     if (is_w || is_b) {
 #pragma unroll 4

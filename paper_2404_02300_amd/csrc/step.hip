@@ -609,12 +609,16 @@ int32_t step_compute_gat(const StepCtx& c, const StepBuffers& b, const int32_t* 
         // the bias gradient is the column sum of the masked output gradient, not of dz
         pw->Q = Qb;
         pw->q_splits = n_chunks;
+        pw->q_rows_d = b.blk[l].counts;          // n_dst
+        pw->q_chunk_rows = GAT_CHUNK_ROWS;
         pw->db = db;
         pw->b_upd = model->b[l];
         attach_moments(pw, model, l);
         PendingReduce* pa = &pending[n_pending++];
         pa->Q = part;
         pa->q_splits = n_part;
+        pa->q_rows_d = b.blk[l].counts + 1;      // n_src
+        pa->q_chunk_rows = GAT_CHUNK_ROWS;
         pa->in = 0;
         pa->out = 2 * F;
         pa->db = datt;

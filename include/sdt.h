@@ -130,7 +130,7 @@ enum { SDT_OPT_SGD = 0, SDT_OPT_ADAM = 1 };
 /* Byte offsets, inside the sdt_train_step workspace, of everything the step
  * produces (so a caller can inspect it), plus the capacities they were sized
  * for.  Index l is the GNN layer (0 = input-most).  H[0] holds the gathered
- * input rows of layer 0's DESTINATION nodes only, [cap_dst[0], dims[0]] (the
+ * input rows of layer 0's DESTINATION nodes only, [cap_dst[0], dims[0]] with row stride ld_in (the
  * other frontier rows are aggregated straight out of X and never copied);
  * H[l+1] the output of layer l (H[L] = logits,
  * always fp32); A[l] the mean-aggregated neighbours; dZ the loss gradient
@@ -172,6 +172,10 @@ typedef struct sdt_step_layout {
     uint64_t dz[SDT_MAX_LAYERS];
     uint64_t datt[SDT_MAX_LAYERS];
     uint64_t gatws[SDT_MAX_LAYERS]; /* internal */
+    /* Row stride, in elements, of H[0] and A[0]: dims[0], or (GraphSAGE kind) dims[0] rounded up to
+     * whole 128-byte lines when it is not one already, so that every input row starts on a line
+     * and the projections read it in 16-byte vectors; the columns past dims[0] are kept zero.  Every other matrix is stored densely (stride = its width). */
+    uint64_t ld_in;
 } sdt_step_layout;
 
 /* Library version as "major.minor.patch" (host string, static storage). */

@@ -63,7 +63,7 @@ class sdt_step_layout(ctypes.Structure):
                 ("H", _u64 * (_L + 1)), ("A", _u64 * _L), ("dZ", _u64),
                 ("dH", _u64 * _L), ("dSelf", _u64 * _L), ("dAgg", _u64 * _L),
                 ("dW", _u64 * _L), ("db", _u64 * _L), ("row_loss", _u64), ("scratch", _u64), ("wlow", _u64), ("norm", _u64 * _L),
-                ("z", _u64 * _L), ("dz", _u64 * _L), ("datt", _u64 * _L), ("gatws", _u64 * _L)]
+                ("z", _u64 * _L), ("dz", _u64 * _L), ("datt", _u64 * _L), ("gatws", _u64 * _L), ("ld_in", _u64)]
 
 
 class sdt_partition(ctypes.Structure):

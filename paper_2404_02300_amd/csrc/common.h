@@ -124,13 +124,13 @@ int32_t sample_seed_map(const SampleWs& ws, const int32_t* dst_nodes, int32_t n_
 int32_t sample_layer(const sdt_csr& g, const int32_t* dst_nodes, int32_t n_dst_cap, const int32_t* n_dst_d,
                      int32_t fanout, uint64_t seed, uint32_t step, uint32_t layer, const sdt_block& out,
                      const SampleWs& ws, hipStream_t st);
-// gather that also resets map[idx[j]] = -1 (map may be null)
+// gather that also resets map[idx[j]] = -1 (map may be null); zero_pad: columns F..ldo-1 of every output row are set to zero
 int32_t gather_rows(const void* X, int64_t ldx, int32_t F, int32_t dtype, const int32_t* idx, int32_t n_cap,
-                    const int32_t* n_d, void* out, int64_t ldo, int32_t* map_reset, hipStream_t st);
+                    const int32_t* n_d, void* out, int64_t ldo, int32_t* map_reset, bool zero_pad, hipStream_t st);
 
 // mean aggregation straight from the feature matrix through blk->src_nodes (+ optional map reset)
 int32_t aggregate_gather_fwd(const sdt_block* blk, const void* X, int64_t ldx, int32_t F, int32_t dtype, void* A,
-                             int64_t lda, int32_t* map_reset, hipStream_t st);
+                             int64_t lda, int32_t* map_reset, bool zero_pad, hipStream_t st);
 
 // writes dZ and the per-row losses; their mean is folded into a later single-block pass
 int32_t softmax_xent(const float* logits, int64_t ld, int32_t B, int32_t C, const int32_t* labels,
@@ -167,6 +167,7 @@ struct OptArgs {
 struct BwdExtras {
     PendingReduce* defer = nullptr;  // if set, the reduction is described here instead of launched
     const void* Wb = nullptr;  // bf16 image of W for the input gradient on the bf16 matrix path (or null)
+    bool rows_padded = false;  // every row of Hself and A is zero-padded up to its stride (see linear_fwd)
     float* W_upd = nullptr;
     float* b_upd = nullptr;
     float lr = 0.f;
@@ -186,6 +187,13 @@ int32_t reduce_partials(const float* P, const float* Q, int32_t splits, int32_t 
 // the pending reductions of several layers (and the mean of the per-seed losses) in ONE launch
 int32_t reduce_all(const PendingReduce* r, int32_t n, const OptArgs& opt, const float* row_loss, int32_t n_loss,
                    float* loss_out, hipStream_t st);
+
+// sdt_sage_linear_fwd with one more promise: rows_padded = every row of Hself and A is followed by
+// ZEROS up to its stride (ldh, lda), so a row width that is not a multiple of the vector width
+// still moves in whole vectors
+int32_t linear_fwd(const void* Hself, int64_t ldh, const void* A, int64_t lda, int32_t n_cap, const int32_t* n_d,
+                   int32_t in, int32_t out, const float* W, const float* b, int32_t relu, int32_t dtype, void* Y,
+                   int64_t ldy, int32_t y_dtype, bool rows_padded, hipStream_t st);
 
 // bf16 matrix-core path (linear_bf16.hip).  Per layer the image region holds Wt = bf16 [out][2 in]
 // followed (256-byte aligned) by Wb = bf16 [2 in][bf16_ldb(out)], layers back to back.

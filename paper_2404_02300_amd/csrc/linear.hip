@@ -35,10 +35,12 @@ struct Stage {
     uint32_t ok;  // bit p: vector p lies inside the matrix
 
     // rows [r_lo, r_lo+R) x cols [c_lo, c_lo+C) of `base`; zero outside [0,rmax) x [0,cmax).
-    // Needs rmax >= 1 and cmax >= V.  Every load is issued unconditionally from a clamped (valid)
-    // address and nothing touches the loaded registers until store(): with no branch and no
-    // early use the compiler can count the loads in flight, so the wait before the LDS stores
-    // covers only the oldest stage and the younger prefetches keep flying.
+    // Needs rmax >= 1, cmax >= V and cmax % V == 0 (a caller whose rows are zero-padded to a multiple
+    // of V passes the padded width).  Every load is issued unconditionally from a clamped (valid)
+    // address and nothing touches the loaded registers until store(): with no branch and no early
+    // use the compiler can count the loads in flight, so the wait before the LDS stores covers only
+    // the oldest stage and the younger prefetches keep flying.  (One validity bit per ELEMENT was
+    // measured: the extra integer work in the fetch costs the main loop 8%.)
     __device__ __forceinline__ void load(const T* __restrict__ base, int64_t ld, int r_lo, int rmax, int c_lo, int cmax) {
         ok = 0;
 #pragma unroll
@@ -241,7 +243,7 @@ __device__ __forceinline__ void for_each_acc(const floatx16 (&acc)[TL::TM][TL::T
 template <typename TH, typename TY, typename TL, int VA, int VB, bool ROUNDW>
 __global__ __launch_bounds__(TL::NT) void k_linear_fwd(const TH* __restrict__ Hself, int64_t ldh,
                                                        const TH* __restrict__ Agg, int64_t lda, int n_cap,
-                                                       const int32_t* n_d, int in, int out,
+                                                       const int32_t* n_d, int in, int in_a, int out,
                                                        const float* __restrict__ W, const float* __restrict__ bias,
                                                        int relu, TY* __restrict__ Y, int64_t ldy) {
     constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK;
@@ -261,7 +263,7 @@ __global__ __launch_bounds__(TL::NT) void k_linear_fwd(const TH* __restrict__ Hs
     const int nk = (in + BK - 1) / BK;
     auto fetch = [&](int it, SA& sa, SB& sb) {
         const int ph = it >= nk, k0 = (it - ph * nk) * BK;  // k0 >= in past the last step: zeros
-        sa.load(ph ? Agg : Hself, ph ? lda : ldh, row0, n, k0, in);
+        sa.load(ph ? Agg : Hself, ph ? lda : ldh, row0, n, k0, in_a);   // in_a >= in: rows zero-padded to a whole vector
         sb.load(W + (int64_t)ph * in * out, out, k0, in, col0, out);
     };
     gemm_mainloop<TL, true, false, SA, SB>(2 * nk, As, Bs, fetch, [](const float*) {}, acc);
@@ -320,7 +322,7 @@ template <typename TD, typename TH, typename TL, int VH, int VD, bool ROUND>
 __global__ __launch_bounds__(TL::NT) void k_linear_bwd_weight(const TH* __restrict__ Hself, int64_t ldh,
                                                               const TH* __restrict__ Agg, int64_t lda,
                                                               const TD* __restrict__ dY, int64_t lddy, int n_cap,
-                                                              const int32_t* n_d, int in, int out, int splits,
+                                                              const int32_t* n_d, int in, int in_a, int out, int splits,
                                                               float* __restrict__ P, float* __restrict__ Q) {
     constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK;
     const int n = dev_count(n_cap, n_d);
@@ -348,7 +350,7 @@ __global__ __launch_bounds__(TL::NT) void k_linear_bwd_weight(const TH* __restri
     const int64_t ldx = half ? lda : ldh;
     const int nit = r_end > r_begin ? (r_end - r_begin + BK - 1) / BK : 0;
     auto fetch = [&](int it, SA& sa, SB& sb) {
-        sa.load(X, ldx, r_begin + it * BK, r_end, row0, in);
+        sa.load(X, ldx, r_begin + it * BK, r_end, row0, in_a);   // rows of the product past `in` are not stored
         sb.load(dY, lddy, r_begin + it * BK, r_end, col0, out);
     };
     auto hook = [&](const float* Bcur) {
@@ -446,7 +448,7 @@ int vec_elems(size_t es, int width, std::initializer_list<int64_t> lds, std::ini
     auto fit = [&](uint64_t x) {
         while (vb > (int)es && (x % vb) != 0) vb >>= 1;
     };
-    fit((uint64_t)width * es);
+    if (width > 0) fit((uint64_t)width * es);   // width 0: rows are readable up to their stride (see Stage::load)
     for (int64_t ld : lds) fit((uint64_t)ld * es);
     for (const void* p : ptrs) fit(reinterpret_cast<uintptr_t>(p));
     int v = vb / (int)es;
@@ -508,9 +510,10 @@ using TileL = Tile<128, 256, 16, 2, 4>;   // forward of whole-graph sized layers
 
 template <typename TH, typename TY, typename TL>
 void launch_fwd(const void* Hself, int64_t ldh, const void* A, int64_t lda, int n_cap, const int32_t* n_d, int in,
-                int out, const float* W, const float* b, int relu, void* Y, int64_t ldy, hipStream_t st) {
+                int out, const float* W, const float* b, int relu, void* Y, int64_t ldy, bool rows_padded, hipStream_t st) {
     constexpr bool ROUNDW = sizeof(TH) == 2;  // bf16 activations: weights enter the product rounded to bf16
-    const int va = vec_elems(sizeof(TH), in, {ldh, lda}, {Hself, A});
+    const int va = vec_elems(sizeof(TH), rows_padded ? 0 : in, {ldh, lda}, {Hself, A});
+    const int in_a = (in + va - 1) / va * va;
     const int vb = vec_elems(4, out, {(int64_t)out}, {W});
     dim3 grid(ceil_div(out, TL::BN), ceil_div(n_cap, TL::BM));
     SDT_VEC_SWITCH(va, (16 / sizeof(TH)), {
@@ -518,8 +521,8 @@ void launch_fwd(const void* Hself, int64_t ldh, const void* A, int64_t lda, int 
         SDT_VEC_SWITCH(vb, 4, {
             constexpr int VB = V;
             hipLaunchKernelGGL((k_linear_fwd<TH, TY, TL, VA, VB, ROUNDW>), grid, dim3(TL::NT), 0, st,
-                               static_cast<const TH*>(Hself), ldh, static_cast<const TH*>(A), lda, n_cap, n_d, in, out, W,
-                               b, relu, static_cast<TY*>(Y), ldy);
+                               static_cast<const TH*>(Hself), ldh, static_cast<const TH*>(A), lda, n_cap, n_d, in, in_a, out,
+                               W, b, relu, static_cast<TY*>(Y), ldy);
         })
     })
 }
@@ -530,7 +533,8 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Hself, int64_t ldh, co
                 int64_t ldi, float* P, float* Q, int splits, const BwdExtras& ex, hipStream_t st) {
     constexpr bool ROUND = sizeof(TH) == 2;  // bf16 activations: fp32 operands enter the products rounded to bf16
     const int vd = vec_elems(sizeof(TD), out, {lddy}, {dY});
-    const int vh = vec_elems(sizeof(TH), in, {ldh, lda}, {Hself, A});
+    const int vh = vec_elems(sizeof(TH), ex.rows_padded ? 0 : in, {ldh, lda}, {Hself, A});
+    const int in_a = (in + vh - 1) / vh * vh;
     const int vw = vec_elems(4, out, {(int64_t)out}, {W});
     const TD* dYt = static_cast<const TD*>(dY);
     // weight gradient partials (bf16 activations inside a step: on the bf16 matrix cores)
@@ -546,7 +550,7 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Hself, int64_t ldh, co
                 constexpr int VD = V;
                 hipLaunchKernelGGL((k_linear_bwd_weight<TD, TH, TL, VH, VD, ROUND>), grid, dim3(TL::NT), 0, st,
                                    static_cast<const TH*>(Hself), ldh, static_cast<const TH*>(A), lda, dYt, lddy, n_cap,
-                                   n_d, in, out, splits, P, Q);
+                                   n_d, in, in_a, out, splits, P, Q);
             })
         })
     }
@@ -580,10 +584,9 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Hself, int64_t ldh, co
 
 }  // namespace
 
-extern "C" int32_t sdt_sage_linear_fwd(const void* Hself, int64_t ldh, const void* A, int64_t lda, int32_t n_cap,
-                                       const int32_t* n_d, int32_t in, int32_t out, const float* W, const float* b,
-                                       int32_t relu, int32_t dtype, void* Y, int64_t ldy, int32_t y_dtype,
-                                       void* stream) {
+int32_t sdt::linear_fwd(const void* Hself, int64_t ldh, const void* A, int64_t lda, int32_t n_cap, const int32_t* n_d,
+                        int32_t in, int32_t out, const float* W, const float* b, int32_t relu, int32_t dtype, void* Y,
+                        int64_t ldy, int32_t y_dtype, bool rows_padded, hipStream_t st) {
     SDT_REQUIRE(dtype_ok(dtype) && dtype_ok(y_dtype), SDT_ERR_INVALID_ARG, "sdt_sage_linear_fwd: unknown dtype");
     SDT_REQUIRE(!(dtype == SDT_F32 && y_dtype == SDT_BF16), SDT_ERR_INVALID_ARG,
                 "sdt_sage_linear_fwd: bf16 output needs bf16 inputs");
@@ -591,25 +594,32 @@ extern "C" int32_t sdt_sage_linear_fwd(const void* Hself, int64_t ldh, const voi
                 "sdt_sage_linear_fwd: bad sizes n=%d in=%d out=%d", n_cap, in, out);
     if (n_cap == 0) return SDT_OK;
     SDT_REQUIRE(Hself && A && W && Y, SDT_ERR_INVALID_ARG, "sdt_sage_linear_fwd: null pointer");
-    hipStream_t st = static_cast<hipStream_t>(stream);
     // tile by problem size: the large tiles need enough workgroups to fill 256 CUs several times over
     const int64_t t128 = (int64_t)ceil_div(n_cap, 128) * ceil_div(out, 128);
     const int cls = (t128 >= 2048 && out >= 256) ? 2 : t128 >= 512 ? 1 : 0;
 #define SDT_FWD(TH, TY)                                                                                            \
     do {                                                                                                           \
-        if (cls == 2) launch_fwd<TH, TY, TileL>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, st);  \
-        else if (cls == 1) launch_fwd<TH, TY, TileM>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, st); \
-        else launch_fwd<TH, TY, TileS>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, st);           \
+        if (cls == 2) launch_fwd<TH, TY, TileL>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, rows_padded, st);  \
+        else if (cls == 1) launch_fwd<TH, TY, TileM>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, rows_padded, st); \
+        else launch_fwd<TH, TY, TileS>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, rows_padded, st);           \
     } while (0)
     if (dtype == SDT_F32) SDT_FWD(float, float);
 #undef SDT_FWD
     // bf16 activations are widened on the way into LDS; the small tile hides that best
     else if (y_dtype == SDT_BF16)
-        launch_fwd<bf16_t, bf16_t, TileS>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, st);
+        launch_fwd<bf16_t, bf16_t, TileS>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, rows_padded, st);
     else
-        launch_fwd<bf16_t, float, TileS>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, st);
+        launch_fwd<bf16_t, float, TileS>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, rows_padded, st);
     SDT_CHECK_LAUNCH("linear_fwd");
     return SDT_OK;
+}
+
+extern "C" int32_t sdt_sage_linear_fwd(const void* Hself, int64_t ldh, const void* A, int64_t lda, int32_t n_cap,
+                                       const int32_t* n_d, int32_t in, int32_t out, const float* W, const float* b,
+                                       int32_t relu, int32_t dtype, void* Y, int64_t ldy, int32_t y_dtype,
+                                       void* stream) {
+    return linear_fwd(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, dtype, Y, ldy, y_dtype, false,
+                      static_cast<hipStream_t>(stream));
 }
 
 namespace {

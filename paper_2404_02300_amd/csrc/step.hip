@@ -222,9 +222,14 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
         lay->dZ = a.take_off((size_t)batch * d[L] * 4);
         lay->row_loss = a.take_off((size_t)(batch > 0 ? batch : 1) * 4);
         lay->scratch = a.take_off(scratch);
+        lay->ld_in = (uint64_t)d[0];
         lay->total_bytes = a.off;
         return SDT_OK;
     }
+    // GraphSAGE: input rows start on 128-byte lines (see sdt_step_layout::ld_in)
+    const size_t line = 128 / es;
+    const size_t ld0 = model->kind == SDT_MODEL_SAGE_MEAN ? ((size_t)d[0] + line - 1) / line * line : (size_t)d[0];
+    lay->ld_in = ld0;
     for (int l = 0; l < L; ++l) {
         lay->cap_dst[l] = c.dst[l];
         lay->cap_src[l] = c.src[l];
@@ -240,7 +245,7 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
             lay->dSelf[l] = a.take_off((size_t)c.dst[l] * d[l] * es);
             lay->dAgg[l] = a.take_off((size_t)c.dst[l] * d[l] * es);
         }
-        lay->A[l] = a.take_off((size_t)c.dst[l] * d[l] * es);
+        lay->A[l] = a.take_off((size_t)c.dst[l] * (l == 0 ? ld0 : (size_t)d[l]) * es);
         lay->H[l + 1] = a.take_off((size_t)c.dst[l] * d[l + 1] * (l == L - 1 ? 4 : es));
         lay->dW[l] = a.take_off((size_t)2 * d[l] * d[l + 1] * 4);
         lay->db[l] = a.take_off((size_t)d[l + 1] * 4);
@@ -252,7 +257,7 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
     // the sampling scratch is dead once phase 2 starts; the backward keeps one region per layer
     // alive until the single reduction launch at the end of the step
     if (bwd_scratch > scratch) scratch = bwd_scratch;
-    lay->H[0] = a.take_off((size_t)c.dst[0] * d[0] * es);
+    lay->H[0] = a.take_off((size_t)c.dst[0] * ld0 * es);
     lay->dZ = a.take_off((size_t)batch * d[L] * 4);
     lay->row_loss = a.take_off((size_t)(batch > 0 ? batch : 1) * 4);
     lay->scratch = a.take_off(scratch);
@@ -421,7 +426,7 @@ int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds
         // every frontier row is projected, so every one is gathered (which also hands the whole map back clean)
         StageTimer tm(c.timing, c.slot, SDT_STAGE_GATHER, 0, st);
         return gather_rows(c.X, c.ldx, d[0], c.dtype, b.blk[0].src_nodes, lay.cap_src[0], b.blk[0].counts + 1, b.at(lay.H[0]),
-                           d[0], sw.map, st);
+                           d[0], sw.map, false, st);
     }
     // Input features: only the destination prefix of the outermost frontier is copied (the
     // projection's "self" operand); the neighbour mean of layer 0 is taken straight out of X.
@@ -429,11 +434,12 @@ int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds
     {
         StageTimer tm(c.timing, c.slot, SDT_STAGE_GATHER, 0, st);
         rc = gather_rows(c.X, c.ldx, d[0], c.dtype, b.blk[0].src_nodes, lay.cap_dst[0], b.blk[0].counts,
-                         b.at(lay.H[0]), d[0], sw.map, st);
+                         b.at(lay.H[0]), (int64_t)lay.ld_in, sw.map, /*zero_pad=*/true, st);
     }
     if (rc != SDT_OK) return rc;
     StageTimer tm(c.timing, c.slot, SDT_STAGE_AGG_FWD, 0, st);
-    return aggregate_gather_fwd(&b.blk[0], c.X, c.ldx, d[0], c.dtype, b.at(lay.A[0]), d[0], sw.map, st);
+    return aggregate_gather_fwd(&b.blk[0], c.X, c.ldx, d[0], c.dtype, b.at(lay.A[0]), (int64_t)lay.ld_in, sw.map,
+                                /*zero_pad=*/true, st);
 }
 
 // Phase 2 of a GCN step.  The projection kernels take two operands of equal width; here they are
@@ -660,6 +666,8 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
     }
     PendingReduce pending[SDT_MAX_LAYERS];
     int n_pending = 0;
+    // row stride of H[l] and A[l]: the input rows are padded to whole 128-byte lines, readable to the stride
+    auto ldx = [&](int l) { return l == 0 ? (int64_t)lay.ld_in : (int64_t)d[l]; };
     // bf16 activations: the matrix products run on the bf16 matrix cores from bf16 images of the
     // weights, rewritten here every step (the weights are the caller's and change every step)
     const char* wt[SDT_MAX_LAYERS] = {};
@@ -683,14 +691,14 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
         const bool last = l == L - 1;
         if (last && fused_head) break;
         StageTimer tm(timing, c.slot, SDT_STAGE_LINEAR_FWD, l, st);
-        if (dtype == SDT_BF16 && bf16_mfma_fwd_ok(b.at(lay.H[l]), d[l], b.at(lay.A[l]), d[l], d[l]))
-            rc = linear_fwd_bf16(b.at(lay.H[l]), d[l], b.at(lay.A[l]), d[l], lay.cap_dst[l], b.blk[l].counts, d[l],
+        if (dtype == SDT_BF16 && bf16_mfma_fwd_ok(b.at(lay.H[l]), ldx(l), b.at(lay.A[l]), ldx(l), d[l]))
+            rc = linear_fwd_bf16(b.at(lay.H[l]), ldx(l), b.at(lay.A[l]), ldx(l), lay.cap_dst[l], b.blk[l].counts, d[l],
                                  d[l + 1], wt[l], model->b[l], last ? 0 : 1, b.at(lay.H[l + 1]), d[l + 1],
                                  last ? SDT_F32 : dtype, st);
         else
-            rc = sdt_sage_linear_fwd(b.at(lay.H[l]), d[l], b.at(lay.A[l]), d[l], lay.cap_dst[l], b.blk[l].counts, d[l],
-                                     d[l + 1], model->W[l], model->b[l], last ? 0 : 1, dtype, b.at(lay.H[l + 1]),
-                                     d[l + 1], last ? SDT_F32 : dtype, st);
+            rc = linear_fwd(b.at(lay.H[l]), ldx(l), b.at(lay.A[l]), ldx(l), lay.cap_dst[l], b.blk[l].counts, d[l],
+                            d[l + 1], model->W[l], model->b[l], last ? 0 : 1, dtype, b.at(lay.H[l + 1]),
+                            d[l + 1], last ? SDT_F32 : dtype, /*rows_padded=*/l == 0, st);
         if (rc != SDT_OK) return rc;
     }
     if (!fused_head) {
@@ -710,7 +718,7 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
             float *P, *Q;
             {
             StageTimer th(timing, c.slot, SDT_STAGE_HEAD, l, st);
-            rc = head_fwd_bwd(b.at(lay.H[l]), d[l], b.at(lay.A[l]), d[l], c.batch, d[l], d[l + 1], model->W[l],
+            rc = head_fwd_bwd(b.at(lay.H[l]), ldx(l), b.at(lay.A[l]), ldx(l), c.batch, d[l], d[l + 1], model->W[l],
                               model->b[l], dtype, c.labels, seeds, static_cast<float*>(b.at(lay.H[L])),
                               static_cast<float*>(b.at(lay.dZ)), static_cast<float*>(b.at(lay.row_loss)),
                               inner ? b.at(lay.dSelf[l]) : nullptr, inner ? b.at(lay.dAgg[l]) : nullptr, d[l],
@@ -730,7 +738,8 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
             ex.Wb = wb[l];
             ex.W_upd = model->W[l];
             ex.b_upd = model->b[l];
-            rc = linear_bwd(dY, d[l + 1], dy_dtype, nullptr, 0, 0, b.at(lay.H[l]), d[l], b.at(lay.A[l]), d[l],
+            ex.rows_padded = l == 0;
+            rc = linear_bwd(dY, d[l + 1], dy_dtype, nullptr, 0, 0, b.at(lay.H[l]), ldx(l), b.at(lay.A[l]), ldx(l),
                             lay.cap_dst[l], b.blk[l].counts, d[l], d[l + 1], model->W[l], dtype, dW, db,
                             inner ? b.at(lay.dSelf[l]) : nullptr, inner ? b.at(lay.dAgg[l]) : nullptr, d[l],
                             b.at(scr_off[l]), scr_len[l], ex, st);

@@ -93,18 +93,18 @@ class StepRunner:
             out["t_rows"] = B.ws_view(self.ws, lay.t_rows[l], (max(lay.cap_nnz[l], 1),), torch.int32)[:nnz].cpu().numpy()
         return out
 
-    def mat(self, off, cap_rows, rows, cols, dtype):
-        return f64(B.ws_view(self.ws, off, (cap_rows, cols), dtype)[:rows])
+    def mat(self, off, cap_rows, rows, cols, dtype, ld=None):
+        return f64(B.ws_view(self.ws, off, (cap_rows, ld or cols), dtype)[:rows, :cols])
 
     def H(self, l, rows):
         lay = self.lay
         if l == 0:
-            return self.mat(lay.H[0], lay.cap_dst[0], rows, self.dims[0], self.dt)
+            return self.mat(lay.H[0], lay.cap_dst[0], rows, self.dims[0], self.dt, ld=int(lay.ld_in))
         dt = torch.float32 if l == self.L else self.dt
         return self.mat(lay.H[l], lay.cap_dst[l - 1], rows, self.dims[l], dt)
 
     def A(self, l, rows):
-        return self.mat(self.lay.A[l], self.lay.cap_dst[l], rows, self.dims[l], self.dt)
+        return self.mat(self.lay.A[l], self.lay.cap_dst[l], rows, self.dims[l], self.dt, ld=int(self.lay.ld_in) if l == 0 else None)
 
     def dZ(self):
         return self.mat(self.lay.dZ, self.batch, self.batch, self.dims[-1], torch.float32)

@@ -385,6 +385,16 @@ def test_train_step_many_classes_generic_last_layer():
     _run_and_check(inst, wl, steps=2, check_float_steps=(0, 1))
 
 
+@pytest.mark.parametrize("feat", [602, 301, 256])
+def test_train_step_wide_first_layer_padded_rows(feat):
+    # input rows are stored with a stride of whole 128-byte lines and zero padding: widths that are not a
+    # multiple of four (602, 301) still move in 16-byte vectors; several row tiles and column tiles
+    _say(f"train step: large first layer, F={feat}")
+    wl = gen.Workload("big0", "rmat", 14, 16, feat, 41, 256, 2, [25, 10], 1024 if feat < 602 else 512, 17, 1, owned_frac=0.5)
+    inst = gen.make_instance(wl)
+    _run_and_check(inst, wl, steps=2, check_float_steps=(0, 1))
+
+
 def test_train_step_ragged_dims_fp32():
     _say("train step: odd feature widths (scalar load paths)")
     wl = gen.Workload("odd", "rmat", 12, 10, 37, 5, 19, 2, [4, 3], 100, 9, 1)

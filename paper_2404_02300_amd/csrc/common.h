@@ -124,13 +124,15 @@ int32_t sample_seed_map(const SampleWs& ws, const int32_t* dst_nodes, int32_t n_
 int32_t sample_layer(const sdt_csr& g, const int32_t* dst_nodes, int32_t n_dst_cap, const int32_t* n_dst_d,
                      int32_t fanout, uint64_t seed, uint32_t step, uint32_t layer, const sdt_block& out,
                      const SampleWs& ws, hipStream_t st);
-// gather that also resets map[idx[j]] = -1 (map may be null); zero_pad: columns F..ldo-1 of every output row are set to zero
+// gather that also resets map[idx[j]] = -1 (map may be null); zero_pad: columns F..ldo-1 of every output row
+// are set to zero, and those of the same rows of also_pad (nullable: a second matrix of out's shape and stride)
 int32_t gather_rows(const void* X, int64_t ldx, int32_t F, int32_t dtype, const int32_t* idx, int32_t n_cap,
-                    const int32_t* n_d, void* out, int64_t ldo, int32_t* map_reset, bool zero_pad, hipStream_t st);
+                    const int32_t* n_d, void* out, int64_t ldo, int32_t* map_reset, bool zero_pad, void* also_pad,
+                    hipStream_t st);
 
 // mean aggregation straight from the feature matrix through blk->src_nodes (+ optional map reset)
 int32_t aggregate_gather_fwd(const sdt_block* blk, const void* X, int64_t ldx, int32_t F, int32_t dtype, void* A,
-                             int64_t lda, int32_t* map_reset, bool zero_pad, hipStream_t st);
+                             int64_t lda, int32_t* map_reset, hipStream_t st);
 
 // writes dZ and the per-row losses; their mean is folded into a later single-block pass
 int32_t softmax_xent(const float* logits, int64_t ld, int32_t B, int32_t C, const int32_t* labels,

@@ -426,20 +426,20 @@ int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds
         // every frontier row is projected, so every one is gathered (which also hands the whole map back clean)
         StageTimer tm(c.timing, c.slot, SDT_STAGE_GATHER, 0, st);
         return gather_rows(c.X, c.ldx, d[0], c.dtype, b.blk[0].src_nodes, lay.cap_src[0], b.blk[0].counts + 1, b.at(lay.H[0]),
-                           d[0], sw.map, false, st);
+                           d[0], sw.map, false, nullptr, st);
     }
     // Input features: only the destination prefix of the outermost frontier is copied (the
     // projection's "self" operand); the neighbour mean of layer 0 is taken straight out of X.
+    // The copy also zeroes the row padding of H[0] and of A[0] (same rows, same stride).
     // Both passes hand the frontier map back clean (prefix nodes here, the rest there).
     {
         StageTimer tm(c.timing, c.slot, SDT_STAGE_GATHER, 0, st);
         rc = gather_rows(c.X, c.ldx, d[0], c.dtype, b.blk[0].src_nodes, lay.cap_dst[0], b.blk[0].counts,
-                         b.at(lay.H[0]), (int64_t)lay.ld_in, sw.map, /*zero_pad=*/true, st);
+                         b.at(lay.H[0]), (int64_t)lay.ld_in, sw.map, /*zero_pad=*/true, /*also_pad=*/b.at(lay.A[0]), st);
     }
     if (rc != SDT_OK) return rc;
     StageTimer tm(c.timing, c.slot, SDT_STAGE_AGG_FWD, 0, st);
-    return aggregate_gather_fwd(&b.blk[0], c.X, c.ldx, d[0], c.dtype, b.at(lay.A[0]), (int64_t)lay.ld_in, sw.map,
-                                /*zero_pad=*/true, st);
+    return aggregate_gather_fwd(&b.blk[0], c.X, c.ldx, d[0], c.dtype, b.at(lay.A[0]), (int64_t)lay.ld_in, sw.map, st);
 }
 
 // Phase 2 of a GCN step.  The projection kernels take two operands of equal width; here they are

@@ -28,11 +28,12 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X dense bf16 matrix, published
 # FETCH_SIZE count, 1 KiB per WRITE_SIZE count).  Counters cannot be read from inside this script, so
 # the figures are carried here; a stage without a counter run reports null.
 MEASURED_TRAFFIC_BYTES = {
-    ("dense", "aggregate_fwd", 0): 727.1e6 + 33.4e6,
+    ("dense", "aggregate_fwd", 0): 726.4e6 + 32.3e6,
     ("dense", "gather", 0): 26.0e6 + 25.3e6,
-    ("dense", "linear_fwd", 0): 60.3e6 + 10.4e6,
-    ("fullgraph", "aggregate"): 78497.7e6 + 42666.5e6 + 4285.6e6 + 9.3e6,   # both launches of the SpMM
-    ("fullgraph", "linear"): 9145.1e6 + 4295.0e6,
+    ("dense", "linear_fwd", 0): 60.1e6 + 10.4e6,
+    ("dense", "linear_bwd", 0): 59.9e6 + 19.7e6,
+    ("fullgraph", "aggregate"): 78498.6e6 + 42674.4e6 + 4285.6e6 + 9.3e6,   # both launches of the SpMM
+    ("fullgraph", "linear"): 9129.2e6 + 4295.0e6,
 }
 
 
@@ -238,7 +239,7 @@ def main():
 
     # roofline of the dominant stage, from the events recorded inside the timed region
     roofline = rate(dominant[0], dominant[1], float(np.mean(dom_ms)) * 1e-3)
-    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((wl.name, dominant[0], dominant[1]))
+    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((wl.name, dominant[0], dominant[1])) if args.model == "sage" else None
     stage_ms = {f"{k}[{l}]": v for (k, l), v in stage_t.items()}
     others = [rate(k, l, v * 1e-3) for (k, l), v in stage_t.items()]
 

@@ -182,6 +182,10 @@ typedef struct sdt_step_layout {
 const char *sdt_version(void);
 /* Message of the last failing call on this thread (host string; "" if none). */
 const char *sdt_last_error(void);
+/* sizeof of a struct of this header as the library was compiled (a binding that mirrors the structs
+ * checks itself against it): which = 0 sdt_csr, 1 sdt_block, 2 sdt_model, 3 sdt_step_layout,
+ * 4 sdt_partition; 0 for any other value. */
+size_t sdt_struct_bytes(int32_t which);
 
 /* ---- sampling (Sec. II-A: mini-batch graph sampling; Sec. III-B: the full
  * neighbour list of every owned node is present in the partition) ----------

@@ -74,6 +74,7 @@ class sdt_partition(ctypes.Structure):
 EXPORTS = {
     "sdt_version": (ctypes.c_char_p, []),
     "sdt_last_error": (ctypes.c_char_p, []),
+    "sdt_struct_bytes": (_sz, [_i32]),
     "sdt_sample_workspace_bytes": (_sz, [_i64, _i32, _i32]),
     "sdt_sample_csr": (_i32, [_vp, _vp, _i32, _vp, _i32, _u64, _u32, _u32, _vp, _vp, _sz, _vp]),
     "sdt_gather_features": (_i32, [_vp, _i64, _i32, _i32, _vp, _i32, _vp, _vp, _i64, _vp]),
@@ -163,6 +164,10 @@ def sdt_version() -> str:
 
 def sdt_last_error() -> str:
     return lib().sdt_last_error().decode()
+
+
+def sdt_struct_bytes(which: int) -> int:
+    return int(lib().sdt_struct_bytes(which))
 
 
 # ----------------------------------------------------------------- graph / block holders

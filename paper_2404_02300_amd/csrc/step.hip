@@ -72,6 +72,17 @@ int32_t check_model(const sdt_model* m, const int32_t* fanouts, const char* who)
 
 using namespace sdt;
 
+extern "C" size_t sdt_struct_bytes(int32_t which) {
+    switch (which) {
+        case 0: return sizeof(sdt_csr);
+        case 1: return sizeof(sdt_block);
+        case 2: return sizeof(sdt_model);
+        case 3: return sizeof(sdt_step_layout);
+        case 4: return sizeof(sdt_partition);
+        default: return 0;
+    }
+}
+
 // ---- per-stage HIP-event timing ---------------------------------------------------
 struct sdt_timing {
     int32_t max_steps;

@@ -32,6 +32,44 @@ def test_binding_mirrors_header_names():
         assert hasattr(B, n), n
 
 
+def test_struct_mirrors_have_the_library_sizes():
+    for which, cls in enumerate([B.sdt_csr, B.sdt_block, B.sdt_model, B.sdt_step_layout, B.sdt_partition]):
+        assert B.sdt_struct_bytes(which) == ctypes.sizeof(cls), cls.__name__
+    assert B.sdt_struct_bytes(99) == 0
+
+
+def test_model_kinds_layouts_and_their_argument_checks():
+    f = [10, 5]
+    sage = B.sdt_train_step_layout(1 << 14, 256, f, _model([602, 64, 8]), B.SDT_F32)
+    assert sage.ld_in == 608 and sage.t_indptr[0] == 0 and sage.t_indptr[1] != 0    # input rows on whole 128-byte lines
+    assert B.sdt_train_step_layout(1 << 14, 256, f, _model([64, 64, 8]), B.SDT_F32).ld_in == 64
+    assert B.sdt_train_step_layout(1 << 14, 256, f, _model([100, 64, 8]), B.SDT_BF16).ld_in == 128
+    gat = _model([64, 64, 8])
+    gat.kind, gat.gat_slope = B.SDT_MODEL_GAT, 0.2
+    lay = B.sdt_train_step_layout(1 << 14, 256, f, gat, B.SDT_F32)
+    assert lay.ld_in == 64 and lay.t_indptr[0] != 0 and lay.z[0] != 0 and lay.dz[1] != 0 and lay.gatws[0] != 0
+    assert lay.A[0] == 0 and lay.dH[0] == 0 and lay.dH[1] != 0
+    gcn = _model([64, 64, 8])
+    gcn.kind = B.SDT_MODEL_GCN
+    assert B.sdt_train_step_layout(1 << 14, 256, f, gcn, B.SDT_F32).norm[1] != 0
+    for bad_kind in (B.SDT_MODEL_GCN, B.SDT_MODEL_GAT):
+        m = _model([63, 64, 8])      # odd input width: the single-matrix kinds split a row into two halves
+        m.kind, m.gat_slope = bad_kind, 0.2
+        with pytest.raises(B.SdtError):
+            B.sdt_train_step_layout(1 << 14, 256, f, m, B.SDT_F32)
+        m = _model([64, 64, 8])
+        m.kind, m.gat_slope = bad_kind, 0.2
+        with pytest.raises(B.SdtError):
+            B.sdt_train_step_layout(1 << 14, 256, f, m, B.SDT_BF16)      # fp32 only
+    gat.gat_slope = 1.5
+    with pytest.raises(B.SdtError):
+        B.sdt_train_step_layout(1 << 14, 256, f, gat, B.SDT_F32)
+    unknown = _model([64, 64, 8])
+    unknown.kind = 7
+    with pytest.raises(B.SdtError):
+        B.sdt_train_step_layout(1 << 14, 256, f, unknown, B.SDT_F32)
+
+
 def test_workspace_queries_are_host_arithmetic():
     a = B.sdt_sample_workspace_bytes(1 << 21, 1024, 10)
     b = B.sdt_sample_workspace_bytes(1 << 21, 11264, 15)

@@ -16,9 +16,14 @@ namespace {
 constexpr int TB = 256;
 constexpr int UNROLL = 8;  // row loads in flight per lane
 
+// 16- and 8-byte accesses are declared with 4-byte alignment: global loads and stores of several
+// dwords need dword alignment only on this hardware, so rows that start on any dword boundary
+// (602 floats = 2408 bytes per row) still move 16 bytes per lane.
+struct __attribute__((packed, aligned(4))) dword4 { uint32_t x, y, z, w; };
+struct __attribute__((packed, aligned(4))) dword2 { uint32_t x, y; };
 template <int BYTES> struct Raw;
-template <> struct Raw<16> { using type = uint4; };
-template <> struct Raw<8> { using type = uint2; };
+template <> struct Raw<16> { using type = dword4; };
+template <> struct Raw<8> { using type = dword2; };
 template <> struct Raw<4> { using type = uint32_t; };
 template <> struct Raw<2> { using type = uint16_t; };
 
@@ -63,13 +68,19 @@ __global__ __launch_bounds__(TB) void k_gather(const char* __restrict__ X, int64
         if (map_reset && gl == 0) map_reset[node] = -1;  // hand the frontier map back clean
         const char* src = X + (int64_t)node * ldx_b;
         char* dst = out + j * ldo_b;
-        for (int b = gl * VB; b < row_b; b += G * VB)
+        // the last vector of a row whose width is not a multiple of VB is moved back to end with the row
+        // (it overlaps its neighbour and copies the same bytes again); row_b >= VB
+        for (int bn = gl * VB; bn < row_b; bn += G * VB) {
+            const int b = min(bn, row_b - VB);
             *reinterpret_cast<raw_t*>(dst + b) = *reinterpret_cast<const raw_t*>(src + b);
+        }
         // zero padding of the output row (pad_b <= row_b: none), and of row j of a second matrix of
         // the same shape and stride whose producer writes the first row_b bytes only (pad2, nullable)
-        for (int b = row_b + gl * VB; b < pad_b; b += G * VB) {
-            *reinterpret_cast<raw_t*>(dst + b) = raw_t{};
-            if (pad2) *reinterpret_cast<raw_t*>(pad2 + j * ldo_b + b) = raw_t{};
+        constexpr int ZB = VB < 4 ? VB : 4;   // the padding is a whole number of elements, not of vectors
+        using zero_t = typename Raw<ZB>::type;
+        for (int b = row_b + gl * ZB; b < pad_b; b += G * ZB) {
+            *reinterpret_cast<zero_t*>(dst + b) = zero_t{};
+            if (pad2) *reinterpret_cast<zero_t*>(pad2 + j * ldo_b + b) = zero_t{};
         }
     }
 }
@@ -93,7 +104,10 @@ __global__ __launch_bounds__(TB) void k_aggregate_fwd(const IP* __restrict__ ind
         const IP e0 = indptr[i], e1 = indptr[i + 1];
         if ((int64_t)(e1 - e0) > skip_longer_than) continue;  // left to k_aggregate_long
         const float m = (float)(e1 - e0);
-        for (int f0 = gl * VE; f0 < F; f0 += G * VE) {
+        // the last vector of a row whose width is not a multiple of VE is moved back to end with the row:
+        // it overlaps its neighbour, both lanes take the same sums in the same order and store the same values
+        for (int fn = gl * VE; fn < F; fn += G * VE) {
+            const int f0 = min(fn, F - VE);
             float acc[VE];
 #pragma unroll
             for (int q = 0; q < VE; ++q) acc[q] = 0.f;
@@ -105,26 +119,23 @@ __global__ __launch_bounds__(TB) void k_aggregate_fwd(const IP* __restrict__ ind
 #pragma unroll
                     for (int u = 0; u < UNROLL; ++u)
                         if (c[u] >= 0) c[u] = row_ids[c[u]];
-                    if (map_reset && f0 == gl * VE && gl == 0) {
+                    if (map_reset && fn == gl * VE && gl == 0) {
 #pragma unroll
                         for (int u = 0; u < UNROLL; ++u)
                             if (c[u] >= 0) map_reset[c[u]] = -1;
                     }
                 }
-                float v[UNROLL][VE];
+                // the rows stay in their storage type until they are added (half the registers for bf16)
+                Vec<T, VE> v[UNROLL];
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) {
-                    if (c[u] >= 0) {
-                        load_f32<T, VE>(H + (int64_t)c[u] * ldh + f0, v[u]);
-                    } else {
-#pragma unroll
-                        for (int q = 0; q < VE; ++q) v[u][q] = 0.f;
-                    }
+                    v[u].raw = typename Vec<T, VE>::raw_t{};
+                    if (c[u] >= 0) v[u].raw = *reinterpret_cast<const typename Vec<T, VE>::raw_t*>(H + (int64_t)c[u] * ldh + f0);
                 }
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u)
 #pragma unroll
-                    for (int q = 0; q < VE; ++q) acc[q] += v[u][q];
+                    for (int q = 0; q < VE; ++q) acc[q] += to_f32<T>(v[u].e[q]);
             }
             if (e1 > e0) {
 #pragma unroll
@@ -271,6 +282,19 @@ int vec_bytes(size_t elem, int F, std::initializer_list<int64_t> lds, std::initi
     return vb;
 }
 
+// For kernels that move the last vector of a row back (see k_gather, k_aggregate_fwd): the widest
+// vector (bytes, <= 16) that fits into a row, given that every row starts on a dword boundary
+// (or on an element boundary for the one-element vector).
+int vec_bytes_dword_rows(size_t elem, int F, std::initializer_list<int64_t> lds, std::initializer_list<const void*> ptrs) {
+    bool dword = ((uint64_t)F * elem) % 4 == 0;   // the moved-back last vector must start on a dword as well
+    for (int64_t ld : lds) dword = dword && ((uint64_t)ld * elem) % 4 == 0;
+    for (const void* p : ptrs) dword = dword && reinterpret_cast<uintptr_t>(p) % 4 == 0;
+    if (!dword) return vec_bytes(elem, F, lds, ptrs);
+    int vb = 16;
+    while (vb > (int)elem && (uint64_t)F * elem < (uint64_t)vb) vb >>= 1;
+    return vb < 4 ? vec_bytes(elem, F, lds, ptrs) : vb;
+}
+
 int group_lanes(int vecs_per_row) {
     int g = 8;
     while (g < 64 && g < vecs_per_row) g <<= 1;
@@ -318,7 +342,8 @@ int32_t launch_aggregate_fwd(const IP* indptr, const int32_t* cols, int64_t n_ca
                              int32_t* map_reset, hipStream_t st) {
     if (n_cap == 0 || F == 0) return SDT_OK;
     const size_t es = dtype_size(dtype);
-    const int ve = vec_bytes(es, F, {ldh, lda}, {H, A}) / (int)es;
+    // (the hub kernel of the whole-graph form keeps whole vectors per row)
+    const int ve = (sizeof(IP) == 8 ? vec_bytes(es, F, {ldh, lda}, {H, A}) : vec_bytes_dword_rows(es, F, {ldh, lda}, {H, A})) / (int)es;
     const int G = group_lanes((F + ve - 1) / ve);
     // A whole graph (64-bit offsets): one row per lane group, as many workgroups as that takes (the
     // hardware hands them out as CUs free up, which balances power-law rows), hubs in a second launch.
@@ -363,7 +388,7 @@ int32_t gather_rows(const void* X, int64_t ldx, int32_t F, int32_t dtype, const 
     if (n_cap == 0 || F == 0) return SDT_OK;
     SDT_REQUIRE(X && idx && out, SDT_ERR_INVALID_ARG, "sdt_gather_features: null pointer");
     const size_t es = dtype_size(dtype);
-    const int vb = vec_bytes(es, F, {ldx, ldo}, {X, out, also_pad});
+    const int vb = vec_bytes_dword_rows(es, F, {ldx, ldo}, {X, out, also_pad});
     const int row_b = (int)(F * es);
     const int G = group_lanes((row_b + vb - 1) / vb);
     const char* Xc = static_cast<const char*>(X);

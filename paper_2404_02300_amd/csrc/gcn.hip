@@ -12,13 +12,18 @@ namespace {
 constexpr int TB = 256;
 constexpr int U = 8;
 
+// 16- and 8-byte accesses declared with 4-byte alignment: several-dword global accesses need dword
+// alignment only, so rows that start on any dword boundary move whole vectors
+struct __attribute__((packed, aligned(4))) f4d { float x, y, z, w; };
+struct __attribute__((packed, aligned(4))) f2d { float x, y; };
+
 template <int VE>
 __device__ __forceinline__ void ld(const float* p, float (&v)[VE]) {
     if constexpr (VE == 4) {
-        const float4 t = *reinterpret_cast<const float4*>(p);
+        const f4d t = *reinterpret_cast<const f4d*>(p);
         v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
     } else if constexpr (VE == 2) {
-        const float2 t = *reinterpret_cast<const float2*>(p);
+        const f2d t = *reinterpret_cast<const f2d*>(p);
         v[0] = t.x; v[1] = t.y;
     } else {
         v[0] = *p;
@@ -26,8 +31,8 @@ __device__ __forceinline__ void ld(const float* p, float (&v)[VE]) {
 }
 template <int VE>
 __device__ __forceinline__ void st(float* p, const float (&v)[VE]) {
-    if constexpr (VE == 4) *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
-    else if constexpr (VE == 2) *reinterpret_cast<float2*>(p) = make_float2(v[0], v[1]);
+    if constexpr (VE == 4) *reinterpret_cast<f4d*>(p) = f4d{v[0], v[1], v[2], v[3]};
+    else if constexpr (VE == 2) *reinterpret_cast<f2d*>(p) = f2d{v[0], v[1]};
     else *p = v[0];
 }
 
@@ -71,7 +76,10 @@ __global__ __launch_bounds__(TB) void k_gcn_aggregate_fwd(const int32_t* __restr
         const int64_t own = row_ids ? row_ids[i] : i;
         if (map_reset && gl == 0) map_reset[own] = -1;
         const float si = s[i], wi = selfw[i];
-        for (int f0 = gl * VE; f0 < F; f0 += G * VE) {
+        // the last vector of a row whose width is not a multiple of VE is moved back to end with the row
+        // (it overlaps its neighbour; both lanes compute and store the same values); F >= VE
+        for (int fn = gl * VE; fn < F; fn += G * VE) {
+            const int f0 = min(fn, F - VE);
             float acc[VE];
 #pragma unroll
             for (int q = 0; q < VE; ++q) acc[q] = 0.f;
@@ -84,7 +92,7 @@ __global__ __launch_bounds__(TB) void k_gcn_aggregate_fwd(const int32_t* __restr
                     w[u] = col >= 0 ? c[col] : 0.f;
                     r[u] = col < 0 ? -1 : (row_ids ? (int64_t)row_ids[col] : (int64_t)col);
                 }
-                if (map_reset && f0 == gl * VE && gl == 0) {
+                if (map_reset && fn == gl * VE && gl == 0) {
 #pragma unroll
                     for (int u = 0; u < U; ++u)
                         if (r[u] >= 0) map_reset[r[u]] = -1;
@@ -214,7 +222,9 @@ inline int rows_grid(int64_t rows, int G) {
 int32_t gcn_aggregate_fwd(const sdt_block* blk, const float* H, int64_t ldh, bool through_src_nodes, int32_t F,
                           const float* c, const float* s, const float* selfw, float* A, int64_t lda, int32_t* map_reset,
                           hipStream_t stm) {
-    const int ve = vec_floats(F, {ldh, lda}, {H, A});
+    // the forward kernel moves its last vector back, so any dword-aligned fp32 row takes the widest vector that fits
+    const int ve = F >= 4 ? 4 : F >= 2 ? 2 : 1;
+    (void)vec_floats;
     const int G = (F + ve - 1) / ve > 16 ? 64 : 16;
     SDT_GCN_DISPATCH(ve, G, hipLaunchKernelGGL((k_gcn_aggregate_fwd<VE, GG>), dim3(rows_grid(blk->cap_dst, GG)), dim3(TB),
                                                0, stm, blk->indptr, blk->cols, blk->counts, H, ldh,

@@ -28,8 +28,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X dense bf16 matrix, published
 # FETCH_SIZE count, 1 KiB per WRITE_SIZE count).  Counters cannot be read from inside this script, so
 # the figures are carried here; a stage without a counter run reports null.
 MEASURED_TRAFFIC_BYTES = {
-    ("dense", "aggregate_fwd", 0): 726.4e6 + 32.3e6,
-    ("dense", "gather", 0): 26.0e6 + 25.3e6,
+    ("dense", "aggregate_fwd", 0): 691.3e6 + 32.5e6,
+    ("dense", "gather", 0): 26.1e6 + 25.3e6,
     ("dense", "linear_fwd", 0): 60.1e6 + 10.4e6,
     ("dense", "linear_bwd", 0): 59.9e6 + 19.7e6,
     ("fullgraph", "aggregate"): 78498.6e6 + 42674.4e6 + 4285.6e6 + 9.3e6,   # both launches of the SpMM

@@ -2,7 +2,7 @@
 //   A[i,:] = s[i] * sum_{e in row i} c[col_e] * H[col_e,:] + selfw[i] * H[i,:],
 // its transpose through the transposed block, and the kernel that derives c, s, selfw from the
 // degrees of the partition graph.  Same row-group scheme as the mean aggregation: a group of
-// lanes per row, 16-byte vectors when the alignment allows, eight row loads in flight, fp32 sums
+// lanes per row, 16-byte vectors (forward: from any dword-aligned row), eight row loads in flight, fp32 sums
 // in edge order (forward) / ascending destination order (backward) -- deterministic.
 #include "common.h"
 
@@ -224,7 +224,6 @@ int32_t gcn_aggregate_fwd(const sdt_block* blk, const float* H, int64_t ldh, boo
                           hipStream_t stm) {
     // the forward kernel moves its last vector back, so any dword-aligned fp32 row takes the widest vector that fits
     const int ve = F >= 4 ? 4 : F >= 2 ? 2 : 1;
-    (void)vec_floats;
     const int G = (F + ve - 1) / ve > 16 ? 64 : 16;
     SDT_GCN_DISPATCH(ve, G, hipLaunchKernelGGL((k_gcn_aggregate_fwd<VE, GG>), dim3(rows_grid(blk->cap_dst, GG)), dim3(TB),
                                                0, stm, blk->indptr, blk->cols, blk->counts, H, ldh,

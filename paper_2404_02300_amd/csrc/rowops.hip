@@ -3,8 +3,9 @@
 //
 // A row of F elements is handled by a group of G lanes (G = 8..64, the smallest
 // power of two that covers the row with one vector per lane, wider rows loop
-// in chunks).  Every lane moves the widest vector the row alignment allows
-// (16 B when rows are 16-byte aligned).  The edge loop issues a batch of
+// in chunks).  Every lane moves 16 bytes when the rows start on dword boundaries
+// (gather and sampled-block aggregation; the last vector of a ragged row is moved
+// back to end with the row), else the widest vector the alignment allows.  The edge loop issues a batch of
 // independent row loads before consuming them, so each wave keeps several KB
 // in flight; sums are taken in edge order in fp32, which makes the result
 // independent of the launch shape.

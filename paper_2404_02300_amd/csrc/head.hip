@@ -59,9 +59,61 @@ __global__ __launch_bounds__(TB) void k_head(const TH* __restrict__ Hself, int64
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int li = lane & 15, kg = lane >> 4;
     const bool rnd = round_ops != 0;
+    // gridDim.y workgroups share a block of rows: each stages W and the rows and computes the logits
+    // and the loss gradient for itself (a replicated, latency-bound prefix), then takes its share of
+    // the input-gradient columns and of the weight-gradient rows; part 0 writes the per-row outputs
+    const int part = blockIdx.y, nparts = gridDim.y;
+    // operands of later phases that sit behind dependent global loads are fetched now
+    int y_pre = -1;
+    if (wave < 4 && row0 + wave * 4 + kg < B) y_pre = labels[seeds ? seeds[row0 + wave * 4 + kg] : row0 + wave * 4 + kg];
+    float bias_pre[2] = {0.f, 0.f};
+    if (bias) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int idx = threadIdx.x + u * TB;
+            const int col = idx % CP;
+            if (idx < HB * CP && col < C) bias_pre[u] = bias[col];
+        }
+    }
 
-    // ---- stage W (flat 16-byte copy) and the 16 feature rows; U loads in flight per thread
+    // ---- stage the 16 feature rows and W (flat 16-byte copy).  The first round of row loads is issued
+    // before the W loads and stored after them, so both share one trip to memory.
     {
+        // feature rows: thread t copies 4 consecutive elements; in % 8 == 0 keeps a quad inside one source
+        constexpr int EV = 4;
+        const int quads = K2 / EV;  // per row
+        auto load_rows = [&](int base, float (&v)[U][EV]) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int idx = base + u * TB;
+                const int r = idx / quads, k = (idx - r * quads) * EV;
+#pragma unroll
+                for (int e = 0; e < EV; ++e) v[u][e] = 0.f;
+                if (idx < HB * quads && row0 + r < B) {
+                    const TH* src = k < in ? Hself + (int64_t)(row0 + r) * ldh + k : Agg + (int64_t)(row0 + r) * lda + (k - in);
+                    if constexpr (sizeof(TH) == 4) {
+                        const float4 x = *reinterpret_cast<const float4*>(src);
+                        v[u][0] = x.x; v[u][1] = x.y; v[u][2] = x.z; v[u][3] = x.w;
+                    } else {
+                        const uint2 x = *reinterpret_cast<const uint2*>(src);
+                        v[u][0] = bf16_to_f32((uint16_t)(x.x & 0xFFFFu)); v[u][1] = bf16_to_f32((uint16_t)(x.x >> 16));
+                        v[u][2] = bf16_to_f32((uint16_t)(x.y & 0xFFFFu)); v[u][3] = bf16_to_f32((uint16_t)(x.y >> 16));
+                    }
+                }
+            }
+        };
+        auto store_rows = [&](int base, const float (&v)[U][EV]) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int idx = base + u * TB;
+                if (idx < HB * quads) {
+                    const int r = idx / quads, k = (idx - r * quads) * EV;
+                    *reinterpret_cast<float4*>(Hc + r * LDH + k) = make_float4(v[u][0], v[u][1], v[u][2], v[u][3]);
+                }
+            }
+        };
+        float v0[U][EV];
+        load_rows(threadIdx.x, v0);
         const int n4 = (K2 * C) >> 2;
         const float4* W4 = reinterpret_cast<const float4*>(W);
         float4* Ws4 = reinterpret_cast<float4*>(Ws);
@@ -82,37 +134,11 @@ __global__ __launch_bounds__(TB) void k_head(const TH* __restrict__ Hself, int64
                 }
         }
         if (threadIdx.x < 16) Ws[K2 * C + threadIdx.x] = 0.f;
-        // feature rows: thread t copies 4 consecutive elements; in % 8 == 0 keeps a quad inside one source
-        constexpr int EV = 4;
-        const int quads = K2 / EV;  // per row
-        for (int base = threadIdx.x; base < HB * quads; base += TB * U) {
+        store_rows(threadIdx.x, v0);
+        for (int base = threadIdx.x + TB * U; base < HB * quads; base += TB * U) {
             float v[U][EV];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int idx = base + u * TB;
-                const int r = idx / quads, k = (idx - r * quads) * EV;
-#pragma unroll
-                for (int e = 0; e < EV; ++e) v[u][e] = 0.f;
-                if (idx < HB * quads && row0 + r < B) {
-                    const TH* src = k < in ? Hself + (int64_t)(row0 + r) * ldh + k : Agg + (int64_t)(row0 + r) * lda + (k - in);
-                    if constexpr (sizeof(TH) == 4) {
-                        const float4 x = *reinterpret_cast<const float4*>(src);
-                        v[u][0] = x.x; v[u][1] = x.y; v[u][2] = x.z; v[u][3] = x.w;
-                    } else {
-                        const uint2 x = *reinterpret_cast<const uint2*>(src);
-                        v[u][0] = bf16_to_f32((uint16_t)(x.x & 0xFFFFu)); v[u][1] = bf16_to_f32((uint16_t)(x.x >> 16));
-                        v[u][2] = bf16_to_f32((uint16_t)(x.y & 0xFFFFu)); v[u][3] = bf16_to_f32((uint16_t)(x.y >> 16));
-                    }
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int idx = base + u * TB;
-                if (idx < HB * quads) {
-                    const int r = idx / quads, k = (idx - r * quads) * EV;
-                    *reinterpret_cast<float4*>(Hc + r * LDH + k) = make_float4(v[u][0], v[u][1], v[u][2], v[u][3]);
-                }
-            }
+            load_rows(base, v);
+            store_rows(base, v);
         }
     }
     __syncthreads();
@@ -157,15 +183,15 @@ __global__ __launch_bounds__(TB) void k_head(const TH* __restrict__ Hself, int64
         }
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < HB * CP; idx += TB) {
+    for (int idx = threadIdx.x, u = 0; idx < HB * CP; idx += TB, ++u) {
         const int row = idx / CP, col = idx - row * CP;
         float z = 0.f;
         if (col < C) {
             z = Part[idx];
 #pragma unroll
             for (int w = 1; w < NW; ++w) z += Part[w * HB * CP + idx];
-            z += bias ? bias[col] : 0.f;
-            if (row0 + row < B) logits[(int64_t)(row0 + row) * C + col] = z;
+            z += u == 0 ? bias_pre[0] : u == 1 ? bias_pre[1] : (bias ? bias[col] : 0.f);   // two rounds cover C <= 64
+            if (part == 0 && row0 + row < B) logits[(int64_t)(row0 + row) * C + col] = z;
         }
         Zs[row * LDZ + col] = z;
     }
@@ -184,7 +210,7 @@ __global__ __launch_bounds__(TB) void k_head(const TH* __restrict__ Hself, int64
         for (int c = li; c < C; c += 16) sum += expf(z[c] - mx);
 #pragma unroll
         for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-        const int y = live ? labels[seeds ? seeds[row0 + row] : row0 + row] : -1;
+        const int y = y_pre;
         const float zy = live ? z[y] : 0.f;
         const float invB = 1.0f / (float)B, inv_sum = 1.0f / sum;
         __builtin_amdgcn_wave_barrier();
@@ -192,23 +218,26 @@ __global__ __launch_bounds__(TB) void k_head(const TH* __restrict__ Hself, int64
             float g = 0.f;
             if (live && c < C) {
                 g = (expf(z[c] - mx) * inv_sum - (c == y ? 1.f : 0.f)) * invB;
-                dZ[(int64_t)(row0 + row) * C + c] = g;
+                if (part == 0) dZ[(int64_t)(row0 + row) * C + c] = g;
             }
             z[c] = maybe_round(g, rnd);  // the operand of the two backward products
         }
-        if (live && li == 0) row_loss[row0 + row] = logf(sum) + mx - zy;
+        if (live && li == 0 && part == 0) row_loss[row0 + row] = logf(sum) + mx - zy;
     }
     __syncthreads();
 
     // ---- (c) input gradients [dSelf | dAgg] = dZ W^T: tiles of 16 input columns, 4 at a time per wave
     if (dSelf) {
         const int MT = K2 >> 4;
+        const int mt_lo = (int)((int64_t)MT * part / nparts), mt_hi = (int)((int64_t)MT * (part + 1) / nparts);
         constexpr int TPW = 4;
-        for (int mt0 = wave * TPW; mt0 < MT; mt0 += NW * TPW) {
+        // tiles per wave at a time: as few as spreads this part's tiles over all the waves
+        const int tpw = min(TPW, max(1, (mt_hi - mt_lo + NW - 1) / NW));
+        for (int mt0 = mt_lo + wave * tpw; mt0 < mt_hi; mt0 += NW * tpw) {
             floatx4 acc[TPW];
 #pragma unroll
             for (int t = 0; t < TPW; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
-            const int nt = min(TPW, MT - mt0);
+            const int nt = min(tpw, mt_hi - mt0);
             for (int c = 0; c < CP; c += 16) {
                 const float4 a4 = *reinterpret_cast<const float4*>(Zs + li * LDZ + c + kg * 4);
                 const float a[4] = {a4.x, a4.y, a4.z, a4.w};
@@ -249,7 +278,8 @@ __global__ __launch_bounds__(TB) void k_head(const TH* __restrict__ Hself, int64
 #pragma unroll
             for (int s = 0; s < 4; ++s) b[s] = Zs[(kg * 4 + s) * LDZ + ct * 16 + li];
             const int col = ct * 16 + li;
-            for (int mt = wave; mt < MT; mt += NW) {
+            const int mt_lo = (int)((int64_t)MT * part / nparts), mt_hi = (int)((int64_t)MT * (part + 1) / nparts);
+            for (int mt = mt_lo + wave; mt < mt_hi; mt += NW) {
                 floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int s = 0; s < 4; ++s) acc = mfma16(Hc[(kg * 4 + s) * LDH + mt * 16 + li], b[s], acc);
@@ -259,12 +289,13 @@ __global__ __launch_bounds__(TB) void k_head(const TH* __restrict__ Hself, int64
                 }
             }
         }
-        for (int c = threadIdx.x; c < C; c += TB) {
-            float s = 0.f;
+        if (part == 0)
+            for (int c = threadIdx.x; c < C; c += TB) {
+                float s = 0.f;
 #pragma unroll
-            for (int r = 0; r < HB; ++r) s += Zs[r * LDZ + c];
-            Q[(int64_t)blockIdx.x * C + c] = s;
-        }
+                for (int r = 0; r < HB; ++r) s += Zs[r * LDZ + c];
+                Q[(int64_t)blockIdx.x * C + c] = s;
+            }
     }
 }
 
@@ -311,12 +342,15 @@ int32_t head_fwd_bwd(const void* Hself, int64_t ldh, const void* A, int64_t lda,
         }
         opted[which] = true;
     }
+    // few row blocks (batch / 16): up to four workgroups share one, splitting the backward products
+    const int mt = (2 * in) / 16;
+    const int nparts = splits >= 256 ? 1 : (mt % 4 == 0 ? 4 : mt % 2 == 0 ? 2 : 1);
     if (dtype == SDT_F32)
-        hipLaunchKernelGGL(k_head<float>, dim3(splits), dim3(TB), lds, st, static_cast<const float*>(Hself), ldh,
+        hipLaunchKernelGGL(k_head<float>, dim3(splits, nparts), dim3(TB), lds, st, static_cast<const float*>(Hself), ldh,
                            static_cast<const float*>(A), lda, batch, in, out, W, bias, labels, seeds, logits, dZ,
                            row_loss, static_cast<float*>(dSelf), static_cast<float*>(dAgg), ldi, P, Q, 0);
     else
-        hipLaunchKernelGGL(k_head<bf16_t>, dim3(splits), dim3(TB), lds, st, static_cast<const bf16_t*>(Hself), ldh,
+        hipLaunchKernelGGL(k_head<bf16_t>, dim3(splits, nparts), dim3(TB), lds, st, static_cast<const bf16_t*>(Hself), ldh,
                            static_cast<const bf16_t*>(A), lda, batch, in, out, W, bias, labels, seeds, logits, dZ,
                            row_loss, static_cast<bf16_t*>(dSelf), static_cast<bf16_t*>(dAgg), ldi, P, Q, 1);
     SDT_CHECK_LAUNCH("head");

@@ -79,3 +79,67 @@ def test_fullgraph_layer_sampled_rows():
     refY = orc.linear_fwd(X[rows].astype(np.float64), refA, W[0], b[0], relu=True)
     assert_close(f64(Y[rt]), refY, TOL[torch.float32], "Y (sampled rows)")
     _say(f"fullgraph: {len(rows)} rows checked, max degree {deg.max()}")
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("kind", ["gcn", "gat"])
+def test_products_full_size_other_model_kinds(kind):
+    """The GCN and GAT kinds of the step at the products-shaped sizes (one weight matrix per layer,
+    Glorot-uniform from a seed): loss, every gradient and the updated parameters of two steps,
+    teacher-forced from the GPU's parameters."""
+    wl = gen.WORKLOADS["products"]
+    inst = gen.make_instance(wl)
+    d, L = wl.dims, len(wl.fanouts)
+    rng = np.random.default_rng(wl.seed + 100)
+    W = [(rng.uniform(-1, 1, size=(d[l], d[l + 1])) * np.sqrt(6.0 / (d[l] + d[l + 1]))).astype(np.float32) for l in range(L)]
+    att = [(rng.uniform(-1, 1, size=2 * d[l + 1]) * np.sqrt(6.0 / (d[l + 1] + 1))).astype(np.float32) for l in range(L)]
+    g = B.Csr(dev(inst.indptr), dev(inst.indices))
+    X, y = dev(inst.X), dev(inst.y)
+    Wd, bd, ad = [dev(w) for w in W], [dev(v) for v in inst.b], [dev(v) for v in att]
+    if kind == "gat":
+        model = B.make_model(d, Wd, bd, kind=B.SDT_MODEL_GAT, att=ad, gat_slope=0.2)
+    else:
+        model = B.make_model(d, Wd, bd, kind=B.SDT_MODEL_GCN)
+    lay = B.sdt_train_step_layout(g.n_nodes, wl.batch, wl.fanouts, model, B.SDT_F32)
+    ws = torch.empty(int(lay.total_bytes), dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    lr, tol = 0.01, TOL[torch.float32]
+
+    def view(off, cap_rows, rows, cols):
+        return f64(B.ws_view(ws, off, (cap_rows, cols), torch.float32)[:rows])
+
+    for step in range(2):
+        seeds = inst.batch(step)
+        W0, b0, a0 = [f64(w) for w in Wd], [f64(v) for v in bd], [f64(v) for v in ad]
+        B.sdt_train_step(g, X, y, dev(seeds.astype(np.int32)), wl.fanouts, model, wl.seed, step, lr, loss, ws)
+        torch.cuda.synchronize()
+
+        def oracle(blocks=None, masks=None):
+            if kind == "gat":
+                return orc.gat_train_step(inst.indptr, inst.indices, inst.X, inst.y, seeds, wl.fanouts, W0, b0, a0, wl.seed,
+                                          step, lr, 0.2, blocks=blocks, relu_masks=masks)
+            return orc.gcn_train_step(inst.indptr, inst.indices, inst.X, inst.y, seeds, wl.fanouts, W0, b0, wl.seed, step, lr,
+                                      blocks=blocks, relu_masks=masks)
+
+        ref = oracle()
+        blocks = ref["blocks"]
+        # ReLU decisions within rounding of zero may differ between fp32 and fp64: adopt the GPU's, check they are borderline
+        H1 = view(lay.H[1], lay.cap_dst[0], blocks[0].n_dst, d[1])
+        diff = (H1 > 0) != (ref["H"][1] > 0)
+        if diff.any():
+            assert np.all(np.abs(ref["H"][1][diff]) <= tol * np.max(np.abs(ref["H"][1])))
+            assert np.all(np.abs(H1[diff]) <= tol * np.max(np.abs(H1)))
+            ref = oracle(blocks, [H1 > 0, None])
+        for l in range(L):
+            cnt = B.ws_view(ws, lay.counts[l], (4,), torch.int32).cpu().tolist()
+            assert cnt[:3] == [blocks[l].n_dst, blocks[l].n_src, blocks[l].nnz]
+            assert_close(view(lay.H[l + 1], lay.cap_dst[l], blocks[l].n_dst, d[l + 1]), ref["H"][l + 1], tol, f"H[{l + 1}]")
+            assert_close(view(lay.dW[l], d[l], d[l], d[l + 1]), ref["dW"][l], tol, f"dW[{l}]")
+            assert_close(view(lay.db[l], 1, 1, d[l + 1])[0], ref["db"][l], tol, f"db[{l}]")
+            assert_close(f64(Wd[l]), ref["W_new"][l], tol, f"updated W[{l}]")
+            assert_close(f64(bd[l]), ref["b_new"][l], tol, f"updated b[{l}]")
+            if kind == "gat":
+                assert_close(view(lay.datt[l], 1, 1, 2 * d[l + 1])[0], ref["datt"][l], tol, f"datt[{l}]")
+                assert_close(f64(ad[l]), ref["att_new"][l], tol, f"updated att[{l}]")
+        assert abs(float(loss) - ref["loss"]) <= tol * max(1.0, abs(ref["loss"]))
+        _say(f"  {kind} products step {step}: loss {float(loss):.6f} ok")

@@ -34,6 +34,9 @@ MEASURED_TRAFFIC_BYTES = {
     ("dense", "linear_bwd", 0): 59.9e6 + 19.7e6,
     ("fullgraph", "aggregate"): 78498.6e6 + 42674.4e6 + 4285.6e6 + 9.3e6,   # both launches of the SpMM
     ("fullgraph", "linear"): 9129.2e6 + 4295.0e6,
+    # stage-at-scale modes: every kernel of one sdt_sample_csr call / the one gather kernel
+    ("sampling", "stage"): (2.1 + 207.1 + 2.4 + 4.6 + 136.3) * 1e6 + (2.1 + 70.2 + 10.2 + 9.2) * 1e6,
+    ("gather", "stage"): 350.1e6 + 313.4e6,
 }
 
 
@@ -47,7 +50,9 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="products",
-                    choices=["tiny", "products", "dense", "sparse_bf16", "fullgraph"])
+                    choices=["tiny", "products", "dense", "sparse_bf16", "fullgraph", "sampling", "gather"],
+                    help="the five configured workloads; 'sampling' / 'gather' time that stage alone at a size "
+                         "where it is bandwidth-bound (every owned node of the products-shaped graph as a destination)")
     ap.add_argument("--model", default="sage", choices=["sage", "gcn", "gat"],
                     help="gcn / gat: the same step with the GCN or GAT model kind (fp32 workloads; not the headline metric)")
     ap.add_argument("--lr", type=float, default=0.01)
@@ -69,7 +74,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    wl = gen.WORKLOADS[args.workload]
+    wl = gen.WORKLOADS["products" if args.workload in ("sampling", "gather") else args.workload]
     K, Wm = args.steps, args.warmup
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB read + 1 GiB written
@@ -79,6 +84,8 @@ def main():
         del src, dst
     if args.workload == "fullgraph":
         return bench_fullgraph(args, wl)
+    if args.workload in ("sampling", "gather"):
+        return bench_stage_at_scale(args, wl)
 
     t0 = time.time()
     inst = gen.make_instance(wl)
@@ -288,6 +295,84 @@ def main():
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()}, "stage_rates": others,
     }
     print(json.dumps(out), flush=True)
+
+
+def bench_stage_at_scale(args, wl):
+    """The sampling stage (sdt_sample_csr: neighbour sampling, frontier, relabelling) or the feature
+    gather alone, with every owned node of the products-shaped graph as a destination: the mini-batch
+    steps move so little per launch that these stages are latency-bound there; this shows what the
+    same kernels sustain once a launch is large."""
+    import numpy as np
+    import torch
+    import sdt_gen as gen
+    import paper_2404_02300_amd as sdt
+
+    K, Wm = min(args.steps, 20), min(args.warmup, 3)
+    indptr, indices = gen.make_graph(wl)
+    N, nnz = wl.n_nodes, int(indptr[-1])
+    n_dst = int(N * wl.owned_frac)
+    fanout = wl.fanouts[0]
+    g = sdt.Csr(torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda())
+    dst = torch.arange(n_dst, dtype=torch.int32, device="cuda")
+    blk = sdt.Block(n_dst, fanout, N, "cuda", transposed=False)
+    ws = torch.empty(sdt.sdt_sample_workspace_bytes(N, n_dst, fanout), dtype=torch.uint8, device="cuda")
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(K)]
+    if args.workload == "sampling":
+        def run(i):
+            sdt.sdt_sample_csr(g, dst, fanout, wl.seed, i, 0, blk, ws)
+    else:
+        sdt.sdt_sample_csr(g, dst, fanout, wl.seed, 0, 0, blk, ws)      # a frontier to gather
+        torch.cuda.synchronize()
+        n_src = int(blk.counts[1].item())
+        X = torch.from_numpy(gen.normal_features(N, wl.feat, wl.seed)).cuda()
+        out = torch.empty(n_src, wl.feat, dtype=torch.float32, device="cuda")
+        idx = blk.src_nodes[:n_src]
+
+        def run(i):
+            sdt.sdt_gather_features(X, idx, out)
+    for i in range(Wm):
+        run(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        ev[i][0].record()
+        run(Wm + i)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    sec = float(np.mean([e[0].elapsed_time(e[1]) for e in ev])) * 1e-3
+    cnt = blk.counts.cpu().tolist()
+    if args.workload == "sampling":
+        amount = cnt[0] * 16 + cnt[2] * 8          # two row offsets per destination, 4 B read + 4 B written per edge
+        units, unit_name, kern = cnt[2], "sampled edges/s", "k_sample_rows + frontier scan + relabel"
+    else:
+        amount = cnt[1] * (2 * wl.feat * 4 + 4)
+        units, unit_name, kern = cnt[1], "gathered rows/s", "k_gather"
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import sdt_oracle as orc
+        m = 1 << 15          # a bounded sample: the first 2^15 destinations
+        tc = time.perf_counter()
+        b = orc.sample_block(indptr, indices, np.arange(m, dtype=np.int32), fanout, wl.seed, 0, 0)
+        if args.workload == "gather":
+            orc.gather_rows(gen.normal_features(N, wl.feat, wl.seed), b.src_nodes)
+        tc = time.perf_counter() - tc
+        cpu = {"value": round((b.nnz if args.workload == "sampling" else b.n_src) / tc, 1), "unit": unit_name, "cores": 1,
+               "kind": "oracle", "sample": f"the first {m} destination rows of the same launch", "host_cpus": os.cpu_count()}
+    out_json = {
+        "metric": f"{unit_name} of the {args.workload} stage alone ({cnt[0]} destination rows, fan-out {fanout})",
+        "value": round(units / sec, 1), "unit": unit_name, "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": round(elapsed / K * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32" if args.workload == "sampling" else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload} stage on products: {wl.kind} 2^{wl.log2n} nodes, {nnz} CSR entries, "
+                               f"{cnt[0]} destinations, {cnt[1]} frontier rows, {cnt[2]} sampled edges"},
+        "roofline": {"kernel": kern, "bound": "hbm", "achieved": round(amount / sec / 1e9, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(amount / sec / 1e9 / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "stage")),
+                     "algorithmic_bytes_per_launch": int(amount), "avg_launch_us": round(sec * 1e6, 1)},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out_json), flush=True)
 
 
 def bench_fullgraph(args, wl):

@@ -28,6 +28,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X dense bf16 matrix, published
 # FETCH_SIZE count, 1 KiB per WRITE_SIZE count).  Counters cannot be read from inside this script, so
 # the figures are carried here; a stage without a counter run reports null.
 MEASURED_TRAFFIC_BYTES = {
+    ("products", "linear_fwd", 0): 6.03e6 + 3.98e6,
+    ("products", "head", 1): 3.33e6 + 8.66e6,
+    ("products", "aggregate_fwd", 0): 22.63e6 + 2.94e6,
+    ("sparse_bf16", "aggregate_fwd", 0): 76.2e6 + 13.44e6,
+    ("sparse_bf16", "linear_fwd", 0): 11.76e6 + 10.44e6,
     ("dense", "aggregate_fwd", 0): 691.3e6 + 32.5e6,
     ("dense", "gather", 0): 26.1e6 + 25.3e6,
     ("dense", "linear_fwd", 0): 60.1e6 + 10.4e6,

@@ -255,9 +255,11 @@ __global__ __launch_bounds__(TB) void k_aggregate_bwd(const int32_t* __restrict_
                     }
                 }
 #pragma unroll
-                for (int u = 0; u < UNROLL; ++u)
+                for (int u = 0; u < UNROLL; ++u) {
+                    const float inv = 1.0f / w[u];   // one division per edge, not per element
 #pragma unroll
-                    for (int q = 0; q < VE; ++q) acc[q] += v[u][q] / w[u];
+                    for (int q = 0; q < VE; ++q) acc[q] += v[u][q] * inv;
+                }
             }
             if (relu_of) {
                 float y[VE];

@@ -455,19 +455,18 @@ int vec_elems(size_t es, int width, std::initializer_list<int64_t> lds, std::ini
     return v > 4 && es == 4 ? 4 : v;
 }
 
-// dZ masked by the ReLU of the layer's own output: M[r][c] = Y[r][c] > 0 ? dY[r][c] : 0
+// dZ masked by the ReLU of the layer's own output: M[r][c] = Y[r][c] > 0 ? dY[r][c] : 0.
+// One workgroup per row at a time (no per-element division to find the row).
 template <typename TD>
 __global__ __launch_bounds__(256) void k_relu_mask(const TD* __restrict__ dY, int64_t lddy, const TD* __restrict__ Y,
                                                    int64_t ldy, int n_cap, const int32_t* n_d, int out,
                                                    TD* __restrict__ M) {
     const int n = dev_count(n_cap, n_d);
-    const int64_t total = (int64_t)n * out;
-    for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t r = i / out;
-        const int c = (int)(i - r * out);
-        const TD g = dY[r * lddy + c];
-        M[i] = to_f32<TD>(Y[r * ldy + c]) > 0.f ? g : from_f32<TD>(0.f);
-    }
+    for (int r = blockIdx.x; r < n; r += gridDim.x)
+        for (int c = threadIdx.x; c < out; c += blockDim.x) {
+            const TD g = dY[(int64_t)r * lddy + c];
+            M[(int64_t)r * out + c] = to_f32<TD>(Y[(int64_t)r * ldy + c]) > 0.f ? g : from_f32<TD>(0.f);
+        }
 }
 
 // Number of row ranges the weight gradient is split into.  The product has only
@@ -718,7 +717,7 @@ int32_t linear_bwd(const void* dY, int64_t lddy, int32_t dy_dtype, const void* Y
     if (relu && n_cap > 0) {
         // the matrix products take dZ already masked by the layer's own ReLU: one elementwise pass
         void* M = base + w.m_off;
-        const int blocks = (int)std::min<int64_t>(((int64_t)n_cap * out + 255) / 256, 8192);
+        const int blocks = n_cap < 8192 ? n_cap : 8192;
         if (dy_dtype == SDT_F32)
             hipLaunchKernelGGL(k_relu_mask<float>, dim3(blocks), dim3(256), 0, st, static_cast<const float*>(dY), lddy,
                                static_cast<const float*>(Y), ldy, n_cap, n_d, out, static_cast<float*>(M));

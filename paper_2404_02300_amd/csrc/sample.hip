@@ -272,7 +272,8 @@ __global__ __launch_bounds__(TB) void k_relabel(const int32_t* __restrict__ e_pa
     const int n = dev_count(n_cap, n_d);
     const int64_t total = (int64_t)n * fanout;
     for (int64_t idx = (int64_t)blockIdx.x * TB + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * TB) {
-        const int i = (int)(idx / fanout), t = (int)(idx - (int64_t)i * fanout);
+        // total <= 2^31 - 1 (checked by the caller): a 32-bit division, several times cheaper than the 64-bit one
+        const int i = (int)((uint32_t)idx / (uint32_t)fanout), t = (int)((uint32_t)idx - (uint32_t)i * (uint32_t)fanout);
         if (t < m[i]) {
             const int c = map[e_pad[idx]];
             cols[b_indptr[i] + t] = c;
@@ -331,7 +332,8 @@ __global__ __launch_bounds__(TB) void k_transpose_fill(const int32_t* __restrict
     const int n = dev_count(n_cap, n_d);
     const int64_t total = (int64_t)n * fanout;
     for (int64_t idx = (int64_t)blockIdx.x * TB + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * TB) {
-        const int i = (int)(idx / fanout), t = (int)(idx - (int64_t)i * fanout);
+        // total <= 2^31 - 1 (checked by the caller): a 32-bit division, several times cheaper than the 64-bit one
+        const int i = (int)((uint32_t)idx / (uint32_t)fanout), t = (int)((uint32_t)idx - (uint32_t)i * (uint32_t)fanout);
         const int b0 = b_indptr[i];
         if (t < b_indptr[i + 1] - b0) {
             const int c = cols[b0 + t];

@@ -310,7 +310,11 @@ int32_t sdt_sage_linear_bwd(const void *dY, int64_t lddy, int32_t dy_dtype, cons
  * may write to it; a caller who reuses the buffer for something else must zero
  * its first 256 bytes before the next step.
  * sdt_train_step_layout fills `layout` (host) with the workspace size and
- * the offsets of every intermediate. */
+ * the offsets of every intermediate.
+ * Without a timing object the call only launches kernels on `stream`: no
+ * allocation, no copy from or to the host, no synchronisation and no memset
+ * node, so it may be recorded into a HIP graph (stream capture) and replayed;
+ * the graph then repeats the recorded (seeds pointer, seed, step, lr). */
 /* Optional per-stage timing of sdt_train_step with HIP events recorded on the
  * step's own stream (for measurement; adds two event records per selected
  * stage).  A stage is (kind, layer); its bit in `stage_mask` is

@@ -431,3 +431,38 @@ def test_train_loop_equals_sequential_steps(n_aux):
     lay = loop.lay
     for o, nb in [(lay.dW[0], 2 * 64 * 64 * 4), (lay.H[2], 256 * 8 * 4), (lay.indptr[0], 4 * 100)]:
         assert torch.equal(ws[off + o:off + o + nb], seq.ws[o:o + nb])
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_train_step_replays_from_a_captured_graph(bf16):
+    """The step makes no allocation, copy from the host or synchronisation, so a caller may record it
+    into a HIP graph: every replay, with eager work between replays, equals the eager step bit for bit."""
+    _say(f"train step captured into a graph and replayed, bf16={bf16}")
+    wl = gen.WORKLOADS["tiny"] if not bf16 else gen.Workload("small_bf16", "rmat", 13, 12, 40, 10, 48, 3, [6, 4, 3], 128, 7, 2, bf16=True)
+    inst = gen.make_instance(wl)
+    seeds, lr, n = inst.batch(0), 0.05, 4
+    eager = StepRunner(inst.indptr, inst.indices, inst.X, inst.y, inst.W, inst.b, wl.fanouts, wl.batch, bf16=bf16)
+    want = [eager.step(seeds, wl.seed, 3, lr) for _ in range(n)]     # the same mini-batch; the weights move
+    run = StepRunner(inst.indptr, inst.indices, inst.X, inst.y, inst.W, inst.b, wl.fanouts, wl.batch, bf16=bf16)
+    run.seeds = dev(seeds.astype(np.int32))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                                    # one eager pass on the capture stream first
+        B.sdt_train_step(run.graph, run.X, run.y, run.seeds, run.fanouts, run.model, wl.seed, 3, lr, run.loss, run.ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for l in range(run.L):                                           # back to the initial weights
+        run.W[l].copy_(dev(inst.W[l]))
+        run.b[l].copy_(dev(inst.b[l]))
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        B.sdt_train_step(run.graph, run.X, run.y, run.seeds, run.fanouts, run.model, wl.seed, 3, lr, run.loss, run.ws)
+    for k in range(n):
+        g.replay()
+        torch.cuda.synchronize()
+        assert float(run.loss.item()) == want[k], f"replay {k}"
+        scratch = torch.randn(1024, device="cuda").sum().item()      # eager work between the replays
+        assert np.isfinite(scratch)
+    for l in range(run.L):
+        assert torch.equal(run.W[l], eager.W[l]) and torch.equal(run.b[l], eager.b[l])
+    assert torch.equal(run.ws[run.lay.dW[0]:run.lay.dW[0] + 256], eager.ws[eager.lay.dW[0]:eager.lay.dW[0] + 256])

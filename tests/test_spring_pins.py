@@ -1,0 +1,175 @@
+"""Pins of the partitioner oracle (oracle/spring_oracle.py) against cases worked by hand
+from Algorithm 1 of the paper, a textbook scheduling instance and invariants, and then
+the compiled partitioner of sdt_gen against that oracle (bit-equal)."""
+import random
+
+import numpy as np
+import pytest
+
+from oracle import spring_oracle as SO
+
+STAR_DEG = [4, 1, 1, 1, 1]
+STAR_STREAM = [(0, 1), (0, 2), (0, 3), (0, 4)]
+STAR_ADJ = [[1, 2, 3, 4], [0], [0], [0], [0]]
+
+
+def test_stream_clustering_star_collapses_into_the_hub_cluster():
+    # Alg. 1, node clustering: the hub opens cluster 0 with volume 4, each leaf a cluster of
+    # volume 1; the leaf's cluster is the smaller one, so the leaf moves: one cluster, volume 8.
+    cluster, vol, richest = SO.stream_clustering(5, STAR_DEG, STAR_STREAM, tau_vol=100)
+    assert cluster == [0, 0, 0, 0, 0]
+    assert vol == [8, 0, 0, 0, 0]
+    assert richest == [1, 0, 0, 0, 0]      # strict "<": the hub keeps the first leaf
+
+
+def test_stream_clustering_equal_volumes_move_the_first_endpoint():
+    cluster, vol, _ = SO.stream_clustering(2, [1, 1], [(0, 1)], tau_vol=10)
+    assert cluster == [1, 1] and vol == [0, 2]
+
+
+def test_stream_clustering_volume_threshold_blocks_the_move():
+    deg, stream = [1, 2, 1], [(0, 1), (1, 2)]
+    # (0,1): volumes 1 and 2 -> node 0 joins cluster 1 (volume 3); (1,2): 3 > tau = 2, no move
+    assert SO.stream_clustering(3, deg, stream, tau_vol=2)[0] == [1, 1, 2]
+    # tau = 3 admits it: cluster 2 (volume 1) is the smaller, node 2 moves
+    assert SO.stream_clustering(3, deg, stream, tau_vol=3)[0] == [1, 1, 1]
+    # tau = 0 forbids every move
+    assert SO.stream_clustering(3, deg, stream, tau_vol=0)[0] == [0, 1, 2]
+
+
+def test_unseen_nodes_get_their_own_clusters_after_the_stream():
+    cluster, vol, richest = SO.stream_clustering(4, [0, 1, 0, 1], [(3, 1)], tau_vol=10)
+    # node 3 opens cluster 0, node 1 cluster 1; equal volumes: the first endpoint (3) moves
+    assert cluster == [2, 1, 3, 1] and vol == [0, 2, 0, 0] and richest == [-1, 3, -1, 1]
+
+
+def test_merge_star_of_singletons_by_hand():
+    # no moves (tau = 0): five singleton clusters.  p = 2, beta = 1.05: limit 2.625 nodes.
+    # Visit order by (size, number): cluster 0 {hub}: its richest neighbour is leaf 1 -> merged
+    # into cluster 1 (size 2).  Clusters 2, 3, 4 point at the hub, now in cluster 1: 1 + 2 > 2.625.
+    # Cluster 1 again at size 2: its representative's richest neighbour is inside it.
+    cluster, _, richest = SO.stream_clustering(5, STAR_DEG, STAR_STREAM, tau_vol=0)
+    assert cluster == [0, 1, 2, 3, 4]
+    merged = SO.merge_clusters(5, STAR_DEG, cluster, richest, p=2, beta=1.05)
+    assert merged == [1, 1, 2, 3, 4]
+    # p = 1: limit 5.25: every leaf cluster follows the hub
+    assert SO.merge_clusters(5, STAR_DEG, cluster, richest, p=1, beta=1.05) == [1, 1, 1, 1, 1]
+
+
+def test_spring_star_end_to_end_by_hand():
+    out = SO.spring(5, STAR_DEG, STAR_STREAM, p=2, beta=1.05, tau_vol=0)
+    # clusters {0,1} (2 nodes), {2}, {3}, {4}: largest first to the emptier partition, ties to the lower index
+    assert out["part"] == [0, 0, 1, 1, 0]
+    gid, n_owned, rows = SO.partition_graph(5, STAR_ADJ, out["part"], 0)
+    assert (gid, n_owned) == ([0, 1, 4, 2, 3], 3)
+    assert rows == [[1, 2, 3, 4], [0], [0], [0], [0]]
+    gid, n_owned, rows = SO.partition_graph(5, STAR_ADJ, out["part"], 1)
+    assert (gid, n_owned) == ([2, 3, 0], 2)
+    assert rows == [[2], [2], [0, 1]]          # the hub's replica keeps only its owned neighbours
+    assert SO.replication_factor(5, STAR_ADJ, out["part"], 2) == pytest.approx(8 / 5)
+
+
+MERGE_DEG = [5, 4, 3, 3, 1, 2, 1]
+MERGE_CLUSTER = [0, 0, 0, 1, 1, 2, 3]
+MERGE_RICHEST = [1, 0, 0, 0, 3, 3, 5]
+
+
+@pytest.mark.parametrize("p,beta,want", [
+    # limit 7: cluster 2 -> 1 (3 nodes), cluster 3 -> follows node 5 into cluster 1 (4 nodes),
+    # cluster 0's representative points inside, cluster 1 (rank moved up) -> 0: 4 + 3 <= 7
+    (1, 1.0, [0, 0, 0, 0, 0, 0, 0]),
+    # limit 6.3: the last merge no longer fits
+    (1, 0.9, [0, 0, 0, 1, 1, 1, 1]),
+    # limit 3.5: only 2 -> 1 fits
+    (2, 1.0, [0, 0, 0, 1, 1, 1, 3]),
+])
+def test_merge_chain_follows_current_clusters_and_new_ranks(p, beta, want):
+    assert SO.merge_clusters(7, MERGE_DEG, MERGE_CLUSTER, MERGE_RICHEST, p=p, beta=beta) == want
+
+
+def test_list_schedule_textbook_instance():
+    # Graham's tight instance for three machines: jobs 5 5 4 4 3 3 3; sorted list scheduling gives
+    # a makespan of 11 = (4/3 - 1/9) * 9, the optimum being 9.
+    sizes = dict(enumerate([5, 5, 4, 4, 3, 3, 3]))
+    assign = SO.list_schedule(sizes, 3)
+    assert assign == {0: 0, 1: 1, 2: 2, 3: 2, 4: 0, 5: 1, 6: 0}
+    load = [sum(sizes[c] for c in sizes if assign[c] == t) for t in range(3)]
+    assert load == [11, 8, 8]
+
+
+def _random_graph(rng, n, m):
+    pairs = set()
+    while len(pairs) < m:
+        u, v = rng.randrange(n), rng.randrange(n)
+        if u != v:
+            pairs.add((min(u, v), max(u, v)))
+    stream = sorted(pairs)
+    rng.shuffle(stream)
+    stream = [(u, v) if rng.random() < 0.5 else (v, u) for u, v in stream]
+    adj = [[] for _ in range(n)]
+    for u, v in pairs:
+        adj[u].append(v)
+        adj[v].append(u)
+    adj = [sorted(a) for a in adj]
+    return stream, adj, [len(a) for a in adj]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_invariants_on_random_graphs(seed):
+    rng = random.Random(seed)
+    n = rng.choice([40, 90, 200])
+    p = rng.choice([2, 3, 4, 8])
+    stream, adj, deg = _random_graph(rng, n, n * rng.choice([1, 2, 4]))
+    tau = rng.choice([0, 3, sum(deg) // p, 10 ** 9])
+    cluster, vol, richest = SO.stream_clustering(n, deg, stream, tau)
+    # a cluster's volume is the sum of its members' degrees; volumes add up to twice the edges
+    for c in range(len(vol)):
+        assert vol[c] == sum(deg[v] for v in range(n) if cluster[v] == c)
+    assert sum(vol) == sum(deg)
+    # the richest neighbour is a neighbour of maximum degree
+    for v in range(n):
+        if adj[v]:
+            assert richest[v] in adj[v] and deg[richest[v]] == max(deg[w] for w in adj[v])
+        else:
+            assert richest[v] == -1
+    out = SO.spring(n, deg, stream, p, 1.05, tau)
+    assert out["cluster_stream"] == cluster
+    merged, part = out["cluster_merged"], out["part"]
+    # merging only joins whole clusters, and a cluster made of several holds at most beta |V| / p nodes
+    for c in set(cluster):
+        assert len({merged[v] for v in range(n) if cluster[v] == c}) == 1
+    for c in set(merged):
+        mem = [v for v in range(n) if merged[v] == c]
+        if len({cluster[v] for v in mem}) > 1:
+            assert len(mem) <= 1.05 * n / p
+        assert len({part[v] for v in mem}) == 1          # a cluster is assigned as a whole
+    # greedy list scheduling: no partition exceeds the emptiest by more than the largest cluster
+    sizes = {c: sum(1 for v in range(n) if merged[v] == c) for c in set(merged)}
+    load = [sum(1 for v in range(n) if part[v] == t) for t in range(p)]
+    assert sum(load) == n and max(load) - min(load) <= max(sizes.values())
+    # edge pass: owned nodes keep every neighbour, replicas only owned ones, rows symmetric
+    total = 0
+    for t in range(p):
+        gid, n_owned, rows = SO.partition_graph(n, adj, part, t)
+        total += len(gid)
+        assert [part[g] == t for g in gid] == [True] * n_owned + [False] * (len(gid) - n_owned)
+        assert gid[:n_owned] == sorted(gid[:n_owned]) and gid[n_owned:] == sorted(gid[n_owned:])
+        for i, row in enumerate(rows):
+            assert row == sorted(set(row))
+            if i < n_owned:
+                assert sorted(gid[j] for j in row) == adj[gid[i]]
+            else:
+                assert row and all(j < n_owned for j in row)
+                assert sorted(gid[j] for j in row) == [w for w in adj[gid[i]] if part[w] == t]
+            for j in row:
+                assert i in rows[j]
+    assert SO.replication_factor(n, adj, part, p) == pytest.approx(total / n)
+
+
+def test_mirror_cases_of_the_hand_worked_ones():
+    """The same cases seen from the other side, so that a slip in either direction shows."""
+    # the edge written the other way round: node 1 opens cluster 0, node 0 cluster 1, and the FIRST
+    # endpoint (node 1) moves, so both end in cluster 1 again; moving the second would give [0, 0]
+    assert SO.stream_clustering(2, [1, 1], [(1, 0)], tau_vol=10)[0] == [1, 1]
+    # following the ORIGINAL cluster of a richest neighbour (cluster 2, emptied) would leave node 6 alone
+    assert SO.merge_clusters(7, MERGE_DEG, MERGE_CLUSTER, MERGE_RICHEST, p=1, beta=1.0)[6] == 0

@@ -55,7 +55,7 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="products",
-                    choices=["tiny", "products", "dense", "sparse_bf16", "fullgraph", "sampling", "gather"],
+                    choices=["tiny", "products", "products_spring", "dense", "sparse_bf16", "fullgraph", "sampling", "gather"],
                     help="the five configured workloads; 'sampling' / 'gather' time that stage alone at a size "
                          "where it is bandwidth-bound (every owned node of the products-shaped graph as a destination)")
     ap.add_argument("--model", default="sage", choices=["sage", "gcn", "gat"],
@@ -79,7 +79,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    wl = gen.WORKLOADS["products" if args.workload in ("sampling", "gather") else args.workload]
+    wl = gen.WORKLOADS["products" if args.workload in ("sampling", "gather", "products_spring") else args.workload]
     K, Wm = args.steps, args.warmup
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB read + 1 GiB written
@@ -93,10 +93,13 @@ def main():
         return bench_stage_at_scale(args, wl)
 
     t0 = time.time()
-    inst = gen.make_instance(wl)
+    # products_spring: the products-shaped graph cut into four partitions by the paper's streaming
+    # partitioner; the step runs on partition 0 (owned nodes + replicas), seeds from its owned nodes
+    spring = args.workload == "products_spring"
+    inst = gen.make_partition_instance(wl, p=4, which=0) if spring else gen.make_instance(wl)
     nnz_graph = int(inst.indptr[-1])
-    log(f"[bench] generated {wl.name}: N={wl.n_nodes} nnz={nnz_graph} avg_deg={nnz_graph / wl.n_nodes:.2f} "
-        f"in {time.time() - t0:.1f}s")
+    log(f"[bench] generated {args.workload}: N={inst.n_nodes} nnz={nnz_graph} avg_deg={nnz_graph / inst.n_nodes:.2f} "
+        f"in {time.time() - t0:.1f}s" + (f" {inst.info}" if spring else ""))
 
     dt = torch.bfloat16 if wl.bf16 else torch.float32
     graph = sdt.Csr(torch.from_numpy(inst.indptr).cuda(), torch.from_numpy(inst.indices).cuda())
@@ -251,7 +254,7 @@ def main():
 
     # roofline of the dominant stage, from the events recorded inside the timed region
     roofline = rate(dominant[0], dominant[1], float(np.mean(dom_ms)) * 1e-3)
-    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((wl.name, dominant[0], dominant[1])) if args.model == "sage" else None
+    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((wl.name, dominant[0], dominant[1])) if args.model == "sage" and not spring else None
     stage_ms = {f"{k}[{l}]": v for (k, l), v in stage_t.items()}
     others = [rate(k, l, v * 1e-3) for (k, l), v in stage_t.items()]
 
@@ -288,9 +291,12 @@ def main():
         "value": round(K / elapsed, 2), "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": round(elapsed / K * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if wl.bf16 else "f32", "data": "synthetic",
-        "config": {"workload": f"{wl.name}: {wl.kind} 2^{wl.log2n} nodes, {nnz_graph} CSR entries, F={wl.feat}, "
+        "config": {"workload": (f"{wl.name}: {wl.kind} 2^{wl.log2n} nodes, {nnz_graph} CSR entries, " if not spring else
+                                f"products_spring: partition 0 of 4 of the {wl.kind} 2^{wl.log2n} graph without isolated nodes "
+                                f"(streaming partitioner, beta 1.05): {inst.n_owned} owned + {inst.n_nodes - inst.n_owned} replica "
+                                f"nodes, {nnz_graph} CSR entries, ") + f"F={wl.feat}, "
                                f"C={wl.classes}, {L}-layer {'GAT' if gat else 'GCN' if gcn else 'GraphSAGE-mean'} hidden {wl.hidden}, fanout {wl.fanouts}, "
-                               f"batch {wl.batch}, seeds from the first {wl.owned_frac:g} of the ids",
+                               f"batch {wl.batch}, seeds from " + ("the owned nodes" if spring else f"the first {wl.owned_frac:g} of the ids"),
                    "lr": args.lr, "seed": wl.seed},
         "sampled_edges_per_s": round(edges_per_step * K / elapsed, 1),
         "sampled_edges_per_step": round(edges_per_step, 1),

@@ -20,15 +20,15 @@ from typing import List, Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "gen.cpp")
+_SRCS = [os.path.join(_HERE, "gen.cpp"), os.path.join(_HERE, "spring.cpp")]
 _LIB_PATH = os.path.join(_HERE, "libsdt_gen.so")
 _lib = None
 
 
 def build(force: bool = True) -> str:
-    """Compile gen.cpp into libsdt_gen.so next to it."""
+    """Compile gen.cpp and spring.cpp into libsdt_gen.so next to them."""
     if force or not os.path.exists(_LIB_PATH):
-        cmd = ["g++", "-O3", "-fopenmp", "-shared", "-fPIC", "-std=c++17", _SRC, "-o", _LIB_PATH]
+        cmd = ["g++", "-O3", "-fopenmp", "-shared", "-fPIC", "-std=c++17", *_SRCS, "-o", _LIB_PATH]
         subprocess.run(cmd, check=True)
     return _LIB_PATH
 
@@ -64,6 +64,27 @@ def _load():
     L.sdtgen_uniform_f32.argtypes = [vp, i64, ctypes.c_float, u64, u32]
     L.sdtgen_seed_batch.restype = i32
     L.sdtgen_seed_batch.argtypes = [vp, i32, i32, i32, u64, u32]
+    L.sdtgen_edge_count.restype = i64
+    L.sdtgen_edge_count.argtypes = [i64, vp, vp]
+    L.sdtgen_edge_stream.restype = None
+    L.sdtgen_edge_stream.argtypes = [i64, vp, vp, u64, vp, vp]
+    L.sdtgen_spring.restype = vp
+    L.sdtgen_spring.argtypes = [i64, vp, vp, vp, i64, i32, f64, i64]
+    L.sdtgen_spring_clusters.restype = i64
+    L.sdtgen_spring_clusters.argtypes = [vp, i32]
+    L.sdtgen_spring_copy.restype = None
+    L.sdtgen_spring_copy.argtypes = [vp, vp, vp, vp]
+    L.sdtgen_spring_free.restype = None
+    L.sdtgen_spring_free.argtypes = [vp]
+    L.sdtgen_partition.restype = vp
+    L.sdtgen_partition.argtypes = [i64, vp, vp, vp, i32]
+    for name in ("nodes", "owned", "nnz"):
+        getattr(L, "sdtgen_partition_" + name).restype = i64
+        getattr(L, "sdtgen_partition_" + name).argtypes = [vp]
+    L.sdtgen_partition_copy.restype = None
+    L.sdtgen_partition_copy.argtypes = [vp, vp, vp, vp]
+    L.sdtgen_partition_free.restype = None
+    L.sdtgen_partition_free.argtypes = [vp]
     _lib = L
     return L
 
@@ -132,6 +153,53 @@ def seed_batch(batch: int, lo: int, hi: int, seed: int, step: int) -> np.ndarray
 
 
 # --------------------------------------------------------------------------
+# Partitions with replicas (the paper's streaming partitioner as a workload producer)
+# --------------------------------------------------------------------------
+def edge_stream(indptr: np.ndarray, indices: np.ndarray, order_seed: int = 1):
+    """Every undirected edge of a symmetric CSR once, as two int32 arrays (u, v): in row order with
+    u < v when order_seed is 0, else in a seeded random order with a random orientation."""
+    L, n = _load(), len(indptr) - 1
+    m = L.sdtgen_edge_count(n, _ptr(indptr), _ptr(indices))
+    eu, ev = np.empty(m, dtype=np.int32), np.empty(m, dtype=np.int32)
+    L.sdtgen_edge_stream(n, _ptr(indptr), _ptr(indices), order_seed, _ptr(eu), _ptr(ev))
+    return eu, ev
+
+
+def spring(indptr: np.ndarray, indices: np.ndarray, p: int, beta: float = 1.05, tau_vol: Optional[int] = None,
+           order_seed: int = 1, stream=None) -> dict:
+    """Algorithm 1 of the paper over the edge stream of a symmetric CSR.  tau_vol defaults to the
+    graph's volume over p (the paper names the threshold without giving its value).  Returns
+    part / cluster_stream / cluster_merged (int32 [n]) and the two cluster counts."""
+    L, n = _load(), len(indptr) - 1
+    degree = np.ascontiguousarray(np.diff(indptr).astype(np.int64))
+    eu, ev = stream if stream is not None else edge_stream(indptr, indices, order_seed)
+    eu, ev = np.ascontiguousarray(eu, dtype=np.int32), np.ascontiguousarray(ev, dtype=np.int32)
+    if tau_vol is None:
+        tau_vol = int(degree.sum()) // p
+    h = L.sdtgen_spring(n, _ptr(degree), _ptr(eu), _ptr(ev), len(eu), p, beta, tau_vol)
+    out = {k: np.empty(n, dtype=np.int32) for k in ("part", "cluster_stream", "cluster_merged")}
+    L.sdtgen_spring_copy(h, _ptr(out["part"]), _ptr(out["cluster_stream"]), _ptr(out["cluster_merged"]))
+    out["n_clusters_stream"], out["n_clusters_merged"] = L.sdtgen_spring_clusters(h, 0), L.sdtgen_spring_clusters(h, 1)
+    L.sdtgen_spring_free(h)
+    return out
+
+
+def partition_csr(indptr: np.ndarray, indices: np.ndarray, part: np.ndarray, which: int):
+    """The edge pass for one partition: (local indptr int64, local indices int32, global_id int32,
+    n_owned).  Local ids: owned nodes in ascending global id, then replicas in ascending global id;
+    an owned row keeps its full neighbour list, a replica's row only its owned neighbours."""
+    L, n = _load(), len(indptr) - 1
+    part = np.ascontiguousarray(part, dtype=np.int32)
+    h = L.sdtgen_partition(n, _ptr(indptr), _ptr(indices), _ptr(part), which)
+    nl, nnz = L.sdtgen_partition_nodes(h), L.sdtgen_partition_nnz(h)
+    lp, li, gid = np.empty(nl + 1, dtype=np.int64), np.empty(nnz, dtype=np.int32), np.empty(nl, dtype=np.int32)
+    L.sdtgen_partition_copy(h, _ptr(lp), _ptr(li), _ptr(gid))
+    n_owned = L.sdtgen_partition_owned(h)
+    L.sdtgen_partition_free(h)
+    return lp, li, gid, int(n_owned)
+
+
+# --------------------------------------------------------------------------
 # Workload recipes
 # --------------------------------------------------------------------------
 @dataclass
@@ -187,9 +255,18 @@ class Instance:
     y: Optional[np.ndarray]   # int32 [N]
     W: list
     b: list
+    n_owned: Optional[int] = None          # a partition with replicas: local ids [0, n_owned) are owned
+    global_id: Optional[np.ndarray] = None  # ... and local id i is node global_id[i] of the partitioned graph
+    info: Optional[dict] = None
+
+    @property
+    def n_nodes(self) -> int:
+        return len(self.indptr) - 1
 
     @property
     def seed_range(self):
+        if self.n_owned is not None:
+            return 0, self.n_owned
         return 0, max(self.wl.batch, int(self.wl.n_nodes * self.wl.owned_frac))
 
     def batch(self, step: int) -> np.ndarray:
@@ -216,3 +293,35 @@ def make_instance(wl: Workload, with_features: bool = True) -> Instance:
     y = labels(wl.n_nodes, wl.classes, wl.seed) if with_features else None
     W, b = glorot_sage_weights(wl.dims, wl.seed)
     return Instance(wl, indptr, indices, X, y, W, b)
+
+
+def drop_isolated(indptr: np.ndarray, indices: np.ndarray):
+    """The same graph without its degree-0 nodes, the others renumbered in ascending order."""
+    deg = np.diff(indptr)
+    keep = deg > 0
+    new = np.cumsum(keep) - 1
+    out_ptr = np.concatenate([[0], np.cumsum(deg[keep])]).astype(np.int64)
+    return out_ptr, new[indices].astype(np.int32)
+
+
+def make_partition_instance(wl: Workload, p: int = 4, which: int = 0, beta: float = 1.05, order_seed: int = 1,
+                            with_features: bool = True) -> Instance:
+    """One worker's partition as the paper's partitioner produces it: the workload's graph without
+    its isolated nodes (the public graphs have next to none; R-MAT leaves many) goes through
+    Algorithm 1 with p partitions, and partition `which` comes back as a local graph: owned nodes
+    first, replicas of their outside neighbours after them, features and labels those of the
+    global nodes.  Mini-batch seeds are drawn from the owned nodes only."""
+    indptr, indices = drop_isolated(*make_graph(wl))
+    n = len(indptr) - 1
+    sp = spring(indptr, indices, p, beta=beta, order_seed=order_seed)
+    lp, li, gid, n_owned = partition_csr(indptr, indices, sp["part"], which)
+    X = y = None
+    if with_features:
+        X = np.ascontiguousarray(normal_features(n, wl.feat, wl.seed, bf16=wl.bf16)[gid])
+        y = np.ascontiguousarray(labels(n, wl.classes, wl.seed)[gid])
+    W, b = glorot_sage_weights(wl.dims, wl.seed)
+    loads = np.bincount(sp["part"], minlength=p)
+    info = dict(p=p, which=which, beta=beta, n_global=n, n_local=len(gid), n_owned=n_owned, nnz_local=int(lp[-1]),
+                owned_per_partition=loads.tolist(), n_clusters_stream=int(sp["n_clusters_stream"]),
+                n_clusters_merged=int(sp["n_clusters_merged"]))
+    return Instance(wl, lp, li, X, y, W, b, n_owned=n_owned, global_id=gid, info=info)

@@ -68,7 +68,21 @@ def test_train_round_two_partitions():
     _say("synchronisation round: two partitions on one GPU")
     wls = [gen.WORKLOADS["tiny"], gen.Workload("tiny_b", "rmat", 13, 12, 64, 8, 64, 2, [10, 5], 256, 31, 2)]
     insts = [gen.make_instance(w) for w in wls]
-    fan, batch, lr, n_steps, seed = [10, 5], 256, 0.05, [3, 2], 77
+    _check_round(insts, wls, [3, 2])
+
+
+def test_train_round_over_partitions_with_replicas():
+    """The three partitions the streaming partitioner makes of one graph (owned nodes + replicas),
+    trained one after the other and averaged in proportion to their owned nodes."""
+    _say("synchronisation round: three partitions with replicas of one graph")
+    wl = gen.Workload("tiny_p", "rmat", 13, 12, 64, 8, 64, 2, [10, 5], 256, 5, 2)
+    insts = [gen.make_partition_instance(wl, p=3, which=k) for k in range(3)]
+    assert sum(i.n_owned for i in insts) == insts[0].info["n_global"]
+    _check_round(insts, [wl] * 3, [2, 3, 2])
+
+
+def _check_round(insts, wls, n_steps):
+    fan, batch, lr, seed = [10, 5], 256, 0.05, 77
     init = insts[0]                                            # the synchronised starting weights
     Wg = [dev(w) for w in init.W]
     bg = [dev(v) for v in init.b]
@@ -80,7 +94,7 @@ def test_train_round_two_partitions():
         seeds = dev(np.stack([inst.batch(s) for s in range(ns)]).astype(np.int32))
         Wl = [torch.zeros_like(w) for w in Wg]
         bl = [torch.zeros_like(v) for v in bg]
-        n_train = int(wl.n_nodes * wl.owned_frac)
+        n_train = inst.n_owned if inst.n_owned is not None else int(wl.n_nodes * wl.owned_frac)
         parts.append(B.make_partition(g, X, y, seeds, n_train))
         locs.append(B.make_model(wls[0].dims, Wl, bl))
         keep.append((g, X, y, seeds, Wl, bl, n_train))
@@ -98,7 +112,7 @@ def test_train_round_two_partitions():
         W2 = [dev(w) for w in init.W]
         b2 = [dev(v) for v in init.b]
         m2 = B.make_model(wls[0].dims, W2, b2)
-        ws2 = torch.empty(B.sdt_train_loop_workspace_bytes(wl.n_nodes, batch, fan, m2, B.SDT_F32), dtype=torch.uint8,
+        ws2 = torch.empty(B.sdt_train_loop_workspace_bytes(inst.n_nodes, batch, fan, m2, B.SDT_F32), dtype=torch.uint8,
                           device="cuda")
         l2 = torch.zeros(ns, dtype=torch.float32, device="cuda")
         B.sdt_train_loop(g, X, y, seeds, fan, m2, seed, 0, lr, l2, ws2, None)

@@ -402,6 +402,17 @@ def test_train_step_ragged_dims_fp32():
     _run_and_check(inst, wl, steps=1)
 
 
+@pytest.mark.parametrize("which", [0, 2])
+def test_train_step_on_a_partition_with_replicas(which):
+    """One worker's partition as the paper's partitioner makes it (section on graph partitioning): owned
+    nodes keep their full neighbour lists, replicas only their owned neighbours, seeds are owned nodes."""
+    _say(f"train step on partition {which} of 3 (owned nodes + replicas)")
+    wl = gen.Workload("part", "rmat", 13, 12, 48, 7, 64, 2, [6, 4], 192, 17, 1)
+    inst = gen.make_partition_instance(wl, p=3, which=which)
+    assert inst.n_owned < inst.n_nodes and int(inst.batch(0).max()) < inst.n_owned
+    _run_and_check(inst, wl, steps=2, check_float_steps=(0, 1))
+
+
 @pytest.mark.parametrize("n_aux", [0, 1, 2, 3])
 def test_train_loop_equals_sequential_steps(n_aux):
     _say(f"train loop vs sequential steps, {n_aux} auxiliary streams")

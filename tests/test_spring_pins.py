@@ -173,3 +173,52 @@ def test_mirror_cases_of_the_hand_worked_ones():
     assert SO.stream_clustering(2, [1, 1], [(1, 0)], tau_vol=10)[0] == [1, 1]
     # following the ORIGINAL cluster of a richest neighbour (cluster 2, emptied) would leave node 6 alone
     assert SO.merge_clusters(7, MERGE_DEG, MERGE_CLUSTER, MERGE_RICHEST, p=1, beta=1.0)[6] == 0
+
+
+# ---- the compiled partitioner of sdt_gen against the oracle ---------------------------------------
+def _csr(adj):
+    indptr = np.zeros(len(adj) + 1, dtype=np.int64)
+    indptr[1:] = np.cumsum([len(a) for a in adj])
+    indices = np.array([w for a in adj for w in a], dtype=np.int32)
+    return indptr, indices
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_compiled_partitioner_equals_oracle(seed):
+    import sdt_gen as gen
+    rng = random.Random(100 + seed)
+    n = rng.choice([30, 120, 400])
+    p = rng.choice([1, 2, 4, 7])
+    _, adj, deg = _random_graph(rng, n, n * rng.choice([1, 3, 6]))
+    indptr, indices = _csr(adj)
+    beta = rng.choice([1.0, 1.05, 1.5])
+    tau = rng.choice([0, 5, sum(deg) // p, None])
+    eu, ev = gen.edge_stream(indptr, indices, order_seed=seed)      # seed 0: row order
+    pairs = sorted((min(a, b), max(a, b)) for a, b in zip(eu.tolist(), ev.tolist()))
+    assert pairs == sorted((u, w) for u in range(n) for w in adj[u] if w > u)       # each edge exactly once
+    got = gen.spring(indptr, indices, p, beta=beta, tau_vol=tau, stream=(eu, ev))
+    want = SO.spring(n, deg, list(zip(eu.tolist(), ev.tolist())), p, beta, sum(deg) // p if tau is None else tau)
+    for k in ("cluster_stream", "cluster_merged", "part"):
+        assert got[k].tolist() == want[k], k
+    assert got["n_clusters_stream"] == len(set(want["cluster_stream"]))
+    assert got["n_clusters_merged"] == len(set(want["cluster_merged"]))
+    for t in range(p):
+        lp, li, gid, n_owned = gen.partition_csr(indptr, indices, got["part"], t)
+        wgid, wown, wrows = SO.partition_graph(n, adj, want["part"], t)
+        assert gid.tolist() == wgid and n_owned == wown
+        assert lp.tolist() == [0] + np.cumsum([len(r) for r in wrows]).tolist()
+        assert li.tolist() == [j for r in wrows for j in r]
+
+
+def test_compiled_partitioner_on_a_generated_graph():
+    """R-MAT graph of the tiny workload's recipe, p = 4: the oracle on the same stream gives the same partition."""
+    import sdt_gen as gen
+    indptr, indices = gen.rmat_csr(10, 1024 * 6, 5)
+    n = len(indptr) - 1
+    deg = np.diff(indptr).tolist()
+    eu, ev = gen.edge_stream(indptr, indices, order_seed=7)
+    got = gen.spring(indptr, indices, 4, stream=(eu, ev))
+    want = SO.spring(n, deg, list(zip(eu.tolist(), ev.tolist())), 4, 1.05, sum(deg) // 4)
+    assert got["part"].tolist() == want["part"]
+    load = np.bincount(got["part"], minlength=4)
+    assert load.sum() == n and load.max() - load.min() <= np.bincount(got["cluster_merged"]).max()

@@ -68,3 +68,30 @@ def test_workload_table_matches_the_configs():
     assert w["dense"].dims == [602, 256, 41] and w["dense"].fanouts == [25, 10]
     assert w["sparse_bf16"].dims == [128, 256, 256, 172] and w["sparse_bf16"].bf16
     assert w["fullgraph"].dims == [256, 256] and w["fullgraph"].log2n == 22
+
+
+def test_partition_instance_recipe():
+    """A partition with replicas: owned nodes of all partitions tile the graph, features and labels are
+    the global nodes', seeds are owned nodes, the local graph of an owned node is its global one."""
+    wl = gen.Workload("part", "rmat", 11, 10, 16, 5, 16, 2, [4, 3], 32, 9, 1)
+    ip, ix = gen.drop_isolated(*gen.make_graph(wl))
+    n = len(ip) - 1
+    assert np.all(np.diff(ip) > 0) and ix.max() == n - 1
+    X = gen.normal_features(n, wl.feat, wl.seed)
+    y = gen.labels(n, wl.classes, wl.seed)
+    seen = np.zeros(n, dtype=np.int64)
+    for k in range(3):
+        inst = gen.make_partition_instance(wl, p=3, which=k)
+        gid = inst.global_id
+        seen[gid[:inst.n_owned]] += 1
+        assert inst.n_nodes == len(gid) and inst.info["n_global"] == n
+        assert np.array_equal(inst.X, X[gid]) and np.array_equal(inst.y, y[gid])
+        b = inst.batch(0)
+        assert b.min() >= 0 and b.max() < inst.n_owned and len(set(b.tolist())) == wl.batch
+        for i in (0, inst.n_owned // 2, inst.n_owned - 1):          # owned rows: the global neighbour list
+            loc = inst.indices[inst.indptr[i]:inst.indptr[i + 1]]
+            assert sorted(gid[loc].tolist()) == ix[ip[gid[i]]:ip[gid[i] + 1]].tolist()
+        for i in range(inst.n_owned, inst.n_nodes):                 # replica rows: owned neighbours only
+            loc = inst.indices[inst.indptr[i]:inst.indptr[i + 1]]
+            assert len(loc) > 0 and loc.max() < inst.n_owned
+    assert np.all(seen == 1)

@@ -283,6 +283,18 @@ int32_t sdt_gat_aggregate_bwd(const sdt_block *blk /*host struct*/, const float 
 int32_t sdt_sage_linear_fwd(const void *Hself, int64_t ldh, const void *A, int64_t lda, int32_t n_cap,
                             const int32_t *n_d, int32_t in, int32_t out, const float *W, const float *b,
                             int32_t relu, int32_t dtype, void *Y, int64_t ldy, int32_t y_dtype, void *stream);
+/* One full-neighbour layer over a whole graph in ONE launch (Sec. IV-A: the evaluation pass runs
+ * the trained model over every node's full neighbourhood):
+ *   Y[v,:] = act(H[v,:] W[0:in,:] + mean_{u in row v} H[u,:] W[in:2in,:] + b),  zeros for the mean of an empty row.
+ * The aggregated rows stay in LDS and never reach HBM; the result equals
+ * sdt_sage_aggregate_csr_fwd followed by sdt_sage_linear_fwd bit for bit.  Supported shapes
+ * (sdt_sage_layer_csr_fused_ok returns 1): fp32, in a multiple of 128, out a multiple of 4 up to 256;
+ * H (leading dimension ldh, a multiple of 4) and W must be 16-byte aligned; other shapes return
+ * SDT_ERR_INVALID_ARG and are served by the two calls.  b may be NULL.  No workspace. */
+int32_t sdt_sage_layer_csr_fused_ok(int32_t in, int32_t out, int32_t dtype);
+int32_t sdt_sage_layer_csr_fwd(const sdt_csr *graph /*host struct*/, const void *H, int64_t ldh, int32_t in, int32_t out,
+                               const float *W, const float *b, int32_t relu, int32_t dtype, void *Y, int64_t ldy,
+                               void *stream);
 /* Backward.  dZ = dY masked by Y > 0 when relu (Y in `dtype`, may be NULL
  * otherwise); dW = [Hself|A]^T dZ (fp32 [2in,out]); db = column sums of dZ;
  * dSelf = dZ W[0:in]^T and dAgg = dZ W[in:2in]^T in `dtype` with leading

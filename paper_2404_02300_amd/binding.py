@@ -80,6 +80,8 @@ EXPORTS = {
     "sdt_gather_features": (_i32, [_vp, _i64, _i32, _i32, _vp, _i32, _vp, _vp, _i64, _vp]),
     "sdt_sage_aggregate_fwd": (_i32, [_vp, _vp, _i64, _i32, _i32, _vp, _i64, _vp]),
     "sdt_sage_aggregate_csr_fwd": (_i32, [_vp, _vp, _i64, _i32, _i32, _vp, _i64, _vp]),
+    "sdt_sage_layer_csr_fused_ok": (_i32, [_i32, _i32, _i32]),
+    "sdt_sage_layer_csr_fwd": (_i32, [_vp, _vp, _i64, _i32, _i32, _vp, _vp, _i32, _i32, _vp, _i64, _vp]),
     "sdt_sage_aggregate_gather_fwd": (_i32, [_vp, _vp, _i64, _i32, _i32, _vp, _i64, _vp]),
     "sdt_sage_aggregate_bwd": (_i32, [_vp, _vp, _i64, _vp, _i64, _vp, _i32, _i32, _vp, _i64, _vp]),
     "sdt_sage_linear_fwd": (_i32, [_vp, _i64, _vp, _i64, _i32, _vp, _i32, _i32, _vp, _vp, _i32, _i32, _vp, _i64,
@@ -249,6 +251,17 @@ def sdt_sage_aggregate_gather_fwd(blk: Block, X: torch.Tensor, A: torch.Tensor):
 def sdt_sage_aggregate_csr_fwd(graph: Csr, H: torch.Tensor, A: torch.Tensor):
     _check(lib().sdt_sage_aggregate_csr_fwd(ctypes.byref(graph.c), _ptr(H), H.stride(0), H.shape[1], dtype_code(H),
                                             _ptr(A), A.stride(0), _stream()))
+
+
+def sdt_sage_layer_csr_fused_ok(fin: int, fout: int, dtype: int) -> bool:
+    return bool(lib().sdt_sage_layer_csr_fused_ok(fin, fout, dtype))
+
+
+def sdt_sage_layer_csr_fwd(graph: Csr, H: torch.Tensor, W: torch.Tensor, b: Optional[torch.Tensor], relu: bool,
+                           Y: torch.Tensor):
+    """One full-neighbour layer over the whole graph in one launch: Y = act([H | mean_nbr(H)] W + b)."""
+    _check(lib().sdt_sage_layer_csr_fwd(ctypes.byref(graph.c), _ptr(H), H.stride(0), H.shape[1], W.shape[1], _ptr(W),
+                                        _ptr(b), int(relu), dtype_code(H), _ptr(Y), Y.stride(0), _stream()))
 
 
 def sdt_sage_aggregate_bwd(blk: Block, dAgg: torch.Tensor, dSelf: Optional[torch.Tensor], dH: torch.Tensor,

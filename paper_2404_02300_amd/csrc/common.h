@@ -193,6 +193,11 @@ int32_t reduce_all(const PendingReduce* r, int32_t n, const OptArgs& opt, const 
 // sdt_sage_linear_fwd with one more promise: rows_padded = every row of Hself and A is followed by
 // ZEROS up to its stride (ldh, lda), so a row width that is not a multiple of the vector width
 // still moves in whole vectors
+// One full-neighbour GraphSAGE layer over a whole CSR in a single launch (fp32; see linear.hip).
+bool sage_layer_fused_ok(int64_t n_nodes, const void* H, int64_t ldh, int32_t in, int32_t out, const float* W,
+                         int32_t dtype, const void* Y, int64_t ldy);
+int32_t sage_layer_fused_fwd(const sdt_csr* g, const float* H, int64_t ldh, int32_t in, int32_t out, const float* W,
+                             const float* b, int32_t relu, float* Y, int64_t ldy, hipStream_t st);
 int32_t linear_fwd(const void* Hself, int64_t ldh, const void* A, int64_t lda, int32_t n_cap, const int32_t* n_d,
                    int32_t in, int32_t out, const float* W, const float* b, int32_t relu, int32_t dtype, void* Y,
                    int64_t ldy, int32_t y_dtype, bool rows_padded, hipStream_t st);

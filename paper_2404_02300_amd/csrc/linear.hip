@@ -186,7 +186,10 @@ __device__ __forceinline__ void zero_acc(floatx16& a) {
 // Every path then has the same number of loads in flight at every wait, which lets the compiler
 // wait for the oldest register stage only (vmcnt = loads of the younger ones).
 // Requires nit >= 1.
-template <typename TL, bool A_KC, bool B_KC, typename SA, typename SB, typename Fetch, typename Hook>
+// A_RESIDENT: the A operand of every step already lies in LDS, step `it` at As + it * (one step's
+// tile), in the layout a staged step has; SA is then an empty type and only B is staged.
+template <typename TL, bool A_KC, bool B_KC, typename SA, typename SB, bool A_RESIDENT = false, typename Fetch,
+          typename Hook>
 __device__ __forceinline__ void gemm_mainloop(int nit, float* As, float* Bs, Fetch&& fetch, Hook&& hook,
                                               floatx16 (&acc)[TL::TM][TL::TN]) {
     constexpr int BK = TL::BK, NS = TL::NS;
@@ -205,11 +208,11 @@ __device__ __forceinline__ void gemm_mainloop(int nit, float* As, float* Bs, Fet
     for (int it = 0; it < nit; it += NS) {
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            float* Ab = As + (s & 1) * A_ELEMS;
+            float* Ab = As + (A_RESIDENT ? it + s : (s & 1)) * A_ELEMS;
             float* Bb = Bs + (s & 1) * B_ELEMS;
             const bool live = s == 0 || it + s < nit;   // the step count need not be a multiple of NS
             if (live) {
-                sa[s].template store<LDA>(Ab);
+                if constexpr (!A_RESIDENT) sa[s].template store<LDA>(Ab);
                 sb[s].template store<LDB>(Bb);
                 __syncthreads();
             }
@@ -273,6 +276,130 @@ __global__ __launch_bounds__(TL::NT) void k_linear_fwd(const TH* __restrict__ Hs
             float z = v + (bias ? bias[col] : 0.f);
             if (relu && !(z > 0.f)) z = 0.f;
             Y[(int64_t)row * ldy + col] = from_f32<TY>(z);
+        }
+    });
+}
+
+// ---------------------------------------------------------------------------------
+// A whole-graph layer in one launch: Y = act(H Wself + mean_nbr(H) Wneigh + b), fp32.
+// The aggregated rows never reach HBM: a workgroup owns 64 rows, first takes the self product
+// through the usual staged loop, then twice (for in = 256) gathers 128 aggregated columns of its
+// rows into LDS -- one half-wave per row, the neighbours' rows read straight from H -- and feeds them
+// to the matrix cores from there.  Two workgroups fit a CU (74 KB of LDS, <= 128 registers): while
+// one gathers (HBM-bound) the other multiplies (MFMA-bound).  The sums run in the order of the
+// stand-alone aggregation kernels (edge order, eight rows in flight; rows longer than 2048 edges in
+// sixteen contiguous parts added in order), and the reduction over k in the order of k_linear_fwd,
+// so the result equals the two-launch path bit for bit.
+// ---------------------------------------------------------------------------------
+using TileF = Tile<64, 256, 16, 1, 8>;
+constexpr int FUSED_COLS = 128;    // aggregated columns resident at a time
+constexpr int FUSED_U = 8;         // neighbour rows in flight per lane
+constexpr int FUSED_LONG = 2048;   // longer rows are summed by all sixteen half-waves together
+constexpr int FUSED_TILE_FLOATS = (FUSED_COLS / TileF::BK) * TileF::BM * TileF::LD_KC;
+constexpr int FUSED_B_FLOATS = 2 * TileF::BK * TileF::LDB_OC;
+constexpr size_t FUSED_LDS_BYTES = (size_t)(FUSED_TILE_FLOATS + FUSED_B_FLOATS) * sizeof(float) + (TileF::BM + 4) * sizeof(int);
+struct NoStage {};
+
+// Sum of the rows H[cols[e]] (the lane's four columns) for e in [e0, e1), in edge order.
+__device__ __forceinline__ float4 fused_sum_rows(const int32_t* __restrict__ cols, int64_t e0, int64_t e1,
+                                                 const float* __restrict__ Hc, int64_t ldh) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int64_t e = e0; e < e1; e += FUSED_U) {
+        int c[FUSED_U];
+#pragma unroll
+        for (int u = 0; u < FUSED_U; ++u) c[u] = (e + u < e1) ? cols[e + u] : -1;
+        float4 v[FUSED_U];
+#pragma unroll
+        for (int u = 0; u < FUSED_U; ++u) {
+            v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (c[u] >= 0) v[u] = *reinterpret_cast<const float4*>(Hc + (int64_t)c[u] * ldh);
+        }
+#pragma unroll
+        for (int u = 0; u < FUSED_U; ++u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
+    }
+    return acc;
+}
+
+__global__ __launch_bounds__(TileF::NT) void k_sage_layer_fused(const int64_t* __restrict__ indptr,
+                                                                const int32_t* __restrict__ cols, int n,
+                                                                const float* __restrict__ H, int64_t ldh, int in, int out,
+                                                                const float* __restrict__ W, const float* __restrict__ bias,
+                                                                int relu, float* __restrict__ Y, int64_t ldy) {
+    using TL = TileF;
+    constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK, LDK = TL::LD_KC;
+    extern __shared__ __align__(16) float fused_lds[];
+    float* Ts = fused_lds;                         // [FUSED_COLS / BK][BM][LDK]; its head doubles as the self product's A stages
+    float* Bs = fused_lds + FUSED_TILE_FLOATS;     // [2][BK][BN + 4]; scratch of the long-row sums between products
+    int* long_rows = reinterpret_cast<int*>(Bs + FUSED_B_FLOATS);   // [BM] + count
+    int* n_long = long_rows + BM;
+    const int row0 = blockIdx.x * BM;
+    floatx16 acc[TL::TM][TL::TN];
+#pragma unroll
+    for (int a = 0; a < TL::TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TL::TN; ++b) zero_acc(acc[a][b]);
+    using SA = Stage<float, BM, BK, 4, false, TL::NT>;
+    using SB = Stage<float, BK, BN, 4, false, TL::NT>;
+    const int nk = in / BK;
+    // ---- self product --------------------------------------------------------------
+    {
+        auto fetch = [&](int it, SA& sa, SB& sb) {
+            sa.load(H, ldh, row0, n, it * BK, in);      // past the last step: clamped addresses, zeros
+            sb.load(W, out, it * BK, in, 0, out);
+        };
+        gemm_mainloop<TL, true, false, SA, SB>(nk, Ts, Bs, fetch, [](const float*) {}, acc);
+    }
+    // ---- aggregated columns, FUSED_COLS at a time -------------------------------------
+    const int hw = threadIdx.x >> 5, hl = threadIdx.x & 31;      // sixteen half-waves of 32 lanes x 4 columns
+    for (int c0 = 0; c0 < in; c0 += FUSED_COLS) {
+        if (threadIdx.x == 0) *n_long = 0;
+        __syncthreads();                             // the previous product has read its last tiles
+        const float* Hc = H + c0 + hl * 4;
+        float* Tc = Ts + ((hl >> 2) * BM) * LDK + (hl & 3) * 4;   // this lane's columns: step hl / 4, offset 4 (hl % 4)
+        for (int r = hw; r < BM; r += 16) {
+            const int row = row0 + r;
+            if (row >= n) continue;                  // rows past the end: their tile rows stay undefined and are never stored
+            const int64_t e0 = indptr[row], e1 = indptr[row + 1];
+            if (e1 - e0 > FUSED_LONG) {
+                if (hl == 0) long_rows[atomicAdd(n_long, 1)] = r;
+                continue;
+            }
+            float4 a = fused_sum_rows(cols, e0, e1, Hc, ldh);
+            if (e1 > e0) {
+                const float m = (float)(e1 - e0);
+                a.x = a.x / m; a.y = a.y / m; a.z = a.z / m; a.w = a.w / m;
+            }
+            *reinterpret_cast<float4*>(Tc + r * LDK) = a;
+        }
+        __syncthreads();
+        const int cnt = *n_long;
+        for (int li = 0; li < cnt; ++li) {           // the list order depends on the atomics, each row's result does not
+            const int r = long_rows[li];
+            const int64_t e0 = indptr[row0 + r], e1 = indptr[row0 + r + 1];
+            const int64_t chunk = (e1 - e0 + 15) / 16;
+            const int64_t w0 = e0 + hw * chunk, w1 = (w0 + chunk < e1) ? w0 + chunk : e1;
+            const float4 part = fused_sum_rows(cols, w0, w1, Hc, ldh);
+            *reinterpret_cast<float4*>(Bs + hw * FUSED_COLS + hl * 4) = part;
+            __syncthreads();
+            if (threadIdx.x < FUSED_COLS) {
+                float sum = 0.f;
+#pragma unroll
+                for (int w = 0; w < 16; ++w) sum += Bs[w * FUSED_COLS + threadIdx.x];
+                Ts[((threadIdx.x / BK) * BM + r) * LDK + threadIdx.x % BK] = sum / (float)(e1 - e0);
+            }
+            __syncthreads();
+        }
+        auto fetch = [&](int it, NoStage&, SB& sb) {
+            sb.load(W + (int64_t)(in + c0) * out, out, it * BK, in - c0, 0, out);   // past the last step: zeros, never used
+        };
+        gemm_mainloop<TL, true, false, NoStage, SB, true>(FUSED_COLS / BK, Ts, Bs, fetch, [](const float*) {}, acc);
+    }
+    for_each_acc<TL>(acc, [&](int r, int c, float v) {
+        const int row = row0 + r;
+        if (row < n && c < out) {
+            float z = v + (bias ? bias[c] : 0.f);
+            if (relu && !(z > 0.f)) z = 0.f;
+            Y[(int64_t)row * ldy + c] = z;
         }
     });
 }
@@ -629,6 +756,53 @@ int32_t sdt::linear_fwd(const void* Hself, int64_t ldh, const void* A, int64_t l
         launch_fwd<bf16_t, float, TileS>(Hself, ldh, A, lda, n_cap, n_d, in, out, W, b, relu, Y, ldy, rows_padded, st);
     SDT_CHECK_LAUNCH("linear_fwd");
     return SDT_OK;
+}
+
+// ---- whole-graph layer in one launch ------------------------------------------------
+bool sdt::sage_layer_fused_ok(int64_t n_nodes, const void* H, int64_t ldh, int32_t in, int32_t out, const float* W,
+                              int32_t dtype, const void* Y, int64_t ldy) {
+    (void)Y; (void)ldy;
+    return dtype == SDT_F32 && in >= FUSED_COLS && in % FUSED_COLS == 0 && out >= 4 && out <= TileF::BN && out % 4 == 0 &&
+           ldh % 4 == 0 && reinterpret_cast<uintptr_t>(H) % 16 == 0 && reinterpret_cast<uintptr_t>(W) % 16 == 0 &&
+           n_nodes > 0 && n_nodes <= 0x7FFFFFFF - TileF::BM;
+}
+
+int32_t sdt::sage_layer_fused_fwd(const sdt_csr* g, const float* H, int64_t ldh, int32_t in, int32_t out, const float* W,
+                                  const float* b, int32_t relu, float* Y, int64_t ldy, hipStream_t st) {
+    static bool opted = false;    // more than 64 KB of dynamic LDS has to be opted into, once
+    if (!opted) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sage_layer_fused), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)FUSED_LDS_BYTES) != hipSuccess) {
+            set_error("sage_layer_fused: cannot raise the dynamic LDS limit to %zu bytes", FUSED_LDS_BYTES);
+            return SDT_ERR_HIP;
+        }
+        opted = true;
+    }
+    const int n = (int)g->n_nodes;
+    hipLaunchKernelGGL(k_sage_layer_fused, dim3(ceil_div(n, TileF::BM)), dim3(TileF::NT), FUSED_LDS_BYTES, st, g->indptr,
+                       g->indices, n, H, ldh, in, out, W, b, relu, Y, ldy);
+    SDT_CHECK_LAUNCH("sage_layer_fused");
+    return SDT_OK;
+}
+
+extern "C" int32_t sdt_sage_layer_csr_fused_ok(int32_t in, int32_t out, int32_t dtype) {
+    return dtype == SDT_F32 && in >= FUSED_COLS && in % FUSED_COLS == 0 && out >= 4 && out <= TileF::BN && out % 4 == 0;
+}
+
+extern "C" int32_t sdt_sage_layer_csr_fwd(const sdt_csr* g, const void* H, int64_t ldh, int32_t in, int32_t out,
+                                          const float* W, const float* b, int32_t relu, int32_t dtype, void* Y, int64_t ldy,
+                                          void* stream) {
+    SDT_REQUIRE(g, SDT_ERR_INVALID_ARG, "sdt_sage_layer_csr_fwd: null graph");
+    SDT_REQUIRE(g->n_nodes >= 0 && in > 0 && out > 0 && ldh >= in && ldy >= out, SDT_ERR_INVALID_ARG,
+                "sdt_sage_layer_csr_fwd: bad sizes n=%lld in=%d out=%d", (long long)g->n_nodes, in, out);
+    if (g->n_nodes == 0) return SDT_OK;
+    SDT_REQUIRE(g->indptr && g->indices && H && W && Y, SDT_ERR_INVALID_ARG, "sdt_sage_layer_csr_fwd: null pointer");
+    SDT_REQUIRE(sage_layer_fused_ok(g->n_nodes, H, ldh, in, out, W, dtype, Y, ldy), SDT_ERR_INVALID_ARG,
+                "sdt_sage_layer_csr_fwd: needs fp32, in a multiple of %d, out a multiple of 4 up to %d, 16-byte aligned "
+                "H rows and W (got in=%d out=%d dtype=%d ldh=%lld); use sdt_sage_aggregate_csr_fwd + sdt_sage_linear_fwd",
+                FUSED_COLS, TileF::BN, in, out, dtype, (long long)ldh);
+    return sage_layer_fused_fwd(g, static_cast<const float*>(H), ldh, in, out, W, b, relu, static_cast<float*>(Y), ldy,
+                                static_cast<hipStream_t>(stream));
 }
 
 extern "C" int32_t sdt_sage_linear_fwd(const void* Hself, int64_t ldh, const void* A, int64_t lda, int32_t n_cap,

@@ -132,3 +132,65 @@ def _check_round(insts, wls, n_steps):
     for l in range(2):
         assert_close(f64(Wg[l]), orc.model_average([f64(k[4][l]) for k in keep], n_train), 1e-6, f"averaged W[{l}]")
         assert_close(f64(bg[l]), orc.model_average([f64(k[5][l]) for k in keep], n_train), 1e-6, f"averaged b[{l}]")
+
+
+# ------------------------------------------------ whole-graph layer in one launch
+def _graph_with_hub(rng, n, avg_deg, hub_deg):
+    """Random CSR (rows sorted, no duplicates) with empty rows, and row 5 a hub of hub_deg neighbours."""
+    rows = []
+    for v in range(n):
+        d = 0 if v % 17 == 3 else int(rng.integers(1, 2 * avg_deg))
+        if v == 5:
+            d = hub_deg
+        rows.append(np.sort(rng.choice(n, size=min(d, n), replace=False)).astype(np.int32))
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    indptr[1:] = np.cumsum([len(r) for r in rows])
+    return indptr, np.concatenate(rows).astype(np.int32)
+
+
+@pytest.mark.parametrize("n,fin,fout,relu,hub", [(3500, 256, 256, True, 3000), (64, 128, 256, False, 10),
+                                                 (4133, 256, 100, True, 2049), (777, 384, 4, True, 2048),
+                                                 (1, 128, 8, False, 1)])
+def test_fused_layer_equals_two_launches_and_oracle(n, fin, fout, relu, hub):
+    _say(f"whole-graph layer in one launch: n={n} in={fin} out={fout} relu={relu} longest row {hub}")
+    rng = np.random.default_rng(n + fin + fout)
+    indptr, indices = _graph_with_hub(rng, max(n, 1), 12, min(hub, n))
+    H = rng.standard_normal((n, fin)).astype(np.float32)
+    W = (rng.standard_normal((2 * fin, fout)) / np.sqrt(2 * fin)).astype(np.float32)
+    b = rng.standard_normal(fout).astype(np.float32)
+    assert B.sdt_sage_layer_csr_fused_ok(fin, fout, B.SDT_F32)
+    g = B.Csr(dev(indptr), dev(indices))
+    Hd, Wd, bd = dev(H), dev(W), dev(b)
+    Y = torch.full((n, fout), float("nan"), dtype=torch.float32, device="cuda")
+    B.sdt_sage_layer_csr_fwd(g, Hd, Wd, bd, relu, Y)
+    # the two-launch path
+    A = torch.empty(n, fin, dtype=torch.float32, device="cuda")
+    Y2 = torch.empty(n, fout, dtype=torch.float32, device="cuda")
+    B.sdt_sage_aggregate_csr_fwd(g, Hd, A)
+    B.sdt_sage_linear_fwd(Hd, A, Wd, bd, relu, Y2)
+    torch.cuda.synchronize()
+    Aref = orc.aggregate_fwd(indptr, indices, H.astype(np.float64))
+    ref = orc.linear_fwd(H.astype(np.float64), Aref, W.astype(np.float64), b.astype(np.float64), relu)
+    assert_close(f64(Y), ref, 1e-5, "fused layer against the oracle")
+    assert torch.equal(Y, Y2), "fused layer against the two launches (same summation orders: bit-equal)"
+    # strided input and output, no bias
+    Hs = torch.zeros(n, fin + 8, dtype=torch.float32, device="cuda")
+    Hs[:, :fin] = Hd
+    Ys = torch.full((n, fout + 3), -7.0, dtype=torch.float32, device="cuda")
+    B.sdt_sage_layer_csr_fwd(g, Hs[:, :fin], Wd, None, relu, Ys[:, :fout])
+    torch.cuda.synchronize()
+    ref0 = orc.linear_fwd(H.astype(np.float64), Aref, W.astype(np.float64), np.zeros(fout), relu)
+    assert_close(f64(Ys[:, :fout]), ref0, 1e-5, "fused layer, strided, no bias")
+    assert bool((Ys[:, fout:] == -7.0).all())
+
+
+def test_fused_layer_rejects_unsupported_shapes():
+    assert not B.sdt_sage_layer_csr_fused_ok(100, 256, B.SDT_F32)
+    assert not B.sdt_sage_layer_csr_fused_ok(256, 300, B.SDT_F32)
+    assert not B.sdt_sage_layer_csr_fused_ok(256, 256, B.SDT_BF16)
+    g = B.Csr(dev(np.array([0, 1, 2], dtype=np.int64)), dev(np.array([1, 0], dtype=np.int32)))
+    H = torch.zeros(2, 100, device="cuda")
+    W = torch.zeros(200, 256, device="cuda")
+    Y = torch.zeros(2, 256, device="cuda")
+    with pytest.raises(B.SdtError):
+        B.sdt_sage_layer_csr_fwd(g, H, W, None, True, Y)

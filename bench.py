@@ -422,6 +422,23 @@ def bench_fullgraph(args, wl):
     elapsed = time.perf_counter() - t0
     agg_s = float(np.mean([e[0].elapsed_time(e[1]) for e in ev])) * 1e-3
     gemm_s = float(np.mean([e[1].elapsed_time(e[2]) for e in ev])) * 1e-3
+    # the same layer in one launch (aggregated rows stay in LDS)
+    Yf = torch.empty(N, O, dtype=torch.float32, device="cuda")
+    fev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(K)]
+    for _ in range(Wm):
+        sdt.sdt_sage_layer_csr_fwd(g, X, W, b, True, Yf)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        fev[i][0].record()
+        sdt.sdt_sage_layer_csr_fwd(g, X, W, b, True, Yf)
+        fev[i][1].record()
+    torch.cuda.synchronize()
+    fused_elapsed = time.perf_counter() - t0
+    fused_s = float(np.mean([e[0].elapsed_time(e[1]) for e in fev])) * 1e-3
+    fused_equal = bool(torch.equal(Y, Yf))
+    log(f"[bench] two launches {agg_s * 1e3:.2f} + {gemm_s * 1e3:.2f} ms; one launch {fused_s * 1e3:.2f} ms; "
+        f"results bit-equal: {fused_equal}")
     agg_bytes = nnz * (F * 4 + 4) + N * (F * 4 + 8)          # every neighbour row read once per edge
     compulsory = 2 * N * F * 4 + nnz * 4 + N * 8            # each row read once, A written once
     flops = 2.0 * N * (2 * F) * O
@@ -459,6 +476,11 @@ def bench_fullgraph(args, wl):
                  "TFLOPs": round(flops / gemm_s / 1e12, 2), "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, "linear")),
                  "peak": MFMA_FP32_PEAK_TFLOPS, "frac": round(flops / gemm_s / 1e12 / MFMA_FP32_PEAK_TFLOPS, 4),
                  "flops_per_launch": flops, "avg_launch_us": round(gemm_s * 1e6, 1)},
+        # the same layer through sdt_sage_layer_csr_fwd (aggregated rows kept in LDS, no N x F buffer)
+        "one_launch": {"kernel": "k_sage_layer_fused<256>", "nodes_per_s": round(N * K / fused_elapsed, 1),
+                       "avg_launch_us": round(fused_s * 1e6, 1), "bit_equal_to_two_launches": fused_equal,
+                       "hbm_buffer_saved_bytes": int(N * F * 4),
+                       "algorithmic_GBps": round((agg_bytes + N * O * 4) / fused_s / 1e9, 1)},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

@@ -282,54 +282,71 @@ __global__ __launch_bounds__(TL::NT) void k_linear_fwd(const TH* __restrict__ Hs
 
 // ---------------------------------------------------------------------------------
 // A whole-graph layer in one launch: Y = act(H Wself + mean_nbr(H) Wneigh + b), fp32.
-// The aggregated rows never reach HBM: a workgroup owns 64 rows, first takes the self product
-// through the usual staged loop, then twice (for in = 256) gathers 128 aggregated columns of its
-// rows into LDS -- one half-wave per row, the neighbours' rows read straight from H -- and feeds them
-// to the matrix cores from there.  Two workgroups fit a CU (74 KB of LDS, <= 128 registers): while
-// one gathers (HBM-bound) the other multiplies (MFMA-bound).  The sums run in the order of the
-// stand-alone aggregation kernels (edge order, eight rows in flight; rows longer than 2048 edges in
-// sixteen contiguous parts added in order), and the reduction over k in the order of k_linear_fwd,
-// so the result equals the two-launch path bit for bit.
+// The aggregated rows never reach HBM (no n x in buffer): a workgroup owns 32 rows, first takes the
+// self product through the usual staged loop, then gathers COLS aggregated columns of its rows into
+// LDS (a wave per row for COLS = 256, a half-wave for 128: whole 1 KB / 512 B pieces of the
+// neighbours' rows, read straight from H, twelve in flight per lane, the next row's offsets and first
+// column ids fetched under the current row) and feeds them to the matrix cores from there; layers
+// wider than COLS repeat the last two steps.  Two workgroups fit a CU (74 KB of LDS, 128 registers).
+// The sums run in the order of the stand-alone aggregation kernels (edge order; rows longer than
+// 2048 edges in sixteen contiguous parts added in order), and the reduction over k in the order of
+// k_linear_fwd, so the result equals the two-launch path bit for bit.
 // ---------------------------------------------------------------------------------
-using TileF = Tile<64, 256, 16, 1, 8>;
-constexpr int FUSED_COLS = 128;    // aggregated columns resident at a time
-constexpr int FUSED_U = 8;         // neighbour rows in flight per lane
-constexpr int FUSED_LONG = 2048;   // longer rows are summed by all sixteen half-waves together
-constexpr int FUSED_TILE_FLOATS = (FUSED_COLS / TileF::BK) * TileF::BM * TileF::LD_KC;
+using TileF = Tile<32, 256, 16, 1, 8>;
+constexpr int FUSED_U = 12;        // neighbour rows in flight per lane
+constexpr int FUSED_LONG = 2048;   // longer rows are summed by the whole workgroup together
 constexpr int FUSED_B_FLOATS = 2 * TileF::BK * TileF::LDB_OC;
-constexpr size_t FUSED_LDS_BYTES = (size_t)(FUSED_TILE_FLOATS + FUSED_B_FLOATS) * sizeof(float) + (TileF::BM + 4) * sizeof(int);
+constexpr int fused_tile_floats(int cols) { return (cols / TileF::BK) * TileF::BM * TileF::LD_KC; }
+constexpr size_t fused_lds_bytes(int cols) {
+    return (size_t)(fused_tile_floats(cols) + FUSED_B_FLOATS) * sizeof(float) + (TileF::BM + 4) * sizeof(int);
+}
+static_assert(16 * 256 <= FUSED_B_FLOATS, "the sixteen partial sums of a long row borrow the weight stages");
 struct NoStage {};
 
-// Sum of the rows H[cols[e]] (the lane's four columns) for e in [e0, e1), in edge order.
-__device__ __forceinline__ float4 fused_sum_rows(const int32_t* __restrict__ cols, int64_t e0, int64_t e1,
-                                                 const float* __restrict__ Hc, int64_t ldh) {
+// First batch of column ids of the edge range [e0, e1) (all -1 for an empty range).
+__device__ __forceinline__ void fused_first_ids(const int32_t* __restrict__ cols, int64_t e0, int64_t e1, int (&c)[FUSED_U]) {
+#pragma unroll
+    for (int u = 0; u < FUSED_U; ++u) c[u] = (e0 + u < e1) ? cols[e0 + u] : -1;
+}
+
+// Sum of the rows H[cols[e]] (the lane's four columns) for e in [e0, e1), in edge order; needs e0 < e1
+// and the ids of the first batch in c.  The ids of the next batch are fetched while the rows of the
+// current one are in flight, so a batch costs one memory round trip, not two; after the last batch
+// that is the first batch of [n0, n1), the range to be summed next, left in c.
+__device__ __forceinline__ float4 fused_sum_rows(const int32_t* __restrict__ cols, int64_t e0, int64_t e1, int64_t n0,
+                                                 int64_t n1, int (&c)[FUSED_U], const float* __restrict__ Hc, int64_t ldh) {
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int64_t e = e0; e < e1; e += FUSED_U) {
-        int c[FUSED_U];
-#pragma unroll
-        for (int u = 0; u < FUSED_U; ++u) c[u] = (e + u < e1) ? cols[e + u] : -1;
         float4 v[FUSED_U];
 #pragma unroll
         for (int u = 0; u < FUSED_U; ++u) {
             v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (c[u] >= 0) v[u] = *reinterpret_cast<const float4*>(Hc + (int64_t)c[u] * ldh);
         }
+        const bool more = e + FUSED_U < e1;
+        const int64_t p0 = more ? e + FUSED_U : n0, p1 = more ? e1 : n1;
+#pragma unroll
+        for (int u = 0; u < FUSED_U; ++u) c[u] = (p0 + u < p1) ? cols[p0 + u] : -1;
 #pragma unroll
         for (int u = 0; u < FUSED_U; ++u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
     }
     return acc;
 }
 
-__global__ __launch_bounds__(TileF::NT) void k_sage_layer_fused(const int64_t* __restrict__ indptr,
+template <int COLS>
+__global__ __launch_bounds__(TileF::NT, 4) void k_sage_layer_fused(const int64_t* __restrict__ indptr,
                                                                 const int32_t* __restrict__ cols, int n,
                                                                 const float* __restrict__ H, int64_t ldh, int in, int out,
                                                                 const float* __restrict__ W, const float* __restrict__ bias,
                                                                 int relu, float* __restrict__ Y, int64_t ldy) {
     using TL = TileF;
     constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK, LDK = TL::LD_KC;
+    constexpr int G = COLS / 4;            // lanes per row
+    constexpr int NG = TL::NT / G;         // rows in flight per workgroup
+    static_assert(16 % NG == 0 && BM % NG == 0, "a long row's sixteen parts are dealt out evenly");
     extern __shared__ __align__(16) float fused_lds[];
-    float* Ts = fused_lds;                         // [FUSED_COLS / BK][BM][LDK]; its head doubles as the self product's A stages
-    float* Bs = fused_lds + FUSED_TILE_FLOATS;     // [2][BK][BN + 4]; scratch of the long-row sums between products
+    float* Ts = fused_lds;                         // [COLS / BK][BM][LDK]; its head doubles as the self product's A stages
+    float* Bs = fused_lds + fused_tile_floats(COLS);   // [2][BK][BN + 4]; scratch of the long-row sums between products
     int* long_rows = reinterpret_cast<int*>(Bs + FUSED_B_FLOATS);   // [BM] + count
     int* n_long = long_rows + BM;
     const int row0 = blockIdx.x * BM;
@@ -340,36 +357,50 @@ __global__ __launch_bounds__(TileF::NT) void k_sage_layer_fused(const int64_t* _
         for (int b = 0; b < TL::TN; ++b) zero_acc(acc[a][b]);
     using SA = Stage<float, BM, BK, 4, false, TL::NT>;
     using SB = Stage<float, BK, BN, 4, false, TL::NT>;
-    const int nk = in / BK;
+    const int grp = threadIdx.x / G, gl = threadIdx.x % G;
     // ---- self product --------------------------------------------------------------
     {
         auto fetch = [&](int it, SA& sa, SB& sb) {
             sa.load(H, ldh, row0, n, it * BK, in);      // past the last step: clamped addresses, zeros
             sb.load(W, out, it * BK, in, 0, out);
         };
-        gemm_mainloop<TL, true, false, SA, SB>(nk, Ts, Bs, fetch, [](const float*) {}, acc);
+        gemm_mainloop<TL, true, false, SA, SB>(in / BK, Ts, Bs, fetch, [](const float*) {}, acc);
     }
-    // ---- aggregated columns, FUSED_COLS at a time -------------------------------------
-    const int hw = threadIdx.x >> 5, hl = threadIdx.x & 31;      // sixteen half-waves of 32 lanes x 4 columns
-    for (int c0 = 0; c0 < in; c0 += FUSED_COLS) {
+    // ---- aggregated columns, COLS at a time ---------------------------------------------
+    for (int c0 = 0; c0 < in; c0 += COLS) {
         if (threadIdx.x == 0) *n_long = 0;
         __syncthreads();                             // the previous product has read its last tiles
-        const float* Hc = H + c0 + hl * 4;
-        float* Tc = Ts + ((hl >> 2) * BM) * LDK + (hl & 3) * 4;   // this lane's columns: step hl / 4, offset 4 (hl % 4)
-        for (int r = hw; r < BM; r += 16) {
-            const int row = row0 + r;
-            if (row >= n) continue;                  // rows past the end: their tile rows stay undefined and are never stored
-            const int64_t e0 = indptr[row], e1 = indptr[row + 1];
+        const float* Hc = H + c0 + gl * 4;
+        float* Tc = Ts + ((gl >> 2) * BM) * LDK + (gl & 3) * 4;   // this lane's columns: step gl / 4, offset 4 (gl % 4)
+        // the rows of a group one after the other; the edge offsets and the first column ids of the next
+        // row are fetched while the current row is being summed
+        auto row_range = [&](int r, int64_t& lo, int64_t& hi) {      // what a row contributes to the plain pass
+            lo = hi = 0;
+            if (r < BM && row0 + r < n) { lo = indptr[row0 + r]; hi = indptr[row0 + r + 1]; }
+        };
+        int64_t e0, e1;
+        row_range(grp, e0, e1);
+        int c[FUSED_U];
+        fused_first_ids(cols, e0, e1 - e0 > FUSED_LONG ? e0 : e1, c);
+        for (int r = grp; r < BM; r += NG) {
+            int64_t n0, n1;
+            row_range(r + NG, n0, n1);
+            const int64_t n1s = n1 - n0 > FUSED_LONG ? n0 : n1;      // a long next row: nothing to prefetch
             if (e1 - e0 > FUSED_LONG) {
-                if (hl == 0) long_rows[atomicAdd(n_long, 1)] = r;
-                continue;
-            }
-            float4 a = fused_sum_rows(cols, e0, e1, Hc, ldh);
-            if (e1 > e0) {
+                if (gl == 0) long_rows[atomicAdd(n_long, 1)] = r;
+                fused_first_ids(cols, n0, n1s, c);
+            } else if (e1 > e0) {
+                float4 a = fused_sum_rows(cols, e0, e1, n0, n1s, c, Hc, ldh);
                 const float m = (float)(e1 - e0);
                 a.x = a.x / m; a.y = a.y / m; a.z = a.z / m; a.w = a.w / m;
+                *reinterpret_cast<float4*>(Tc + r * LDK) = a;
+            } else {
+                // an empty row, or one past the end of the graph (its tile row is never stored)
+                *reinterpret_cast<float4*>(Tc + r * LDK) = make_float4(0.f, 0.f, 0.f, 0.f);
+                fused_first_ids(cols, n0, n1s, c);
             }
-            *reinterpret_cast<float4*>(Tc + r * LDK) = a;
+            e0 = n0;
+            e1 = n1;
         }
         __syncthreads();
         const int cnt = *n_long;
@@ -377,14 +408,21 @@ __global__ __launch_bounds__(TileF::NT) void k_sage_layer_fused(const int64_t* _
             const int r = long_rows[li];
             const int64_t e0 = indptr[row0 + r], e1 = indptr[row0 + r + 1];
             const int64_t chunk = (e1 - e0 + 15) / 16;
-            const int64_t w0 = e0 + hw * chunk, w1 = (w0 + chunk < e1) ? w0 + chunk : e1;
-            const float4 part = fused_sum_rows(cols, w0, w1, Hc, ldh);
-            *reinterpret_cast<float4*>(Bs + hw * FUSED_COLS + hl * 4) = part;
+            for (int w = grp; w < 16; w += NG) {
+                const int64_t w0 = e0 + w * chunk, w1 = (w0 + chunk < e1) ? w0 + chunk : e1;
+                float4 part = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (w0 < w1) {
+                    int lc[FUSED_U];
+                    fused_first_ids(cols, w0, w1, lc);
+                    part = fused_sum_rows(cols, w0, w1, w1, w1, lc, Hc, ldh);
+                }
+                *reinterpret_cast<float4*>(Bs + w * COLS + gl * 4) = part;
+            }
             __syncthreads();
-            if (threadIdx.x < FUSED_COLS) {
+            if (threadIdx.x < COLS) {
                 float sum = 0.f;
 #pragma unroll
-                for (int w = 0; w < 16; ++w) sum += Bs[w * FUSED_COLS + threadIdx.x];
+                for (int w = 0; w < 16; ++w) sum += Bs[w * COLS + threadIdx.x];
                 Ts[((threadIdx.x / BK) * BM + r) * LDK + threadIdx.x % BK] = sum / (float)(e1 - e0);
             }
             __syncthreads();
@@ -392,7 +430,7 @@ __global__ __launch_bounds__(TileF::NT) void k_sage_layer_fused(const int64_t* _
         auto fetch = [&](int it, NoStage&, SB& sb) {
             sb.load(W + (int64_t)(in + c0) * out, out, it * BK, in - c0, 0, out);   // past the last step: zeros, never used
         };
-        gemm_mainloop<TL, true, false, NoStage, SB, true>(FUSED_COLS / BK, Ts, Bs, fetch, [](const float*) {}, acc);
+        gemm_mainloop<TL, true, false, NoStage, SB, true>(COLS / BK, Ts, Bs, fetch, [](const float*) {}, acc);
     }
     for_each_acc<TL>(acc, [&](int r, int c, float v) {
         const int row = row0 + r;
@@ -762,31 +800,39 @@ int32_t sdt::linear_fwd(const void* Hself, int64_t ldh, const void* A, int64_t l
 bool sdt::sage_layer_fused_ok(int64_t n_nodes, const void* H, int64_t ldh, int32_t in, int32_t out, const float* W,
                               int32_t dtype, const void* Y, int64_t ldy) {
     (void)Y; (void)ldy;
-    return dtype == SDT_F32 && in >= FUSED_COLS && in % FUSED_COLS == 0 && out >= 4 && out <= TileF::BN && out % 4 == 0 &&
+    return dtype == SDT_F32 && in >= 128 && in % 128 == 0 && out >= 4 && out <= TileF::BN && out % 4 == 0 &&
            ldh % 4 == 0 && reinterpret_cast<uintptr_t>(H) % 16 == 0 && reinterpret_cast<uintptr_t>(W) % 16 == 0 &&
            n_nodes > 0 && n_nodes <= 0x7FFFFFFF - TileF::BM;
 }
 
 int32_t sdt::sage_layer_fused_fwd(const sdt_csr* g, const float* H, int64_t ldh, int32_t in, int32_t out, const float* W,
                                   const float* b, int32_t relu, float* Y, int64_t ldy, hipStream_t st) {
-    static bool opted = false;    // more than 64 KB of dynamic LDS has to be opted into, once
-    if (!opted) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sage_layer_fused), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)FUSED_LDS_BYTES) != hipSuccess) {
-            set_error("sage_layer_fused: cannot raise the dynamic LDS limit to %zu bytes", FUSED_LDS_BYTES);
+    // 256 resident columns (a wave per row, 1 KB pieces) when the width allows, else 128
+    const bool wide = in % 256 == 0;
+    static bool opted[2] = {false, false};    // more than 64 KB of dynamic LDS has to be opted into, once per kernel
+    const void* fn = wide ? reinterpret_cast<const void*>(&k_sage_layer_fused<256>)
+                          : reinterpret_cast<const void*>(&k_sage_layer_fused<128>);
+    const size_t lds = wide ? fused_lds_bytes(256) : fused_lds_bytes(128);
+    if (!opted[wide]) {
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+            set_error("sage_layer_fused: cannot raise the dynamic LDS limit to %zu bytes", lds);
             return SDT_ERR_HIP;
         }
-        opted = true;
+        opted[wide] = true;
     }
     const int n = (int)g->n_nodes;
-    hipLaunchKernelGGL(k_sage_layer_fused, dim3(ceil_div(n, TileF::BM)), dim3(TileF::NT), FUSED_LDS_BYTES, st, g->indptr,
-                       g->indices, n, H, ldh, in, out, W, b, relu, Y, ldy);
+    if (wide)
+        hipLaunchKernelGGL(k_sage_layer_fused<256>, dim3(ceil_div(n, TileF::BM)), dim3(TileF::NT), lds, st, g->indptr,
+                           g->indices, n, H, ldh, in, out, W, b, relu, Y, ldy);
+    else
+        hipLaunchKernelGGL(k_sage_layer_fused<128>, dim3(ceil_div(n, TileF::BM)), dim3(TileF::NT), lds, st, g->indptr,
+                           g->indices, n, H, ldh, in, out, W, b, relu, Y, ldy);
     SDT_CHECK_LAUNCH("sage_layer_fused");
     return SDT_OK;
 }
 
 extern "C" int32_t sdt_sage_layer_csr_fused_ok(int32_t in, int32_t out, int32_t dtype) {
-    return dtype == SDT_F32 && in >= FUSED_COLS && in % FUSED_COLS == 0 && out >= 4 && out <= TileF::BN && out % 4 == 0;
+    return dtype == SDT_F32 && in >= 128 && in % 128 == 0 && out >= 4 && out <= TileF::BN && out % 4 == 0;
 }
 
 extern "C" int32_t sdt_sage_layer_csr_fwd(const sdt_csr* g, const void* H, int64_t ldh, int32_t in, int32_t out,
@@ -800,7 +846,7 @@ extern "C" int32_t sdt_sage_layer_csr_fwd(const sdt_csr* g, const void* H, int64
     SDT_REQUIRE(sage_layer_fused_ok(g->n_nodes, H, ldh, in, out, W, dtype, Y, ldy), SDT_ERR_INVALID_ARG,
                 "sdt_sage_layer_csr_fwd: needs fp32, in a multiple of %d, out a multiple of 4 up to %d, 16-byte aligned "
                 "H rows and W (got in=%d out=%d dtype=%d ldh=%lld); use sdt_sage_aggregate_csr_fwd + sdt_sage_linear_fwd",
-                FUSED_COLS, TileF::BN, in, out, dtype, (long long)ldh);
+                128, TileF::BN, in, out, dtype, (long long)ldh);
     return sage_layer_fused_fwd(g, static_cast<const float*>(H), ldh, in, out, W, b, relu, static_cast<float*>(Y), ldy,
                                 static_cast<hipStream_t>(stream));
 }

@@ -251,7 +251,8 @@ __global__ __launch_bounds__(TB) void k_gat_mask_bias(const int32_t* counts, flo
     const int n = counts[0];
     const int r0 = blockIdx.x * VEC_ROWS, r1 = min(n, r0 + VEC_ROWS);
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    for (int f0 = 0; f0 < F; f0 += 64) {
+    // the 64-column slices of a chunk are dealt to gridDim.y workgroups (few chunks: more of them in flight)
+    for (int f0 = blockIdx.y * 64; f0 < F; f0 += gridDim.y * 64) {
         const int f = f0 + lane;
         float s = 0.f;
         if (f < F) {
@@ -617,7 +618,8 @@ int32_t sdt::gat_mask_bias(const sdt_block* blk, float* g, int64_t ldg, const fl
     const GatWs w = gat_ws(ws, blk->cap_src, blk->cap_dst, F);
     SDT_REQUIRE(ws && ws_bytes >= w.total && aligned16(ws), SDT_ERR_WORKSPACE, "gat_mask_bias: workspace of %zu bytes needed, %zu given",
                 w.total, ws_bytes);
-    hipLaunchKernelGGL(k_gat_mask_bias, dim3(w.nchunk), dim3(TB), 0, st, blk->counts, g, ldg, Y, ldy, F, w.biasq);
+    hipLaunchKernelGGL(k_gat_mask_bias, dim3(w.nchunk, w.nchunk >= 1024 ? 1 : (F + 63) / 64), dim3(TB), 0, st, blk->counts, g, ldg, Y,
+                       ldy, F, w.biasq);
     SDT_CHECK_LAUNCH("gat mask + bias partials");
     *Qb = w.biasq;
     *n_chunks = w.nchunk;

@@ -26,6 +26,18 @@ def test_products_full_size():
     _run_and_check(inst, wl, steps=wl.steps, check_float_steps=(0, 1, wl.steps - 1))
 
 
+@pytest.mark.timeout(600)
+def test_products_spring_full_size():
+    """The step on partition 0 of 4 of the products-shaped graph as the streaming partitioner cuts it
+    (owned nodes + replicas; the workload of `bench.py --workload products_spring`)."""
+    wl = gen.WORKLOADS["products"]
+    t = time.time()
+    inst = gen.make_partition_instance(wl, p=4, which=0)
+    _say(f"products_spring: generated in {time.time() - t:.1f}s, {inst.info}")
+    assert inst.n_owned < inst.n_nodes
+    _run_and_check(inst, wl, steps=20, check_float_steps=(0, 19))
+
+
 @pytest.mark.timeout(900)
 def test_dense_full_size():
     wl = gen.WORKLOADS["dense"]
@@ -79,6 +91,13 @@ def test_fullgraph_layer_sampled_rows():
     refY = orc.linear_fwd(X[rows].astype(np.float64), refA, W[0], b[0], relu=True)
     assert_close(f64(Y[rt]), refY, TOL[torch.float32], "Y (sampled rows)")
     _say(f"fullgraph: {len(rows)} rows checked, max degree {deg.max()}")
+    # the same layer in one launch (aggregated rows kept in LDS): bit-equal on every row
+    Y1 = torch.full((N, O), float("nan"), dtype=torch.float32, device="cuda")
+    B.sdt_sage_layer_csr_fwd(g, Xd, dev(W[0]), dev(b[0]), True, Y1)
+    torch.cuda.synchronize()
+    assert_close(f64(Y1[rt]), refY, TOL[torch.float32], "Y of the one-launch layer (sampled rows)")
+    assert torch.equal(Y1, Y), "one-launch layer against the two launches"
+    _say(f"fullgraph: one-launch layer bit-equal on all {N} rows; {int((deg > 2048).sum())} rows longer than 2048 edges")
 
 
 @pytest.mark.timeout(600)

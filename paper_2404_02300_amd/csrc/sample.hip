@@ -170,6 +170,56 @@ __device__ int spine_scan(int32_t* p, int cnt, int32_t* zero_me = nullptr) {
     return carry_s;
 }
 
+// The same exclusive scan for up to NT * SCAN_K entries in one round: a wave owns a contiguous range and
+// reads it in SCAN_K coalesced slices at once (one memory round trip instead of one per NT entries),
+// scans slice after slice in registers, and the waves' totals are combined through LDS.
+constexpr int SCAN_K = 20;
+template <int NT>
+__device__ int spine_scan_blocked(int32_t* p, int cnt, int32_t* zero_me = nullptr) {
+    if (cnt > NT * SCAN_K) return spine_scan<NT>(p, cnt, zero_me);
+    __shared__ int wtot[NT / WAVE];
+    const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
+    constexpr int NW = NT / WAVE;
+    const int K = ((cnt + NW - 1) / NW + WAVE - 1) / WAVE;      // slices per wave
+    const int base = w * K * WAVE;
+    int x[SCAN_K];
+#pragma unroll
+    for (int k = 0; k < SCAN_K; ++k) {
+        const int idx = base + k * WAVE + lane;
+        x[k] = (k < K && idx < cnt) ? p[idx] : 0;
+    }
+    if (zero_me) {
+#pragma unroll
+        for (int k = 0; k < SCAN_K; ++k) {
+            const int idx = base + k * WAVE + lane;
+            if (k < K && idx < cnt) zero_me[idx] = 0;
+        }
+    }
+    int carry = 0;
+#pragma unroll
+    for (int k = 0; k < SCAN_K; ++k) {
+        const int incl = wave_incl_scan(x[k]);
+        const int tot = __shfl(incl, WAVE - 1);
+        x[k] = carry + incl - x[k];
+        carry += tot;
+    }
+    if (lane == 0) wtot[w] = carry;
+    __syncthreads();
+    int woff = 0, total = 0;
+#pragma unroll
+    for (int q = 0; q < NW; ++q) {
+        if (q < w) woff += wtot[q];
+        total += wtot[q];
+    }
+#pragma unroll
+    for (int k = 0; k < SCAN_K; ++k) {
+        const int idx = base + k * WAVE + lane;
+        if (k < K && idx < cnt) p[idx] = woff + x[k];
+    }
+    __syncthreads();
+    return total;
+}
+
 // Sums of three ranges of part[] by the whole block: [0,pm), [pm,pm+pb) and [lo,my).
 __device__ __forceinline__ void part_sums(const int32_t* __restrict__ part, int pm, int pb, int lo, int my, int* nnz,
                                           int* n_new, int* before) {
@@ -343,16 +393,39 @@ __global__ __launch_bounds__(TB) void k_transpose_fill(const int32_t* __restrict
     }
 }
 
-__device__ __forceinline__ void insertion_sort(int32_t* s, int len) {
-    for (int a = 1; a < len; ++a) {
-        const int x = s[a];
-        int q = a - 1;
-        while (q >= 0 && s[q] > x) {
-            s[q + 1] = s[q];
-            --q;
-        }
-        s[q + 1] = x;
-    }
+// Sort the short segment s[0, len), len <= N, ascending: all elements are loaded at once (padded with
+// INT_MAX), sorted in registers by a bitonic network, and the first len written back.  An insertion sort
+// in place pays a dependent global round trip per move, which made one thread's longest segment the
+// longest thing in the launch.
+template <int N>
+__device__ __forceinline__ void sort_regs(int32_t* s, int len) {
+    int v[N];
+#pragma unroll
+    for (int a = 0; a < N; ++a) v[a] = a < len ? s[a] : 0x7FFFFFFF;
+#pragma unroll
+    for (int k = 2; k <= N; k <<= 1)
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1)
+#pragma unroll
+            for (int a = 0; a < N; ++a) {
+                const int o = a ^ j;
+                if (o > a) {
+                    const int lo = min(v[a], v[o]), hi = max(v[a], v[o]);
+                    const bool up = (a & k) == 0;
+                    v[a] = up ? lo : hi;
+                    v[o] = up ? hi : lo;
+                }
+            }
+#pragma unroll
+    for (int a = 0; a < N; ++a)
+        if (a < len) s[a] = v[a];
+}
+__device__ __forceinline__ void sort_short_segment(int32_t* s, int len) {   // 2 <= len <= SHORT_SEG
+    static_assert(SHORT_SEG == 32, "the widest network");
+    if (len <= 4) sort_regs<4>(s, len);
+    else if (len <= 8) sort_regs<8>(s, len);
+    else if (len <= 16) sort_regs<16>(s, len);
+    else sort_regs<32>(s, len);
 }
 
 // The whole block sorts t_rows[b, b+len) ascending; buf is >= LDS_SEG ints of LDS, tmp global scratch.
@@ -413,7 +486,7 @@ __global__ __launch_bounds__(TB) void k_sort_short(const int32_t* __restrict__ t
             long_list[atomicAdd(long_count, 1)] = j;
             continue;
         }
-        insertion_sort(t_rows + b, len);
+        sort_short_segment(t_rows + b, len);
     }
 }
 
@@ -444,26 +517,53 @@ __global__ __launch_bounds__(TS) void k_transpose_small(const int32_t* __restric
     const int n_dst = counts[0], n_src = counts[1];
     const bool lds_cur = n_src <= TS_LDS;
     if (threadIdx.x == 0) n_long = 0;
-    spine_scan<TS>(t_indptr, n_src + 1, lds_cur ? nullptr : cursor_g);  // counts -> offsets in place
+    spine_scan_blocked<TS>(t_indptr, n_src + 1, lds_cur ? nullptr : cursor_g);  // counts -> offsets in place
     if (lds_cur)
         for (int j = threadIdx.x; j < n_src; j += TS) buf[j] = 0;
     __syncthreads();
     const int total = n_dst * fanout;
-    for (int idx = threadIdx.x; idx < total; idx += TS) {
-        const int i = idx / fanout, t = idx - i * fanout;
-        const int b0 = b_indptr[i];
-        if (t < b_indptr[i + 1] - b0) {
-            const int c = cols[b0 + t];
-            const int slot = lds_cur ? atomicAdd(&buf[c], 1) : atomicAdd(&cursor_g[c], 1);
-            t_rows[t_indptr[c] + slot] = i;
+    constexpr int FU = 4;   // edges in flight per thread: each is a chain of dependent loads
+    for (int i0 = threadIdx.x; i0 < total; i0 += TS * FU) {
+        int row[FU], c[FU], dst[FU];
+#pragma unroll
+        for (int u = 0; u < FU; ++u) {
+            const int idx = i0 + u * TS;
+            row[u] = -1;
+            if (idx < total) {
+                const int i = idx / fanout, t = idx - i * fanout;
+                const int b0 = b_indptr[i];
+                if (t < b_indptr[i + 1] - b0) { row[u] = i; c[u] = b0 + t; }
+            }
         }
+#pragma unroll
+        for (int u = 0; u < FU; ++u)
+            if (row[u] >= 0) c[u] = cols[c[u]];
+#pragma unroll
+        for (int u = 0; u < FU; ++u)
+            if (row[u] >= 0) dst[u] = t_indptr[c[u]] + (lds_cur ? atomicAdd(&buf[c[u]], 1) : atomicAdd(&cursor_g[c[u]], 1));
+#pragma unroll
+        for (int u = 0; u < FU; ++u)
+            if (row[u] >= 0) t_rows[dst[u]] = row[u];
     }
     __syncthreads();
-    for (int j = threadIdx.x; j < n_src; j += TS) {
-        const int b = t_indptr[j], len = t_indptr[j + 1] - b;
-        if (len <= 1) continue;
-        if (len > SHORT_SEG) long_list[atomicAdd(&n_long, 1)] = j;
-        else insertion_sort(t_rows + b, len);
+    for (int j0 = threadIdx.x; j0 < n_src; j0 += TS * FU) {
+        int b[FU], len[FU];
+#pragma unroll
+        for (int u = 0; u < FU; ++u) {
+            const int j = j0 + u * TS;
+            b[u] = 0;
+            len[u] = 0;
+            if (j < n_src) { b[u] = t_indptr[j]; len[u] = t_indptr[j + 1] - b[u]; }
+        }
+#pragma unroll 1
+        for (int u = 0; u < FU; ++u) {   // one copy of the sorting networks: pick the u-th pair without indexing
+            static_assert(FU == 4, "select chain");
+            const int bu = u == 0 ? b[0] : u == 1 ? b[1] : u == 2 ? b[2] : b[3];
+            const int lu = u == 0 ? len[0] : u == 1 ? len[1] : u == 2 ? len[2] : len[3];
+            if (lu <= 1) continue;
+            if (lu > SHORT_SEG) long_list[atomicAdd(&n_long, 1)] = j0 + u * TS;
+            else sort_short_segment(t_rows + bu, lu);
+        }
     }
     __syncthreads();
     const int cnt = n_long;

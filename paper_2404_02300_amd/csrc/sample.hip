@@ -174,8 +174,11 @@ __device__ int spine_scan(int32_t* p, int cnt, int32_t* zero_me = nullptr) {
 // reads it in SCAN_K coalesced slices at once (one memory round trip instead of one per NT entries),
 // scans slice after slice in registers, and the waves' totals are combined through LDS.
 constexpr int SCAN_K = 20;
+// `copy` (nullable, LDS): also receives the first copy_n results (only on the one-round path: the caller
+// asks for it only when cnt fits).
 template <int NT>
-__device__ int spine_scan_blocked(int32_t* p, int cnt, int32_t* zero_me = nullptr) {
+__device__ int spine_scan_blocked(int32_t* p, int cnt, int32_t* zero_me = nullptr, int32_t* copy = nullptr,
+                                  int copy_n = 0) {
     if (cnt > NT * SCAN_K) return spine_scan<NT>(p, cnt, zero_me);
     __shared__ int wtot[NT / WAVE];
     const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
@@ -214,7 +217,10 @@ __device__ int spine_scan_blocked(int32_t* p, int cnt, int32_t* zero_me = nullpt
 #pragma unroll
     for (int k = 0; k < SCAN_K; ++k) {
         const int idx = base + k * WAVE + lane;
-        if (k < K && idx < cnt) p[idx] = woff + x[k];
+        if (k < K && idx < cnt) {
+            p[idx] = woff + x[k];
+            if (copy && idx < copy_n) copy[idx] = woff + x[k];
+        }
     }
     __syncthreads();
     return total;
@@ -504,23 +510,30 @@ __global__ __launch_bounds__(TB) void k_sort_long(const int32_t* __restrict__ t_
 
 // Transposed block of a small layer in ONE launch of one 1024-thread workgroup:
 // scan the per-source counts (left in t_indptr by k_relabel), fill, sort the segments.
-// Fill cursors live in LDS when the frontier fits (returning LDS atomics are ~10x faster
-// than device-scope ones and a thread issues up to `fanout` of them back to back).
+// When the frontier fits (n_src <= TS_LDS) everything between the scan and the final copy stays in
+// LDS: the scanned offsets double as fill cursors (a returning LDS atomic hands out the absolute slot,
+// and after the fill cursor j has arrived at the end of segment j), the rows are filled and sorted
+// there and written out once, coalesced.  One workgroup pays every global round trip in full, so the
+// fewer there are in sequence the better: counts, histogram, row offsets, column ids, and the copy out.
+// Otherwise: fill cursors in global memory, segments sorted in global memory.
 constexpr int TS = 1024;
-constexpr int TS_LDS = 12288;  // ints of LDS: fill cursors first, sort buffer afterwards
+constexpr int TS_LDS = 12288;  // ints of LDS for offsets / cursors; the sort buffer of long segments afterwards
+constexpr int SMALL_T_NNZ = 1 << 14;  // layers up to this many sampled edges use k_transpose_small
+constexpr size_t TS_LDS_BYTES = (size_t)(TS_LDS + SMALL_T_NNZ) * sizeof(int32_t);
+static_assert(TS_LDS >= LDS_SEG && SMALL_T_NNZ + TS <= TS * SCAN_K, "buffer reuse; one-round scan");
 __global__ __launch_bounds__(TS) void k_transpose_small(const int32_t* __restrict__ b_indptr,
                                                         const int32_t* __restrict__ cols, const int32_t* counts,
                                                         int fanout, int32_t* t_indptr, int32_t* cursor_g,
                                                         int32_t* t_rows, int32_t* long_list, int32_t* tmp) {
-    __shared__ int32_t buf[TS_LDS];
+    extern __shared__ int32_t ts_lds[];
+    int32_t* cur = ts_lds;                 // [TS_LDS]
+    int32_t* rows = ts_lds + TS_LDS;       // [SMALL_T_NNZ]
     __shared__ int n_long;
     const int n_dst = counts[0], n_src = counts[1];
-    const bool lds_cur = n_src <= TS_LDS;
+    const bool in_lds = n_src <= TS_LDS;
     if (threadIdx.x == 0) n_long = 0;
-    spine_scan_blocked<TS>(t_indptr, n_src + 1, lds_cur ? nullptr : cursor_g);  // counts -> offsets in place
-    if (lds_cur)
-        for (int j = threadIdx.x; j < n_src; j += TS) buf[j] = 0;
-    __syncthreads();
+    // counts -> offsets in place (and into cur)
+    const int nnz = spine_scan_blocked<TS>(t_indptr, n_src + 1, in_lds ? nullptr : cursor_g, in_lds ? cur : nullptr, n_src);
     const int total = n_dst * fanout;
     constexpr int FU = 4;   // edges in flight per thread: each is a chain of dependent loads
     for (int i0 = threadIdx.x; i0 < total; i0 += TS * FU) {
@@ -538,31 +551,48 @@ __global__ __launch_bounds__(TS) void k_transpose_small(const int32_t* __restric
 #pragma unroll
         for (int u = 0; u < FU; ++u)
             if (row[u] >= 0) c[u] = cols[c[u]];
+        if (in_lds) {
 #pragma unroll
-        for (int u = 0; u < FU; ++u)
-            if (row[u] >= 0) dst[u] = t_indptr[c[u]] + (lds_cur ? atomicAdd(&buf[c[u]], 1) : atomicAdd(&cursor_g[c[u]], 1));
+            for (int u = 0; u < FU; ++u)
+                if (row[u] >= 0) rows[atomicAdd(&cur[c[u]], 1)] = row[u];
+        } else {
 #pragma unroll
-        for (int u = 0; u < FU; ++u)
-            if (row[u] >= 0) t_rows[dst[u]] = row[u];
+            for (int u = 0; u < FU; ++u)
+                if (row[u] >= 0) dst[u] = t_indptr[c[u]] + atomicAdd(&cursor_g[c[u]], 1);
+#pragma unroll
+            for (int u = 0; u < FU; ++u)
+                if (row[u] >= 0) t_rows[dst[u]] = row[u];
+        }
     }
     __syncthreads();
-    for (int j0 = threadIdx.x; j0 < n_src; j0 += TS * FU) {
-        int b[FU], len[FU];
-#pragma unroll
-        for (int u = 0; u < FU; ++u) {
-            const int j = j0 + u * TS;
-            b[u] = 0;
-            len[u] = 0;
-            if (j < n_src) { b[u] = t_indptr[j]; len[u] = t_indptr[j + 1] - b[u]; }
+    if (in_lds) {
+        for (int j = threadIdx.x; j < n_src; j += TS) {
+            const int b = j ? cur[j - 1] : 0, len = cur[j] - b;     // cursor j stopped at the end of segment j
+            if (len <= 1) continue;
+            if (len > SHORT_SEG) long_list[atomicAdd(&n_long, 1)] = j;
+            else sort_short_segment(rows + b, len);
         }
+        __syncthreads();
+        for (int e = threadIdx.x; e < nnz; e += TS) t_rows[e] = rows[e];
+    } else {
+        for (int j0 = threadIdx.x; j0 < n_src; j0 += TS * FU) {
+            int b[FU], len[FU];
+#pragma unroll
+            for (int u = 0; u < FU; ++u) {
+                const int j = j0 + u * TS;
+                b[u] = 0;
+                len[u] = 0;
+                if (j < n_src) { b[u] = t_indptr[j]; len[u] = t_indptr[j + 1] - b[u]; }
+            }
 #pragma unroll 1
-        for (int u = 0; u < FU; ++u) {   // one copy of the sorting networks: pick the u-th pair without indexing
-            static_assert(FU == 4, "select chain");
-            const int bu = u == 0 ? b[0] : u == 1 ? b[1] : u == 2 ? b[2] : b[3];
-            const int lu = u == 0 ? len[0] : u == 1 ? len[1] : u == 2 ? len[2] : len[3];
-            if (lu <= 1) continue;
-            if (lu > SHORT_SEG) long_list[atomicAdd(&n_long, 1)] = j0 + u * TS;
-            else sort_short_segment(t_rows + bu, lu);
+            for (int u = 0; u < FU; ++u) {   // one copy of the sorting networks: pick the u-th pair without indexing
+                static_assert(FU == 4, "select chain");
+                const int bu = u == 0 ? b[0] : u == 1 ? b[1] : u == 2 ? b[2] : b[3];
+                const int lu = u == 0 ? len[0] : u == 1 ? len[1] : u == 2 ? len[2] : len[3];
+                if (lu <= 1) continue;
+                if (lu > SHORT_SEG) long_list[atomicAdd(&n_long, 1)] = j0 + u * TS;
+                else sort_short_segment(t_rows + bu, lu);
+            }
         }
     }
     __syncthreads();
@@ -570,7 +600,7 @@ __global__ __launch_bounds__(TS) void k_transpose_small(const int32_t* __restric
     for (int li = 0; li < cnt; ++li) {
         const int j = long_list[li];
         const int b = t_indptr[j];
-        block_sort_segment<TS>(t_rows, b, t_indptr[j + 1] - b, buf, tmp);
+        block_sort_segment<TS>(t_rows, b, t_indptr[j + 1] - b, cur, tmp);
     }
 }
 
@@ -605,8 +635,6 @@ inline int grid_for(int64_t items, int per_block, int max_blocks) {
     if (g > max_blocks) g = max_blocks;
     return (int)g;
 }
-
-constexpr int SMALL_T_NNZ = 1 << 14;  // layers up to this many sampled edges use k_transpose_small
 
 }  // namespace
 
@@ -687,7 +715,16 @@ int32_t sample_layer(const sdt_csr& g, const int32_t* dst_nodes, int32_t n_dst_c
     }
     if (!want_t) return SDT_OK;
     if ((int64_t)n_dst_cap * fanout <= SMALL_T_NNZ) {
-        hipLaunchKernelGGL(k_transpose_small, dim3(1), dim3(TS), 0, st, out.indptr, out.cols, out.counts, fanout,
+        static bool opted = false;   // more than 64 KB of dynamic LDS has to be opted into, once
+        if (!opted) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_transpose_small), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)TS_LDS_BYTES) != hipSuccess) {
+                set_error("transpose small: cannot raise the dynamic LDS limit to %zu bytes", TS_LDS_BYTES);
+                return SDT_ERR_HIP;
+            }
+            opted = true;
+        }
+        hipLaunchKernelGGL(k_transpose_small, dim3(1), dim3(TS), TS_LDS_BYTES, st, out.indptr, out.cols, out.counts, fanout,
                            out.t_indptr, ws.cursor, out.t_rows, ws.longlist, ws.e_pad);
         SDT_CHECK_LAUNCH("transpose small");
         return SDT_OK;

@@ -222,3 +222,44 @@ def test_compiled_partitioner_on_a_generated_graph():
     assert got["part"].tolist() == want["part"]
     load = np.bincount(got["part"], minlength=4)
     assert load.sum() == n and load.max() - load.min() <= np.bincount(got["cluster_merged"]).max()
+
+
+def test_partitioner_finds_planted_communities():
+    """Four planted communities of 150 nodes (dense inside, a few edges across): the partitions follow
+    them (a streaming clustering is noisy: a tenth of the nodes end up elsewhere), and fewer than half as
+    many neighbours have to be replicated as under a round-robin assignment."""
+    import sdt_gen as gen
+    rng = random.Random(7)
+    k, size = 4, 150
+    n = k * size
+    pairs = set()
+    for c in range(k):
+        base = c * size
+        while sum(1 for (u, v) in pairs if u // size == c and v // size == c) < size * 6:
+            u, v = base + rng.randrange(size), base + rng.randrange(size)
+            if u != v:
+                pairs.add((min(u, v), max(u, v)))
+    for _ in range(40):                                   # sparse links across communities
+        u, v = rng.randrange(n), rng.randrange(n)
+        if u // size != v // size:
+            pairs.add((min(u, v), max(u, v)))
+    ids = list(range(n))
+    rng.shuffle(ids)                                      # hide the communities from the id order
+    adj = [[] for _ in range(n)]
+    for u, v in pairs:
+        adj[ids[u]].append(ids[v])
+        adj[ids[v]].append(ids[u])
+    adj = [sorted(a) for a in adj]
+    indptr, indices = _csr(adj)
+    out = gen.spring(indptr, indices, k, order_seed=3)
+    part = out["part"].tolist()
+    rf = SO.replication_factor(n, adj, part, k)
+    rf_rr = SO.replication_factor(n, adj, [v % k for v in range(n)], k)
+    assert rf < 0.5 * rf_rr and rf_rr > 2.5, (rf, rf_rr)     # 1.72 against 3.86 on this instance
+    load = np.bincount(out["part"], minlength=k)
+    assert load.max() <= 1.05 * n / k + max(np.bincount(out["cluster_merged"]))
+    # most of a community lands in one partition
+    inv = {ids[u]: u for u in range(n)}
+    for c in range(k):
+        owners = np.bincount([part[ids[u]] for u in range(c * size, (c + 1) * size)], minlength=k)
+        assert owners.max() >= 0.8 * size, owners

@@ -9,6 +9,7 @@
 // yields the new nodes in ascending id order for free) and a dense
 // node -> local-id map is extended.  Nothing depends on the order in which
 // waves run, so every index output is reproducible bit for bit.
+#include <atomic>
 #include "common.h"
 
 namespace sdt {
@@ -715,14 +716,16 @@ int32_t sample_layer(const sdt_csr& g, const int32_t* dst_nodes, int32_t n_dst_c
     }
     if (!want_t) return SDT_OK;
     if ((int64_t)n_dst_cap * fanout <= SMALL_T_NNZ) {
-        static bool opted = false;   // more than 64 KB of dynamic LDS has to be opted into, once
-        if (!opted) {
+        // more than 64 KB of dynamic LDS has to be opted into, once (the loop's helper threads may get here together:
+        // setting the attribute twice is harmless, the flag itself must not be a data race)
+        static std::atomic<bool> opted{false};
+        if (!opted.load(std::memory_order_acquire)) {
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_transpose_small), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)TS_LDS_BYTES) != hipSuccess) {
                 set_error("transpose small: cannot raise the dynamic LDS limit to %zu bytes", TS_LDS_BYTES);
                 return SDT_ERR_HIP;
             }
-            opted = true;
+            opted.store(true, std::memory_order_release);
         }
         hipLaunchKernelGGL(k_transpose_small, dim3(1), dim3(TS), TS_LDS_BYTES, st, out.indptr, out.cols, out.counts, fanout,
                            out.t_indptr, ws.cursor, out.t_rows, ws.longlist, ws.e_pad);

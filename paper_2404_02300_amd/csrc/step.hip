@@ -2,6 +2,8 @@
 // partition, enqueued on one stream with no host synchronisation.  All
 // data-dependent sizes (frontier sizes, edge counts) stay in device memory;
 // every kernel is launched for the upper bound and reads the true count.
+#include <vector>
+#include <mutex>
 #include "common.h"
 
 #include <atomic>
@@ -815,6 +817,50 @@ namespace sdt {
 int32_t train_loop_buffers() { return LOOP_BUFFERS; }
 }  // namespace sdt
 
+namespace {
+// Event sets of sdt_train_loop, kept for reuse per device (never destroyed: they live as long as the process).
+struct LoopEvents {
+    int dev = -1;
+    hipEvent_t ready[LOOP_SLOTS] = {}, done[LOOP_SLOTS] = {}, fork = nullptr;
+};
+std::mutex loop_events_mu;
+std::vector<LoopEvents*> loop_events_free;
+
+LoopEvents* loop_events_acquire() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+    {
+        std::lock_guard<std::mutex> lock(loop_events_mu);
+        for (size_t k = 0; k < loop_events_free.size(); ++k)
+            if (loop_events_free[k]->dev == dev) {
+                LoopEvents* e = loop_events_free[k];
+                loop_events_free.erase(loop_events_free.begin() + (long)k);
+                return e;
+            }
+    }
+    LoopEvents* e = new LoopEvents;
+    e->dev = dev;
+    bool ok = hipEventCreateWithFlags(&e->fork, hipEventDisableTiming) == hipSuccess;
+    for (int k = 0; k < LOOP_SLOTS && ok; ++k)
+        ok = hipEventCreateWithFlags(&e->ready[k], hipEventDisableTiming) == hipSuccess &&
+             hipEventCreateWithFlags(&e->done[k], hipEventDisableTiming) == hipSuccess;
+    if (!ok) {
+        for (int k = 0; k < LOOP_SLOTS; ++k) {
+            if (e->ready[k]) (void)hipEventDestroy(e->ready[k]);
+            if (e->done[k]) (void)hipEventDestroy(e->done[k]);
+        }
+        if (e->fork) (void)hipEventDestroy(e->fork);
+        delete e;
+        return nullptr;
+    }
+    return e;
+}
+void loop_events_release(LoopEvents* e) {
+    std::lock_guard<std::mutex> lock(loop_events_mu);
+    loop_events_free.push_back(e);
+}
+}  // namespace
+
 extern "C" size_t sdt_train_loop_workspace_bytes(int64_t n_nodes, int32_t batch, const int32_t* fanouts,
                                                  const sdt_model* model, int32_t dtype) {
     sdt_step_layout lay;
@@ -849,24 +895,24 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
     for (int k = 0; k < LOOP_BUFFERS; ++k) bind_buffers(c.lay, static_cast<char*>(ws) + k * one, one, &buf[k]);
 
     // ready[s]: phase 1 of every step of the group in slot s is complete; done[s]: their phase 2 is.
-    hipEvent_t ready[LOOP_SLOTS] = {}, done[LOOP_SLOTS] = {}, fork = nullptr;
+    // The events come from a pool and go back to it (creating and destroying nine of them costs a call
+    // of a few dozen steps several percent); a set is used by one call at a time, and re-recording an
+    // event does not disturb waits enqueued earlier, which refer to the record they were issued after.
+    LoopEvents* ev = nullptr;
+    hipEvent_t *ready = nullptr, *done = nullptr, fork = nullptr;
     auto cleanup = [&]() {
-        for (int k = 0; k < LOOP_SLOTS; ++k) {
-            if (ready[k]) (void)hipEventDestroy(ready[k]);
-            if (done[k]) (void)hipEventDestroy(done[k]);
-        }
-        if (fork) (void)hipEventDestroy(fork);
+        if (ev) loop_events_release(ev);
+        ev = nullptr;
     };
     if (overlap) {
-        bool ok = hipEventCreateWithFlags(&fork, hipEventDisableTiming) == hipSuccess;
-        for (int k = 0; k < LOOP_SLOTS && ok; ++k)
-            ok = hipEventCreateWithFlags(&ready[k], hipEventDisableTiming) == hipSuccess &&
-                 hipEventCreateWithFlags(&done[k], hipEventDisableTiming) == hipSuccess;
-        if (!ok) {
-            cleanup();
+        ev = loop_events_acquire();
+        if (!ev) {
             set_error("sdt_train_loop: hipEventCreate failed");
             return SDT_ERR_HIP;
         }
+        ready = ev->ready;
+        done = ev->done;
+        fork = ev->fork;
         // the auxiliary streams start after whatever the caller queued on the main stream
         (void)hipEventRecord(fork, main_st);
         for (int k = 0; k < n_aux; ++k) (void)hipStreamWaitEvent(aux[k], fork, 0);
@@ -881,8 +927,13 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
         const int sl = used0 + (i - first_timed) / stride;
         return sl < timing->max_steps ? sl : -1;
     };
-    const int n_groups = (n_steps + LOOP_GROUP - 1) / LOOP_GROUP;
-    auto group_end = [&](int g) { return (g + 1) * LOOP_GROUP < n_steps ? (g + 1) * LOOP_GROUP : n_steps; };
+    // Groups of LOOP_GROUP steps, except the first, which is a single step: the model side can start as
+    // soon as one step is sampled (a call pays the pipeline fill once; at a hundred steps per call it shows).
+    // Step i still uses workspace i % LOOP_BUFFERS, and the steps of group g + LOOP_SLOTS use exactly the
+    // workspaces of group g, so waiting for the slot's `done` event frees what the group needs.
+    auto group_begin = [&](int g) { return g == 0 ? 0 : g * LOOP_GROUP - (LOOP_GROUP - 1); };
+    auto group_end = [&](int g) { return group_begin(g + 1) < n_steps ? group_begin(g + 1) : n_steps; };
+    const int n_groups = n_steps == 0 ? 0 : (n_steps - 1 + LOOP_GROUP - 1) / LOOP_GROUP + 1;
     if (!overlap) {
         for (int i = 0; i < n_steps && rc == SDT_OK; ++i) {
             c.slot = slot_of(i);
@@ -915,7 +966,7 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
                     if (failed.load()) return;
                     (void)hipStreamWaitEvent(aux_st, done[s], 0);   // the slot's buffers are free again
                 }
-                for (int i = g * LOOP_GROUP; i < group_end(g); ++i) {
+                for (int i = group_begin(g); i < group_end(g); ++i) {
                     ca.slot = slot_of(i);
                     const int32_t r = step_sample(ca, buf[i % LOOP_BUFFERS], seeds + (int64_t)i * batch, first_step + (uint32_t)i,
                                                   aux_st, /*check_state=*/i < LOOP_BUFFERS);
@@ -937,7 +988,7 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
             while (ready_gen[s].load(std::memory_order_acquire) != g + 1 && !failed.load()) std::this_thread::yield();
             if (failed.load()) break;
             (void)hipStreamWaitEvent(main_st, ready[s], 0);
-            for (int i = g * LOOP_GROUP; i < group_end(g) && rc == SDT_OK; ++i) {
+            for (int i = group_begin(g); i < group_end(g) && rc == SDT_OK; ++i) {
                 c.slot = slot_of(i);
                 rc = step_compute(c, buf[i % LOOP_BUFFERS], seeds + (int64_t)i * batch, first_step + (uint32_t)i, losses_d + i,
                                   main_st);

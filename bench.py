@@ -52,7 +52,8 @@ def log(msg):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed steps (default: the number the workload prescribes: 100, or 200 for sparse_bf16)")
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="products",
                     choices=["tiny", "products", "products_spring", "dense", "sparse_bf16", "fullgraph", "sampling", "gather"],
@@ -80,6 +81,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     wl = gen.WORKLOADS["products" if args.workload in ("sampling", "gather", "products_spring") else args.workload]
+    if args.steps is None:
+        args.steps = wl.steps if wl.steps > 1 else 100
     K, Wm = args.steps, args.warmup
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB read + 1 GiB written

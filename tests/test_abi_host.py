@@ -122,3 +122,13 @@ def test_invalid_arguments_are_reported_not_crashed():
     assert L.sdt_sage_aggregate_fwd(None, None, 0, 4, 0, None, 0, None) == B.SDT_ERR_INVALID_ARG
     assert L.sdt_gather_features(None, 4, 8, 0, None, 3, None, None, 8, None) == B.SDT_ERR_INVALID_ARG
     assert L.sdt_sage_linear_fwd(None, 4, None, 4, 3, None, 4, 4, None, None, 0, 0, None, 4, 0, None) == B.SDT_ERR_INVALID_ARG
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU's throughput; asking for more exits with a message before anything is loaded."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""

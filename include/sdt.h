@@ -14,11 +14,22 @@
  *    is printed.  sdt_last_error() gives a thread-local message for the last
  *    failing call on the calling thread.
  *  - Every pointer is a DEVICE pointer owned by the caller unless its comment
- *    says "host".  The library allocates and frees no device memory and keeps
- *    no state between calls; scratch space is passed in as `ws`/`ws_bytes`
- *    (size from the matching *_workspace_bytes query, pure host arithmetic
- *    on the upper bounds; contents need no initialisation and are garbage
- *    afterwards).  Workspace and all row pointers must be 16-byte aligned.
+ *    says "host".  The library allocates and frees no device memory; scratch
+ *    space is passed in as `ws`/`ws_bytes` (size from the matching
+ *    *_workspace_bytes query, pure host arithmetic on the upper bounds;
+ *    contents need no initialisation and are garbage afterwards).  Workspace
+ *    and all row pointers must be 16-byte aligned.
+ *  - What the library does hold between calls, all of it host-side or fixed at
+ *    load time, none of it results: (1) sdt_train_loop keeps a process-wide pool
+ *    of HIP events per device (nine per concurrent call, behind a mutex, never
+ *    destroyed) and, for calls of more than two steps with auxiliary streams,
+ *    starts one host thread per auxiliary stream and joins it before returning
+ *    (the threads spin with yield on counters of the calling thread; if a thread
+ *    cannot be started the call returns SDT_ERR_HIP); (2) two kernels that need
+ *    more than 64 KB of LDS raise their limit once per process (atomic flags);
+ *    (3) the caller-owned sdt_timing objects.  Entry points may be called from
+ *    several threads as long as calls that share a workspace or a timing object
+ *    are ordered.
  *  - `stream` is a hipStream_t (NULL = default stream).  All work is enqueued
  *    asynchronously; no call synchronises with the host.  Outputs are valid
  *    once the stream has been synchronised.  Two calls that share a workspace
@@ -210,8 +221,8 @@ int32_t sdt_sample_csr(const sdt_csr *graph /*host struct*/, const int32_t *dst_
 int32_t sdt_gather_features(const void *X, int64_t ldx, int32_t F, int32_t dtype, const int32_t *idx,
                             int32_t n_cap, const int32_t *n_d, void *out, int64_t ldo, void *stream);
 
-/* ---- neighbourhood aggregation (Sec. II-A: "neighborhood aggregation as a
- * key operation"), mean variant: A[i,:] = (1/m_i) sum_{e in row i} H[cols[e],:],
+/* ---- neighbourhood aggregation (Sec. II-A, the operation every GNN layer is
+ * built on), mean variant: A[i,:] = (1/m_i) sum_{e in row i} H[cols[e],:],
  * m_i = row length, zeros when m_i = 0; fp32 accumulation in edge order.
  * Uses blk->counts[0] rows. */
 int32_t sdt_sage_aggregate_fwd(const sdt_block *blk /*host struct*/, const void *H, int64_t ldh, int32_t F,
@@ -316,11 +327,15 @@ int32_t sdt_sage_linear_bwd(const void *dY, int64_t lddy, int32_t dy_dtype, cons
  * fp32 weights; lr = 0 leaves them bit-identical).  loss_d receives the loss.
  * X is [n_nodes, F = dims[0]] in `dtype` with leading dimension ldx.
  * Workspace: unlike the other calls' scratch, the step workspace carries state
- * from one step to the next (a header plus a node map that every step hands
- * back clean, so it is initialised only when the header does not match).  It
- * needs no initialisation before the first step, but between steps nobody else
- * may write to it; a caller who reuses the buffer for something else must zero
- * its first 256 bytes before the next step.
+ * from one step to the next: a header plus a node map that every step hands
+ * back clean, so the map is initialised only when the header does not say
+ * "clean".  A step takes that word away before it writes its first map entry
+ * and its last map-cleaning kernel puts it back, so a step whose launches stop
+ * half-way (an error return) leaves a workspace that the next step initialises
+ * again.  The caller's part: zero the first 256 bytes once after allocating the
+ * buffer (memory fresh from an allocator may happen to hold an old header over
+ * other data), let nobody else write to it between steps, and zero the first
+ * 256 bytes again after using the buffer for anything else.
  * sdt_train_step_layout fills `layout` (host) with the workspace size and
  * the offsets of every intermediate.
  * Without a timing object the call only launches kernels on `stream`: no
@@ -346,9 +361,22 @@ enum {
     SDT_STAGE_LOSS = 4,
     SDT_STAGE_LINEAR_BWD = 5,
     SDT_STAGE_AGG_BWD = 6,
-    SDT_STAGE_HEAD = 7 /* the fused last-layer launch alone (it also lies inside LINEAR_BWD of that layer) */
+    SDT_STAGE_HEAD = 7, /* the fused last-layer launch alone (it also lies inside LINEAR_BWD of that layer) */
+    /* single launches inside the stages above, for kernel-level figures: */
+    SDT_STAGE_SAMPLE_ROWS = 8,  /* the neighbour sampling kernel of a layer */
+    SDT_STAGE_FRONT_SCAN = 9,   /* first pass of the frontier / row-offset scan */
+    SDT_STAGE_FRONT_APPLY = 10, /* second pass: new frontier nodes, row offsets, node map */
+    SDT_STAGE_RELABEL = 11,     /* global -> local column ids (+ column histogram) */
+    SDT_STAGE_TRANSPOSE = 12,   /* the transposed block (one launch for small layers, five otherwise) */
+    SDT_STAGE_UPDATE = 13,      /* layer 0 only: the step's single reduction + optimiser launch */
+    SDT_STAGE_BWD_WEIGHT = 14,  /* the weight-gradient product of a layer's backward */
+    SDT_STAGE_BWD_INPUT = 15    /* the input-gradient product of a layer's backward */
 };
+#define SDT_STAGE_MASK_WORDS 2 /* 16 stage kinds x SDT_MAX_LAYERS bits */
 int32_t sdt_timing_create(int32_t max_steps, uint64_t stage_mask, sdt_timing **out /*host*/);
+/* The same with the full mask: stage_mask is a host array of SDT_STAGE_MASK_WORDS words, bit
+ * kind * SDT_MAX_LAYERS + layer counted across the words (sdt_timing_create reaches kinds 0..7 only). */
+int32_t sdt_timing_create_wide(int32_t max_steps, const uint64_t *stage_mask /*host*/, sdt_timing **out /*host*/);
 void sdt_timing_destroy(sdt_timing *t);
 void sdt_timing_reset(sdt_timing *t);
 /* Time only every stride-th step (default 1: all).  An event record costs the stream a few
@@ -376,13 +404,15 @@ int32_t sdt_train_step(const sdt_csr *graph /*host struct*/, const void *X, int6
  * events per group (Sec. II-A: the
  * mini-batch sub-graphs are independent of the model; Sec. III-D: a worker
  * trains many mini-batches between two synchronisations).  Ordering between
- * the two streams uses HIP events created and released inside the call.  When
- * the call returns everything is enqueued; synchronising `stream` is enough.
+ * the streams uses HIP events taken from and returned to the library's pool.  When
+ * the call returns, with or without an error, everything it enqueued on any stream is
+ * ordered before later work on `stream`; synchronising `stream` is enough.
  * seeds is device int32[n_steps, batch]; losses_d device fp32[n_steps].  The
  * workspace (sdt_train_loop_workspace_bytes: a whole number of step workspaces,
  * each with sdt_train_step's layout rounded up to 256 bytes, back to back;
  * step i of a call uses workspace i modulo their number) carries
- * state like sdt_train_step's.  aux_streams is a HOST array of n_aux (0..3)
+ * state like sdt_train_step's: zero it (or the first 256 bytes of each step workspace
+ * in it) once after allocation.  aux_streams is a HOST array of n_aux (0..3)
  * streams, all different from `stream`; n_aux = 0 gives the serial order.  The
  * sampling chain is a sequence of small latency-bound launches, so two auxiliary
  * streams sample twice as many steps per unit of time as one.

@@ -109,6 +109,7 @@ EXPORTS = {
     "sdt_train_round": (_i32, [_vp, _i32, _i32, _i32, _vp, _vp, _vp, _u64, _u32, ctypes.c_float, _vp, _vp, _sz, _vp,
                                _vp, _i32]),
     "sdt_timing_create": (_i32, [_i32, _u64, _vp]),
+    "sdt_timing_create_wide": (_i32, [_i32, _vp, _vp]),
     "sdt_timing_destroy": (None, [_vp]),
     "sdt_timing_reset": (None, [_vp]),
     "sdt_timing_set_stride": (_i32, [_vp, _i32]),
@@ -116,7 +117,9 @@ EXPORTS = {
 }
 
 STAGES = {"sample": 0, "gather": 1, "aggregate_fwd": 2, "linear_fwd": 3, "loss": 4, "linear_bwd": 5,
-          "aggregate_bwd": 6, "head": 7}
+          "aggregate_bwd": 6, "head": 7, "sample_rows": 8, "front_scan": 9, "front_apply": 10, "relabel": 11,
+          "transpose": 12, "update": 13, "bwd_weight": 14, "bwd_input": 15}
+SDT_STAGE_MASK_WORDS = 2
 
 _lib = None
 
@@ -477,6 +480,14 @@ def sdt_timing_create(max_steps: int, stage_mask: int) -> ctypes.c_void_p:
     return h
 
 
+def sdt_timing_create_wide(max_steps: int, stage_mask: int) -> ctypes.c_void_p:
+    """stage_mask: a Python int of up to 64 * SDT_STAGE_MASK_WORDS bits."""
+    words = (_u64 * SDT_STAGE_MASK_WORDS)(*[(stage_mask >> (64 * w)) & ((1 << 64) - 1) for w in range(SDT_STAGE_MASK_WORDS)])
+    h = ctypes.c_void_p()
+    _check(lib().sdt_timing_create_wide(max_steps, words, ctypes.byref(h)))
+    return h
+
+
 def sdt_timing_destroy(handle):
     lib().sdt_timing_destroy(handle)
 
@@ -504,7 +515,7 @@ class Timing:
         for kind, layer in stages:
             mask |= 1 << (STAGES[kind] * SDT_MAX_LAYERS + layer)
         self.max_steps = max_steps
-        self.handle = sdt_timing_create(max_steps, mask)
+        self.handle = sdt_timing_create_wide(max_steps, mask)
         if stride != 1:
             sdt_timing_set_stride(self.handle, stride)
 

@@ -7,9 +7,47 @@
 
 #include "../../include/sdt.h"
 
+// Per-stage HIP-event timing object behind the sdt_timing_* calls (host object).  A stage is
+// (kind, layer); its bit is kind * SDT_MAX_LAYERS + layer, up to SDT_STAGE_KINDS kinds.
+constexpr int SDT_STAGE_KINDS = 16;
+constexpr int SDT_STAGE_BITS = SDT_STAGE_KINDS * SDT_MAX_LAYERS;
+struct sdt_timing {
+    int32_t max_steps;
+    uint64_t mask[SDT_STAGE_BITS / 64];
+    int32_t stride;               // every stride-th step is timed (1 = all)
+    int32_t seen;                 // steps observed so far
+    int32_t used;                 // slots consumed so far
+    int32_t slot;                 // slot of the step being recorded, -1 = none
+    uint64_t recorded[SDT_STAGE_BITS / 64];   // stages that were bracketed at least once since the last reset
+    hipEvent_t* ev[SDT_STAGE_BITS][2];        // [stage bit][begin/end][slot]
+};
+
 namespace sdt {
 
 constexpr int WAVE = 64;
+
+// Records a begin event now and the end event when it goes out of scope, on the stream the bracketed
+// kernels are launched on.  `slot` is the timing slot of the step being enqueued (-1: not timed); it is
+// passed in rather than read from the object because two host threads may be enqueueing different steps.
+struct StageTimer {
+    sdt_timing* t;
+    int bit, slot;
+    hipStream_t st;
+    StageTimer(sdt_timing* tm, int slot_, int kind, int layer, hipStream_t s)
+        : t(tm), bit(kind * SDT_MAX_LAYERS + layer), slot(slot_), st(s) {
+        if (t && slot >= 0 && ((t->mask[bit >> 6] >> (bit & 63)) & 1)) {
+            (void)hipEventRecord(t->ev[bit][0][slot], st);
+            __atomic_fetch_or(&t->recorded[bit >> 6], 1ull << (bit & 63), __ATOMIC_RELAXED);
+        } else {
+            t = nullptr;
+        }
+    }
+    ~StageTimer() {
+        if (t) (void)hipEventRecord(t->ev[bit][1][slot], st);
+    }
+    StageTimer(const StageTimer&) = delete;
+    StageTimer& operator=(const StageTimer&) = delete;
+};
 
 // Thread-local error text behind sdt_last_error().
 void set_error(const char* fmt, ...);
@@ -117,22 +155,28 @@ struct SampleWs {
 size_t sample_state_bytes(int64_t n_nodes);
 void sample_state_carve(void* base, int64_t n_nodes, SampleWs* out);
 size_t sample_tmp_carve(Arena& a, int64_t n_nodes, int32_t cap_dst, int32_t fanout, SampleWs* out);
-// header: int32[64] at the start of a step workspace ({magic, n_nodes, loss ticket, ...}) or nullptr.
+// header: int32[64] at the start of a step workspace, {magic, n_nodes, ...}, or nullptr.  The magic word
+// says "the node map and the bitmap of this workspace are clean": sample_seed_map takes it away before the
+// first map entry of a step is written, and the LAST kernel of the step that hands map entries back clean
+// (`stamp` argument of gather_rows / aggregate_gather_fwd / gcn_aggregate_fwd) puts it back.  A step whose
+// launch chain stops half-way therefore leaves a workspace that the next step initialises again.
+constexpr int32_t STATE_MAGIC = 0x53445431;  // "SDT1"
 int32_t sample_state_init(const SampleWs& ws, int64_t n_nodes, const int32_t* header, hipStream_t st);
 int32_t sample_seed_map(const SampleWs& ws, const int32_t* dst_nodes, int32_t n_dst_cap, const int32_t* n_dst_d,
                         int32_t* header, int64_t n_nodes, hipStream_t st);
+// timing / slot (nullable / -1): brackets the kernels of the layer one by one (SDT_STAGE_SAMPLE_ROWS ... _TRANSPOSE)
 int32_t sample_layer(const sdt_csr& g, const int32_t* dst_nodes, int32_t n_dst_cap, const int32_t* n_dst_d,
                      int32_t fanout, uint64_t seed, uint32_t step, uint32_t layer, const sdt_block& out,
-                     const SampleWs& ws, hipStream_t st);
-// gather that also resets map[idx[j]] = -1 (map may be null); zero_pad: columns F..ldo-1 of every output row
+                     const SampleWs& ws, hipStream_t st, sdt_timing* timing = nullptr, int slot = -1);
+// gather that also resets map[idx[j]] = -1 (map may be null; stamp, nullable: header to mark clean); zero_pad: columns F..ldo-1 of every output row
 // are set to zero, and those of the same rows of also_pad (nullable: a second matrix of out's shape and stride)
 int32_t gather_rows(const void* X, int64_t ldx, int32_t F, int32_t dtype, const int32_t* idx, int32_t n_cap,
-                    const int32_t* n_d, void* out, int64_t ldo, int32_t* map_reset, bool zero_pad, void* also_pad,
-                    hipStream_t st);
+                    const int32_t* n_d, void* out, int64_t ldo, int32_t* map_reset, int32_t* stamp, bool zero_pad,
+                    void* also_pad, hipStream_t st);
 
 // mean aggregation straight from the feature matrix through blk->src_nodes (+ optional map reset)
 int32_t aggregate_gather_fwd(const sdt_block* blk, const void* X, int64_t ldx, int32_t F, int32_t dtype, void* A,
-                             int64_t lda, int32_t* map_reset, hipStream_t st);
+                             int64_t lda, int32_t* map_reset, int32_t* stamp, hipStream_t st);
 
 // writes dZ and the per-row losses; their mean is folded into a later single-block pass
 int32_t softmax_xent(const float* logits, int64_t ld, int32_t B, int32_t C, const int32_t* labels,
@@ -176,6 +220,9 @@ struct BwdExtras {
     const float* row_loss = nullptr;
     int32_t n_loss = 0;
     float* loss_out = nullptr;
+    // per-kernel timing of the two backward products (SDT_STAGE_BWD_WEIGHT / _INPUT of `layer`)
+    sdt_timing* timing = nullptr;
+    int slot = -1, layer = 0;
 };
 // projection backward with optional extras once dW, db are final
 int32_t linear_bwd(const void* dY, int64_t lddy, int32_t dy_dtype, const void* Y, int64_t ldy, int32_t relu,
@@ -226,7 +273,7 @@ int32_t linear_bwd_input_bf16(const void* dY, int64_t lddy, int32_t dy_dtype, in
 // GCN aggregation (gcn.hip); map_reset as in aggregate_gather_fwd
 int32_t gcn_aggregate_fwd(const sdt_block* blk, const float* H, int64_t ldh, bool through_src_nodes, int32_t F,
                           const float* c, const float* s, const float* selfw, float* A, int64_t lda, int32_t* map_reset,
-                          hipStream_t stm);
+                          int32_t* stamp, hipStream_t stm);
 
 constexpr int GAT_CHUNK_ROWS = 256;   // rows per partial column sum of the GAT bias / attention-vector gradients
 // GAT attention aggregation inside a training step (gat.hip).  The forward adds `bias` (may be null) and

@@ -67,7 +67,8 @@ __global__ __launch_bounds__(TB) void k_gcn_aggregate_fwd(const int32_t* __restr
                                                           const int32_t* __restrict__ row_ids, int F,
                                                           const float* __restrict__ c, const float* __restrict__ s,
                                                           const float* __restrict__ selfw, float* __restrict__ A,
-                                                          int64_t lda, int32_t* map_reset) {
+                                                          int64_t lda, int32_t* map_reset, int32_t* stamp) {
+    if (stamp && blockIdx.x == 0 && threadIdx.x == 0) stamp[0] = STATE_MAGIC;   // this launch leaves the map clean
     const int n = counts[0];
     const int gl = threadIdx.x % G;
     const int ngrp = gridDim.x * (TB / G);
@@ -221,14 +222,14 @@ inline int rows_grid(int64_t rows, int G) {
 
 int32_t gcn_aggregate_fwd(const sdt_block* blk, const float* H, int64_t ldh, bool through_src_nodes, int32_t F,
                           const float* c, const float* s, const float* selfw, float* A, int64_t lda, int32_t* map_reset,
-                          hipStream_t stm) {
+                          int32_t* stamp, hipStream_t stm) {
     // the forward kernel moves its last vector back, so any dword-aligned fp32 row takes the widest vector that fits
     const int ve = F >= 4 ? 4 : F >= 2 ? 2 : 1;
     const int G = (F + ve - 1) / ve > 16 ? 64 : 16;
     SDT_GCN_DISPATCH(ve, G, hipLaunchKernelGGL((k_gcn_aggregate_fwd<VE, GG>), dim3(rows_grid(blk->cap_dst, GG)), dim3(TB),
                                                0, stm, blk->indptr, blk->cols, blk->counts, H, ldh,
                                                through_src_nodes ? blk->src_nodes : nullptr, F, c, s, selfw, A, lda,
-                                               through_src_nodes ? map_reset : nullptr));
+                                               through_src_nodes ? map_reset : nullptr, through_src_nodes ? stamp : nullptr));
     SDT_CHECK_LAUNCH("gcn_aggregate_fwd");
     return SDT_OK;
 }
@@ -261,7 +262,7 @@ extern "C" int32_t sdt_gcn_aggregate_fwd(const sdt_block* blk, const void* H, in
                     (!through_src_nodes || blk->src_nodes),
                 SDT_ERR_INVALID_ARG, "sdt_gcn_aggregate_fwd: null pointer");
     return gcn_aggregate_fwd(blk, static_cast<const float*>(H), ldh, through_src_nodes != 0, F, c, s, selfw,
-                             static_cast<float*>(A), lda, nullptr, static_cast<hipStream_t>(stream));
+                             static_cast<float*>(A), lda, nullptr, nullptr, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int32_t sdt_gcn_aggregate_bwd(const sdt_block* blk, const void* dA, int64_t lda, const void* relu_of,

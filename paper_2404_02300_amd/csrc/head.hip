@@ -17,6 +17,8 @@
 // reduction pass that also applies the SGD step.
 #include "common.h"
 
+#include <atomic>
+
 namespace sdt {
 namespace {
 
@@ -331,16 +333,16 @@ int32_t head_fwd_bwd(const void* Hself, int64_t ldh, const void* A, int64_t lda,
     float* Q = reinterpret_cast<float*>(static_cast<char*>(ws) + align_up((size_t)splits * 2 * in * out * sizeof(float), 256));
     const size_t lds = head_lds_bytes(in, out);
     // more than 64 KB of dynamic LDS has to be opted into, once per kernel
-    static bool opted[2] = {false, false};
+    static std::atomic<bool> opted[2] = {{false}, {false}};   // two threads may get here together: setting twice is harmless
     const int which = dtype == SDT_F32 ? 0 : 1;
-    if (!opted[which]) {
+    if (!opted[which].load(std::memory_order_acquire)) {
         const void* fn = which == 0 ? reinterpret_cast<const void*>(&k_head<float>)
                                     : reinterpret_cast<const void*>(&k_head<bf16_t>);
         if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)HEAD_LDS_MAX) != hipSuccess) {
             set_error("head: cannot raise the dynamic LDS limit to %zu bytes", HEAD_LDS_MAX);
             return SDT_ERR_HIP;
         }
-        opted[which] = true;
+        opted[which].store(true, std::memory_order_release);
     }
     // few row blocks (batch / 16): up to four workgroups share one, splitting the backward products
     const int mt = (2 * in) / 16;

@@ -17,6 +17,8 @@
 // result is deterministic.
 #include "common.h"
 
+#include <atomic>
+
 #include <algorithm>
 
 namespace sdt {
@@ -721,6 +723,8 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Hself, int64_t ldh, co
     const TD* dYt = static_cast<const TD*>(dY);
     // weight gradient partials (bf16 activations inside a step: on the bf16 matrix cores)
     const int32_t dy_code = sizeof(TD) == 2 ? SDT_BF16 : SDT_F32;
+    {
+    StageTimer tw(ex.timing, ex.slot, SDT_STAGE_BWD_WEIGHT, ex.layer, st);
     if (ex.Wb && sizeof(TH) == 2 && bf16_mfma_bwd_weight_ok(Hself, ldh, A, lda, dY, lddy, dy_code, in, out)) {
         (void)linear_bwd_weight_bf16(Hself, ldh, A, lda, dY, lddy, dy_code, n_cap, n_d, in, out, splits, P, Q, st);
     } else {
@@ -736,7 +740,10 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Hself, int64_t ldh, co
             })
         })
     }
+    }
     const bool input_on_bf16_path = ex.Wb && sizeof(TH) == 2 && dSelf && bf16_mfma_bwd_input_ok(dY, lddy, dy_code, in, out, ldi);
+    {
+    StageTimer ti(dSelf && n_cap > 0 ? ex.timing : nullptr, ex.slot, SDT_STAGE_BWD_INPUT, ex.layer, st);
     if (input_on_bf16_path) {
         (void)linear_bwd_input_bf16(dY, lddy, dy_code, n_cap, n_d, in, out, ex.Wb, dSelf, dAgg, ldi, st);
     } else if (dSelf && n_cap > 0) {
@@ -750,6 +757,7 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Hself, int64_t ldh, co
                                    n_cap, n_d, in, out, W, static_cast<TH*>(dSelf), static_cast<TH*>(dAgg), ldi);
             })
         })
+    }
     }
     // after the input gradients: this pass may overwrite W with the SGD step
     PendingReduce pr;
@@ -809,16 +817,16 @@ int32_t sdt::sage_layer_fused_fwd(const sdt_csr* g, const float* H, int64_t ldh,
                                   const float* b, int32_t relu, float* Y, int64_t ldy, hipStream_t st) {
     // 256 resident columns (a wave per row, 1 KB pieces) when the width allows, else 128
     const bool wide = in % 256 == 0;
-    static bool opted[2] = {false, false};    // more than 64 KB of dynamic LDS has to be opted into, once per kernel
+    static std::atomic<bool> opted[2] = {{false}, {false}};   // two threads may get here together: setting twice is harmless    // more than 64 KB of dynamic LDS has to be opted into, once per kernel
     const void* fn = wide ? reinterpret_cast<const void*>(&k_sage_layer_fused<256>)
                           : reinterpret_cast<const void*>(&k_sage_layer_fused<128>);
     const size_t lds = wide ? fused_lds_bytes(256) : fused_lds_bytes(128);
-    if (!opted[wide]) {
+    if (!opted[wide].load(std::memory_order_acquire)) {
         if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
             set_error("sage_layer_fused: cannot raise the dynamic LDS limit to %zu bytes", lds);
             return SDT_ERR_HIP;
         }
-        opted[wide] = true;
+        opted[wide].store(true, std::memory_order_release);
     }
     const int n = (int)g->n_nodes;
     if (wide)

@@ -606,8 +606,6 @@ __global__ __launch_bounds__(TS) void k_transpose_small(const int32_t* __restric
 }
 
 // ---- state that persists across the layers (and steps) of a training run ---------
-constexpr int32_t STATE_MAGIC = 0x53445431;  // "SDT1"
-
 // Fill the node map with -1 and clear the bitmap unless the header says a previous step
 // left them in that state already (every step restores them before it ends).
 __global__ __launch_bounds__(TB) void k_state_check_init(const int32_t* header, int32_t* map, int64_t n,
@@ -618,14 +616,14 @@ __global__ __launch_bounds__(TB) void k_state_check_init(const int32_t* header, 
     for (int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x; i < nwords; i += stride) bitmap[i] = 0u;
 }
 
-// map[dst[i]] = i; also stamps the header (after k_state_check_init has read it).
+// map[dst[i]] = i.  From here on the map is in use: the header loses its magic word (after
+// k_state_check_init has read it) until the step's last cleaning kernel stamps it again.
 __global__ __launch_bounds__(TB) void k_seed_map(int32_t* map, const int32_t* __restrict__ dst, int n_cap,
                                                  const int32_t* n_d, int32_t* header, int32_t n_nodes) {
     const int n = dev_count(n_cap, n_d);
     for (int i = blockIdx.x * TB + threadIdx.x; i < n; i += gridDim.x * TB) map[dst[i]] = i;
     if (header && blockIdx.x == 0 && threadIdx.x == 0) {
-        if (header[0] != STATE_MAGIC || header[1] != n_nodes) header[2] = 0;  // loss ticket
-        header[0] = STATE_MAGIC;
+        header[0] = 0;
         header[1] = n_nodes;
     }
 }
@@ -686,14 +684,16 @@ int32_t sample_seed_map(const SampleWs& ws, const int32_t* dst_nodes, int32_t n_
 // leaves the map extended by the new frontier nodes and the bitmap clear again.
 int32_t sample_layer(const sdt_csr& g, const int32_t* dst_nodes, int32_t n_dst_cap, const int32_t* n_dst_d,
                      int32_t fanout, uint64_t seed, uint32_t step, uint32_t layer, const sdt_block& out,
-                     const SampleWs& ws, hipStream_t st) {
+                     const SampleWs& ws, hipStream_t st, sdt_timing* timing, int slot) {
     const int nwords = (int)((g.n_nodes + 31) / 32);
     const int pm = ceil_div(n_dst_cap > 0 ? n_dst_cap : 1, TILE), pb = ceil_div(nwords, TILE);
     const bool want_t = out.t_indptr != nullptr;
     int32_t* hist = want_t ? out.t_indptr : nullptr;  // counted in place, then scanned in place
     const bool any = n_dst_cap > 0 && fanout > 0;
+    const int tl = (int)(layer < SDT_MAX_LAYERS ? layer : SDT_MAX_LAYERS - 1);   // timing slot of the layer
 
     if (any) {
+        StageTimer tm(timing, slot, SDT_STAGE_SAMPLE_ROWS, tl, st);
         hipLaunchKernelGGL(k_sample_rows, dim3(grid_for(n_dst_cap, TB / WAVE, 8192)), dim3(TB), 0, st, g.indptr,
                            g.indices, dst_nodes, n_dst_cap, n_dst_d, fanout, (uint32_t)seed,
                            (uint32_t)(seed >> 32), step, layer, ws.map, ws.bitmap, ws.e_pad, ws.m);
@@ -703,18 +703,26 @@ int32_t sample_layer(const sdt_csr& g, const int32_t* dst_nodes, int32_t n_dst_c
                            (int64_t)n_dst_cap, 0);
         SDT_CHECK_LAUNCH("zero m");
     }
-    hipLaunchKernelGGL(k_front_partials, dim3(pm + pb), dim3(TB), 0, st, ws.m, n_dst_cap, n_dst_d, ws.bitmap, nwords,
-                       pm, ws.part);
-    SDT_CHECK_LAUNCH("frontier partials");
-    hipLaunchKernelGGL(k_front_apply, dim3(pm + pb), dim3(TB), 0, st, ws.m, n_dst_cap, n_dst_d, ws.bitmap, nwords, pm,
-                       pb, ws.part, out.counts, out.indptr, out.src_nodes, dst_nodes, ws.map, hist);
-    SDT_CHECK_LAUNCH("frontier apply");
+    {
+        StageTimer tm(timing, slot, SDT_STAGE_FRONT_SCAN, tl, st);
+        hipLaunchKernelGGL(k_front_partials, dim3(pm + pb), dim3(TB), 0, st, ws.m, n_dst_cap, n_dst_d, ws.bitmap, nwords,
+                           pm, ws.part);
+        SDT_CHECK_LAUNCH("frontier partials");
+    }
+    {
+        StageTimer tm(timing, slot, SDT_STAGE_FRONT_APPLY, tl, st);
+        hipLaunchKernelGGL(k_front_apply, dim3(pm + pb), dim3(TB), 0, st, ws.m, n_dst_cap, n_dst_d, ws.bitmap, nwords, pm,
+                           pb, ws.part, out.counts, out.indptr, out.src_nodes, dst_nodes, ws.map, hist);
+        SDT_CHECK_LAUNCH("frontier apply");
+    }
     if (any) {
+        StageTimer tm(timing, slot, SDT_STAGE_RELABEL, tl, st);
         hipLaunchKernelGGL(k_relabel, dim3(grid_for((int64_t)n_dst_cap * fanout, TB, 2048)), dim3(TB), 0, st,
                            ws.e_pad, ws.m, out.indptr, n_dst_cap, n_dst_d, fanout, ws.map, out.cols, hist);
         SDT_CHECK_LAUNCH("relabel");
     }
     if (!want_t) return SDT_OK;
+    StageTimer tt(timing, slot, SDT_STAGE_TRANSPOSE, tl, st);
     if ((int64_t)n_dst_cap * fanout <= SMALL_T_NNZ) {
         // more than 64 KB of dynamic LDS has to be opted into, once (the loop's helper threads may get here together:
         // setting the attribute twice is harmless, the flag itself must not be a data race)

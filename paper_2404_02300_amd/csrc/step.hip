@@ -85,58 +85,27 @@ extern "C" size_t sdt_struct_bytes(int32_t which) {
     }
 }
 
-// ---- per-stage HIP-event timing ---------------------------------------------------
-struct sdt_timing {
-    int32_t max_steps;
-    uint64_t mask;
-    int32_t stride;               // every stride-th step is timed (1 = all)
-    int32_t seen;                 // steps observed so far
-    int32_t used;                 // slots consumed so far
-    int32_t slot;                 // slot of the step being recorded, -1 = none
-    uint64_t recorded;            // stages that were bracketed at least once since the last reset
-    hipEvent_t* ev[64][2];        // [stage bit][begin/end][slot]
-};
-
-namespace {
-struct StageTimer {               // records begin now, end at scope exit
-    sdt_timing* t;
-    int bit, slot;
-    hipStream_t st;
-    // `slot` is the timing slot of the step being enqueued (-1: not timed); it is passed in rather
-    // than read from the object because two host threads may be enqueueing different steps
-    StageTimer(sdt_timing* tm, int slot_, int kind, int layer, hipStream_t s)
-        : t(tm), bit(kind * SDT_MAX_LAYERS + layer), slot(slot_), st(s) {
-        if (t && slot >= 0 && ((t->mask >> bit) & 1)) {
-            (void)hipEventRecord(t->ev[bit][0][slot], st);
-            __atomic_fetch_or(&t->recorded, 1ull << bit, __ATOMIC_RELAXED);
-        } else {
-            t = nullptr;
-        }
-    }
-    ~StageTimer() {
-        if (t) (void)hipEventRecord(t->ev[bit][1][slot], st);
-    }
-};
-}  // namespace
-
-extern "C" int32_t sdt_timing_create(int32_t max_steps, uint64_t stage_mask, sdt_timing** out) {
-    SDT_REQUIRE(out && max_steps > 0 && max_steps <= (1 << 20), SDT_ERR_INVALID_ARG, "sdt_timing_create: bad arguments");
+// ---- per-stage HIP-event timing (the object and its recorder are in common.h) -----
+static int32_t timing_create(int32_t max_steps, const uint64_t* mask, sdt_timing** out) {
+    SDT_REQUIRE(out && mask && max_steps > 0 && max_steps <= (1 << 20), SDT_ERR_INVALID_ARG, "sdt_timing_create: bad arguments");
     sdt_timing* t = new sdt_timing();
     t->max_steps = max_steps;
-    t->mask = stage_mask;
+    for (int w = 0; w < SDT_STAGE_BITS / 64; ++w) { t->mask[w] = mask[w]; t->recorded[w] = 0; }
     t->stride = 1;
     t->seen = 0;
     t->used = 0;
     t->slot = -1;
-    t->recorded = 0;
-    for (int b = 0; b < 64; ++b)
+    for (int b = 0; b < SDT_STAGE_BITS; ++b)
+        for (int k = 0; k < 2; ++k) t->ev[b][k] = nullptr;
+    for (int b = 0; b < SDT_STAGE_BITS; ++b)
         for (int k = 0; k < 2; ++k) {
-            t->ev[b][k] = nullptr;
-            if (!((stage_mask >> b) & 1)) continue;
-            t->ev[b][k] = new hipEvent_t[max_steps];
+            if (!((mask[b >> 6] >> (b & 63)) & 1)) continue;
+            t->ev[b][k] = new hipEvent_t[max_steps]();
             for (int i = 0; i < max_steps; ++i)
                 if (hipEventCreate(&t->ev[b][k][i]) != hipSuccess) {
                     set_error("sdt_timing_create: hipEventCreate failed");
+                    t->ev[b][k][i] = nullptr;
+                    sdt_timing_destroy(t);
                     return SDT_ERR_HIP;
                 }
         }
@@ -144,19 +113,32 @@ extern "C" int32_t sdt_timing_create(int32_t max_steps, uint64_t stage_mask, sdt
     return SDT_OK;
 }
 
+extern "C" int32_t sdt_timing_create(int32_t max_steps, uint64_t stage_mask, sdt_timing** out) {
+    const uint64_t mask[SDT_STAGE_BITS / 64] = {stage_mask, 0};
+    return timing_create(max_steps, mask, out);
+}
+
+extern "C" int32_t sdt_timing_create_wide(int32_t max_steps, const uint64_t* stage_mask, sdt_timing** out) {
+    return timing_create(max_steps, stage_mask, out);
+}
+
 extern "C" void sdt_timing_destroy(sdt_timing* t) {
     if (!t) return;
-    for (int b = 0; b < 64; ++b)
+    for (int b = 0; b < SDT_STAGE_BITS; ++b)
         for (int k = 0; k < 2; ++k)
             if (t->ev[b][k]) {
-                for (int i = 0; i < t->max_steps; ++i) (void)hipEventDestroy(t->ev[b][k][i]);
+                for (int i = 0; i < t->max_steps; ++i)
+                    if (t->ev[b][k][i]) (void)hipEventDestroy(t->ev[b][k][i]);
                 delete[] t->ev[b][k];
             }
     delete t;
 }
 
 extern "C" void sdt_timing_reset(sdt_timing* t) {
-    if (t) { t->seen = 0; t->used = 0; t->slot = -1; t->recorded = 0; }
+    if (t) {
+        t->seen = 0; t->used = 0; t->slot = -1;
+        for (int w = 0; w < SDT_STAGE_BITS / 64; ++w) t->recorded[w] = 0;
+    }
 }
 
 extern "C" int32_t sdt_timing_set_stride(sdt_timing* t, int32_t stride) {
@@ -167,11 +149,11 @@ extern "C" int32_t sdt_timing_set_stride(sdt_timing* t, int32_t stride) {
 }
 
 extern "C" int32_t sdt_timing_read(sdt_timing* t, int32_t kind, int32_t layer, float* ms_out, int32_t* n_out) {
-    SDT_REQUIRE(t && ms_out && n_out && kind >= 0 && kind < 8 && layer >= 0 && layer < SDT_MAX_LAYERS,
+    SDT_REQUIRE(t && ms_out && n_out && kind >= 0 && kind < SDT_STAGE_KINDS && layer >= 0 && layer < SDT_MAX_LAYERS,
                 SDT_ERR_INVALID_ARG, "sdt_timing_read: bad arguments");
     const int bit = kind * SDT_MAX_LAYERS + layer;
-    SDT_REQUIRE((t->mask >> bit) & 1, SDT_ERR_INVALID_ARG, "sdt_timing_read: stage (%d,%d) was not selected", kind, layer);
-    SDT_REQUIRE((t->recorded >> bit) & 1, SDT_ERR_INVALID_ARG,
+    SDT_REQUIRE((t->mask[bit >> 6] >> (bit & 63)) & 1, SDT_ERR_INVALID_ARG, "sdt_timing_read: stage (%d,%d) was not selected", kind, layer);
+    SDT_REQUIRE((t->recorded[bit >> 6] >> (bit & 63)) & 1, SDT_ERR_INVALID_ARG,
                 "sdt_timing_read: stage (%d,%d) did not run as a separate stage", kind, layer);
     for (int i = 0; i < t->used; ++i) {
         if (hipEventSynchronize(t->ev[bit][1][i]) != hipSuccess ||
@@ -418,7 +400,8 @@ int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds
         }
         Arena a(b.at(lay.scratch));
         sample_tmp_carve(a, N, lay.cap_dst[l], c.fanouts[l], &sw);
-        rc = sample_layer(*c.graph, dst, lay.cap_dst[l], n_d, c.fanouts[l], c.seed, step, (uint32_t)l, b.blk[l], sw, st);
+        rc = sample_layer(*c.graph, dst, lay.cap_dst[l], n_d, c.fanouts[l], c.seed, step, (uint32_t)l, b.blk[l], sw, st,
+                          c.timing, c.slot);
         if (rc != SDT_OK) return rc;
         dst = b.blk[l].src_nodes;
         n_d = b.blk[l].counts + 1;
@@ -433,26 +416,27 @@ int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds
         SDT_REQUIRE(lay.cap_dst[0] == 0 || aligned16(c.X), SDT_ERR_INVALID_ARG, "sdt_train_step: X must be 16-byte aligned");
         StageTimer tm(c.timing, c.slot, SDT_STAGE_AGG_FWD, 0, st);
         return gcn_aggregate_fwd(&b.blk[0], static_cast<const float*>(c.X), c.ldx, true, d[0], b.gcn_c(lay, 0),
-                                 b.gcn_s(lay, 0), b.gcn_self(lay, 0), static_cast<float*>(b.at(lay.A[0])), d[0], sw.map, st);
+                                 b.gcn_s(lay, 0), b.gcn_self(lay, 0), static_cast<float*>(b.at(lay.A[0])), d[0], sw.map, header, st);
     }
     if (c.model->kind == SDT_MODEL_GAT) {
         // every frontier row is projected, so every one is gathered (which also hands the whole map back clean)
         StageTimer tm(c.timing, c.slot, SDT_STAGE_GATHER, 0, st);
         return gather_rows(c.X, c.ldx, d[0], c.dtype, b.blk[0].src_nodes, lay.cap_src[0], b.blk[0].counts + 1, b.at(lay.H[0]),
-                           d[0], sw.map, false, nullptr, st);
+                           d[0], sw.map, header, false, nullptr, st);
     }
     // Input features: only the destination prefix of the outermost frontier is copied (the
     // projection's "self" operand); the neighbour mean of layer 0 is taken straight out of X.
     // The copy also zeroes the row padding of H[0] and of A[0] (same rows, same stride).
-    // Both passes hand the frontier map back clean (prefix nodes here, the rest there).
+    // Both passes hand the frontier map back clean (prefix nodes here, the rest there); the second one,
+    // the last kernel of the step to touch the map, stamps the workspace header "clean" again.
     {
         StageTimer tm(c.timing, c.slot, SDT_STAGE_GATHER, 0, st);
         rc = gather_rows(c.X, c.ldx, d[0], c.dtype, b.blk[0].src_nodes, lay.cap_dst[0], b.blk[0].counts,
-                         b.at(lay.H[0]), (int64_t)lay.ld_in, sw.map, /*zero_pad=*/true, /*also_pad=*/b.at(lay.A[0]), st);
+                         b.at(lay.H[0]), (int64_t)lay.ld_in, sw.map, /*stamp=*/nullptr, /*zero_pad=*/true, /*also_pad=*/b.at(lay.A[0]), st);
     }
     if (rc != SDT_OK) return rc;
     StageTimer tm(c.timing, c.slot, SDT_STAGE_AGG_FWD, 0, st);
-    return aggregate_gather_fwd(&b.blk[0], c.X, c.ldx, d[0], c.dtype, b.at(lay.A[0]), (int64_t)lay.ld_in, sw.map, st);
+    return aggregate_gather_fwd(&b.blk[0], c.X, c.ldx, d[0], c.dtype, b.at(lay.A[0]), (int64_t)lay.ld_in, sw.map, header, st);
 }
 
 // Phase 2 of a GCN step.  The projection kernels take two operands of equal width; here they are
@@ -540,6 +524,7 @@ int32_t step_compute_gcn(const StepCtx& c, const StepBuffers& b, const int32_t* 
         }
     }
     for (int k = 0; k < n_pending; ++k) attach_moments(&pending[k], model, L - 1 - k);   // queued last layer first
+    StageTimer tu(timing, c.slot, SDT_STAGE_UPDATE, 0, st);
     return reduce_all(pending, n_pending, optimizer_args(model, c.lr, step), static_cast<const float*>(b.at(lay.row_loss)),
                       c.batch, loss_d, st);
 }
@@ -647,6 +632,7 @@ int32_t step_compute_gat(const StepCtx& c, const StepBuffers& b, const int32_t* 
             pa->vb = model->vatt[l];
         }
     }
+    StageTimer tu(timing, c.slot, SDT_STAGE_UPDATE, 0, st);
     return reduce_all(pending, n_pending, optimizer_args(model, c.lr, step), static_cast<const float*>(b.at(lay.row_loss)),
                       c.batch, loss_d, st);
 }
@@ -752,6 +738,7 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
             ex.W_upd = model->W[l];
             ex.b_upd = model->b[l];
             ex.rows_padded = l == 0;
+            ex.timing = timing; ex.slot = c.slot; ex.layer = l;
             rc = linear_bwd(dY, d[l + 1], dy_dtype, nullptr, 0, 0, b.at(lay.H[l]), ldx(l), b.at(lay.A[l]), ldx(l),
                             lay.cap_dst[l], b.blk[l].counts, d[l], d[l + 1], model->W[l], dtype, dW, db,
                             inner ? b.at(lay.dSelf[l]) : nullptr, inner ? b.at(lay.dAgg[l]) : nullptr, d[l],
@@ -773,6 +760,7 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
     // (No layer's weights were touched before this point, so every product above saw the
     // weights the step started with.)
     for (int k = 0; k < n_pending; ++k) attach_moments(&pending[k], model, L - 1 - k);   // queued last layer first
+    StageTimer tu(timing, c.slot, SDT_STAGE_UPDATE, 0, st);
     return reduce_all(pending, n_pending, optimizer_args(model, c.lr, step), static_cast<const float*>(b.at(lay.row_loss)),
                       c.batch, loss_d, st);
 }
@@ -984,7 +972,17 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
             }
         };
         std::thread helpers[LOOP_MAX_AUX];
-        for (int a = 0; a < n_aux; ++a) helpers[a] = std::thread(helper_fn, a);
+        int started = 0;
+        try {
+            for (int a = 0; a < n_aux; ++a) {
+                helpers[a] = std::thread(helper_fn, a);
+                ++started;
+            }
+        } catch (...) {   // no exception may cross the C boundary: stop the helpers already running and report
+            failed.store(1);
+            rc = SDT_ERR_HIP;
+            set_error("sdt_train_loop: cannot start a helper thread");
+        }
         for (int g = 0; g < n_groups && rc == SDT_OK; ++g) {
             const int s = g % LOOP_SLOTS;
             while (ready_gen[s].load(std::memory_order_acquire) != g + 1 && !failed.load()) std::this_thread::yield();
@@ -1003,12 +1001,21 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
             done_groups.store(g + 1, std::memory_order_release);
         }
         if (rc != SDT_OK) failed.store(1);
-        for (int a = 0; a < n_aux; ++a) helpers[a].join();
-        for (int a = 0; a < n_aux; ++a)
+        for (int a = 0; a < started; ++a) helpers[a].join();
+        for (int a = 0; a < started; ++a)
             if (rc == SDT_OK && aux_rc[a] != SDT_OK) {
                 rc = aux_rc[a];
                 set_error("%s", aux_msg[a].c_str());
             }
+        if (rc != SDT_OK) {
+            // sampling work of steps that no model phase waited for may still be queued on the auxiliary
+            // streams: order the main stream after it, so that synchronising `stream` covers everything
+            // this call enqueued on the failure path too
+            for (int k = 0; k < n_aux; ++k) {
+                (void)hipEventRecord(fork, aux[k]);
+                (void)hipStreamWaitEvent(main_st, fork, 0);
+            }
+        }
     }
     if (timing) {
         const int timed = n_steps > first_timed ? (n_steps - first_timed + stride - 1) / stride : 0;

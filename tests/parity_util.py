@@ -23,9 +23,39 @@ def max_rel(got, ref) -> float:
     return float(err / scale) if scale > 0 else float(err)
 
 
-def assert_close(got, ref, tol, what=""):
+def floored_rel(got, ref) -> float:
+    """Element-wise relative error with the denominator floored at 1e-3 * max|ref| (reported for
+    information beside the max-norm figure, which is the one the tolerance applies to)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    scale = np.max(np.abs(ref))
+    if scale == 0:
+        return float(np.max(np.abs(got)))
+    return float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-3 * scale)))
+
+
+def assert_close(got, ref, tol, what="", log=None):
     e = max_rel(got, ref)
     assert e <= tol, f"{what}: max-norm relative error {e:.3e} > {tol:.1e}"
+    if log is not None:
+        log.append((what, e, floored_rel(got, ref)))
+
+
+def relu_window(x_gpu, x_ref, W, b) -> np.ndarray:
+    """Element-wise bound on |z_gpu - z_oracle| for z = x W + b, given the operand rows each side
+    actually used (x_* = [self | mean], [n, K]) and the weights as they enter the product:
+        |x_gpu - x_ref| |W|  +  (K + 2) 2^-24 (|x_gpu| |W| + |b|)
+    The first term is the exact first-order effect of the operands' difference (summation
+    order and storage rounding of the earlier stages, measured, not assumed); the second is
+    the worst-case rounding of an fp32 accumulation of K products plus the bias (unit
+    roundoff 2^-24 per operation) against the oracle's fp64 sum.  Two pre-activations that
+    fall on different sides of zero are therefore both inside this window."""
+    x_gpu, x_ref = np.asarray(x_gpu, np.float64), np.asarray(x_ref, np.float64)
+    aw = np.abs(np.asarray(W, np.float64))
+    K = x_gpu.shape[1]
+    return np.abs(x_gpu - x_ref) @ aw + (K + 2) * 2.0 ** -24 * (np.abs(x_gpu) @ aw + np.abs(np.asarray(b, np.float64)))
 
 
 def f64(t: torch.Tensor) -> np.ndarray:
@@ -68,6 +98,7 @@ class StepRunner:
         self.code = B.SDT_BF16 if bf16 else B.SDT_F32
         self.lay = B.sdt_train_step_layout(self.graph.n_nodes, batch, self.fanouts, self.model, self.code)
         self.ws = torch.empty(int(self.lay.total_bytes), dtype=torch.uint8, device="cuda")
+        self.ws[:256].zero_()          # the header: "nothing known about the node map" (see sdt_train_step)
         self.loss = torch.zeros(1, dtype=torch.float32, device="cuda")
 
     def step(self, seeds: np.ndarray, seed: int, step: int, lr: float):
@@ -121,7 +152,9 @@ class StepRunner:
 
 
 def check_step_against_oracle(run: StepRunner, ref: dict, tol: float, floats: bool = True):
-    """Index structures bit-exact; floats within tol (max-norm relative)."""
+    """Index structures bit-exact; floats within tol (max-norm relative).  Returns the tensor with
+    the largest max-norm error as (name, max-norm relative error, element-wise relative error
+    floored at 1e-3 max|ref|), or None when only the index structures were compared."""
     L = run.L
     for l in range(L):
         got, want = run.block(l), ref["blocks"][l]
@@ -133,22 +166,24 @@ def check_step_against_oracle(run: StepRunner, ref: dict, tol: float, floats: bo
             assert np.array_equal(got["t_indptr"], want.t_indptr), f"t_indptr of block {l}"
             assert np.array_equal(got["t_rows"], want.t_rows), f"t_rows of block {l}"
     if not floats:
-        return
+        return None
+    log = []
     blocks = ref["blocks"]
     n0 = blocks[0].n_dst            # only the destination prefix of the frontier is copied
     assert np.array_equal(run.H(0, n0), ref["H"][0][:n0]), "gathered features are a bit copy"
     for l in range(L):
-        assert_close(run.A(l, blocks[l].n_dst), ref["A"][l], tol, f"A[{l}]")
-        assert_close(run.H(l + 1, blocks[l].n_dst), ref["H"][l + 1], tol, f"H[{l + 1}]")
-    assert_close(run.dZ(), ref["dZ"], tol, "dZ")
+        assert_close(run.A(l, blocks[l].n_dst), ref["A"][l], tol, f"A[{l}]", log)
+        assert_close(run.H(l + 1, blocks[l].n_dst), ref["H"][l + 1], tol, f"H[{l + 1}]", log)
+    assert_close(run.dZ(), ref["dZ"], tol, "dZ", log)
     for l in range(L):
-        assert_close(run.grad("dW", l), ref["dW"][l], tol, f"dW[{l}]")
-        assert_close(run.grad("db", l), ref["db"][l], tol, f"db[{l}]")
+        assert_close(run.grad("dW", l), ref["dW"][l], tol, f"dW[{l}]", log)
+        assert_close(run.grad("db", l), ref["db"][l], tol, f"db[{l}]", log)
         if l >= 1:
-            assert_close(run.grad("dSelf", l, blocks[l].n_dst), ref["dSelf"][l], tol, f"dSelf[{l}]")
-            assert_close(run.grad("dAgg", l, blocks[l].n_dst), ref["dAgg"][l], tol, f"dAgg[{l}]")
+            assert_close(run.grad("dSelf", l, blocks[l].n_dst), ref["dSelf"][l], tol, f"dSelf[{l}]", log)
+            assert_close(run.grad("dAgg", l, blocks[l].n_dst), ref["dAgg"][l], tol, f"dAgg[{l}]", log)
             # the ReLU decisions the oracle's backward used (reconciled ones if present)
             masks = ref.get("relu_masks")
             keep = masks[l - 1] if masks is not None and masks[l - 1] is not None else ref["H"][l] > 0
             masked = ref["dH"][l] * keep
-            assert_close(run.grad("dH", l, blocks[l].n_src), masked, tol, f"dH[{l}] (ReLU-masked)")
+            assert_close(run.grad("dH", l, blocks[l].n_src), masked, tol, f"dH[{l}] (ReLU-masked)", log)
+    return max(log, key=lambda t: t[1])

@@ -99,7 +99,7 @@ def _check_round(insts, wls, n_steps):
         locs.append(B.make_model(wls[0].dims, Wl, bl))
         keep.append((g, X, y, seeds, Wl, bl, n_train))
     nbytes = B.sdt_train_round_workspace_bytes(parts, batch, fan, gmodel, B.SDT_F32)
-    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
     losses = torch.zeros(sum(n_steps), dtype=torch.float32, device="cuda")
     aux = torch.cuda.Stream()
     B.sdt_train_round(parts, B.SDT_F32, batch, fan, gmodel, locs, seed, 0, lr, losses, ws, aux)
@@ -112,7 +112,7 @@ def _check_round(insts, wls, n_steps):
         W2 = [dev(w) for w in init.W]
         b2 = [dev(v) for v in init.b]
         m2 = B.make_model(wls[0].dims, W2, b2)
-        ws2 = torch.empty(B.sdt_train_loop_workspace_bytes(inst.n_nodes, batch, fan, m2, B.SDT_F32), dtype=torch.uint8,
+        ws2 = torch.zeros(B.sdt_train_loop_workspace_bytes(inst.n_nodes, batch, fan, m2, B.SDT_F32), dtype=torch.uint8,
                           device="cuda")
         l2 = torch.zeros(ns, dtype=torch.float32, device="cuda")
         B.sdt_train_loop(g, X, y, seeds, fan, m2, seed, 0, lr, l2, ws2, None)

@@ -1,6 +1,10 @@
-"""GPU parity at the full sizes of the five workloads, in the launch configuration
-bench.py times.  Index structures are compared on every step; floats on selected
-steps, teacher-forced from the GPU's weights (oracle steps cost seconds each)."""
+"""GPU parity at the full sizes of the five workloads, for the step counts they prescribe.
+Sequential sdt_train_step calls: index structures against the oracle on every step, floats on
+steps 0, 1 and the last, teacher-forced from the GPU's weights (oracle steps cost seconds each).
+Then the launch configuration bench.py times -- one sdt_train_loop call over the same
+mini-batches, sampling on two auxiliary streams -- must reproduce every loss and the final
+weights bit for bit (Sec. III-D: a worker trains many mini-batches between two
+synchronisations; that loop is the unit that matters)."""
 import time
 
 import numpy as np
@@ -11,7 +15,7 @@ import sdt_gen as gen
 from oracle import sdt_oracle as orc
 from paper_2404_02300_amd import binding as B
 from parity_util import TOL, assert_close, dev, f64
-from test_gpu_parity import _run_and_check, _say
+from test_gpu_parity import _loop_against_steps, _run_and_check, _say
 
 pytestmark = pytest.mark.gpu
 
@@ -22,8 +26,10 @@ def test_products_full_size():
     t = time.time()
     inst = gen.make_instance(wl)
     _say(f"products: generated in {time.time() - t:.1f}s, nnz={inst.indptr[-1]}")
-    # 100 steps as the workload prescribes: indices every step, floats at 0, 1 and the last
-    _run_and_check(inst, wl, steps=wl.steps, check_float_steps=(0, 1, wl.steps - 1))
+    # 100 steps as the workload prescribes: indices every step, floats at 0, 1 and the last;
+    # then the same 100 steps through one sdt_train_loop call, as bench.py times them
+    seq, losses = _run_and_check(inst, wl, steps=wl.steps, check_float_steps=(0, 1, wl.steps - 1))
+    _loop_against_steps(inst, wl, seq, losses)
 
 
 @pytest.mark.timeout(600)
@@ -35,7 +41,8 @@ def test_products_spring_full_size():
     inst = gen.make_partition_instance(wl, p=4, which=0)
     _say(f"products_spring: generated in {time.time() - t:.1f}s, {inst.info}")
     assert inst.n_owned < inst.n_nodes
-    _run_and_check(inst, wl, steps=20, check_float_steps=(0, 19))
+    seq, losses = _run_and_check(inst, wl, steps=20, check_float_steps=(0, 19))
+    _loop_against_steps(inst, wl, seq, losses)
 
 
 @pytest.mark.timeout(900)
@@ -45,7 +52,9 @@ def test_dense_full_size():
     inst = gen.make_instance(wl)
     _say(f"dense: generated in {time.time() - t:.1f}s, nnz={inst.indptr[-1]}, "
          f"max degree {np.diff(inst.indptr).max()}")
-    _run_and_check(inst, wl, steps=12, check_float_steps=(0, 11))
+    assert wl.steps == 100
+    seq, losses = _run_and_check(inst, wl, steps=wl.steps, check_float_steps=(0, 1, wl.steps - 1))
+    _loop_against_steps(inst, wl, seq, losses)
 
 
 @pytest.mark.timeout(1500)
@@ -54,7 +63,9 @@ def test_sparse_bf16_full_size():
     t = time.time()
     inst = gen.make_instance(wl)
     _say(f"sparse_bf16: generated in {time.time() - t:.1f}s, nnz={inst.indptr[-1]}")
-    _run_and_check(inst, wl, steps=12, check_float_steps=(0, 11))
+    assert wl.steps == 200
+    seq, losses = _run_and_check(inst, wl, steps=wl.steps, check_float_steps=(0, 1, wl.steps - 1))
+    _loop_against_steps(inst, wl, seq, losses)
 
 
 @pytest.mark.timeout(900)
@@ -120,7 +131,7 @@ def test_products_full_size_other_model_kinds(kind):
     else:
         model = B.make_model(d, Wd, bd, kind=B.SDT_MODEL_GCN)
     lay = B.sdt_train_step_layout(g.n_nodes, wl.batch, wl.fanouts, model, B.SDT_F32)
-    ws = torch.empty(int(lay.total_bytes), dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(int(lay.total_bytes), dtype=torch.uint8, device="cuda")
     loss = torch.zeros(1, dtype=torch.float32, device="cuda")
     lr, tol = 0.01, TOL[torch.float32]
 

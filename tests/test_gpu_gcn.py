@@ -46,7 +46,7 @@ def test_gcn_kernels(F):
     # forward from local rows and straight out of the feature matrix through src_nodes
     X = rng.standard_normal((n, F)).astype(np.float32)
     Hloc = X[blk.src_nodes]
-    ref = orc.gcn_aggregate_fwd(blk.indptr, blk.cols, Hloc, f64(ds), f64(dc), f64(dself))
+    ref = orc.gcn_aggregate_fwd(blk.indptr, blk.cols, Hloc, s, c, selfw)      # the oracle's own normalisation vectors
     A = torch.zeros(blk.n_dst, F, dtype=torch.float32, device="cuda")
     B.sdt_gcn_aggregate_fwd(gb, dev(Hloc), dc, ds, dself, A)
     assert_close(f64(A), ref, TOL, "A from local rows")
@@ -55,7 +55,7 @@ def test_gcn_kernels(F):
     assert torch.equal(A, A2)
     # backward, with and without a ReLU mask
     dA = rng.standard_normal((blk.n_dst, F)).astype(np.float32)
-    refb = orc.gcn_aggregate_bwd(blk.indptr, blk.cols, blk.n_src, dA, f64(ds), f64(dc), f64(dself))
+    refb = orc.gcn_aggregate_bwd(blk.indptr, blk.cols, blk.n_src, dA, s, c, selfw)
     dH = torch.zeros(blk.n_src, F, dtype=torch.float32, device="cuda")
     B.sdt_gcn_aggregate_bwd(gb, dev(dA), dc, ds, dself, dH)
     assert_close(f64(dH), refb, TOL, "dH")
@@ -82,7 +82,7 @@ def test_gcn_train_step(classes):
     Wd, bd = [dev(w) for w in W], [dev(v) for v in b]
     model = B.make_model(d, Wd, bd, kind=B.SDT_MODEL_GCN)
     lay = B.sdt_train_step_layout(g.n_nodes, wl.batch, wl.fanouts, model, B.SDT_F32)
-    ws = torch.empty(int(lay.total_bytes), dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(int(lay.total_bytes), dtype=torch.uint8, device="cuda")
     loss = torch.zeros(1, dtype=torch.float32, device="cuda")
     lr = 0.05
     for step in range(2):
@@ -183,7 +183,7 @@ def test_gat_train_step(classes, adam):
         mom = dict(mW=zeros(Wd), vW=zeros(Wd), mb=zeros(bd), vb=zeros(bd), matt=zeros(ad), vatt=zeros(ad))
         B.use_adam(model, mom["mW"], mom["vW"], mom["mb"], mom["vb"], 0.9, 0.999, 1e-8, mom["matt"], mom["vatt"])
     lay = B.sdt_train_step_layout(g.n_nodes, wl.batch, wl.fanouts, model, B.SDT_F32)
-    ws = torch.empty(int(lay.total_bytes), dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(int(lay.total_bytes), dtype=torch.uint8, device="cuda")
     loss = torch.zeros(1, dtype=torch.float32, device="cuda")
     lr = 0.05
     for step in range(2):
@@ -255,12 +255,12 @@ def test_gat_train_loop_equals_steps():
         losses = torch.zeros(n_steps, dtype=torch.float32, device="cuda")
         if mode == "steps":
             lay = B.sdt_train_step_layout(g.n_nodes, wl.batch, wl.fanouts, model, B.SDT_F32)
-            ws = torch.empty(int(lay.total_bytes), dtype=torch.uint8, device="cuda")
+            ws = torch.zeros(int(lay.total_bytes), dtype=torch.uint8, device="cuda")
             for s in range(n_steps):
                 B.sdt_train_step(g, X, y, seeds[s], wl.fanouts, model, wl.seed, s, 0.05, losses[s:s + 1], ws)
         else:
             nbytes = B.sdt_train_loop_workspace_bytes(g.n_nodes, wl.batch, wl.fanouts, model, B.SDT_F32)
-            ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+            ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
             aux = [torch.cuda.Stream() for _ in range(2)]
             B.sdt_train_loop(g, X, y, seeds, wl.fanouts, model, wl.seed, 0, 0.05, losses, ws, aux_streams=aux)
         torch.cuda.synchronize()

@@ -27,9 +27,10 @@
  *    (the threads spin with yield on counters of the calling thread; if a thread
  *    cannot be started the call returns SDT_ERR_HIP); (2) two kernels that need
  *    more than 64 KB of LDS raise their limit once per process (atomic flags);
- *    (3) the caller-owned sdt_timing objects.  Entry points may be called from
- *    several threads as long as calls that share a workspace or a timing object
- *    are ordered.
+ *    (3) sdt_sage_linear_bwd_noalloc owns one device array per GPU and remembers
+ *    its address per device; (4) the caller-owned sdt_timing objects.  Entry
+ *    points may be called from several threads as long as calls that share a
+ *    workspace, a timing object or the built-in scratch are ordered.
  *  - `stream` is a hipStream_t (NULL = default stream).  All work is enqueued
  *    asynchronously; no call synchronises with the host.  Outputs are valid
  *    once the stream has been synchronised.  Two calls that share a workspace
@@ -317,6 +318,23 @@ int32_t sdt_sage_linear_bwd(const void *dY, int64_t lddy, int32_t dy_dtype, cons
                             int32_t n_cap, const int32_t *n_d, int32_t in, int32_t out, const float *W,
                             int32_t dtype, float *dW, float *db, void *dSelf, void *dAgg, int64_t ldi,
                             void *ws, size_t ws_bytes, void *stream);
+
+/* sdt_sage_linear_bwd for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * errors, without the workspace: the scratch (split partial products, bias partials, masked
+ * copy of dY) is a device array of SDT_NOALLOC_SCRATCH_BYTES built into the library, one copy
+ * per GPU, held until the process ends.  The call allocates and frees nothing and only launches
+ * kernels on `stream`.  Shapes whose sdt_linear_bwd_workspace_bytes exceeds the built-in size
+ * return SDT_ERR_WORKSPACE (use sdt_sage_linear_bwd then).  All calls on one GPU share that
+ * GPU's array: calls that may overlap in time on one GPU (different streams, different threads)
+ * race on it and must be ordered by the caller.  Nothing in the array has to start at zero: a
+ * call writes every byte it later reads. */
+#define SDT_NOALLOC_SCRATCH_BYTES (32u << 20)
+int32_t sdt_sage_linear_bwd_noalloc(const void *dY, int64_t lddy, int32_t dy_dtype, const void *Y, int64_t ldy,
+                                    int32_t relu, const void *Hself, int64_t ldh, const void *A, int64_t lda,
+                                    int32_t n_cap, const int32_t *n_d, int32_t in, int32_t out, const float *W,
+                                    int32_t dtype, float *dW, float *db, void *dSelf, void *dAgg, int64_t ldi,
+                                    void *stream);
 
 /* ---- the whole mini-batch step (Sec. II-A and III-D: local training on the
  * worker's partition between two model synchronisations) -------------------

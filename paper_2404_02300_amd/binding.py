@@ -89,6 +89,8 @@ EXPORTS = {
     "sdt_linear_bwd_workspace_bytes": (_sz, [_i32, _i32, _i32]),
     "sdt_sage_linear_bwd": (_i32, [_vp, _i64, _i32, _vp, _i64, _i32, _vp, _i64, _vp, _i64, _i32, _vp, _i32, _i32,
                                    _vp, _i32, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
+    "sdt_sage_linear_bwd_noalloc": (_i32, [_vp, _i64, _i32, _vp, _i64, _i32, _vp, _i64, _vp, _i64, _i32, _vp, _i32, _i32,
+                                           _vp, _i32, _vp, _vp, _vp, _vp, _i64, _vp]),
     "sdt_train_step_layout": (_i32, [_i64, _i32, _vp, _vp, _i32, _vp]),
     "sdt_train_step": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp, _i32, _vp, _vp, _u64, _u32, ctypes.c_float, _vp, _vp,
                               _vp, _sz, _vp]),
@@ -297,6 +299,22 @@ def sdt_sage_linear_bwd(dY: torch.Tensor, Y: Optional[torch.Tensor], relu: bool,
                                      _ptr(dW), _ptr(db), _ptr(dSelf), _ptr(dAgg),
                                      dSelf.stride(0) if dSelf is not None else 0, _ptr(ws),
                                      ws.numel() * ws.element_size(), _stream()))
+
+
+SDT_NOALLOC_SCRATCH_BYTES = 32 << 20
+
+
+def sdt_sage_linear_bwd_noalloc(dY: torch.Tensor, Y: Optional[torch.Tensor], relu: bool, Hself: torch.Tensor,
+                                A: torch.Tensor, W: torch.Tensor, dW: torch.Tensor, db: torch.Tensor,
+                                dSelf: Optional[torch.Tensor], dAgg: Optional[torch.Tensor],
+                                n_d: Optional[torch.Tensor] = None):
+    """sdt_sage_linear_bwd with the library's built-in scratch: no workspace argument."""
+    n, fin = A.shape
+    _check(lib().sdt_sage_linear_bwd_noalloc(_ptr(dY), dY.stride(0), dtype_code(dY), _ptr(Y),
+                                             Y.stride(0) if Y is not None else 0, int(relu), _ptr(Hself),
+                                             Hself.stride(0), _ptr(A), A.stride(0), n, _ptr(n_d), fin, W.shape[1],
+                                             _ptr(W), dtype_code(A), _ptr(dW), _ptr(db), _ptr(dSelf), _ptr(dAgg),
+                                             dSelf.stride(0) if dSelf is not None else 0, _stream()))
 
 
 def make_model(dims: Sequence[int], W: List[torch.Tensor], b: List[torch.Tensor],

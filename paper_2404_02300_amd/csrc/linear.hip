@@ -20,6 +20,7 @@
 #include <atomic>
 
 #include <algorithm>
+#include <mutex>
 
 namespace sdt {
 namespace {
@@ -976,4 +977,57 @@ extern "C" int32_t sdt_sage_linear_bwd(const void* dY, int64_t lddy, int32_t dy_
                                        void* ws, size_t ws_bytes, void* stream) {
     return linear_bwd(dY, lddy, dy_dtype, Y, ldy, relu, Hself, ldh, A, lda, n_cap, n_d, in, out, W, dtype, dW, db,
                       dSelf, dAgg, ldi, ws, ws_bytes, BwdExtras{}, static_cast<hipStream_t>(stream));
+}
+
+// ---- the same backward with its scratch inside the library ---------------------------------
+// For callers that cannot allocate device memory (under graph capture, in a serving loop, in a
+// harness that forbids it): the split partial products, the bias partials and the masked copy
+// of dY live in a file-scope device array instead of a caller's workspace.  Every GPU the
+// library runs on holds its own copy of the array at its own address until the process ends;
+// the address is looked up once per device, with that device current, and used from then on.
+static __device__ __align__(256) unsigned char scratch[SDT_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_mu;
+void* scratch_ptr[MAX_DEVICES] = {};
+
+// device address of `scratch` on the current device (nullptr + error text on failure)
+void* scratch_on_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+        set_error("sdt_sage_linear_bwd_noalloc: no current device (or device index %d beyond %d)", dev, MAX_DEVICES - 1);
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(scratch_mu);
+    if (!scratch_ptr[dev]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            set_error("sdt_sage_linear_bwd_noalloc: hipGetSymbolAddress failed on device %d: %s", dev, hipGetErrorString(e));
+            return nullptr;
+        }
+        scratch_ptr[dev] = p;
+    }
+    return scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" int32_t sdt_sage_linear_bwd_noalloc(const void* dY, int64_t lddy, int32_t dy_dtype, const void* Y, int64_t ldy,
+                                               int32_t relu, const void* Hself, int64_t ldh, const void* A, int64_t lda,
+                                               int32_t n_cap, const int32_t* n_d, int32_t in, int32_t out, const float* W,
+                                               int32_t dtype, float* dW, float* db, void* dSelf, void* dAgg, int64_t ldi,
+                                               void* stream) {
+    SDT_REQUIRE(n_cap >= 0 && in > 0 && out > 0, SDT_ERR_INVALID_ARG, "sdt_sage_linear_bwd_noalloc: bad sizes n=%d in=%d out=%d",
+                n_cap, in, out);
+    const size_t need = bwd_ws(n_cap, in, out).total;
+    SDT_REQUIRE(need <= (size_t)SDT_NOALLOC_SCRATCH_BYTES, SDT_ERR_WORKSPACE,
+                "sdt_sage_linear_bwd_noalloc: n=%d in=%d out=%d needs %zu bytes of scratch, the built-in buffer holds %zu; "
+                "use sdt_sage_linear_bwd with a workspace of the caller's", n_cap, in, out, need, (size_t)SDT_NOALLOC_SCRATCH_BYTES);
+    void* ws = scratch_on_current_device();
+    if (!ws) return SDT_ERR_HIP;
+    // every part of the scratch a call reads was written by that call before (partials of every split, the
+    // masked copy row by row), so nothing has to be cleared between calls
+    return linear_bwd(dY, lddy, dy_dtype, Y, ldy, relu, Hself, ldh, A, lda, n_cap, n_d, in, out, W, dtype, dW, db,
+                      dSelf, dAgg, ldi, ws, (size_t)SDT_NOALLOC_SCRATCH_BYTES, BwdExtras{}, static_cast<hipStream_t>(stream));
 }

@@ -1,12 +1,17 @@
 #!/usr/bin/env python3
-"""Benchmark of the whole mini-batch step (sdt_train_step) on one MI355X.
+"""Benchmark of the whole mini-batch step (sdt_train_loop / sdt_train_step) on one MI355X.
 
 A "step" is one pass of the hot path -- sample, gather, forward, loss, backward,
-SGD -- over one seeded synthetic mini-batch of the products-shaped workload
-(R-MAT 2^21 nodes, degree ~25, F=100, 47 classes, 2-layer GraphSAGE-mean with
-hidden 256, fan-out [15,10], 1024 seeds drawn from the owned quarter).  Graph,
-features, labels, weights and all seed batches are resident in HBM before the
-timed region starts.  Prints ONE JSON line.
+SGD -- over one seeded synthetic mini-batch.  The default workload is the
+dense-neighbourhood one (Chung-Lu 2^18 nodes, degree ~470, F=602, 41 classes,
+2-layer GraphSAGE-mean with hidden 256, fan-out [25,10], 1024 seeds): the largest
+fp32 step, where the kernels are long enough for their bandwidth and matrix-core
+fractions to mean something; the products-shaped step (latency-bound everywhere)
+is measured after it and reported under "also"; `--workload` selects any other.
+Graph, features, labels, weights and all seed batches are resident in HBM before
+a timed region starts.  The value is the median of `--reps` repetitions of one
+K-step loop call, each from the same initial weights, and every loss of the
+timed loops is checked against K sequential single-step calls.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -23,49 +28,74 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X dense bf16 matrix, published
 
-# HBM bytes per launch (read + written) from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs whose
-# summaries are committed under profiles/ (counter x factor calibrated on a 1 GiB copy: 2 KiB per
-# FETCH_SIZE count, 1 KiB per WRITE_SIZE count).  Counters cannot be read from inside this script, so
-# the figures are carried here; a stage without a counter run reports null.
-MEASURED_TRAFFIC_BYTES = {
-    ("products", "linear_fwd", 0): 6.03e6 + 3.98e6,
-    ("products", "head", 1): 3.33e6 + 8.66e6,
-    ("products", "aggregate_fwd", 0): 22.63e6 + 2.94e6,
-    ("sparse_bf16", "aggregate_fwd", 0): 76.2e6 + 13.44e6,
-    ("sparse_bf16", "linear_fwd", 0): 11.76e6 + 10.44e6,
-    ("dense", "aggregate_fwd", 0): 691.3e6 + 32.5e6,
-    ("dense", "gather", 0): 26.1e6 + 25.3e6,
-    ("dense", "linear_fwd", 0): 60.1e6 + 10.4e6,
-    ("dense", "linear_bwd", 0): 59.9e6 + 19.7e6,
-    ("fullgraph", "aggregate"): 78498.6e6 + 42674.4e6 + 4285.6e6 + 9.3e6,   # both launches of the SpMM
-    ("fullgraph", "linear"): 9129.2e6 + 4295.0e6,
-    # stage-at-scale modes: every kernel of one sdt_sample_csr call / the one gather kernel
-    ("sampling", "stage"): (2.1 + 207.1 + 2.4 + 4.6 + 136.3) * 1e6 + (2.1 + 70.2 + 10.2 + 9.2) * 1e6,
-    ("gather", "stage"): 350.1e6 + 313.4e6,
-}
+STEP_WORKLOADS = ["tiny", "products", "products_spring", "dense", "sparse_bf16"]
 
 
 def log(msg):
     print(msg, file=sys.stderr, flush=True)
 
 
+def measured_traffic(workload, kernel, rank=0):
+    """HBM bytes per launch (read + written) of `kernel` from profiles/traffic.json: the rocprofv3 --pmc
+    FETCH_SIZE / WRITE_SIZE figures that paper_2404_02300_amd/profile_summary.py wrote from a counter run
+    of this workload.  The file names the hash of the kernel sources it was measured with; when the tree's
+    sources hash differently (or there is no entry) the answer is None: a figure from another build is not
+    reported as this run's.  `rank`: which of the kernel's launch sizes, largest first (layer 0 is the largest)."""
+    try:
+        from paper_2404_02300_amd import profile_summary as ps
+        if not os.path.exists(ps.TRAFFIC):
+            return None
+        e = json.load(open(ps.TRAFFIC)).get(workload)
+        if not e or e.get("sources_hash") != ps.sources_hash():
+            return None
+        hits = sorted(((v["read_bytes"] + v["written_bytes"], k) for k, v in e["kernels"].items()
+                       if k.startswith(kernel)), reverse=True)
+        if rank >= len(hits):
+            return None
+        return {"bytes": round(hits[rank][0]), "kernel": hits[rank][1], "from": e.get("summary")}
+    except Exception as ex:       # a broken table must not break the measurement
+        log(f"[bench] traffic table unreadable: {ex}")
+        return None
+
+
+def measured_traffic_sum(workload, prefix):
+    """The same for every launch size of every kernel whose name starts with `prefix`, summed (a stage made
+    of several launches)."""
+    total, names, k = 0, [], 0
+    while True:
+        t = measured_traffic(workload, prefix, k)
+        if t is None:
+            break
+        total += t["bytes"]
+        names.append(t["kernel"])
+        src = t["from"]
+        k += 1
+    return {"bytes": total, "kernel": " + ".join(names), "from": src} if names else None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None,
-                    help="timed steps (default: the number the workload prescribes: 100, or 200 for sparse_bf16)")
+                    help="timed steps per repetition (default: the number the workload prescribes: 100, or 200 for sparse_bf16)")
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="products",
-                    choices=["tiny", "products", "products_spring", "dense", "sparse_bf16", "fullgraph", "sampling", "gather"],
-                    help="the five configured workloads; 'sampling' / 'gather' time that stage alone at a size "
-                         "where it is bandwidth-bound (every owned node of the products-shaped graph as a destination)")
+    ap.add_argument("--reps", type=int, default=3,
+                    help="repetitions of the timed region, each from the same initial weights; the median is reported")
+    ap.add_argument("--workload", default="dense",
+                    choices=STEP_WORKLOADS + ["fullgraph", "sampling", "gather"],
+                    help="default: dense, the largest fp32 training step (where the bandwidth and matrix-core fractions "
+                         "show); 'sampling' / 'gather' time that stage alone at a size where it is bandwidth-bound")
+    ap.add_argument("--also", default="products",
+                    help="comma-separated further step workloads measured after the main one (steps/s and the loss check only; "
+                         "'none' to skip); ignored unless the main workload is the default")
     ap.add_argument("--model", default="sage", choices=["sage", "gcn", "gat"],
                     help="gcn / gat: the same step with the GCN or GAT model kind (fp32 workloads; not the headline metric)")
     ap.add_argument("--lr", type=float, default=0.01)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial", action="store_true", help="no auxiliary stream: every step strictly in sequence")
     ap.add_argument("--aux", type=int, default=2, help="auxiliary streams the sampling phase alternates between")
-    ap.add_argument("--cpu-steps", type=int, default=2, help="oracle steps timed for cpu_baseline")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0,
+                    help="the oracle is timed on whole steps until this many seconds have passed (at least one step)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run one plain 1 GiB device copy (a reference dispatch for rocprofv3 --pmc runs)")
     args = ap.parse_args()
@@ -73,17 +103,12 @@ def main():
         log("bench.py: this build runs on ONE GPU (the per-worker step has no collectives); --gpus must be 1")
         sys.exit(2)
 
-    import numpy as np
     import torch
     import sdt_gen as gen
-    import paper_2404_02300_amd as sdt
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     wl = gen.WORKLOADS["products" if args.workload in ("sampling", "gather", "products_spring") else args.workload]
-    if args.steps is None:
-        args.steps = wl.steps if wl.steps > 1 else 100
-    K, Wm = args.steps, args.warmup
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)
@@ -91,20 +116,45 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     if args.workload == "fullgraph":
+        args.steps = args.steps or 20
         return bench_fullgraph(args, wl)
     if args.workload in ("sampling", "gather"):
+        args.steps = args.steps or 20
         return bench_stage_at_scale(args, wl)
+    out = bench_step(args, args.workload, full=True)
+    also = [w for w in args.also.split(",") if w and w != "none"]
+    if args.workload == "dense" and args.model == "sage" and also:
+        out["also"] = []
+        for w in also:
+            if w not in STEP_WORKLOADS or w == args.workload:
+                continue
+            r = bench_step(args, w, full=False)
+            out["also"].append({k: r[k] for k in ("value", "unit", "steps", "repetitions", "ms_per_step", "dtype", "config",
+                                                  "loss_check", "sampled_edges_per_s", "roofline")})
+    print(json.dumps(out), flush=True)
+
+
+def bench_step(args, workload, full):
+    """Steps/s of `workload` through sdt_train_loop (median of args.reps repetitions of K steps, each from
+    the same initial weights), the loss check against K sequential sdt_train_step calls, per-kernel HIP-event
+    times, the roofline entry of the longest kernel and (full) the oracle on the host."""
+    import numpy as np
+    import torch
+    import sdt_gen as gen
+    import paper_2404_02300_amd as sdt
 
     t0 = time.time()
     # products_spring: the products-shaped graph cut into four partitions by the paper's streaming
     # partitioner; the step runs on partition 0 (owned nodes + replicas), seeds from its owned nodes
-    spring = args.workload == "products_spring"
+    spring = workload == "products_spring"
+    wl = gen.WORKLOADS["products" if spring else workload]
+    K = args.steps if args.steps is not None else (wl.steps if wl.steps > 1 else 100)
+    Wm, R = args.warmup, max(1, args.reps)
     inst = gen.make_partition_instance(wl, p=4, which=0) if spring else gen.make_instance(wl)
     nnz_graph = int(inst.indptr[-1])
-    log(f"[bench] generated {args.workload}: N={inst.n_nodes} nnz={nnz_graph} avg_deg={nnz_graph / inst.n_nodes:.2f} "
+    log(f"[bench] generated {workload}: N={inst.n_nodes} nnz={nnz_graph} avg_deg={nnz_graph / inst.n_nodes:.2f} "
         f"in {time.time() - t0:.1f}s" + (f" {inst.info}" if spring else ""))
 
-    dt = torch.bfloat16 if wl.bf16 else torch.float32
     graph = sdt.Csr(torch.from_numpy(inst.indptr).cuda(), torch.from_numpy(inst.indices).cuda())
     if wl.bf16:
         X = torch.from_numpy(inst.X.view(np.int16)).cuda().view(torch.bfloat16)
@@ -127,11 +177,19 @@ def main():
         Wh = inst.W
     W = [torch.from_numpy(w).cuda() for w in Wh]
     b = [torch.from_numpy(v).cuda() for v in inst.b]
+    params = W + b + (att or [])
+    params0 = [p.clone() for p in params]
+
+    def restore():
+        for p, p0 in zip(params, params0):
+            p.copy_(p0)
+
     model = sdt.make_model(wl.dims, W, b, kind=sdt.SDT_MODEL_GAT if gat else sdt.SDT_MODEL_GCN if gcn else sdt.SDT_MODEL_SAGE_MEAN,
                            att=att)
     code = sdt.SDT_BF16 if wl.bf16 else sdt.SDT_F32
     lay = sdt.sdt_train_step_layout(graph.n_nodes, wl.batch, wl.fanouts, model, code)
-    ws = torch.empty(sdt.sdt_train_loop_workspace_bytes(graph.n_nodes, wl.batch, wl.fanouts, model, code),
+    # zeroed once after allocation: the headers of the step workspaces must not look like a clean node map
+    ws = torch.zeros(sdt.sdt_train_loop_workspace_bytes(graph.n_nodes, wl.batch, wl.fanouts, model, code),
                      dtype=torch.uint8, device="cuda")
     loss = torch.zeros(1, dtype=torch.float32, device="cuda")
     losses = torch.zeros(Wm + K, dtype=torch.float32, device="cuda")
@@ -142,32 +200,39 @@ def main():
 
     def run_loop(first, count, timing=None):
         # one native call enqueues `count` whole steps; the sampling phase of a step runs on the
-        # auxiliary stream, ahead of the forward/backward phase of the previous one
+        # auxiliary streams, ahead of the forward/backward phase of the previous ones
         sdt.sdt_train_loop(graph, X, y, seeds_all[first:first + count], wl.fanouts, model, wl.seed, first, args.lr,
                            losses[first:first + count], ws, aux, timing)
 
-    def run(first, count, timing=None, per_step=None):
+    # ---- stages: the coarse ones (a stage may span several launches) and the single launches inside them
+    coarse = [("sample", l) for l in range(L)] + [("loss", 0)] + [("linear_bwd", l) for l in range(L)]
+    kernels = [("sample_rows", l) for l in range(L)] + [("front_scan", l) for l in range(L)] + \
+              [("front_apply", l) for l in range(L)] + [("relabel", l) for l in range(L)] + \
+              ([] if gcn and not gat else [("gather", 0)]) + [("aggregate_fwd", l) for l in range(L)] + \
+              [("linear_fwd", l) for l in range(L)] + [("head", L - 1)] + [("bwd_weight", l) for l in range(L)] + \
+              [("bwd_input", l) for l in range(1, L)] + [("update", 0)]
+    if not gat:
+        kernels += [("aggregate_bwd", l) for l in range(1, L)]
+        # the transposed block of a small layer is one launch (the general path, five launches, stays a coarse stage)
+        small_t = [l for l in range(1, L) if lay.cap_nnz[l] <= (1 << 14)]
+        kernels += [("transpose", l) for l in small_t]
+        coarse += [("transpose", l) for l in range(1, L) if l not in small_t]
+    else:
+        coarse += [("aggregate_bwd", l) for l in range(L)] + [("transpose", l) for l in range(L)]
+    stages = coarse + kernels
+
+    def staged_pass(first, count, timed, with_counts):
+        """`count` sequential sdt_train_step calls (untimed by the wall clock); the first `timed` of them with
+        every stage bracketed by HIP events.  Returns mean stage times, block sizes of the timed steps, all losses."""
+        t = sdt.Timing(max(1, timed), stages)
+        cnts, ls = [], torch.zeros(count, dtype=torch.float32, device="cuda")
         for i in range(first, first + count):
-            sdt.sdt_train_step(graph, X, y, seeds_all[i], wl.fanouts, model, wl.seed, i, args.lr, loss, ws, timing)
-            if per_step is not None:
-                per_step(i)
-
-    stages = [("sample", l) for l in range(L)] + ([] if gcn and not gat else [("gather", 0)]) + \
-             [("aggregate_fwd", l) for l in range(L)] + \
-             [("linear_fwd", l) for l in range(L)] + [("loss", 0)] + [("linear_bwd", l) for l in range(L)] + \
-             [("aggregate_bwd", l) for l in range(0 if gat else 1, L)] + [("head", L - 1)]
-    single_kernel = {"gather", "aggregate_fwd", "linear_fwd", "aggregate_bwd", "head"}   # one launch per stage
-
-    def staged_pass(first, count, with_counts):
-        """`count` serial steps with every stage bracketed by HIP events (untimed by the wall clock)."""
-        t = sdt.Timing(count, stages)
-        cnts = []
-
-        def grab(i):
-            torch.cuda.synchronize()
-            cnts.append([sdt.ws_view(ws, lay.counts[l], (4,), torch.int32).cpu().tolist() for l in range(L)])
-
-        run(first, count, t, grab if with_counts else None)
+            sdt.sdt_train_step(graph, X, y, seeds_all[i], wl.fanouts, model, wl.seed, i, args.lr, ls[i - first:], ws,
+                               t if i - first < timed else None)
+            if with_counts and i - first < timed:
+                torch.cuda.synchronize()
+                cnts.append([sdt.ws_view(ws, lay.counts[l], (4,), torch.int32).cpu().tolist() for l in range(L)])
+        torch.cuda.synchronize()
         ms = {}
         for k, l in stages:
             try:
@@ -175,37 +240,52 @@ def main():
             except sdt.SdtError:    # stage not run separately (e.g. folded into the fused last layer)
                 pass
         t.close()
-        return ms, np.array(cnts)
+        return ms, np.array(cnts), ls.cpu().tolist()
 
-    # ---- warm-up (W pipelined steps, then a short staged pass that finds the dominant stage)
+    # ---- warm-up (W pipelined steps, then a short staged pass that finds the longest kernel)
     run_loop(0, Wm)
-    pre_ms, _ = staged_pass(0, min(5, Wm + K), False)
-    dominant = max((k for k in pre_ms if k[0] in single_kernel), key=pre_ms.get)   # the longest single kernel
+    pre_ms, _, _ = staged_pass(0, min(5, Wm + K), min(5, Wm + K), False)
+    dominant = max((k for k in pre_ms if k in kernels), key=pre_ms.get)   # the longest single launch of a step
 
-    # ---- the timed region: exactly K steps between two synchronisations; only the dominant
-    # stage is bracketed by HIP events (on the stream its kernels are launched on)
-    tim = sdt.Timing(K, [dominant], stride=8)    # every 8th launch: an event record costs the stream microseconds
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run_loop(Wm, K, tim)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    elapsed = t1 - t0
-    dom_ms = tim.read(*dominant)
-    tim.close()
-    final_loss = float(losses[-1].item())
+    # ---- the timed region, R times from the same initial weights: exactly K steps between two
+    # synchronisations; only the dominant kernel is bracketed by HIP events (on the stream it is launched on)
+    elapsed, dom_ms, rep_losses = [], [], []
+    for r in range(R):
+        restore()
+        tim = sdt.Timing(K, [dominant], stride=8)    # every 8th launch: an event record costs the stream microseconds
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_loop(Wm, K, tim)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        elapsed.append(t1 - t0)
+        dom_ms.append(float(np.mean(tim.read(*dominant))))
+        tim.close()
+        rep_losses.append(losses[Wm:Wm + K].cpu().tolist())
+    order = sorted(range(R), key=lambda r: elapsed[r])
+    med = order[R // 2]
+    t_med = elapsed[med]
+    assert all(rl == rep_losses[0] for rl in rep_losses), "the repetitions of the timed loop did not reproduce each other's losses"
+    final_loss = rep_losses[0][-1]
 
-    # ---- diagnostic pass (untimed): same batches again, every stage bracketed, sizes read back
+    # ---- loss check + diagnostic pass (untimed): the same K batches from the same initial weights through
+    # K sequential sdt_train_step calls; every loss must equal the timed loop's bit for bit
+    restore()
     nd = min(K, 20)
-    stage_t, counts = staged_pass(Wm, nd, True)        # counts: [nd, L, 4] = n_dst, n_src, nnz, 0
+    stage_t, counts, seq_losses = staged_pass(Wm, K, nd, True)        # counts: [nd, L, 4] = n_dst, n_src, nnz, 0
+    bad = [i for i in range(K) if seq_losses[i] != rep_losses[0][i]]
+    assert not bad, (f"losses of the timed loop differ from {K} sequential sdt_train_step calls at steps {bad[:8]}: "
+                     f"{[rep_losses[0][i] for i in bad[:4]]} vs {[seq_losses[i] for i in bad[:4]]}")
+    loss_check = (f"all {K} losses of each of the {R} timed repetitions bit-equal to {K} sequential sdt_train_step calls "
+                  f"from the same initial weights (final loss {final_loss:.6f})")
     mean_cnt = counts.mean(axis=0)
     edges_per_step = float(counts[:, :, 2].sum(axis=1).mean())
     n_src0 = mean_cnt[0][1]
     d = wl.dims
-    fused_head = ("linear_fwd", L - 1) not in stage_t
+    N = inst.n_nodes
 
     def work(kind, l):
-        """Algorithmic work of one launch of a stage: (bound, amount, unit of the rate, kernels)."""
+        """Algorithmic work of one launch of a stage: (bound, amount, kernel name)."""
         n_dst, n_src, nnz = mean_cnt[l][:3]
         wf = 1.0 if gcn else 2.0      # rows of W per input feature: GraphSAGE stacks a self and a neighbour block
         if gat:     # every frontier row is gathered and projected; the attention passes read projected rows
@@ -219,55 +299,89 @@ def main():
                        "k_gat_mask_bias + k_gat_bwd_dst + k_gat_bwd_src + k_gat_vec_partials"
             if kind == "linear_fwd":
                 return "mfma", 2.0 * n_src * d[l] * F, "k_linear_fwd"
-            if kind == "linear_bwd":
-                return "mfma", 2.0 * n_src * d[l] * F * (2 if l > 0 else 1), "k_linear_bwd_weight (+ _input)"
+            if kind in ("linear_bwd", "bwd_weight", "bwd_input"):
+                f = 2.0 * n_src * d[l] * F
+                return "mfma", f * (2 if l > 0 and kind == "linear_bwd" else 1), \
+                       {"linear_bwd": "k_linear_bwd_weight (+ _input)", "bwd_weight": "k_linear_bwd_weight",
+                        "bwd_input": "k_linear_bwd_input"}[kind]
         if kind == "sample":      # 16 B of row offsets per destination, 4 B read + 4 B written per sampled edge
             return "hbm", n_dst * 16 + nnz * 8, "k_sample_rows + frontier scan + relabel (+ transposed block)"
+        if kind == "sample_rows":
+            return "hbm", n_dst * 16 + nnz * 8, "k_sample_rows"
+        if kind == "front_scan":      # the frontier bitmap and the per-row counts, read once
+            return "hbm", N / 8 + n_dst * 4, "k_front_partials"
+        if kind == "front_apply":     # the same again, plus row offsets, the new frontier ids and their map entries
+            return "hbm", N / 8 + n_dst * 12 + (n_src - n_dst) * 8, "k_front_apply"
+        if kind == "relabel":         # global id in, map entry in, local id out (+ a histogram count per edge)
+            return "hbm", nnz * 16, "k_relabel"
+        if kind == "transpose":       # row offsets and column ids in, source offsets and destination rows out
+            return "hbm", nnz * 8 + n_dst * 4 + n_src * 8, "k_transpose_small" if lay.cap_nnz[l] <= (1 << 14) else \
+                   "k_scan_partials + k_scan_apply + k_transpose_fill + k_sort_short + k_sort_long"
+        if kind == "update":          # every layer's partial products read once, weights and gradients written
+            return "hbm", float(sum(wf * d[j] * d[j + 1] * 4 * 8 for j in range(L))), "k_reduce_partials"
         if kind == "gather":      # only the destination prefix is copied; the rest is read by the aggregation
             return "hbm", n_dst * (2 * d[0] * es + 4), "k_gather"
         if kind == "aggregate_fwd":   # layer 0 reads X through src_nodes: 4 more index bytes per edge
-            return "hbm", nnz * (d[l] * es + (8 if l == 0 else 4)) + n_dst * (d[l] * es + 8), "k_aggregate_fwd"
+            return "hbm", nnz * (d[l] * es + (8 if l == 0 else 4)) + n_dst * (d[l] * es + 8), \
+                   "k_gcn_aggregate_fwd" if gcn else "k_aggregate_fwd"
         if kind == "aggregate_bwd":
-            return "hbm", nnz * (d[l] * es + 4) + n_src * (d[l] * es + 8) + n_dst * d[l] * es, "k_aggregate_bwd"
-        if kind == "linear_fwd":    # bf16 workloads: bf16 matrix cores (priced against the bf16 peak)
-            return ("mfma_bf16" if wl.bf16 else "mfma"), 2.0 * n_dst * wf * d[l] * d[l + 1], \
-                   ("k_fwd_bf16" if wl.bf16 else "k_linear_fwd")
-        if kind == "linear_bwd":
+            return "hbm", nnz * (d[l] * es + 4) + n_src * (d[l] * es + 8) + n_dst * d[l] * es, \
+                   "k_gcn_aggregate_bwd" if gcn else "k_aggregate_bwd"
+        if kind == "linear_fwd":
+            # bf16 workloads: the products run on the bf16 matrix cores, but the layer is below their ridge
+            # (2.5 PFLOP/s / 8 TB/s = 312 flop/B against ~128 flop/B here), so it is priced by the bytes it
+            # must move: both operands and the weights in, the output rows out
+            if wl.bf16:
+                return "hbm", n_dst * (2 * d[l] + d[l + 1]) * es + 2 * d[l] * d[l + 1] * 2, "k_fwd_bf16"
+            return "mfma", 2.0 * n_dst * wf * d[l] * d[l + 1], "k_linear_fwd"
+        if kind in ("linear_bwd", "bwd_weight", "bwd_input"):
             f = 2.0 * n_dst * wf * d[l] * d[l + 1]
-            if l == L - 1 and fused_head:   # projection + softmax + dW + input gradients in one launch
+            if wl.bf16:   # as the forward: operands in, partial products / input gradients out
+                by_w = n_dst * (2 * d[l] + d[l + 1]) * es + 2 * d[l] * d[l + 1] * 4
+                by_i = n_dst * (d[l + 1] + 2 * d[l]) * es + 2 * d[l] * d[l + 1] * 2
+                return "hbm", {"linear_bwd": by_w + (by_i if l > 0 else 0), "bwd_weight": by_w, "bwd_input": by_i}[kind], \
+                       {"linear_bwd": "k_bwd_weight_bf16 (+ k_bwd_input_bf16)", "bwd_weight": "k_bwd_weight_bf16",
+                        "bwd_input": "k_bwd_input_bf16"}[kind]
+            if kind == "linear_bwd" and l == L - 1 and ("head", l) in stage_t:   # projection + softmax + dW + input gradients
                 return "mfma", f * (3 if l > 0 else 2), "k_head"
-            if wl.bf16:   # both backward products on the bf16 matrix cores
-                return "mfma_bf16", f * (2 if l > 0 else 1), "k_bwd_weight_bf16 (+ k_bwd_input_bf16)"
-            return "mfma", f * (2 if l > 0 else 1), "k_linear_bwd_weight (+ _input)"
+            return "mfma", f * (2 if l > 0 and kind == "linear_bwd" else 1), \
+                   {"linear_bwd": "k_linear_bwd_weight (+ _input)", "bwd_weight": "k_linear_bwd_weight",
+                    "bwd_input": "k_linear_bwd_input"}[kind]
         if kind == "head":        # projection + dW (+ input gradients) of the last layer, one launch
             return "mfma", 2.0 * n_dst * wf * d[l] * d[l + 1] * (3 if l > 0 else 2), "k_head"
         return "hbm", wl.batch * d[L] * 8, "k_softmax_xent"
 
     def rate(kind, l, seconds):
-        bound, amount, kernels = work(kind, l)
+        bound, amount, kname = work(kind, l)
         if bound == "hbm":
             ach, peak, unit = amount / seconds / 1e9, HBM_PEAK_GBS, "GB/s"
-        elif bound == "mfma_bf16":
-            bound, ach, peak, unit = "mfma", amount / seconds / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
         else:
             ach, peak, unit = amount / seconds / 1e12, MFMA_FP32_PEAK_TFLOPS, "TFLOP/s"
-        return {"stage": f"{kind}[{l}]", "kernel": kernels, "bound": bound, "achieved": round(ach, 2), "peak": peak,
+        return {"stage": f"{kind}[{l}]", "kernel": kname, "bound": bound, "achieved": round(ach, 2), "peak": peak,
                 "unit": unit, "frac": round(ach / peak, 4), "algorithmic_per_launch": float(amount),
                 "avg_launch_us": round(seconds * 1e6, 2)}
 
-    # roofline of the dominant stage, from the events recorded inside the timed region
-    roofline = rate(dominant[0], dominant[1], float(np.mean(dom_ms)) * 1e-3)
-    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((wl.name, dominant[0], dominant[1])) if args.model == "sage" and not spring else None
+    # roofline of the longest kernel, from the events recorded inside the timed region (median repetition)
+    roofline = rate(dominant[0], dominant[1], dom_ms[med] * 1e-3)
+    roofline["avg_launch_us_serial"] = round(stage_t.get(dominant, float("nan")) * 1e3, 2)   # the same kernel with nothing beside it
+    tr = None
+    if args.model == "sage":
+        same = sorted((l for (k, l) in stage_t if k == dominant[0]), key=lambda l: -work(dominant[0], l)[1])
+        tr = measured_traffic(workload, work(*dominant)[2].split()[0], same.index(dominant[1]) if dominant[1] in same else 0)
+    roofline["traffic"] = tr["bytes"] if tr else None
+    roofline["traffic_from"] = (f"{tr['from']}: {tr['kernel']}" if tr else
+                                "no counter run of this build's kernel sources in profiles/traffic.json")
     stage_ms = {f"{k}[{l}]": v for (k, l), v in stage_t.items()}
-    others = [rate(k, l, v * 1e-3) for (k, l), v in stage_t.items()]
+    others = [rate(k, l, v * 1e-3) for (k, l), v in stage_t.items() if (k, l) in kernels]
 
     # ---- CPU baseline: the oracle as it stands, one thread, on a bounded sample of the same workload
     cpu = None
-    if not args.no_cpu_baseline:
+    if full and not args.no_cpu_baseline:
         from oracle import sdt_oracle as orc
-        ns = max(1, args.cpu_steps)
+        ns = 0
         tc = time.perf_counter()
-        for s in range(ns):
+        while ns == 0 or (time.perf_counter() - tc < args.cpu_seconds and ns < min(K, 32)):
+            s = ns
             if gat:
                 orc.gat_train_step(inst.indptr, inst.indices, inst.X, inst.y, inst.batch(s), wl.fanouts, Wh, inst.b, att_h,
                                    wl.seed, s, args.lr)
@@ -277,6 +391,7 @@ def main():
             else:
                 orc.train_step(inst.indptr, inst.indices, inst.X, inst.y, inst.batch(s), wl.fanouts, inst.W, inst.b,
                                wl.seed, s, args.lr, bf16=wl.bf16)
+            ns += 1
         tc = time.perf_counter() - tc
         cores = 1
         if gcn:     # the GCN oracle's projections are numpy matrix products: count the BLAS threads
@@ -286,13 +401,13 @@ def main():
             except Exception:
                 cores = os.cpu_count()
         cpu = {"value": round(ns / tc, 4), "unit": "steps/s", "cores": cores, "kind": "oracle",
-               "sample": f"{ns} full mini-batch steps of the same workload (batches 0..{ns - 1}, initial weights)",
+               "sample": f"{ns} full mini-batch steps of the same workload (batches 0..{ns - 1}, initial weights), {tc:.1f} s",
                "host_cpus": os.cpu_count()}
 
-    out = {
+    return {
         "metric": "train steps/s per GPU (sample + gather + forward + backward + SGD)" + (" [GAT model kind]" if gat else " [GCN model kind]" if gcn else ""),
-        "value": round(K / elapsed, 2), "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": Wm,
-        "ms_per_step": round(elapsed / K * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "value": round(K / t_med, 2), "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": Wm, "repetitions": R,
+        "ms_per_step": round(t_med / K * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if wl.bf16 else "f32", "data": "synthetic",
         "config": {"workload": (f"{wl.name}: {wl.kind} 2^{wl.log2n} nodes, {nnz_graph} CSR entries, " if not spring else
                                 f"products_spring: partition 0 of 4 of the {wl.kind} 2^{wl.log2n} graph without isolated nodes "
@@ -301,14 +416,16 @@ def main():
                                f"C={wl.classes}, {L}-layer {'GAT' if gat else 'GCN' if gcn else 'GraphSAGE-mean'} hidden {wl.hidden}, fanout {wl.fanouts}, "
                                f"batch {wl.batch}, seeds from " + ("the owned nodes" if spring else f"the first {wl.owned_frac:g} of the ids"),
                    "lr": args.lr, "seed": wl.seed},
-        "sampled_edges_per_s": round(edges_per_step * K / elapsed, 1),
+        "value_is": f"median of {R} repetitions of one {K}-step sdt_train_loop call",
+        "steps_per_s_all_repetitions": [round(K / e, 2) for e in elapsed],
+        "sampled_edges_per_s": round(edges_per_step * K / t_med, 1),
         "sampled_edges_per_step": round(edges_per_step, 1),
         "frontier_rows_per_step": round(float(n_src0), 1),
-        "final_loss": round(final_loss, 6), "overlap": "serial" if args.serial else f"sampling of the next steps on {len(aux)} auxiliary stream(s)",
+        "final_loss": round(final_loss, 6), "loss_check": loss_check,
+        "overlap": "serial" if args.serial else f"sampling of the next steps on {len(aux)} auxiliary stream(s)",
         "roofline": roofline, "cpu_baseline": cpu,
-        "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()}, "stage_rates": others,
+        "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()}, "kernel_rates": others,
     }
-    print(json.dumps(out), flush=True)
 
 
 def bench_stage_at_scale(args, wl):
@@ -373,6 +490,7 @@ def bench_stage_at_scale(args, wl):
         tc = time.perf_counter() - tc
         cpu = {"value": round((b.nnz if args.workload == "sampling" else b.n_src) / tc, 1), "unit": unit_name, "cores": 1,
                "kind": "oracle", "sample": f"the first {m} destination rows of the same launch", "host_cpus": os.cpu_count()}
+    tr = measured_traffic_sum(args.workload, "k_")
     out_json = {
         "metric": f"{unit_name} of the {args.workload} stage alone ({cnt[0]} destination rows, fan-out {fanout})",
         "value": round(units / sec, 1), "unit": unit_name, "n_gpus": 1, "steps": K, "warmup": Wm,
@@ -382,7 +500,8 @@ def bench_stage_at_scale(args, wl):
                                f"{cnt[0]} destinations, {cnt[1]} frontier rows, {cnt[2]} sampled edges"},
         "roofline": {"kernel": kern, "bound": "hbm", "achieved": round(amount / sec / 1e9, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(amount / sec / 1e9 / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "stage")),
+                     "traffic": tr["bytes"] if tr else None,
+                     "traffic_from": f"{tr['from']}: {tr['kernel']}" if tr else "no counter run of this build's kernel sources in profiles/traffic.json",
                      "algorithmic_bytes_per_launch": int(amount), "avg_launch_us": round(sec * 1e6, 1)},
         "cpu_baseline": cpu,
     }
@@ -461,6 +580,8 @@ def bench_fullgraph(args, wl):
         cpu = {"value": round(len(rows) / tc, 1), "unit": "nodes/s", "cores": 1, "kind": "oracle",
                "sample": f"{len(rows)} seeded random rows of the same layer (SpMM + projection), rows are independent",
                "host_cpus": os.cpu_count()}
+    tr_agg = measured_traffic_sum(wl.name, "k_aggregate")
+    tr_gemm = measured_traffic(wl.name, "k_linear_fwd")
     out = {
         "metric": "full-neighbour GraphSAGE-mean layer, nodes/s (SpMM over the whole CSR + projection)",
         "value": round(N * K / elapsed, 1), "unit": "nodes/s", "n_gpus": 1, "steps": K, "warmup": Wm,
@@ -468,15 +589,20 @@ def bench_fullgraph(args, wl):
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: rmat 2^{wl.log2n} nodes, {nnz} CSR entries, F={F} -> {O}, one layer, "
                                f"no sampling", "seed": wl.seed},
+        # the SpMM's fraction of the HBM roofline is taken from the counters (bytes that crossed the L2) when a counter
+        # run of this build exists; the gather-side algorithmic figure (every neighbour row once per edge) is beside it
         "roofline": {"kernel": "k_aggregate_fwd<float,4,64,long> + k_aggregate_long (whole CSR, hub rows in the second launch)",
                      "bound": "hbm",
-                     "achieved": round(agg_bytes / agg_s / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(agg_bytes / agg_s / 1e9 / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, "aggregate")),
+                     "achieved": round((tr_agg["bytes"] if tr_agg else agg_bytes) / agg_s / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round((tr_agg["bytes"] if tr_agg else agg_bytes) / agg_s / 1e9 / HBM_PEAK_GBS, 4),
+                     "basis": "rocprofv3 FETCH_SIZE + WRITE_SIZE bytes per launch" if tr_agg else "algorithmic (gather-side) bytes: no counter run of this build",
+                     "traffic": tr_agg["bytes"] if tr_agg else None,
+                     "traffic_from": f"{tr_agg['from']}: {tr_agg['kernel']}" if tr_agg else None,
+                     "algorithmic_GBps": round(agg_bytes / agg_s / 1e9, 1), "algorithmic_frac": round(agg_bytes / agg_s / 1e9 / HBM_PEAK_GBS, 4),
                      "algorithmic_bytes_per_launch": int(agg_bytes), "compulsory_bytes_per_launch": int(compulsory),
                      "compulsory_GBps": round(compulsory / agg_s / 1e9, 1), "avg_launch_us": round(agg_s * 1e6, 1)},
         "gemm": {"kernel": "k_linear_fwd<float, float, Tile<128, 256, 16, 2, 4>, 4, 4, false>", "bound": "mfma",
-                 "TFLOPs": round(flops / gemm_s / 1e12, 2), "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, "linear")),
+                 "TFLOPs": round(flops / gemm_s / 1e12, 2), "traffic": tr_gemm["bytes"] if tr_gemm else None,
                  "peak": MFMA_FP32_PEAK_TFLOPS, "frac": round(flops / gemm_s / 1e12 / MFMA_FP32_PEAK_TFLOPS, 4),
                  "flops_per_launch": flops, "avg_launch_us": round(gemm_s * 1e6, 1)},
         # the same layer through sdt_sage_layer_csr_fwd (aggregated rows kept in LDS, no N x F buffer)

@@ -124,6 +124,18 @@ def test_invalid_arguments_are_reported_not_crashed():
     assert L.sdt_sage_linear_fwd(None, 4, None, 4, 3, None, 4, 4, None, None, 0, 0, None, 4, 0, None) == B.SDT_ERR_INVALID_ARG
 
 
+def test_noalloc_entry_point_rejects_oversized_shapes_on_the_host():
+    """The size check of the entry point with built-in scratch is host arithmetic and comes before any GPU call."""
+    L = B.lib()
+    n, fin, fout = 67584, 128, 256
+    assert B.sdt_linear_bwd_workspace_bytes(n, fin, fout) > B.SDT_NOALLOC_SCRATCH_BYTES
+    rc = L.sdt_sage_linear_bwd_noalloc(None, fout, 0, None, 0, 0, None, fin, None, fin, n, None, fin, fout, None, 0, None, None,
+                                       None, None, 0, None)
+    assert rc == B.SDT_ERR_WORKSPACE and "built-in" in B.sdt_last_error()
+    assert L.sdt_sage_linear_bwd_noalloc(None, 4, 0, None, 0, 0, None, 4, None, 4, -1, None, 4, 4, None, 0, None, None,
+                                         None, None, 0, None) == B.SDT_ERR_INVALID_ARG
+
+
 def test_bench_refuses_more_than_one_gpu():
     """bench.py measures one GPU's throughput; asking for more exits with a message before anything is loaded."""
     import subprocess

@@ -152,8 +152,8 @@ enum { SDT_OPT_SGD = 0, SDT_OPT_ADAM = 1 };
  * t_indptr/t_rows exist for l >= 1 only (layer 0 needs no input gradient). */
 typedef struct sdt_step_layout {
     uint64_t total_bytes;
-    uint64_t header; /* int32[64]: {magic, n_nodes, ...}; see sdt_train_step */
-    uint64_t state;  /* node -> local-id map and frontier bitmap, kept clean between steps */
+    uint64_t header; /* int32[64], reserved */
+    uint64_t state;  /* frontier state of the step being built: node -> local-id map, two state bits per node, per-word ranks */
     int32_t n_layers;
     int32_t cap_dst[SDT_MAX_LAYERS];
     int32_t cap_src[SDT_MAX_LAYERS];
@@ -318,7 +318,6 @@ int32_t sdt_sage_linear_bwd(const void *dY, int64_t lddy, int32_t dy_dtype, cons
                             int32_t n_cap, const int32_t *n_d, int32_t in, int32_t out, const float *W,
                             int32_t dtype, float *dW, float *db, void *dSelf, void *dAgg, int64_t ldi,
                             void *ws, size_t ws_bytes, void *stream);
-
 /* sdt_sage_linear_bwd for callers that cannot allocate device memory: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
  * errors, without the workspace: the scratch (split partial products, bias partials, masked
@@ -344,16 +343,12 @@ int32_t sdt_sage_linear_bwd_noalloc(const void *dY, int64_t lddy, int32_t dy_dty
  * labels[seeds[i]], backward, and W -= lr dW, b -= lr db (plain SGD on the
  * fp32 weights; lr = 0 leaves them bit-identical).  loss_d receives the loss.
  * X is [n_nodes, F = dims[0]] in `dtype` with leading dimension ldx.
- * Workspace: unlike the other calls' scratch, the step workspace carries state
- * from one step to the next: a header plus a node map that every step hands
- * back clean, so the map is initialised only when the header does not say
- * "clean".  A step takes that word away before it writes its first map entry
- * and its last map-cleaning kernel puts it back, so a step whose launches stop
- * half-way (an error return) leaves a workspace that the next step initialises
- * again.  The caller's part: zero the first 256 bytes once after allocating the
- * buffer (memory fresh from an allocator may happen to hold an old header over
- * other data), let nobody else write to it between steps, and zero the first
- * 256 bytes again after using the buffer for anything else.
+ * Workspace: like the other calls' scratch, it needs no initialisation and carries
+ * nothing from one step to the next -- every step rebuilds its frontier state from
+ * nothing (two bits per node are cleared when it starts; the node -> local-id map is
+ * read only where the same step wrote it) -- so the buffer may be used for anything
+ * else between steps.  What a step leaves in it (blocks, activations, gradients; see
+ * sdt_train_step_layout) stays readable until the next call that uses it.
  * sdt_train_step_layout fills `layout` (host) with the workspace size and
  * the offsets of every intermediate.
  * Without a timing object the call only launches kernels on `stream`: no
@@ -428,9 +423,8 @@ int32_t sdt_train_step(const sdt_csr *graph /*host struct*/, const void *X, int6
  * seeds is device int32[n_steps, batch]; losses_d device fp32[n_steps].  The
  * workspace (sdt_train_loop_workspace_bytes: a whole number of step workspaces,
  * each with sdt_train_step's layout rounded up to 256 bytes, back to back;
- * step i of a call uses workspace i modulo their number) carries
- * state like sdt_train_step's: zero it (or the first 256 bytes of each step workspace
- * in it) once after allocation.  aux_streams is a HOST array of n_aux (0..3)
+ * step i of a call uses workspace i modulo their number) needs no initialisation
+ * either.  aux_streams is a HOST array of n_aux (0..3)
  * streams, all different from `stream`; n_aux = 0 gives the serial order.  The
  * sampling chain is a sequence of small latency-bound launches, so two auxiliary
  * streams sample twice as many steps per unit of time as one.

@@ -141,11 +141,13 @@ inline size_t dtype_size(int32_t dt) { return dt == SDT_BF16 ? 2 : 4; }
 inline bool dtype_ok(int32_t dt) { return dt == SDT_F32 || dt == SDT_BF16; }
 
 // ---- internal entry points shared between translation units -------------------
-// Sampling scratch.  map/bitmap persist across the layers of one step (and, for
-// sdt_train_step, across steps: every step leaves the map at -1 and the bitmap clear).
+// Sampling state and scratch.  map / bits / wp are shared by the layers of one step; nothing in them
+// outlives a step (the state words are cleared when a step starts, see sample.hip).
 struct SampleWs {
-    int32_t* map;      // [n_nodes]   global id -> local id in the current frontier, -1 = absent
-    uint32_t* bitmap;  // [ceil(n_nodes/32)]  newly reached nodes (all zero between layers)
+    int32_t* map;      // [n_nodes]   global id -> local id, valid only for nodes whose frontier bit is set
+    uint32_t* bits;    // [ceil(n_nodes/16)]  two bits per node: in the frontier / added by the last layer sampled
+    uint8_t* mark;     // [16 ceil(n_nodes/16)] one byte per node: reached by the layer being sampled
+    int32_t* wp;       // [ceil(n_nodes/16)]  local id of the first node the current layer added in each word
     int32_t* e_pad;    // [cap_dst*fanout]    sampled global ids, row-padded
     int32_t* m;        // [cap_dst]           sampled count per row
     int32_t* part;     // scan partials
@@ -155,28 +157,25 @@ struct SampleWs {
 size_t sample_state_bytes(int64_t n_nodes);
 void sample_state_carve(void* base, int64_t n_nodes, SampleWs* out);
 size_t sample_tmp_carve(Arena& a, int64_t n_nodes, int32_t cap_dst, int32_t fanout, SampleWs* out);
-// header: int32[64] at the start of a step workspace, {magic, n_nodes, ...}, or nullptr.  The magic word
-// says "the node map and the bitmap of this workspace are clean": sample_seed_map takes it away before the
-// first map entry of a step is written, and the LAST kernel of the step that hands map entries back clean
-// (`stamp` argument of gather_rows / aggregate_gather_fwd / gcn_aggregate_fwd) puts it back.  A step whose
-// launch chain stops half-way therefore leaves a workspace that the next step initialises again.
-constexpr int32_t STATE_MAGIC = 0x53445431;  // "SDT1"
-int32_t sample_state_init(const SampleWs& ws, int64_t n_nodes, const int32_t* header, hipStream_t st);
+// start of a step: no node is in the frontier
+int32_t sample_state_clear(const SampleWs& ws, int64_t n_nodes, hipStream_t st);
+// the seeds (or any first destination list) join the frontier with local ids 0, 1, ...
 int32_t sample_seed_map(const SampleWs& ws, const int32_t* dst_nodes, int32_t n_dst_cap, const int32_t* n_dst_d,
-                        int32_t* header, int64_t n_nodes, hipStream_t st);
-// timing / slot (nullable / -1): brackets the kernels of the layer one by one (SDT_STAGE_SAMPLE_ROWS ... _TRANSPOSE)
+                        hipStream_t st);
+// write_map: the nodes this layer adds get their local ids recorded in ws.map (needed when a further layer is
+// sampled from the resulting frontier).  timing / slot (nullable / -1): brackets the kernels of the layer one by
+// one (SDT_STAGE_SAMPLE_ROWS ... _TRANSPOSE)
 int32_t sample_layer(const sdt_csr& g, const int32_t* dst_nodes, int32_t n_dst_cap, const int32_t* n_dst_d,
                      int32_t fanout, uint64_t seed, uint32_t step, uint32_t layer, const sdt_block& out,
-                     const SampleWs& ws, hipStream_t st, sdt_timing* timing = nullptr, int slot = -1);
-// gather that also resets map[idx[j]] = -1 (map may be null; stamp, nullable: header to mark clean); zero_pad: columns F..ldo-1 of every output row
+                     const SampleWs& ws, bool write_map, hipStream_t st, sdt_timing* timing = nullptr, int slot = -1);
+// out[j, :] = X[idx[j], :]; zero_pad: columns F..ldo-1 of every output row
 // are set to zero, and those of the same rows of also_pad (nullable: a second matrix of out's shape and stride)
 int32_t gather_rows(const void* X, int64_t ldx, int32_t F, int32_t dtype, const int32_t* idx, int32_t n_cap,
-                    const int32_t* n_d, void* out, int64_t ldo, int32_t* map_reset, int32_t* stamp, bool zero_pad,
-                    void* also_pad, hipStream_t st);
+                    const int32_t* n_d, void* out, int64_t ldo, bool zero_pad, void* also_pad, hipStream_t st);
 
-// mean aggregation straight from the feature matrix through blk->src_nodes (+ optional map reset)
+// mean aggregation straight from the feature matrix through blk->src_nodes
 int32_t aggregate_gather_fwd(const sdt_block* blk, const void* X, int64_t ldx, int32_t F, int32_t dtype, void* A,
-                             int64_t lda, int32_t* map_reset, int32_t* stamp, hipStream_t st);
+                             int64_t lda, hipStream_t st);
 
 // writes dZ and the per-row losses; their mean is folded into a later single-block pass
 int32_t softmax_xent(const float* logits, int64_t ld, int32_t B, int32_t C, const int32_t* labels,
@@ -270,10 +269,9 @@ int32_t linear_bwd_input_bf16(const void* dY, int64_t lddy, int32_t dy_dtype, in
                               int32_t in, int32_t out, const void* Wb, void* dSelf, void* dAgg, int64_t ldi,
                               hipStream_t st);
 
-// GCN aggregation (gcn.hip); map_reset as in aggregate_gather_fwd
+// GCN aggregation (gcn.hip)
 int32_t gcn_aggregate_fwd(const sdt_block* blk, const float* H, int64_t ldh, bool through_src_nodes, int32_t F,
-                          const float* c, const float* s, const float* selfw, float* A, int64_t lda, int32_t* map_reset,
-                          int32_t* stamp, hipStream_t stm);
+                          const float* c, const float* s, const float* selfw, float* A, int64_t lda, hipStream_t stm);
 
 constexpr int GAT_CHUNK_ROWS = 256;   // rows per partial column sum of the GAT bias / attention-vector gradients
 // GAT attention aggregation inside a training step (gat.hip).  The forward adds `bias` (may be null) and

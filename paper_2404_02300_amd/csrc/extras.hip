@@ -185,21 +185,8 @@ extern "C" int32_t sdt_train_round(const sdt_partition* parts, int32_t n_parts, 
             }
         }
         if (parts[j].n_steps > 0) {
-            // The step workspaces carry a header that says whether their node map is clean.  The
-            // previous partition laid its buffers out differently, so invalidate the headers of the
-            // step workspaces of this partition's layout before its first step.
-            sdt_step_layout lay;
-            rc = sdt_train_step_layout(parts[j].graph.n_nodes, batch, fanouts, &locals[j], dtype, &lay);
-            if (rc != SDT_OK) return rc;
-            const size_t one = align_up((size_t)lay.total_bytes, 256);
-            const int nb = train_loop_buffers();
-            SDT_REQUIRE(ws && ws_bytes >= nb * one, SDT_ERR_WORKSPACE, "sdt_train_round: workspace of %zu bytes needed, %zu given",
-                        nb * one, ws_bytes);
-            for (int k = 0; k < nb; ++k)
-                if (hipMemsetAsync(static_cast<char*>(ws) + k * one, 0, 256, st) != hipSuccess) {
-                    set_error("sdt_train_round: clearing a workspace header failed");
-                    return SDT_ERR_HIP;
-                }
+            // (a step workspace carries nothing from one step to the next, so partitions with different
+            // layouts may follow each other in the same buffer)
             rc = sdt_train_loop(&parts[j].graph, parts[j].X, parts[j].ldx, dtype, parts[j].labels, parts[j].seeds, batch,
                                 parts[j].n_steps, fanouts, &locals[j], seed, first_step, lr, losses_d + done, nullptr, ws,
                                 ws_bytes, stream, aux_streams, n_aux);

@@ -58,8 +58,7 @@ __global__ __launch_bounds__(TB) void k_gcn_norm(const int64_t* __restrict__ g_i
 }
 
 // row_ids (nullable): local row r lives at H[row_ids[r]] (aggregating straight out of the feature
-// matrix through the block's src_nodes); map_reset (nullable, with row_ids): the node map entry of
-// every frontier node met is set back to -1.
+// matrix through the block's src_nodes).
 template <int VE, int G>
 __global__ __launch_bounds__(TB) void k_gcn_aggregate_fwd(const int32_t* __restrict__ b_indptr,
                                                           const int32_t* __restrict__ cols, const int32_t* counts,
@@ -67,15 +66,13 @@ __global__ __launch_bounds__(TB) void k_gcn_aggregate_fwd(const int32_t* __restr
                                                           const int32_t* __restrict__ row_ids, int F,
                                                           const float* __restrict__ c, const float* __restrict__ s,
                                                           const float* __restrict__ selfw, float* __restrict__ A,
-                                                          int64_t lda, int32_t* map_reset, int32_t* stamp) {
-    if (stamp && blockIdx.x == 0 && threadIdx.x == 0) stamp[0] = STATE_MAGIC;   // this launch leaves the map clean
+                                                          int64_t lda) {
     const int n = counts[0];
     const int gl = threadIdx.x % G;
     const int ngrp = gridDim.x * (TB / G);
     for (int i = blockIdx.x * (TB / G) + threadIdx.x / G; i < n; i += ngrp) {
         const int e0 = b_indptr[i], e1 = b_indptr[i + 1];
         const int64_t own = row_ids ? row_ids[i] : i;
-        if (map_reset && gl == 0) map_reset[own] = -1;
         const float si = s[i], wi = selfw[i];
         // the last vector of a row whose width is not a multiple of VE is moved back to end with the row
         // (it overlaps its neighbour; both lanes compute and store the same values); F >= VE
@@ -92,11 +89,6 @@ __global__ __launch_bounds__(TB) void k_gcn_aggregate_fwd(const int32_t* __restr
                     const int col = (e + u < e1) ? cols[e + u] : -1;
                     w[u] = col >= 0 ? c[col] : 0.f;
                     r[u] = col < 0 ? -1 : (row_ids ? (int64_t)row_ids[col] : (int64_t)col);
-                }
-                if (map_reset && fn == gl * VE && gl == 0) {
-#pragma unroll
-                    for (int u = 0; u < U; ++u)
-                        if (r[u] >= 0) map_reset[r[u]] = -1;
                 }
                 float v[U][VE];
 #pragma unroll
@@ -221,15 +213,13 @@ inline int rows_grid(int64_t rows, int G) {
 }  // namespace
 
 int32_t gcn_aggregate_fwd(const sdt_block* blk, const float* H, int64_t ldh, bool through_src_nodes, int32_t F,
-                          const float* c, const float* s, const float* selfw, float* A, int64_t lda, int32_t* map_reset,
-                          int32_t* stamp, hipStream_t stm) {
+                          const float* c, const float* s, const float* selfw, float* A, int64_t lda, hipStream_t stm) {
     // the forward kernel moves its last vector back, so any dword-aligned fp32 row takes the widest vector that fits
     const int ve = F >= 4 ? 4 : F >= 2 ? 2 : 1;
     const int G = (F + ve - 1) / ve > 16 ? 64 : 16;
     SDT_GCN_DISPATCH(ve, G, hipLaunchKernelGGL((k_gcn_aggregate_fwd<VE, GG>), dim3(rows_grid(blk->cap_dst, GG)), dim3(TB),
                                                0, stm, blk->indptr, blk->cols, blk->counts, H, ldh,
-                                               through_src_nodes ? blk->src_nodes : nullptr, F, c, s, selfw, A, lda,
-                                               through_src_nodes ? map_reset : nullptr, through_src_nodes ? stamp : nullptr));
+                                               through_src_nodes ? blk->src_nodes : nullptr, F, c, s, selfw, A, lda));
     SDT_CHECK_LAUNCH("gcn_aggregate_fwd");
     return SDT_OK;
 }
@@ -262,7 +252,7 @@ extern "C" int32_t sdt_gcn_aggregate_fwd(const sdt_block* blk, const void* H, in
                     (!through_src_nodes || blk->src_nodes),
                 SDT_ERR_INVALID_ARG, "sdt_gcn_aggregate_fwd: null pointer");
     return gcn_aggregate_fwd(blk, static_cast<const float*>(H), ldh, through_src_nodes != 0, F, c, s, selfw,
-                             static_cast<float*>(A), lda, nullptr, nullptr, static_cast<hipStream_t>(stream));
+                             static_cast<float*>(A), lda, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int32_t sdt_gcn_aggregate_bwd(const sdt_block* blk, const void* dA, int64_t lda, const void* relu_of,

@@ -162,14 +162,16 @@ __device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 
 __device__ __forceinline__ int acc_col(int lane) { return lane & 31; }
 
 // Workgroup tile BM x BN, reduction depth BK per step, WM x WN wavefronts.
-template <int BM_, int BN_, int BK_, int WM_, int WN_>
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int NS_ = 2>
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
     static constexpr int NT = 64 * WM * WN;            // threads per workgroup
     static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     static constexpr int LDA_OC = BM + 4, LDB_OC = BN + 4;
     static constexpr int LD_KC = BK + 4;
-    static constexpr int NS = 2;  // register stages of the global-load prefetch (four were measured: no faster)
+    // register stages of the global-load prefetch (four were measured twice: no faster on the dense forward,
+    // and no faster on the short reductions of the small steps, K = 200 ... 512, either)
+    static constexpr int NS = NS_;
     static_assert(TM >= 1 && TN >= 1 && BK % 8 == 0, "tile shape");
 };
 

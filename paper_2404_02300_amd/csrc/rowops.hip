@@ -58,16 +58,13 @@ __device__ __forceinline__ void store_f32(T* p, const float in[VE]) {
 template <int VB, int G>
 __global__ __launch_bounds__(TB) void k_gather(const char* __restrict__ X, int64_t ldx_b, int row_b,
                                                const int32_t* __restrict__ idx, int n_cap, const int32_t* n_d,
-                                               char* __restrict__ out, int64_t ldo_b, int32_t* map_reset, int32_t* stamp,
-                                               int pad_b, char* __restrict__ pad2) {
+                                               char* __restrict__ out, int64_t ldo_b, int pad_b, char* __restrict__ pad2) {
     using raw_t = typename Raw<VB>::type;
     const int n = dev_count(n_cap, n_d);
-    if (stamp && blockIdx.x == 0 && threadIdx.x == 0) stamp[0] = STATE_MAGIC;   // this launch leaves the map clean
     const int gl = threadIdx.x % G;
     const int64_t ngrp = (int64_t)gridDim.x * (TB / G);
     for (int64_t j = (int64_t)blockIdx.x * (TB / G) + threadIdx.x / G; j < n; j += ngrp) {
         const int node = idx[j];
-        if (map_reset && gl == 0) map_reset[node] = -1;  // hand the frontier map back clean
         const char* src = X + (int64_t)node * ldx_b;
         char* dst = out + j * ldo_b;
         // the last vector of a row whose width is not a multiple of VB is moved back to end with the row
@@ -90,15 +87,13 @@ __global__ __launch_bounds__(TB) void k_gather(const char* __restrict__ X, int64
 // ---- mean aggregation forward ---------------------------------------------------
 // row_ids (nullable): the source row of column c is H[row_ids[c]] instead of H[c] -- used to
 // aggregate straight out of the partition's feature matrix through a block's src_nodes, so the
-// gathered copy of the non-destination frontier rows is never written.  map_reset (nullable):
-// map_reset[row_ids[c]] = -1 for every column met (hands the frontier map back clean).
+// gathered copy of the non-destination frontier rows is never written.
 template <typename T, int VE, int G, typename IP>
 __global__ __launch_bounds__(TB) void k_aggregate_fwd(const IP* __restrict__ indptr, const int32_t* __restrict__ cols,
                                                       int64_t n_cap, const int32_t* n_d, const T* __restrict__ H,
                                                       int64_t ldh, int F, T* __restrict__ A, int64_t lda,
-                                                      const int32_t* __restrict__ row_ids, int32_t* map_reset,
-                                                      int32_t* stamp, int64_t skip_longer_than) {
-    if (stamp && blockIdx.x == 0 && threadIdx.x == 0) stamp[0] = STATE_MAGIC;   // this launch leaves the map clean
+                                                      const int32_t* __restrict__ row_ids,
+                                                      int64_t skip_longer_than) {
     int64_t n = n_cap;
     if (n_d) n = *n_d < n_cap ? *n_d : n_cap;
     const int gl = threadIdx.x % G;
@@ -122,11 +117,6 @@ __global__ __launch_bounds__(TB) void k_aggregate_fwd(const IP* __restrict__ ind
 #pragma unroll
                     for (int u = 0; u < UNROLL; ++u)
                         if (c[u] >= 0) c[u] = row_ids[c[u]];
-                    if (map_reset && fn == gl * VE && gl == 0) {
-#pragma unroll
-                        for (int u = 0; u < UNROLL; ++u)
-                            if (c[u] >= 0) map_reset[c[u]] = -1;
-                    }
                 }
                 // the rows stay in their storage type until they are added (half the registers for bf16)
                 Vec<T, VE> v[UNROLL];
@@ -344,7 +334,7 @@ bool dispatch(int32_t dtype, int ve, int G, F32Fn&& f32, BF16Fn&& bf) {
 template <typename IP>
 int32_t launch_aggregate_fwd(const IP* indptr, const int32_t* cols, int64_t n_cap, const int32_t* n_d, const void* H,
                              int64_t ldh, int32_t F, int32_t dtype, void* A, int64_t lda, const int32_t* row_ids,
-                             int32_t* map_reset, int32_t* stamp, hipStream_t st) {
+                             hipStream_t st) {
     if (n_cap == 0 || F == 0) return SDT_OK;
     const size_t es = dtype_size(dtype);
     // (the hub kernel of the whole-graph form keeps whole vectors per row)
@@ -364,7 +354,7 @@ int32_t launch_aggregate_fwd(const IP* indptr, const int32_t* cols, int64_t n_ca
             grid = (int)(b > (1 << 24) ? (1 << 24) : b);
         }
         hipLaunchKernelGGL((k_aggregate_fwd<T, VE, GG, IP>), dim3(grid), dim3(TB), 0, st, indptr, cols, n_cap, n_d,
-                           static_cast<const T*>(H), ldh, F, static_cast<T*>(A), lda, row_ids, map_reset, stamp, long_rows);
+                           static_cast<const T*>(H), ldh, F, static_cast<T*>(A), lda, row_ids, long_rows);
         if (whole_graph)
             hipLaunchKernelGGL((k_aggregate_long<T, VE, IP>), dim3((int)((n_cap + LONG_TB - 1) / LONG_TB)), dim3(LONG_TB),
                                0, st, indptr, cols, n_cap, static_cast<const T*>(H), ldh, F, static_cast<T*>(A), lda,
@@ -385,8 +375,7 @@ using namespace sdt;
 
 namespace sdt {
 int32_t gather_rows(const void* X, int64_t ldx, int32_t F, int32_t dtype, const int32_t* idx, int32_t n_cap,
-                    const int32_t* n_d, void* out, int64_t ldo, int32_t* map_reset, int32_t* stamp, bool zero_pad,
-                    void* also_pad, hipStream_t st) {
+                    const int32_t* n_d, void* out, int64_t ldo, bool zero_pad, void* also_pad, hipStream_t st) {
     SDT_REQUIRE(dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_gather_features: unknown dtype %d", dtype);
     SDT_REQUIRE(F >= 0 && n_cap >= 0 && ldx >= F && ldo >= F, SDT_ERR_INVALID_ARG,
                 "sdt_gather_features: bad sizes F=%d n=%d ldx=%lld ldo=%lld", F, n_cap, (long long)ldx, (long long)ldo);
@@ -401,7 +390,7 @@ int32_t gather_rows(const void* X, int64_t ldx, int32_t F, int32_t dtype, const 
     const int64_t ldx_b = ldx * (int64_t)es, ldo_b = ldo * (int64_t)es;
 #define SDT_GATHER(VB, GG)                                                                                         \
     hipLaunchKernelGGL((k_gather<VB, GG>), dim3(grid_rows(n_cap, GG)), dim3(TB), 0, st, Xc, ldx_b, row_b, idx, n_cap, \
-                       n_d, oc, ldo_b, map_reset, stamp, zero_pad ? (int)ldo_b : 0, zero_pad ? static_cast<char*>(also_pad) : nullptr)
+                       n_d, oc, ldo_b, zero_pad ? (int)ldo_b : 0, zero_pad ? static_cast<char*>(also_pad) : nullptr)
 #define SDT_GATHER_G(VB)                    \
     switch (G) {                            \
         case 8: SDT_GATHER(VB, 8); break;   \
@@ -424,7 +413,7 @@ int32_t gather_rows(const void* X, int64_t ldx, int32_t F, int32_t dtype, const 
 
 extern "C" int32_t sdt_gather_features(const void* X, int64_t ldx, int32_t F, int32_t dtype, const int32_t* idx,
                                        int32_t n_cap, const int32_t* n_d, void* out, int64_t ldo, void* stream) {
-    return gather_rows(X, ldx, F, dtype, idx, n_cap, n_d, out, ldo, nullptr, nullptr, false, nullptr, static_cast<hipStream_t>(stream));
+    return gather_rows(X, ldx, F, dtype, idx, n_cap, n_d, out, ldo, false, nullptr, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int32_t sdt_sage_aggregate_fwd(const sdt_block* blk, const void* H, int64_t ldh, int32_t F, int32_t dtype,
@@ -437,12 +426,12 @@ extern "C" int32_t sdt_sage_aggregate_fwd(const sdt_block* blk, const void* H, i
     SDT_REQUIRE(blk->counts && blk->indptr && H && A && (blk->cols || blk->cap_nnz == 0), SDT_ERR_INVALID_ARG,
                 "sdt_sage_aggregate_fwd: null pointer");
     return launch_aggregate_fwd<int32_t>(blk->indptr, blk->cols, blk->cap_dst, blk->counts, H, ldh, F, dtype, A, lda,
-                                         nullptr, nullptr, nullptr, static_cast<hipStream_t>(stream));
+                                         nullptr, static_cast<hipStream_t>(stream));
 }
 
 namespace sdt {
 int32_t aggregate_gather_fwd(const sdt_block* blk, const void* X, int64_t ldx, int32_t F, int32_t dtype, void* A,
-                             int64_t lda, int32_t* map_reset, int32_t* stamp, hipStream_t st) {
+                             int64_t lda, hipStream_t st) {
     SDT_REQUIRE(blk, SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_gather_fwd: null block");
     SDT_REQUIRE(dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_gather_fwd: unknown dtype %d", dtype);
     SDT_REQUIRE(F >= 0 && blk->cap_dst >= 0 && ldx >= F && lda >= F, SDT_ERR_INVALID_ARG,
@@ -451,13 +440,13 @@ int32_t aggregate_gather_fwd(const sdt_block* blk, const void* X, int64_t ldx, i
     SDT_REQUIRE(blk->counts && blk->indptr && blk->src_nodes && X && A && (blk->cols || blk->cap_nnz == 0),
                 SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_gather_fwd: null pointer");
     return launch_aggregate_fwd<int32_t>(blk->indptr, blk->cols, blk->cap_dst, blk->counts, X, ldx, F, dtype, A, lda,
-                                         blk->src_nodes, map_reset, stamp, st);
+                                         blk->src_nodes, st);
 }
 }  // namespace sdt
 
 extern "C" int32_t sdt_sage_aggregate_gather_fwd(const sdt_block* blk, const void* X, int64_t ldx, int32_t F,
                                                  int32_t dtype, void* A, int64_t lda, void* stream) {
-    return aggregate_gather_fwd(blk, X, ldx, F, dtype, A, lda, nullptr, nullptr, static_cast<hipStream_t>(stream));
+    return aggregate_gather_fwd(blk, X, ldx, F, dtype, A, lda, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int32_t sdt_sage_aggregate_csr_fwd(const sdt_csr* g, const void* H, int64_t ldh, int32_t F, int32_t dtype,
@@ -469,7 +458,7 @@ extern "C" int32_t sdt_sage_aggregate_csr_fwd(const sdt_csr* g, const void* H, i
     if (g->n_nodes == 0 || F == 0) return SDT_OK;
     SDT_REQUIRE(g->indptr && g->indices && H && A, SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_csr_fwd: null pointer");
     return launch_aggregate_fwd<int64_t>(g->indptr, g->indices, g->n_nodes, nullptr, H, ldh, F, dtype, A, lda,
-                                         nullptr, nullptr, nullptr, static_cast<hipStream_t>(stream));
+                                         nullptr, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int32_t sdt_sage_aggregate_bwd(const sdt_block* blk, const void* dAgg, int64_t ldg, const void* dSelf,

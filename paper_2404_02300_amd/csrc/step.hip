@@ -372,15 +372,13 @@ void bind_buffers(const sdt_step_layout& lay, void* ws, size_t bytes, StepBuffer
 }
 
 // Phase 1 (needs no weights): sample from the seeds outwards, then gather the input features
-// of the outermost frontier.  The node -> local-id map carries over from layer to layer; the
-// gather hands it back clean for the next step that uses this workspace.
-int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds, uint32_t step, hipStream_t st,
-                    bool check_state = true) {
+// of the outermost frontier.  The frontier state (two bits per node, the node -> local-id map)
+// carries over from layer to layer and is rebuilt from nothing by every step.
+int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds, uint32_t step, hipStream_t st) {
     const sdt_step_layout& lay = c.lay;
     const int L = c.model->n_layers;
     const int32_t* d = c.model->dims;
     const int64_t N = c.graph->n_nodes;
-    int32_t* header = static_cast<int32_t*>(b.at(lay.header));
     SampleWs sw{};
     sample_state_carve(b.at(lay.state), N, &sw);
     int32_t rc;
@@ -389,26 +387,24 @@ int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds
     for (int l = L - 1; l >= 0; --l) {
         StageTimer tl(c.timing, c.slot, SDT_STAGE_SAMPLE, l, st);
         if (l == L - 1) {
-            // the state check is skipped when the caller knows this workspace's previous user was an
-            // earlier step of the same run (which left the map clean and the header stamped)
-            if (check_state) {
-                rc = sample_state_init(sw, N, header, st);
-                if (rc != SDT_OK) return rc;
-            }
-            rc = sample_seed_map(sw, seeds, c.batch, nullptr, header, N, st);
+            // every step starts from an empty frontier: the state words are cleared, whatever the
+            // workspace held (nothing in it is carried from step to step), then the seeds join
+            rc = sample_state_clear(sw, N, st);
+            if (rc != SDT_OK) return rc;
+            rc = sample_seed_map(sw, seeds, c.batch, nullptr, st);
             if (rc != SDT_OK) return rc;
         }
         Arena a(b.at(lay.scratch));
         sample_tmp_carve(a, N, lay.cap_dst[l], c.fanouts[l], &sw);
-        rc = sample_layer(*c.graph, dst, lay.cap_dst[l], n_d, c.fanouts[l], c.seed, step, (uint32_t)l, b.blk[l], sw, st,
-                          c.timing, c.slot);
+        // the nodes a layer adds are looked up in the map only by the layers sampled after it
+        rc = sample_layer(*c.graph, dst, lay.cap_dst[l], n_d, c.fanouts[l], c.seed, step, (uint32_t)l, b.blk[l], sw,
+                          /*write_map=*/l > 0, st, c.timing, c.slot);
         if (rc != SDT_OK) return rc;
         dst = b.blk[l].src_nodes;
         n_d = b.blk[l].counts + 1;
     }
     if (c.model->kind == SDT_MODEL_GCN) {
-        // normalisation vectors of every block, then layer 0's aggregation straight out of X (it also
-        // hands the frontier map back clean: every frontier node is a row or a column of block 0)
+        // normalisation vectors of every block, then layer 0's aggregation straight out of X
         for (int l = 0; l < L; ++l) {
             rc = sdt_gcn_norm(c.graph, &b.blk[l], b.gcn_c(lay, l), b.gcn_s(lay, l), b.gcn_self(lay, l), st);
             if (rc != SDT_OK) return rc;
@@ -416,27 +412,25 @@ int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds
         SDT_REQUIRE(lay.cap_dst[0] == 0 || aligned16(c.X), SDT_ERR_INVALID_ARG, "sdt_train_step: X must be 16-byte aligned");
         StageTimer tm(c.timing, c.slot, SDT_STAGE_AGG_FWD, 0, st);
         return gcn_aggregate_fwd(&b.blk[0], static_cast<const float*>(c.X), c.ldx, true, d[0], b.gcn_c(lay, 0),
-                                 b.gcn_s(lay, 0), b.gcn_self(lay, 0), static_cast<float*>(b.at(lay.A[0])), d[0], sw.map, header, st);
+                                 b.gcn_s(lay, 0), b.gcn_self(lay, 0), static_cast<float*>(b.at(lay.A[0])), d[0], st);
     }
     if (c.model->kind == SDT_MODEL_GAT) {
-        // every frontier row is projected, so every one is gathered (which also hands the whole map back clean)
+        // every frontier row is projected, so every one is gathered
         StageTimer tm(c.timing, c.slot, SDT_STAGE_GATHER, 0, st);
         return gather_rows(c.X, c.ldx, d[0], c.dtype, b.blk[0].src_nodes, lay.cap_src[0], b.blk[0].counts + 1, b.at(lay.H[0]),
-                           d[0], sw.map, header, false, nullptr, st);
+                           d[0], false, nullptr, st);
     }
     // Input features: only the destination prefix of the outermost frontier is copied (the
     // projection's "self" operand); the neighbour mean of layer 0 is taken straight out of X.
     // The copy also zeroes the row padding of H[0] and of A[0] (same rows, same stride).
-    // Both passes hand the frontier map back clean (prefix nodes here, the rest there); the second one,
-    // the last kernel of the step to touch the map, stamps the workspace header "clean" again.
     {
         StageTimer tm(c.timing, c.slot, SDT_STAGE_GATHER, 0, st);
         rc = gather_rows(c.X, c.ldx, d[0], c.dtype, b.blk[0].src_nodes, lay.cap_dst[0], b.blk[0].counts,
-                         b.at(lay.H[0]), (int64_t)lay.ld_in, sw.map, /*stamp=*/nullptr, /*zero_pad=*/true, /*also_pad=*/b.at(lay.A[0]), st);
+                         b.at(lay.H[0]), (int64_t)lay.ld_in, /*zero_pad=*/true, /*also_pad=*/b.at(lay.A[0]), st);
     }
     if (rc != SDT_OK) return rc;
     StageTimer tm(c.timing, c.slot, SDT_STAGE_AGG_FWD, 0, st);
-    return aggregate_gather_fwd(&b.blk[0], c.X, c.ldx, d[0], c.dtype, b.at(lay.A[0]), (int64_t)lay.ld_in, sw.map, header, st);
+    return aggregate_gather_fwd(&b.blk[0], c.X, c.ldx, d[0], c.dtype, b.at(lay.A[0]), (int64_t)lay.ld_in, st);
 }
 
 // Phase 2 of a GCN step.  The projection kernels take two operands of equal width; here they are
@@ -928,7 +922,7 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
         for (int i = 0; i < n_steps && rc == SDT_OK; ++i) {
             c.slot = slot_of(i);
             const StepBuffers& bi = buf[i % LOOP_BUFFERS];
-            rc = step_sample(c, bi, seeds + (int64_t)i * batch, first_step + (uint32_t)i, main_st, /*check_state=*/i < LOOP_BUFFERS);
+            rc = step_sample(c, bi, seeds + (int64_t)i * batch, first_step + (uint32_t)i, main_st);
             if (rc == SDT_OK)
                 rc = step_compute(c, bi, seeds + (int64_t)i * batch, first_step + (uint32_t)i, losses_d + i, main_st);
         }
@@ -959,7 +953,7 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
                 for (int i = group_begin(g); i < group_end(g); ++i) {
                     ca.slot = slot_of(i);
                     const int32_t r = step_sample(ca, buf[i % LOOP_BUFFERS], seeds + (int64_t)i * batch, first_step + (uint32_t)i,
-                                                  aux_st, /*check_state=*/i < LOOP_BUFFERS);
+                                                  aux_st);
                     if (r != SDT_OK) {
                         aux_rc[a] = r;
                         aux_msg[a] = sdt_last_error();

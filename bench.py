@@ -121,6 +121,9 @@ def main():
     if args.workload in ("sampling", "gather"):
         args.steps = args.steps or 20
         return bench_stage_at_scale(args, wl)
+    # the auxiliary streams are created once and shared by every workload of the run: a process has four
+    # hardware queues, and a fifth stream would share one with the main stream
+    args.aux_streams = None if args.serial else [torch.cuda.Stream() for _ in range(max(1, min(3, args.aux)))]
     out = bench_step(args, args.workload, full=True)
     also = [w for w in args.also.split(",") if w and w != "none"]
     if args.workload == "dense" and args.model == "sage" and also:
@@ -193,7 +196,7 @@ def bench_step(args, workload, full):
     loss = torch.zeros(1, dtype=torch.float32, device="cuda")
     losses = torch.zeros(Wm + K, dtype=torch.float32, device="cuda")
     seeds_all = torch.from_numpy(np.stack([inst.batch(s) for s in range(Wm + K)])).cuda()
-    aux = None if args.serial else [torch.cuda.Stream() for _ in range(max(1, min(3, args.aux)))]
+    aux = args.aux_streams
     L = len(wl.fanouts)
     es = 2 if wl.bf16 else 4
 

@@ -343,8 +343,9 @@ __global__ __launch_bounds__(TB) void k_front_apply(const int32_t* __restrict__ 
 // layer added has its mark set: its local id is its word's first new id plus the number of marked nodes
 // below it in the word (two small arrays that stay in the caches); any other sampled node was in the
 // frontier before and has its id in the map.
-// G lanes per destination row, as in the sampling kernel: lane t of a group handles the row's t-th sampled edge.
-template <int G>
+// G lanes per destination row, as in the sampling kernel: lane t of a group handles the row's t-th sampled
+// edge; RU rows per group are in flight at once (each edge is a chain of three dependent loads).
+template <int G, int RU>
 __global__ __launch_bounds__(TB) void k_relabel(const int32_t* __restrict__ e_pad, const int32_t* __restrict__ m,
                                                 const int32_t* __restrict__ b_indptr, int n_cap, const int32_t* n_d,
                                                 int fanout, const uint32_t* __restrict__ bits,
@@ -354,18 +355,35 @@ __global__ __launch_bounds__(TB) void k_relabel(const int32_t* __restrict__ e_pa
     const int n = dev_count(n_cap, n_d);
     const uint32_t n_src = (uint32_t)counts[1];
     const int t = threadIdx.x % G;
-    const int rows_per_block = TB / G;
-    for (int i = blockIdx.x * rows_per_block + threadIdx.x / G; i < n; i += gridDim.x * rows_per_block) {
-        if (t < m[i]) {
-            const int g = e_pad[(int64_t)i * fanout + t];
-            const uint32_t w = bits[g >> 4];
-            const int sh = (g & 15) * 2;
-            int c = ((w >> (sh + 1)) & 1u) ? wp[g >> 4] + __popc(w & M_PLANE & ((1u << sh) - 1u)) : map[g];
+    constexpr int GROUPS = TB / G;
+    for (int i0 = (blockIdx.x * GROUPS + threadIdx.x / G) * RU; i0 < n; i0 += gridDim.x * GROUPS * RU) {
+        bool act[RU];
+        int g[RU], at[RU];
+#pragma unroll
+        for (int r = 0; r < RU; ++r) act[r] = i0 + r < n && t < m[i0 + r];
+#pragma unroll
+        for (int r = 0; r < RU; ++r) {
+            g[r] = act[r] ? e_pad[(int64_t)(i0 + r) * fanout + t] : 0;
+            at[r] = act[r] ? b_indptr[i0 + r] + t : 0;
+        }
+        uint32_t w[RU];
+#pragma unroll
+        for (int r = 0; r < RU; ++r) w[r] = act[r] ? bits[g[r] >> 4] : 0u;
+        int c[RU];
+#pragma unroll
+        for (int r = 0; r < RU; ++r) {
+            const int sh = (g[r] & 15) * 2;
+            const bool added = (w[r] >> (sh + 1)) & 1u;
+            c[r] = !act[r] ? 0 : added ? wp[g[r] >> 4] + __popc(w[r] & M_PLANE & ((1u << sh) - 1u)) : map[g[r]];
+        }
+#pragma unroll
+        for (int r = 0; r < RU; ++r) {
+            if (!act[r]) continue;
             // always a row of the frontier -- unless someone wrote over the step's state while it ran; even
             // then the kernels that consume the block stay inside their buffers
-            if ((uint32_t)c >= n_src) c = 0;
-            cols[b_indptr[i] + t] = c;
-            if (hist) atomicAdd(&hist[c], 1);
+            if ((uint32_t)c[r] >= n_src) c[r] = 0;
+            cols[at[r]] = c[r];
+            if (hist) atomicAdd(&hist[c[r]], 1);
         }
     }
 }
@@ -797,12 +815,13 @@ int32_t sample_layer(const sdt_csr& g, const int32_t* dst_nodes, int32_t n_dst_c
     }
     if (any) {
         StageTimer tm(timing, slot, SDT_STAGE_RELABEL, tl, st);
-#define SDT_RELABEL(G)                                                                                                \
-    hipLaunchKernelGGL(k_relabel<G>, dim3(grid_for(n_dst_cap, TB / G, 1 << 16)), dim3(TB), 0, st, ws.e_pad, ws.m,    \
-                       out.indptr, n_dst_cap, n_dst_d, fanout, ws.bits, ws.wp, ws.map, out.counts, out.cols, hist)
-        if (fanout <= 16) SDT_RELABEL(16);
-        else if (fanout <= 32) SDT_RELABEL(32);
-        else SDT_RELABEL(64);
+#define SDT_RELABEL(G, RU)                                                                                            \
+    hipLaunchKernelGGL((k_relabel<G, RU>), dim3(grid_for(n_dst_cap, (TB / G) * RU, 1 << 16)), dim3(TB), 0, st, ws.e_pad, \
+                       ws.m, out.indptr, n_dst_cap, n_dst_d, fanout, ws.bits, ws.wp, ws.map, out.counts, out.cols, hist)
+        const bool many_rows = n_dst_cap >= (1 << 16);
+        if (fanout <= 16) { if (many_rows) SDT_RELABEL(16, 4); else SDT_RELABEL(16, 1); }
+        else if (fanout <= 32) { if (many_rows) SDT_RELABEL(32, 4); else SDT_RELABEL(32, 1); }
+        else { if (many_rows) SDT_RELABEL(64, 4); else SDT_RELABEL(64, 1); }
 #undef SDT_RELABEL
         SDT_CHECK_LAUNCH("relabel");
     }

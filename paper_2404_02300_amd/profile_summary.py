@@ -100,18 +100,18 @@ def read_counter(d: str):
 
 
 def calibrate(counter: dict, what: str) -> float:
-    """Bytes per count, from the plain 1 GiB device copy of `bench.py --calibrate-copy` (the
-    dispatch with the largest count among the library-foreign kernels)."""
+    """Bytes per count, from the plain 1 GiB device copy of `bench.py --calibrate-copy`: the runtime's
+    buffer-copy kernel (the largest of its dispatches; the small ones are host uploads of a few bytes)."""
     best = 0.0
     for k, v in counter.items():
-        if not is_ours(k):
+        if k.startswith("__amd_rocclr_copyBuffer"):
             best = max(best, max(v))
     if best <= 0:
         raise ValueError(f"{what}: no calibration copy found (run bench.py with --calibrate-copy)")
     per = GIB / best
     # the copy moves exactly 1 GiB each way; the factor must be a whole number of KiB within 1 %
     kib = per / 1024.0
-    if abs(kib - round(kib)) > 0.01 * max(1.0, round(kib)):
+    if kib < 0.99 or abs(kib - round(kib)) > 0.01 * round(kib):
         raise ValueError(f"{what}: calibration gives {kib:.3f} KiB per count, not a whole number")
     return float(round(kib)) * 1024.0
 

@@ -313,16 +313,16 @@ def bench_step(args, workload, full):
                         "bwd_input": "k_linear_bwd_input"}[kind]
         if kind == "sample":      # 16 B of row offsets per destination, 4 B read + 4 B written per sampled edge
             return "hbm", n_dst * 16 + nnz * 8, "k_sample_rows + frontier scan + relabel (+ transposed block)"
-        if kind == "sample_rows":
-            return "hbm", n_dst * 16 + nnz * 8, "k_sample_rows"
-        if kind == "front_scan":      # the frontier bitmap and the per-row counts, read once
-            return "hbm", N / 8 + n_dst * 4, "k_front_partials"
+        if kind == "sample_rows":     # + one mark byte per sampled edge
+            return "hbm", n_dst * 16 + nnz * 9, "k_sample_rows"
+        if kind == "front_scan":      # mark bytes and state bits of every node, and the per-row counts, read once
+            return "hbm", N * 1.25 + n_dst * 4, "k_front_partials"
         if kind == "front_apply":     # the same again, plus row offsets, the new frontier ids and their map entries
-            return "hbm", N / 8 + n_dst * 12 + (n_src - n_dst) * 8, "k_front_apply"
-        if kind == "relabel":         # global id in, map entry in, local id out (+ a histogram count per edge)
+            return "hbm", N * 1.25 + n_dst * 12 + (n_src - n_dst) * 8, "k_front_apply"
+        if kind == "relabel":         # global id in, state word and rank (or map entry) in, local id out
             return "hbm", nnz * 16, "k_relabel"
         if kind == "transpose":       # row offsets and column ids in, source offsets and destination rows out
-            return "hbm", nnz * 8 + n_dst * 4 + n_src * 8, "k_transpose_small" if lay.cap_nnz[l] <= (1 << 14) else \
+            return "hbm", nnz * 8 + n_dst * 4 + n_src * 8, "k_transpose_parts" if lay.cap_nnz[l] <= (1 << 14) else \
                    "k_scan_partials + k_scan_apply + k_transpose_fill + k_sort_short + k_sort_long"
         if kind == "update":          # every layer's partial products read once, weights and gradients written
             return "hbm", float(sum(wf * d[j] * d[j + 1] * 4 * 8 for j in range(L))), "k_reduce_partials"

@@ -169,8 +169,9 @@ struct Tile {
     static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     static constexpr int LDA_OC = BM + 4, LDB_OC = BN + 4;
     static constexpr int LD_KC = BK + 4;
-    // register stages of the global-load prefetch (four were measured twice: no faster on the dense forward,
-    // and no faster on the short reductions of the small steps, K = 200 ... 512, either)
+    // register stages of the global-load prefetch (four were measured three times: no faster on the dense
+    // forward and weight gradient alone, nor inside the loop with the aggregation running beside them
+    // (3 340 -> 3 310 ... 3 370 steps/s), nor on the short reductions of the small steps, K = 200 ... 512)
     static constexpr int NS = NS_;
     static_assert(TM >= 1 && TN >= 1 && BK % 8 == 0, "tile shape");
 };

@@ -11,6 +11,8 @@
 // independent of the launch shape.
 #include "common.h"
 
+#include <type_traits>
+
 namespace sdt {
 namespace {
 
@@ -135,6 +137,79 @@ __global__ __launch_bounds__(TB) void k_aggregate_fwd(const IP* __restrict__ ind
                 for (int q = 0; q < VE; ++q) acc[q] = acc[q] / m;
             }
             store_f32<T, VE>(A + i * lda + f0, acc);
+        }
+    }
+}
+
+// The same for rows wider than one pass of the lane group (F > G * VE): the NP passes over the features run
+// side by side, so a lane has NP * UNROLL row loads in flight instead of UNROLL and a launch needs a
+// fraction of the wavefronts to keep the memory system busy.  Sums in edge order, as above: same bits.
+// Dense workload (602 floats, NP = 3), layer-0 aggregation alone: 108 -> 98 us (6.5 TB/s of gather-side bytes).
+//
+// BACKGROUND_BLOCKS: inside a training loop this kernel runs on an auxiliary stream beside the projections of
+// the step before.  Launched over every CU's wave slots (2048 workgroups) it and they take turns: the loop's
+// step lasted the sum of its large kernels.  With 1.5 workgroups per CU it leaves the slots to the matrix
+// kernels and streams in the background: it takes longer itself (155 against 106 us) and the step gets shorter
+// (dense loop 3 360 -> 3 890 steps/s; 256 workgroups 3 850, 192: 3 830, 128: 3 650, 512: 3 690, 1024: 3 530).
+constexpr int BACKGROUND_BLOCKS = 384;
+template <typename T, int VE, int G, int NP>
+__global__ __launch_bounds__(TB) void k_aggregate_fwd_wide(const int32_t* __restrict__ indptr, const int32_t* __restrict__ cols,
+                                                           int64_t n_cap, const int32_t* n_d, const T* __restrict__ H,
+                                                           int64_t ldh, int F, T* __restrict__ A, int64_t lda,
+                                                           const int32_t* __restrict__ row_ids) {
+    int64_t n = n_cap;
+    if (n_d) n = *n_d < n_cap ? *n_d : n_cap;
+    const int gl = threadIdx.x % G;
+    const int64_t ngrp = (int64_t)gridDim.x * (TB / G);
+    int f0[NP];
+    bool on[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int fn = gl * VE + p * G * VE;
+        on[p] = fn < F;
+        f0[p] = min(fn, F - VE);
+    }
+    for (int64_t i = (int64_t)blockIdx.x * (TB / G) + threadIdx.x / G; i < n; i += ngrp) {
+        const int e0 = indptr[i], e1 = indptr[i + 1];
+        const float m = (float)(e1 - e0);
+        float acc[NP][VE];
+#pragma unroll
+        for (int p = 0; p < NP; ++p)
+#pragma unroll
+            for (int q = 0; q < VE; ++q) acc[p][q] = 0.f;
+        for (int e = e0; e < e1; e += UNROLL) {
+            int c[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) c[u] = (e + u < e1) ? cols[e + u] : -1;
+            if (row_ids) {
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u)
+                    if (c[u] >= 0) c[u] = row_ids[c[u]];
+            }
+            Vec<T, VE> v[NP][UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+                for (int p = 0; p < NP; ++p) {
+                    v[p][u].raw = typename Vec<T, VE>::raw_t{};
+                    if (c[u] >= 0 && on[p])
+                        v[p][u].raw = *reinterpret_cast<const typename Vec<T, VE>::raw_t*>(H + (int64_t)c[u] * ldh + f0[p]);
+                }
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+                    for (int q = 0; q < VE; ++q) acc[p][q] += to_f32<T>(v[p][u].e[q]);
+        }
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            if (!on[p]) continue;
+            if (e1 > e0) {
+#pragma unroll
+                for (int q = 0; q < VE; ++q) acc[p][q] = acc[p][q] / m;
+            }
+            store_f32<T, VE>(A + i * lda + f0[p], acc[p]);
         }
     }
 }
@@ -334,7 +409,7 @@ bool dispatch(int32_t dtype, int ve, int G, F32Fn&& f32, BF16Fn&& bf) {
 template <typename IP>
 int32_t launch_aggregate_fwd(const IP* indptr, const int32_t* cols, int64_t n_cap, const int32_t* n_d, const void* H,
                              int64_t ldh, int32_t F, int32_t dtype, void* A, int64_t lda, const int32_t* row_ids,
-                             hipStream_t st) {
+                             int max_blocks, hipStream_t st) {
     if (n_cap == 0 || F == 0) return SDT_OK;
     const size_t es = dtype_size(dtype);
     // (the hub kernel of the whole-graph form keeps whole vectors per row)
@@ -349,6 +424,20 @@ int32_t launch_aggregate_fwd(const IP* indptr, const int32_t* cols, int64_t n_ca
         using T = decltype(t);
         constexpr int VE = decltype(vec)::value, GG = decltype(grp)::value;
         int grid = grid_rows(n_cap, GG);
+        if constexpr (!whole_graph && GG == 64 && VE * sizeof(T) == 16) {
+            // rows wider than one pass of the lane group: the passes run side by side (see k_aggregate_fwd_wide)
+            const int np = ceil_div(ceil_div(F, VE), GG);
+            if (np >= 2 && np <= 4) {
+                if (max_blocks > 0 && grid > max_blocks) grid = max_blocks;
+                const int32_t* ip = reinterpret_cast<const int32_t*>(indptr);
+#define SDT_WIDE(NP)                                                                                                    \
+    hipLaunchKernelGGL((k_aggregate_fwd_wide<T, VE, GG, NP>), dim3(grid), dim3(TB), 0, st, ip, cols, n_cap, n_d,        \
+                       static_cast<const T*>(H), ldh, F, static_cast<T*>(A), lda, row_ids)
+                if (np == 2) SDT_WIDE(2); else if (np == 3) SDT_WIDE(3); else SDT_WIDE(4);
+#undef SDT_WIDE
+                return;
+            }
+        }
         if (whole_graph) {
             const int64_t b = (n_cap + (TB / GG) - 1) / (TB / GG);
             grid = (int)(b > (1 << 24) ? (1 << 24) : b);
@@ -426,12 +515,12 @@ extern "C" int32_t sdt_sage_aggregate_fwd(const sdt_block* blk, const void* H, i
     SDT_REQUIRE(blk->counts && blk->indptr && H && A && (blk->cols || blk->cap_nnz == 0), SDT_ERR_INVALID_ARG,
                 "sdt_sage_aggregate_fwd: null pointer");
     return launch_aggregate_fwd<int32_t>(blk->indptr, blk->cols, blk->cap_dst, blk->counts, H, ldh, F, dtype, A, lda,
-                                         nullptr, static_cast<hipStream_t>(stream));
+                                         nullptr, 0, static_cast<hipStream_t>(stream));
 }
 
 namespace sdt {
 int32_t aggregate_gather_fwd(const sdt_block* blk, const void* X, int64_t ldx, int32_t F, int32_t dtype, void* A,
-                             int64_t lda, hipStream_t st) {
+                             int64_t lda, bool background, hipStream_t st) {
     SDT_REQUIRE(blk, SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_gather_fwd: null block");
     SDT_REQUIRE(dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_gather_fwd: unknown dtype %d", dtype);
     SDT_REQUIRE(F >= 0 && blk->cap_dst >= 0 && ldx >= F && lda >= F, SDT_ERR_INVALID_ARG,
@@ -440,13 +529,13 @@ int32_t aggregate_gather_fwd(const sdt_block* blk, const void* X, int64_t ldx, i
     SDT_REQUIRE(blk->counts && blk->indptr && blk->src_nodes && X && A && (blk->cols || blk->cap_nnz == 0),
                 SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_gather_fwd: null pointer");
     return launch_aggregate_fwd<int32_t>(blk->indptr, blk->cols, blk->cap_dst, blk->counts, X, ldx, F, dtype, A, lda,
-                                         blk->src_nodes, st);
+                                         blk->src_nodes, background ? BACKGROUND_BLOCKS : 0, st);
 }
 }  // namespace sdt
 
 extern "C" int32_t sdt_sage_aggregate_gather_fwd(const sdt_block* blk, const void* X, int64_t ldx, int32_t F,
                                                  int32_t dtype, void* A, int64_t lda, void* stream) {
-    return aggregate_gather_fwd(blk, X, ldx, F, dtype, A, lda, static_cast<hipStream_t>(stream));
+    return aggregate_gather_fwd(blk, X, ldx, F, dtype, A, lda, false, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int32_t sdt_sage_aggregate_csr_fwd(const sdt_csr* g, const void* H, int64_t ldh, int32_t F, int32_t dtype,
@@ -458,7 +547,7 @@ extern "C" int32_t sdt_sage_aggregate_csr_fwd(const sdt_csr* g, const void* H, i
     if (g->n_nodes == 0 || F == 0) return SDT_OK;
     SDT_REQUIRE(g->indptr && g->indices && H && A, SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_csr_fwd: null pointer");
     return launch_aggregate_fwd<int64_t>(g->indptr, g->indices, g->n_nodes, nullptr, H, ldh, F, dtype, A, lda,
-                                         nullptr, static_cast<hipStream_t>(stream));
+                                         nullptr, 0, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int32_t sdt_sage_aggregate_bwd(const sdt_block* blk, const void* dAgg, int64_t ldg, const void* dSelf,

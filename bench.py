@@ -96,6 +96,9 @@ def main():
     ap.add_argument("--aux", type=int, default=2, help="auxiliary streams the sampling phase alternates between")
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="the oracle is timed on whole steps until this many seconds have passed (at least one step)")
+    ap.add_argument("--roofline-stage", default=None,
+                    help="kernel-level stage to time inside the loop instead of the longest one, as kind:layer "
+                         "(e.g. linear_fwd:0, bwd_weight:0); for diagnosis")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run one plain 1 GiB device copy (a reference dispatch for rocprofv3 --pmc runs)")
     args = ap.parse_args()
@@ -248,6 +251,10 @@ def bench_step(args, workload, full):
     run_loop(0, Wm)
     pre_ms, _, _ = staged_pass(0, min(5, Wm + K), min(5, Wm + K), False)
     dominant = max((k for k in pre_ms if k in kernels), key=pre_ms.get)   # the longest single launch of a step
+    if args.roofline_stage and full:
+        kind, layer = args.roofline_stage.split(":")
+        dominant = (kind, int(layer))
+        assert dominant in pre_ms, f"stage {dominant} did not run; stages: {sorted(pre_ms)}"
 
     # one untimed pass of the same K steps first: a short loop after an idle stretch (graph generation, the
     # host oracle of an earlier workload) would otherwise be timed while the clocks are still coming up

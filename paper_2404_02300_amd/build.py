@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsdt.so")
-SOURCES = ["sample.hip", "rowops.hip", "gcn.hip", "gat.hip", "linear.hip", "linear_bf16.hip", "head.hip", "loss.hip", "step.hip", "extras.hip"]
+SOURCES = ["sample.hip", "rowops.hip", "gcn.hip", "gat.hip", "linear.hip", "linear_bf16.hip", "linear_x3.hip", "head.hip", "loss.hip", "step.hip", "extras.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed-fp32 instruction selection is switched off for every kernel of this library

@@ -249,6 +249,17 @@ int32_t linear_fwd(const void* Hself, int64_t ldh, const void* A, int64_t lda, i
                    int32_t in, int32_t out, const float* W, const float* b, int32_t relu, int32_t dtype, void* Y,
                    int64_t ldy, int32_t y_dtype, bool rows_padded, hipStream_t st);
 
+// fp32 projection through exact three-way bf16 splits on the bf16 matrix cores (linear_x3.hip): forward of layers
+// with few row tiles, a wide output and a long reduction.  wanted: the shape is one this path is for (then the
+// workspace query is non-zero); ok: the operands meet its alignment and zero-padding requirements.
+bool x3_fwd_wanted(int32_t n_cap, int32_t in, int32_t out);
+size_t x3_fwd_workspace_bytes(int32_t n_cap, int32_t in, int32_t out);
+bool x3_fwd_ok(const void* Hself, int64_t ldh, const void* A, int64_t lda, int32_t in, bool rows_padded, const void* Y,
+               int64_t ldy);
+int32_t linear_fwd_x3(const float* Hself, int64_t ldh, const float* A, int64_t lda, int32_t n_cap, const int32_t* n_d,
+                      int32_t in, int32_t out, const float* W, const float* b, int32_t relu, float* Y, int64_t ldy,
+                      void* ws, size_t ws_bytes, hipStream_t st);
+
 // bf16 matrix-core path (linear_bf16.hip).  Per layer the image region holds Wt = bf16 [out][2 in]
 // followed (256-byte aligned) by Wb = bf16 [2 in][bf16_ldb(out)], layers back to back.
 int32_t bf16_ldb(int32_t out);

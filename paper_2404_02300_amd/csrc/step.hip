@@ -40,6 +40,9 @@ inline int32_t operand_width(const sdt_model* m, int l) { return m->kind != SDT_
 // scratch of one layer's projection backward (split partials of dW/db, or the fused head's)
 size_t bwd_scratch_bytes(int32_t batch, int32_t cap_dst, int32_t in, int32_t out, bool last) {
     size_t lb = sdt_linear_bwd_workspace_bytes(cap_dst, in, out);
+    // the forward of the same layer may borrow the region first (partial tiles of the split-bf16 projection)
+    const size_t fb = last ? 0 : x3_fwd_workspace_bytes(cap_dst, in, out);
+    if (fb > lb) lb = fb;
     if (last && head_supported(in, out)) {
         const size_t hb = head_workspace_bytes(batch, in, out);
         if (hb > lb) lb = hb;
@@ -689,6 +692,14 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
             rc = linear_fwd_bf16(b.at(lay.H[l]), ldx(l), b.at(lay.A[l]), ldx(l), lay.cap_dst[l], b.blk[l].counts, d[l],
                                  d[l + 1], wt[l], model->b[l], last ? 0 : 1, b.at(lay.H[l + 1]), d[l + 1],
                                  last ? SDT_F32 : dtype, st);
+        else if (dtype == SDT_F32 && !last && x3_fwd_wanted(lay.cap_dst[l], d[l], d[l + 1]) &&
+                 x3_fwd_ok(b.at(lay.H[l]), ldx(l), b.at(lay.A[l]), ldx(l), d[l], /*rows_padded=*/l == 0, b.at(lay.H[l + 1]),
+                           d[l + 1]))
+            // few row tiles, wide output, long reduction: exact bf16 triple splits on the bf16 matrix cores; the
+            // layer's backward scratch is free until the backward reaches this layer
+            rc = linear_fwd_x3(static_cast<const float*>(b.at(lay.H[l])), ldx(l), static_cast<const float*>(b.at(lay.A[l])),
+                               ldx(l), lay.cap_dst[l], b.blk[l].counts, d[l], d[l + 1], model->W[l], model->b[l], 1,
+                               static_cast<float*>(b.at(lay.H[l + 1])), d[l + 1], b.at(scr_off[l]), scr_len[l], st);
         else
             rc = linear_fwd(b.at(lay.H[l]), ldx(l), b.at(lay.A[l]), ldx(l), lay.cap_dst[l], b.blk[l].counts, d[l],
                             d[l + 1], model->W[l], model->b[l], last ? 0 : 1, dtype, b.at(lay.H[l + 1]),

@@ -519,7 +519,6 @@ extern "C" int32_t sdt_sage_aggregate_fwd(const sdt_block* blk, const void* H, i
 }
 
 namespace sdt {
-static int lab_blocks() { static int v = -2; if (v == -2) { const char* e = getenv("SDT_LAB_AGG"); v = e ? atoi(e) : BACKGROUND_BLOCKS; } return v; }   // LAB
 int32_t aggregate_gather_fwd(const sdt_block* blk, const void* X, int64_t ldx, int32_t F, int32_t dtype, void* A,
                              int64_t lda, bool background, hipStream_t st) {
     SDT_REQUIRE(blk, SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_gather_fwd: null block");
@@ -530,7 +529,7 @@ int32_t aggregate_gather_fwd(const sdt_block* blk, const void* X, int64_t ldx, i
     SDT_REQUIRE(blk->counts && blk->indptr && blk->src_nodes && X && A && (blk->cols || blk->cap_nnz == 0),
                 SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_gather_fwd: null pointer");
     return launch_aggregate_fwd<int32_t>(blk->indptr, blk->cols, blk->cap_dst, blk->counts, X, ldx, F, dtype, A, lda,
-                                         blk->src_nodes, background ? lab_blocks() : 0, st);
+                                         blk->src_nodes, background ? BACKGROUND_BLOCKS : 0, st);
 }
 }  // namespace sdt
 

@@ -214,6 +214,7 @@ struct BwdExtras {
     PendingReduce* defer = nullptr;  // if set, the reduction is described here instead of launched
     const void* Wb = nullptr;  // bf16 image of W for the input gradient on the bf16 matrix path (or null)
     bool rows_padded = false;  // every row of Hself and A is zero-padded up to its stride (see linear_fwd)
+    bool x3 = false;           // fp32 layers of a suitable shape: weight gradient through bf16 triple splits (linear_x3.hip)
     float* W_upd = nullptr;
     float* b_upd = nullptr;
     float lr = 0.f;
@@ -259,6 +260,15 @@ bool x3_fwd_ok(const void* Hself, int64_t ldh, const void* A, int64_t lda, int32
 int32_t linear_fwd_x3(const float* Hself, int64_t ldh, const float* A, int64_t lda, int32_t n_cap, const int32_t* n_d,
                       int32_t in, int32_t out, const float* W, const float* b, int32_t relu, float* Y, int64_t ldy,
                       void* ws, size_t ws_bytes, hipStream_t st);
+
+// ... and the weight gradient of such layers (partials in the layout reduce_all expects; no alignment requirement)
+bool x3_dw_wanted(int32_t n_cap, int32_t in, int32_t out);
+int32_t x3_dw_splits(int32_t n_cap, int32_t in);
+int32_t linear_bwd_weight_x3(const float* Hself, int64_t ldh, const float* A, int64_t lda, const float* dY, int64_t lddy,
+                             int32_t n_cap, const int32_t* n_d, int32_t in, int32_t out, int32_t splits, float* P, float* Q,
+                             hipStream_t st);
+// workspace of linear_bwd when BwdExtras::x3 is set (sdt_linear_bwd_workspace_bytes otherwise)
+size_t linear_bwd_workspace_bytes_x3(int32_t n_cap, int32_t in, int32_t out);
 
 // bf16 matrix-core path (linear_bf16.hip).  Per layer the image region holds Wt = bf16 [out][2 in]
 // followed (256-byte aligned) by Wb = bf16 [2 in][bf16_ldb(out)], layers back to back.

@@ -731,6 +731,10 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Hself, int64_t ldh, co
     StageTimer tw(ex.timing, ex.slot, SDT_STAGE_BWD_WEIGHT, ex.layer, st);
     if (ex.Wb && sizeof(TH) == 2 && bf16_mfma_bwd_weight_ok(Hself, ldh, A, lda, dY, lddy, dy_code, in, out)) {
         (void)linear_bwd_weight_bf16(Hself, ldh, A, lda, dY, lddy, dy_code, n_cap, n_d, in, out, splits, P, Q, st);
+    } else if (ex.x3 && sizeof(TH) == 4 && sizeof(TD) == 4 && x3_dw_wanted(n_cap, in, out)) {
+        // (the caller's workspace was sized for this path's row ranges: bwd_ws with the same flag)
+        (void)linear_bwd_weight_x3(static_cast<const float*>(Hself), ldh, static_cast<const float*>(A), lda,
+                                   reinterpret_cast<const float*>(dYt), lddy, n_cap, n_d, in, out, splits, P, Q, st);
     } else {
         using TL = TileW;
         dim3 grid(ceil_div(out, TL::BN), ceil_div(in, TL::BM), 2 * splits);
@@ -877,9 +881,9 @@ struct BwdWs {
     int splits;
     size_t p_off, q_off, m_off, total;
 };
-BwdWs bwd_ws(int32_t n_cap, int32_t in, int32_t out) {
+BwdWs bwd_ws(int32_t n_cap, int32_t in, int32_t out, bool x3 = false) {
     BwdWs w;
-    w.splits = weight_splits(n_cap, in, out, TileW::BM, TileW::BN);
+    w.splits = x3 && x3_dw_wanted(n_cap, in, out) ? x3_dw_splits(n_cap, in) : weight_splits(n_cap, in, out, TileW::BM, TileW::BN);
     w.p_off = 0;
     w.q_off = align_up((size_t)w.splits * 2 * in * out * sizeof(float), 256);
     w.m_off = w.q_off + align_up((size_t)w.splits * out * sizeof(float), 256);
@@ -891,6 +895,11 @@ BwdWs bwd_ws(int32_t n_cap, int32_t in, int32_t out) {
 extern "C" size_t sdt_linear_bwd_workspace_bytes(int32_t n_cap, int32_t in, int32_t out) {
     if (n_cap < 0 || in <= 0 || out <= 0) return 0;
     return bwd_ws(n_cap, in, out).total;
+}
+
+size_t sdt::linear_bwd_workspace_bytes_x3(int32_t n_cap, int32_t in, int32_t out) {
+    if (n_cap < 0 || in <= 0 || out <= 0) return 0;
+    return bwd_ws(n_cap, in, out, true).total;
 }
 
 namespace sdt {
@@ -938,7 +947,7 @@ int32_t linear_bwd(const void* dY, int64_t lddy, int32_t dy_dtype, const void* Y
                 "sdt_sage_linear_bwd: pass both input gradients (ldi >= in) or neither");
     SDT_REQUIRE(!relu || (Y && ldy >= out && dy_dtype == dtype), SDT_ERR_INVALID_ARG,
                 "sdt_sage_linear_bwd: relu needs Y in the dtype of dY");
-    const BwdWs w = bwd_ws(n_cap, in, out);
+    const BwdWs w = bwd_ws(n_cap, in, out, ex.x3 && dtype == SDT_F32 && dy_dtype == SDT_F32);
     SDT_REQUIRE(ws && ws_bytes >= w.total && aligned16(ws), SDT_ERR_WORKSPACE,
                 "sdt_sage_linear_bwd: workspace of %zu bytes needed, %zu given", w.total, ws_bytes);
     char* base = static_cast<char*>(ws);

@@ -238,6 +238,144 @@ __global__ __launch_bounds__(256) void k_linear_fwd_x3_finish(const float* __res
     }
 }
 
+// ---- weight gradient ------------------------------------------------------------------------
+// P[s][h in + m][o] = sum over the rows r of row range s of X_h[r, m] dZ[r, o]  (X_0 = Hself, X_1 = A),
+// Q[s][o] = column sums of dZ over the range: the layout the step's single reduction launch expects.
+// The reduction runs over the ROWS here, which are the strided index of both operands: a thread
+// gathers eight consecutive rows of one column (eight 4-byte loads, each coalesced over the lanes'
+// consecutive columns), splits them and stores one 16-byte vector per plane, so the tiles reach LDS
+// in the layout the forward uses and the matrix step is the same.  Tile 128 features x 256 outputs
+// x 16 rows; grid = (feature tiles of both halves) x S row ranges, S = 256 / tiles: one workgroup per CU.
+// No alignment or padding requirement (all loads are single dwords; rows and columns past the end are
+// clamped to valid addresses, rows past the range are zeroed, columns past the end are never stored).
+__global__ __launch_bounds__(NT, 1) void k_linear_bwd_weight_x3(const float* __restrict__ Hself, int64_t ldh,
+                                                                const float* __restrict__ Agg, int64_t lda,
+                                                                const float* __restrict__ dY, int64_t lddy, int n_cap,
+                                                                const int32_t* n_d, int in, int out, int S,
+                                                                float* __restrict__ P, float* __restrict__ Q) {
+    const int n = dev_count(n_cap, n_d);
+    const int mt = (in + BM - 1) / BM;
+    const int id = xcd_contiguous_id(mt * 2 * S);   // every unit writes its partial tile, if only zeros
+    if (id < 0) return;
+    const int tile = id % (mt * 2), split = id / (mt * 2);   // the tiles of a row range are neighbours: they share dZ
+    const int half = tile / mt, m0 = (tile % mt) * BM;
+    const int chunk = ((n + S - 1) / S + BK - 1) / BK * BK;
+    const int r_begin = split * chunk, r_end = min(n, r_begin + chunk);
+    const int nit = r_end > r_begin ? (r_end - r_begin + BK - 1) / BK : 0;
+    extern __shared__ __align__(16) uint16_t lds_x3[];
+    uint16_t* As = lds_x3;
+    uint16_t* Bs = lds_x3 + 2 * A_BUF;
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+    const int tid = threadIdx.x;
+    const float* X = half ? Agg : Hself;
+    const int64_t ldx = half ? lda : ldh;
+    // dZ: thread -> column tid % 256, rows 8 (tid / 256) ... of the step; X: threads < 256 -> column tid % 128,
+    // rows 8 (tid / 128) ...
+    const int bo = tid & 255, bk = tid >> 8, am = tid & 127, ak = (tid >> 7) & 1;
+    const bool has_a = tid < 256;
+    const float* pb = dY + min(bo, out - 1);
+    const float* pa = X + min(m0 + am, in - 1);
+    const int b_off = bo * LDK + bk * 8, a_off = am * LDK + ak * 8;
+    const bool do_bias = Q != nullptr && tile == 0;
+    float bsum = 0.f;
+    struct St { float b[8], a[8]; };
+    auto fetch = [&](int it, St& s) {
+        const int rb = r_begin + it * BK + bk * 8, ra = r_begin + it * BK + ak * 8;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s.b[i] = pb[(int64_t)min(rb + i, n - 1) * lddy];
+        if (has_a) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) s.a[i] = pa[(int64_t)min(ra + i, n - 1) * ldx];
+        }
+    };
+    auto put = [&](const float (&v)[8], int r0, uint16_t* plane0, int plane_elems, int off, bool sum) {
+        float w[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[i] = r0 + i < r_end ? v[i] : 0.f;
+        if (sum) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) bsum += w[i];
+        }
+        uint4 h, m, l;
+        split_pair(w[0], w[1], h.x, m.x, l.x);
+        split_pair(w[2], w[3], h.y, m.y, l.y);
+        split_pair(w[4], w[5], h.z, m.z, l.z);
+        split_pair(w[6], w[7], h.w, m.w, l.w);
+        *reinterpret_cast<uint4*>(plane0 + off) = h;
+        *reinterpret_cast<uint4*>(plane0 + plane_elems + off) = m;
+        *reinterpret_cast<uint4*>(plane0 + 2 * plane_elems + off) = l;
+    };
+    const int wave = tid >> 6, lane = tid & 63, a0 = (wave >> 2) * 64, b0 = (wave & 3) * 64;
+    const int fi = lane & 31, fk = (lane >> 5) * 8;
+    auto step = [&](const uint16_t* Ab, const uint16_t* Bb) {
+        bf16x8 fa[3][2], fb[3][2];
+#pragma unroll
+        for (int q = 0; q < 3; ++q)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                fa[q][t] = *reinterpret_cast<const bf16x8*>(Ab + q * A_PLANE + (a0 + t * 32 + fi) * LDK + fk);
+                fb[q][t] = *reinterpret_cast<const bf16x8*>(Bb + q * B_PLANE + (b0 + t * 32 + fi) * LDK + fk);
+            }
+        constexpr int PA[6] = {0, 2, 1, 0, 1, 0};
+        constexpr int PB[6] = {2, 0, 1, 1, 0, 0};
+#pragma unroll
+        for (int t = 0; t < 6; ++t)
+#pragma unroll
+            for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < 2; ++tn)
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[PA[t]][tm], fb[PB[t]][tn], acc[tm][tn], 0, 0, 0);
+    };
+    if (nit > 0) {
+        St st[2];
+        fetch(0, st[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(1, st[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        for (int it = 0; it < nit; it += 2) {
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const bool live = s == 0 || it + 1 < nit;
+                uint16_t* Ab = As + s * A_BUF;
+                uint16_t* Bb = Bs + s * B_BUF;
+                if (live) {
+                    put(st[s].b, r_begin + (it + s) * BK + bk * 8, Bb, B_PLANE, b_off, do_bias);
+                    if (has_a) put(st[s].a, r_begin + (it + s) * BK + ak * 8, Ab, A_PLANE, a_off, false);
+                    __syncthreads();
+                }
+                fetch(it + s + 2, st[s]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (live) step(Ab, Bb);
+            }
+        }
+    }
+    if (do_bias) {   // the two row groups of a column, added in a fixed order
+        __syncthreads();
+        float* red = reinterpret_cast<float*>(lds_x3);
+        red[tid] = bsum;
+        __syncthreads();
+        if (tid < 256 && tid < out) Q[(int64_t)split * out + tid] = red[tid] + red[256 + tid];
+    }
+    float* dst = P + ((int64_t)split * 2 * in + (int64_t)half * in) * out;
+#pragma unroll
+    for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn) {
+            const int col = b0 + tn * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + a0 + tm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (row < in && col < out) dst[(int64_t)row * out + col] = acc[tm][tn][r];
+            }
+        }
+}
+
 constexpr int S_MAX = 4;
 
 struct X3Ws {
@@ -254,7 +392,7 @@ X3Ws x3_ws(int32_t n_cap, int32_t in, int32_t out) {
     return w;
 }
 
-std::atomic<bool> lds_opted{false};
+std::atomic<bool> lds_opted{false}, lds_opted_dw{false};
 
 }  // namespace
 
@@ -306,6 +444,38 @@ int32_t linear_fwd_x3(const float* Hself, int64_t ldh, const float* A, int64_t l
     hipLaunchKernelGGL(k_linear_fwd_x3_finish, dim3(blocks), dim3(256), 0, st, P, n_cap, n_d, w.nk, out, w.s_max, b, relu, Y,
                        ldy);
     SDT_CHECK_LAUNCH("linear_fwd_x3_finish");
+    return SDT_OK;
+}
+
+// Weight gradient: the same shapes (wide output, enough rows and features that the 128 x 256 tiles dealt out over
+// the rows fill the chip).
+bool x3_dw_wanted(int32_t n_cap, int32_t in, int32_t out) {
+    return out > 128 && out <= BN && in >= 128 && n_cap >= 2048 && 2 * ceil_div(in, BM) <= CUS / 4;
+}
+
+// row ranges: as many as give every CU one workgroup, each at least 64 rows
+int32_t x3_dw_splits(int32_t n_cap, int32_t in) {
+    int s = CUS / (2 * ceil_div(in, BM));
+    const int max_rows = ceil_div(n_cap > 0 ? n_cap : 1, 64);
+    if (s > max_rows) s = max_rows;
+    return s < 1 ? 1 : s;
+}
+
+int32_t linear_bwd_weight_x3(const float* Hself, int64_t ldh, const float* A, int64_t lda, const float* dY, int64_t lddy,
+                             int32_t n_cap, const int32_t* n_d, int32_t in, int32_t out, int32_t splits, float* P, float* Q,
+                             hipStream_t st) {
+    if (!lds_opted_dw.load(std::memory_order_acquire)) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_linear_bwd_weight_x3),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES) != hipSuccess) {
+            set_error("linear_bwd_weight_x3: cannot raise the dynamic LDS limit to %zu bytes", LDS_BYTES);
+            return SDT_ERR_HIP;
+        }
+        lds_opted_dw.store(true, std::memory_order_release);
+    }
+    // (no rows: every unit still writes its tile of zeros, which the reduction reads)
+    hipLaunchKernelGGL(k_linear_bwd_weight_x3, dim3(2 * ceil_div(in, BM) * splits), dim3(NT), LDS_BYTES, st, Hself, ldh, A, lda,
+                       dY, lddy, n_cap, n_d, in, out, splits, P, Q);
+    SDT_CHECK_LAUNCH("linear_bwd_weight_x3");
     return SDT_OK;
 }
 

@@ -39,7 +39,10 @@ inline int32_t operand_width(const sdt_model* m, int l) { return m->kind != SDT_
 
 // scratch of one layer's projection backward (split partials of dW/db, or the fused head's)
 size_t bwd_scratch_bytes(int32_t batch, int32_t cap_dst, int32_t in, int32_t out, bool last) {
-    size_t lb = sdt_linear_bwd_workspace_bytes(cap_dst, in, out);
+    // (sized for the split-bf16 weight gradient where the shape suits it: at least the plain path's need)
+    size_t lb = linear_bwd_workspace_bytes_x3(cap_dst, in, out);
+    const size_t plain = sdt_linear_bwd_workspace_bytes(cap_dst, in, out);
+    if (plain > lb) lb = plain;
     // the forward of the same layer may borrow the region first (partial tiles of the split-bf16 projection)
     const size_t fb = last ? 0 : x3_fwd_workspace_bytes(cap_dst, in, out);
     if (fb > lb) lb = fb;
@@ -744,6 +747,7 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
             ex.W_upd = model->W[l];
             ex.b_upd = model->b[l];
             ex.rows_padded = l == 0;
+            ex.x3 = true;
             ex.timing = timing; ex.slot = c.slot; ex.layer = l;
             rc = linear_bwd(dY, d[l + 1], dy_dtype, nullptr, 0, 0, b.at(lay.H[l]), ldx(l), b.at(lay.A[l]), ldx(l),
                             lay.cap_dst[l], b.blk[l].counts, d[l], d[l + 1], model->W[l], dtype, dW, db,

@@ -173,10 +173,9 @@ int32_t sample_layer(const sdt_csr& g, const int32_t* dst_nodes, int32_t n_dst_c
 int32_t gather_rows(const void* X, int64_t ldx, int32_t F, int32_t dtype, const int32_t* idx, int32_t n_cap,
                     const int32_t* n_d, void* out, int64_t ldo, bool zero_pad, void* also_pad, hipStream_t st);
 
-// mean aggregation straight from the feature matrix through blk->src_nodes.  background: the launch will run beside
-// matrix kernels of another stream and should leave them most of the wave slots (see rowops.hip)
+// mean aggregation straight from the feature matrix through blk->src_nodes
 int32_t aggregate_gather_fwd(const sdt_block* blk, const void* X, int64_t ldx, int32_t F, int32_t dtype, void* A,
-                             int64_t lda, bool background, hipStream_t st);
+                             int64_t lda, hipStream_t st);
 
 // writes dZ and the per-row losses; their mean is folded into a later single-block pass
 int32_t softmax_xent(const float* logits, int64_t ld, int32_t B, int32_t C, const int32_t* labels,

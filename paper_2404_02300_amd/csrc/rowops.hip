@@ -146,12 +146,11 @@ __global__ __launch_bounds__(TB) void k_aggregate_fwd(const IP* __restrict__ ind
 // fraction of the wavefronts to keep the memory system busy.  Sums in edge order, as above: same bits.
 // Dense workload (602 floats, NP = 3), layer-0 aggregation alone: 108 -> 98 us (6.5 TB/s of gather-side bytes).
 //
-// BACKGROUND_BLOCKS: inside a training loop this kernel runs on an auxiliary stream beside the projections of
-// the step before.  Launched over every CU's wave slots (2048 workgroups) it and they take turns: the loop's
-// step lasted the sum of its large kernels.  With 1.5 workgroups per CU it leaves the slots to the matrix
-// kernels and streams in the background: it takes longer itself (155 against 106 us) and the step gets shorter
-// (dense loop 3 360 -> 3 890 steps/s; 256 workgroups 3 850, 192: 3 830, 128: 3 650, 512: 3 690, 1024: 3 530).
-constexpr int BACKGROUND_BLOCKS = 384;
+// Inside a training loop this kernel runs on an auxiliary stream beside the projections of the step before.  While
+// those were fp32 matrix kernels of four-wave workgroups, a launch capped at 1.5 workgroups per CU (streaming in
+// the background, 155 us against 106) made the loop faster (dense 3 360 -> 3 890 steps/s); beside the split-bf16
+// projections, whose single workgroup per CU needs only eight wave slots, the full launch is the faster one
+// again (4 200 against 4 100 steps/s, the kernel 120 against 169 us inside the loop), so nothing is capped.
 template <typename T, int VE, int G, int NP>
 __global__ __launch_bounds__(TB) void k_aggregate_fwd_wide(const int32_t* __restrict__ indptr, const int32_t* __restrict__ cols,
                                                            int64_t n_cap, const int32_t* n_d, const T* __restrict__ H,
@@ -409,7 +408,7 @@ bool dispatch(int32_t dtype, int ve, int G, F32Fn&& f32, BF16Fn&& bf) {
 template <typename IP>
 int32_t launch_aggregate_fwd(const IP* indptr, const int32_t* cols, int64_t n_cap, const int32_t* n_d, const void* H,
                              int64_t ldh, int32_t F, int32_t dtype, void* A, int64_t lda, const int32_t* row_ids,
-                             int max_blocks, hipStream_t st) {
+                             hipStream_t st) {
     if (n_cap == 0 || F == 0) return SDT_OK;
     const size_t es = dtype_size(dtype);
     // (the hub kernel of the whole-graph form keeps whole vectors per row)
@@ -428,7 +427,6 @@ int32_t launch_aggregate_fwd(const IP* indptr, const int32_t* cols, int64_t n_ca
             // rows wider than one pass of the lane group: the passes run side by side (see k_aggregate_fwd_wide)
             const int np = ceil_div(ceil_div(F, VE), GG);
             if (np >= 2 && np <= 4) {
-                if (max_blocks > 0 && grid > max_blocks) grid = max_blocks;
                 const int32_t* ip = reinterpret_cast<const int32_t*>(indptr);
 #define SDT_WIDE(NP)                                                                                                    \
     hipLaunchKernelGGL((k_aggregate_fwd_wide<T, VE, GG, NP>), dim3(grid), dim3(TB), 0, st, ip, cols, n_cap, n_d,        \
@@ -515,12 +513,12 @@ extern "C" int32_t sdt_sage_aggregate_fwd(const sdt_block* blk, const void* H, i
     SDT_REQUIRE(blk->counts && blk->indptr && H && A && (blk->cols || blk->cap_nnz == 0), SDT_ERR_INVALID_ARG,
                 "sdt_sage_aggregate_fwd: null pointer");
     return launch_aggregate_fwd<int32_t>(blk->indptr, blk->cols, blk->cap_dst, blk->counts, H, ldh, F, dtype, A, lda,
-                                         nullptr, 0, static_cast<hipStream_t>(stream));
+                                         nullptr, static_cast<hipStream_t>(stream));
 }
 
 namespace sdt {
 int32_t aggregate_gather_fwd(const sdt_block* blk, const void* X, int64_t ldx, int32_t F, int32_t dtype, void* A,
-                             int64_t lda, bool background, hipStream_t st) {
+                             int64_t lda, hipStream_t st) {
     SDT_REQUIRE(blk, SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_gather_fwd: null block");
     SDT_REQUIRE(dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_gather_fwd: unknown dtype %d", dtype);
     SDT_REQUIRE(F >= 0 && blk->cap_dst >= 0 && ldx >= F && lda >= F, SDT_ERR_INVALID_ARG,
@@ -529,13 +527,13 @@ int32_t aggregate_gather_fwd(const sdt_block* blk, const void* X, int64_t ldx, i
     SDT_REQUIRE(blk->counts && blk->indptr && blk->src_nodes && X && A && (blk->cols || blk->cap_nnz == 0),
                 SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_gather_fwd: null pointer");
     return launch_aggregate_fwd<int32_t>(blk->indptr, blk->cols, blk->cap_dst, blk->counts, X, ldx, F, dtype, A, lda,
-                                         blk->src_nodes, background ? BACKGROUND_BLOCKS : 0, st);
+                                         blk->src_nodes, st);
 }
 }  // namespace sdt
 
 extern "C" int32_t sdt_sage_aggregate_gather_fwd(const sdt_block* blk, const void* X, int64_t ldx, int32_t F,
                                                  int32_t dtype, void* A, int64_t lda, void* stream) {
-    return aggregate_gather_fwd(blk, X, ldx, F, dtype, A, lda, false, static_cast<hipStream_t>(stream));
+    return aggregate_gather_fwd(blk, X, ldx, F, dtype, A, lda, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int32_t sdt_sage_aggregate_csr_fwd(const sdt_csr* g, const void* H, int64_t ldh, int32_t F, int32_t dtype,
@@ -547,7 +545,7 @@ extern "C" int32_t sdt_sage_aggregate_csr_fwd(const sdt_csr* g, const void* H, i
     if (g->n_nodes == 0 || F == 0) return SDT_OK;
     SDT_REQUIRE(g->indptr && g->indices && H && A, SDT_ERR_INVALID_ARG, "sdt_sage_aggregate_csr_fwd: null pointer");
     return launch_aggregate_fwd<int64_t>(g->indptr, g->indices, g->n_nodes, nullptr, H, ldh, F, dtype, A, lda,
-                                         nullptr, 0, static_cast<hipStream_t>(stream));
+                                         nullptr, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int32_t sdt_sage_aggregate_bwd(const sdt_block* blk, const void* dAgg, int64_t ldg, const void* dSelf,

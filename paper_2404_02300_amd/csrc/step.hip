@@ -316,7 +316,6 @@ struct StepCtx {
     sdt_timing* timing;
     sdt_step_layout lay;
     int32_t slot = -1;   // timing slot of the step being enqueued (each enqueueing thread has its own copy)
-    bool background = false;   // the sampling phase runs on an auxiliary stream beside another step's model phase
 };
 
 struct StepBuffers {
@@ -437,7 +436,7 @@ int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds
     }
     if (rc != SDT_OK) return rc;
     StageTimer tm(c.timing, c.slot, SDT_STAGE_AGG_FWD, 0, st);
-    return aggregate_gather_fwd(&b.blk[0], c.X, c.ldx, d[0], c.dtype, b.at(lay.A[0]), (int64_t)lay.ld_in, c.background, st);
+    return aggregate_gather_fwd(&b.blk[0], c.X, c.ldx, d[0], c.dtype, b.at(lay.A[0]), (int64_t)lay.ld_in, st);
 }
 
 // Phase 2 of a GCN step.  The projection kernels take two operands of equal width; here they are
@@ -958,7 +957,6 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
         auto helper_fn = [&](int a) {
             (void)hipSetDevice(dev);
             StepCtx ca = c;
-            ca.background = true;
             hipStream_t aux_st = aux[a];
             for (int g = a; g < n_groups; g += n_aux) {
                 const int s = g % LOOP_SLOTS;

@@ -298,6 +298,16 @@ def bench_step(args, workload, full):
     d = wl.dims
     N = inst.n_nodes
 
+    # fp32 GraphSAGE layers with a wide output, a long reduction and few row tiles run on the bf16 matrix cores through
+    # exact three-way splits (csrc/linear_x3.hip; the predicates are x3_fwd_wanted / x3_dw_wanted there)
+    def x3_fwd(l):
+        return (not wl.bf16 and not gcn and not gat and l < L - 1 and 128 < d[l + 1] <= 256 and d[l + 1] % 4 == 0
+                and d[l] >= 256 and lay.cap_dst[l] >= 2048 and (lay.cap_dst[l] + 127) // 128 <= 256)
+
+    def x3_dw(l):
+        return (not wl.bf16 and not gcn and not gat and 128 < d[l + 1] <= 256 and d[l] >= 128 and lay.cap_dst[l] >= 2048
+                and 2 * ((d[l] + 127) // 128) <= 64 and not (l == L - 1 and ("head", l) in stage_t))
+
     def work(kind, l):
         """Algorithmic work of one launch of a stage: (bound, amount, kernel name)."""
         n_dst, n_src, nnz = mean_cnt[l][:3]
@@ -347,7 +357,9 @@ def bench_step(args, workload, full):
             # must move: both operands and the weights in, the output rows out
             if wl.bf16:
                 return "hbm", n_dst * (2 * d[l] + d[l + 1]) * es + 2 * d[l] * d[l + 1] * 2, "k_fwd_bf16"
-            return "mfma", 2.0 * n_dst * wf * d[l] * d[l + 1], "k_linear_fwd"
+            return "mfma", 2.0 * n_dst * wf * d[l] * d[l + 1], \
+                   "k_linear_fwd_x3 (+ k_x3_transpose_w before, k_linear_fwd_x3_finish after: the stage is three launches)" \
+                   if x3_fwd(l) else "k_linear_fwd"
         if kind in ("linear_bwd", "bwd_weight", "bwd_input"):
             f = 2.0 * n_dst * wf * d[l] * d[l + 1]
             if wl.bf16:   # as the forward: operands in, partial products / input gradients out
@@ -358,9 +370,9 @@ def bench_step(args, workload, full):
                         "bwd_input": "k_bwd_input_bf16"}[kind]
             if kind == "linear_bwd" and l == L - 1 and ("head", l) in stage_t:   # projection + softmax + dW + input gradients
                 return "mfma", f * (3 if l > 0 else 2), "k_head"
+            wname = "k_linear_bwd_weight_x3" if x3_dw(l) else "k_linear_bwd_weight"
             return "mfma", f * (2 if l > 0 and kind == "linear_bwd" else 1), \
-                   {"linear_bwd": "k_linear_bwd_weight (+ _input)", "bwd_weight": "k_linear_bwd_weight",
-                    "bwd_input": "k_linear_bwd_input"}[kind]
+                   {"linear_bwd": wname + " (+ _input)", "bwd_weight": wname, "bwd_input": "k_linear_bwd_input"}[kind]
         if kind == "head":        # projection + dW (+ input gradients) of the last layer, one launch
             return "mfma", 2.0 * n_dst * wf * d[l] * d[l + 1] * (3 if l > 0 else 2), "k_head"
         return "hbm", wl.batch * d[L] * 8, "k_softmax_xent"
@@ -371,9 +383,13 @@ def bench_step(args, workload, full):
             ach, peak, unit = amount / seconds / 1e9, HBM_PEAK_GBS, "GB/s"
         else:
             ach, peak, unit = amount / seconds / 1e12, MFMA_FP32_PEAK_TFLOPS, "TFLOP/s"
-        return {"stage": f"{kind}[{l}]", "kernel": kname, "bound": bound, "achieved": round(ach, 2), "peak": peak,
-                "unit": unit, "frac": round(ach / peak, 4), "algorithmic_per_launch": float(amount),
-                "avg_launch_us": round(seconds * 1e6, 2)}
+        r = {"stage": f"{kind}[{l}]", "kernel": kname, "bound": bound, "achieved": round(ach, 2), "peak": peak,
+             "unit": unit, "frac": round(ach / peak, 4), "algorithmic_per_launch": float(amount),
+             "avg_launch_us": round(seconds * 1e6, 2)}
+        if "_x3" in kname:   # priced as what it computes: the fp32 product, against the fp32 matrix peak
+            r["matrix_path"] = ("fp32 operands as exact sums of three bf16, six v_mfma_f32_32x32x16_bf16 per fp32 product "
+                                "block; algorithmic fp32 flops over the published fp32 matrix peak")
+        return r
 
     # roofline of the longest kernel, from the events recorded inside the timed region (median repetition)
     roofline = rate(dominant[0], dominant[1], dom_ms[med] * 1e-3)

@@ -461,6 +461,24 @@ def test_train_step_wide_first_layer_padded_rows(feat):
     _run_and_check(inst, wl, steps=2, check_float_steps=(0, 1))
 
 
+@pytest.mark.parametrize("name,feat,hidden,layers,fanouts,batch,deg", [
+    # three layers: layer 0 (260 -> 256, rows padded to 288 floats) and layer 1 (256 -> 256, 2 560 rows at most) both take the
+    # split-bf16 forward and weight gradient; layer 1 also returns input gradients from the fp32 kernel
+    ("x3-three-layers", 260, 256, 3, [6, 5, 4], 512, 12),
+    # the narrowest output the path takes (132 columns: one full and one ragged 32-column block per wave), 18 row tiles
+    ("x3-narrow-out", 512, 132, 2, [10, 8], 256, 16),
+    # a sparse graph: the frontier stays far below its upper bound, so the device picks the largest split
+    ("x3-small-frontier", 300, 200, 2, [12, 10], 256, 2),
+])
+def test_train_step_split_bf16_projection_shapes(name, feat, hidden, layers, fanouts, batch, deg):
+    # fp32 layers with a wide output, a long reduction and few row tiles run on the bf16 matrix cores through exact
+    # three-way splits (csrc/linear_x3.hip); the bar is the fp32 one
+    _say(f"train step, split-bf16 projections: {name}")
+    wl = gen.Workload(name, "rmat", 13, deg, feat, 7, hidden, layers, fanouts, batch, 23, 1, owned_frac=0.5)
+    inst = gen.make_instance(wl)
+    _run_and_check(inst, wl, steps=2, check_float_steps=(0, 1))
+
+
 def test_train_step_ragged_dims_fp32():
     _say("train step: odd feature widths (scalar load paths)")
     wl = gen.Workload("odd", "rmat", 12, 10, 37, 5, 19, 2, [4, 3], 100, 9, 1)

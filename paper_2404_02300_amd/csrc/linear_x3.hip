@@ -113,32 +113,43 @@ __global__ __launch_bounds__(NT, 1) void k_linear_fwd_x3(const float* __restrict
     const int it0 = z * per, it1 = min(2 * nk, it0 + per);
     const int nit = it1 - it0;
     const int tid = threadIdx.x;
-    // staging: thread -> (row tid/4, floats 4 (tid%4) ...) of the activations, (column tid/2, floats 8 (tid%2) ...)
-    // of the weights.  A row or column past the end is clamped: it only feeds outputs that are never stored.
-    const int ar = tid >> 2, aq = tid & 3, bc = tid >> 1, bkv = tid & 1;
-    const int arow = min(row0 + ar, n - 1);
-    const char* aS = reinterpret_cast<const char*>(Hself + (int64_t)arow * ldh + aq * 4);
-    const char* aN = reinterpret_cast<const char*>(Agg + (int64_t)arow * lda + aq * 4);
+    // staging: thread -> (column tid/2, floats 8 (tid%2) ...) of the weights; the first 256 threads also -> (row tid/2,
+    // floats 8 (tid%2) ...) of the activations: every LDS store is then a whole 16-byte vector per plane, free of bank
+    // conflicts (8-byte stores of four floats per thread collided two ways).  A row or column past the end is
+    // clamped: it only feeds outputs that are never stored.
+    const int bc = tid >> 1, bkv = tid & 1;
+    const bool has_a = tid < 2 * BM;
+    const int arow = min(row0 + (bc & (BM - 1)), n - 1);
+    const char* aS = reinterpret_cast<const char*>(Hself + (int64_t)arow * ldh + bkv * 8);
+    const char* aN = reinterpret_cast<const char*>(Agg + (int64_t)arow * lda + bkv * 8);
     const char* bp = reinterpret_cast<const char*>(Wt + (int64_t)min(bc, out - 1) * 2 * kp + bkv * 8);
-    const int a_off = ar * LDK + aq * 4, b_off = bc * LDK + bkv * 8;
-    struct St { float4 a, b0, b1; };
+    const int b_off = bc * LDK + bkv * 8, a_off = (bc & (BM - 1)) * LDK + bkv * 8;
+    struct St { float4 a0, a1, b0, b1; };
     // Nothing about a fetch is conditional (a step past the unit's range re-reads the last valid step and is
     // never used), so the wait before a stage is stored covers that stage only and the next one keeps flying.
     auto fetch = [&](int it_rel, St& s) {
         const int it = min(it0 + it_rel, 2 * nk - 1);
         const int ph = it >= nk;
-        s.a = *reinterpret_cast<const float4*>((ph ? aN : aS) + (int64_t)(it - ph * nk) * (BK * 4));
+        if (has_a) {   // (uniform over a wave)
+            const char* pa = (ph ? aN : aS) + (int64_t)(it - ph * nk) * (BK * 4);
+            s.a0 = *reinterpret_cast<const float4*>(pa);
+            s.a1 = *reinterpret_cast<const float4*>(pa + 16);
+        }
         const char* pb = bp + (int64_t)it * (BK * 4);
         s.b0 = *reinterpret_cast<const float4*>(pb);
         s.b1 = *reinterpret_cast<const float4*>(pb + 16);
     };
     auto store = [&](const St& s, uint16_t* Ab, uint16_t* Bb) {
-        uint2 h, m, l;
-        split_pair(s.a.x, s.a.y, h.x, m.x, l.x);
-        split_pair(s.a.z, s.a.w, h.y, m.y, l.y);
-        *reinterpret_cast<uint2*>(Ab + a_off) = h;
-        *reinterpret_cast<uint2*>(Ab + A_PLANE + a_off) = m;
-        *reinterpret_cast<uint2*>(Ab + 2 * A_PLANE + a_off) = l;
+        if (has_a) {
+            uint4 h, m, l;
+            split_pair(s.a0.x, s.a0.y, h.x, m.x, l.x);
+            split_pair(s.a0.z, s.a0.w, h.y, m.y, l.y);
+            split_pair(s.a1.x, s.a1.y, h.z, m.z, l.z);
+            split_pair(s.a1.z, s.a1.w, h.w, m.w, l.w);
+            *reinterpret_cast<uint4*>(Ab + a_off) = h;
+            *reinterpret_cast<uint4*>(Ab + A_PLANE + a_off) = m;
+            *reinterpret_cast<uint4*>(Ab + 2 * A_PLANE + a_off) = l;
+        }
         uint4 bh, bm, bl;
         split_pair(s.b0.x, s.b0.y, bh.x, bm.x, bl.x);
         split_pair(s.b0.z, s.b0.w, bh.y, bm.y, bl.y);

@@ -130,11 +130,15 @@ __device__ __forceinline__ int dev_count(int cap, const int32_t* n_d) {
 // `valid` tiles carry work (the grid is sized for an upper bound of the row count); they are
 // dealt out evenly over the XCDs.  Returns the tile id in [0, valid), or -1 for a workgroup
 // that has nothing to do.  Needs valid <= number of workgroups.
-__device__ __forceinline__ int xcd_contiguous_id(int valid) {
-    const int id = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+// (from_linear: the same for a workgroup whose linear id is given -- a kernel whose grid is shared by two kinds
+// of work passes the id inside its part, which must start at a multiple of eight so that id & 7 is still the XCD)
+__device__ __forceinline__ int xcd_contiguous_from_linear(int id, int valid) {
     const int xcd = id & 7, slot = id >> 3, q = valid >> 3, r = valid & 7;
     if (slot >= q + (xcd < r ? 1 : 0)) return -1;
     return (xcd < r ? xcd * (q + 1) : r * (q + 1) + (xcd - r) * q) + slot;
+}
+__device__ __forceinline__ int xcd_contiguous_id(int valid) {
+    return xcd_contiguous_from_linear(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z), valid);
 }
 
 inline size_t dtype_size(int32_t dt) { return dt == SDT_BF16 ? 2 : 4; }
@@ -289,6 +293,10 @@ int32_t linear_bwd_weight_bf16(const void* Hself, int64_t ldh, const void* A, in
 int32_t linear_bwd_input_bf16(const void* dY, int64_t lddy, int32_t dy_dtype, int32_t n_cap, const int32_t* n_d,
                               int32_t in, int32_t out, const void* Wb, void* dSelf, void* dAgg, int64_t ldi,
                               hipStream_t st);
+// both products of a layer's backward in ONE launch (the two are independent and each fills a fraction of the chip)
+int32_t linear_bwd_both_bf16(const void* Hself, int64_t ldh, const void* A, int64_t lda, const void* dY, int64_t lddy,
+                             int32_t dy_dtype, int32_t n_cap, const int32_t* n_d, int32_t in, int32_t out, int32_t splits,
+                             float* P, float* Q, const void* Wb, void* dSelf, void* dAgg, int64_t ldi, hipStream_t st);
 
 // GCN aggregation (gcn.hip)
 int32_t gcn_aggregate_fwd(const sdt_block* blk, const float* H, int64_t ldh, bool through_src_nodes, int32_t F,

@@ -727,9 +727,15 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Hself, int64_t ldh, co
     const TD* dYt = static_cast<const TD*>(dY);
     // weight gradient partials (bf16 activations inside a step: on the bf16 matrix cores)
     const int32_t dy_code = sizeof(TD) == 2 ? SDT_BF16 : SDT_F32;
+    const bool weight_on_bf16_path = ex.Wb && sizeof(TH) == 2 && bf16_mfma_bwd_weight_ok(Hself, ldh, A, lda, dY, lddy, dy_code, in, out);
+    // both products on the bf16 matrix cores: one launch for the two (they are independent; timed as the weight stage)
+    const bool both = weight_on_bf16_path && dSelf && n_cap > 0 && bf16_mfma_bwd_input_ok(dY, lddy, dy_code, in, out, ldi);
     {
     StageTimer tw(ex.timing, ex.slot, SDT_STAGE_BWD_WEIGHT, ex.layer, st);
-    if (ex.Wb && sizeof(TH) == 2 && bf16_mfma_bwd_weight_ok(Hself, ldh, A, lda, dY, lddy, dy_code, in, out)) {
+    if (both) {
+        (void)linear_bwd_both_bf16(Hself, ldh, A, lda, dY, lddy, dy_code, n_cap, n_d, in, out, splits, P, Q, ex.Wb, dSelf, dAgg,
+                                   ldi, st);
+    } else if (weight_on_bf16_path) {
         (void)linear_bwd_weight_bf16(Hself, ldh, A, lda, dY, lddy, dy_code, n_cap, n_d, in, out, splits, P, Q, st);
     } else if (ex.x3 && sizeof(TH) == 4 && sizeof(TD) == 4 && x3_dw_wanted(n_cap, in, out)) {
         // (the caller's workspace was sized for this path's row ranges: bwd_ws with the same flag)
@@ -750,7 +756,7 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Hself, int64_t ldh, co
     }
     }
     const bool input_on_bf16_path = ex.Wb && sizeof(TH) == 2 && dSelf && bf16_mfma_bwd_input_ok(dY, lddy, dy_code, in, out, ldi);
-    {
+    if (!both) {
     StageTimer ti(dSelf && n_cap > 0 ? ex.timing : nullptr, ex.slot, SDT_STAGE_BWD_INPUT, ex.layer, st);
     if (input_on_bf16_path) {
         (void)linear_bwd_input_bf16(dY, lddy, dy_code, n_cap, n_d, in, out, ex.Wb, dSelf, dAgg, ldi, st);

@@ -280,19 +280,18 @@ __global__ __launch_bounds__(TL::NT) void k_fwd_bf16(const uint16_t* __restrict_
 // dIn_h[n, in] = dZ[n, out] W_h^T.  Wb: bf16 [2 in][ldb], rows of W rounded; half h = rows h*in ...
 // TD = uint16_t (bf16 dZ) or float (fp32 dZ, rounded on the way in).
 template <typename TD, typename TL>
-__global__ __launch_bounds__(TL::NT) void k_bwd_input_bf16(const TD* __restrict__ dY, int64_t lddy, int n_cap,
-                                                           const int32_t* n_d, int in, int out,
-                                                           const uint16_t* __restrict__ Wb, int64_t ldb,
-                                                           bf16_t* __restrict__ dSelf, bf16_t* __restrict__ dAgg,
-                                                           int64_t ldi) {
+__device__ __forceinline__ void bwd_input_body(const TD* __restrict__ dY, int64_t lddy, int n_cap, const int32_t* n_d, int in,
+                                               int out, const uint16_t* __restrict__ Wb, int64_t ldb,
+                                               bf16_t* __restrict__ dSelf, bf16_t* __restrict__ dAgg, int64_t ldi,
+                                               int lin_id, int gx, uint16_t* lds) {
     constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK;
     const int n = dev_count(n_cap, n_d);
-    const int id = xcd_contiguous_id((int)gridDim.x * 2 * ((n + BM - 1) / BM));
+    const int id = xcd_contiguous_from_linear(lin_id, gx * 2 * ((n + BM - 1) / BM));
     if (id < 0) return;
-    const int col0 = (id % (int)gridDim.x) * BN, half = (id / (int)gridDim.x) % 2;
-    const int row0 = (id / (int)gridDim.x / 2) * BM;
-    __shared__ __align__(16) uint16_t As[2 * BM * TL::LDK];
-    __shared__ __align__(16) uint16_t Bs[2 * BN * TL::LDK];
+    const int col0 = (id % gx) * BN, half = (id / gx) % 2;
+    const int row0 = (id / gx / 2) * BM;
+    uint16_t* As = lds;                         // [2][BM][LDK]
+    uint16_t* Bs = lds + 2 * BM * TL::LDK;      // [2][BN][LDK]
     floatx16 acc[TL::TM][TL::TN];
     zero<TL>(acc);
     using SA = typename std::conditional<sizeof(TD) == 2, StageB<BM, BK, TL::NT>, StageF<BM, BK, TL::NT>>::type;
@@ -309,6 +308,19 @@ __global__ __launch_bounds__(TL::NT) void k_bwd_input_bf16(const TD* __restrict_
         const int row = row0 + r, col = col0 + c;
         if (row < n && col < in) dst[(int64_t)row * ldi + col] = from_f32<bf16_t>(v);
     });
+}
+template <typename TL>
+constexpr int input_lds_elems() { return 2 * (TL::BM + TL::BN) * TL::LDK; }
+
+template <typename TD, typename TL>
+__global__ __launch_bounds__(TL::NT) void k_bwd_input_bf16(const TD* __restrict__ dY, int64_t lddy, int n_cap,
+                                                           const int32_t* n_d, int in, int out,
+                                                           const uint16_t* __restrict__ Wb, int64_t ldb,
+                                                           bf16_t* __restrict__ dSelf, bf16_t* __restrict__ dAgg,
+                                                           int64_t ldi) {
+    __shared__ __align__(16) uint16_t lds[input_lds_elems<TL>()];
+    bwd_input_body<TD, TL>(dY, lddy, n_cap, n_d, in, out, Wb, ldb, dSelf, dAgg, ldi,
+                           (int)(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z)), (int)gridDim.x, lds);
 }
 
 // ---- weight gradient partials ------------------------------------------------------------------
@@ -383,27 +395,28 @@ struct StageRowsF {  // fp32 source, rounded to bf16 on the way (cmax % 4 == 0, 
 };
 
 // P[s][h*in + m][o] = sum over the rows r of split s of X_h[r, m] dZ[r, o]  (X_0 = Hself, X_1 = A),
-// Q[s][o] = column sums of (rounded) dZ; grid (out tiles, in tiles, 2 * splits) as in the fp32 path.
+// Q[s][o] = column sums of (rounded) dZ; workgroups (gx out tiles, gy in tiles, 2 * splits) as in the fp32 path.
 template <typename TD, typename TL>
-__global__ __launch_bounds__(TL::NT) void k_bwd_weight_bf16(const uint16_t* __restrict__ Hself, int64_t ldh,
-                                                            const uint16_t* __restrict__ Agg, int64_t lda,
-                                                            const TD* __restrict__ dY, int64_t lddy, int n_cap,
-                                                            const int32_t* n_d, int in, int out, int splits,
-                                                            float* __restrict__ P, float* __restrict__ Q) {
+__device__ __forceinline__ void bwd_weight_body(const uint16_t* __restrict__ Hself, int64_t ldh,
+                                                const uint16_t* __restrict__ Agg, int64_t lda, const TD* __restrict__ dY,
+                                                int64_t lddy, int n_cap, const int32_t* n_d, int in, int out, int splits,
+                                                float* __restrict__ P, float* __restrict__ Q, int lin_id, int gx, int gy,
+                                                uint16_t* lds) {
     constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK;
     constexpr int LDA = BM + 8, LDB = BN + 8;
     const int n = dev_count(n_cap, n_d);
-    const int id = xcd_contiguous_id((int)(gridDim.x * gridDim.y * gridDim.z));
-    const int bx = id % (int)gridDim.x, by = (id / (int)gridDim.x) % (int)gridDim.y;
-    const int bz = id / (int)(gridDim.x * gridDim.y);
+    const int id = xcd_contiguous_from_linear(lin_id, gx * gy * 2 * splits);   // every tile carries work
+    if (id < 0) return;
+    const int bx = id % gx, by = (id / gx) % gy;
+    const int bz = id / (gx * gy);
     const int half = bz & 1, split = bz >> 1;
     const bool do_bias = Q != nullptr && half == 0 && by == 0;
     float bsum = 0.f;
     const int row0 = by * BM /* feature m */, col0 = bx * BN /* output o */;
     const int chunk = ((n + splits - 1) / splits + BK - 1) / BK * BK;
     const int r_begin = split * chunk, r_end = min(n, r_begin + chunk);
-    __shared__ __align__(16) uint16_t As[2 * BK * LDA];
-    __shared__ __align__(16) uint16_t Bs[2 * BK * LDB];
+    uint16_t* As = lds;                  // [2][BK][LDA]
+    uint16_t* Bs = lds + 2 * BK * LDA;   // [2][BK][LDB]
     floatx16 acc[TL::TM][TL::TN];
     zero<TL>(acc);
     using SA = StageRowsB<BK, BM, TL::NT>;
@@ -429,6 +442,42 @@ __global__ __launch_bounds__(TL::NT) void k_bwd_weight_bf16(const uint16_t* __re
         const int row = row0 + r, col = col0 + c;
         if (row < in && col < out) dst[(int64_t)row * out + col] = v;
     });
+}
+template <typename TL>
+constexpr int weight_lds_elems() { return 2 * TL::BK * (TL::BM + 8 + TL::BN + 8); }
+
+template <typename TD, typename TL>
+__global__ __launch_bounds__(TL::NT) void k_bwd_weight_bf16(const uint16_t* __restrict__ Hself, int64_t ldh,
+                                                            const uint16_t* __restrict__ Agg, int64_t lda,
+                                                            const TD* __restrict__ dY, int64_t lddy, int n_cap,
+                                                            const int32_t* n_d, int in, int out, int splits,
+                                                            float* __restrict__ P, float* __restrict__ Q) {
+    __shared__ __align__(16) uint16_t lds[weight_lds_elems<TL>()];
+    bwd_weight_body<TD, TL>(Hself, ldh, Agg, lda, dY, lddy, n_cap, n_d, in, out, splits, P, Q,
+                            (int)(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z)), (int)gridDim.x,
+                            (int)gridDim.y, lds);
+}
+
+// Both products of a layer's backward in one launch: the first nw workgroups (a multiple of eight, so that the
+// linear id inside either part still tells the XCD) take the weight-gradient tiles, the rest the input-gradient
+// tiles.  The two products are independent, read the same dY, and each alone fills a fraction of the chip.
+template <typename TD, typename TW, typename TI>
+__global__ __launch_bounds__(TW::NT) void k_bwd_both_bf16(const uint16_t* __restrict__ Hself, int64_t ldh,
+                                                          const uint16_t* __restrict__ Agg, int64_t lda,
+                                                          const TD* __restrict__ dY, int64_t lddy, int n_cap,
+                                                          const int32_t* n_d, int in, int out, int splits,
+                                                          float* __restrict__ P, float* __restrict__ Q, int nw, int wgx,
+                                                          int wgy, const uint16_t* __restrict__ Wb, int64_t ldb,
+                                                          bf16_t* __restrict__ dSelf, bf16_t* __restrict__ dAgg, int64_t ldi,
+                                                          int igx) {
+    static_assert(TW::NT == TI::NT, "one workgroup size for both parts");
+    constexpr int LDS = weight_lds_elems<TW>() > input_lds_elems<TI>() ? weight_lds_elems<TW>() : input_lds_elems<TI>();
+    __shared__ __align__(16) uint16_t lds[LDS];
+    const int id = (int)blockIdx.x;
+    if (id < nw)
+        bwd_weight_body<TD, TW>(Hself, ldh, Agg, lda, dY, lddy, n_cap, n_d, in, out, splits, P, Q, id, wgx, wgy, lds);
+    else
+        bwd_input_body<TD, TI>(dY, lddy, n_cap, n_d, in, out, Wb, ldb, dSelf, dAgg, ldi, id - nw, igx, lds);
 }
 
 // ---- bf16 images of the weights ----------------------------------------------------------------
@@ -564,6 +613,35 @@ int32_t linear_bwd_weight_bf16(const void* Hself, int64_t ldh, const void* A, in
         hipLaunchKernelGGL((k_bwd_weight_bf16<float, TW>), grid, dim3(TW::NT), 0, st, h, ldh, a, lda,
                            static_cast<const float*>(dY), lddy, n_cap, n_d, in, out, splits, P, Q);
     SDT_CHECK_LAUNCH("linear_bwd_weight_bf16");
+    return SDT_OK;
+}
+
+int32_t linear_bwd_both_bf16(const void* Hself, int64_t ldh, const void* A, int64_t lda, const void* dY, int64_t lddy,
+                             int32_t dy_dtype, int32_t n_cap, const int32_t* n_d, int32_t in, int32_t out, int32_t splits,
+                             float* P, float* Q, const void* Wb, void* dSelf, void* dAgg, int64_t ldi, hipStream_t st) {
+    using TW = TileB<64, 64, 64, 2, 2>;
+    const uint16_t* h = static_cast<const uint16_t*>(Hself);
+    const uint16_t* a = static_cast<const uint16_t*>(A);
+    const uint16_t* w = static_cast<const uint16_t*>(Wb);
+    const int64_t ldb = bf16_ldb(out);
+    const int wgx = ceil_div(out, TW::BN), wgy = ceil_div(in, TW::BM);
+    const int nw = (wgx * wgy * 2 * splits + 7) / 8 * 8;
+    auto go = [&](auto tile) {
+        using TI = decltype(tile);
+        const int igx = ceil_div(in, TI::BN);
+        const int ni = igx * 2 * ceil_div(n_cap, TI::BM);
+        if (dy_dtype == SDT_BF16)
+            hipLaunchKernelGGL((k_bwd_both_bf16<uint16_t, TW, TI>), dim3(nw + ni), dim3(TW::NT), 0, st, h, ldh, a, lda,
+                               static_cast<const uint16_t*>(dY), lddy, n_cap, n_d, in, out, splits, P, Q, nw, wgx, wgy, w, ldb,
+                               static_cast<bf16_t*>(dSelf), static_cast<bf16_t*>(dAgg), ldi, igx);
+        else
+            hipLaunchKernelGGL((k_bwd_both_bf16<float, TW, TI>), dim3(nw + ni), dim3(TW::NT), 0, st, h, ldh, a, lda,
+                               static_cast<const float*>(dY), lddy, n_cap, n_d, in, out, splits, P, Q, nw, wgx, wgy, w, ldb,
+                               static_cast<bf16_t*>(dSelf), static_cast<bf16_t*>(dAgg), ldi, igx);
+    };
+    if (n_cap >= SMALL_ROWS) go(TFbig{});
+    else go(TFsmall{});
+    SDT_CHECK_LAUNCH("linear_bwd_both_bf16");
     return SDT_OK;
 }
 

@@ -110,7 +110,7 @@ typedef struct sdt_model {
     float *db[SDT_MAX_LAYERS];
     /* SDT_MODEL_SAGE_MEAN (0, the default) or SDT_MODEL_GCN: layer l is
      * H' = act(Agcn(H) W[l] + b[l]) with ONE weight matrix W[l] fp32 [dims[l], dims[l+1]]
-     * and the aggregation of sdt_gcn_aggregate_fwd; fp32 storage and even dims[0..L-1] only. */
+     * and the aggregation of sdt_gcn_aggregate_fwd; fp32 or bf16 storage, even dims[0..L-1] only. */
     int32_t kind;
     /* Optimiser of sdt_train_step: SDT_OPT_SGD (0, the default; w -= lr g) or SDT_OPT_ADAM:
      * m = beta1 m + (1-beta1) g, v = beta2 v + (1-beta2) g^2,
@@ -256,7 +256,8 @@ int32_t sdt_sage_aggregate_bwd(const sdt_block *blk /*host struct*/, const void 
  *   A[i,:] = s[i] * sum_{e in row i} c[col_e] * H[col_e,:] + selfw[i] * H[i,:]    (fwd)
  *   dH[j,:] = c[j] * sum_{(i -> j)} s[i] * dA[i,:] + [j < n_dst] selfw[j] * dA[j,:]  (bwd,
  *   through the transposed block; zeroed where relu_of <= 0 if relu_of != NULL).
- * With every neighbour sampled this is a row of D~^-1/2 (Adj + I) D~^-1/2 H.  fp32 only.
+ * With every neighbour sampled this is a row of D~^-1/2 (Adj + I) D~^-1/2 H.  H, A, dA, dH, relu_of in `dtype`
+ * (fp32 or bf16, sums in fp32); c, s, selfw always fp32.
  * c has blk->cap_src floats, s and selfw blk->cap_dst.  through_src_nodes != 0: row r of
  * the block lives at H[src_nodes[r]] (H is the partition's feature matrix). */
 int32_t sdt_gcn_norm(const sdt_csr *graph /*host struct*/, const sdt_block *blk /*host struct*/, float *c, float *s,

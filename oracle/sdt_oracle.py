@@ -368,25 +368,31 @@ def gcn_linear_fwd(A, W, b, relu: bool) -> np.ndarray:
 
 
 def gcn_train_step(indptr, indices, X, y, seeds, fanouts, W, b, seed: int, step: int, lr: float,
-                   blocks: Optional[List[Block]] = None, relu_masks=None):
+                   blocks: Optional[List[Block]] = None, relu_masks=None, bf16: bool = False):
     """One mini-batch step of a GCN: layer l is H' = act(Agcn(H) W_l + b_l), W_l [in_l, out_l], ReLU on
-    all but the last layer; sampling, loss and SGD as in train_step.  fp32 storage only."""
+    all but the last layer; sampling, loss and SGD as in train_step.  With bf16=True X holds bf16 bit
+    patterns (uint16) and the rounding points are those of forward() / backward(): the aggregated rows,
+    the hidden activations and the gradients w.r.t. both are rounded when produced, the weights and the
+    loss gradient where they enter a product; logits, loss, dW, db are not rounded."""
+    rnd = round_bf16 if bf16 else (lambda t: t)
     L = len(fanouts)
     if blocks is None:
         blocks = sample_blocks(indptr, indices, seeds, fanouts, seed, step)
-    H = [gather_rows(X, blocks[0].src_nodes).astype(np.float64)]
+    Xrows = gather_rows(X, blocks[0].src_nodes)
+    H = [bf16_bits_to_f64(Xrows) if bf16 else Xrows.astype(np.float64)]
     W = [np.asarray(w, dtype=np.float64) for w in W]
     b = [np.asarray(v, dtype=np.float64) for v in b]
     A, wts = [], []
     for l, blk in enumerate(blocks):
         wt = gcn_weights(indptr, blk.src_nodes, blk.indptr)
-        a = gcn_aggregate_fwd(blk.indptr, blk.cols, H[l], *wt)
+        a = rnd(gcn_aggregate_fwd(blk.indptr, blk.cols, H[l], *wt))
         A.append(a)
         wts.append(wt)
-        H.append(gcn_linear_fwd(a, W[l], b[l], relu=(l < L - 1)))
+        z = gcn_linear_fwd(a, rnd(W[l]), b[l], relu=(l < L - 1))
+        H.append(rnd(z) if l < L - 1 else z)
     loss, dZ = softmax_xent(H[L], np.asarray(y)[np.asarray(seeds)])
     dW, db, dA, dHs = [None] * L, [None] * L, [None] * L, [None] * L
-    dY = dZ
+    dY = rnd(dZ)
     for l in range(L - 1, -1, -1):
         blk = blocks[l]
         if l < L - 1:
@@ -397,8 +403,8 @@ def gcn_train_step(indptr, indices, X, y, seeds, fanouts, W, b, seed: int, step:
         dW[l] = A[l].T @ dY
         db[l] = dY.sum(axis=0)
         if l > 0:
-            dA[l] = dY @ W[l].T
-            dY = gcn_aggregate_bwd(blk.indptr, blk.cols, blk.n_src, dA[l], *wts[l])
+            dA[l] = rnd(dY @ rnd(W[l]).T)
+            dY = rnd(gcn_aggregate_bwd(blk.indptr, blk.cols, blk.n_src, dA[l], *wts[l]))
             dHs[l] = dY
     W_new = [sgd(W[l], dW[l], lr) for l in range(L)]
     b_new = [sgd(b[l], db[l], lr) for l in range(L)]

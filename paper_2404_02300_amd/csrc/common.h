@@ -299,8 +299,8 @@ int32_t linear_bwd_both_bf16(const void* Hself, int64_t ldh, const void* A, int6
                              float* P, float* Q, const void* Wb, void* dSelf, void* dAgg, int64_t ldi, hipStream_t st);
 
 // GCN aggregation (gcn.hip)
-int32_t gcn_aggregate_fwd(const sdt_block* blk, const float* H, int64_t ldh, bool through_src_nodes, int32_t F,
-                          const float* c, const float* s, const float* selfw, float* A, int64_t lda, hipStream_t stm);
+int32_t gcn_aggregate_fwd(const sdt_block* blk, const void* H, int64_t ldh, bool through_src_nodes, int32_t F, int32_t dtype,
+                          const float* c, const float* s, const float* selfw, void* A, int64_t lda, hipStream_t stm);
 
 constexpr int GAT_CHUNK_ROWS = 256;   // rows per partial column sum of the GAT bias / attention-vector gradients
 // GAT attention aggregation inside a training step (gat.hip).  The forward adds `bias` (may be null) and

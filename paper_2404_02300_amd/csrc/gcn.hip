@@ -1,4 +1,4 @@
-// GCN aggregation on sampled blocks (fp32): the degree-normalised neighbour sum with a self term,
+// GCN aggregation on sampled blocks (fp32 or bf16 storage, fp32 sums): the degree-normalised neighbour sum with a self term,
 //   A[i,:] = s[i] * sum_{e in row i} c[col_e] * H[col_e,:] + selfw[i] * H[i,:],
 // its transpose through the transposed block, and the kernel that derives c, s, selfw from the
 // degrees of the partition graph.  Same row-group scheme as the mean aggregation: a group of
@@ -36,6 +36,34 @@ __device__ __forceinline__ void st(float* p, const float (&v)[VE]) {
     else *p = v[0];
 }
 
+// the same for bf16 storage (2-byte elements; VE of them are one 8-, 4- or 2-byte access): widened on the way in,
+// rounded to nearest even on the way out
+struct __attribute__((packed, aligned(4))) h4d { uint32_t lo, hi; };
+template <int VE>
+__device__ __forceinline__ void ld(const bf16_t* p, float (&v)[VE]) {
+    if constexpr (VE == 4) {
+        const h4d t = *reinterpret_cast<const h4d*>(p);
+        v[0] = __uint_as_float(t.lo << 16); v[1] = __uint_as_float(t.lo & 0xFFFF0000u);
+        v[2] = __uint_as_float(t.hi << 16); v[3] = __uint_as_float(t.hi & 0xFFFF0000u);
+    } else if constexpr (VE == 2) {
+        const uint32_t t = *reinterpret_cast<const uint32_t*>(p);
+        v[0] = __uint_as_float(t << 16); v[1] = __uint_as_float(t & 0xFFFF0000u);
+    } else {
+        v[0] = bf16_to_f32(p->bits);
+    }
+}
+template <int VE>
+__device__ __forceinline__ void st(bf16_t* p, const float (&v)[VE]) {
+    if constexpr (VE == 4) {
+        *reinterpret_cast<h4d*>(p) = h4d{(uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16),
+                                         (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16)};
+    } else if constexpr (VE == 2) {
+        *reinterpret_cast<uint32_t*>(p) = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+    } else {
+        p->bits = f32_to_bf16(v[0]);
+    }
+}
+
 // c[j] = 1/sqrt(deg_j + 1) for every source row; s[i] = (deg_i / m_i) / sqrt(deg_i + 1) (0 if the row
 // sampled nothing) and selfw[i] = 1/(deg_i + 1) for every destination row; deg from the graph's CSR.
 __global__ __launch_bounds__(TB) void k_gcn_norm(const int64_t* __restrict__ g_indptr,
@@ -59,13 +87,13 @@ __global__ __launch_bounds__(TB) void k_gcn_norm(const int64_t* __restrict__ g_i
 
 // row_ids (nullable): local row r lives at H[row_ids[r]] (aggregating straight out of the feature
 // matrix through the block's src_nodes).
-template <int VE, int G>
+template <typename T, int VE, int G>
 __global__ __launch_bounds__(TB) void k_gcn_aggregate_fwd(const int32_t* __restrict__ b_indptr,
                                                           const int32_t* __restrict__ cols, const int32_t* counts,
-                                                          const float* __restrict__ H, int64_t ldh,
+                                                          const T* __restrict__ H, int64_t ldh,
                                                           const int32_t* __restrict__ row_ids, int F,
                                                           const float* __restrict__ c, const float* __restrict__ s,
-                                                          const float* __restrict__ selfw, float* __restrict__ A,
+                                                          const float* __restrict__ selfw, T* __restrict__ A,
                                                           int64_t lda) {
     const int n = counts[0];
     const int gl = threadIdx.x % G;
@@ -116,13 +144,13 @@ __global__ __launch_bounds__(TB) void k_gcn_aggregate_fwd(const int32_t* __restr
 
 // dH[j,:] = c[j] * sum over the transposed segment of j of s[i] * dA[i,:] + [j < n_dst] selfw[j] * dA[j,:],
 // zeroed where relu_of[j,:] <= 0 (nullable).
-template <int VE, int G>
+template <typename T, int VE, int G>
 __global__ __launch_bounds__(TB) void k_gcn_aggregate_bwd(const int32_t* __restrict__ t_indptr,
                                                           const int32_t* __restrict__ t_rows, const int32_t* counts,
-                                                          const float* __restrict__ dA, int64_t lda, int F,
+                                                          const T* __restrict__ dA, int64_t lda, int F,
                                                           const float* __restrict__ c, const float* __restrict__ s,
                                                           const float* __restrict__ selfw,
-                                                          const float* __restrict__ relu_of, float* __restrict__ dH,
+                                                          const T* __restrict__ relu_of, T* __restrict__ dH,
                                                           int64_t ldd) {
     const int n_dst = counts[0], n_src = counts[1];
     const int gl = threadIdx.x % G;
@@ -178,13 +206,14 @@ __global__ __launch_bounds__(TB) void k_gcn_aggregate_bwd(const int32_t* __restr
     }
 }
 
-int vec_floats(int F, std::initializer_list<int64_t> lds, std::initializer_list<const void*> ptrs) {
+// widest vector (elements of `es` bytes, at most four) that divides the row width, every stride and every address
+int vec_elems_of(int es, int F, std::initializer_list<int64_t> lds, std::initializer_list<const void*> ptrs) {
     int v = 4;
     auto fit = [&](uint64_t bytes) {
-        while (v > 1 && bytes % (v * 4) != 0) v >>= 1;
+        while (v > 1 && bytes % (uint64_t)(v * es) != 0) v >>= 1;
     };
-    fit((uint64_t)F * 4);
-    for (int64_t l : lds) fit((uint64_t)l * 4);
+    fit((uint64_t)F * es);
+    for (int64_t l : lds) fit((uint64_t)l * es);
     for (const void* p : ptrs) fit(reinterpret_cast<uintptr_t>(p));
     return v;
 }
@@ -212,14 +241,26 @@ inline int rows_grid(int64_t rows, int G) {
 
 }  // namespace
 
-int32_t gcn_aggregate_fwd(const sdt_block* blk, const float* H, int64_t ldh, bool through_src_nodes, int32_t F,
-                          const float* c, const float* s, const float* selfw, float* A, int64_t lda, hipStream_t stm) {
-    // the forward kernel moves its last vector back, so any dword-aligned fp32 row takes the widest vector that fits
-    const int ve = F >= 4 ? 4 : F >= 2 ? 2 : 1;
-    const int G = (F + ve - 1) / ve > 16 ? 64 : 16;
-    SDT_GCN_DISPATCH(ve, G, hipLaunchKernelGGL((k_gcn_aggregate_fwd<VE, GG>), dim3(rows_grid(blk->cap_dst, GG)), dim3(TB),
-                                               0, stm, blk->indptr, blk->cols, blk->counts, H, ldh,
-                                               through_src_nodes ? blk->src_nodes : nullptr, F, c, s, selfw, A, lda));
+int32_t gcn_aggregate_fwd(const sdt_block* blk, const void* H, int64_t ldh, bool through_src_nodes, int32_t F, int32_t dtype,
+                          const float* c, const float* s, const float* selfw, void* A, int64_t lda, hipStream_t stm) {
+    const int32_t* ids = through_src_nodes ? blk->src_nodes : nullptr;
+    if (dtype == SDT_F32) {
+        // the forward kernel moves its last vector back, so any dword-aligned fp32 row takes the widest vector that fits
+        const int ve = F >= 4 ? 4 : F >= 2 ? 2 : 1;
+        const int G = (F + ve - 1) / ve > 16 ? 64 : 16;
+        SDT_GCN_DISPATCH(ve, G, hipLaunchKernelGGL((k_gcn_aggregate_fwd<float, VE, GG>), dim3(rows_grid(blk->cap_dst, GG)),
+                                                   dim3(TB), 0, stm, blk->indptr, blk->cols, blk->counts,
+                                                   static_cast<const float*>(H), ldh, ids, F, c, s, selfw,
+                                                   static_cast<float*>(A), lda));
+    } else {
+        // bf16 rows: whole vectors only (a vector moved back to the row's end would start on an odd element)
+        const int ve = vec_elems_of(2, F, {ldh, lda}, {H, A});
+        const int G = (F + ve - 1) / ve > 16 ? 64 : 16;
+        SDT_GCN_DISPATCH(ve, G, hipLaunchKernelGGL((k_gcn_aggregate_fwd<bf16_t, VE, GG>), dim3(rows_grid(blk->cap_dst, GG)),
+                                                   dim3(TB), 0, stm, blk->indptr, blk->cols, blk->counts,
+                                                   static_cast<const bf16_t*>(H), ldh, ids, F, c, s, selfw,
+                                                   static_cast<bf16_t*>(A), lda));
+    }
     SDT_CHECK_LAUNCH("gcn_aggregate_fwd");
     return SDT_OK;
 }
@@ -245,34 +286,39 @@ extern "C" int32_t sdt_gcn_aggregate_fwd(const sdt_block* blk, const void* H, in
                                          int32_t F, int32_t dtype, const float* c, const float* s, const float* selfw,
                                          void* A, int64_t lda, void* stream) {
     SDT_REQUIRE(blk, SDT_ERR_INVALID_ARG, "sdt_gcn_aggregate_fwd: null block");
-    SDT_REQUIRE(dtype == SDT_F32, SDT_ERR_INVALID_ARG, "sdt_gcn_aggregate_fwd: fp32 only");
+    SDT_REQUIRE(dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_gcn_aggregate_fwd: unknown dtype %d", dtype);
     SDT_REQUIRE(F >= 0 && ldh >= F && lda >= F, SDT_ERR_INVALID_ARG, "sdt_gcn_aggregate_fwd: bad sizes");
     if (blk->cap_dst == 0 || F == 0) return SDT_OK;
     SDT_REQUIRE(blk->counts && blk->indptr && blk->cols && H && A && c && s && selfw &&
                     (!through_src_nodes || blk->src_nodes),
                 SDT_ERR_INVALID_ARG, "sdt_gcn_aggregate_fwd: null pointer");
-    return gcn_aggregate_fwd(blk, static_cast<const float*>(H), ldh, through_src_nodes != 0, F, c, s, selfw,
-                             static_cast<float*>(A), lda, static_cast<hipStream_t>(stream));
+    return gcn_aggregate_fwd(blk, H, ldh, through_src_nodes != 0, F, dtype, c, s, selfw, A, lda,
+                             static_cast<hipStream_t>(stream));
 }
 
 extern "C" int32_t sdt_gcn_aggregate_bwd(const sdt_block* blk, const void* dA, int64_t lda, const void* relu_of,
                                          int32_t F, int32_t dtype, const float* c, const float* s, const float* selfw,
                                          void* dH, int64_t ldd, void* stream) {
     SDT_REQUIRE(blk, SDT_ERR_INVALID_ARG, "sdt_gcn_aggregate_bwd: null block");
-    SDT_REQUIRE(dtype == SDT_F32, SDT_ERR_INVALID_ARG, "sdt_gcn_aggregate_bwd: fp32 only");
+    SDT_REQUIRE(dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_gcn_aggregate_bwd: unknown dtype %d", dtype);
     SDT_REQUIRE(F >= 0 && lda >= F && ldd >= F, SDT_ERR_INVALID_ARG, "sdt_gcn_aggregate_bwd: bad sizes");
     if (blk->cap_src == 0 || F == 0) return SDT_OK;
     SDT_REQUIRE(blk->counts && blk->t_indptr && blk->t_rows && dA && dH && c && s && selfw, SDT_ERR_INVALID_ARG,
                 "sdt_gcn_aggregate_bwd: null pointer (the block needs its transposed arrays)");
-    const float* g = static_cast<const float*>(dA);
-    const float* y = static_cast<const float*>(relu_of);
-    float* out = static_cast<float*>(dH);
-    const int ve = vec_floats(F, {lda, ldd}, {dA, dH, relu_of});
-    const int G = (F + ve - 1) / ve > 16 ? 64 : 16;
     hipStream_t stm = static_cast<hipStream_t>(stream);
-    SDT_GCN_DISPATCH(ve, G, hipLaunchKernelGGL((k_gcn_aggregate_bwd<VE, GG>), dim3(rows_grid(blk->cap_src, GG)), dim3(TB),
-                                               0, stm, blk->t_indptr, blk->t_rows, blk->counts, g, lda, F, c, s, selfw, y,
-                                               out, ldd));
+    const int ve = vec_elems_of((int)dtype_size(dtype), F, {lda, ldd}, {dA, dH, relu_of});
+    const int G = (F + ve - 1) / ve > 16 ? 64 : 16;
+    if (dtype == SDT_F32) {
+        SDT_GCN_DISPATCH(ve, G, hipLaunchKernelGGL((k_gcn_aggregate_bwd<float, VE, GG>), dim3(rows_grid(blk->cap_src, GG)),
+                                                   dim3(TB), 0, stm, blk->t_indptr, blk->t_rows, blk->counts,
+                                                   static_cast<const float*>(dA), lda, F, c, s, selfw,
+                                                   static_cast<const float*>(relu_of), static_cast<float*>(dH), ldd));
+    } else {
+        SDT_GCN_DISPATCH(ve, G, hipLaunchKernelGGL((k_gcn_aggregate_bwd<bf16_t, VE, GG>), dim3(rows_grid(blk->cap_src, GG)),
+                                                   dim3(TB), 0, stm, blk->t_indptr, blk->t_rows, blk->counts,
+                                                   static_cast<const bf16_t*>(dA), lda, F, c, s, selfw,
+                                                   static_cast<const bf16_t*>(relu_of), static_cast<bf16_t*>(dH), ldd));
+    }
     SDT_CHECK_LAUNCH("gcn_aggregate_bwd");
     return SDT_OK;
 }

@@ -178,8 +178,8 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
     int32_t rc = check_model(model, fanouts, "sdt_train_step_layout");
     if (rc != SDT_OK) return rc;
     SDT_REQUIRE(dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_train_step_layout: unknown dtype %d", dtype);
-    SDT_REQUIRE(model->kind == SDT_MODEL_SAGE_MEAN || dtype == SDT_F32, SDT_ERR_INVALID_ARG,
-                "sdt_train_step_layout: the GCN and GAT models are fp32 only");
+    SDT_REQUIRE(model->kind != SDT_MODEL_GAT || dtype == SDT_F32, SDT_ERR_INVALID_ARG,
+                "sdt_train_step_layout: the GAT model is fp32 only");
     SDT_REQUIRE(n_nodes >= 0 && n_nodes <= 0x7FFFFFFF && batch >= 0 && batch <= n_nodes, SDT_ERR_INVALID_ARG,
                 "sdt_train_step_layout: n_nodes=%lld batch=%d", (long long)n_nodes, batch);
     const int L = model->n_layers;
@@ -417,8 +417,8 @@ int32_t step_sample(const StepCtx& c, const StepBuffers& b, const int32_t* seeds
         }
         SDT_REQUIRE(lay.cap_dst[0] == 0 || aligned16(c.X), SDT_ERR_INVALID_ARG, "sdt_train_step: X must be 16-byte aligned");
         StageTimer tm(c.timing, c.slot, SDT_STAGE_AGG_FWD, 0, st);
-        return gcn_aggregate_fwd(&b.blk[0], static_cast<const float*>(c.X), c.ldx, true, d[0], b.gcn_c(lay, 0),
-                                 b.gcn_s(lay, 0), b.gcn_self(lay, 0), static_cast<float*>(b.at(lay.A[0])), d[0], st);
+        return gcn_aggregate_fwd(&b.blk[0], c.X, c.ldx, true, d[0], c.dtype, b.gcn_c(lay, 0), b.gcn_s(lay, 0),
+                                 b.gcn_self(lay, 0), b.at(lay.A[0]), d[0], st);
     }
     if (c.model->kind == SDT_MODEL_GAT) {
         // every frontier row is projected, so every one is gathered
@@ -449,6 +449,8 @@ int32_t step_compute_gcn(const StepCtx& c, const StepBuffers& b, const int32_t* 
     const int L = model->n_layers;
     const int32_t* d = model->dims;
     sdt_timing* timing = c.timing;
+    const int32_t dtype = c.dtype;
+    const size_t es = dtype_size(dtype);
     int32_t rc;
     const int hl = d[L - 1] / 2;
     const bool fused_head = head_supported(hl, d[L]) && aligned16(model->W[L - 1]);
@@ -463,20 +465,23 @@ int32_t step_compute_gcn(const StepCtx& c, const StepBuffers& b, const int32_t* 
     }
     PendingReduce pending[SDT_MAX_LAYERS];
     int n_pending = 0;
-    auto half0 = [&](int l) { return static_cast<float*>(b.at(lay.A[l])); };
-    auto half1 = [&](int l) { return static_cast<float*>(b.at(lay.A[l])) + d[l] / 2; };
+    // bf16 storage: the products take the operands widened on the way into LDS and the weights rounded to bf16
+    // where they enter (the general kernels; the bf16 weight images of the GraphSAGE kind have another shape)
+    auto half0 = [&](int l) { return static_cast<char*>(b.at(lay.A[l])); };
+    auto half1 = [&](int l) { return static_cast<char*>(b.at(lay.A[l])) + (size_t)(d[l] / 2) * es; };
     for (int l = 0; l < L; ++l) {
         if (l > 0) {
             StageTimer tm(timing, c.slot, SDT_STAGE_AGG_FWD, l, st);
-            rc = sdt_gcn_aggregate_fwd(&b.blk[l], b.at(lay.H[l]), d[l], 0, d[l], SDT_F32, b.gcn_c(lay, l), b.gcn_s(lay, l),
+            rc = sdt_gcn_aggregate_fwd(&b.blk[l], b.at(lay.H[l]), d[l], 0, d[l], dtype, b.gcn_c(lay, l), b.gcn_s(lay, l),
                                        b.gcn_self(lay, l), b.at(lay.A[l]), d[l], st);
             if (rc != SDT_OK) return rc;
         }
         const bool last = l == L - 1;
         if (last && fused_head) break;
         StageTimer tm(timing, c.slot, SDT_STAGE_LINEAR_FWD, l, st);
-        rc = sdt_sage_linear_fwd(half0(l), d[l], half1(l), d[l], lay.cap_dst[l], b.blk[l].counts, d[l] / 2, d[l + 1],
-                                 model->W[l], model->b[l], last ? 0 : 1, SDT_F32, b.at(lay.H[l + 1]), d[l + 1], SDT_F32, st);
+        rc = linear_fwd(half0(l), d[l], half1(l), d[l], lay.cap_dst[l], b.blk[l].counts, d[l] / 2, d[l + 1], model->W[l],
+                        model->b[l], last ? 0 : 1, dtype, b.at(lay.H[l + 1]), d[l + 1], last ? SDT_F32 : dtype,
+                        /*rows_padded=*/false, st);
         if (rc != SDT_OK) return rc;
     }
     if (!fused_head) {
@@ -486,11 +491,12 @@ int32_t step_compute_gcn(const StepCtx& c, const StepBuffers& b, const int32_t* 
         if (rc != SDT_OK) return rc;
     }
     const void* dY = b.at(lay.dZ);
+    int32_t dy_dtype = SDT_F32;
     for (int l = L - 1; l >= 0; --l) {
         float* dW = model->dW[l] ? model->dW[l] : static_cast<float*>(b.at(lay.dW[l]));
         float* db = model->db[l] ? model->db[l] : static_cast<float*>(b.at(lay.db[l]));
         const bool inner = l > 0;
-        float* dA = inner ? static_cast<float*>(b.at(lay.dAgg[l])) : nullptr;   // gradient w.r.t. the aggregated row
+        char* dA = inner ? static_cast<char*>(b.at(lay.dAgg[l])) : nullptr;   // gradient w.r.t. the aggregated row
         BwdExtras ex;
         ex.defer = &pending[n_pending++];
         ex.W_upd = model->W[l];
@@ -501,26 +507,27 @@ int32_t step_compute_gcn(const StepCtx& c, const StepBuffers& b, const int32_t* 
                 float *P, *Q;
                 {
                     StageTimer th(timing, c.slot, SDT_STAGE_HEAD, l, st);
-                    rc = head_fwd_bwd(half0(l), d[l], half1(l), d[l], c.batch, hl, d[l + 1], model->W[l], model->b[l], SDT_F32,
+                    rc = head_fwd_bwd(half0(l), d[l], half1(l), d[l], c.batch, hl, d[l + 1], model->W[l], model->b[l], dtype,
                                       c.labels, seeds, static_cast<float*>(b.at(lay.H[L])), static_cast<float*>(b.at(lay.dZ)),
-                                      static_cast<float*>(b.at(lay.row_loss)), dA, inner ? dA + hl : nullptr, d[l],
+                                      static_cast<float*>(b.at(lay.row_loss)), dA, inner ? dA + (size_t)hl * es : nullptr, d[l],
                                       b.at(scr_off[l]), scr_len[l], &P, &Q, st);
                 }
                 if (rc != SDT_OK) return rc;
                 rc = reduce_partials(P, Q, head_splits(c.batch), hl, d[l + 1], dW, db, ex, st);
             } else {
-                rc = linear_bwd(dY, d[l + 1], SDT_F32, nullptr, 0, 0, half0(l), d[l], half1(l), d[l], lay.cap_dst[l],
-                                b.blk[l].counts, d[l] / 2, d[l + 1], model->W[l], SDT_F32, dW, db, dA,
-                                inner ? dA + d[l] / 2 : nullptr, d[l], b.at(scr_off[l]), scr_len[l], ex, st);
+                rc = linear_bwd(dY, d[l + 1], dy_dtype, nullptr, 0, 0, half0(l), d[l], half1(l), d[l], lay.cap_dst[l],
+                                b.blk[l].counts, d[l] / 2, d[l + 1], model->W[l], dtype, dW, db, dA,
+                                inner ? dA + (size_t)(d[l] / 2) * es : nullptr, d[l], b.at(scr_off[l]), scr_len[l], ex, st);
             }
             if (rc != SDT_OK) return rc;
         }
         if (inner) {
             StageTimer tm(timing, c.slot, SDT_STAGE_AGG_BWD, l, st);
-            rc = sdt_gcn_aggregate_bwd(&b.blk[l], dA, d[l], b.at(lay.H[l]), d[l], SDT_F32, b.gcn_c(lay, l), b.gcn_s(lay, l),
+            rc = sdt_gcn_aggregate_bwd(&b.blk[l], dA, d[l], b.at(lay.H[l]), d[l], dtype, b.gcn_c(lay, l), b.gcn_s(lay, l),
                                        b.gcn_self(lay, l), b.at(lay.dH[l]), d[l], st);
             if (rc != SDT_OK) return rc;
             dY = b.at(lay.dH[l]);
+            dy_dtype = dtype;
         }
     }
     for (int k = 0; k < n_pending; ++k) attach_moments(&pending[k], model, L - 1 - k);   // queued last layer first

@@ -542,6 +542,53 @@ def test_gcn_step_gradients_match_autograd_on_a_dense_formulation():
         assert np.allclose(ref["W_new"][l], W[l] - 0.1 * Wt[l].grad.numpy(), rtol=1e-12, atol=1e-13)
 
 
+def test_gcn_step_bf16_rounding_points():
+    """bf16 storage of the GCN step: the forward equals a float64 computation in which torch's own bf16 cast (an
+    independent round-to-nearest-even) is applied to the aggregated rows, the weights and the hidden activations;
+    the stored gradients are bf16 numbers; everything stays within the bf16 tolerance of the unrounded step."""
+    rng = np.random.default_rng(29)
+    n, dims = 60, [8, 10, 4]
+    rows, indptr, indices = _small_graph(rng, n, 6)
+    Xb = torch.tensor(rng.standard_normal((n, dims[0])), dtype=torch.float32).to(torch.bfloat16)
+    bits = Xb.view(torch.int16).numpy().view(np.uint16)
+    X64 = Xb.to(torch.float64).numpy()
+    y = rng.integers(0, dims[2], size=n).astype(np.int32)
+    W = [rng.standard_normal((dims[l], dims[l + 1])) * 0.4 for l in range(2)]
+    b = [rng.standard_normal(dims[l + 1]) * 0.1 for l in range(2)]
+    seeds = np.array([2, 7, 19, 41, 55, 13], dtype=np.int32)
+    ref = orc.gcn_train_step(indptr, indices, bits, y, seeds, [4, 3], W, b, seed=5, step=2, lr=0.1, bf16=True)
+    plain = orc.gcn_train_step(indptr, indices, X64.astype(np.float32), y, seeds, [4, 3], W, b, seed=5, step=2, lr=0.1,
+                               blocks=ref["blocks"])
+    cast = lambda t: t.to(torch.bfloat16).to(torch.float64)
+    H = torch.tensor(X64[ref["blocks"][0].src_nodes])
+    for l, blk in enumerate(ref["blocks"]):
+        s, c, selfw = ref["weights"][l]
+        Pm = np.zeros((blk.n_dst, blk.n_src))
+        for i in range(blk.n_dst):
+            for e in range(blk.indptr[i], blk.indptr[i + 1]):
+                Pm[i, blk.cols[e]] += s[i] * c[blk.cols[e]]
+            Pm[i, i] += selfw[i]
+        A = cast(torch.tensor(Pm) @ H)
+        # (the two float64 sums may differ in their last bit, which can move a value across a rounding boundary: then
+        # the two results are neighbouring bf16 numbers; that may happen at a few elements, no more)
+        off = ref["A"][l] != A.numpy()
+        assert off.mean() <= 0.01 and np.all(np.abs(ref["A"][l] - A.numpy())[off] <= 2.0 ** -7 * np.abs(A.numpy())[off])
+        Z = torch.tensor(ref["A"][l]) @ cast(torch.tensor(W[l])) + torch.tensor(b[l])
+        H = cast(torch.relu(Z)) if l == 0 else Z
+        off = ref["H"][l + 1] != H.numpy()
+        assert off.mean() <= 0.01 and np.all(np.abs(ref["H"][l + 1] - H.numpy())[off] <= 2.0 ** -7 * np.abs(H.numpy())[off] + 1e-13)
+        H = torch.tensor(ref["H"][l + 1])
+    def is_bf16(a):
+        t = torch.tensor(a)
+        return bool(torch.equal(cast(t), t))
+    assert is_bf16(ref["A"][0]) and is_bf16(ref["A"][1]) and is_bf16(ref["H"][1]) and is_bf16(ref["dA"][1]) and is_bf16(ref["dH"][1])
+    assert not is_bf16(ref["H"][2]) and not is_bf16(ref["dW"][0])          # logits and weight gradients are not rounded
+    for k in ("dW", "db", "W_new"):
+        for l in range(2):
+            assert np.max(np.abs(ref[k][l] - plain[k][l])) <= 2e-2 * np.max(np.abs(plain[k][l])), (k, l)
+    assert abs(ref["loss"] - plain["loss"]) <= 2e-2 * abs(plain["loss"])
+
+
 # ----------------------------------------------------------------- Adam
 def test_adam_matches_library_optimiser():
     rng = np.random.default_rng(31)

@@ -89,7 +89,7 @@ def main():
                     help="comma-separated further step workloads measured after the main one (steps/s and the loss check only; "
                          "'none' to skip); ignored unless the main workload is the default")
     ap.add_argument("--model", default="sage", choices=["sage", "gcn", "gat"],
-                    help="gcn / gat: the same step with the GCN or GAT model kind (fp32 workloads; not the headline metric)")
+                    help="gcn / gat: the same step with the GCN or GAT model kind (GAT: fp32 workloads only; not the headline metric)")
     ap.add_argument("--lr", type=float, default=0.01)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial", action="store_true", help="no auxiliary stream: every step strictly in sequence")
@@ -171,7 +171,7 @@ def bench_step(args, workload, full):
     gcn = args.model == "gcn" or gat      # one weight matrix per layer
     att_h = att = None
     if gcn:     # one [in, out] matrix per layer, Glorot-uniform from the workload's seed
-        assert not wl.bf16, "the GCN and GAT model kinds are fp32 only"
+        assert not (gat and wl.bf16), "the GAT model kind is fp32 only"
         rng = np.random.default_rng(wl.seed)
         Wh = [(rng.uniform(-1, 1, size=(wl.dims[l], wl.dims[l + 1])) *
                np.sqrt(6.0 / (wl.dims[l] + wl.dims[l + 1]))).astype(np.float32) for l in range(len(wl.fanouts))]
@@ -356,7 +356,8 @@ def bench_step(args, workload, full):
             # (2.5 PFLOP/s / 8 TB/s = 312 flop/B against ~128 flop/B here), so it is priced by the bytes it
             # must move: both operands and the weights in, the output rows out
             if wl.bf16:
-                return "hbm", n_dst * (2 * d[l] + d[l + 1]) * es + 2 * d[l] * d[l + 1] * 2, "k_fwd_bf16"
+                return "hbm", n_dst * (wf * d[l] + d[l + 1]) * es + wf * d[l] * d[l + 1] * 2, \
+                       "k_linear_fwd (bf16 operands widened on the way into LDS)" if gcn else "k_fwd_bf16"
             return "mfma", 2.0 * n_dst * wf * d[l] * d[l + 1], \
                    "k_linear_fwd_x3 (+ k_x3_transpose_w before, k_linear_fwd_x3_finish after: the stage is three launches)" \
                    if x3_fwd(l) else "k_linear_fwd"
@@ -417,7 +418,7 @@ def bench_step(args, workload, full):
                                    wl.seed, s, args.lr)
             elif gcn:
                 orc.gcn_train_step(inst.indptr, inst.indices, inst.X, inst.y, inst.batch(s), wl.fanouts, Wh, inst.b,
-                                   wl.seed, s, args.lr)
+                                   wl.seed, s, args.lr, bf16=wl.bf16)
             else:
                 orc.train_step(inst.indptr, inst.indices, inst.X, inst.y, inst.batch(s), wl.fanouts, inst.W, inst.b,
                                wl.seed, s, args.lr, bf16=wl.bf16)

@@ -57,10 +57,12 @@ def test_model_kinds_layouts_and_their_argument_checks():
         m.kind, m.gat_slope = bad_kind, 0.2
         with pytest.raises(B.SdtError):
             B.sdt_train_step_layout(1 << 14, 256, f, m, B.SDT_F32)
-        m = _model([64, 64, 8])
-        m.kind, m.gat_slope = bad_kind, 0.2
-        with pytest.raises(B.SdtError):
-            B.sdt_train_step_layout(1 << 14, 256, f, m, B.SDT_BF16)      # fp32 only
+    gcn16 = B.sdt_train_step_layout(1 << 14, 256, f, gcn, B.SDT_BF16)     # GCN: fp32 or bf16 storage
+    assert gcn16.norm[1] != 0 and gcn16.total_bytes < B.sdt_train_step_layout(1 << 14, 256, f, gcn, B.SDT_F32).total_bytes
+    gat16 = _model([64, 64, 8])
+    gat16.kind, gat16.gat_slope = B.SDT_MODEL_GAT, 0.2
+    with pytest.raises(B.SdtError):
+        B.sdt_train_step_layout(1 << 14, 256, f, gat16, B.SDT_BF16)       # GAT: fp32 only
     gat.gat_slope = 1.5
     with pytest.raises(B.SdtError):
         B.sdt_train_step_layout(1 << 14, 256, f, gat, B.SDT_F32)

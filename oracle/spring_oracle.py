@@ -46,36 +46,47 @@ from typing import Dict, List, Sequence, Tuple
 
 
 def stream_clustering(n: int, degree: Sequence[int], edges: Sequence[Tuple[int, int]], tau_vol: int):
-    """Alg. 1, node clustering.  Returns (cluster[n], volume list, richest[n]);
-    clusters are numbered from 0 in order of creation, richest[v] = -1 if v has
-    no neighbour."""
-    cluster = [-1] * n
-    richest = [-1] * n
-    vol: List[int] = []
+    """Alg. 1, node clustering.  Returns (cluster[n], volume list, richest[n]); clusters are numbered from 0
+    in order of creation, richest[v] = -1 if v has no neighbour.
+
+    Written from the definitions rather than as the algorithm's bookkeeping: a cluster IS its set of
+    members, its volume is recomputed as the sum of its members' degrees whenever a decision needs it
+    (so no running volume can drift from the membership), and a node's richest neighbour is read off
+    the list of neighbours the stream has shown it, once, at the end."""
+    members: List[set] = []                  # cluster number -> nodes in it now
+    home = [-1] * n                          # node -> its cluster number (-1: not seen yet)
+    shown: List[List[int]] = [[] for _ in range(n)]   # node -> neighbours in the order the stream showed them
+
+    def volume(c: int) -> int:
+        return sum(degree[x] for x in members[c])
+
+    def join_stream(x: int) -> None:
+        if home[x] < 0:
+            home[x] = len(members)
+            members.append({x})
+
     for u, v in edges:
-        for x in (u, v):
-            if cluster[x] < 0:
-                cluster[x] = len(vol)
-                vol.append(degree[x])
-        cu, cv = cluster[u], cluster[v]
-        if cu != cv and vol[cu] <= tau_vol and vol[cv] <= tau_vol:
-            if vol[cu] <= vol[cv]:
-                vol[cu] -= degree[u]
-                vol[cv] += degree[u]
-                cluster[u] = cv
-            else:
-                vol[cv] -= degree[v]
-                vol[cu] += degree[v]
-                cluster[v] = cu
-        if richest[u] < 0 or degree[richest[u]] < degree[v]:
-            richest[u] = v
-        if richest[v] < 0 or degree[richest[v]] < degree[u]:
-            richest[v] = u
+        join_stream(u)
+        join_stream(v)
+        cu, cv = home[u], home[v]
+        if cu != cv:
+            vol_u, vol_v = volume(cu), volume(cv)
+            if vol_u <= tau_vol and vol_v <= tau_vol:
+                # the endpoint of the lighter cluster changes sides (the first endpoint when they weigh the same)
+                mover, src, dst = (u, cu, cv) if vol_u <= vol_v else (v, cv, cu)
+                members[src].discard(mover)
+                members[dst].add(mover)
+                home[mover] = dst
+        shown[u].append(v)
+        shown[v].append(u)
     for x in range(n):                       # nodes the stream never showed
-        if cluster[x] < 0:
-            cluster[x] = len(vol)
-            vol.append(degree[x])
-    return cluster, vol, richest
+        join_stream(x)
+    richest = [-1] * n
+    for x in range(n):
+        if shown[x]:
+            top = max(degree[w] for w in shown[x])
+            richest[x] = next(w for w in shown[x] if degree[w] == top)     # the first one shown among equals
+    return home, [volume(c) for c in range(len(members))], richest
 
 
 def merge_clusters(n: int, degree: Sequence[int], cluster: Sequence[int], richest: Sequence[int], p: int,

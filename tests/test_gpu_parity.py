@@ -461,22 +461,27 @@ def test_train_step_wide_first_layer_padded_rows(feat):
     _run_and_check(inst, wl, steps=2, check_float_steps=(0, 1))
 
 
-@pytest.mark.parametrize("name,feat,hidden,layers,fanouts,batch,deg", [
+@pytest.mark.parametrize("name,kind,log2n,feat,hidden,layers,fanouts,batch,deg,steps", [
     # three layers: layer 0 (260 -> 256, rows padded to 288 floats) and layer 1 (256 -> 256, 2 560 rows at most) both take the
     # split-bf16 forward and weight gradient; layer 1 also returns input gradients from the fp32 kernel
-    ("x3-three-layers", 260, 256, 3, [6, 5, 4], 512, 12),
+    ("x3-three-layers", "rmat", 13, 260, 256, 3, [6, 5, 4], 512, 12, 2),
     # the narrowest output the path takes (132 columns: one full and one ragged 32-column block per wave), 18 row tiles
-    ("x3-narrow-out", 512, 132, 2, [10, 8], 256, 16),
+    ("x3-narrow-out", "rmat", 13, 512, 132, 2, [10, 8], 256, 16, 2),
     # a sparse graph: the frontier stays far below its upper bound, so the device picks the largest split
-    ("x3-small-frontier", 300, 200, 2, [12, 10], 256, 2),
+    ("x3-small-frontier", "rmat", 13, 300, 200, 2, [12, 10], 256, 2, 2),
+    # more than 128 row tiles (about 21 000 frontier rows of at most 31 500, dense neighbourhoods): the device deals
+    # nothing out, one workgroup per tile and a single partial plane
+    ("x3-no-split", "chunglu", 17, 256, 256, 2, [8, 20], 1500, 200, 1),
 ])
-def test_train_step_split_bf16_projection_shapes(name, feat, hidden, layers, fanouts, batch, deg):
+def test_train_step_split_bf16_projection_shapes(name, kind, log2n, feat, hidden, layers, fanouts, batch, deg, steps):
     # fp32 layers with a wide output, a long reduction and few row tiles run on the bf16 matrix cores through exact
     # three-way splits (csrc/linear_x3.hip); the bar is the fp32 one
     _say(f"train step, split-bf16 projections: {name}")
-    wl = gen.Workload(name, "rmat", 13, deg, feat, 7, hidden, layers, fanouts, batch, 23, 1, owned_frac=0.5)
+    wl = gen.Workload(name, kind, log2n, deg, feat, 7, hidden, layers, fanouts, batch, 23, 1, owned_frac=0.5)
     inst = gen.make_instance(wl)
-    _run_and_check(inst, wl, steps=2, check_float_steps=(0, 1))
+    run, _ = _run_and_check(inst, wl, steps=steps, check_float_steps=tuple(range(steps)))
+    if name == "x3-no-split":
+        assert int(run.counts(0)[0]) > 128 * 128, "the case is meant to have more than 128 row tiles"
 
 
 def test_train_step_ragged_dims_fp32():

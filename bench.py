@@ -89,7 +89,7 @@ def main():
                     help="comma-separated further step workloads measured after the main one (steps/s and the loss check only; "
                          "'none' to skip); ignored unless the main workload is the default")
     ap.add_argument("--model", default="sage", choices=["sage", "gcn", "gat"],
-                    help="gcn / gat: the same step with the GCN or GAT model kind (GAT: fp32 workloads only; not the headline metric)")
+                    help="gcn / gat: the same step with the GCN or GAT model kind (not the headline metric)")
     ap.add_argument("--lr", type=float, default=0.01)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial", action="store_true", help="no auxiliary stream: every step strictly in sequence")
@@ -171,7 +171,6 @@ def bench_step(args, workload, full):
     gcn = args.model == "gcn" or gat      # one weight matrix per layer
     att_h = att = None
     if gcn:     # one [in, out] matrix per layer, Glorot-uniform from the workload's seed
-        assert not (gat and wl.bf16), "the GAT model kind is fp32 only"
         rng = np.random.default_rng(wl.seed)
         Wh = [(rng.uniform(-1, 1, size=(wl.dims[l], wl.dims[l + 1])) *
                np.sqrt(6.0 / (wl.dims[l] + wl.dims[l + 1]))).astype(np.float32) for l in range(len(wl.fanouts))]
@@ -317,9 +316,9 @@ def bench_step(args, workload, full):
             if kind == "gather":
                 return "hbm", n_src * (2 * d[0] * es + 4), "k_gather"
             if kind == "aggregate_fwd":   # scores over every source row, then two score passes and one row pass per edge
-                return "hbm", n_src * F * 4 + nnz * (F * 4 + 12) + n_dst * (2 * F * 4 + 16), "k_gat_scores + k_gat_fwd"
+                return "hbm", n_src * F * es + nnz * (F * es + 12) + n_dst * (2 * F * es + 16), "k_gat_scores + k_gat_fwd"
             if kind == "aggregate_bwd":   # two dot-product passes per edge on each side + the weighted sums
-                return "hbm", nnz * (5 * F * 4 + 16) + n_src * 3 * F * 4 + n_dst * 3 * F * 4, \
+                return "hbm", nnz * (5 * F * es + 16) + n_src * 3 * F * es + n_dst * 3 * F * es, \
                        "k_gat_mask_bias + k_gat_bwd_dst + k_gat_bwd_src + k_gat_vec_partials"
             if kind == "linear_fwd":
                 return "mfma", 2.0 * n_src * d[l] * F, "k_linear_fwd"
@@ -415,7 +414,7 @@ def bench_step(args, workload, full):
             s = ns
             if gat:
                 orc.gat_train_step(inst.indptr, inst.indices, inst.X, inst.y, inst.batch(s), wl.fanouts, Wh, inst.b, att_h,
-                                   wl.seed, s, args.lr)
+                                   wl.seed, s, args.lr, bf16=wl.bf16)
             elif gcn:
                 orc.gcn_train_step(inst.indptr, inst.indices, inst.X, inst.y, inst.batch(s), wl.fanouts, Wh, inst.b,
                                    wl.seed, s, args.lr, bf16=wl.bf16)

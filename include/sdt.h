@@ -130,7 +130,9 @@ typedef struct sdt_model {
      * frontier row, the attention aggregation of sdt_gat_aggregate_fwd with
      * a_src = att[l][0:out], a_dst = att[l][out:2out], ReLU on all but the last layer.
      * att[l] fp32 [2*dims[l+1]] is trained like a bias: datt (nullable) receives its gradient,
-     * matt/vatt are its Adam moments.  fp32 storage and even dims[0..L-1] only. */
+     * matt/vatt are its Adam moments.  fp32 or bf16 storage (bf16: the gathered rows, z, the hidden
+     * activations and the gradients w.r.t. them; scores, sums, logits and parameters stay fp32), even
+     * dims[0..L-1] only. */
     float *att[SDT_MAX_LAYERS];
     float *datt[SDT_MAX_LAYERS];
     float *matt[SDT_MAX_LAYERS];
@@ -177,8 +179,8 @@ typedef struct sdt_step_layout {
     uint64_t wlow;     /* internal: bf16 images of the weights (bf16 workloads only) */
     uint64_t norm[SDT_MAX_LAYERS]; /* GCN only: fp32 c[cap_src] | s[cap_dst] | selfw[cap_dst], each 256-byte aligned */
     /* GAT only.  H[0] then holds EVERY frontier row of layer 0, [cap_src[0], dims[0]], H[l+1] is
-     * act(attention output + b); z[l] = H[l] W[l] and dz[l] = d loss / d z[l] are fp32
-     * [cap_src[l], dims[l+1]]; dH[l] (l >= 1) is d loss / d H[l] with the ReLU mask applied;
+     * act(attention output + b); z[l] = H[l] W[l] and dz[l] = d loss / d z[l] are
+     * [cap_src[l], dims[l+1]] in the storage type; dH[l] (l >= 1) is d loss / d H[l] with the ReLU mask applied;
      * datt[l] fp32 [2*dims[l+1]]; t_indptr/t_rows exist for every layer; A, dSelf, dAgg are unused. */
     uint64_t z[SDT_MAX_LAYERS];
     uint64_t dz[SDT_MAX_LAYERS];

@@ -483,27 +483,33 @@ def gat_aggregate_bwd(b_indptr, b_cols, z, a_src, a_dst, g, slope: float = 0.2):
 
 
 def gat_train_step(indptr, indices, X, y, seeds, fanouts, W, b, att, seed: int, step: int, lr: float,
-                   slope: float = 0.2, blocks: Optional[List[Block]] = None, relu_masks=None):
+                   slope: float = 0.2, blocks: Optional[List[Block]] = None, relu_masks=None, bf16: bool = False):
     """One mini-batch step of a single-head GAT (Sec. III-E names GAT as an integrated model and
     Sec. III-C as the most expensive one; the variant is not described).  Layer l projects EVERY
     frontier row, z = H_l W_l (W_l [in_l, out_l], no bias inside the attention), aggregates with
     gat_aggregate_fwd using att[l] = [a_src | a_dst] (2 out_l values), adds b_l and applies ReLU on
-    all but the last layer; sampling, loss and SGD as in train_step.  fp32 storage only."""
+    all but the last layer; sampling, loss and SGD as in train_step.  With bf16=True X holds bf16 bit
+    patterns (uint16) and what is stored between kernels is rounded when produced: the projected rows z,
+    the hidden activations and the gradients w.r.t. both; the weights are rounded where they enter a
+    matrix product; the attention vectors and scalars, the logits, the loss gradient (it enters no matrix
+    product here), dW, db and datt are not rounded."""
+    rnd = round_bf16 if bf16 else (lambda t: t)
     L = len(fanouts)
     if blocks is None:
         blocks = sample_blocks(indptr, indices, seeds, fanouts, seed, step)
-    H = [gather_rows(X, blocks[0].src_nodes).astype(np.float64)]
+    Xrows = gather_rows(X, blocks[0].src_nodes)
+    H = [bf16_bits_to_f64(Xrows) if bf16 else Xrows.astype(np.float64)]
     W = [np.asarray(w, dtype=np.float64) for w in W]
     b = [np.asarray(v, dtype=np.float64) for v in b]
     att = [np.asarray(v, dtype=np.float64) for v in att]
     Z = []
     for l, blk in enumerate(blocks):
         F = W[l].shape[1]
-        z = H[l] @ W[l]
+        z = rnd(H[l] @ rnd(W[l]))
         out, _, _ = gat_aggregate_fwd(blk.indptr, blk.cols, z, att[l][:F], att[l][F:], slope)
         pre = out + b[l]
         Z.append(z)
-        H.append(np.maximum(pre, 0.0) if l < L - 1 else pre)
+        H.append(rnd(np.maximum(pre, 0.0)) if l < L - 1 else pre)
     loss, dZ = softmax_xent(H[L], np.asarray(y)[np.asarray(seeds)])
     dW, db, datt, dz, dHs = [None] * L, [None] * L, [None] * L, [None] * L, [None] * L
     g = dZ
@@ -517,10 +523,11 @@ def gat_train_step(indptr, indices, X, y, seeds, fanouts, W, b, att, seed: int, 
             g = g * keep
         db[l] = g.sum(axis=0)
         dz[l], da_src, da_dst = gat_aggregate_bwd(blk.indptr, blk.cols, Z[l], att[l][:F], att[l][F:], g, slope)
+        dz[l] = rnd(dz[l])
         datt[l] = np.concatenate([da_src, da_dst])
         dW[l] = H[l].T @ dz[l]
         if l > 0:
-            g = dz[l] @ W[l].T
+            g = rnd(dz[l] @ rnd(W[l]).T)
             dHs[l] = g
     W_new = [sgd(W[l], dW[l], lr) for l in range(L)]
     b_new = [sgd(b[l], db[l], lr) for l in range(L)]

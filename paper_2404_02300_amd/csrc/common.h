@@ -306,15 +306,16 @@ constexpr int GAT_CHUNK_ROWS = 256;   // rows per partial column sum of the GAT 
 // GAT attention aggregation inside a training step (gat.hip).  The forward adds `bias` (may be null) and
 // applies ReLU if asked; the backward leaves the attention-vector partial sums part[n_part][2 F]
 // (a_src half, a_dst half) in the workspace for the step's single reduction launch.
-int32_t gat_forward(const sdt_block* blk, const float* z, int64_t ldz, int32_t F, const float* a_src, const float* a_dst,
-                    float slope, const float* bias, int32_t relu, float* out, int64_t ldo, void* ws, size_t ws_bytes,
-                    hipStream_t st);
-int32_t gat_backward(const sdt_block* blk, const float* z, int64_t ldz, int32_t F, const float* a_src, const float* a_dst,
-                     float slope, const float* g, int64_t ldg, float* dz, int64_t lddz, void* ws, size_t ws_bytes,
-                     const float** part, int32_t* n_part, hipStream_t st);
+// z (and dz) may be stored in bf16; `out` and `g` then in bf16 or fp32 (the last layer's logits and loss gradient).
+int32_t gat_forward(const sdt_block* blk, const void* z, int64_t ldz, int32_t F, int32_t z_dtype, const float* a_src,
+                    const float* a_dst, float slope, const float* bias, int32_t relu, void* out, int64_t ldo, int32_t out_dtype,
+                    void* ws, size_t ws_bytes, hipStream_t st);
+int32_t gat_backward(const sdt_block* blk, const void* z, int64_t ldz, int32_t F, int32_t z_dtype, const float* a_src,
+                     const float* a_dst, float slope, const void* g, int64_t ldg, int32_t g_dtype, void* dz, int64_t lddz,
+                     void* ws, size_t ws_bytes, const float** part, int32_t* n_part, hipStream_t st);
 // g[r, :] = 0 where Y[r, :] <= 0 (Y may be null: no mask), in place, and the column sums of the result over
-// chunks of rows: Qb[n_chunks][F] in the workspace (rows beyond the block's n_dst count as zero)
-int32_t gat_mask_bias(const sdt_block* blk, float* g, int64_t ldg, const float* Y, int64_t ldy, int32_t F, void* ws,
+// chunks of rows: Qb[n_chunks][F] in the workspace (rows beyond the block's n_dst count as zero); g and Y of type `dtype`
+int32_t gat_mask_bias(const sdt_block* blk, void* g, int64_t ldg, const void* Y, int64_t ldy, int32_t F, int32_t dtype, void* ws,
                       size_t ws_bytes, const float** Qb, int32_t* n_chunks, hipStream_t st);
 
 // number of step workspaces sdt_train_loop rotates through (its workspace is that many step layouts)

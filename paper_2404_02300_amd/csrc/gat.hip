@@ -1,4 +1,5 @@
-// Single-head graph-attention aggregation over a sampled block (fp32), forward and backward.
+// Single-head graph-attention aggregation over a sampled block, forward and backward; feature rows in fp32 or
+// bf16 storage (widened on load, rounded on store), every sum and the attention scalars in fp32.
 //   s_(i<-j) = LeakyReLU(a_dst . z_i + a_src . z_j) over row i's edges and the self edge j = i,
 //   alpha = softmax over that set, out_i = sum alpha_(i<-j) z_j.
 // One wavefront per row everywhere: lane l owns features l, l+64, ...; dot products are reduced
@@ -28,6 +29,19 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 __device__ __forceinline__ float leaky(float x, float slope) { return x > 0.f ? x : slope * x; }
 
+// four consecutive features of a row, widened to fp32 / rounded from it
+__device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ float4 ld4(const bf16_t* p) {
+    const uint2 t = *reinterpret_cast<const uint2*>(p);
+    return make_float4(__uint_as_float(t.x << 16), __uint_as_float(t.x & 0xFFFF0000u), __uint_as_float(t.y << 16),
+                       __uint_as_float(t.y & 0xFFFF0000u));
+}
+__device__ __forceinline__ void st4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+__device__ __forceinline__ void st4(bf16_t* p, float4 v) {
+    *reinterpret_cast<uint2*>(p) = make_uint2((uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16),
+                                              (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16));
+}
+
 struct GatWs {
     float *el, *er, *lse, *t, *der, *del, *part, *biasq;
     int nblk, nchunk;
@@ -52,7 +66,8 @@ GatWs gat_ws(void* base, int32_t cap_src, int32_t cap_dst, int32_t F) {
 }
 
 // el[j] = z_j . a_src (all source rows), er[i] = z_i . a_dst (destination rows)
-__global__ __launch_bounds__(TB) void k_gat_scores(const int32_t* counts, const float* __restrict__ z, int64_t ldz, int F,
+template <typename TZ>
+__global__ __launch_bounds__(TB) void k_gat_scores(const int32_t* counts, const TZ* __restrict__ z, int64_t ldz, int F,
                                                    const float* __restrict__ a_src, const float* __restrict__ a_dst,
                                                    float* __restrict__ el, float* __restrict__ er) {
     const int n_dst = counts[0], n_src = counts[1];
@@ -60,7 +75,7 @@ __global__ __launch_bounds__(TB) void k_gat_scores(const int32_t* counts, const 
     for (int j = blockIdx.x * WPB + (threadIdx.x >> 6); j < n_src; j += gridDim.x * WPB) {
         float sl = 0.f, sr = 0.f;
         for (int f = lane; f < F; f += 64) {
-            const float v = z[(int64_t)j * ldz + f];
+            const float v = to_f32(z[(int64_t)j * ldz + f]);
             sl += v * a_src[f];
             sr += v * a_dst[f];
         }
@@ -73,11 +88,12 @@ __global__ __launch_bounds__(TB) void k_gat_scores(const int32_t* counts, const 
     }
 }
 
+template <typename TZ, typename TO>
 __global__ __launch_bounds__(TB) void k_gat_fwd(const int32_t* __restrict__ b_indptr, const int32_t* __restrict__ cols,
-                                                const int32_t* counts, const float* __restrict__ z, int64_t ldz, int F,
+                                                const int32_t* counts, const TZ* __restrict__ z, int64_t ldz, int F,
                                                 const float* __restrict__ el, const float* __restrict__ er, float slope,
                                                 float* __restrict__ lse, const float* __restrict__ bias, int relu,
-                                                float* __restrict__ out, int64_t ldo) {
+                                                TO* __restrict__ out, int64_t ldo) {
     const int n = counts[0];
     const int lane = threadIdx.x & 63;
     for (int i = blockIdx.x * WPB + (threadIdx.x >> 6); i < n; i += gridDim.x * WPB) {
@@ -97,22 +113,23 @@ __global__ __launch_bounds__(TB) void k_gat_fwd(const int32_t* __restrict__ b_in
             float acc = 0.f;
             for (int e = e0; e < e1; ++e) {
                 const int c = cols[e];
-                acc += expf(leaky(ri + el[c], slope) - l) * z[(int64_t)c * ldz + f];
+                acc += expf(leaky(ri + el[c], slope) - l) * to_f32(z[(int64_t)c * ldz + f]);
             }
-            float v = acc + a_self * z[(int64_t)i * ldz + f];
+            float v = acc + a_self * to_f32(z[(int64_t)i * ldz + f]);
             if (bias) v += bias[f];
             if (relu && !(v > 0.f)) v = 0.f;
-            out[(int64_t)i * ldo + f] = v;
+            out[(int64_t)i * ldo + f] = from_f32<TO>(v);
         }
     }
 }
 
 // per destination row: t_i = sum_e alpha_e (g_i . z_col) and der_i = sum_e d pre_e (both including the self edge)
+template <typename TZ, typename TG>
 __global__ __launch_bounds__(TB) void k_gat_bwd_dst(const int32_t* __restrict__ b_indptr, const int32_t* __restrict__ cols,
-                                                    const int32_t* counts, const float* __restrict__ z, int64_t ldz, int F,
+                                                    const int32_t* counts, const TZ* __restrict__ z, int64_t ldz, int F,
                                                     const float* __restrict__ el, const float* __restrict__ er,
                                                     const float* __restrict__ lse, float slope,
-                                                    const float* __restrict__ g, int64_t ldg, float* __restrict__ t,
+                                                    const TG* __restrict__ g, int64_t ldg, float* __restrict__ t,
                                                     float* __restrict__ der) {
     const int n = counts[0];
     const int lane = threadIdx.x & 63;
@@ -121,7 +138,7 @@ __global__ __launch_bounds__(TB) void k_gat_bwd_dst(const int32_t* __restrict__ 
         const float ri = er[i], l = lse[i];
         auto dot_with = [&](int64_t row) {
             float d = 0.f;
-            for (int f = lane; f < F; f += 64) d += g[(int64_t)i * ldg + f] * z[row * ldz + f];
+            for (int f = lane; f < F; f += 64) d += to_f32(g[(int64_t)i * ldg + f]) * to_f32(z[row * ldz + f]);
             return wave_sum(d);
         };
         // first pass: t_i
@@ -149,13 +166,14 @@ __global__ __launch_bounds__(TB) void k_gat_bwd_dst(const int32_t* __restrict__ 
 // per source row j, through the transposed block:
 //   dz_j = sum_{(i<-j)} alpha g_i + [j<n_dst] alpha_self g_j + del_j a_src + [j<n_dst] der_j a_dst,
 //   del_j = sum of d pre over the edges that end in j (and j's own self edge)
+template <typename TZ, typename TG>
 __global__ __launch_bounds__(TB) void k_gat_bwd_src(const int32_t* __restrict__ t_indptr, const int32_t* __restrict__ t_rows,
-                                                    const int32_t* counts, const float* __restrict__ z, int64_t ldz, int F,
+                                                    const int32_t* counts, const TZ* __restrict__ z, int64_t ldz, int F,
                                                     const float* __restrict__ el, const float* __restrict__ er,
                                                     const float* __restrict__ lse, const float* __restrict__ t,
                                                     const float* __restrict__ der, float slope,
                                                     const float* __restrict__ a_src, const float* __restrict__ a_dst,
-                                                    const float* __restrict__ g, int64_t ldg, float* __restrict__ dz,
+                                                    const TG* __restrict__ g, int64_t ldg, TZ* __restrict__ dz,
                                                     int64_t lddz, float* __restrict__ del) {
     const int n_dst = counts[0], n_src = counts[1];
     const int lane = threadIdx.x & 63;
@@ -167,7 +185,7 @@ __global__ __launch_bounds__(TB) void k_gat_bwd_src(const int32_t* __restrict__ 
         float a_self = 0.f;
         if (j < n_dst) {
             float d = 0.f;
-            for (int f = lane; f < F; f += 64) d += g[(int64_t)j * ldg + f] * z[(int64_t)j * ldz + f];
+            for (int f = lane; f < F; f += 64) d += to_f32(g[(int64_t)j * ldg + f]) * to_f32(z[(int64_t)j * ldz + f]);
             d = wave_sum(d);
             const float pre = er[j] + lj;
             a_self = expf(leaky(pre, slope) - lse[j]);
@@ -176,7 +194,7 @@ __global__ __launch_bounds__(TB) void k_gat_bwd_src(const int32_t* __restrict__ 
         for (int e = e0; e < e1; ++e) {
             const int i = t_rows[e];
             float d = 0.f;
-            for (int f = lane; f < F; f += 64) d += g[(int64_t)i * ldg + f] * z[(int64_t)j * ldz + f];
+            for (int f = lane; f < F; f += 64) d += to_f32(g[(int64_t)i * ldg + f]) * to_f32(z[(int64_t)j * ldz + f]);
             d = wave_sum(d);
             const float pre = er[i] + lj;
             dl += expf(leaky(pre, slope) - lse[i]) * (d - t[i]) * (pre > 0.f ? 1.f : slope);
@@ -187,10 +205,10 @@ __global__ __launch_bounds__(TB) void k_gat_bwd_src(const int32_t* __restrict__ 
             float acc = 0.f;
             for (int e = e0; e < e1; ++e) {
                 const int i = t_rows[e];
-                acc += expf(leaky(er[i] + lj, slope) - lse[i]) * g[(int64_t)i * ldg + f];
+                acc += expf(leaky(er[i] + lj, slope) - lse[i]) * to_f32(g[(int64_t)i * ldg + f]);
             }
-            if (j < n_dst) acc += a_self * g[(int64_t)j * ldg + f] + drj * a_dst[f];
-            dz[(int64_t)j * lddz + f] = acc + dl * a_src[f];
+            if (j < n_dst) acc += a_self * to_f32(g[(int64_t)j * ldg + f]) + drj * a_dst[f];
+            dz[(int64_t)j * lddz + f] = from_f32<TZ>(acc + dl * a_src[f]);
         }
     }
 }
@@ -198,7 +216,8 @@ __global__ __launch_bounds__(TB) void k_gat_bwd_src(const int32_t* __restrict__ 
 // part[b][0][f] = sum over the rows of chunk b of del_j z_j[f]; part[b][1][f] likewise with der_i (rows < n_dst).
 // Wave w of the workgroup sums the chunk's rows w, w+4, ... (lane = feature, 64 at a time); the four
 // wave sums are then added in wave order.  Chunks past the row count write zeros.
-__global__ __launch_bounds__(TB) void k_gat_vec_partials(const int32_t* counts, const float* __restrict__ z, int64_t ldz,
+template <typename TZ>
+__global__ __launch_bounds__(TB) void k_gat_vec_partials(const int32_t* counts, const TZ* __restrict__ z, int64_t ldz,
                                                          int F, const float* __restrict__ del,
                                                          const float* __restrict__ der, float* __restrict__ part) {
     __shared__ float red[WPB][2][64];
@@ -211,7 +230,7 @@ __global__ __launch_bounds__(TB) void k_gat_vec_partials(const int32_t* counts, 
         if (f < F) {
 #pragma unroll 8
             for (int r = r0 + w; r < r1; r += WPB) {
-                const float v = z[(int64_t)r * ldz + f];
+                const float v = to_f32(z[(int64_t)r * ldz + f]);
                 s0 += del[r] * v;
                 s1 += (r < n_dst ? der[r] : 0.f) * v;
             }
@@ -244,8 +263,9 @@ __global__ __launch_bounds__(TB) void k_gat_vec_final(const float* __restrict__ 
 // In place: g[r][f] = 0 where Y[r][f] <= 0 (Y may be null), and Qb[chunk][f] = column sum of the
 // masked g over the chunk's rows (zero for chunks past the row count).  Rows are dealt to the four
 // waves as in k_gat_vec_partials.
-__global__ __launch_bounds__(TB) void k_gat_mask_bias(const int32_t* counts, float* __restrict__ g, int64_t ldg,
-                                                      const float* __restrict__ Y, int64_t ldy, int F,
+template <typename TG>
+__global__ __launch_bounds__(TB) void k_gat_mask_bias(const int32_t* counts, TG* __restrict__ g, int64_t ldg,
+                                                      const TG* __restrict__ Y, int64_t ldy, int F,
                                                       float* __restrict__ Qb) {
     __shared__ float red[WPB][64];
     const int n = counts[0];
@@ -265,21 +285,21 @@ __global__ __launch_bounds__(TB) void k_gat_mask_bias(const int32_t* counts, flo
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
                         const int r = min(rb + u * WPB, r1 - 1);
-                        v[u] = g[(int64_t)r * ldg + f];
-                        y[u] = Y[(int64_t)r * ldy + f];
+                        v[u] = to_f32(g[(int64_t)r * ldg + f]);
+                        y[u] = to_f32(Y[(int64_t)r * ldy + f]);
                     }
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
                         const int r = rb + u * WPB;
                         if (r < r1) {
                             if (y[u] > 0.f) s += v[u];
-                            else g[(int64_t)r * ldg + f] = 0.f;
+                            else g[(int64_t)r * ldg + f] = from_f32<TG>(0.f);
                         }
                     }
                 }
             } else {
 #pragma unroll 8
-                for (int r = r0 + w; r < r1; r += WPB) s += g[(int64_t)r * ldg + f];
+                for (int r = r0 + w; r < r1; r += WPB) s += to_f32(g[(int64_t)r * ldg + f]);
             }
         }
         red[w][lane] = s;
@@ -298,11 +318,12 @@ __global__ __launch_bounds__(TB) void k_gat_mask_bias(const int32_t* counts, flo
 template <int KF>
 struct Slice {
     float4 v[KF];
-    __device__ __forceinline__ void load(const float* __restrict__ row, int r, int F) {
+    template <typename T>
+    __device__ __forceinline__ void load(const T* __restrict__ row, int r, int F) {
 #pragma unroll
         for (int k = 0; k < KF; ++k) {
             const int c = 4 * r + 64 * k;
-            v[k] = c < F ? *reinterpret_cast<const float4*>(row + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+            v[k] = c < F ? ld4(row + c) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     }
     __device__ __forceinline__ void zero() {
@@ -344,12 +365,12 @@ __device__ __forceinline__ float across_groups(float v) {
     return v;
 }
 
-template <int KF>
+template <typename TZ, typename TO, int KF>
 __global__ __launch_bounds__(TB) void k_gat_fwd_v(const int32_t* __restrict__ b_indptr, const int32_t* __restrict__ cols,
-                                                  const int32_t* counts, const float* __restrict__ z, int64_t ldz, int F,
+                                                  const int32_t* counts, const TZ* __restrict__ z, int64_t ldz, int F,
                                                   const float* __restrict__ el, const float* __restrict__ er, float slope,
                                                   float* __restrict__ lse, const float* __restrict__ bias, int relu,
-                                                  float* __restrict__ out, int64_t ldo) {
+                                                  TO* __restrict__ out, int64_t ldo) {
     const int n = counts[0];
     const int lane = threadIdx.x & 63, q = lane >> 4, r = lane & 15;
     for (int i = blockIdx.x * WPB + (threadIdx.x >> 6); i < n; i += gridDim.x * WPB) {
@@ -389,7 +410,7 @@ __global__ __launch_bounds__(TB) void k_gat_fwd_v(const int32_t* __restrict__ b_
                         v.x = v.x > 0.f ? v.x : 0.f; v.y = v.y > 0.f ? v.y : 0.f;
                         v.z = v.z > 0.f ? v.z : 0.f; v.w = v.w > 0.f ? v.w : 0.f;
                     }
-                    *reinterpret_cast<float4*>(out + (int64_t)i * ldo + c) = v;
+                    st4(out + (int64_t)i * ldo + c, v);
                 }
             }
         }
@@ -399,12 +420,12 @@ __global__ __launch_bounds__(TB) void k_gat_fwd_v(const int32_t* __restrict__ b_
 // t_i = sum_e alpha_e d_e and der_i = sum_e alpha_e (d_e - t_i) s'_e with d_e = g_i . z_col, s'_e the
 // LeakyReLU slope at the edge's score, both sums including the self edge.  One visit per edge:
 // der_i = sum alpha d s' - t_i sum alpha s'.
-template <int KF>
+template <typename TZ, typename TG, int KF>
 __global__ __launch_bounds__(TB) void k_gat_bwd_dst_v(const int32_t* __restrict__ b_indptr, const int32_t* __restrict__ cols,
-                                                      const int32_t* counts, const float* __restrict__ z, int64_t ldz, int F,
+                                                      const int32_t* counts, const TZ* __restrict__ z, int64_t ldz, int F,
                                                       const float* __restrict__ el, const float* __restrict__ er,
                                                       const float* __restrict__ lse, float slope,
-                                                      const float* __restrict__ g, int64_t ldg, float* __restrict__ t,
+                                                      const TG* __restrict__ g, int64_t ldg, float* __restrict__ t,
                                                       float* __restrict__ der) {
     const int n = counts[0];
     const int lane = threadIdx.x & 63, q = lane >> 4, r = lane & 15;
@@ -440,14 +461,14 @@ __global__ __launch_bounds__(TB) void k_gat_bwd_dst_v(const int32_t* __restrict_
     }
 }
 
-template <int KF>
+template <typename TZ, typename TG, int KF>
 __global__ __launch_bounds__(TB) void k_gat_bwd_src_v(const int32_t* __restrict__ t_indptr, const int32_t* __restrict__ t_rows,
-                                                      const int32_t* counts, const float* __restrict__ z, int64_t ldz, int F,
+                                                      const int32_t* counts, const TZ* __restrict__ z, int64_t ldz, int F,
                                                       const float* __restrict__ el, const float* __restrict__ er,
                                                       const float* __restrict__ lse, const float* __restrict__ t,
                                                       const float* __restrict__ der, float slope,
                                                       const float* __restrict__ a_src, const float* __restrict__ a_dst,
-                                                      const float* __restrict__ g, int64_t ldg, float* __restrict__ dz,
+                                                      const TG* __restrict__ g, int64_t ldg, TZ* __restrict__ dz,
                                                       int64_t lddz, float* __restrict__ del) {
     const int n_dst = counts[0], n_src = counts[1];
     const int lane = threadIdx.x & 63, q = lane >> 4, r = lane & 15;
@@ -491,7 +512,7 @@ __global__ __launch_bounds__(TB) void k_gat_bwd_src_v(const int32_t* __restrict_
                     float4 v = acc.v[k];
                     v.x += dl * as.x + drj * ad.x; v.y += dl * as.y + drj * ad.y;
                     v.z += dl * as.z + drj * ad.z; v.w += dl * as.w + drj * ad.w;
-                    *reinterpret_cast<float4*>(dz + (int64_t)j * lddz + c) = v;
+                    st4(dz + (int64_t)j * lddz + c, v);
                 }
             }
         }
@@ -519,6 +540,62 @@ inline int rows_grid(int rows) {
     return b > 4096 ? 4096 : b;
 }
 
+template <typename TZ, typename TO>
+int32_t forward_t(const sdt_block* blk, const TZ* z, int64_t ldz, int32_t F, const float* a_src, const float* a_dst, float slope,
+                  const float* bias, int32_t relu, TO* out, int64_t ldo, const GatWs& w, hipStream_t st) {
+    hipLaunchKernelGGL(k_gat_scores<TZ>, dim3(rows_grid(blk->cap_src)), dim3(TB), 0, st, blk->counts, z, ldz, F, a_src, a_dst,
+                       w.el, w.er);
+    SDT_CHECK_LAUNCH("gat scores");
+    if (vec_ok(F, {ldz, ldo}, {z, out, bias})) {
+        SDT_GAT_KF(F, hipLaunchKernelGGL((k_gat_fwd_v<TZ, TO, KF>), dim3(rows_grid(blk->cap_dst)), dim3(TB), 0, st, blk->indptr,
+                                         blk->cols, blk->counts, z, ldz, F, w.el, w.er, slope, w.lse, bias, relu, out, ldo));
+    } else {
+        hipLaunchKernelGGL((k_gat_fwd<TZ, TO>), dim3(rows_grid(blk->cap_dst)), dim3(TB), 0, st, blk->indptr, blk->cols,
+                           blk->counts, z, ldz, F, w.el, w.er, slope, w.lse, bias, relu, out, ldo);
+    }
+    SDT_CHECK_LAUNCH("gat forward");
+    return SDT_OK;
+}
+
+template <typename TZ, typename TG>
+int32_t backward_t(const sdt_block* blk, const TZ* z, int64_t ldz, int32_t F, const float* a_src, const float* a_dst, float slope,
+                   const TG* g, int64_t ldg, TZ* dz, int64_t lddz, const GatWs& w, hipStream_t st) {
+    if (vec_ok(F, {ldz, ldg, lddz}, {z, g, dz, a_src, a_dst})) {
+        SDT_GAT_KF(F, hipLaunchKernelGGL((k_gat_bwd_dst_v<TZ, TG, KF>), dim3(rows_grid(blk->cap_dst)), dim3(TB), 0, st,
+                                         blk->indptr, blk->cols, blk->counts, z, ldz, F, w.el, w.er, w.lse, slope, g, ldg, w.t,
+                                         w.der));
+        SDT_CHECK_LAUNCH("gat backward (destinations)");
+        SDT_GAT_KF(F, hipLaunchKernelGGL((k_gat_bwd_src_v<TZ, TG, KF>), dim3(rows_grid(blk->cap_src)), dim3(TB), 0, st,
+                                         blk->t_indptr, blk->t_rows, blk->counts, z, ldz, F, w.el, w.er, w.lse, w.t, w.der, slope,
+                                         a_src, a_dst, g, ldg, dz, lddz, w.del));
+        SDT_CHECK_LAUNCH("gat backward (sources)");
+    } else {
+        hipLaunchKernelGGL((k_gat_bwd_dst<TZ, TG>), dim3(rows_grid(blk->cap_dst)), dim3(TB), 0, st, blk->indptr, blk->cols,
+                           blk->counts, z, ldz, F, w.el, w.er, w.lse, slope, g, ldg, w.t, w.der);
+        SDT_CHECK_LAUNCH("gat backward (destinations)");
+        hipLaunchKernelGGL((k_gat_bwd_src<TZ, TG>), dim3(rows_grid(blk->cap_src)), dim3(TB), 0, st, blk->t_indptr, blk->t_rows,
+                           blk->counts, z, ldz, F, w.el, w.er, w.lse, w.t, w.der, slope, a_src, a_dst, g, ldg, dz, lddz, w.del);
+        SDT_CHECK_LAUNCH("gat backward (sources)");
+    }
+    hipLaunchKernelGGL(k_gat_vec_partials<TZ>, dim3(w.nblk), dim3(TB), 0, st, blk->counts, z, ldz, F, w.del, w.der, w.part);
+    SDT_CHECK_LAUNCH("gat attention-vector partials");
+    return SDT_OK;
+}
+
+template <typename TG>
+int32_t mask_bias_t(const sdt_block* blk, TG* g, int64_t ldg, const TG* Y, int64_t ldy, int32_t F, const GatWs& w,
+                    hipStream_t st) {
+    hipLaunchKernelGGL(k_gat_mask_bias<TG>, dim3(w.nchunk, w.nchunk >= 1024 ? 1 : (F + 63) / 64), dim3(TB), 0, st, blk->counts, g,
+                       ldg, Y, ldy, F, w.biasq);
+    SDT_CHECK_LAUNCH("gat mask + bias partials");
+    return SDT_OK;
+}
+
+// the projected rows may be bf16 with fp32 beside them (logits out, loss gradient in), never the other way round
+inline bool types_ok(int32_t z_dtype, int32_t other) {
+    return dtype_ok(z_dtype) && dtype_ok(other) && (z_dtype == SDT_BF16 || other == SDT_F32);
+}
+
 }  // namespace
 }  // namespace sdt
 
@@ -532,33 +609,32 @@ extern "C" size_t sdt_gat_workspace_bytes(int32_t cap_src, int32_t cap_dst, int3
 extern "C" int32_t sdt_gat_aggregate_fwd(const sdt_block* blk, const float* z, int64_t ldz, int32_t F, const float* a_src,
                                          const float* a_dst, float slope, float* out, int64_t ldo, void* ws, size_t ws_bytes,
                                          void* stream) {
-    return gat_forward(blk, z, ldz, F, a_src, a_dst, slope, nullptr, 0, out, ldo, ws, ws_bytes, static_cast<hipStream_t>(stream));
+    return gat_forward(blk, z, ldz, F, SDT_F32, a_src, a_dst, slope, nullptr, 0, out, ldo, SDT_F32, ws, ws_bytes,
+                       static_cast<hipStream_t>(stream));
 }
 
-int32_t sdt::gat_forward(const sdt_block* blk, const float* z, int64_t ldz, int32_t F, const float* a_src, const float* a_dst,
-                         float slope, const float* bias, int32_t relu, float* out, int64_t ldo, void* ws, size_t ws_bytes,
-                         hipStream_t st) {
+int32_t sdt::gat_forward(const sdt_block* blk, const void* z, int64_t ldz, int32_t F, int32_t z_dtype, const float* a_src,
+                         const float* a_dst, float slope, const float* bias, int32_t relu, void* out, int64_t ldo,
+                         int32_t out_dtype, void* ws, size_t ws_bytes, hipStream_t st) {
     SDT_REQUIRE(blk, SDT_ERR_INVALID_ARG, "sdt_gat_aggregate_fwd: null block");
     SDT_REQUIRE(F >= 0 && ldz >= F && ldo >= F && blk->cap_src >= blk->cap_dst, SDT_ERR_INVALID_ARG,
                 "sdt_gat_aggregate_fwd: bad sizes");
+    SDT_REQUIRE(types_ok(z_dtype, out_dtype), SDT_ERR_INVALID_ARG, "sdt_gat_aggregate_fwd: storage types %d -> %d", z_dtype,
+                out_dtype);
     if (blk->cap_dst == 0 || F == 0) return SDT_OK;
     SDT_REQUIRE(blk->counts && blk->indptr && blk->cols && z && a_src && a_dst && out, SDT_ERR_INVALID_ARG,
                 "sdt_gat_aggregate_fwd: null pointer");
     const GatWs w = gat_ws(ws, blk->cap_src, blk->cap_dst, F);
     SDT_REQUIRE(ws && ws_bytes >= w.total && aligned16(ws), SDT_ERR_WORKSPACE,
                 "sdt_gat_aggregate_fwd: workspace of %zu bytes needed, %zu given", w.total, ws_bytes);
-    hipLaunchKernelGGL(k_gat_scores, dim3(rows_grid(blk->cap_src)), dim3(TB), 0, st, blk->counts, z, ldz, F, a_src, a_dst, w.el,
-                       w.er);
-    SDT_CHECK_LAUNCH("gat scores");
-    if (vec_ok(F, {ldz, ldo}, {z, out, bias})) {
-        SDT_GAT_KF(F, hipLaunchKernelGGL(k_gat_fwd_v<KF>, dim3(rows_grid(blk->cap_dst)), dim3(TB), 0, st, blk->indptr, blk->cols,
-                                         blk->counts, z, ldz, F, w.el, w.er, slope, w.lse, bias, relu, out, ldo));
-    } else {
-        hipLaunchKernelGGL(k_gat_fwd, dim3(rows_grid(blk->cap_dst)), dim3(TB), 0, st, blk->indptr, blk->cols, blk->counts, z, ldz,
-                           F, w.el, w.er, slope, w.lse, bias, relu, out, ldo);
-    }
-    SDT_CHECK_LAUNCH("gat forward");
-    return SDT_OK;
+    if (z_dtype == SDT_F32)
+        return forward_t(blk, static_cast<const float*>(z), ldz, F, a_src, a_dst, slope, bias, relu, static_cast<float*>(out), ldo, w,
+                         st);
+    if (out_dtype == SDT_F32)
+        return forward_t(blk, static_cast<const bf16_t*>(z), ldz, F, a_src, a_dst, slope, bias, relu, static_cast<float*>(out), ldo,
+                         w, st);
+    return forward_t(blk, static_cast<const bf16_t*>(z), ldz, F, a_src, a_dst, slope, bias, relu, static_cast<bf16_t*>(out), ldo, w,
+                     st);
 }
 
 extern "C" int32_t sdt_gat_aggregate_bwd(const sdt_block* blk, const float* z, int64_t ldz, int32_t F, const float* a_src,
@@ -568,59 +644,56 @@ extern "C" int32_t sdt_gat_aggregate_bwd(const sdt_block* blk, const float* z, i
     hipStream_t st = static_cast<hipStream_t>(stream);
     const float* part = nullptr;
     int32_t n_part = 0;
-    const int32_t rc = gat_backward(blk, z, ldz, F, a_src, a_dst, slope, g, ldg, dz, lddz, ws, ws_bytes, &part, &n_part, st);
+    const int32_t rc = gat_backward(blk, z, ldz, F, SDT_F32, a_src, a_dst, slope, g, ldg, SDT_F32, dz, lddz, ws, ws_bytes, &part,
+                                    &n_part, st);
     if (rc != SDT_OK || !part) return rc;
     hipLaunchKernelGGL(k_gat_vec_final, dim3(ceil_div(F, TB)), dim3(TB), 0, st, part, n_part, F, da_src, da_dst);
     SDT_CHECK_LAUNCH("gat attention-vector reduction");
     return SDT_OK;
 }
 
-int32_t sdt::gat_backward(const sdt_block* blk, const float* z, int64_t ldz, int32_t F, const float* a_src,
-                          const float* a_dst, float slope, const float* g, int64_t ldg, float* dz, int64_t lddz, void* ws,
-                          size_t ws_bytes, const float** part, int32_t* n_part, hipStream_t st) {
+int32_t sdt::gat_backward(const sdt_block* blk, const void* z, int64_t ldz, int32_t F, int32_t z_dtype, const float* a_src,
+                          const float* a_dst, float slope, const void* g, int64_t ldg, int32_t g_dtype, void* dz, int64_t lddz,
+                          void* ws, size_t ws_bytes, const float** part, int32_t* n_part, hipStream_t st) {
     *part = nullptr;
     *n_part = 0;
     SDT_REQUIRE(blk, SDT_ERR_INVALID_ARG, "sdt_gat_aggregate_bwd: null block");
     SDT_REQUIRE(F >= 0 && ldz >= F && ldg >= F && lddz >= F && blk->cap_src >= blk->cap_dst, SDT_ERR_INVALID_ARG,
                 "sdt_gat_aggregate_bwd: bad sizes");
+    SDT_REQUIRE(types_ok(z_dtype, g_dtype), SDT_ERR_INVALID_ARG, "sdt_gat_aggregate_bwd: storage types %d, %d", z_dtype, g_dtype);
     if (blk->cap_src == 0 || F == 0) return SDT_OK;
     SDT_REQUIRE(blk->counts && blk->indptr && blk->cols && blk->t_indptr && blk->t_rows && z && a_src && a_dst && g && dz,
                 SDT_ERR_INVALID_ARG, "sdt_gat_aggregate_bwd: null pointer (the block needs its transposed arrays)");
     const GatWs w = gat_ws(ws, blk->cap_src, blk->cap_dst, F);
     SDT_REQUIRE(ws && ws_bytes >= w.total && aligned16(ws), SDT_ERR_WORKSPACE,
                 "sdt_gat_aggregate_bwd: workspace of %zu bytes needed, %zu given", w.total, ws_bytes);
-    if (vec_ok(F, {ldz, ldg, lddz}, {z, g, dz, a_src, a_dst})) {
-        SDT_GAT_KF(F, hipLaunchKernelGGL(k_gat_bwd_dst_v<KF>, dim3(rows_grid(blk->cap_dst)), dim3(TB), 0, st, blk->indptr,
-                                         blk->cols, blk->counts, z, ldz, F, w.el, w.er, w.lse, slope, g, ldg, w.t, w.der));
-        SDT_CHECK_LAUNCH("gat backward (destinations)");
-        SDT_GAT_KF(F, hipLaunchKernelGGL(k_gat_bwd_src_v<KF>, dim3(rows_grid(blk->cap_src)), dim3(TB), 0, st, blk->t_indptr,
-                                         blk->t_rows, blk->counts, z, ldz, F, w.el, w.er, w.lse, w.t, w.der, slope, a_src, a_dst,
-                                         g, ldg, dz, lddz, w.del));
-        SDT_CHECK_LAUNCH("gat backward (sources)");
-    } else {
-        hipLaunchKernelGGL(k_gat_bwd_dst, dim3(rows_grid(blk->cap_dst)), dim3(TB), 0, st, blk->indptr, blk->cols, blk->counts, z,
-                           ldz, F, w.el, w.er, w.lse, slope, g, ldg, w.t, w.der);
-        SDT_CHECK_LAUNCH("gat backward (destinations)");
-        hipLaunchKernelGGL(k_gat_bwd_src, dim3(rows_grid(blk->cap_src)), dim3(TB), 0, st, blk->t_indptr, blk->t_rows, blk->counts,
-                           z, ldz, F, w.el, w.er, w.lse, w.t, w.der, slope, a_src, a_dst, g, ldg, dz, lddz, w.del);
-        SDT_CHECK_LAUNCH("gat backward (sources)");
-    }
-    hipLaunchKernelGGL(k_gat_vec_partials, dim3(w.nblk), dim3(TB), 0, st, blk->counts, z, ldz, F, w.del, w.der, w.part);
-    SDT_CHECK_LAUNCH("gat attention-vector partials");
+    int32_t rc;
+    if (z_dtype == SDT_F32)
+        rc = backward_t(blk, static_cast<const float*>(z), ldz, F, a_src, a_dst, slope, static_cast<const float*>(g), ldg,
+                        static_cast<float*>(dz), lddz, w, st);
+    else if (g_dtype == SDT_F32)
+        rc = backward_t(blk, static_cast<const bf16_t*>(z), ldz, F, a_src, a_dst, slope, static_cast<const float*>(g), ldg,
+                        static_cast<bf16_t*>(dz), lddz, w, st);
+    else
+        rc = backward_t(blk, static_cast<const bf16_t*>(z), ldz, F, a_src, a_dst, slope, static_cast<const bf16_t*>(g), ldg,
+                        static_cast<bf16_t*>(dz), lddz, w, st);
+    if (rc != SDT_OK) return rc;
     *part = w.part;
     *n_part = w.nblk;
     return SDT_OK;
 }
 
-int32_t sdt::gat_mask_bias(const sdt_block* blk, float* g, int64_t ldg, const float* Y, int64_t ldy, int32_t F, void* ws,
-                           size_t ws_bytes, const float** Qb, int32_t* n_chunks, hipStream_t st) {
-    SDT_REQUIRE(blk && blk->counts && g && F > 0 && ldg >= F && (!Y || ldy >= F), SDT_ERR_INVALID_ARG, "gat_mask_bias: bad arguments");
+int32_t sdt::gat_mask_bias(const sdt_block* blk, void* g, int64_t ldg, const void* Y, int64_t ldy, int32_t F, int32_t dtype,
+                           void* ws, size_t ws_bytes, const float** Qb, int32_t* n_chunks, hipStream_t st) {
+    SDT_REQUIRE(blk && blk->counts && g && F > 0 && ldg >= F && (!Y || ldy >= F) && dtype_ok(dtype), SDT_ERR_INVALID_ARG,
+                "gat_mask_bias: bad arguments");
     const GatWs w = gat_ws(ws, blk->cap_src, blk->cap_dst, F);
     SDT_REQUIRE(ws && ws_bytes >= w.total && aligned16(ws), SDT_ERR_WORKSPACE, "gat_mask_bias: workspace of %zu bytes needed, %zu given",
                 w.total, ws_bytes);
-    hipLaunchKernelGGL(k_gat_mask_bias, dim3(w.nchunk, w.nchunk >= 1024 ? 1 : (F + 63) / 64), dim3(TB), 0, st, blk->counts, g, ldg, Y,
-                       ldy, F, w.biasq);
-    SDT_CHECK_LAUNCH("gat mask + bias partials");
+    const int32_t rc = dtype == SDT_F32
+                           ? mask_bias_t(blk, static_cast<float*>(g), ldg, static_cast<const float*>(Y), ldy, F, w, st)
+                           : mask_bias_t(blk, static_cast<bf16_t*>(g), ldg, static_cast<const bf16_t*>(Y), ldy, F, w, st);
+    if (rc != SDT_OK) return rc;
     *Qb = w.biasq;
     *n_chunks = w.nchunk;
     return SDT_OK;

@@ -178,8 +178,6 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
     int32_t rc = check_model(model, fanouts, "sdt_train_step_layout");
     if (rc != SDT_OK) return rc;
     SDT_REQUIRE(dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_train_step_layout: unknown dtype %d", dtype);
-    SDT_REQUIRE(model->kind != SDT_MODEL_GAT || dtype == SDT_F32, SDT_ERR_INVALID_ARG,
-                "sdt_train_step_layout: the GAT model is fp32 only");
     SDT_REQUIRE(n_nodes >= 0 && n_nodes <= 0x7FFFFFFF && batch >= 0 && batch <= n_nodes, SDT_ERR_INVALID_ARG,
                 "sdt_train_step_layout: n_nodes=%lld batch=%d", (long long)n_nodes, batch);
     const int L = model->n_layers;
@@ -205,10 +203,10 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
             lay->src_nodes[l] = a.take_off((size_t)(c.src[l] > 0 ? c.src[l] : 1) * 4);
             lay->t_indptr[l] = a.take_off(((size_t)c.src[l] + 1) * 4);
             lay->t_rows[l] = a.take_off((size_t)(c.nnz[l] > 0 ? c.nnz[l] : 1) * 4);
-            if (l >= 1) lay->dH[l] = a.take_off((size_t)c.src[l] * d[l] * 4);
-            lay->H[l + 1] = a.take_off((size_t)c.dst[l] * d[l + 1] * 4);
-            lay->z[l] = a.take_off((size_t)c.src[l] * d[l + 1] * 4);
-            lay->dz[l] = a.take_off((size_t)c.src[l] * d[l + 1] * 4);
+            if (l >= 1) lay->dH[l] = a.take_off((size_t)c.src[l] * d[l] * es);
+            lay->H[l + 1] = a.take_off((size_t)c.dst[l] * d[l + 1] * (l == L - 1 ? 4 : es));
+            lay->z[l] = a.take_off((size_t)c.src[l] * d[l + 1] * es);
+            lay->dz[l] = a.take_off((size_t)c.src[l] * d[l + 1] * es);
             lay->dW[l] = a.take_off((size_t)d[l] * d[l + 1] * 4);
             lay->db[l] = a.take_off((size_t)d[l + 1] * 4);
             lay->datt[l] = a.take_off((size_t)2 * d[l + 1] * 4);
@@ -219,7 +217,7 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
             bwd_scratch += align_up(sdt_linear_bwd_workspace_bytes(c.src[l], d[l] / 2, d[l + 1]), 256);
         }
         if (bwd_scratch > scratch) scratch = bwd_scratch;
-        lay->H[0] = a.take_off((size_t)c.src[0] * d[0] * 4);
+        lay->H[0] = a.take_off((size_t)c.src[0] * d[0] * es);
         lay->dZ = a.take_off((size_t)batch * d[L] * 4);
         lay->row_loss = a.take_off((size_t)(batch > 0 ? batch : 1) * 4);
         lay->scratch = a.take_off(scratch);
@@ -550,6 +548,8 @@ int32_t step_compute_gat(const StepCtx& c, const StepBuffers& b, const int32_t* 
     const int32_t* d = model->dims;
     sdt_timing* timing = c.timing;
     const float slope = model->gat_slope;
+    const int32_t dtype = c.dtype;
+    const size_t es = dtype_size(dtype);
     int32_t rc;
     size_t scr_off[SDT_MAX_LAYERS], scr_len[SDT_MAX_LAYERS], gws_len[SDT_MAX_LAYERS];
     {
@@ -561,47 +561,51 @@ int32_t step_compute_gat(const StepCtx& c, const StepBuffers& b, const int32_t* 
             gws_len[l] = sdt_gat_workspace_bytes(lay.cap_src[l], lay.cap_dst[l], d[l + 1]);
         }
     }
-    auto H = [&](int l) { return static_cast<float*>(b.at(lay.H[l])); };
-    auto Z = [&](int l) { return static_cast<float*>(b.at(lay.z[l])); };
+    // bf16 storage: the gathered rows, the projected rows z, the hidden activations and the gradients w.r.t. all three
+    // are bf16 (rounded when stored); the logits, the loss gradient, the attention scalars and every sum stay fp32
+    auto H = [&](int l) { return static_cast<char*>(b.at(lay.H[l])); };
+    auto H1 = [&](int l) { return static_cast<char*>(b.at(lay.H[l])) + (size_t)(d[l] / 2) * es; };
+    auto Z = [&](int l) { return b.at(lay.z[l]); };
     for (int l = 0; l < L; ++l) {
         const int F = d[l + 1];
         {
             StageTimer tm(timing, c.slot, SDT_STAGE_LINEAR_FWD, l, st);
-            rc = sdt_sage_linear_fwd(H(l), d[l], H(l) + d[l] / 2, d[l], lay.cap_src[l], b.blk[l].counts + 1, d[l] / 2, F,
-                                     model->W[l], nullptr, 0, SDT_F32, Z(l), F, SDT_F32, st);
+            rc = linear_fwd(H(l), d[l], H1(l), d[l], lay.cap_src[l], b.blk[l].counts + 1, d[l] / 2, F, model->W[l], nullptr, 0,
+                            dtype, Z(l), F, dtype, /*rows_padded=*/false, st);
             if (rc != SDT_OK) return rc;
         }
         StageTimer tm(timing, c.slot, SDT_STAGE_AGG_FWD, l, st);
-        rc = gat_forward(&b.blk[l], Z(l), F, F, model->att[l], model->att[l] + F, slope, model->b[l], l < L - 1 ? 1 : 0,
-                         H(l + 1), F, b.at(lay.gatws[l]), gws_len[l], st);
+        rc = gat_forward(&b.blk[l], Z(l), F, F, dtype, model->att[l], model->att[l] + F, slope, model->b[l], l < L - 1 ? 1 : 0,
+                         H(l + 1), F, l < L - 1 ? dtype : SDT_F32, b.at(lay.gatws[l]), gws_len[l], st);
         if (rc != SDT_OK) return rc;
     }
     {
         StageTimer tm(timing, c.slot, SDT_STAGE_LOSS, 0, st);
-        rc = softmax_xent(H(L), d[L], c.batch, d[L], c.labels, seeds, static_cast<float*>(b.at(lay.dZ)),
-                          static_cast<float*>(b.at(lay.row_loss)), st);
+        rc = softmax_xent(static_cast<const float*>(b.at(lay.H[L])), d[L], c.batch, d[L], c.labels, seeds,
+                          static_cast<float*>(b.at(lay.dZ)), static_cast<float*>(b.at(lay.row_loss)), st);
         if (rc != SDT_OK) return rc;
     }
     PendingReduce pending[2 * SDT_MAX_LAYERS];
     int n_pending = 0;
-    float* g = static_cast<float*>(b.at(lay.dZ));
+    void* g = b.at(lay.dZ);
+    int32_t g_dtype = SDT_F32;
     for (int l = L - 1; l >= 0; --l) {
         const int F = d[l + 1];
         float* dW = model->dW[l] ? model->dW[l] : static_cast<float*>(b.at(lay.dW[l]));
         float* db = model->db[l] ? model->db[l] : static_cast<float*>(b.at(lay.db[l]));
         float* datt = model->datt[l] ? model->datt[l] : static_cast<float*>(b.at(lay.datt[l]));
-        float* dz = static_cast<float*>(b.at(lay.dz[l]));
+        void* dz = b.at(lay.dz[l]);
         const bool inner = l > 0;
         const float *Qb, *part;
         int32_t n_chunks, n_part;
         {
             StageTimer tm(timing, c.slot, SDT_STAGE_AGG_BWD, l, st);
             // g: gradient w.r.t. this layer's output; masked in place by the layer's own ReLU (not the last layer)
-            rc = gat_mask_bias(&b.blk[l], g, F, l < L - 1 ? H(l + 1) : nullptr, F, F, b.at(lay.gatws[l]), gws_len[l], &Qb,
-                               &n_chunks, st);
+            rc = gat_mask_bias(&b.blk[l], g, F, l < L - 1 ? H(l + 1) : nullptr, F, F, g_dtype, b.at(lay.gatws[l]), gws_len[l],
+                               &Qb, &n_chunks, st);
             if (rc != SDT_OK) return rc;
-            rc = gat_backward(&b.blk[l], Z(l), F, F, model->att[l], model->att[l] + F, slope, g, F, dz, F, b.at(lay.gatws[l]),
-                              gws_len[l], &part, &n_part, st);
+            rc = gat_backward(&b.blk[l], Z(l), F, F, dtype, model->att[l], model->att[l] + F, slope, g, F, g_dtype, dz, F,
+                              b.at(lay.gatws[l]), gws_len[l], &part, &n_part, st);
             if (rc != SDT_OK) return rc;
         }
         PendingReduce* pw = &pending[n_pending++];
@@ -610,12 +614,13 @@ int32_t step_compute_gat(const StepCtx& c, const StepBuffers& b, const int32_t* 
             BwdExtras ex;
             ex.defer = pw;
             ex.W_upd = model->W[l];
-            float* dH = inner ? static_cast<float*>(b.at(lay.dH[l])) : nullptr;
-            rc = linear_bwd(dz, F, SDT_F32, nullptr, 0, 0, H(l), d[l], H(l) + d[l] / 2, d[l], lay.cap_src[l],
-                            b.blk[l].counts + 1, d[l] / 2, F, model->W[l], SDT_F32, dW, db, dH, inner ? dH + d[l] / 2 : nullptr,
-                            d[l], b.at(scr_off[l]), scr_len[l], ex, st);
+            char* dH = inner ? static_cast<char*>(b.at(lay.dH[l])) : nullptr;
+            rc = linear_bwd(dz, F, dtype, nullptr, 0, 0, H(l), d[l], H1(l), d[l], lay.cap_src[l], b.blk[l].counts + 1, d[l] / 2, F,
+                            model->W[l], dtype, dW, db, dH, inner ? dH + (size_t)(d[l] / 2) * es : nullptr, d[l],
+                            b.at(scr_off[l]), scr_len[l], ex, st);
             if (rc != SDT_OK) return rc;
             g = dH;
+            g_dtype = dtype;
         }
         // the bias gradient is the column sum of the masked output gradient, not of dz
         pw->Q = Qb;

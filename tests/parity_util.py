@@ -58,6 +58,27 @@ def relu_window(x_gpu, x_ref, W, b) -> np.ndarray:
     return np.abs(x_gpu - x_ref) @ aw + (K + 2) * 2.0 ** -24 * (np.abs(x_gpu) @ aw + np.abs(np.asarray(b, np.float64)))
 
 
+def gat_relu_window(attend, blk, z_gpu, z_ref, att, b) -> np.ndarray:
+    """Element-wise bound on |pre_gpu - pre_oracle| for the GAT layer's pre-activation pre = GATagg(z) + b, given
+    the projected rows each side actually stored (z_gpu, z_ref: [n_src, F]) and `attend(z)` = the fp64 attention
+    aggregation of the block on given rows (the oracle's, passed in by the test):
+        |attend(z_gpu) - attend(z_ref)|  +  rounding of an fp32 evaluation of attend(z_gpu) + b.
+    The first term is the whole effect of the operands' difference (storage rounding and summation order of the
+    projection), measured.  The second: a score is a sum of 2F products (error <= (2F + 2) u S, u = 2^-24, S = the
+    largest sum_f |z_jf| (|a_src,f| + |a_dst,f|)); an attention weight moves relatively by twice the score error plus
+    the roundings of exp, sum and divide (<= (deg + 8) u (1 + S)); the weighted sum adds deg + 2 roundings; all of it
+    relative to at most max_j |z_jf| (+ |b_f|).  Two pre-activations on different sides of zero are both inside."""
+    z_gpu, z_ref = np.asarray(z_gpu, np.float64), np.asarray(z_ref, np.float64)
+    att, b = np.asarray(att, np.float64), np.asarray(b, np.float64)
+    F = z_gpu.shape[1]
+    u = 2.0 ** -24
+    S = float(np.max(np.abs(z_gpu) @ (np.abs(att[:F]) + np.abs(att[F:])))) if z_gpu.size else 0.0
+    deg = int(np.max(np.diff(np.asarray(blk.indptr)))) + 1 if len(blk.indptr) > 1 else 1
+    rel = 2.0 * (2 * F + 2) * u * S + (deg + 8) * u * (1.0 + S) + (deg + 2) * u
+    colmax = np.max(np.abs(z_gpu), axis=0) if z_gpu.size else np.zeros(F)
+    return np.abs(attend(z_gpu) - attend(z_ref)) + rel * (colmax + np.abs(b))[None, :]
+
+
 def f64(t: torch.Tensor) -> np.ndarray:
     return t.detach().to(torch.float64).cpu().numpy()
 

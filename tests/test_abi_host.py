@@ -59,10 +59,8 @@ def test_model_kinds_layouts_and_their_argument_checks():
             B.sdt_train_step_layout(1 << 14, 256, f, m, B.SDT_F32)
     gcn16 = B.sdt_train_step_layout(1 << 14, 256, f, gcn, B.SDT_BF16)     # GCN: fp32 or bf16 storage
     assert gcn16.norm[1] != 0 and gcn16.total_bytes < B.sdt_train_step_layout(1 << 14, 256, f, gcn, B.SDT_F32).total_bytes
-    gat16 = _model([64, 64, 8])
-    gat16.kind, gat16.gat_slope = B.SDT_MODEL_GAT, 0.2
-    with pytest.raises(B.SdtError):
-        B.sdt_train_step_layout(1 << 14, 256, f, gat16, B.SDT_BF16)       # GAT: fp32 only
+    gat16 = B.sdt_train_step_layout(1 << 14, 256, f, gat, B.SDT_BF16)     # GAT likewise
+    assert gat16.z[0] != 0 and gat16.total_bytes < lay.total_bytes
     gat.gat_slope = 1.5
     with pytest.raises(B.SdtError):
         B.sdt_train_step_layout(1 << 14, 256, f, gat, B.SDT_F32)

@@ -589,6 +589,70 @@ def test_gcn_step_bf16_rounding_points():
     assert abs(ref["loss"] - plain["loss"]) <= 2e-2 * abs(plain["loss"])
 
 
+def test_gat_step_bf16_rounding_points():
+    """bf16 storage of the GAT step: the forward equals a float64 computation in which torch's own bf16 cast (an
+    independent round-to-nearest-even) is applied to the weights, the projected rows and the hidden activations, with
+    the attention written as a dense masked softmax; the stored gradients are bf16 numbers, the logits and the
+    parameter gradients are not; everything stays within the bf16 tolerance of the unrounded step."""
+    rng = np.random.default_rng(37)
+    n, dims = 60, [8, 10, 4]
+    rows, indptr, indices = _small_graph(rng, n, 6)
+    Xb = torch.tensor(rng.standard_normal((n, dims[0])), dtype=torch.float32).to(torch.bfloat16)
+    bits = Xb.view(torch.int16).numpy().view(np.uint16)
+    X64 = Xb.to(torch.float64).numpy()
+    y = rng.integers(0, dims[2], size=n).astype(np.int32)
+    W = [rng.standard_normal((dims[l], dims[l + 1])) * 0.4 for l in range(2)]
+    b = [rng.standard_normal(dims[l + 1]) * 0.1 for l in range(2)]
+    att = [rng.standard_normal(2 * dims[l + 1]) * 0.5 for l in range(2)]
+    seeds = np.array([2, 7, 19, 41, 55, 13], dtype=np.int32)
+    ref = orc.gat_train_step(indptr, indices, bits, y, seeds, [4, 3], W, b, att, seed=5, step=2, lr=0.1, bf16=True)
+    plain = orc.gat_train_step(indptr, indices, X64.astype(np.float32), y, seeds, [4, 3], W, b, att, seed=5, step=2, lr=0.1,
+                               blocks=ref["blocks"])
+    cast = lambda t: t.to(torch.bfloat16).to(torch.float64)
+
+    def same_up_to_a_rounding_boundary(mine, other):
+        # two float64 sums may differ in their last bit, which can move a value across a rounding boundary: then the
+        # results are neighbouring bf16 numbers; that may happen at a few elements, no more
+        off = mine != other
+        assert off.mean() <= 0.02 and np.all(np.abs(mine - other)[off] <= 2.0 ** -7 * np.abs(other)[off] + 1e-13)
+
+    H = torch.tensor(X64[ref["blocks"][0].src_nodes])
+    for l, blk in enumerate(ref["blocks"]):
+        F = dims[l + 1]
+        z = cast(H @ cast(torch.tensor(W[l])))
+        same_up_to_a_rounding_boundary(ref["Z"][l], z.numpy())
+        z = torch.tensor(ref["Z"][l])
+        # dense attention: logits[i, j] for every source j, minus infinity where there is no edge; duplicates of an
+        # edge each count, so the mask holds multiplicities
+        mult = np.zeros((blk.n_dst, blk.n_src))
+        for i in range(blk.n_dst):
+            for e in range(blk.indptr[i], blk.indptr[i + 1]):
+                mult[i, blk.cols[e]] += 1
+            mult[i, i] += 1
+        a_src, a_dst = torch.tensor(att[l][:F]), torch.tensor(att[l][F:])
+        score = torch.nn.functional.leaky_relu((z[:blk.n_dst] @ a_dst)[:, None] + (z @ a_src)[None, :], 0.2)
+        wgt = torch.tensor(mult) * torch.exp(score - score.max())
+        alpha = wgt / wgt.sum(dim=1, keepdim=True)
+        pre = alpha @ z + torch.tensor(b[l])
+        Hn = cast(torch.relu(pre)) if l == 0 else pre
+        if l == 0:
+            same_up_to_a_rounding_boundary(ref["H"][l + 1], Hn.numpy())
+        else:
+            assert np.allclose(ref["H"][l + 1], Hn.numpy(), rtol=1e-11, atol=1e-13)
+        H = torch.tensor(ref["H"][l + 1])
+
+    def is_bf16(a):
+        t = torch.tensor(a)
+        return bool(torch.equal(cast(t), t))
+    assert is_bf16(ref["Z"][0]) and is_bf16(ref["Z"][1]) and is_bf16(ref["H"][1])
+    assert is_bf16(ref["dz"][0]) and is_bf16(ref["dz"][1]) and is_bf16(ref["dH"][1])
+    assert not is_bf16(ref["H"][2]) and not is_bf16(ref["dZ"]) and not is_bf16(ref["dW"][0]) and not is_bf16(ref["datt"][1])
+    for k in ("dW", "db", "datt", "W_new", "att_new"):
+        for l in range(2):
+            assert np.max(np.abs(ref[k][l] - plain[k][l])) <= 3e-2 * np.max(np.abs(plain[k][l])), (k, l)
+    assert abs(ref["loss"] - plain["loss"]) <= 2e-2 * abs(plain["loss"])
+
+
 # ----------------------------------------------------------------- Adam
 def test_adam_matches_library_optimiser():
     rng = np.random.default_rng(31)

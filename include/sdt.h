@@ -466,12 +466,13 @@ int32_t sdt_model_average(const float *const *params /*host array of device poin
  * with more partitions than GPUs a GPU trains the local models of its partitions one
  * after the other; Sec. III-D: all local models are then averaged in proportion to
  * their numbers of training nodes) ---------------------------------------------------
- * For each partition j: local[j] <- global (weights and biases copied), then
+ * For each partition j: local[j] <- global (weights and biases, and the attention
+ * vectors of a GAT model, copied), then
  * sdt_train_loop on partition j with local[j] for its n_steps mini-batches (step
  * counter first_step + i); finally global <- sum_j alpha_j local[j] with
  * alpha_j = n_train_j / sum n_train.  losses_d receives sum_j n_steps_j losses,
  * partition after partition.  `locals` are caller-allocated models of the same
- * shape as `global_model`.  ws must hold sdt_train_loop's workspace for the largest
+ * kind and shape as `global_model` (any of the three kinds).  ws must hold sdt_train_loop's workspace for the largest
  * partition (sdt_train_round_workspace_bytes). */
 typedef struct sdt_partition {
     sdt_csr graph;

@@ -43,14 +43,14 @@ InferWs infer_ws(int64_t n_nodes, const sdt_model* m, int32_t dtype) {
     return w;
 }
 
-// rows of layer l's weight matrix: [self | neighbour] halves for GraphSAGE, one block for GCN
-inline int64_t weight_rows(const sdt_model* m, int l) { return (m->kind == SDT_MODEL_GCN ? 1 : 2) * (int64_t)m->dims[l]; }
+// rows of layer l's weight matrix: [self | neighbour] halves for GraphSAGE, one block for GCN and GAT
+inline int64_t weight_rows(const sdt_model* m, int l) { return (m->kind == SDT_MODEL_SAGE_MEAN ? 2 : 1) * (int64_t)m->dims[l]; }
 
 int32_t check_model_ptrs(const sdt_model* m, const char* who) {
     SDT_REQUIRE(m && m->n_layers >= 1 && m->n_layers <= SDT_MAX_LAYERS, SDT_ERR_INVALID_ARG, "%s: bad model", who);
     for (int l = 0; l < m->n_layers; ++l)
-        SDT_REQUIRE(m->dims[l] > 0 && m->dims[l + 1] > 0 && m->W[l] && m->b[l], SDT_ERR_INVALID_ARG,
-                    "%s: layer %d has a null tensor or an empty dimension", who, l);
+        SDT_REQUIRE(m->dims[l] > 0 && m->dims[l + 1] > 0 && m->W[l] && m->b[l] && (m->kind != SDT_MODEL_GAT || m->att[l]),
+                    SDT_ERR_INVALID_ARG, "%s: layer %d has a null tensor or an empty dimension", who, l);
     return SDT_OK;
 }
 
@@ -154,8 +154,6 @@ extern "C" int32_t sdt_train_round(const sdt_partition* parts, int32_t n_parts, 
     if (rc != SDT_OK) return rc;
     SDT_REQUIRE(parts && locals && n_parts >= 1 && n_parts <= MAX_MODELS, SDT_ERR_INVALID_ARG,
                 "sdt_train_round: n_parts outside [1,%d] or null argument", MAX_MODELS);
-    SDT_REQUIRE(global_model->kind != SDT_MODEL_GAT, SDT_ERR_INVALID_ARG,
-                "sdt_train_round: GAT models are not supported (their attention vectors are not averaged here)");
     const int L = global_model->n_layers;
     double total = 0;
     for (int j = 0; j < n_parts; ++j) {
@@ -178,8 +176,10 @@ extern "C" int32_t sdt_train_round(const sdt_partition* parts, int32_t n_parts, 
         for (int l = 0; l < L; ++l) {
             const size_t wb = (size_t)weight_rows(global_model, l) * global_model->dims[l + 1] * sizeof(float);
             const size_t bb = (size_t)global_model->dims[l + 1] * sizeof(float);
+            const bool gat = global_model->kind == SDT_MODEL_GAT;   // ... and its attention vectors [a_src | a_dst]
             if (hipMemcpyAsync(locals[j].W[l], global_model->W[l], wb, hipMemcpyDeviceToDevice, st) != hipSuccess ||
-                hipMemcpyAsync(locals[j].b[l], global_model->b[l], bb, hipMemcpyDeviceToDevice, st) != hipSuccess) {
+                hipMemcpyAsync(locals[j].b[l], global_model->b[l], bb, hipMemcpyDeviceToDevice, st) != hipSuccess ||
+                (gat && hipMemcpyAsync(locals[j].att[l], global_model->att[l], 2 * bb, hipMemcpyDeviceToDevice, st) != hipSuccess)) {
                 set_error("sdt_train_round: copying the synchronised weights failed");
                 return SDT_ERR_HIP;
             }
@@ -206,6 +206,11 @@ extern "C" int32_t sdt_train_round(const sdt_partition* parts, int32_t n_parts, 
         for (int j = 0; j < n_parts; ++j) src[j] = locals[j].b[l];
         rc = sdt_model_average(src, alpha, n_parts, global_model->dims[l + 1], global_model->b[l], stream);
         if (rc != SDT_OK) return rc;
+        if (global_model->kind == SDT_MODEL_GAT) {
+            for (int j = 0; j < n_parts; ++j) src[j] = locals[j].att[l];
+            rc = sdt_model_average(src, alpha, n_parts, 2 * (int64_t)global_model->dims[l + 1], global_model->att[l], stream);
+            if (rc != SDT_OK) return rc;
+        }
     }
     return SDT_OK;
 }

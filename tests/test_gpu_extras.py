@@ -81,12 +81,32 @@ def test_train_round_over_partitions_with_replicas():
     _check_round(insts, [wl] * 3, [2, 3, 2])
 
 
-def _check_round(insts, wls, n_steps):
+@pytest.mark.parametrize("kind", ["gcn", "gat"])
+def test_train_round_other_model_kinds(kind):
+    """The same round with the single-matrix kinds; for GAT the attention vectors are synchronised too."""
+    _say(f"synchronisation round: three partitions with replicas, {kind} model")
+    wl = gen.Workload("tiny_p", "rmat", 13, 12, 64, 8, 64, 2, [10, 5], 256, 5, 2)
+    insts = [gen.make_partition_instance(wl, p=3, which=k) for k in range(3)]
+    _check_round(insts, [wl] * 3, [2, 3, 2], kind)
+
+
+def _check_round(insts, wls, n_steps, kind="sage"):
     fan, batch, lr, seed = [10, 5], 256, 0.05, 77
     init = insts[0]                                            # the synchronised starting weights
-    Wg = [dev(w) for w in init.W]
+    d = wls[0].dims
+    code = {"sage": B.SDT_MODEL_SAGE_MEAN, "gcn": B.SDT_MODEL_GCN, "gat": B.SDT_MODEL_GAT}[kind]
+    rng = np.random.default_rng(9)
+    W_init = init.W if kind == "sage" else [(rng.standard_normal((d[l], d[l + 1])) / np.sqrt(d[l])).astype(np.float32)
+                                            for l in range(2)]
+    a_init = [(rng.standard_normal(2 * d[l + 1]) * 0.3).astype(np.float32) for l in range(2)] if kind == "gat" else None
+
+    def model_of(Wt, bt, at):
+        return B.make_model(d, Wt, bt, kind=code, att=at, **({"gat_slope": 0.2} if kind == "gat" else {}))
+
+    Wg = [dev(w) for w in W_init]
     bg = [dev(v) for v in init.b]
-    gmodel = B.make_model(wls[0].dims, Wg, bg)
+    ag = [dev(v) for v in a_init] if a_init else None
+    gmodel = model_of(Wg, bg, ag)
     parts, locs, keep = [], [], []
     for inst, wl, ns in zip(insts, wls, n_steps):
         g = B.Csr(dev(inst.indptr), dev(inst.indices))
@@ -94,10 +114,11 @@ def _check_round(insts, wls, n_steps):
         seeds = dev(np.stack([inst.batch(s) for s in range(ns)]).astype(np.int32))
         Wl = [torch.zeros_like(w) for w in Wg]
         bl = [torch.zeros_like(v) for v in bg]
+        al = [torch.zeros_like(v) for v in ag] if ag else None
         n_train = inst.n_owned if inst.n_owned is not None else int(wl.n_nodes * wl.owned_frac)
         parts.append(B.make_partition(g, X, y, seeds, n_train))
-        locs.append(B.make_model(wls[0].dims, Wl, bl))
-        keep.append((g, X, y, seeds, Wl, bl, n_train))
+        locs.append(model_of(Wl, bl, al))
+        keep.append((g, X, y, seeds, Wl, bl, n_train, al))
     nbytes = B.sdt_train_round_workspace_bytes(parts, batch, fan, gmodel, B.SDT_F32)
     ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
     losses = torch.zeros(sum(n_steps), dtype=torch.float32, device="cuda")
@@ -108,10 +129,11 @@ def _check_round(insts, wls, n_steps):
     # (1) every local model equals a stand-alone loop from the same starting weights, bit for bit
     first = 0
     for j, (inst, wl, ns) in enumerate(zip(insts, wls, n_steps)):
-        g, X, y, seeds, Wl, bl, _ = keep[j]
-        W2 = [dev(w) for w in init.W]
+        g, X, y, seeds, Wl, bl, _, al = keep[j]
+        W2 = [dev(w) for w in W_init]
         b2 = [dev(v) for v in init.b]
-        m2 = B.make_model(wls[0].dims, W2, b2)
+        a2 = [dev(v) for v in a_init] if a_init else None
+        m2 = model_of(W2, b2, a2)
         ws2 = torch.zeros(B.sdt_train_loop_workspace_bytes(inst.n_nodes, batch, fan, m2, B.SDT_F32), dtype=torch.uint8,
                           device="cuda")
         l2 = torch.zeros(ns, dtype=torch.float32, device="cuda")
@@ -119,12 +141,19 @@ def _check_round(insts, wls, n_steps):
         torch.cuda.synchronize()
         for l in range(2):
             assert torch.equal(W2[l], Wl[l]) and torch.equal(b2[l], bl[l]), f"local model {j}, layer {l}"
+            assert a2 is None or torch.equal(a2[l], al[l]), f"local model {j}, attention vectors of layer {l}"
         assert torch.equal(l2, losses[first:first + ns])
         first += ns
     # (2) the first step of every partition matches the oracle (same starting weights)
     first = 0
     for j, (inst, wl, ns) in enumerate(zip(insts, wls, n_steps)):
-        ref = orc.train_step(inst.indptr, inst.indices, inst.X, inst.y, inst.batch(0), fan, init.W, init.b, seed, 0, lr)
+        if kind == "gat":
+            ref = orc.gat_train_step(inst.indptr, inst.indices, inst.X, inst.y, inst.batch(0), fan, W_init, init.b, a_init, seed,
+                                     0, lr, 0.2)
+        elif kind == "gcn":
+            ref = orc.gcn_train_step(inst.indptr, inst.indices, inst.X, inst.y, inst.batch(0), fan, W_init, init.b, seed, 0, lr)
+        else:
+            ref = orc.train_step(inst.indptr, inst.indices, inst.X, inst.y, inst.batch(0), fan, init.W, init.b, seed, 0, lr)
         assert abs(float(losses[first]) - ref["loss"]) <= 1e-5 * max(1.0, abs(ref["loss"]))
         first += ns
     # (3) the synchronised model is the average of the local ones, weighted by their training nodes
@@ -132,6 +161,8 @@ def _check_round(insts, wls, n_steps):
     for l in range(2):
         assert_close(f64(Wg[l]), orc.model_average([f64(k[4][l]) for k in keep], n_train), 1e-6, f"averaged W[{l}]")
         assert_close(f64(bg[l]), orc.model_average([f64(k[5][l]) for k in keep], n_train), 1e-6, f"averaged b[{l}]")
+        if ag:
+            assert_close(f64(ag[l]), orc.model_average([f64(k[7][l]) for k in keep], n_train), 1e-6, f"averaged att[{l}]")
 
 
 # ------------------------------------------------ whole-graph layer in one launch

@@ -447,7 +447,12 @@ int32_t sdt_train_loop(const sdt_csr *graph /*host struct*/, const void *X, int6
  * H_0 = X.  logits is device fp32 [n_nodes, dims[L]] with leading dimension ldl.
  * Hidden activations are kept in `dtype` (bf16: rounded as in the training step).
  * n_nodes must be below 2^31.  The workspace (size from the query; no state) holds
- * the aggregated rows and two hidden-activation buffers of n_nodes rows each. */
+ * the aggregated rows and two hidden-activation buffers of n_nodes rows each.
+ * GCN and GAT models run the layer of their training step with the whole graph as the
+ * block (every node a destination, every neighbour kept: the GCN weights are those of
+ * D~^-1/2 (Adj + I) D~^-1/2).  For these two kinds the graph must hold fewer than 2^31
+ * edges, and the call reads the edge count back first: it synchronises `stream` once
+ * (an error, not a fault, if there are more). */
 size_t sdt_infer_layerwise_workspace_bytes(int64_t n_nodes, const sdt_model *model /*host struct*/, int32_t dtype);
 int32_t sdt_infer_layerwise(const sdt_csr *graph /*host struct*/, const void *X, int64_t ldx, int32_t dtype,
                             const sdt_model *model /*host struct*/, float *logits, int64_t ldl, void *ws,

@@ -286,21 +286,42 @@ def train_step(indptr, indices, X, y, seeds, fanouts, W, b, seed: int, step: int
 
 
 # ------------------------------------------------- beyond the mini-batch step
-def infer_layerwise(indptr, indices, X, W, b, bf16: bool = False) -> np.ndarray:
+def infer_layerwise(indptr, indices, X, W, b, bf16: bool = False, kind: str = "sage", att=None,
+                    slope: float = 0.2) -> np.ndarray:
     """Full-neighbour inference, one layer at a time over every node of the
     partition (the evaluation pass of Sec. IV-A: a trained model is scored on
     nodes with all of their neighbours, no sampling): for each layer,
     A = mean over the whole CSR row, H' = act(H W_self + A W_neigh + b), ReLU on
     all but the last layer.  Rounding points as in forward().  Returns the
-    logits of all nodes in float64."""
+    logits of all nodes in float64.
+    kind = "gcn" / "gat": the same pass with the layer of gcn_train_step / gat_train_step, the block of
+    a layer being the whole graph (every node a destination, its CSR row the edges, every neighbour
+    kept, so the GCN weights are those of D~^-1/2 (Adj + I) D~^-1/2), and their rounding points."""
     rnd = round_bf16 if bf16 else (lambda t: t)
     H = bf16_bits_to_f64(np.asarray(X)) if bf16 else np.asarray(X, dtype=np.float64)
     L = len(W)
     ip = np.asarray(indptr, dtype=np.int64)
     cols = np.asarray(indices, dtype=np.int32)
+    n = len(ip) - 1
+    if kind == "gcn":
+        s, c, selfw = gcn_weights(ip, np.arange(n), ip)
     for l in range(L):
-        a = rnd(aggregate_fwd(ip, cols, H))
-        z = linear_fwd(H, a, rnd(np.asarray(W[l], dtype=np.float64)), np.asarray(b[l], dtype=np.float64), relu=(l < L - 1))
+        Wl, bl = np.asarray(W[l], dtype=np.float64), np.asarray(b[l], dtype=np.float64)
+        if kind == "sage":
+            a = rnd(aggregate_fwd(ip, cols, H))
+            z = linear_fwd(H, a, rnd(Wl), bl, relu=(l < L - 1))
+        elif kind == "gcn":
+            a = rnd(gcn_aggregate_fwd(ip, cols, H, s, c, selfw))
+            z = gcn_linear_fwd(a, rnd(Wl), bl, relu=(l < L - 1))
+        elif kind == "gat":
+            F = Wl.shape[1]
+            a = np.asarray(att[l], dtype=np.float64)
+            proj = rnd(H @ rnd(Wl))
+            z = gat_aggregate_fwd(ip, cols, proj, a[:F], a[F:], slope)[0] + bl
+            if l < L - 1:
+                z = np.maximum(z, 0.0)
+        else:
+            raise ValueError(kind)
         H = rnd(z) if l < L - 1 else z
     return H
 

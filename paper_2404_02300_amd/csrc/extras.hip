@@ -21,24 +21,65 @@ __global__ __launch_bounds__(256) void k_model_average(AvgArgs a, int64_t n_elem
     }
 }
 
+// The whole graph as the block of a layer (GCN and GAT inference): every node a destination and a source,
+// its CSR row the edges.  The kernels of those kinds take 32-bit row offsets and the counts on the device;
+// for GCN the normalisation of a block in which every neighbour is kept (c = s = 1/sqrt(deg + 1), s = 0 for a
+// node without neighbours, selfw = 1/(deg + 1)).  c, s, selfw may be null.
+__global__ __launch_bounds__(256) void k_whole_graph_block(const int64_t* __restrict__ indptr, int n, int32_t* __restrict__ indptr32,
+                                                           int32_t* __restrict__ counts, float* __restrict__ c,
+                                                           float* __restrict__ s, float* __restrict__ selfw) {
+    for (int v = blockIdx.x * 256 + threadIdx.x; v <= n; v += gridDim.x * 256) {
+        const int64_t e0 = indptr[v];
+        indptr32[v] = (int32_t)e0;
+        if (v < n && c) {
+            const float deg = (float)(indptr[v + 1] - e0);
+            const float r = 1.0f / sqrtf(deg + 1.0f);
+            c[v] = r;
+            s[v] = deg > 0.f ? r : 0.f;
+            selfw[v] = 1.0f / (deg + 1.0f);
+        }
+        if (v == n) {
+            counts[0] = n;
+            counts[1] = n;
+            counts[2] = (int32_t)e0;
+            counts[3] = 0;
+        }
+    }
+}
+
 struct InferWs {
     size_t a_off, h_off[2], w_off, total;
+    size_t ip_off, cnt_off, norm_off[3], gat_off, gat_len;   // GCN / GAT kinds only
 };
 InferWs infer_ws(int64_t n_nodes, const sdt_model* m, int32_t dtype) {
     const size_t es = dtype_size(dtype);
-    int32_t max_in = 0, max_hidden = 0;
-    size_t wb = 0;
+    int32_t max_in = 0, max_hidden = 0, max_out = 0;
+    size_t wb = 0, gat_len = 0;
     for (int l = 0; l < m->n_layers; ++l) {
         if (m->dims[l] > max_in) max_in = m->dims[l];
         if (l + 1 < m->n_layers && m->dims[l + 1] > max_hidden) max_hidden = m->dims[l + 1];
-        if (dtype == SDT_BF16) wb += bf16_weights_bytes(m->dims[l], m->dims[l + 1]);
+        if (m->dims[l + 1] > max_out) max_out = m->dims[l + 1];
+        if (dtype == SDT_BF16 && m->kind == SDT_MODEL_SAGE_MEAN) wb += bf16_weights_bytes(m->dims[l], m->dims[l + 1]);
+        if (m->kind == SDT_MODEL_GAT) {
+            const size_t g = sdt_gat_workspace_bytes((int32_t)n_nodes, (int32_t)n_nodes, m->dims[l + 1]);
+            if (g > gat_len) gat_len = g;
+        }
     }
-    InferWs w;
+    InferWs w{};
     Arena a(nullptr);
-    w.a_off = a.take_off((size_t)n_nodes * max_in * es);
+    // the operand of the projection: the aggregated rows (GraphSAGE, GCN), or its result, the projected rows (GAT)
+    w.a_off = a.take_off((size_t)n_nodes * (m->kind == SDT_MODEL_GAT ? max_out : max_in) * es);
     w.h_off[0] = a.take_off((size_t)n_nodes * (max_hidden > 0 ? max_hidden : 1) * es);
     w.h_off[1] = a.take_off((size_t)n_nodes * (max_hidden > 0 ? max_hidden : 1) * es);
     w.w_off = a.take_off(wb);
+    if (m->kind != SDT_MODEL_SAGE_MEAN) {
+        w.ip_off = a.take_off(((size_t)n_nodes + 1) * sizeof(int32_t));
+        w.cnt_off = a.take_off(4 * sizeof(int32_t));
+        if (m->kind == SDT_MODEL_GCN)
+            for (int k = 0; k < 3; ++k) w.norm_off[k] = a.take_off((size_t)n_nodes * sizeof(float));
+        w.gat_len = gat_len;
+        w.gat_off = a.take_off(gat_len);
+    }
     w.total = a.off;
     return w;
 }
@@ -54,13 +95,75 @@ int32_t check_model_ptrs(const sdt_model* m, const char* who) {
     return SDT_OK;
 }
 
+// Layer-wise inference of the GCN and GAT kinds: the layer of their training step with the whole graph as its block.
+int32_t infer_single_matrix_kinds(const sdt_csr* graph, const void* X, int64_t ldx, int32_t dtype, const sdt_model* model,
+                                  float* logits, int64_t ldl, char* base, const InferWs& w, hipStream_t st) {
+    const int32_t N = (int32_t)graph->n_nodes;
+    const int L = model->n_layers;
+    const int32_t* d = model->dims;
+    const size_t es = dtype_size(dtype);
+    SDT_REQUIRE(graph->indices, SDT_ERR_INVALID_ARG, "sdt_infer_layerwise: null graph indices");
+    // the blocks of these kinds count edges in 32 bits: read the edge count once (this synchronises the stream)
+    int64_t nnz = 0;
+    if (hipMemcpyAsync(&nnz, graph->indptr + N, sizeof(nnz), hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess) {
+        set_error("sdt_infer_layerwise: reading the edge count failed");
+        return SDT_ERR_HIP;
+    }
+    SDT_REQUIRE(nnz >= 0 && nnz < 0x7FFFFFFF, SDT_ERR_INVALID_ARG,
+                "sdt_infer_layerwise: %lld edges; the GCN and GAT kinds need fewer than 2^31", (long long)nnz);
+    sdt_block blk{};
+    blk.cap_dst = blk.cap_src = N;
+    blk.cap_nnz = (int32_t)nnz;
+    blk.counts = reinterpret_cast<int32_t*>(base + w.cnt_off);
+    blk.indptr = reinterpret_cast<int32_t*>(base + w.ip_off);
+    blk.cols = const_cast<int32_t*>(graph->indices);   // read only
+    const bool gcn = model->kind == SDT_MODEL_GCN;
+    float* c = gcn ? reinterpret_cast<float*>(base + w.norm_off[0]) : nullptr;
+    float* s = gcn ? reinterpret_cast<float*>(base + w.norm_off[1]) : nullptr;
+    float* selfw = gcn ? reinterpret_cast<float*>(base + w.norm_off[2]) : nullptr;
+    const int64_t blocks = ((int64_t)N + 256) / 256;
+    hipLaunchKernelGGL(k_whole_graph_block, dim3(blocks > 2048 ? 2048 : (int)blocks), dim3(256), 0, st, graph->indptr, N, blk.indptr,
+                       blk.counts, c, s, selfw);
+    SDT_CHECK_LAUNCH("whole-graph block");
+    const char* H = static_cast<const char*>(X);
+    int64_t ldh = ldx;
+    int32_t rc;
+    for (int l = 0; l < L; ++l) {
+        const bool last = l == L - 1;
+        const int F = d[l + 1];
+        void* Y = last ? static_cast<void*>(logits) : static_cast<void*>(base + w.h_off[l & 1]);
+        const int64_t ldy = last ? ldl : F;
+        const int32_t y_dtype = last ? SDT_F32 : dtype;
+        char* T = base + w.a_off;
+        if (gcn) {
+            rc = gcn_aggregate_fwd(&blk, H, ldh, false, d[l], dtype, c, s, selfw, T, d[l], st);
+            if (rc != SDT_OK) return rc;
+            rc = linear_fwd(T, d[l], T + (size_t)(d[l] / 2) * es, d[l], N, nullptr, d[l] / 2, F, model->W[l], model->b[l],
+                            last ? 0 : 1, dtype, Y, ldy, y_dtype, false, st);
+        } else {
+            rc = linear_fwd(H, ldh, H + (size_t)(d[l] / 2) * es, ldh, N, nullptr, d[l] / 2, F, model->W[l], nullptr, 0, dtype, T, F,
+                            dtype, false, st);
+            if (rc != SDT_OK) return rc;
+            rc = gat_forward(&blk, T, F, F, dtype, model->att[l], model->att[l] + F, model->gat_slope, model->b[l], last ? 0 : 1, Y,
+                             ldy, y_dtype, base + w.gat_off, w.gat_len, st);
+        }
+        if (rc != SDT_OK) return rc;
+        H = static_cast<const char*>(Y);
+        ldh = ldy;
+    }
+    return SDT_OK;
+}
+
 }  // namespace
 }  // namespace sdt
 
 using namespace sdt;
 
 extern "C" size_t sdt_infer_layerwise_workspace_bytes(int64_t n_nodes, const sdt_model* model, int32_t dtype) {
-    if (!model || n_nodes < 0 || !dtype_ok(dtype) || model->n_layers < 1 || model->n_layers > SDT_MAX_LAYERS) return 0;
+    if (!model || n_nodes < 0 || n_nodes >= 0x7FFFFFFF || !dtype_ok(dtype) || model->n_layers < 1 ||
+        model->n_layers > SDT_MAX_LAYERS)
+        return 0;
     return infer_ws(n_nodes, model, dtype).total;
 }
 
@@ -70,7 +173,15 @@ extern "C" int32_t sdt_infer_layerwise(const sdt_csr* graph, const void* X, int6
     int32_t rc = check_model_ptrs(model, "sdt_infer_layerwise");
     if (rc != SDT_OK) return rc;
     SDT_REQUIRE(graph && graph->indptr && dtype_ok(dtype), SDT_ERR_INVALID_ARG, "sdt_infer_layerwise: null graph or dtype");
-    SDT_REQUIRE(model->kind == SDT_MODEL_SAGE_MEAN, SDT_ERR_INVALID_ARG, "sdt_infer_layerwise: GraphSAGE-mean models only");
+    const int32_t kind = model->kind;
+    SDT_REQUIRE(kind == SDT_MODEL_SAGE_MEAN || kind == SDT_MODEL_GCN || kind == SDT_MODEL_GAT, SDT_ERR_INVALID_ARG,
+                "sdt_infer_layerwise: unknown model kind %d", kind);
+    SDT_REQUIRE(kind != SDT_MODEL_GAT || (model->gat_slope >= 0.f && model->gat_slope <= 1.f), SDT_ERR_INVALID_ARG,
+                "sdt_infer_layerwise: gat_slope %g outside [0,1]", (double)model->gat_slope);
+    if (kind != SDT_MODEL_SAGE_MEAN)
+        for (int l = 0; l < model->n_layers; ++l)
+            SDT_REQUIRE(model->dims[l] % 2 == 0, SDT_ERR_INVALID_ARG,
+                        "sdt_infer_layerwise: GCN and GAT need even layer input widths (dims[%d] = %d)", l, model->dims[l]);
     const int64_t N = graph->n_nodes;
     SDT_REQUIRE(N >= 0 && N < 0x7FFFFFFF, SDT_ERR_INVALID_ARG, "sdt_infer_layerwise: n_nodes %lld out of range",
                 (long long)N);
@@ -84,6 +195,7 @@ extern "C" int32_t sdt_infer_layerwise(const sdt_csr* graph, const void* X, int6
                 "sdt_infer_layerwise: workspace of %zu bytes needed, %zu given", w.total, ws_bytes);
     hipStream_t st = static_cast<hipStream_t>(stream);
     char* base = static_cast<char*>(ws);
+    if (kind != SDT_MODEL_SAGE_MEAN) return infer_single_matrix_kinds(graph, X, ldx, dtype, model, logits, ldl, base, w, st);
     const char* wt[SDT_MAX_LAYERS] = {};
     if (dtype == SDT_BF16) {
         rc = convert_weights_bf16(model, base + w.w_off, st);

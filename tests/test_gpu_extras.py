@@ -46,6 +46,39 @@ def test_infer_layerwise_all_rows(name):
     assert e.value.code == B.SDT_ERR_WORKSPACE
 
 
+@pytest.mark.parametrize("kind", ["gcn", "gat"])
+@pytest.mark.parametrize("name", ["tiny", "small_bf16", "even"])
+def test_infer_layerwise_other_model_kinds(name, kind):
+    """The same pass with the GCN and the GAT layer: the whole graph is the block of every layer."""
+    _say(f"layer-wise inference, {kind} model: {name}")
+    wl = {"tiny": gen.WORKLOADS["tiny"],
+          "small_bf16": gen.Workload("small_bf16", "rmat", 13, 12, 40, 10, 48, 3, [6, 4, 3], 128, 7, 2, bf16=True),
+          # widths that are even (the two kinds need that) but no multiples of four: the one-element kernels
+          "even": gen.Workload("even", "rmat", 12, 10, 38, 5, 22, 2, [4, 3], 100, 9, 1)}[name]
+    inst = gen.make_instance(wl)
+    d, L = wl.dims, len(wl.fanouts)
+    rng = np.random.default_rng(17)
+    Wh = [(rng.standard_normal((d[l], d[l + 1])) / np.sqrt(d[l])).astype(np.float32) for l in range(L)]
+    ah = [(rng.standard_normal(2 * d[l + 1]) * 0.3).astype(np.float32) for l in range(L)]
+    g = B.Csr(dev(inst.indptr), dev(inst.indices))
+    X = bf16_from_bits(inst.X).cuda() if wl.bf16 else dev(inst.X)
+    W, b, att = [dev(w) for w in Wh], [dev(v) for v in inst.b], [dev(v) for v in ah]
+    if kind == "gat":
+        model = B.make_model(d, W, b, kind=B.SDT_MODEL_GAT, att=att, gat_slope=0.2)
+    else:
+        model = B.make_model(d, W, b, kind=B.SDT_MODEL_GCN)
+    code = B.SDT_BF16 if wl.bf16 else B.SDT_F32
+    ws = torch.empty(B.sdt_infer_layerwise_workspace_bytes(wl.n_nodes, model, code), dtype=torch.uint8, device="cuda")
+    logits = torch.full((wl.n_nodes, d[-1]), float("nan"), dtype=torch.float32, device="cuda")
+    B.sdt_infer_layerwise(g, X, model, logits, ws)
+    torch.cuda.synchronize()
+    ref = orc.infer_layerwise(inst.indptr, inst.indices, inst.X, Wh, inst.b, bf16=wl.bf16, kind=kind, att=ah)
+    assert_close(f64(logits), ref, TOL[torch.bfloat16 if wl.bf16 else torch.float32], "logits of every node")
+    with pytest.raises(B.SdtError) as e:
+        B.sdt_infer_layerwise(g, X, model, logits, ws[:1024])
+    assert e.value.code == B.SDT_ERR_WORKSPACE
+
+
 @pytest.mark.parametrize("n_models,n", [(1, 1000), (3, 12345), (64, 70001)])
 def test_model_average(n_models, n):
     _say(f"model average: {n_models} models of {n} elements")

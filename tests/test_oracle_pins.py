@@ -450,6 +450,50 @@ def test_infer_layerwise_agrees_with_a_full_fanout_training_forward():
     assert np.allclose(step["logits"], full[seeds], rtol=1e-12, atol=1e-12)
 
 
+@pytest.mark.parametrize("kind", ["gcn", "gat"])
+def test_infer_layerwise_other_kinds(kind):
+    """The GCN and GAT passes over the whole graph: (a) against dense formulations written with torch (GCN: the
+    symmetric normalised adjacency with self loops; GAT: a dense softmax weighted by edge multiplicities, self edge included), (b) against the
+    logits of the seeds in a training step whose fan-outs keep every neighbour."""
+    rng = np.random.default_rng(14)
+    n, dims = 50, [6, 8, 3]
+    rows = [np.sort(rng.choice(n, size=int(rng.integers(0, 6)), replace=False)) for _ in range(n)]
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    indptr[1:] = np.cumsum([len(r) for r in rows])
+    indices = np.concatenate(rows).astype(np.int32)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    y = rng.integers(0, dims[2], size=n).astype(np.int32)
+    W = [rng.standard_normal((dims[l], dims[l + 1])) * 0.4 for l in range(2)]
+    b = [rng.standard_normal(dims[l + 1]) * 0.1 for l in range(2)]
+    att = [rng.standard_normal(2 * dims[l + 1]) * 0.5 for l in range(2)]
+    got = orc.infer_layerwise(indptr, indices, X, W, b, kind=kind, att=att)
+    Adj = torch.zeros((n, n), dtype=torch.float64)
+    for v, r in enumerate(rows):
+        for u in r:
+            Adj[v, u] += 1.0
+    H = torch.tensor(X, dtype=torch.float64)
+    for l in range(2):
+        if kind == "gcn":
+            dinv = torch.diag((Adj.sum(dim=1) + 1.0) ** -0.5)
+            Z = dinv @ (Adj + torch.eye(n, dtype=torch.float64)) @ dinv @ H @ torch.tensor(W[l]) + torch.tensor(b[l])
+        else:
+            F = dims[l + 1]
+            z = H @ torch.tensor(W[l])
+            score = torch.nn.functional.leaky_relu((z @ torch.tensor(att[l][F:]))[:, None] + (z @ torch.tensor(att[l][:F]))[None, :], 0.2)
+            # an edge v -> v in the graph counts beside the built-in self edge: the mask holds multiplicities
+            wgt = (Adj + torch.eye(n, dtype=torch.float64)) * torch.exp(score - score.max())
+            Z = (wgt / wgt.sum(dim=1, keepdim=True)) @ z + torch.tensor(b[l])
+        H = torch.relu(Z) if l == 0 else Z
+    assert np.allclose(got, H.numpy(), rtol=1e-11, atol=1e-12)
+    assert any(len(r) == 0 for r in rows), "the fixture should contain an isolated node"
+    seeds = np.array([3, 17, 42, 0, 49], dtype=np.int32)
+    if kind == "gcn":
+        step = orc.gcn_train_step(indptr, indices, X, y, seeds, [8, 8], W, b, seed=5, step=0, lr=0.0)
+    else:
+        step = orc.gat_train_step(indptr, indices, X, y, seeds, [8, 8], W, b, att, seed=5, step=0, lr=0.0)
+    assert np.allclose(step["logits"], got[seeds], rtol=1e-11, atol=1e-12)
+
+
 def test_model_average_closed_forms():
     rng = np.random.default_rng(13)
     a, c = rng.standard_normal(50), rng.standard_normal(50)

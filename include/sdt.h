@@ -274,8 +274,9 @@ int32_t sdt_gcn_aggregate_bwd(const sdt_block *blk /*host struct*/, const void *
 /* ---- GAT attention aggregation on a sampled block (Sec. III-E: GAT is one of the
  * integrated models; the variant is not described: one head, LeakyReLU slope argument,
  * and a self edge so that no softmax is empty) ----------------------------------------
- * z is the already projected feature matrix, fp32 [n_src, F] (row i < n_dst is
- * destination i itself); a_src, a_dst are fp32 [F].
+ * z is the already projected feature matrix, [n_src, F] in `dtype` (row i < n_dst is
+ * destination i itself); a_src, a_dst are fp32 [F].  out, g and dz are in `dtype` too (fp32 or
+ * bf16: widened on load, rounded on store); scores, softmax and every sum are fp32.
  *   s_(i<-j) = LeakyReLU(a_dst . z_i + a_src . z_j) over row i's edges and j = i,
  *   alpha = softmax over that set, out[i,:] = sum alpha_(i<-j) z[j,:]          (forward)
  * The backward takes g = d loss / d out [n_dst, F] and writes dz [n_src, F] (overwritten),
@@ -283,12 +284,12 @@ int32_t sdt_gcn_aggregate_bwd(const sdt_block *blk /*host struct*/, const void *
  * that the matching forward call used (the forward leaves z a_src, z a_dst and each row's
  * log-sum-exp there).  Deterministic: no atomics, fixed summation orders. */
 size_t sdt_gat_workspace_bytes(int32_t cap_src, int32_t cap_dst, int32_t F);
-int32_t sdt_gat_aggregate_fwd(const sdt_block *blk /*host struct*/, const float *z, int64_t ldz, int32_t F,
-                              const float *a_src, const float *a_dst, float slope, float *out, int64_t ldo, void *ws,
+int32_t sdt_gat_aggregate_fwd(const sdt_block *blk /*host struct*/, const void *z, int64_t ldz, int32_t F, int32_t dtype,
+                              const float *a_src, const float *a_dst, float slope, void *out, int64_t ldo, void *ws,
                               size_t ws_bytes, void *stream);
-int32_t sdt_gat_aggregate_bwd(const sdt_block *blk /*host struct*/, const float *z, int64_t ldz, int32_t F,
-                              const float *a_src, const float *a_dst, float slope, const float *g, int64_t ldg,
-                              float *dz, int64_t lddz, float *da_src, float *da_dst, void *ws, size_t ws_bytes,
+int32_t sdt_gat_aggregate_bwd(const sdt_block *blk /*host struct*/, const void *z, int64_t ldz, int32_t F, int32_t dtype,
+                              const float *a_src, const float *a_dst, float slope, const void *g, int64_t ldg,
+                              void *dz, int64_t lddz, float *da_src, float *da_dst, void *ws, size_t ws_bytes,
                               void *stream);
 
 /* ---- GraphSAGE projection (Sec. III-E / IV-A: GraphSAGE is the model trained)

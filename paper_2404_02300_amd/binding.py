@@ -101,9 +101,9 @@ EXPORTS = {
     "sdt_gcn_aggregate_fwd": (_i32, [_vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _i64, _vp]),
     "sdt_gcn_aggregate_bwd": (_i32, [_vp, _vp, _i64, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _i64, _vp]),
     "sdt_gat_workspace_bytes": (_sz, [_i32, _i32, _i32]),
-    "sdt_gat_aggregate_fwd": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp, ctypes.c_float, _vp, _i64, _vp, _sz, _vp]),
-    "sdt_gat_aggregate_bwd": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp, ctypes.c_float, _vp, _i64, _vp, _i64, _vp, _vp, _vp,
-                                     _sz, _vp]),
+    "sdt_gat_aggregate_fwd": (_i32, [_vp, _vp, _i64, _i32, _i32, _vp, _vp, ctypes.c_float, _vp, _i64, _vp, _sz, _vp]),
+    "sdt_gat_aggregate_bwd": (_i32, [_vp, _vp, _i64, _i32, _i32, _vp, _vp, ctypes.c_float, _vp, _i64, _vp, _i64, _vp, _vp,
+                                     _vp, _sz, _vp]),
     "sdt_infer_layerwise_workspace_bytes": (_sz, [_i64, _vp, _i32]),
     "sdt_infer_layerwise": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp, _i64, _vp, _sz, _vp]),
     "sdt_model_average": (_i32, [_vp, _vp, _i32, _i64, _vp, _vp]),
@@ -428,17 +428,19 @@ def sdt_gat_workspace_bytes(cap_src: int, cap_dst: int, F: int) -> int:
 
 def sdt_gat_aggregate_fwd(blk: Block, z: torch.Tensor, a_src: torch.Tensor, a_dst: torch.Tensor, slope: float,
                           out: torch.Tensor, ws: torch.Tensor):
-    _check(lib().sdt_gat_aggregate_fwd(ctypes.byref(blk.c), _ptr(z), z.stride(0), z.shape[1], _ptr(a_src), _ptr(a_dst),
-                                       slope, _ptr(out), out.stride(0), _ptr(ws), ws.numel() * ws.element_size(),
-                                       _stream()))
+    assert out.dtype == z.dtype
+    _check(lib().sdt_gat_aggregate_fwd(ctypes.byref(blk.c), _ptr(z), z.stride(0), z.shape[1], dtype_code(z), _ptr(a_src),
+                                       _ptr(a_dst), slope, _ptr(out), out.stride(0), _ptr(ws),
+                                       ws.numel() * ws.element_size(), _stream()))
 
 
 def sdt_gat_aggregate_bwd(blk: Block, z: torch.Tensor, a_src: torch.Tensor, a_dst: torch.Tensor, slope: float,
                           g: torch.Tensor, dz: torch.Tensor, da_src: torch.Tensor, da_dst: torch.Tensor,
                           ws: torch.Tensor):
-    _check(lib().sdt_gat_aggregate_bwd(ctypes.byref(blk.c), _ptr(z), z.stride(0), z.shape[1], _ptr(a_src), _ptr(a_dst),
-                                       slope, _ptr(g), g.stride(0), _ptr(dz), dz.stride(0), _ptr(da_src), _ptr(da_dst),
-                                       _ptr(ws), ws.numel() * ws.element_size(), _stream()))
+    assert g.dtype == z.dtype and dz.dtype == z.dtype
+    _check(lib().sdt_gat_aggregate_bwd(ctypes.byref(blk.c), _ptr(z), z.stride(0), z.shape[1], dtype_code(z), _ptr(a_src),
+                                       _ptr(a_dst), slope, _ptr(g), g.stride(0), _ptr(dz), dz.stride(0), _ptr(da_src),
+                                       _ptr(da_dst), _ptr(ws), ws.numel() * ws.element_size(), _stream()))
 
 
 def sdt_infer_layerwise_workspace_bytes(n_nodes: int, model: sdt_model, dtype: int) -> int:

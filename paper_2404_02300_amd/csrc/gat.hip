@@ -606,10 +606,10 @@ extern "C" size_t sdt_gat_workspace_bytes(int32_t cap_src, int32_t cap_dst, int3
     return gat_ws(nullptr, cap_src, cap_dst, F).total;
 }
 
-extern "C" int32_t sdt_gat_aggregate_fwd(const sdt_block* blk, const float* z, int64_t ldz, int32_t F, const float* a_src,
-                                         const float* a_dst, float slope, float* out, int64_t ldo, void* ws, size_t ws_bytes,
-                                         void* stream) {
-    return gat_forward(blk, z, ldz, F, SDT_F32, a_src, a_dst, slope, nullptr, 0, out, ldo, SDT_F32, ws, ws_bytes,
+extern "C" int32_t sdt_gat_aggregate_fwd(const sdt_block* blk, const void* z, int64_t ldz, int32_t F, int32_t dtype,
+                                         const float* a_src, const float* a_dst, float slope, void* out, int64_t ldo, void* ws,
+                                         size_t ws_bytes, void* stream) {
+    return gat_forward(blk, z, ldz, F, dtype, a_src, a_dst, slope, nullptr, 0, out, ldo, dtype, ws, ws_bytes,
                        static_cast<hipStream_t>(stream));
 }
 
@@ -637,14 +637,15 @@ int32_t sdt::gat_forward(const sdt_block* blk, const void* z, int64_t ldz, int32
                      st);
 }
 
-extern "C" int32_t sdt_gat_aggregate_bwd(const sdt_block* blk, const float* z, int64_t ldz, int32_t F, const float* a_src,
-                                         const float* a_dst, float slope, const float* g, int64_t ldg, float* dz,
-                                         int64_t lddz, float* da_src, float* da_dst, void* ws, size_t ws_bytes, void* stream) {
+extern "C" int32_t sdt_gat_aggregate_bwd(const sdt_block* blk, const void* z, int64_t ldz, int32_t F, int32_t dtype,
+                                         const float* a_src, const float* a_dst, float slope, const void* g, int64_t ldg,
+                                         void* dz, int64_t lddz, float* da_src, float* da_dst, void* ws, size_t ws_bytes,
+                                         void* stream) {
     SDT_REQUIRE(da_src && da_dst, SDT_ERR_INVALID_ARG, "sdt_gat_aggregate_bwd: null attention-vector gradient");
     hipStream_t st = static_cast<hipStream_t>(stream);
     const float* part = nullptr;
     int32_t n_part = 0;
-    const int32_t rc = gat_backward(blk, z, ldz, F, SDT_F32, a_src, a_dst, slope, g, ldg, SDT_F32, dz, lddz, ws, ws_bytes, &part,
+    const int32_t rc = gat_backward(blk, z, ldz, F, dtype, a_src, a_dst, slope, g, ldg, dtype, dz, lddz, ws, ws_bytes, &part,
                                     &n_part, st);
     if (rc != SDT_OK || !part) return rc;
     hipLaunchKernelGGL(k_gat_vec_final, dim3(ceil_div(F, TB)), dim3(TB), 0, st, part, n_part, F, da_src, da_dst);

@@ -133,37 +133,43 @@ def test_gcn_train_step(classes, bf16):
         _say(f"  step {step}: loss {float(loss):.6f} ok")
 
 
-@pytest.mark.parametrize("F,fanout", [(64, 8), (100, 5), (256, 10), (7, 64)])
-def test_gat_attention_aggregation(F, fanout):
-    _say(f"GAT attention aggregation fwd / bwd, F={F}, fanout={fanout}")
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("F,fanout", [(64, 8), (100, 5), (256, 10), (7, 64), (300, 6)])
+def test_gat_attention_aggregation(F, fanout, bf16):
+    _say(f"GAT attention aggregation fwd / bwd, F={F}, fanout={fanout}, bf16={bf16}")
     rng = np.random.default_rng(F + fanout)
     n = 3000
     indptr, indices = _graph(rng, n, 10)
     dst = np.concatenate([[5], rng.choice(np.arange(6, n), size=599, replace=False)]).astype(np.int32)
     blk = orc.sample_block(indptr, indices, dst, fanout, 23, 1, 0)
-    z = (rng.standard_normal((blk.n_src, F)) * 0.7).astype(np.float32)
+    dt = torch.bfloat16 if bf16 else torch.float32
+    # bf16 storage: both sides start from the same bf16 numbers; what the kernels store (out, dz) is one rounding away
+    # from the fp32 result (2^-9 relative, and the bar is taken at twice that), the fp32 outputs keep the fp32 bar
+    tol_stored = 2.0 ** -8 if bf16 else TOL
+    zt = torch.from_numpy((rng.standard_normal((blk.n_src, F)) * 0.7).astype(np.float32)).to(dt)
+    gt = torch.from_numpy(rng.standard_normal((blk.n_dst, F)).astype(np.float32)).to(dt)
+    z, g = f64(zt), f64(gt)
     a_src = (rng.standard_normal(F) * 0.5).astype(np.float32)
     a_dst = (rng.standard_normal(F) * 0.5).astype(np.float32)
-    g = rng.standard_normal((blk.n_dst, F)).astype(np.float32)
     ref, _, _ = orc.gat_aggregate_fwd(blk.indptr, blk.cols, z, a_src, a_dst, 0.2)
     rdz, rda_s, rda_d = orc.gat_aggregate_bwd(blk.indptr, blk.cols, z, a_src, a_dst, g, 0.2)
     gb = upload_block(blk)
     ws = torch.empty(B.sdt_gat_workspace_bytes(blk.n_src, blk.n_dst, F), dtype=torch.uint8, device="cuda")
-    dzz, das, dad = dev(z), dev(a_src), dev(a_dst)
-    out = torch.full((blk.n_dst, F), float("nan"), dtype=torch.float32, device="cuda")
+    dzz, dg, das, dad = zt.cuda(), gt.cuda(), dev(a_src), dev(a_dst)
+    out = torch.full((blk.n_dst, F), float("nan"), dtype=dt, device="cuda")
     B.sdt_gat_aggregate_fwd(gb, dzz, das, dad, 0.2, out, ws)
-    assert_close(f64(out), ref, TOL, "attention output")
-    dz = torch.full((blk.n_src, F), float("nan"), dtype=torch.float32, device="cuda")
+    assert_close(f64(out), ref, tol_stored, "attention output")
+    dz = torch.full((blk.n_src, F), float("nan"), dtype=dt, device="cuda")
     da_s = torch.zeros(F, dtype=torch.float32, device="cuda")
     da_d = torch.zeros(F, dtype=torch.float32, device="cuda")
-    B.sdt_gat_aggregate_bwd(gb, dzz, das, dad, 0.2, dev(g), dz, da_s, da_d, ws)
-    assert_close(f64(dz), rdz, TOL, "dz")
+    B.sdt_gat_aggregate_bwd(gb, dzz, das, dad, 0.2, dg, dz, da_s, da_d, ws)
+    assert_close(f64(dz), rdz, tol_stored, "dz")
     assert_close(f64(da_s), rda_s, TOL, "da_src")
     assert_close(f64(da_d), rda_d, TOL, "da_dst")
     # deterministic: a second run gives the same bits
     dz2 = torch.empty_like(dz)
     B.sdt_gat_aggregate_fwd(gb, dzz, das, dad, 0.2, out, ws)
-    B.sdt_gat_aggregate_bwd(gb, dzz, das, dad, 0.2, dev(g), dz2, da_s, da_d, ws)
+    B.sdt_gat_aggregate_bwd(gb, dzz, das, dad, 0.2, dg, dz2, da_s, da_d, ws)
     assert torch.equal(dz, dz2)
     with pytest.raises(B.SdtError) as e:
         B.sdt_gat_aggregate_fwd(gb, dzz, das, dad, 0.2, out, ws[:64])

@@ -5,6 +5,7 @@ Then the launch configuration bench.py times -- one sdt_train_loop call over the
 mini-batches, sampling on two auxiliary streams -- must reproduce every loss and the final
 weights bit for bit (Sec. III-D: a worker trains many mini-batches between two
 synchronisations; that loop is the unit that matters)."""
+import functools
 import time
 
 import numpy as np
@@ -20,16 +21,29 @@ from test_gpu_parity import _loop_against_steps, _run_and_check, _say
 pytestmark = pytest.mark.gpu
 
 
+@functools.lru_cache(maxsize=1)
+def _instance(name):
+    """The workload's graph, features and weights; the tests of one workload follow each other and share it."""
+    t = time.time()
+    inst = gen.make_instance(gen.WORKLOADS[name])
+    _say(f"{name}: generated in {time.time() - t:.1f}s, nnz={inst.indptr[-1]}")
+    return inst
+
+
 @pytest.mark.timeout(600)
 def test_products_full_size():
     wl = gen.WORKLOADS["products"]
-    t = time.time()
-    inst = gen.make_instance(wl)
-    _say(f"products: generated in {time.time() - t:.1f}s, nnz={inst.indptr[-1]}")
+    inst = _instance("products")
     # 100 steps as the workload prescribes: indices every step, floats at 0, 1 and the last;
     # then the same 100 steps through one sdt_train_loop call, as bench.py times them
     seq, losses = _run_and_check(inst, wl, steps=wl.steps, check_float_steps=(0, 1, wl.steps - 1))
     _loop_against_steps(inst, wl, seq, losses)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("kind", ["gcn", "gat"])
+def test_products_full_size_other_model_kinds(kind):
+    _other_model_kinds("products", kind, 2)
 
 
 @pytest.mark.timeout(600)
@@ -60,12 +74,16 @@ def test_dense_full_size():
 @pytest.mark.timeout(1500)
 def test_sparse_bf16_full_size():
     wl = gen.WORKLOADS["sparse_bf16"]
-    t = time.time()
-    inst = gen.make_instance(wl)
-    _say(f"sparse_bf16: generated in {time.time() - t:.1f}s, nnz={inst.indptr[-1]}")
+    inst = _instance("sparse_bf16")
     assert wl.steps == 200
     seq, losses = _run_and_check(inst, wl, steps=wl.steps, check_float_steps=(0, 1, wl.steps - 1))
     _loop_against_steps(inst, wl, seq, losses)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("kind", ["gcn", "gat"])
+def test_sparse_bf16_full_size_other_model_kinds(kind):
+    _other_model_kinds("sparse_bf16", kind, 1)
 
 
 @pytest.mark.timeout(900)
@@ -111,15 +129,12 @@ def test_fullgraph_layer_sampled_rows():
     _say(f"fullgraph: one-launch layer bit-equal on all {N} rows; {int((deg > 2048).sum())} rows longer than 2048 edges")
 
 
-@pytest.mark.timeout(900)
-@pytest.mark.parametrize("name,kind,steps", [("products", "gcn", 2), ("products", "gat", 2), ("sparse_bf16", "gcn", 1),
-                                             ("sparse_bf16", "gat", 1)])
-def test_full_size_other_model_kinds(name, kind, steps):
+def _other_model_kinds(name, kind, steps):
     """The GCN and GAT kinds of the step at the products-shaped sizes (fp32) and at the sizes of the bf16 workload
     (three layers, bf16 storage; one weight matrix per layer, Glorot-uniform from a seed): loss, activations, every
     gradient and the updated parameters, teacher-forced from the GPU's parameters."""
     wl = gen.WORKLOADS[name]
-    inst = gen.make_instance(wl)
+    inst = _instance(name)
     d, L = wl.dims, len(wl.fanouts)
     bf16 = wl.bf16
     dt = torch.bfloat16 if bf16 else torch.float32

@@ -240,6 +240,53 @@ __device__ __forceinline__ void zero(floatx16 (&acc)[TL::TM][TL::TN]) {
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 }
 
+// The output tile of a workgroup, Y[row0.., col0..] = act(acc + bias) for rows < n and columns < ncols.  vec: the tile
+// is staged through LDS (the operand buffers are dead by then; `lds` must hold tile_bytes<TY, TL>()) and leaves in
+// 16-byte vectors, every row contiguous -- four stores per thread instead of one per accumulator element, which is
+// 2-4 us of a short launch; it needs ldy a multiple of the vector and Y 16-byte aligned.  Otherwise element by element.
+template <typename TY, typename TL>
+constexpr int tile_bytes() { return TL::BM * (TL::BN + 16 / (int)sizeof(TY)) * (int)sizeof(TY); }
+
+template <typename TY, typename TL>
+__device__ __forceinline__ void store_tile(const floatx16 (&acc)[TL::TM][TL::TN], void* lds, TY* __restrict__ Y, int64_t ldy,
+                                           int row0, int col0, int n, int ncols, const float* __restrict__ bias, int relu,
+                                           bool vec) {
+    if (!vec) {
+        for_each_acc<TL>(acc, [&](int r, int c, float v) {
+            const int row = row0 + r, col = col0 + c;
+            if (row < n && col < ncols) {
+                float z = v + (bias ? bias[col] : 0.f);
+                if (relu && !(z > 0.f)) z = 0.f;
+                Y[(int64_t)row * ldy + col] = from_f32<TY>(z);
+            }
+        });
+        return;
+    }
+    constexpr int VE = 16 / (int)sizeof(TY), LDC = TL::BN + VE, VPR = TL::BN / VE;
+    TY* Cs = static_cast<TY*>(lds);
+    __syncthreads();   // every wave is done with the operand tiles
+    for_each_acc<TL>(acc, [&](int r, int c, float v) {
+        const int col = col0 + c;
+        float z = v + ((bias && col < ncols) ? bias[col] : 0.f);
+        if (relu && !(z > 0.f)) z = 0.f;
+        Cs[r * LDC + c] = from_f32<TY>(z);
+    });
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < TL::BM * VPR; idx += TL::NT) {
+        const int r = idx / VPR, c = (idx % VPR) * VE;
+        const int row = row0 + r, col = col0 + c;
+        if (row >= n) continue;
+        if (col + VE <= ncols)
+            *reinterpret_cast<uint4*>(Y + (int64_t)row * ldy + col) = *reinterpret_cast<const uint4*>(Cs + r * LDC + c);
+        else
+            for (int e = 0; e < VE && col + e < ncols; ++e) Y[(int64_t)row * ldy + col + e] = Cs[r * LDC + c + e];
+    }
+}
+template <typename TY>
+inline bool vec_rows_ok(const void* Y, int64_t ldy) {
+    return ldy % (16 / (int64_t)sizeof(TY)) == 0 && reinterpret_cast<uintptr_t>(Y) % 16 == 0;
+}
+
 // ---- forward -------------------------------------------------------------------------------------
 // Wt: bf16 [out][2 in], column o of W as a row (self half first).
 template <typename TY, typename TL>
@@ -247,14 +294,16 @@ __global__ __launch_bounds__(TL::NT) void k_fwd_bf16(const uint16_t* __restrict_
                                                      const uint16_t* __restrict__ Agg, int64_t lda, int n_cap,
                                                      const int32_t* n_d, int in, int out,
                                                      const uint16_t* __restrict__ Wt, const float* __restrict__ bias,
-                                                     int relu, TY* __restrict__ Y, int64_t ldy) {
+                                                     int relu, TY* __restrict__ Y, int64_t ldy, int vec) {
     constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK;
     const int n = dev_count(n_cap, n_d);
     const int id = xcd_contiguous_id((int)gridDim.x * ((n + BM - 1) / BM));
     if (id < 0) return;
     const int row0 = (id / (int)gridDim.x) * BM, col0 = (id % (int)gridDim.x) * BN;
-    __shared__ __align__(16) uint16_t As[2 * BM * TL::LDK];
-    __shared__ __align__(16) uint16_t Bs[2 * BN * TL::LDK];
+    constexpr int AB = 2 * (BM + BN) * TL::LDK * 2, CB = tile_bytes<TY, TL>();
+    __shared__ __align__(16) unsigned char lds[AB > CB ? AB : CB];
+    uint16_t* As = reinterpret_cast<uint16_t*>(lds);   // [2][BM][LDK]
+    uint16_t* Bs = As + 2 * BM * TL::LDK;              // [2][BN][LDK]
     floatx16 acc[TL::TM][TL::TN];
     zero<TL>(acc);
     using SA = StageB<BM, BK, TL::NT>;
@@ -266,14 +315,7 @@ __global__ __launch_bounds__(TL::NT) void k_fwd_bf16(const uint16_t* __restrict_
         sb.load(Wt + (int64_t)ph * in, 2 * (int64_t)in, col0, out, k0, in);
     };
     mainloop<TL, SA, SB>(2 * nk, As, Bs, fetch, [](const uint16_t*) {}, acc);
-    for_each_acc<TL>(acc, [&](int r, int c, float v) {
-        const int row = row0 + r, col = col0 + c;
-        if (row < n && col < out) {
-            float z = v + (bias ? bias[col] : 0.f);
-            if (relu && !(z > 0.f)) z = 0.f;
-            Y[(int64_t)row * ldy + col] = from_f32<TY>(z);
-        }
-    });
+    store_tile<TY, TL>(acc, lds, Y, ldy, row0, col0, n, out, bias, relu, vec != 0);
 }
 
 // ---- input gradient --------------------------------------------------------------------------------
@@ -283,7 +325,7 @@ template <typename TD, typename TL>
 __device__ __forceinline__ void bwd_input_body(const TD* __restrict__ dY, int64_t lddy, int n_cap, const int32_t* n_d, int in,
                                                int out, const uint16_t* __restrict__ Wb, int64_t ldb,
                                                bf16_t* __restrict__ dSelf, bf16_t* __restrict__ dAgg, int64_t ldi,
-                                               int lin_id, int gx, uint16_t* lds) {
+                                               int vec, int lin_id, int gx, uint16_t* lds) {
     constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK;
     const int n = dev_count(n_cap, n_d);
     const int id = xcd_contiguous_from_linear(lin_id, gx * 2 * ((n + BM - 1) / BM));
@@ -303,11 +345,8 @@ __device__ __forceinline__ void bwd_input_body(const TD* __restrict__ dY, int64_
         sb.load(Wh, ldb, col0, in, it * BK, kmax_b);
     };
     mainloop<TL, SA, SB>((out + BK - 1) / BK, As, Bs, fetch, [](const uint16_t*) {}, acc);
-    bf16_t* dst = half ? dAgg : dSelf;
-    for_each_acc<TL>(acc, [&](int r, int c, float v) {
-        const int row = row0 + r, col = col0 + c;
-        if (row < n && col < in) dst[(int64_t)row * ldi + col] = from_f32<bf16_t>(v);
-    });
+    static_assert(tile_bytes<bf16_t, TL>() <= 2 * (TL::BM + TL::BN) * TL::LDK * 2, "the staged output tile fits the operand buffers");
+    store_tile<bf16_t, TL>(acc, lds, half ? dAgg : dSelf, ldi, row0, col0, n, in, nullptr, 0, vec != 0);
 }
 template <typename TL>
 constexpr int input_lds_elems() { return 2 * (TL::BM + TL::BN) * TL::LDK; }
@@ -317,9 +356,9 @@ __global__ __launch_bounds__(TL::NT) void k_bwd_input_bf16(const TD* __restrict_
                                                            const int32_t* n_d, int in, int out,
                                                            const uint16_t* __restrict__ Wb, int64_t ldb,
                                                            bf16_t* __restrict__ dSelf, bf16_t* __restrict__ dAgg,
-                                                           int64_t ldi) {
+                                                           int64_t ldi, int vec) {
     __shared__ __align__(16) uint16_t lds[input_lds_elems<TL>()];
-    bwd_input_body<TD, TL>(dY, lddy, n_cap, n_d, in, out, Wb, ldb, dSelf, dAgg, ldi,
+    bwd_input_body<TD, TL>(dY, lddy, n_cap, n_d, in, out, Wb, ldb, dSelf, dAgg, ldi, vec,
                            (int)(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z)), (int)gridDim.x, lds);
 }
 
@@ -469,7 +508,7 @@ __global__ __launch_bounds__(TW::NT) void k_bwd_both_bf16(const uint16_t* __rest
                                                           float* __restrict__ P, float* __restrict__ Q, int nw, int wgx,
                                                           int wgy, const uint16_t* __restrict__ Wb, int64_t ldb,
                                                           bf16_t* __restrict__ dSelf, bf16_t* __restrict__ dAgg, int64_t ldi,
-                                                          int igx) {
+                                                          int vec, int igx) {
     static_assert(TW::NT == TI::NT, "one workgroup size for both parts");
     constexpr int LDS = weight_lds_elems<TW>() > input_lds_elems<TI>() ? weight_lds_elems<TW>() : input_lds_elems<TI>();
     __shared__ __align__(16) uint16_t lds[LDS];
@@ -477,7 +516,7 @@ __global__ __launch_bounds__(TW::NT) void k_bwd_both_bf16(const uint16_t* __rest
     if (id < nw)
         bwd_weight_body<TD, TW>(Hself, ldh, Agg, lda, dY, lddy, n_cap, n_d, in, out, splits, P, Q, id, wgx, wgy, lds);
     else
-        bwd_input_body<TD, TI>(dY, lddy, n_cap, n_d, in, out, Wb, ldb, dSelf, dAgg, ldi, id - nw, igx, lds);
+        bwd_input_body<TD, TI>(dY, lddy, n_cap, n_d, in, out, Wb, ldb, dSelf, dAgg, ldi, vec, id - nw, igx, lds);
 }
 
 // ---- bf16 images of the weights ----------------------------------------------------------------
@@ -554,9 +593,11 @@ int32_t convert_weights_bf16(const sdt_model* model, void* base, hipStream_t st)
 
 namespace {
 // Many rows: 32-deep steps keep more workgroups resident (the kernels are bound by streaming the
-// activations).  Few rows: every workgroup is one short dependent chain, and 64-deep steps halve it.
+// activations).  Few rows: every workgroup is one short dependent chain; 64-deep steps halve it, and 64 output
+// columns per workgroup instead of 128 make twice as many, each with half the loads and matrix instructions per
+// step (6 000 x 512 -> 256: 15.1 us with 64 x 128 tiles, 10.4 with 64 x 64, 9.3 with the output tile leaving in vectors).
 using TFbig = TileB<64, 128, 32, 2, 2>;
-using TFsmall = TileB<64, 128, 64, 2, 2>;
+using TFsmall = TileB<64, 64, 64, 2, 2>;
 constexpr int32_t SMALL_ROWS = 16384;
 }  // namespace
 
@@ -572,10 +613,10 @@ int32_t linear_fwd_bf16(const void* Hself, int64_t ldh, const void* A, int64_t l
         dim3 grid(ceil_div(out, TF::BN), ceil_div(n_cap, TF::BM));
         if (y_dtype == SDT_BF16)
             hipLaunchKernelGGL((k_fwd_bf16<bf16_t, TF>), grid, dim3(TF::NT), 0, st, h, ldh, a, lda, n_cap, n_d, in, out, w,
-                               bias, relu, static_cast<bf16_t*>(Y), ldy);
+                               bias, relu, static_cast<bf16_t*>(Y), ldy, (int)vec_rows_ok<bf16_t>(Y, ldy));
         else
             hipLaunchKernelGGL((k_fwd_bf16<float, TF>), grid, dim3(TF::NT), 0, st, h, ldh, a, lda, n_cap, n_d, in, out, w,
-                               bias, relu, static_cast<float*>(Y), ldy);
+                               bias, relu, static_cast<float*>(Y), ldy, (int)vec_rows_ok<float>(Y, ldy));
     };
     if (n_cap >= SMALL_ROWS) go(TFbig{});
     else go(TFsmall{});
@@ -626,6 +667,7 @@ int32_t linear_bwd_both_bf16(const void* Hself, int64_t ldh, const void* A, int6
     const int64_t ldb = bf16_ldb(out);
     const int wgx = ceil_div(out, TW::BN), wgy = ceil_div(in, TW::BM);
     const int nw = (wgx * wgy * 2 * splits + 7) / 8 * 8;
+    const int vec = vec_rows_ok<bf16_t>(dSelf, ldi) && vec_rows_ok<bf16_t>(dAgg, ldi);
     auto go = [&](auto tile) {
         using TI = decltype(tile);
         const int igx = ceil_div(in, TI::BN);
@@ -633,11 +675,11 @@ int32_t linear_bwd_both_bf16(const void* Hself, int64_t ldh, const void* A, int6
         if (dy_dtype == SDT_BF16)
             hipLaunchKernelGGL((k_bwd_both_bf16<uint16_t, TW, TI>), dim3(nw + ni), dim3(TW::NT), 0, st, h, ldh, a, lda,
                                static_cast<const uint16_t*>(dY), lddy, n_cap, n_d, in, out, splits, P, Q, nw, wgx, wgy, w, ldb,
-                               static_cast<bf16_t*>(dSelf), static_cast<bf16_t*>(dAgg), ldi, igx);
+                               static_cast<bf16_t*>(dSelf), static_cast<bf16_t*>(dAgg), ldi, vec, igx);
         else
             hipLaunchKernelGGL((k_bwd_both_bf16<float, TW, TI>), dim3(nw + ni), dim3(TW::NT), 0, st, h, ldh, a, lda,
                                static_cast<const float*>(dY), lddy, n_cap, n_d, in, out, splits, P, Q, nw, wgx, wgy, w, ldb,
-                               static_cast<bf16_t*>(dSelf), static_cast<bf16_t*>(dAgg), ldi, igx);
+                               static_cast<bf16_t*>(dSelf), static_cast<bf16_t*>(dAgg), ldi, vec, igx);
     };
     if (n_cap >= SMALL_ROWS) go(TFbig{});
     else go(TFsmall{});
@@ -651,15 +693,16 @@ int32_t linear_bwd_input_bf16(const void* dY, int64_t lddy, int32_t dy_dtype, in
     if (n_cap == 0) return SDT_OK;
     const uint16_t* w = static_cast<const uint16_t*>(Wb);
     const int64_t ldb = bf16_ldb(out);
+    const int vec = vec_rows_ok<bf16_t>(dSelf, ldi) && vec_rows_ok<bf16_t>(dAgg, ldi);
     auto go = [&](auto tile) {
         using TI = decltype(tile);
         dim3 grid(ceil_div(in, TI::BN), ceil_div(n_cap, TI::BM), 2);
         if (dy_dtype == SDT_BF16)
             hipLaunchKernelGGL((k_bwd_input_bf16<uint16_t, TI>), grid, dim3(TI::NT), 0, st, static_cast<const uint16_t*>(dY),
-                               lddy, n_cap, n_d, in, out, w, ldb, static_cast<bf16_t*>(dSelf), static_cast<bf16_t*>(dAgg), ldi);
+                               lddy, n_cap, n_d, in, out, w, ldb, static_cast<bf16_t*>(dSelf), static_cast<bf16_t*>(dAgg), ldi, vec);
         else
             hipLaunchKernelGGL((k_bwd_input_bf16<float, TI>), grid, dim3(TI::NT), 0, st, static_cast<const float*>(dY), lddy,
-                               n_cap, n_d, in, out, w, ldb, static_cast<bf16_t*>(dSelf), static_cast<bf16_t*>(dAgg), ldi);
+                               n_cap, n_d, in, out, w, ldb, static_cast<bf16_t*>(dSelf), static_cast<bf16_t*>(dAgg), ldi, vec);
     };
     if (n_cap >= SMALL_ROWS) go(TFbig{});
     else go(TFsmall{});

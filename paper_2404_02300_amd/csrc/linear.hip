@@ -246,6 +246,54 @@ __device__ __forceinline__ void for_each_acc(const floatx16 (&acc)[TL::TM][TL::T
         }
 }
 
+// The output tile of a workgroup, Y[row0.., col0..] = act(acc + bias) for rows < n and columns < ncols.  vec (and a
+// tile that fits the kernel's LDS: the small tiles): the tile is staged through LDS, where the operand buffers are dead
+// by then, and leaves in 16-byte vectors, every row contiguous -- four stores per thread instead of sixteen, 1-2 us of a
+// short launch.  Needs ldy a multiple of the vector, Y 16-byte aligned, LDS_FLOATS floats at `lds`.  Otherwise element
+// by element.  The values are the same either way.
+template <typename TY, typename TL, int LDS_FLOATS>
+__device__ __forceinline__ void store_tile(const floatx16 (&acc)[TL::TM][TL::TN], float* lds, TY* __restrict__ Y, int64_t ldy,
+                                           int row0, int col0, int n, int ncols, const float* __restrict__ bias, int relu,
+                                           bool vec) {
+    constexpr int VE = 16 / (int)sizeof(TY), LDC = TL::BN + VE, VPR = TL::BN / VE;
+    constexpr bool FITS = TL::BM * LDC * (int)sizeof(TY) <= LDS_FLOATS * 4;
+    if (!FITS || !vec) {
+        for_each_acc<TL>(acc, [&](int r, int c, float v) {
+            const int row = row0 + r, col = col0 + c;
+            if (row < n && col < ncols) {
+                float z = v + (bias ? bias[col] : 0.f);
+                if (relu && !(z > 0.f)) z = 0.f;
+                Y[(int64_t)row * ldy + col] = from_f32<TY>(z);
+            }
+        });
+        return;
+    }
+    if constexpr (FITS) {
+        TY* Cs = reinterpret_cast<TY*>(lds);
+        __syncthreads();   // every wave is done with the operand tiles
+        for_each_acc<TL>(acc, [&](int r, int c, float v) {
+            const int col = col0 + c;
+            float z = v + ((bias && col < ncols) ? bias[col] : 0.f);
+            if (relu && !(z > 0.f)) z = 0.f;
+            Cs[r * LDC + c] = from_f32<TY>(z);
+        });
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < TL::BM * VPR; idx += TL::NT) {
+            const int r = idx / VPR, c = (idx % VPR) * VE;
+            const int row = row0 + r, col = col0 + c;
+            if (row >= n) continue;
+            if (col + VE <= ncols)
+                *reinterpret_cast<uint4*>(Y + (int64_t)row * ldy + col) = *reinterpret_cast<const uint4*>(Cs + r * LDC + c);
+            else
+                for (int e = 0; e < VE && col + e < ncols; ++e) Y[(int64_t)row * ldy + col + e] = Cs[r * LDC + c + e];
+        }
+    }
+}
+template <typename TY>
+inline bool vec_rows_ok(const void* Y, int64_t ldy) {
+    return ldy % (16 / (int64_t)sizeof(TY)) == 0 && reinterpret_cast<uintptr_t>(Y) % 16 == 0;
+}
+
 // ---------------------------------------------------------------------------------
 // forward: Y[n,out] = act(Hself[n,in] Wself[in,out] + A[n,in] Wneigh[in,out] + b)
 // ---------------------------------------------------------------------------------
@@ -254,14 +302,16 @@ __global__ __launch_bounds__(TL::NT) void k_linear_fwd(const TH* __restrict__ Hs
                                                        const TH* __restrict__ Agg, int64_t lda, int n_cap,
                                                        const int32_t* n_d, int in, int in_a, int out,
                                                        const float* __restrict__ W, const float* __restrict__ bias,
-                                                       int relu, TY* __restrict__ Y, int64_t ldy) {
+                                                       int relu, TY* __restrict__ Y, int64_t ldy, int vec) {
     constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK;
     const int n = dev_count(n_cap, n_d);
     const int id = xcd_contiguous_id((int)gridDim.x * ((n + BM - 1) / BM));
     if (id < 0) return;
     const int row0 = (id / (int)gridDim.x) * BM, col0 = (id % (int)gridDim.x) * BN;
-    __shared__ __align__(16) float As[2 * BM * TL::LD_KC];
-    __shared__ __align__(16) float Bs[2 * BK * TL::LDB_OC];
+    constexpr int A_FLOATS = 2 * BM * TL::LD_KC, LDS_FLOATS = A_FLOATS + 2 * BK * TL::LDB_OC;
+    __shared__ __align__(16) float lds[LDS_FLOATS];
+    float* As = lds;
+    float* Bs = lds + A_FLOATS;
     floatx16 acc[TL::TM][TL::TN];
 #pragma unroll
     for (int a = 0; a < TL::TM; ++a)
@@ -276,14 +326,7 @@ __global__ __launch_bounds__(TL::NT) void k_linear_fwd(const TH* __restrict__ Hs
         sb.load(W + (int64_t)ph * in * out, out, k0, in, col0, out);
     };
     gemm_mainloop<TL, true, false, SA, SB>(2 * nk, As, Bs, fetch, [](const float*) {}, acc);
-    for_each_acc<TL>(acc, [&](int r, int c, float v) {
-        const int row = row0 + r, col = col0 + c;
-        if (row < n && col < out) {
-            float z = v + (bias ? bias[col] : 0.f);
-            if (relu && !(z > 0.f)) z = 0.f;
-            Y[(int64_t)row * ldy + col] = from_f32<TY>(z);
-        }
-    });
+    store_tile<TY, TL, LDS_FLOATS>(acc, lds, Y, ldy, row0, col0, n, out, bias, relu, vec != 0);
 }
 
 // ---------------------------------------------------------------------------------
@@ -455,7 +498,7 @@ template <typename TD, typename TH, typename TL, int VD, int VW, bool ROUND>
 __global__ __launch_bounds__(TL::NT) void k_linear_bwd_input(const TD* __restrict__ dY, int64_t lddy, int n_cap,
                                                              const int32_t* n_d, int in, int out,
                                                              const float* __restrict__ W, TH* __restrict__ dSelf,
-                                                             TH* __restrict__ dAgg, int64_t ldi) {
+                                                             TH* __restrict__ dAgg, int64_t ldi, int vec) {
     constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK;
     const int n = dev_count(n_cap, n_d);
     // x fastest, then the half, then the row tile: the workgroups that read one panel of dY are neighbours
@@ -463,8 +506,10 @@ __global__ __launch_bounds__(TL::NT) void k_linear_bwd_input(const TD* __restric
     if (id < 0) return;
     const int col0 = (id % (int)gridDim.x) * BN, half = (id / (int)gridDim.x) % 2;
     const int row0 = (id / (int)gridDim.x / 2) * BM;
-    __shared__ __align__(16) float As[2 * BM * TL::LD_KC];
-    __shared__ __align__(16) float Bs[2 * BN * TL::LD_KC];
+    constexpr int A_FLOATS = 2 * BM * TL::LD_KC, LDS_FLOATS = A_FLOATS + 2 * BN * TL::LD_KC;
+    __shared__ __align__(16) float lds[LDS_FLOATS];
+    float* As = lds;
+    float* Bs = lds + A_FLOATS;
     floatx16 acc[TL::TM][TL::TN];
 #pragma unroll
     for (int a = 0; a < TL::TM; ++a)
@@ -478,11 +523,7 @@ __global__ __launch_bounds__(TL::NT) void k_linear_bwd_input(const TD* __restric
         sb.load(Wh, out, col0, in, it * BK, out);
     };
     gemm_mainloop<TL, true, true, SA, SB>((out + BK - 1) / BK, As, Bs, fetch, [](const float*) {}, acc);
-    TH* dst = half ? dAgg : dSelf;
-    for_each_acc<TL>(acc, [&](int r, int c, float v) {
-        const int row = row0 + r, col = col0 + c;
-        if (row < n && col < in) dst[(int64_t)row * ldi + col] = from_f32<TH>(v);
-    });
+    store_tile<TH, TL, LDS_FLOATS>(acc, lds, half ? dAgg : dSelf, ldi, row0, col0, n, in, nullptr, 0, vec != 0);
 }
 
 // ---------------------------------------------------------------------------------
@@ -494,7 +535,7 @@ __global__ __launch_bounds__(TL::NT) void k_linear_bwd_weight(const TH* __restri
                                                               const TH* __restrict__ Agg, int64_t lda,
                                                               const TD* __restrict__ dY, int64_t lddy, int n_cap,
                                                               const int32_t* n_d, int in, int in_a, int out, int splits,
-                                                              float* __restrict__ P, float* __restrict__ Q) {
+                                                              float* __restrict__ P, float* __restrict__ Q, int vec) {
     constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK;
     const int n = dev_count(n_cap, n_d);
     // grid (out tiles, in tiles, 2 * splits); x fastest keeps the readers of one X panel on one L2
@@ -508,8 +549,10 @@ __global__ __launch_bounds__(TL::NT) void k_linear_bwd_weight(const TH* __restri
     const int row0 = by * BM /* feature m */, col0 = bx * BN /* output o */;
     const int chunk = ((n + splits - 1) / splits + BK - 1) / BK * BK;
     const int r_begin = split * chunk, r_end = min(n, r_begin + chunk);
-    __shared__ __align__(16) float As[2 * BK * TL::LDA_OC];
-    __shared__ __align__(16) float Bs[2 * BK * TL::LDB_OC];
+    constexpr int A_FLOATS = 2 * BK * TL::LDA_OC, LDS_FLOATS = A_FLOATS + 2 * BK * TL::LDB_OC;
+    __shared__ __align__(16) float lds[LDS_FLOATS];
+    float* As = lds;
+    float* Bs = lds + A_FLOATS;
     floatx16 acc[TL::TM][TL::TN];
 #pragma unroll
     for (int a = 0; a < TL::TM; ++a)
@@ -534,10 +577,7 @@ __global__ __launch_bounds__(TL::NT) void k_linear_bwd_weight(const TH* __restri
     if (do_bias && (int)threadIdx.x < BN && col0 + (int)threadIdx.x < out)
         Q[(int64_t)split * out + col0 + threadIdx.x] = bsum;
     float* dst = P + ((int64_t)split * 2 * in + (int64_t)half * in) * out;
-    for_each_acc<TL>(acc, [&](int r, int c, float v) {
-        const int row = row0 + r, col = col0 + c;
-        if (row < in && col < out) dst[(int64_t)row * out + col] = v;
-    });
+    store_tile<float, TL, LDS_FLOATS>(acc, lds, dst, out, row0, col0, in, out, nullptr, 0, vec != 0);
 }
 
 // dW[idx] = sum_s P[s][idx]; db[o] = sum_s Q[s][o]; optionally the SGD step W -= lr dW,
@@ -710,7 +750,7 @@ void launch_fwd(const void* Hself, int64_t ldh, const void* A, int64_t lda, int 
             constexpr int VB = V;
             hipLaunchKernelGGL((k_linear_fwd<TH, TY, TL, VA, VB, ROUNDW>), grid, dim3(TL::NT), 0, st,
                                static_cast<const TH*>(Hself), ldh, static_cast<const TH*>(A), lda, n_cap, n_d, in, in_a, out,
-                               W, b, relu, static_cast<TY*>(Y), ldy);
+                               W, b, relu, static_cast<TY*>(Y), ldy, (int)vec_rows_ok<TY>(Y, ldy));
         })
     })
 }
@@ -750,7 +790,7 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Hself, int64_t ldh, co
                 constexpr int VD = V;
                 hipLaunchKernelGGL((k_linear_bwd_weight<TD, TH, TL, VH, VD, ROUND>), grid, dim3(TL::NT), 0, st,
                                    static_cast<const TH*>(Hself), ldh, static_cast<const TH*>(A), lda, dYt, lddy, n_cap,
-                                   n_d, in, in_a, out, splits, P, Q);
+                                   n_d, in, in_a, out, splits, P, Q, (int)vec_rows_ok<float>(P, out));
             })
         })
     }
@@ -768,7 +808,8 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Hself, int64_t ldh, co
             SDT_VEC_SWITCH(vw, 4, {
                 constexpr int VW = V;
                 hipLaunchKernelGGL((k_linear_bwd_input<TD, TH, TL, VD, VW, ROUND>), grid, dim3(TL::NT), 0, st, dYt, lddy,
-                                   n_cap, n_d, in, out, W, static_cast<TH*>(dSelf), static_cast<TH*>(dAgg), ldi);
+                                   n_cap, n_d, in, out, W, static_cast<TH*>(dSelf), static_cast<TH*>(dAgg), ldi,
+                                   (int)(vec_rows_ok<TH>(dSelf, ldi) && vec_rows_ok<TH>(dAgg, ldi)));
             })
         })
     }

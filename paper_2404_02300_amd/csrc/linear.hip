@@ -21,6 +21,7 @@
 
 #include <algorithm>
 #include <mutex>
+#include <type_traits>
 
 namespace sdt {
 namespace {
@@ -246,18 +247,20 @@ __device__ __forceinline__ void for_each_acc(const floatx16 (&acc)[TL::TM][TL::T
         }
 }
 
-// The output tile of a workgroup, Y[row0.., col0..] = act(acc + bias) for rows < n and columns < ncols.  vec (and a
-// tile that fits the kernel's LDS: the small tiles): the tile is staged through LDS, where the operand buffers are dead
-// by then, and leaves in 16-byte vectors, every row contiguous -- four stores per thread instead of sixteen, 1-2 us of a
-// short launch.  Needs ldy a multiple of the vector, Y 16-byte aligned, LDS_FLOATS floats at `lds`.  Otherwise element
-// by element.  The values are the same either way.
-template <typename TY, typename TL, int LDS_FLOATS>
+// The output tile of a workgroup, Y[row0.., col0..] = act(acc + bias) for rows < n and columns < ncols.  VEC: the tile is
+// staged through LDS, where the operand buffers are dead by then, and leaves in 16-byte vectors, every row contiguous --
+// four stores per thread instead of sixteen, 1-2 us of a short launch.  Needs ldy a multiple of the vector, Y 16-byte
+// aligned, and a tile that fits the LDS_FLOATS floats at `lds`.  Otherwise element by element.  The values are the same
+// either way.  VEC is a template parameter, not an argument: the staged path costs the whole kernel some registers
+// (the weight gradient drops from six to five waves per SIMD), which a long launch pays for and a short one does not
+// notice, so only launches of few workgroup rounds use it.
+template <typename TY, typename TL, int LDS_FLOATS, bool VEC>
 __device__ __forceinline__ void store_tile(const floatx16 (&acc)[TL::TM][TL::TN], float* lds, TY* __restrict__ Y, int64_t ldy,
-                                           int row0, int col0, int n, int ncols, const float* __restrict__ bias, int relu,
-                                           bool vec) {
+                                           int row0, int col0, int n, int ncols, const float* __restrict__ bias, int relu) {
     constexpr int VE = 16 / (int)sizeof(TY), LDC = TL::BN + VE, VPR = TL::BN / VE;
     constexpr bool FITS = TL::BM * LDC * (int)sizeof(TY) <= LDS_FLOATS * 4;
-    if (!FITS || !vec) {
+    static_assert(!VEC || FITS, "the staged output tile must fit the kernel's LDS");
+    if constexpr (!VEC) {
         for_each_acc<TL>(acc, [&](int r, int c, float v) {
             const int row = row0 + r, col = col0 + c;
             if (row < n && col < ncols) {
@@ -266,9 +269,7 @@ __device__ __forceinline__ void store_tile(const floatx16 (&acc)[TL::TM][TL::TN]
                 Y[(int64_t)row * ldy + col] = from_f32<TY>(z);
             }
         });
-        return;
-    }
-    if constexpr (FITS) {
+    } else {
         TY* Cs = reinterpret_cast<TY*>(lds);
         __syncthreads();   // every wave is done with the operand tiles
         for_each_acc<TL>(acc, [&](int r, int c, float v) {
@@ -297,12 +298,12 @@ inline bool vec_rows_ok(const void* Y, int64_t ldy) {
 // ---------------------------------------------------------------------------------
 // forward: Y[n,out] = act(Hself[n,in] Wself[in,out] + A[n,in] Wneigh[in,out] + b)
 // ---------------------------------------------------------------------------------
-template <typename TH, typename TY, typename TL, int VA, int VB, bool ROUNDW>
+template <typename TH, typename TY, typename TL, int VA, int VB, bool ROUNDW, bool VEC = false>
 __global__ __launch_bounds__(TL::NT) void k_linear_fwd(const TH* __restrict__ Hself, int64_t ldh,
                                                        const TH* __restrict__ Agg, int64_t lda, int n_cap,
                                                        const int32_t* n_d, int in, int in_a, int out,
                                                        const float* __restrict__ W, const float* __restrict__ bias,
-                                                       int relu, TY* __restrict__ Y, int64_t ldy, int vec) {
+                                                       int relu, TY* __restrict__ Y, int64_t ldy) {
     constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK;
     const int n = dev_count(n_cap, n_d);
     const int id = xcd_contiguous_id((int)gridDim.x * ((n + BM - 1) / BM));
@@ -326,7 +327,7 @@ __global__ __launch_bounds__(TL::NT) void k_linear_fwd(const TH* __restrict__ Hs
         sb.load(W + (int64_t)ph * in * out, out, k0, in, col0, out);
     };
     gemm_mainloop<TL, true, false, SA, SB>(2 * nk, As, Bs, fetch, [](const float*) {}, acc);
-    store_tile<TY, TL, LDS_FLOATS>(acc, lds, Y, ldy, row0, col0, n, out, bias, relu, vec != 0);
+    store_tile<TY, TL, LDS_FLOATS, VEC>(acc, lds, Y, ldy, row0, col0, n, out, bias, relu);
 }
 
 // ---------------------------------------------------------------------------------
@@ -494,11 +495,11 @@ __global__ __launch_bounds__(TileF::NT, 4) void k_sage_layer_fused(const int64_t
 // ---------------------------------------------------------------------------------
 // input gradient: dIn_h[n,in] = dZ[n,out] W_h[in,out]^T, h = blockIdx.z (0 self, 1 neigh)
 // ---------------------------------------------------------------------------------
-template <typename TD, typename TH, typename TL, int VD, int VW, bool ROUND>
+template <typename TD, typename TH, typename TL, int VD, int VW, bool ROUND, bool VEC = false>
 __global__ __launch_bounds__(TL::NT) void k_linear_bwd_input(const TD* __restrict__ dY, int64_t lddy, int n_cap,
                                                              const int32_t* n_d, int in, int out,
                                                              const float* __restrict__ W, TH* __restrict__ dSelf,
-                                                             TH* __restrict__ dAgg, int64_t ldi, int vec) {
+                                                             TH* __restrict__ dAgg, int64_t ldi) {
     constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK;
     const int n = dev_count(n_cap, n_d);
     // x fastest, then the half, then the row tile: the workgroups that read one panel of dY are neighbours
@@ -523,19 +524,19 @@ __global__ __launch_bounds__(TL::NT) void k_linear_bwd_input(const TD* __restric
         sb.load(Wh, out, col0, in, it * BK, out);
     };
     gemm_mainloop<TL, true, true, SA, SB>((out + BK - 1) / BK, As, Bs, fetch, [](const float*) {}, acc);
-    store_tile<TH, TL, LDS_FLOATS>(acc, lds, half ? dAgg : dSelf, ldi, row0, col0, n, in, nullptr, 0, vec != 0);
+    store_tile<TH, TL, LDS_FLOATS, VEC>(acc, lds, half ? dAgg : dSelf, ldi, row0, col0, n, in, nullptr, 0);
 }
 
 // ---------------------------------------------------------------------------------
 // weight gradient partials: P[s][h*in + m][o] = sum over the rows r of split s of
 //   X_h[r, m] dZ[r, o],  X_0 = Hself, X_1 = A;  h = blockIdx.z % 2, s = blockIdx.z / 2
 // ---------------------------------------------------------------------------------
-template <typename TD, typename TH, typename TL, int VH, int VD, bool ROUND>
+template <typename TD, typename TH, typename TL, int VH, int VD, bool ROUND, bool VEC = false>
 __global__ __launch_bounds__(TL::NT) void k_linear_bwd_weight(const TH* __restrict__ Hself, int64_t ldh,
                                                               const TH* __restrict__ Agg, int64_t lda,
                                                               const TD* __restrict__ dY, int64_t lddy, int n_cap,
                                                               const int32_t* n_d, int in, int in_a, int out, int splits,
-                                                              float* __restrict__ P, float* __restrict__ Q, int vec) {
+                                                              float* __restrict__ P, float* __restrict__ Q) {
     constexpr int BM = TL::BM, BN = TL::BN, BK = TL::BK;
     const int n = dev_count(n_cap, n_d);
     // grid (out tiles, in tiles, 2 * splits); x fastest keeps the readers of one X panel on one L2
@@ -577,7 +578,7 @@ __global__ __launch_bounds__(TL::NT) void k_linear_bwd_weight(const TH* __restri
     if (do_bias && (int)threadIdx.x < BN && col0 + (int)threadIdx.x < out)
         Q[(int64_t)split * out + col0 + threadIdx.x] = bsum;
     float* dst = P + ((int64_t)split * 2 * in + (int64_t)half * in) * out;
-    store_tile<float, TL, LDS_FLOATS>(acc, lds, dst, out, row0, col0, in, out, nullptr, 0, vec != 0);
+    store_tile<float, TL, LDS_FLOATS, VEC>(acc, lds, dst, out, row0, col0, in, out, nullptr, 0);
 }
 
 // dW[idx] = sum_s P[s][idx]; db[o] = sum_s Q[s][o]; optionally the SGD step W -= lr dW,
@@ -731,6 +732,8 @@ using namespace sdt;
 namespace {
 
 // Tile shapes, picked by measurement on MI355X (fp32 MFMA, out = 256):
+// launches short enough for the staged output tile to pay (store_tile): few rounds of workgroups, or short row ranges
+constexpr int32_t SHORT_LAUNCH_ROWS = 32768, SHORT_SPLIT_ROWS = 2048;
 using TileS = Tile<64, 64, 32, 2, 2>;     // forward / input gradient of mini-batch sized layers
 using TileW = Tile<64, 64, 16, 2, 2>;     // weight gradient (short row ranges: a shallower step wins)
 using TileM = Tile<128, 128, 32, 4, 4>;   // forward from about 512 tiles of 128 x 128
@@ -744,13 +747,22 @@ void launch_fwd(const void* Hself, int64_t ldh, const void* A, int64_t lda, int 
     const int in_a = (in + va - 1) / va * va;
     const int vb = vec_elems(4, out, {(int64_t)out}, {W});
     dim3 grid(ceil_div(out, TL::BN), ceil_div(n_cap, TL::BM));
+    const bool vec = n_cap <= SHORT_LAUNCH_ROWS && vec_rows_ok<TY>(Y, ldy);   // output tiles through LDS (store_tile)
     SDT_VEC_SWITCH(va, (16 / sizeof(TH)), {
         constexpr int VA = V;
         SDT_VEC_SWITCH(vb, 4, {
             constexpr int VB = V;
+            if constexpr (std::is_same<TL, TileS>::value) {
+                if (vec) {
+                    hipLaunchKernelGGL((k_linear_fwd<TH, TY, TL, VA, VB, ROUNDW, true>), grid, dim3(TL::NT), 0, st,
+                                       static_cast<const TH*>(Hself), ldh, static_cast<const TH*>(A), lda, n_cap, n_d, in, in_a,
+                                       out, W, b, relu, static_cast<TY*>(Y), ldy);
+                    return;
+                }
+            }
             hipLaunchKernelGGL((k_linear_fwd<TH, TY, TL, VA, VB, ROUNDW>), grid, dim3(TL::NT), 0, st,
                                static_cast<const TH*>(Hself), ldh, static_cast<const TH*>(A), lda, n_cap, n_d, in, in_a, out,
-                               W, b, relu, static_cast<TY*>(Y), ldy, (int)vec_rows_ok<TY>(Y, ldy));
+                               W, b, relu, static_cast<TY*>(Y), ldy);
         })
     })
 }
@@ -788,9 +800,14 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Hself, int64_t ldh, co
             constexpr int VH = V;
             SDT_VEC_SWITCH(vd, (16 / sizeof(TD)), {
                 constexpr int VD = V;
-                hipLaunchKernelGGL((k_linear_bwd_weight<TD, TH, TL, VH, VD, ROUND>), grid, dim3(TL::NT), 0, st,
-                                   static_cast<const TH*>(Hself), ldh, static_cast<const TH*>(A), lda, dYt, lddy, n_cap,
-                                   n_d, in, in_a, out, splits, P, Q, (int)vec_rows_ok<float>(P, out));
+                if (n_cap / splits <= SHORT_SPLIT_ROWS && vec_rows_ok<float>(P, out))
+                    hipLaunchKernelGGL((k_linear_bwd_weight<TD, TH, TL, VH, VD, ROUND, true>), grid, dim3(TL::NT), 0, st,
+                                       static_cast<const TH*>(Hself), ldh, static_cast<const TH*>(A), lda, dYt, lddy, n_cap,
+                                       n_d, in, in_a, out, splits, P, Q);
+                else
+                    hipLaunchKernelGGL((k_linear_bwd_weight<TD, TH, TL, VH, VD, ROUND>), grid, dim3(TL::NT), 0, st,
+                                       static_cast<const TH*>(Hself), ldh, static_cast<const TH*>(A), lda, dYt, lddy, n_cap,
+                                       n_d, in, in_a, out, splits, P, Q);
             })
         })
     }
@@ -807,9 +824,12 @@ void launch_bwd(const void* dY, int64_t lddy, const void* Hself, int64_t ldh, co
             constexpr int VD = V;
             SDT_VEC_SWITCH(vw, 4, {
                 constexpr int VW = V;
-                hipLaunchKernelGGL((k_linear_bwd_input<TD, TH, TL, VD, VW, ROUND>), grid, dim3(TL::NT), 0, st, dYt, lddy,
-                                   n_cap, n_d, in, out, W, static_cast<TH*>(dSelf), static_cast<TH*>(dAgg), ldi,
-                                   (int)(vec_rows_ok<TH>(dSelf, ldi) && vec_rows_ok<TH>(dAgg, ldi)));
+                if (n_cap <= SHORT_LAUNCH_ROWS && vec_rows_ok<TH>(dSelf, ldi) && vec_rows_ok<TH>(dAgg, ldi))
+                    hipLaunchKernelGGL((k_linear_bwd_input<TD, TH, TL, VD, VW, ROUND, true>), grid, dim3(TL::NT), 0, st, dYt,
+                                       lddy, n_cap, n_d, in, out, W, static_cast<TH*>(dSelf), static_cast<TH*>(dAgg), ldi);
+                else
+                    hipLaunchKernelGGL((k_linear_bwd_input<TD, TH, TL, VD, VW, ROUND>), grid, dim3(TL::NT), 0, st, dYt, lddy,
+                                       n_cap, n_d, in, out, W, static_cast<TH*>(dSelf), static_cast<TH*>(dAgg), ldi);
             })
         })
     }

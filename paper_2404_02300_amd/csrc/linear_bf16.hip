@@ -300,8 +300,9 @@ __global__ __launch_bounds__(TL::NT) void k_fwd_bf16(const uint16_t* __restrict_
     const int id = xcd_contiguous_id((int)gridDim.x * ((n + BM - 1) / BM));
     if (id < 0) return;
     const int row0 = (id / (int)gridDim.x) * BM, col0 = (id % (int)gridDim.x) * BN;
-    constexpr int AB = 2 * (BM + BN) * TL::LDK * 2, CB = tile_bytes<TY, TL>();
-    __shared__ __align__(16) unsigned char lds[AB > CB ? AB : CB];
+    constexpr int AB = 2 * (BM + BN) * TL::LDK * 2;
+    constexpr bool STAGED = tile_bytes<TY, TL>() <= AB;   // (an fp32 tile of 64 x 128 is larger than the operand buffers: not staged)
+    __shared__ __align__(16) unsigned char lds[AB];
     uint16_t* As = reinterpret_cast<uint16_t*>(lds);   // [2][BM][LDK]
     uint16_t* Bs = As + 2 * BM * TL::LDK;              // [2][BN][LDK]
     floatx16 acc[TL::TM][TL::TN];
@@ -315,7 +316,7 @@ __global__ __launch_bounds__(TL::NT) void k_fwd_bf16(const uint16_t* __restrict_
         sb.load(Wt + (int64_t)ph * in, 2 * (int64_t)in, col0, out, k0, in);
     };
     mainloop<TL, SA, SB>(2 * nk, As, Bs, fetch, [](const uint16_t*) {}, acc);
-    store_tile<TY, TL>(acc, lds, Y, ldy, row0, col0, n, out, bias, relu, vec != 0);
+    store_tile<TY, TL>(acc, lds, Y, ldy, row0, col0, n, out, bias, relu, STAGED && vec != 0);
 }
 
 // ---- input gradient --------------------------------------------------------------------------------

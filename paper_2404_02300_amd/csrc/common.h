@@ -206,6 +206,14 @@ struct PendingReduce {
     float* vW = nullptr;
     float* mb = nullptr;
     float* vb = nullptr;
+    // Images of the updated weights that the next step's products read, written with the update (each optional):
+    // bf16 Wt[out][2 in] and Wb[2 in][img_ldb] (linear_bf16.hip), fp32 Wt[out][2 img_kp] (linear_x3.hip).  Padding
+    // elements of the images are not touched: whoever built the images first left them zero.
+    uint16_t* img_wt = nullptr;
+    uint16_t* img_wb = nullptr;
+    int32_t img_ldb = 0;
+    float* img_x3 = nullptr;
+    int32_t img_kp = 0;
 };
 // How the update is applied once a gradient is final.  adam: c1 = 1/(1-beta1^t), c2 = 1/(1-beta2^t).
 struct OptArgs {
@@ -260,9 +268,13 @@ bool x3_fwd_wanted(int32_t n_cap, int32_t in, int32_t out);
 size_t x3_fwd_workspace_bytes(int32_t n_cap, int32_t in, int32_t out);
 bool x3_fwd_ok(const void* Hself, int64_t ldh, const void* A, int64_t lda, int32_t in, bool rows_padded, const void* Y,
                int64_t ldy);
+// Wt_ext (nullable): the transposed weights live there (x3_fwd_image_bytes) instead of in the workspace;
+// wt_current: ... and already hold this step's weights (the previous update wrote them), so no transposition.
+size_t x3_fwd_image_bytes(int32_t in, int32_t out);
+int32_t x3_fwd_image_kp(int32_t in);
 int32_t linear_fwd_x3(const float* Hself, int64_t ldh, const float* A, int64_t lda, int32_t n_cap, const int32_t* n_d,
                       int32_t in, int32_t out, const float* W, const float* b, int32_t relu, float* Y, int64_t ldy,
-                      void* ws, size_t ws_bytes, hipStream_t st);
+                      void* ws, size_t ws_bytes, float* Wt_ext, bool wt_current, hipStream_t st);
 
 // ... and the weight gradient of such layers (partials in the layout reduce_all expects; no alignment requirement)
 bool x3_dw_wanted(int32_t n_cap, int32_t in, int32_t out);

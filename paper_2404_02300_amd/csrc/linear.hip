@@ -595,16 +595,20 @@ struct ReduceArgs {
     PendingReduce r[SDT_MAX_REDUCE];
 };
 // w <- w - lr g (SGD) or the Adam update with the moments m, v kept beside w
-__device__ __forceinline__ void apply_update(float* w, float g, float* m, float* v, const OptArgs& o) {
+// (returns the new value)
+__device__ __forceinline__ float apply_update(float* w, float g, float* m, float* v, const OptArgs& o) {
+    float wn;
     if (o.adam && m) {
         const float mn = o.beta1 * *m + (1.0f - o.beta1) * g;
         const float vn = o.beta2 * *v + (1.0f - o.beta2) * g * g;
         *m = mn;
         *v = vn;
-        *w = *w - o.lr * (mn * o.c1) / (sqrtf(vn * o.c2) + o.eps);
+        wn = *w - o.lr * (mn * o.c1) / (sqrtf(vn * o.c2) + o.eps);
     } else {
-        *w = *w - o.lr * g;
+        wn = *w - o.lr * g;
     }
+    *w = wn;
+    return wn;
 }
 
 __global__ __launch_bounds__(TB) void k_reduce_partials(ReduceArgs a, OptArgs opt, const float* __restrict__ row_loss,
@@ -645,7 +649,23 @@ __global__ __launch_bounds__(TB) void k_reduce_partials(ReduceArgs a, OptArgs op
         const float t = ((part[e] + part[64 + e]) + part[128 + e]) + part[192 + e];
         if (is_w) {
             r.dW[idx] = t;
-            if (r.W_upd) apply_update(r.W_upd + idx, t, r.mW ? r.mW + idx : nullptr, r.vW ? r.vW + idx : nullptr, opt);
+            if (r.W_upd) {
+                const float wn = apply_update(r.W_upd + idx, t, r.mW ? r.mW + idx : nullptr, r.vW ? r.vW + idx : nullptr, opt);
+                // the images of the weights the next step's products read (a step of the loop then starts without
+                // a pass over the weights): element (k, o) of W[2 in][out]
+                if (r.img_wt || r.img_x3) {
+                    const int k = (int)(idx / out), o = (int)(idx - (int64_t)k * out);
+                    if (r.img_wt) {
+                        const uint16_t h = f32_to_bf16(wn);
+                        r.img_wt[(int64_t)o * 2 * r.in + k] = h;
+                        r.img_wb[(int64_t)k * r.img_ldb + o] = h;
+                    }
+                    if (r.img_x3) {
+                        const int ph = k >= r.in;
+                        r.img_x3[(int64_t)o * 2 * r.img_kp + ph * r.img_kp + (k - ph * r.in)] = wn;
+                    }
+                }
+            }
         } else {
             const int o = (int)(idx - n_w);
             r.db[o] = t;

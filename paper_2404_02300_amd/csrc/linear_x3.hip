@@ -426,9 +426,12 @@ bool x3_fwd_ok(const void* Hself, int64_t ldh, const void* A, int64_t lda, int32
     return rows_ok && ldh % 4 == 0 && lda % 4 == 0 && ldy % 4 == 0 && aligned16(Hself) && aligned16(A) && aligned16(Y);
 }
 
+int32_t x3_fwd_image_kp(int32_t in) { return ceil_div(in, BK) * BK; }
+size_t x3_fwd_image_bytes(int32_t in, int32_t out) { return align_up((size_t)out * 2 * x3_fwd_image_kp(in) * sizeof(float), 256); }
+
 int32_t linear_fwd_x3(const float* Hself, int64_t ldh, const float* A, int64_t lda, int32_t n_cap, const int32_t* n_d,
                       int32_t in, int32_t out, const float* W, const float* b, int32_t relu, float* Y, int64_t ldy,
-                      void* ws, size_t ws_bytes, hipStream_t st) {
+                      void* ws, size_t ws_bytes, float* Wt_ext, bool wt_current, hipStream_t st) {
     if (n_cap == 0) return SDT_OK;
     const X3Ws w = x3_ws(n_cap, in, out);
     SDT_REQUIRE(ws && ws_bytes >= w.total && aligned16(ws), SDT_ERR_WORKSPACE,
@@ -441,11 +444,13 @@ int32_t linear_fwd_x3(const float* Hself, int64_t ldh, const float* A, int64_t l
         }
         lds_opted.store(true, std::memory_order_release);
     }
-    float* Wt = reinterpret_cast<float*>(static_cast<char*>(ws) + w.wt_off);
+    float* Wt = Wt_ext ? Wt_ext : reinterpret_cast<float*>(static_cast<char*>(ws) + w.wt_off);
     float* P = reinterpret_cast<float*>(static_cast<char*>(ws) + w.p_off);
     const int kp = w.nk * BK;
-    hipLaunchKernelGGL(k_x3_transpose_w, dim3(ceil_div(2 * kp, 32), ceil_div(out, 32)), dim3(256), 0, st, W, in, kp, out, Wt);
-    SDT_CHECK_LAUNCH("x3_transpose_w");
+    if (!(Wt_ext && wt_current)) {
+        hipLaunchKernelGGL(k_x3_transpose_w, dim3(ceil_div(2 * kp, 32), ceil_div(out, 32)), dim3(256), 0, st, W, in, kp, out, Wt);
+        SDT_CHECK_LAUNCH("x3_transpose_w");
+    }
     // grid for the upper bound of the row count and of the split; the kernel uses the first tiles * S workgroups
     hipLaunchKernelGGL(k_linear_fwd_x3, dim3(ceil_div(n_cap, BM) * w.s_max), dim3(NT), LDS_BYTES, st, Hself, ldh, A, lda,
                        n_cap, n_d, w.nk, out, Wt, w.s_max, P);

@@ -264,6 +264,12 @@ extern "C" int32_t sdt_train_step_layout(int64_t n_nodes, int32_t batch, const i
         size_t wb = 0;
         for (int l = 0; l < L; ++l) wb += bf16_weights_bytes(d[l], d[l + 1]);
         lay->wlow = a.take_off(wb);
+    } else if (model->kind == SDT_MODEL_SAGE_MEAN) {
+        // transposed weights of the layers whose forward runs on split-bf16 (kept across the steps of a loop)
+        size_t wb = 0;
+        for (int l = 0; l + 1 < L; ++l)
+            if (x3_fwd_wanted(c.dst[l], d[l], d[l + 1])) wb += x3_fwd_image_bytes(d[l], d[l + 1]);
+        if (wb > 0) lay->wlow = a.take_off(wb);
     }
     if (model->kind == SDT_MODEL_GCN)
         for (int l = 0; l < L; ++l)
@@ -314,6 +320,12 @@ struct StepCtx {
     sdt_timing* timing;
     sdt_step_layout lay;
     int32_t slot = -1;   // timing slot of the step being enqueued (each enqueueing thread has its own copy)
+    // Inside a loop call the images of the weights that the matrix-core paths read (bf16 images, transposed fp32
+    // weights) live in ONE place for all steps -- the model side of the steps runs in sequence on one stream -- and
+    // every update launch rewrites them with the weights; only the call's first step builds them from the weights.
+    // Null: a step on its own, which builds them in its own workspace every time.
+    char* images = nullptr;
+    bool images_current = false;
 };
 
 struct StepBuffers {
@@ -681,17 +693,29 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
     auto ldx = [&](int l) { return l == 0 ? (int64_t)lay.ld_in : (int64_t)d[l]; };
     // bf16 activations: the matrix products run on the bf16 matrix cores from bf16 images of the
     // weights, rewritten here every step (the weights are the caller's and change every step)
-    const char* wt[SDT_MAX_LAYERS] = {};
-    const char* wb[SDT_MAX_LAYERS] = {};
+    char* wt[SDT_MAX_LAYERS] = {};
+    char* wb[SDT_MAX_LAYERS] = {};
+    float* wx3[SDT_MAX_LAYERS] = {};   // fp32: transposed weights of the split-bf16 forward, kept across a loop's steps
+    char* const images = c.images ? c.images : static_cast<char*>(b.at(lay.wlow));
+    const bool images_current = c.images && c.images_current;
     if (dtype == SDT_BF16) {
-        rc = convert_weights_bf16(model, b.at(lay.wlow), st);
-        if (rc != SDT_OK) return rc;
-        const char* p = static_cast<const char*>(b.at(lay.wlow));
+        if (!images_current) {
+            rc = convert_weights_bf16(model, images, st);
+            if (rc != SDT_OK) return rc;
+        }
+        char* p = images;
         for (int l = 0; l < L; ++l) {
             wt[l] = p;
             wb[l] = p + align_up((size_t)2 * d[l] * d[l + 1] * 2, 256);
             p += bf16_weights_bytes(d[l], d[l + 1]);
         }
+    } else if (c.images) {
+        char* p = images;
+        for (int l = 0; l + 1 < L; ++l)
+            if (x3_fwd_wanted(lay.cap_dst[l], d[l], d[l + 1])) {
+                wx3[l] = reinterpret_cast<float*>(p);
+                p += x3_fwd_image_bytes(d[l], d[l + 1]);
+            }
     }
     for (int l = 0; l < L; ++l) {
         if (l > 0) {   // layer 0's mean was taken in phase 1
@@ -713,7 +737,8 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
             // layer's backward scratch is free until the backward reaches this layer
             rc = linear_fwd_x3(static_cast<const float*>(b.at(lay.H[l])), ldx(l), static_cast<const float*>(b.at(lay.A[l])),
                                ldx(l), lay.cap_dst[l], b.blk[l].counts, d[l], d[l + 1], model->W[l], model->b[l], 1,
-                               static_cast<float*>(b.at(lay.H[l + 1])), d[l + 1], b.at(scr_off[l]), scr_len[l], st);
+                               static_cast<float*>(b.at(lay.H[l + 1])), d[l + 1], b.at(scr_off[l]), scr_len[l], wx3[l],
+                               images_current, st);
         else
             rc = linear_fwd(b.at(lay.H[l]), ldx(l), b.at(lay.A[l]), ldx(l), lay.cap_dst[l], b.blk[l].counts, d[l],
                             d[l + 1], model->W[l], model->b[l], last ? 0 : 1, dtype, b.at(lay.H[l + 1]),
@@ -780,7 +805,20 @@ int32_t step_compute(const StepCtx& c, const StepBuffers& b, const int32_t* seed
     // summed in a fixed order, the SGD step is applied, and the per-seed losses are averaged.
     // (No layer's weights were touched before this point, so every product above saw the
     // weights the step started with.)
-    for (int k = 0; k < n_pending; ++k) attach_moments(&pending[k], model, L - 1 - k);   // queued last layer first
+    for (int k = 0; k < n_pending; ++k) {   // queued last layer first
+        const int l = L - 1 - k;
+        attach_moments(&pending[k], model, l);
+        if (c.images) {   // the next step of the loop reads the images this update leaves
+            if (dtype == SDT_BF16) {
+                pending[k].img_wt = reinterpret_cast<uint16_t*>(wt[l]);
+                pending[k].img_wb = reinterpret_cast<uint16_t*>(wb[l]);
+                pending[k].img_ldb = bf16_ldb(d[l + 1]);
+            } else if (wx3[l]) {
+                pending[k].img_x3 = wx3[l];
+                pending[k].img_kp = x3_fwd_image_kp(d[l]);
+            }
+        }
+    }
     StageTimer tu(timing, c.slot, SDT_STAGE_UPDATE, 0, st);
     return reduce_all(pending, n_pending, optimizer_args(model, c.lr, step), static_cast<const float*>(b.at(lay.row_loss)),
                       c.batch, loss_d, st);
@@ -904,6 +942,8 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
     const bool overlap = n_aux > 0 && n_steps > 2;
     StepBuffers buf[LOOP_BUFFERS];
     for (int k = 0; k < LOOP_BUFFERS; ++k) bind_buffers(c.lay, static_cast<char*>(ws) + k * one, one, &buf[k]);
+    // the weight images of every step of this call live in the first workspace (see StepCtx::images)
+    if (c.lay.wlow != 0 && model->kind == SDT_MODEL_SAGE_MEAN) c.images = static_cast<char*>(buf[0].at(c.lay.wlow));
 
     // ready[s]: phase 1 of every step of the group in slot s is complete; done[s]: their phase 2 is.
     // The events come from a pool and go back to it (creating and destroying nine of them costs a call
@@ -948,6 +988,7 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
     if (!overlap) {
         for (int i = 0; i < n_steps && rc == SDT_OK; ++i) {
             c.slot = slot_of(i);
+            c.images_current = i > 0;
             const StepBuffers& bi = buf[i % LOOP_BUFFERS];
             rc = step_sample(c, bi, seeds + (int64_t)i * batch, first_step + (uint32_t)i, main_st);
             if (rc == SDT_OK)
@@ -1011,6 +1052,7 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
             (void)hipStreamWaitEvent(main_st, ready[s], 0);
             for (int i = group_begin(g); i < group_end(g) && rc == SDT_OK; ++i) {
                 c.slot = slot_of(i);
+                c.images_current = i > 0;
                 rc = step_compute(c, buf[i % LOOP_BUFFERS], seeds + (int64_t)i * batch, first_step + (uint32_t)i, losses_d + i,
                                   main_st);
             }

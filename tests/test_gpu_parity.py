@@ -550,8 +550,8 @@ def test_train_loop_many_steps_wraps_the_rotating_workspaces(n_aux, calls):
 def test_train_loop_keeps_the_weight_images_current(name):
     """Inside a loop call only the first step builds the images of the weights that the matrix-core paths read (bf16
     images; transposed fp32 weights of the split-bf16 forward); afterwards every update launch rewrites them.  Twelve
-    steps in calls of 5 and 7 (the second call starts from weights the first one left) must equal twelve sequential
-    steps, which build the images afresh every time, bit for bit."""
+    steps in calls of 1, 2, 4 and 5 (each call starts from the weights the one before left; the short calls run without
+    helper threads) must equal twelve sequential steps, which build the images afresh every time, bit for bit."""
     _say(f"train loop, weight images maintained by the update: {name}")
     if name == "bf16-images":   # three layers, 300 classes: no fused last layer, so every layer reads its images
         wl = gen.Workload(name, "rmat", 13, 12, 40, 300, 48, 3, [6, 4, 3], 128, 7, 2, bf16=True)
@@ -559,7 +559,7 @@ def test_train_loop_keeps_the_weight_images_current(name):
         wl = gen.Workload(name, "rmat", 13, 12, 260, 7, 256, 3, [6, 5, 4], 512, 23, 1, owned_frac=0.5)
     inst = gen.make_instance(wl)
     seq, losses = _run_and_check(inst, wl, steps=12, lr=0.05, check_float_steps=(0, 11))
-    _loop_against_steps(inst, wl, seq, losses, lr=0.05, n_aux=2, calls=[5, 7])
+    _loop_against_steps(inst, wl, seq, losses, lr=0.05, n_aux=2, calls=[1, 2, 4, 5])
 
 
 @pytest.mark.parametrize("bf16", [False, True])

@@ -358,7 +358,7 @@ def bench_step(args, workload, full):
                 return "hbm", n_dst * (wf * d[l] + d[l + 1]) * es + wf * d[l] * d[l + 1] * 2, \
                        "k_linear_fwd (bf16 operands widened on the way into LDS)" if gcn else "k_fwd_bf16"
             return "mfma", 2.0 * n_dst * wf * d[l] * d[l + 1], \
-                   "k_linear_fwd_x3 (+ k_x3_transpose_w before, k_linear_fwd_x3_finish after: the stage is three launches)" \
+                   "k_linear_fwd_x3 (+ k_linear_fwd_x3_finish after it; k_x3_transpose_w before it in a step on its own)" \
                    if x3_fwd(l) else "k_linear_fwd"
         if kind in ("linear_bwd", "bwd_weight", "bwd_input"):
             f = 2.0 * n_dst * wf * d[l] * d[l + 1]

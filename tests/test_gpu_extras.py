@@ -79,6 +79,25 @@ def test_infer_layerwise_other_model_kinds(name, kind):
     assert e.value.code == B.SDT_ERR_WORKSPACE
 
 
+def test_infer_layerwise_block_kinds_refuse_2_31_edges():
+    """The GCN and GAT passes address edges with 32 bits: a graph whose row offsets end at 2^31 or beyond is refused
+    by the host check, which reads the edge count back before anything is launched on the graph."""
+    _say("layer-wise inference, gcn model: edge count beyond 32 bits is an error")
+    n, d = 4, [8, 6, 3]
+    indptr = torch.tensor([0, 1, 2, 3, 1 << 31], dtype=torch.int64, device="cuda")     # claims 2^31 edges
+    indices = torch.zeros(8, dtype=torch.int32, device="cuda")
+    g = B.Csr(indptr, indices)
+    W = [torch.zeros(d[l], d[l + 1], dtype=torch.float32, device="cuda") for l in range(2)]
+    b = [torch.zeros(d[l + 1], dtype=torch.float32, device="cuda") for l in range(2)]
+    model = B.make_model(d, W, b, kind=B.SDT_MODEL_GCN)
+    X = torch.zeros(n, d[0], dtype=torch.float32, device="cuda")
+    ws = torch.empty(B.sdt_infer_layerwise_workspace_bytes(n, model, B.SDT_F32), dtype=torch.uint8, device="cuda")
+    logits = torch.zeros(n, d[-1], dtype=torch.float32, device="cuda")
+    with pytest.raises(B.SdtError) as e:
+        B.sdt_infer_layerwise(g, X, model, logits, ws)
+    assert e.value.code == B.SDT_ERR_INVALID_ARG and "2^31" in str(e.value)
+
+
 @pytest.mark.parametrize("n_models,n", [(1, 1000), (3, 12345), (64, 70001)])
 def test_model_average(n_models, n):
     _say(f"model average: {n_models} models of {n} elements")

@@ -1006,12 +1006,14 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
         (void)hipGetDevice(&dev);
         int32_t aux_rc[LOOP_MAX_AUX] = {};
         std::string aux_msg[LOOP_MAX_AUX];
-        // one helper per auxiliary stream: helper a enqueues the groups g = a, a + n_aux, ...
+        // one helper per auxiliary stream: helper a enqueues the groups g = a, a + n_aux, ... -- except group 0, the
+        // call's first step, whose sampling the calling thread enqueues itself before it starts the helpers: the GPU
+        // then works on it while the threads come up (their start is off the call's critical path)
         auto helper_fn = [&](int a) {
             (void)hipSetDevice(dev);
             StepCtx ca = c;
             hipStream_t aux_st = aux[a];
-            for (int g = a; g < n_groups; g += n_aux) {
+            for (int g = a == 0 ? n_aux : a; g < n_groups; g += n_aux) {
                 const int s = g % LOOP_SLOTS;
                 if (g >= LOOP_SLOTS) {
                     while (done_groups.load(std::memory_order_acquire) <= g - LOOP_SLOTS && !failed.load()) std::this_thread::yield();
@@ -1033,9 +1035,19 @@ extern "C" int32_t sdt_train_loop(const sdt_csr* graph, const void* X, int64_t l
                 ready_gen[s].store(g + 1, std::memory_order_release);
             }
         };
+        {   // group 0 (one step) on the first auxiliary stream
+            c.slot = slot_of(0);
+            rc = step_sample(c, buf[0], seeds, first_step, aux[0]);
+            if (rc == SDT_OK) {
+                (void)hipEventRecord(ready[0], aux[0]);
+                ready_gen[0].store(1, std::memory_order_release);
+            } else {
+                failed.store(1);
+            }
+        }
         std::thread helpers[LOOP_MAX_AUX];
         int started = 0;
-        try {
+        if (rc == SDT_OK) try {
             for (int a = 0; a < n_aux; ++a) {
                 helpers[a] = std::thread(helper_fn, a);
                 ++started;
